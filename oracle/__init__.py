@@ -1,0 +1,177 @@
+"""ctypes front end of the CPU oracle (``tileq_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the benchmark's
+cpu_baseline leg.  The product package never imports this module and shares no code with it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_DIR, "tileq_oracle.c")
+_LIB = os.path.join(_DIR, "libtileq_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP).  Returns the path of the shared object."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"]
+        subprocess.check_call(cmd)
+    return _LIB
+
+
+class OrcLayer(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("n_experts", "n_shared", "top_k", "hidden", "ffn", "group", "bits", "rank")]
+
+
+class OrcWeights(ctypes.Structure):
+    _fields_ = [("codes", ctypes.c_void_p), ("scale", ctypes.c_void_p), ("zero", ctypes.c_void_p),
+                ("A", ctypes.c_void_p), ("B", ctypes.c_void_p)]
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        L.orc_half_to_double.restype = ctypes.c_double
+        L.orc_half_to_double.argtypes = [ctypes.c_uint16]
+        L.orc_silu_export.restype = ctypes.c_double
+        L.orc_silu_export.argtypes = [ctypes.c_double]
+        L.orc_moe_forward.restype = ctypes.c_int32
+        L.orc_num_threads.restype = ctypes.c_int32
+        _lib = L
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dt):
+    a = np.ascontiguousarray(a, dtype=dt)
+    return a
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    lib().orc_set_num_threads(ctypes.c_int32(n))
+
+
+def half_to_double(bits: int) -> float:
+    return float(lib().orc_half_to_double(ctypes.c_uint16(bits)))
+
+
+def silu(v: float) -> float:
+    return float(lib().orc_silu_export(ctypes.c_double(v)))
+
+
+def route(logits: np.ndarray, bias: Optional[np.ndarray], k: int):
+    """Top-k routing.  Returns (idx int32 [T,k], w fp32 [T,k])."""
+    logits = _c(logits, np.float32)
+    T, E = logits.shape
+    b = None if bias is None else _c(bias, np.float32)
+    idx = np.empty((T, k), dtype=np.int32)
+    w = np.empty((T, k), dtype=np.float32)
+    lib().orc_route(_p(logits), _p(b), ctypes.c_int32(T), ctypes.c_int32(E), ctypes.c_int32(k),
+                    _p(idx), _p(w))
+    return idx, w
+
+
+def permute(idx: np.ndarray, E: int):
+    """Returns (offsets int32 [E+1], slot_of int32 [T*k], src_of int32 [T*k])."""
+    idx = _c(idx, np.int32)
+    T, k = idx.shape
+    offsets = np.empty(E + 1, dtype=np.int32)
+    slot_of = np.empty(T * k, dtype=np.int32)
+    src_of = np.empty(T * k, dtype=np.int32)
+    lib().orc_permute(_p(idx), ctypes.c_int32(T), ctypes.c_int32(E), ctypes.c_int32(k),
+                      _p(offsets), _p(slot_of), _p(src_of))
+    return offsets, slot_of, src_of
+
+
+def dequant(codes: np.ndarray, scale_bits: np.ndarray, zero_bits: np.ndarray, g: int) -> np.ndarray:
+    """codes uint8 [N,K], scale/zero fp16 bit patterns [N,K/g] -> float64 [N,K]."""
+    codes = _c(codes, np.uint8)
+    N, K = codes.shape
+    s = _c(scale_bits, np.uint16)
+    z = _c(zero_bits, np.uint16)
+    assert s.size == N * (K // g) and z.size == s.size
+    W = np.empty((N, K), dtype=np.float64)
+    lib().orc_dequant(_p(codes), _p(s), _p(z), ctypes.c_int32(N), ctypes.c_int32(K), ctypes.c_int32(g), _p(W))
+    return W
+
+
+def project(v: np.ndarray, codes: np.ndarray, scale_bits: np.ndarray, zero_bits: np.ndarray,
+            A_bits: Optional[np.ndarray], B_bits: Optional[np.ndarray], g: int) -> np.ndarray:
+    """One projection of one vector: v [K] float64 -> [N] float64.  A [K,r], B [r,N] fp16 bits or None."""
+    codes = _c(codes, np.uint8)
+    N, K = codes.shape
+    v = _c(v, np.float64)
+    assert v.shape == (K,)
+    s = _c(scale_bits, np.uint16)
+    z = _c(zero_bits, np.uint16)
+    r = 0
+    A = B = None
+    if A_bits is not None and A_bits.size:
+        A = _c(A_bits, np.uint16)
+        B = _c(B_bits, np.uint16)
+        r = A.size // K
+        assert A.size == K * r and B.size == r * N
+    out = np.empty(N, dtype=np.float64)
+    lib().orc_project(_p(v), _p(codes), _p(s), _p(z), _p(A), _p(B), ctypes.c_int32(N), ctypes.c_int32(K),
+                      ctypes.c_int32(g), ctypes.c_int32(r), _p(out))
+    return out
+
+
+def moe_forward(E: int, S: int, k: int, H: int, F: int, g: int, bits: int, r: int,
+                codes: np.ndarray, scale: np.ndarray, zero: np.ndarray,
+                A: Optional[np.ndarray], B: Optional[np.ndarray],
+                x: np.ndarray, idx: np.ndarray, w: np.ndarray,
+                tokens: Optional[np.ndarray] = None) -> np.ndarray:
+    """The whole layer on canonical weight arrays.  x fp32 [T,H]; returns float64 [n_tokens, H]."""
+    x = _c(x, np.float32)
+    T = x.shape[0]
+    assert x.shape == (T, H)
+    idx = _c(idx, np.int32)
+    w = _c(w, np.float32)
+    assert idx.shape == (T, k) and w.shape == (T, k)
+    ne, HF = E + S, H * F
+    codes = _c(codes, np.uint8)
+    scale = _c(scale, np.uint16)
+    zero = _c(zero, np.uint16)
+    assert codes.size == ne * 3 * HF and scale.size == ne * 3 * HF // g and zero.size == scale.size
+    if r > 0:
+        A = _c(A, np.uint16)
+        B = _c(B, np.uint16)
+        assert A.size == ne * (2 * H + F) * r and B.size == ne * (2 * F + H) * r
+    else:
+        A = B = None
+    tok = None if tokens is None else _c(tokens, np.int32)
+    n = T if tok is None else tok.size
+    y = np.empty((n, H), dtype=np.float64)
+    L = OrcLayer(E, S, k, H, F, g, bits, r)
+    Wt = OrcWeights(_p(codes), _p(scale), _p(zero), _p(A), _p(B))
+    rc = lib().orc_moe_forward(ctypes.byref(L), ctypes.byref(Wt), _p(x), _p(idx), _p(w), ctypes.c_int32(T),
+                               _p(tok), ctypes.c_int32(n), _p(y))
+    if rc != 0:
+        raise ValueError("oracle: expert or token index out of range")
+    return y
+
+
+def moe_forward_layer(layer, x: np.ndarray, idx: np.ndarray, w: np.ndarray,
+                      tokens: Optional[np.ndarray] = None) -> np.ndarray:
+    """Convenience wrapper over an object with .cfg (E,S,k,H,F,g,bits,r) and canonical arrays."""
+    c = layer.cfg
+    return moe_forward(c.E, c.S, c.k, c.H, c.F, c.g, c.bits, c.r, layer.codes, layer.scale, layer.zero,
+                       layer.A if c.r else None, layer.B if c.r else None, x, idx, w, tokens)

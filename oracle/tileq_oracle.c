@@ -1,0 +1,253 @@
+/*
+ * CPU oracle for the quantised-expert MoE forward with low-rank compensation.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain definition of what the HIP library must
+ * compute, written for checking, not for speed: fp64 arithmetic over the exact values of the
+ * fp16 / bf16 / integer inputs, no blocking, no fusion, no reordering beyond the definition.
+ * It shares no code with the HIP path and must never be linked into, or called from, the
+ * product library.  Only the tests, the smoke check and the benchmark's cpu_baseline leg use it.
+ *
+ * What each function follows in the paper (TileQ, arXiv 2605.09281):
+ *   - routing and the weighted combination over the selected top-K experts: the MoE forward,
+ *     Eq. 3 (Section 3, "Model"), with G(x) the routing scores and g_{b,t} the routing weights
+ *     of Section 3.2;
+ *   - a projection on "quantised weights + rank-r term": Eq. 2 (Section 2.2) and Eq. 4
+ *     (Section 3.1), W ~ Q(W - W_r) + U V, evaluated per expert in the per-expert
+ *     ("element-wise") form of Appendix A.3 / A.4, with the input-side scaling s_k and Sigma
+ *     already folded into the left factor offline (Algorithm 1);
+ *   - group-wise scalar quantisation with one scale per group of g weights: Appendix A.3
+ *     ("Basic Quantization").
+ * Readings taken where the paper is silent (stated once more in the repository's design notes):
+ *   - routing weights are the softmax over the k selected logits (equal to softmax over all
+ *     experts renormalised over the selected ones);
+ *   - ties between equal logits go to the lower expert index, output in descending score;
+ *   - an expert is a SwiGLU MLP: h = silu(gate(x)) * up(x), y = down(h), each of the three
+ *     projections independently "quantised + low-rank", the low-rank term added before SiLU;
+ *   - row-vector convention y = x W^T with W stored [out, in]; A is [in, r], B is [r, out];
+ *   - asymmetric codes: deq = (q - zero) * scale with fp16 scale and fp16 zero per (row, group);
+ *   - shared experts see every token with weight exactly 1, outside the top-k normalisation.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct {
+    int32_t n_experts; /* E, routed */
+    int32_t n_shared;  /* S, always on */
+    int32_t top_k;
+    int32_t hidden;    /* H */
+    int32_t ffn;       /* F */
+    int32_t group;     /* g */
+    int32_t bits;      /* 3 or 4 (informational; codes arrive one per byte) */
+    int32_t rank;      /* r, may be 0 */
+} orc_layer;
+
+/* IEEE binary16 -> double, written out from the format definition. */
+double orc_half_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int expo = (h >> 10) & 0x1F;
+    int mant = h & 0x3FF;
+    double v;
+    if (expo == 0)
+        v = ldexp((double)mant, -24);             /* subnormal: mant * 2^-10 * 2^-14 */
+    else if (expo == 31)
+        v = mant ? NAN : INFINITY;
+    else
+        v = ldexp((double)(mant + 1024), expo - 25); /* (1 + mant/1024) * 2^(expo-15) */
+    return sign ? -v : v;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Routing (Eq. 3: the selected top-K set and the routing scores).
+ * For each token: l = logits (+ bias) in fp32; the k largest by the key (-l, index); weights
+ * w_j = exp(l_j - l_max) / sum over the selected k, evaluated in double, stored as fp32.
+ * idx is [T, k] in descending score order; w is [T, k].
+ */
+void orc_route(const float *logits, const float *bias, int32_t T, int32_t E, int32_t k,
+               int32_t *idx, float *w)
+{
+    float *l = (float *)malloc(sizeof(float) * (size_t)E);
+    char *taken = (char *)malloc((size_t)E);
+    for (int32_t t = 0; t < T; ++t) {
+        for (int32_t e = 0; e < E; ++e) {
+            float v = logits[(size_t)t * E + e];
+            if (bias) v = v + bias[e];     /* one fp32 addition, as the selection is made on fp32 scores */
+            l[e] = v;
+        }
+        memset(taken, 0, (size_t)E);
+        /* selection by repeated maximum: the first maximum found scanning upward is the lowest index */
+        for (int32_t j = 0; j < k; ++j) {
+            int32_t best = -1;
+            for (int32_t e = 0; e < E; ++e) {
+                if (taken[e]) continue;
+                if (best < 0 || l[e] > l[best]) best = e;
+            }
+            taken[best] = 1;
+            idx[(size_t)t * k + j] = best;
+        }
+        double lmax = (double)l[idx[(size_t)t * k]];
+        double den = 0.0;
+        for (int32_t j = 0; j < k; ++j) den += exp((double)l[idx[(size_t)t * k + j]] - lmax);
+        for (int32_t j = 0; j < k; ++j)
+            w[(size_t)t * k + j] = (float)(exp((double)l[idx[(size_t)t * k + j]] - lmax) / den);
+    }
+    free(l);
+    free(taken);
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Token -> expert permutation.  Assignment a = t*k + j goes to expert idx[a].  offsets[E+1] is
+ * the exclusive prefix sum of the per-expert counts; within one expert, assignments keep their
+ * order in a (stable).  slot_of[a] is the position of assignment a in expert-sorted order and
+ * src_of[slot] its inverse.
+ */
+void orc_permute(const int32_t *idx, int32_t T, int32_t E, int32_t k, int32_t *offsets,
+                 int32_t *slot_of, int32_t *src_of)
+{
+    int64_t n = (int64_t)T * k;
+    for (int32_t e = 0; e <= E; ++e) offsets[e] = 0;
+    for (int64_t a = 0; a < n; ++a) offsets[idx[a] + 1] += 1;
+    for (int32_t e = 0; e < E; ++e) offsets[e + 1] += offsets[e];
+    int32_t *cursor = (int32_t *)malloc(sizeof(int32_t) * (size_t)E);
+    for (int32_t e = 0; e < E; ++e) cursor[e] = offsets[e];
+    for (int64_t a = 0; a < n; ++a) {
+        int32_t s = cursor[idx[a]]++;
+        slot_of[a] = s;
+        src_of[s] = (int32_t)a;
+    }
+    free(cursor);
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Dequantisation of one [N, K] matrix: W[n, kk] = (q[n, kk] - zero[n, kk/g]) * scale[n, kk/g].
+ */
+void orc_dequant(const uint8_t *q, const uint16_t *scale, const uint16_t *zero, int32_t N,
+                 int32_t K, int32_t g, double *W)
+{
+    int32_t G = K / g;
+    for (int32_t n = 0; n < N; ++n)
+        for (int32_t kk = 0; kk < K; ++kk) {
+            double s = orc_half_to_double(scale[(size_t)n * G + kk / g]);
+            double z = orc_half_to_double(zero[(size_t)n * G + kk / g]);
+            W[(size_t)n * K + kk] = ((double)q[(size_t)n * K + kk] - z) * s;
+        }
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * One projection of one vector (Eq. 2 / Eq. 4 applied to a row vector):
+ *   out[n] = sum_kk v[kk] * deq(W)[n, kk]  +  sum_rho ( sum_kk v[kk] * A[kk, rho] ) * B[rho, n]
+ * A is [K, r], B is [r, N], both fp16 bit patterns; r may be 0 (then A, B are not read).
+ */
+void orc_project(const double *v, const uint8_t *q, const uint16_t *scale, const uint16_t *zero,
+                 const uint16_t *A, const uint16_t *B, int32_t N, int32_t K, int32_t g, int32_t r,
+                 double *out)
+{
+    int32_t G = K / g;
+    double *t = (double *)malloc(sizeof(double) * (size_t)(r > 0 ? r : 1));
+    for (int32_t rho = 0; rho < r; ++rho) {
+        double acc = 0.0;
+        for (int32_t kk = 0; kk < K; ++kk) acc += v[kk] * orc_half_to_double(A[(size_t)kk * r + rho]);
+        t[rho] = acc;
+    }
+#pragma omp parallel for schedule(static)
+    for (int32_t n = 0; n < N; ++n) {
+        double acc = 0.0;
+        for (int32_t gi = 0; gi < G; ++gi) {
+            double s = orc_half_to_double(scale[(size_t)n * G + gi]);
+            double z = orc_half_to_double(zero[(size_t)n * G + gi]);
+            for (int32_t kk = gi * g; kk < (gi + 1) * g; ++kk)
+                acc += v[kk] * (((double)q[(size_t)n * K + kk] - z) * s);
+        }
+        double lr = 0.0;
+        for (int32_t rho = 0; rho < r; ++rho) lr += t[rho] * orc_half_to_double(B[(size_t)rho * N + n]);
+        out[n] = acc + lr;
+    }
+    free(t);
+}
+
+static double orc_silu(double v) { return v / (1.0 + exp(-v)); }
+double orc_silu_export(double v) { return orc_silu(v); }
+
+/* Canonical weight arrays of a whole layer, expert-major (see the layout in the header comment of
+ * orc_moe_forward).  Offsets of expert e, projection p (0 gate, 1 up, 2 down). */
+typedef struct {
+    const uint8_t *codes;  /* [E+S][3][H*F] */
+    const uint16_t *scale; /* [E+S][3][H*F/g] */
+    const uint16_t *zero;  /* [E+S][3][H*F/g] */
+    const uint16_t *A;     /* [E+S][(2H+F)*r]: gate [H,r] | up [H,r] | down [F,r] */
+    const uint16_t *B;     /* [E+S][(2F+H)*r]: gate [r,F] | up [r,F] | down [r,H] */
+} orc_weights;
+
+/* ---------------------------------------------------------------------------------------------
+ * One expert applied to one token: G = proj(x; gate), U = proj(x; up), h = silu(G) * U,
+ * y = proj(h; down).  Nothing is rounded in between.
+ */
+void orc_expert(const orc_layer *L, const orc_weights *Wt, int32_t e, const double *x, double *y,
+                double *scratch /* 3*F doubles */)
+{
+    int32_t H = L->hidden, F = L->ffn, g = L->group, r = L->rank;
+    size_t HF = (size_t)H * F, HFg = HF / g;
+    const uint8_t *cq = Wt->codes + (size_t)e * 3 * HF;
+    const uint16_t *cs = Wt->scale + (size_t)e * 3 * HFg;
+    const uint16_t *cz = Wt->zero + (size_t)e * 3 * HFg;
+    const uint16_t *Ae = r ? Wt->A + (size_t)e * (2 * (size_t)H + F) * r : NULL;
+    const uint16_t *Be = r ? Wt->B + (size_t)e * (2 * (size_t)F + H) * r : NULL;
+    double *Gv = scratch, *Uv = scratch + F, *hv = scratch + 2 * (size_t)F;
+    orc_project(x, cq, cs, cz, Ae, Be, F, H, g, r, Gv);
+    orc_project(x, cq + HF, cs + HFg, cz + HFg, r ? Ae + (size_t)H * r : NULL,
+                r ? Be + (size_t)F * r : NULL, F, H, g, r, Uv);
+    for (int32_t f = 0; f < F; ++f) hv[f] = orc_silu(Gv[f]) * Uv[f];
+    orc_project(hv, cq + 2 * HF, cs + 2 * HFg, cz + 2 * HFg, r ? Ae + 2 * (size_t)H * r : NULL,
+                r ? Be + 2 * (size_t)F * r : NULL, H, F, g, r, y);
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * The MoE layer (Eq. 3) for a list of tokens:
+ *   y[t] = sum_j w[t, j] * Expert_{idx[t, j]}(x[t])  +  sum over shared experts s of Expert_s(x[t])
+ * x is [T, H] fp32 (the exact values of the bf16 or fp32 activations), idx/w are [T, k].
+ * tokens[n_tokens] selects which rows to evaluate (NULL = all T, then n_tokens must equal T);
+ * y is [n_tokens, H] in double.  The k terms are added in slot order j = 0..k-1, then the shared
+ * experts in index order.  Returns 0, or -1 on an expert index outside [0, E).
+ */
+int32_t orc_moe_forward(const orc_layer *L, const orc_weights *Wt, const float *x, const int32_t *idx,
+                        const float *w, int32_t T, const int32_t *tokens, int32_t n_tokens, double *y)
+{
+    int32_t H = L->hidden, F = L->ffn, k = L->top_k, E = L->n_experts, S = L->n_shared;
+    double *xv = (double *)malloc(sizeof(double) * (size_t)H);
+    double *ye = (double *)malloc(sizeof(double) * (size_t)H);
+    double *scratch = (double *)malloc(sizeof(double) * 3 * (size_t)F);
+    int32_t rc = 0;
+    for (int32_t i = 0; i < n_tokens && rc == 0; ++i) {
+        int32_t t = tokens ? tokens[i] : i;
+        if (t < 0 || t >= T) { rc = -1; break; }
+        for (int32_t c = 0; c < H; ++c) xv[c] = (double)x[(size_t)t * H + c];
+        double *yt = y + (size_t)i * H;
+        for (int32_t c = 0; c < H; ++c) yt[c] = 0.0;
+        for (int32_t j = 0; j < k; ++j) {
+            int32_t e = idx[(size_t)t * k + j];
+            if (e < 0 || e >= E) { rc = -1; break; }
+            orc_expert(L, Wt, e, xv, ye, scratch);
+            double wj = (double)w[(size_t)t * k + j];
+            for (int32_t c = 0; c < H; ++c) yt[c] += wj * ye[c];
+        }
+        for (int32_t s = 0; s < S && rc == 0; ++s) {
+            orc_expert(L, Wt, E + s, xv, ye, scratch);
+            for (int32_t c = 0; c < H; ++c) yt[c] += ye[c];
+        }
+    }
+    free(xv);
+    free(ye);
+    free(scratch);
+    return rc;
+}
+
+#ifdef _OPENMP
+#include <omp.h>
+int32_t orc_num_threads(void) { return omp_get_max_threads(); }
+void orc_set_num_threads(int32_t n) { omp_set_num_threads(n); }
+#else
+int32_t orc_num_threads(void) { return 1; }
+void orc_set_num_threads(int32_t n) { (void)n; }
+#endif

@@ -1,0 +1,242 @@
+"""Seeded synthetic inputs with the shapes and value distributions of the five benchmark layers.
+
+Everything here is input manufacture: counter-based random draws (numpy Philox), bf16/fp16
+rounding of the drawn values, and a plain round-to-nearest group quantiser that turns a random
+fp32 weight matrix into (codes, scale, zero).  The forward pass itself (dequantisation,
+projections, routing, packing) lives elsewhere, once in ``oracle/`` and once in the HIP library.
+
+Canonical (unpacked) weight layout, expert-major, ``p`` in {0: gate, 1: up, 2: down}:
+
+  codes  uint8  [E+S, 3, N*K]      one code per byte, row-major [N, K]
+                                   (gate/up: N=F, K=H; down: N=H, K=F)
+  scale  fp16   [E+S, 3, N*K/g]    row-major [N, K/g]
+  zero   fp16   [E+S, 3, N*K/g]    row-major [N, K/g]
+  A      fp16   [E+S, (2H+F)*r]    per expert: gate [H, r] | up [H, r] | down [F, r]
+  B      fp16   [E+S, (2F+H)*r]    per expert: gate [r, F] | up [r, F] | down [r, H]
+
+Experts 0..E-1 are routed, E..E+S-1 are the always-on shared experts.
+"""
+from __future__ import annotations
+
+import dataclasses
+from concurrent.futures import ThreadPoolExecutor
+from typing import Optional
+
+import numpy as np
+
+SEED_BASE = 0x71170000
+
+# tensor ids that are mixed into the Philox key
+_TID_X, _TID_LOGITS, _TID_ZIPF, _TID_WEIGHT, _TID_FACTOR, _TID_OUTLIER = 0, 1, 2, 3, 4, 5
+
+
+@dataclasses.dataclass(frozen=True)
+class LayerConfig:
+    cfg_id: int
+    name: str
+    E: int          # routed experts
+    S: int          # always-on shared experts
+    k: int          # top-k
+    H: int          # hidden
+    F: int          # expert FFN width
+    T: int          # tokens
+    g: int          # quantisation group size along the contraction dim
+    r: int          # rank of the low-rank factors
+    bits: int       # 4, or 3 (codes 0..7 stored in 4-bit slots)
+    outlier_frac: float = 0.0   # fraction of input channels drawn heavy-tailed (Student-t, df=3)
+    zipf_s: float = 0.0         # expert bias -s*ln(rank) added to the router logits
+    w_std: float = 0.02
+    f_std: float = 0.01
+
+    @property
+    def qmax(self) -> int:
+        return (1 << self.bits) - 1
+
+    @property
+    def n_exp(self) -> int:
+        return self.E + self.S
+
+    @property
+    def a_tot(self) -> int:
+        return self.T * (self.k + self.S)
+
+    def replace(self, **kw) -> "LayerConfig":
+        return dataclasses.replace(self, **kw)
+
+
+CONFIGS = {
+    1: LayerConfig(1, "tiny", E=8, S=0, k=2, H=256, F=512, T=64, g=64, r=8, bits=4),
+    2: LayerConfig(2, "mixtral_decode", E=8, S=0, k=2, H=4096, F=14336, T=16, g=128, r=32, bits=4,
+                   outlier_frac=0.05),
+    3: LayerConfig(3, "dsv2lite_prefill", E=64, S=2, k=6, H=2048, F=1408, T=4096, g=128, r=16, bits=4,
+                   zipf_s=1.1),
+    4: LayerConfig(4, "qwenmoe_mixed", E=60, S=0, k=4, H=2048, F=1408, T=1024, g=64, r=64, bits=3),
+    5: LayerConfig(5, "large_finegrained", E=128, S=0, k=8, H=4096, F=1536, T=8192, g=128, r=32, bits=4,
+                   zipf_s=1.1),
+}
+
+
+def _rng(cfg_id: int, tensor_id: int, sub: int = 0) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[SEED_BASE + 16 * cfg_id + tensor_id, sub]))
+
+
+# ----------------------------------------------------------------------------- bf16 helpers
+def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bit patterns (uint16), round-to-nearest-even.  Finite inputs only."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    bias = ((u >> 16) & 1) + np.uint32(0x7FFF)
+    return ((u + bias) >> 16).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def bf16_round(a: np.ndarray) -> np.ndarray:
+    """fp32 values rounded to the nearest bf16, returned as fp32."""
+    return bf16_bits_to_f32(f32_to_bf16_bits(a))
+
+
+# ----------------------------------------------------------------------------- activations / router
+def make_x(cfg: LayerConfig) -> np.ndarray:
+    """Activations ~N(0,1), rounded to bf16, returned as fp32 [T, H] (exactly bf16-representable)."""
+    x = _rng(cfg.cfg_id, _TID_X).standard_normal((cfg.T, cfg.H), dtype=np.float32)
+    return bf16_round(x)
+
+
+def make_logits(cfg: LayerConfig):
+    """Router logits ~N(0,1) fp32 [T, E] and the optional Zipf expert bias fp32 [E] (or None)."""
+    logits = _rng(cfg.cfg_id, _TID_LOGITS).standard_normal((cfg.T, cfg.E), dtype=np.float32)
+    bias = None
+    if cfg.zipf_s > 0.0:
+        rank = _rng(cfg.cfg_id, _TID_ZIPF).permutation(cfg.E) + 1
+        bias = (-cfg.zipf_s * np.log(rank.astype(np.float64))).astype(np.float32)
+    return logits, bias
+
+
+# ----------------------------------------------------------------------------- quantiser
+def rtn_quantize(w: np.ndarray, g: int, qmax: int):
+    """Asymmetric round-to-nearest group quantiser for a [N, K] fp32 matrix, groups along K.
+
+    Per (row, group): lo=min(w,0), hi=max(w,0), scale=fp16((hi-lo)/qmax) (1 where that is 0),
+    zero=fp16(clip(rint(-lo/scale), 0, qmax)), code=clip(rint(w/scale)+zero, 0, qmax);
+    rint rounds half to even.  Returns (codes uint8 [N,K], scale fp16 [N,K/g], zero fp16 [N,K/g]).
+    """
+    N, K = w.shape
+    assert K % g == 0
+    wg = w.reshape(N, K // g, g)
+    lo = np.minimum(wg.min(axis=-1), 0.0)
+    hi = np.maximum(wg.max(axis=-1), 0.0)
+    scale = ((hi - lo) / np.float32(qmax)).astype(np.float16)
+    scale[scale == 0] = np.float16(1.0)
+    sf = scale.astype(np.float32)
+    zero = np.clip(np.rint(-lo / sf), 0, qmax).astype(np.float16)
+    q = np.rint(wg / sf[..., None])
+    q += zero.astype(np.float32)[..., None]
+    np.clip(q, 0, qmax, out=q)
+    return q.astype(np.uint8).reshape(N, K), scale, zero
+
+
+def _outlier_channels(cfg: LayerConfig, p: int, K: int) -> Optional[np.ndarray]:
+    """The heavy-tailed input channels of projection p: one seeded subset shared by all experts."""
+    if cfg.outlier_frac <= 0.0:
+        return None
+    n = int(round(cfg.outlier_frac * K))
+    if n == 0:
+        return None
+    return np.sort(_rng(cfg.cfg_id, _TID_OUTLIER, p).choice(K, size=n, replace=False))
+
+
+def _gen_matrix(cfg: LayerConfig, e: int, p: int, N: int, K: int, cols: Optional[np.ndarray],
+                codes_out: np.ndarray, scale_out: np.ndarray, zero_out: np.ndarray) -> None:
+    rng = _rng(cfg.cfg_id, _TID_WEIGHT, 3 * e + p)
+    rows_per_chunk = max(1, min(N, (1 << 22) // K))
+    G = K // cfg.g
+    for r0 in range(0, N, rows_per_chunk):
+        r1 = min(N, r0 + rows_per_chunk)
+        w = rng.standard_normal((r1 - r0, K), dtype=np.float32)
+        w *= np.float32(cfg.w_std)
+        if cols is not None:
+            nz = rng.standard_normal((r1 - r0, cols.size), dtype=np.float32)
+            chi = rng.chisquare(3.0, size=(r1 - r0, cols.size)).astype(np.float32)
+            w[:, cols] = np.float32(cfg.w_std) * nz / np.sqrt(chi / np.float32(3.0))
+        q, s, z = rtn_quantize(w, cfg.g, cfg.qmax)
+        codes_out[r0 * K:r1 * K] = q.reshape(-1)
+        scale_out[r0 * G:r1 * G] = s.view(np.uint16).reshape(-1)
+        zero_out[r0 * G:r1 * G] = z.view(np.uint16).reshape(-1)
+
+
+@dataclasses.dataclass
+class Layer:
+    cfg: LayerConfig
+    codes: np.ndarray   # uint8  [E+S, 3, H*F]
+    scale: np.ndarray   # uint16 (fp16 bits) [E+S, 3, H*F/g]
+    zero: np.ndarray    # uint16 (fp16 bits) [E+S, 3, H*F/g]
+    A: np.ndarray       # uint16 (fp16 bits) [E+S, (2H+F)*r]
+    B: np.ndarray       # uint16 (fp16 bits) [E+S, (2F+H)*r]
+
+    def shapes(self, p: int):
+        """(N, K) of projection p."""
+        c = self.cfg
+        return (c.F, c.H) if p < 2 else (c.H, c.F)
+
+    def a_offset(self, p: int) -> int:
+        c = self.cfg
+        return (0, c.H * c.r, 2 * c.H * c.r)[p]
+
+    def b_offset(self, p: int) -> int:
+        c = self.cfg
+        return (0, c.F * c.r, 2 * c.F * c.r)[p]
+
+    def codes_matrix(self, e: int, p: int) -> np.ndarray:
+        N, K = self.shapes(p)
+        return self.codes[e, p].reshape(N, K)
+
+    def scale_matrix(self, e: int, p: int) -> np.ndarray:
+        N, K = self.shapes(p)
+        return self.scale[e, p].view(np.float16).reshape(N, K // self.cfg.g)
+
+    def zero_matrix(self, e: int, p: int) -> np.ndarray:
+        N, K = self.shapes(p)
+        return self.zero[e, p].view(np.float16).reshape(N, K // self.cfg.g)
+
+    def a_matrix(self, e: int, p: int) -> np.ndarray:
+        N, K = self.shapes(p)
+        o = self.a_offset(p)
+        return self.A[e, o:o + K * self.cfg.r].view(np.float16).reshape(K, self.cfg.r)
+
+    def b_matrix(self, e: int, p: int) -> np.ndarray:
+        N, K = self.shapes(p)
+        o = self.b_offset(p)
+        return self.B[e, o:o + N * self.cfg.r].view(np.float16).reshape(self.cfg.r, N)
+
+
+def make_layer(cfg: LayerConfig, workers: int = 8) -> Layer:
+    """All expert weights of one layer: random fp32 weights -> RTN codes/scale/zero, random fp16 factors."""
+    assert cfg.H % cfg.g == 0 and cfg.F % cfg.g == 0
+    ne, HF = cfg.n_exp, cfg.H * cfg.F
+    codes = np.empty((ne, 3, HF), dtype=np.uint8)
+    scale = np.empty((ne, 3, HF // cfg.g), dtype=np.uint16)
+    zero = np.empty((ne, 3, HF // cfg.g), dtype=np.uint16)
+    A = np.empty((ne, (2 * cfg.H + cfg.F) * cfg.r), dtype=np.uint16)
+    B = np.empty((ne, (2 * cfg.F + cfg.H) * cfg.r), dtype=np.uint16)
+    cols = [_outlier_channels(cfg, p, cfg.H if p < 2 else cfg.F) for p in range(3)]
+
+    def one(e: int) -> None:
+        for p in range(3):
+            N, K = (cfg.F, cfg.H) if p < 2 else (cfg.H, cfg.F)
+            _gen_matrix(cfg, e, p, N, K, cols[p], codes[e, p], scale[e, p], zero[e, p])
+        if cfg.r > 0:
+            rng = _rng(cfg.cfg_id, _TID_FACTOR, e)
+            a = rng.standard_normal(A.shape[1], dtype=np.float32) * np.float32(cfg.f_std)
+            b = rng.standard_normal(B.shape[1], dtype=np.float32) * np.float32(cfg.f_std)
+            A[e] = a.astype(np.float16).view(np.uint16)
+            B[e] = b.astype(np.float16).view(np.uint16)
+
+    if workers > 1 and ne > 1:
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            list(ex.map(one, range(ne)))
+    else:
+        for e in range(ne):
+            one(e)
+    return Layer(cfg, codes, scale, zero, A, B)
