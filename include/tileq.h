@@ -1,0 +1,163 @@
+/*
+ * tileq.h — C ABI of the MI355X (gfx950) quantised-expert MoE forward with low-rank compensation.
+ *
+ * The operation (TileQ, arXiv 2605.09281): an MoE layer  MoE(X) = sum_{k in topK} G_k(X) * W_k(X)
+ * (Eq. 3) whose expert weights are stored as "quantised residual + rank-r term",
+ * W ~ Q(W - W_r) + U V (Eq. 2, Eq. 4), evaluated at inference as the quantised forward plus the
+ * low-rank forward (Eq. 14).  The factors taken here are the effective per-expert ones of Eq. 4 /
+ * Algorithm 1: A_e = diag(s_e)^-1 U_{m(e)} Sigma  ([in, r]) and B_e = V_{n(e)} ([r, out]); the
+ * input-side scaling, Sigma and the position table are folded offline and never reach this API.
+ * Each expert is a SwiGLU MLP (gate, up, down); each of the three projections is
+ *     proj(v)[n] = sum_kk v[kk] * (q[n,kk] - zero[n,kk/g]) * scale[n,kk/g]
+ *                + sum_rho ( sum_kk v[kk] * A[kk,rho] ) * B[rho,n]
+ * with group-wise scales as in Appendix A.3 ("Basic Quantization"), h = silu(gate(x)) * up(x),
+ * y_e = down(h), and  y[t] = sum_j w[t,j] * y_{idx[t,j]}(x[t]) + sum_{shared s} y_s(x[t]).
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer unless it is said to be host.  Descriptors (tq_layer_desc,
+ *    tq_weights_src, tq_weights_dst) are small host structs whose members are device pointers.
+ *  - The caller owns every buffer.  The library allocates nothing, frees nothing and never
+ *    synchronises; all work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *    default stream).  Outputs are valid once the stream has reached the end of the call.
+ *  - Every entry point returns tq_status; argument errors are found on the host before any launch
+ *    and nothing is enqueued then.  Launch failures map to TQ_ERR_HIP.
+ *  - Device pointers must be 16-byte aligned; `packed` and `workspace` 256-byte aligned.
+ *  - fp16 / bf16 values travel as uint16_t bit patterns.
+ *
+ * Canonical (unpacked) weights, expert-major, experts 0..E-1 routed then E..E+S-1 shared,
+ * projection p in {0 gate, 1 up, 2 down}; gate/up are [N=F, K=H], down is [N=H, K=F]:
+ *     codes  uint8  [E+S][3][N*K]     one code per byte (0..15, or 0..7 when bits == 3), row-major [N,K]
+ *     scale  fp16   [E+S][3][N*K/g]   row-major [N, K/g]
+ *     zero   fp16   [E+S][3][N*K/g]   row-major [N, K/g]
+ *     A      fp16   [E+S][(2H+F)*r]   gate [H,r] | up [H,r] | down [F,r]
+ *     B      fp16   [E+S][(2F+H)*r]   gate [r,F] | up [r,F] | down [r,H]
+ *
+ * Packed blob (what tq_pack_weights writes, version 1).  256-byte header, then one record per expert
+ * at  256 + e * expert_stride.  A record holds two sections, GU (gate and up interleaved; N2 = 2F
+ * columns, K = H) and D (down; N2 = H columns, K = F), each made of four 256-byte aligned parts.
+ * Columns are taken in tiles of 32 and tiles in pairs: in GU pair j = (gate rows 32j..32j+31,
+ * up rows 32j..32j+31); in D pair j = (rows 64j..64j+31, rows 64j+32..64j+63).  `lane` runs over
+ * 0..63, the column inside a tile is lane%32 and hf = lane/32 picks the upper or lower 8 of a 16-wide
+ * contraction step.  r16 = rank rounded up to a multiple of 16.
+ *   codes  uint32 [pairs][K/64][2 tiles][64 lanes][4]
+ *          word w of (pair, chunk c, tile, lane) carries the 8 codes of column (tile, lane%32) at
+ *          kk = 64c + 16w + 8hf + i, i = 0..7; code i sits in nibble position (i/2) + 4*(i%2), i.e.
+ *          the nibbles from least significant upward hold i = 0,2,4,6,1,3,5,7.
+ *   sz     uint32 [pairs][K/g][2 tiles][32]      low half = scale fp16 bits, high half = zero fp16 bits
+ *   bfrag  fp16   [pairs][r16/16][2 tiles][64 lanes][8]
+ *          element i of (pair, step s, tile, lane) = B[rho = 16s + 8hf + i][column], 0 where rho >= r
+ *   afrag  fp16   [ceil(NA/32)][K/16][64 lanes][8]   NA = 2*r16 in GU (gate factors then up factors), r16 in D
+ *          element i of (tile ta, step s, lane) = A_p[kk = 16s + 8hf + i][rho] with column
+ *          c = 32ta + lane%32, p = c / r16, rho = c % r16; 0 where rho >= r or c >= NA
+ * The blob is position independent (offsets only) and may be stored and reloaded byte for byte.
+ */
+#ifndef TILEQ_H
+#define TILEQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TQ_OK = 0,
+    TQ_ERR_NULL = 1,        /* a required pointer is NULL */
+    TQ_ERR_SHAPE = 2,       /* non-positive or inconsistent dimensions (H % g, F % g, top_k > E, ...) */
+    TQ_ERR_ALIGN = 3,       /* a pointer misses its alignment */
+    TQ_ERR_RANGE = 4,       /* a code above qmax or an expert index outside [0, E), found on the device */
+    TQ_ERR_WORKSPACE = 5,   /* workspace or output buffer too small */
+    TQ_ERR_UNSUPPORTED = 6, /* valid request this build has no kernel for */
+    TQ_ERR_HIP = 7,         /* a HIP call or launch failed */
+    TQ_ERR_BLOB = 8         /* the packed blob's header does not match the descriptor */
+} tq_status;
+
+enum { TQ_ACT_BF16 = 0, TQ_ACT_FP32 = 1 };
+
+/* flags of tq_layer_desc (test hooks; 0 in production) */
+enum {
+    TQ_FLAG_FORCE_SMALL_TILE = 1, /* bf16 path: always the 32-row (decode) tile */
+    TQ_FLAG_FORCE_LARGE_TILE = 2  /* bf16 path: always the 128-row (prefill) tile */
+};
+
+typedef struct tq_layer_desc {
+    int32_t n_experts; /* E  routed experts, >= 1 */
+    int32_t n_shared;  /* S  always-on shared experts, >= 0 */
+    int32_t top_k;     /* k  in [1, E] */
+    int32_t hidden;    /* H  multiple of 64 and of group */
+    int32_t ffn;       /* F  multiple of 64 and of group */
+    int32_t group;     /* g  quantisation group along the contraction dim; 32, 64, 128 or 256 */
+    int32_t bits;      /* 4, or 3 (codes 0..7 kept in 4-bit slots) */
+    int32_t rank;      /* r  in [0, 256]; 0 = no low-rank term */
+    int32_t act_dtype; /* TQ_ACT_BF16: x, y bf16, MFMA path.  TQ_ACT_FP32: x, y fp32, exact-dequant debug path */
+    int32_t flags;
+} tq_layer_desc;
+
+typedef struct tq_weights_src { /* canonical layout above; A, B may be NULL when rank == 0 */
+    const uint8_t *codes;
+    const uint16_t *scale, *zero;
+    const uint16_t *A, *B;
+} tq_weights_src;
+
+typedef struct tq_weights_dst {
+    uint8_t *codes;
+    uint16_t *scale, *zero;
+    uint16_t *A, *B;
+} tq_weights_dst;
+
+/* Text for a status code (static storage, host). */
+const char *tq_status_str(tq_status s);
+
+/* Bytes of the packed blob for this layer; 0 if the descriptor is invalid.  Host only.  With r a multiple
+ * of 32 this is 256 + (E+S) * 3HF * (4 + 32/g + 16 r (1/H + 1/F)) / 8 up to 256-byte padding per part:
+ * the per-expert low-rank storage count of Appendix A.3 with a 16-bit scale and a 16-bit zero per group. */
+size_t tq_packed_size(const tq_layer_desc *desc);
+
+/* Packs canonical weights into the blob (layout above).  `err_flag` (device int32, may be NULL) is set
+ * to 1 by the kernel if any code exceeds qmax = 2^bits - 1; it is not cleared here, and the offending
+ * code is stored masked to 4 bits.  Returns TQ_ERR_WORKSPACE if packed_bytes < tq_packed_size(). */
+tq_status tq_pack_weights(const tq_layer_desc *desc, const tq_weights_src *src, void *packed,
+                          size_t packed_bytes, int32_t *err_flag, void *stream);
+
+/* Exact inverse of tq_pack_weights (bit for bit on codes, scale, zero, A, B).  For tests and tools. */
+tq_status tq_unpack_weights(const tq_layer_desc *desc, const void *packed, const tq_weights_dst *dst,
+                            void *stream);
+
+/* Routing (Eq. 3's top-K set and routing weights).  logits fp32 [T,E]; bias fp32 [E] or NULL, added to
+ * the logits in fp32 before selection.  topk_idx int32 [T,k]: the k highest scores in descending order,
+ * equal scores to the lower expert index.  topk_w fp32 [T,k]: softmax over the k selected scores (sums
+ * to 1).  NaN logits are not supported.  E <= 1024 and k <= 64 (TQ_ERR_UNSUPPORTED beyond). */
+tq_status tq_route(const float *logits, const float *bias, int32_t T, int32_t E, int32_t k,
+                   int32_t *topk_idx, float *topk_w, void *stream);
+
+/* Bytes of scratch tq_permute needs. Host only. */
+size_t tq_permute_workspace_size(int32_t T, int32_t E, int32_t k);
+
+/* Token -> expert permutation with prefix-sum offsets: assignment a = t*k + j belongs to expert
+ * topk_idx[a].  offsets int32 [E+1] = exclusive prefix sum of the per-expert counts; slot_of int32 [T*k]
+ * = position of assignment a in expert-sorted order, stable (assignments of one expert keep their order
+ * in a); src_of int32 [T*k] = its inverse.  err_flag as in tq_pack_weights, set when an index is outside
+ * [0,E) (that assignment is then dropped from the counts).  Exported for bit-exact tests; tq_moe_forward
+ * runs the same kernels internally. */
+tq_status tq_permute(const int32_t *topk_idx, int32_t T, int32_t E, int32_t k, int32_t *offsets,
+                     int32_t *slot_of, int32_t *src_of, int32_t *err_flag, void *workspace,
+                     size_t workspace_bytes, void *stream);
+
+/* Bytes of workspace tq_moe_forward needs for up to T tokens.  Host only; 0 if desc is invalid. */
+size_t tq_moe_workspace_size(const tq_layer_desc *desc, int32_t T);
+
+/* The expert forward: permutation, gate/up with fused dequant + low-rank term + SwiGLU, down with the
+ * same, routing-weighted combination.  x, y are [T,H] bf16 (act_dtype 0) or fp32 (act_dtype 1); y is
+ * overwritten.  topk_idx / topk_w as produced by tq_route.  The first int32 of `workspace` is an error
+ * flag the kernels set to 1 on an out-of-range expert index (such assignments contribute nothing); the
+ * call clears it at its start and never reads it back — the caller may inspect it after synchronising.
+ * T == 0 is a no-op. */
+tq_status tq_moe_forward(const tq_layer_desc *desc, const void *packed, const void *x,
+                         const int32_t *topk_idx, const float *topk_w, int32_t T, void *y,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TILEQ_H */

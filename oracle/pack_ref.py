@@ -1,0 +1,97 @@
+"""Independent packer for the library's weight blob, written from the layout prose in
+``include/tileq.h`` with numpy reshapes/transposes (no code shared with the HIP packer).
+
+TEST INFRASTRUCTURE ONLY: used to check tq_pack_weights byte for byte.
+Returns the blob body (everything after the 256-byte header).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+_NIBBLE_POS = [(i // 2) + 4 * (i % 2) for i in range(8)]
+
+
+def _words(codes_nk: np.ndarray) -> np.ndarray:
+    """[N, K] codes -> [N, K/64 (chunk), 4 (word), 2 (hf)] uint32 words of 8 codes each."""
+    N, K = codes_nk.shape
+    c = codes_nk.reshape(N, K // 64, 4, 2, 8).astype(np.uint32) & 15
+    out = np.zeros(c.shape[:-1], dtype=np.uint32)
+    for i in range(8):
+        out |= c[..., i] << np.uint32(4 * _NIBBLE_POS[i])
+    return out
+
+
+def _pad_rows(a: np.ndarray, rows: int) -> np.ndarray:
+    if a.shape[0] == rows:
+        return a
+    out = np.zeros((rows,) + a.shape[1:], dtype=a.dtype)
+    out[:a.shape[0]] = a
+    return out
+
+
+def _pad_cols(a: np.ndarray, cols: int) -> np.ndarray:
+    if a.shape[1] == cols:
+        return a
+    out = np.zeros((a.shape[0], cols), dtype=a.dtype)
+    out[:, :a.shape[1]] = a
+    return out
+
+
+def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r) -> bytes:
+    """codes3[p]: [N,K] uint8; scale3/zero3[p]: [N,K/g] uint16; A3[p]: [K,r] uint16; B3[p]: [r,N] uint16."""
+    r16 = (r + 15) // 16 * 16
+    parts = []
+
+    def section(is_d: bool):
+        if not is_d:
+            K, pairs = H, F // 32
+            # codes: [pairs, chunks, tile, hf, col, word]
+            w = np.stack([_words(codes3[p]).reshape(pairs, 32, K // 64, 4, 2) for p in (0, 1)], axis=0)
+            # w: [tile, pairs, col, chunk, word, hf] -> [pairs, chunk, tile, hf, col, word]
+            parts.append(np.ascontiguousarray(w.transpose(1, 3, 0, 5, 2, 4)).tobytes())
+            sz = np.stack([(scale3[p].astype(np.uint32) | (zero3[p].astype(np.uint32) << 16)).reshape(pairs, 32, K // g)
+                           for p in (0, 1)], axis=0)          # [tile, pairs, col, G]
+            parts.append(np.ascontiguousarray(sz.transpose(1, 3, 0, 2)).tobytes())
+            if r > 0:
+                b = np.stack([_pad_rows(B3[p], r16).reshape(r16 // 16, 2, 8, pairs, 32) for p in (0, 1)], axis=0)
+                # [tile, step, hf, i, pairs, col] -> [pairs, step, tile, hf, col, i]
+                parts.append(np.ascontiguousarray(b.transpose(4, 1, 0, 2, 5, 3)).tobytes())
+                acat = np.concatenate([_pad_cols(A3[0], r16), _pad_cols(A3[1], r16)], axis=1)   # [K, 2*r16]
+                nat = (2 * r16 + 31) // 32
+                acat = _pad_cols(acat, 32 * nat).reshape(K // 16, 2, 8, nat, 32)
+                # [step, hf, i, ta, col] -> [ta, step, hf, col, i]
+                parts.append(np.ascontiguousarray(acat.transpose(3, 0, 1, 4, 2)).tobytes())
+        else:
+            K, pairs = F, H // 64
+            w = _words(codes3[2]).reshape(pairs, 2, 32, K // 64, 4, 2)
+            # [pairs, tile, col, chunk, word, hf] -> [pairs, chunk, tile, hf, col, word]
+            parts.append(np.ascontiguousarray(w.transpose(0, 3, 1, 5, 2, 4)).tobytes())
+            sz = (scale3[2].astype(np.uint32) | (zero3[2].astype(np.uint32) << 16)).reshape(pairs, 2, 32, K // g)
+            parts.append(np.ascontiguousarray(sz.transpose(0, 3, 1, 2)).tobytes())
+            if r > 0:
+                b = _pad_rows(B3[2], r16).reshape(r16 // 16, 2, 8, pairs, 2, 32)
+                # [step, hf, i, pairs, tile, col] -> [pairs, step, tile, hf, col, i]
+                parts.append(np.ascontiguousarray(b.transpose(3, 0, 4, 1, 5, 2)).tobytes())
+                nat = (r16 + 31) // 32
+                a = _pad_cols(_pad_cols(A3[2], r16), 32 * nat).reshape(K // 16, 2, 8, nat, 32)
+                parts.append(np.ascontiguousarray(a.transpose(3, 0, 1, 4, 2)).tobytes())
+
+    section(False)
+    section(True)
+    body = b"".join(parts)
+    pad = (-len(body)) % 256
+    return body + b"\0" * pad
+
+
+def pack_layer(layer) -> np.ndarray:
+    """Blob body (after the 256-byte header) for a synth.Layer-like object, as a uint8 array."""
+    c = layer.cfg
+    out = []
+    for e in range(c.E + c.S):
+        codes3 = [layer.codes_matrix(e, p) for p in range(3)]
+        scale3 = [layer.scale_matrix(e, p).view(np.uint16) for p in range(3)]
+        zero3 = [layer.zero_matrix(e, p).view(np.uint16) for p in range(3)]
+        A3 = [layer.a_matrix(e, p).view(np.uint16) for p in range(3)] if c.r else [None] * 3
+        B3 = [layer.b_matrix(e, p).view(np.uint16) for p in range(3)] if c.r else [None] * 3
+        out.append(pack_expert(codes3, scale3, zero3, A3, B3, c.H, c.F, c.g, c.r))
+    return np.frombuffer(b"".join(out), dtype=np.uint8)

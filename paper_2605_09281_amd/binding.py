@@ -1,0 +1,164 @@
+"""ctypes binding of libtileq.so: same names as the C ABI, torch tensors in and out.
+
+Marshalling only.  Every step of the path runs in the library's kernels; torch is used for
+device allocations and for the current stream.  Fails loudly when the library is missing.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+from .build import library_path
+
+TQ_OK = 0
+TQ_ACT_BF16, TQ_ACT_FP32 = 0, 1
+TQ_FLAG_FORCE_SMALL_TILE, TQ_FLAG_FORCE_LARGE_TILE = 1, 2
+STATUS_NAMES = {0: "TQ_OK", 1: "TQ_ERR_NULL", 2: "TQ_ERR_SHAPE", 3: "TQ_ERR_ALIGN", 4: "TQ_ERR_RANGE",
+                5: "TQ_ERR_WORKSPACE", 6: "TQ_ERR_UNSUPPORTED", 7: "TQ_ERR_HIP", 8: "TQ_ERR_BLOB"}
+
+EXPORTS = ["tq_status_str", "tq_packed_size", "tq_pack_weights", "tq_unpack_weights", "tq_route",
+           "tq_permute_workspace_size", "tq_permute", "tq_moe_workspace_size", "tq_moe_forward"]
+
+
+class TqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {STATUS_NAMES.get(status, status)}")
+
+
+class LayerDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("n_experts", "n_shared", "top_k", "hidden", "ffn", "group", "bits", "rank", "act_dtype", "flags")]
+
+
+class _WeightsPtrs(ctypes.Structure):
+    _fields_ = [("codes", ctypes.c_void_p), ("scale", ctypes.c_void_p), ("zero", ctypes.c_void_p),
+                ("A", ctypes.c_void_p), ("B", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = library_path()
+        if not os.path.exists(path):
+            raise ImportError(f"{path} is not built: run __graft_entry__.build() (there is no fallback path)")
+        L = ctypes.CDLL(path)
+        L.tq_status_str.restype = ctypes.c_char_p
+        L.tq_status_str.argtypes = [ctypes.c_int]
+        L.tq_packed_size.restype = ctypes.c_size_t
+        L.tq_packed_size.argtypes = [ctypes.POINTER(LayerDesc)]
+        L.tq_moe_workspace_size.restype = ctypes.c_size_t
+        L.tq_moe_workspace_size.argtypes = [ctypes.POINTER(LayerDesc), ctypes.c_int32]
+        L.tq_permute_workspace_size.restype = ctypes.c_size_t
+        L.tq_permute_workspace_size.argtypes = [ctypes.c_int32] * 3
+        L.tq_pack_weights.restype = ctypes.c_int
+        L.tq_pack_weights.argtypes = [ctypes.POINTER(LayerDesc), ctypes.POINTER(_WeightsPtrs), ctypes.c_void_p,
+                                      ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+        L.tq_unpack_weights.restype = ctypes.c_int
+        L.tq_unpack_weights.argtypes = [ctypes.POINTER(LayerDesc), ctypes.c_void_p, ctypes.POINTER(_WeightsPtrs),
+                                        ctypes.c_void_p]
+        L.tq_route.restype = ctypes.c_int
+        L.tq_route.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.tq_permute.restype = ctypes.c_int
+        L.tq_permute.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                 ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                 ctypes.c_size_t, ctypes.c_void_p]
+        L.tq_moe_forward.restype = ctypes.c_int
+        L.tq_moe_forward.argtypes = [ctypes.POINTER(LayerDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                     ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                     ctypes.c_size_t, ctypes.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous()
+    return t.data_ptr()
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != TQ_OK:
+        raise TqError(rc, where)
+
+
+def make_desc(E, S, k, H, F, g, bits, r, act_dtype=TQ_ACT_BF16, flags=0) -> LayerDesc:
+    return LayerDesc(E, S, k, H, F, g, bits, r, act_dtype, flags)
+
+
+def tq_status_str(status: int) -> str:
+    return lib().tq_status_str(status).decode()
+
+
+def tq_packed_size(desc: LayerDesc) -> int:
+    return int(lib().tq_packed_size(ctypes.byref(desc)))
+
+
+def tq_moe_workspace_size(desc: LayerDesc, T: int) -> int:
+    return int(lib().tq_moe_workspace_size(ctypes.byref(desc), T))
+
+
+def tq_pack_weights(desc: LayerDesc, codes, scale, zero, A=None, B=None, packed=None, err_flag=None):
+    """Canonical device tensors (uint8 codes, int16/uint16 fp16-bit scale/zero/A/B) -> packed uint8 blob."""
+    n = tq_packed_size(desc)
+    if n == 0:
+        raise TqError(2, "tq_packed_size")
+    if packed is None:
+        packed = torch.empty(n, dtype=torch.uint8, device=codes.device)
+    src = _WeightsPtrs(_ptr(codes), _ptr(scale), _ptr(zero), _ptr(A), _ptr(B))
+    rc = lib().tq_pack_weights(ctypes.byref(desc), ctypes.byref(src), _ptr(packed), packed.numel(),
+                               _ptr(err_flag), _stream())
+    _check(rc, "tq_pack_weights")
+    return packed
+
+
+def tq_unpack_weights(desc: LayerDesc, packed, codes, scale, zero, A=None, B=None) -> None:
+    dst = _WeightsPtrs(_ptr(codes), _ptr(scale), _ptr(zero), _ptr(A), _ptr(B))
+    _check(lib().tq_unpack_weights(ctypes.byref(desc), _ptr(packed), ctypes.byref(dst), _stream()),
+           "tq_unpack_weights")
+
+
+def tq_route(logits, bias, k: int, topk_idx=None, topk_w=None):
+    T, E = logits.shape
+    if topk_idx is None:
+        topk_idx = torch.empty((T, k), dtype=torch.int32, device=logits.device)
+    if topk_w is None:
+        topk_w = torch.empty((T, k), dtype=torch.float32, device=logits.device)
+    _check(lib().tq_route(_ptr(logits), _ptr(bias), T, E, k, _ptr(topk_idx), _ptr(topk_w), _stream()), "tq_route")
+    return topk_idx, topk_w
+
+
+def tq_permute(topk_idx, E: int, err_flag=None):
+    T, k = topk_idx.shape
+    dev = topk_idx.device
+    offsets = torch.empty(E + 1, dtype=torch.int32, device=dev)
+    slot_of = torch.empty(T * k, dtype=torch.int32, device=dev)
+    src_of = torch.empty(T * k, dtype=torch.int32, device=dev)
+    nws = int(lib().tq_permute_workspace_size(T, E, k))
+    ws = torch.empty(max(nws, 256), dtype=torch.uint8, device=dev)
+    _check(lib().tq_permute(_ptr(topk_idx), T, E, k, _ptr(offsets), _ptr(slot_of), _ptr(src_of), _ptr(err_flag),
+                            _ptr(ws), ws.numel(), _stream()), "tq_permute")
+    return offsets, slot_of, src_of
+
+
+def tq_moe_forward(desc: LayerDesc, packed, x, topk_idx, topk_w, y=None, workspace=None):
+    T = x.shape[0]
+    if y is None:
+        y = torch.empty_like(x)
+    if workspace is None:
+        workspace = torch.empty(max(tq_moe_workspace_size(desc, T), 256), dtype=torch.uint8, device=x.device)
+    _check(lib().tq_moe_forward(ctypes.byref(desc), _ptr(packed), _ptr(x), _ptr(topk_idx), _ptr(topk_w), T, _ptr(y),
+                                _ptr(workspace), workspace.numel(), _stream()), "tq_moe_forward")
+    return y

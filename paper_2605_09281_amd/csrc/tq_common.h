@@ -1,0 +1,180 @@
+// Internal definitions shared by the HIP translation units of libtileq: blob layout arithmetic,
+// workspace carve-up, and a few device helpers.  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "tileq.h"
+
+#define TQ_BLOB_MAGIC 0x31425154u /* "TQB1" */
+#define TQ_BLOB_VERSION 1u
+#define TQ_HEADER_BYTES 256
+
+// error-flag bits written by kernels into the first int32 of the workspace / into err_flag
+#define TQ_FLAG_BIT_RANGE 1
+#define TQ_FLAG_BIT_BLOB 2
+
+struct TqSection {
+    // geometry of one section (GU or D) of an expert record
+    int32_t pairs;   // column-tile pairs
+    int32_t K;       // contraction length
+    int32_t chunks;  // K / 64
+    int32_t groups;  // K / g
+    int32_t na_tiles;  // 32-wide tiles of the A-factor columns
+    // byte offsets from the start of the expert record
+    size_t codes, sz, bfrag, afrag, end;
+};
+
+struct TqLayout {
+    int32_t E, S, k, H, F, g, bits, r, r16;
+    TqSection gu, d;
+    size_t expert_stride;
+    size_t total_bytes;
+};
+
+struct TqBlobHeader {
+    uint32_t magic, version;
+    int32_t n_experts, n_shared, hidden, ffn, group, bits, rank, r16;
+    uint64_t expert_stride, total_bytes;
+    uint64_t off[8];  // gu.codes, gu.sz, gu.bfrag, gu.afrag, d.codes, d.sz, d.bfrag, d.afrag
+};
+static_assert(sizeof(TqBlobHeader) <= TQ_HEADER_BYTES, "header too large");
+
+__host__ __device__ inline size_t tq_align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Returns false if the descriptor is outside what the layout supports.
+__host__ inline bool tq_make_layout(const tq_layer_desc* d, TqLayout* L)
+{
+    if (!d) return false;
+    if (d->n_experts < 1 || d->n_shared < 0 || d->top_k < 1 || d->top_k > d->n_experts) return false;
+    if (d->n_experts > 1024 || d->n_shared > 64) return false;
+    if (d->hidden < 64 || d->ffn < 64 || d->hidden % 64 || d->ffn % 64) return false;
+    if (d->hidden > (1 << 16) || d->ffn > (1 << 17)) return false;
+    if (!(d->group == 32 || d->group == 64 || d->group == 128 || d->group == 256)) return false;
+    if (d->hidden % d->group || d->ffn % d->group) return false;
+    if (d->bits != 3 && d->bits != 4) return false;
+    if (d->rank < 0 || d->rank > 256) return false;
+    if (d->act_dtype != TQ_ACT_BF16 && d->act_dtype != TQ_ACT_FP32) return false;
+    L->E = d->n_experts; L->S = d->n_shared; L->k = d->top_k; L->H = d->hidden; L->F = d->ffn;
+    L->g = d->group; L->bits = d->bits; L->r = d->rank; L->r16 = (d->rank + 15) / 16 * 16;
+    size_t off = 0;
+    auto fill = [&](TqSection& s, int pairs, int K, int na) {
+        s.pairs = pairs; s.K = K; s.chunks = K / 64; s.groups = K / L->g; s.na_tiles = (na + 31) / 32;
+        s.codes = off; off += (size_t)pairs * s.chunks * 2048;
+        s.sz = off;    off += (size_t)pairs * s.groups * 256;
+        s.bfrag = off; off += (size_t)pairs * (L->r16 / 16) * 2048;
+        s.afrag = off; off += (size_t)s.na_tiles * (K / 16) * 1024;
+        s.end = off;
+    };
+    fill(L->gu, L->F / 32, L->H, 2 * L->r16);
+    fill(L->d, L->H / 64, L->F, L->r16);
+    L->expert_stride = tq_align256(off);
+    L->total_bytes = TQ_HEADER_BYTES + (size_t)(L->E + L->S) * L->expert_stride;
+    return true;
+}
+
+// position of code i (0..7, consecutive kk) inside a packed 32-bit word, in nibbles
+__host__ __device__ inline int tq_nibble_pos(int i) { return (i >> 1) + 4 * (i & 1); }
+
+// ------------------------------------------------------------------------------------------------
+// Workspace of tq_moe_forward.  All offsets are multiples of 256 bytes.
+struct TqWorkspace {
+    size_t ctrl;        // int32[64]: [0] error flag, [1] row tiles (32-row), [2] row tiles (128-row), [3] rows
+    size_t offsets;     // int32 [E+S+1]
+    size_t slot_of;     // int32 [T*(k+S)]
+    size_t row_token;   // int32 [A_tot]
+    size_t row_w;       // float [A_tot]
+    size_t tile_e;      // int32 [2][RT]  expert of each row tile, for the 32- and the 128-row tiling
+    size_t tile_row0;   // int32 [2][RT]  first slot of each row tile
+    size_t hist;        // int32 [nblk][E] permutation scratch
+    size_t xaug_gu;     // bf16 [A_tot][ka_gu]   (bf16 path)
+    size_t xaug_d;      // bf16 [A_tot][ka_d]
+    size_t h;           // bf16 [A_tot][F]  or fp32 [A_tot][F]
+    size_t yd;          // fp32 [nsplit][A_tot][H]
+    size_t total;
+    int32_t a_tot, rt_max, nblk, ka_gu, ka_d, nsplit_max;
+};
+
+#define TQ_PERM_CHUNK 1024  // assignments handled by one permutation block
+#define TQ_MAX_SPLIT 8      // K-splits of the down projection on the small-tile path
+
+__host__ __device__ inline int tq_pad64(int v) { return (v + 63) / 64 * 64; }
+// augmented-K length: three bf16 split terms per quantisation group (zero-point correction) followed by
+// the rank-r intermediate, each region padded to 16, the whole to 64
+__host__ __device__ inline int tq_zero_terms(int K, int g) { return (3 * (K / g) + 15) / 16 * 16; }
+__host__ __device__ inline int tq_aug_len(int K, int g, int n_lr) { return tq_pad64(tq_zero_terms(K, g) + n_lr); }
+
+__host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t T, TqWorkspace* W)
+{
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += tq_align256(bytes); return o; };
+    int64_t a_tot = (int64_t)T * (L.k + L.S);
+    W->a_tot = (int32_t)a_tot;
+    W->rt_max = (int32_t)(a_tot / 32 + L.E + L.S + 1);
+    W->nblk = (int32_t)(((int64_t)T * L.k + TQ_PERM_CHUNK - 1) / TQ_PERM_CHUNK);
+    if (W->nblk < 1) W->nblk = 1;
+    W->ka_gu = tq_aug_len(L.H, L.g, 2 * L.r16);
+    W->ka_d = tq_aug_len(L.F, L.g, L.r16);
+    W->nsplit_max = TQ_MAX_SPLIT;
+    W->ctrl = take(64 * sizeof(int32_t));
+    W->offsets = take((size_t)(L.E + L.S + 1) * 4);
+    W->slot_of = take((size_t)a_tot * 4);
+    W->row_token = take((size_t)a_tot * 4);
+    W->row_w = take((size_t)a_tot * 4);
+    W->tile_e = take((size_t)2 * W->rt_max * 4);
+    W->tile_row0 = take((size_t)2 * W->rt_max * 4);
+    W->hist = take((size_t)W->nblk * L.E * 4);
+    if (act_dtype == TQ_ACT_BF16) {
+        W->xaug_gu = take((size_t)a_tot * W->ka_gu * 2);
+        W->xaug_d = take((size_t)a_tot * W->ka_d * 2);
+        W->h = take((size_t)a_tot * L.F * 2);
+        // the small-tile path may split the down projection's K; the large-tile path never does
+        size_t planes = (a_tot <= 4096) ? TQ_MAX_SPLIT : 1;
+        W->yd = take(planes * (size_t)a_tot * L.H * 4);
+    } else {
+        W->xaug_gu = W->xaug_d = off;
+        W->h = take((size_t)a_tot * L.F * 4);
+        W->yd = take((size_t)a_tot * L.H * 4);
+    }
+    W->total = off;
+}
+
+// ------------------------------------------------------------------------------------------------
+#ifdef __HIPCC__
+__device__ inline float tq_half_bits_to_float(uint16_t h)
+{
+    return __half2float(__ushort_as_half(h));
+}
+
+// expert owning slot `s`: largest e with offsets[e] <= s (offsets is non-decreasing, n+1 entries)
+__device__ inline int tq_find_expert(const int32_t* __restrict__ offsets, int n, int s)
+{
+    int lo = 0, hi = n;  // invariant: offsets[lo] <= s < offsets[hi]
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (offsets[mid] <= s) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+#endif
+
+// internal entry points implemented across the translation units (host side)
+tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32_t T, int32_t E, int32_t S,
+                             int32_t k, int32_t* offsets, int32_t* slot_of, int32_t slot_stride,
+                             int32_t* src_of, int32_t* row_token, float* row_w, int32_t* tile_e,
+                             int32_t* tile_row0, int32_t rt_max, int32_t* ctrl, int32_t* err_flag,
+                             int32_t* hist, int32_t nblk, const void* blob, const TqLayout* L,
+                             hipStream_t stream);
+tq_status tqi_forward_f32(const TqLayout& L, const TqWorkspace& W, const uint8_t* blob, const float* x,
+                          int32_t T, float* y, uint8_t* ws, hipStream_t stream, const float* topk_w);
+tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, const uint8_t* blob,
+                           const uint16_t* x, int32_t T, uint16_t* y, uint8_t* ws, hipStream_t stream,
+                           const float* topk_w);
+
+#define TQ_CHECK_LAUNCH()                                         \
+    do {                                                          \
+        if (hipGetLastError() != hipSuccess) return TQ_ERR_HIP;   \
+    } while (0)

@@ -1,0 +1,168 @@
+// fp32-activation debug path of tq_moe_forward: exact (q - zero) * scale dequantisation, fp32 FMA
+// accumulation, no rounding of intermediates below fp32.  One workgroup per (assignment row, four
+// column-tile pairs); it reads the same packed blob as the MFMA path by index arithmetic.
+// Built for checking the data flow at ~1e-6, not for speed.
+#include "tq_common.h"
+
+namespace {
+
+struct F32Geom {
+    int32_t ne, H, F, g, r, r16, k, S;
+    TqSection gu, d;
+    size_t expert_stride;
+};
+
+__device__ inline float silu_f32(float v) { return v / (1.0f + expf(-v)); }
+
+// STAGE 0: gate/up + SwiGLU (input x gathered by token, output h32[slot][F])
+// STAGE 1: down (input h32[slot][F], output yd[slot][H])
+template <int STAGE>
+__global__ void __launch_bounds__(256) f32_proj_kernel(F32Geom G, const uint8_t* __restrict__ blob,
+                                                       const float* __restrict__ xin,
+                                                       const int32_t* __restrict__ row_token,
+                                                       const int32_t* __restrict__ offsets,
+                                                       const int32_t* __restrict__ ctrl, float* __restrict__ out)
+{
+    extern __shared__ float smem[];
+    const TqSection& sec = STAGE == 0 ? G.gu : G.d;
+    const int K = sec.K;
+    const int NA = STAGE == 0 ? 2 * G.r16 : G.r16;
+    float* xs = smem;        // [K]
+    float* ts = smem + K;    // [NA]
+    const int slot = blockIdx.x;
+    if (slot >= ctrl[3]) return;
+    const int e = tq_find_expert(offsets, G.ne, slot);
+    const float* xrow = STAGE == 0 ? xin + (size_t)row_token[slot] * G.H : xin + (size_t)slot * G.F;
+    for (int kk = threadIdx.x; kk < K; kk += 256) xs[kk] = xrow[kk];
+    __syncthreads();
+    const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 31, hf = lane >> 5;
+    // t[c] = sum_kk x[kk] * A[kk][c]
+    if (G.r > 0) {
+        const uint16_t* af = reinterpret_cast<const uint16_t*>(rec + sec.afrag);
+        const int ksteps = K / 16;
+        for (int c = wave; c < NA; c += 4) {
+            const int ta = c >> 5, cl = c & 31;
+            float p = 0.f;
+            for (int kk = lane; kk < K; kk += 64) {
+                int s = kk >> 4, h2 = (kk >> 3) & 1, i = kk & 7;
+                size_t ai = (((size_t)ta * ksteps + s) * 64 + h2 * 32 + cl) * 8 + i;
+                p = fmaf(xs[kk], tq_half_bits_to_float(af[ai]), p);
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) p += __shfl_xor(p, off);
+            if (lane == 0) ts[c] = p;
+        }
+    }
+    __syncthreads();
+    const int pair = blockIdx.y * 4 + wave;
+    if (pair >= sec.pairs) return;
+    float res[2];
+#pragma unroll
+    for (int tile = 0; tile < 2; ++tile) {
+        const uint4* cw = reinterpret_cast<const uint4*>(rec + sec.codes) + ((size_t)pair * sec.chunks * 2 + tile) * 64 + lane;
+        const uint32_t* szp = reinterpret_cast<const uint32_t*>(rec + sec.sz) + ((size_t)pair * sec.groups * 2 + tile) * 32 + col;
+        float acc = 0.f, part = 0.f, s = 0.f, z = 0.f;
+        int cur = -1;
+        for (int c = 0; c < sec.chunks; ++c) {
+            uint4 v = cw[(size_t)c * 128];
+            uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                int gi = (64 * c + 16 * w) / G.g;
+                if (gi != cur) {
+                    acc = fmaf(part, s, acc);
+                    part = 0.f;
+                    uint32_t sz = szp[(size_t)gi * 64];
+                    s = tq_half_bits_to_float((uint16_t)(sz & 0xFFFF));
+                    z = tq_half_bits_to_float((uint16_t)(sz >> 16));
+                    cur = gi;
+                }
+                const int kk0 = 64 * c + 16 * w + 8 * hf;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    float q = (float)((wd[w] >> (4 * tq_nibble_pos(i))) & 15u);
+                    part = fmaf(xs[kk0 + i], q - z, part);
+                }
+            }
+        }
+        acc = fmaf(part, s, acc);
+        if (G.r > 0) {
+            const uint4* bf = reinterpret_cast<const uint4*>(rec + sec.bfrag) + ((size_t)pair * (G.r16 / 16) * 2 + tile) * 64 + lane;
+            const float* tp = ts + (STAGE == 0 ? tile * G.r16 : 0);
+            float lr = 0.f;
+            for (int st = 0; st < G.r16 / 16; ++st) {
+                uint4 b = bf[(size_t)st * 128];
+                uint32_t bw[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    uint16_t hb = (uint16_t)(bw[i >> 1] >> (16 * (i & 1)));
+                    lr = fmaf(tp[16 * st + 8 * hf + i], tq_half_bits_to_float(hb), lr);
+                }
+            }
+            acc += lr;
+        }
+        acc += __shfl_xor(acc, 32);
+        res[tile] = acc;
+    }
+    if (hf == 0) {
+        if (STAGE == 0) {
+            out[(size_t)slot * G.F + 32 * pair + col] = silu_f32(res[0]) * res[1];
+        } else {
+            out[(size_t)slot * G.H + 64 * pair + col] = res[0];
+            out[(size_t)slot * G.H + 64 * pair + 32 + col] = res[1];
+        }
+    }
+}
+
+// y[t][c] = sum_j w[t][j] * yd[slot_of[t][j]][c] + sum_s yd[slot_of[t][k+s]][c], terms added in slot order
+__global__ void __launch_bounds__(256) f32_combine_kernel(int T, int H, int k, int S,
+                                                          const int32_t* __restrict__ slot_of,
+                                                          const float* __restrict__ w,
+                                                          const float* __restrict__ yd, float* __restrict__ y)
+{
+    const int t = blockIdx.x;
+    const int c = blockIdx.y * 256 + threadIdx.x;
+    if (c >= H) return;
+    float acc = 0.f;
+    for (int j = 0; j < k + S; ++j) {
+        int slot = slot_of[(size_t)t * (k + S) + j];
+        if (slot < 0) continue;
+        float wj = j < k ? w[(size_t)t * k + j] : 1.0f;
+        acc = fmaf(wj, yd[(size_t)slot * H + c], acc);
+    }
+    y[(size_t)t * H + c] = acc;
+}
+
+}  // namespace
+
+tq_status tqi_forward_f32(const TqLayout& L, const TqWorkspace& W, const uint8_t* blob, const float* x,
+                          int32_t T, float* y, uint8_t* ws, hipStream_t stream, const float* topk_w)
+{
+    F32Geom G;
+    G.ne = L.E + L.S; G.H = L.H; G.F = L.F; G.g = L.g; G.r = L.r; G.r16 = L.r16; G.k = L.k; G.S = L.S;
+    G.gu = L.gu; G.d = L.d; G.expert_stride = L.expert_stride;
+    const int32_t* ctrl = reinterpret_cast<const int32_t*>(ws + W.ctrl);
+    const int32_t* offsets = reinterpret_cast<const int32_t*>(ws + W.offsets);
+    const int32_t* slot_of = reinterpret_cast<const int32_t*>(ws + W.slot_of);
+    const int32_t* row_token = reinterpret_cast<const int32_t*>(ws + W.row_token);
+    float* h32 = reinterpret_cast<float*>(ws + W.h);
+    float* yd = reinterpret_cast<float*>(ws + W.yd);
+    size_t sm0 = ((size_t)L.H + 2 * L.r16) * 4, sm1 = ((size_t)L.F + L.r16) * 4;
+    if (sm0 > 160 * 1024 || sm1 > 160 * 1024) return TQ_ERR_UNSUPPORTED;
+    if (sm0 > 48 * 1024)
+        if (hipFuncSetAttribute((const void*)f32_proj_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm0) != hipSuccess) return TQ_ERR_HIP;
+    if (sm1 > 48 * 1024)
+        if (hipFuncSetAttribute((const void*)f32_proj_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm1) != hipSuccess) return TQ_ERR_HIP;
+    hipLaunchKernelGGL(f32_proj_kernel<0>, dim3(W.a_tot, (L.gu.pairs + 3) / 4), dim3(256), sm0, stream, G, blob, x,
+                       row_token, offsets, ctrl, h32);
+    TQ_CHECK_LAUNCH();
+    hipLaunchKernelGGL(f32_proj_kernel<1>, dim3(W.a_tot, (L.d.pairs + 3) / 4), dim3(256), sm1, stream, G, blob, h32,
+                       row_token, offsets, ctrl, yd);
+    TQ_CHECK_LAUNCH();
+    hipLaunchKernelGGL(f32_combine_kernel, dim3(T, (L.H + 255) / 256), dim3(256), 0, stream, T, L.H, L.k, L.S,
+                       slot_of, topk_w, yd, y);
+    TQ_CHECK_LAUNCH();
+    return TQ_OK;
+}

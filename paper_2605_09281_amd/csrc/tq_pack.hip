@@ -1,0 +1,263 @@
+// tq_pack_weights / tq_unpack_weights: canonical expert weights <-> the packed blob whose layout
+// include/tileq.h specifies.  Pure index arithmetic; every element is moved bit for bit.
+#include "tq_common.h"
+
+namespace {
+
+struct PackGeom {
+    int32_t n_exp, H, F, g, r, r16, qmax;
+    TqSection gu, d;
+    size_t expert_stride;
+};
+
+__global__ void write_header_kernel(TqBlobHeader hdr, uint8_t* blob)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        TqBlobHeader* out = reinterpret_cast<TqBlobHeader*>(blob);
+        *out = hdr;
+    }
+}
+
+// One thread per packed 32-bit code word.  PACK: gather 8 canonical bytes -> word.  !PACK: scatter.
+template <bool PACK>
+__global__ void codes_kernel(PackGeom G, uint8_t* __restrict__ blob, uint8_t* __restrict__ codes,
+                             int32_t* __restrict__ err_flag)
+{
+    const size_t words_gu = (size_t)G.gu.pairs * G.gu.chunks * 512;  // 2 tiles * 64 lanes * 4 words
+    const size_t words_d = (size_t)G.d.pairs * G.d.chunks * 512;
+    const size_t per_exp = words_gu + words_d;
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= per_exp * G.n_exp) return;
+    int e = (int)(idx / per_exp);
+    size_t w = idx % per_exp;
+    const bool is_d = w >= words_gu;
+    const TqSection& sec = is_d ? G.d : G.gu;
+    if (is_d) w -= words_gu;
+    int word = (int)(w & 3);
+    int lane = (int)((w >> 2) & 63);
+    int tile = (int)((w >> 8) & 1);
+    size_t pc = w >> 9;
+    int chunk = (int)(pc % sec.chunks);
+    int pair = (int)(pc / sec.chunks);
+    int col = lane & 31, hf = lane >> 5;
+    int kk = 64 * chunk + 16 * word + 8 * hf;
+    int p, n, K = sec.K;
+    if (!is_d) { p = tile; n = 32 * pair + col; }
+    else       { p = 2;    n = 64 * pair + 32 * tile + col; }
+    const size_t HF = (size_t)G.H * G.F;
+    uint8_t* src = codes + ((size_t)e * 3 + p) * HF + (size_t)n * K + kk;
+    uint32_t* dst = reinterpret_cast<uint32_t*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.codes) + w;
+    if (PACK) {
+        uint64_t v = *reinterpret_cast<const uint64_t*>(src);
+        uint32_t out = 0;
+        bool bad = false;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            uint32_t c = (uint32_t)(v >> (8 * i)) & 0xFF;
+            bad |= c > (uint32_t)G.qmax;
+            out |= (c & 15u) << (4 * tq_nibble_pos(i));
+        }
+        *dst = out;
+        if (bad && err_flag) atomicOr(err_flag, TQ_FLAG_BIT_RANGE);
+    } else {
+        uint32_t in = *dst;
+        uint64_t v = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v |= (uint64_t)((in >> (4 * tq_nibble_pos(i))) & 15u) << (8 * i);
+        *reinterpret_cast<uint64_t*>(src) = v;
+    }
+}
+
+// One thread per (scale, zero) word.
+template <bool PACK>
+__global__ void sz_kernel(PackGeom G, uint8_t* __restrict__ blob, uint16_t* __restrict__ scale,
+                          uint16_t* __restrict__ zero)
+{
+    const size_t n_gu = (size_t)G.gu.pairs * G.gu.groups * 64;
+    const size_t n_d = (size_t)G.d.pairs * G.d.groups * 64;
+    const size_t per_exp = n_gu + n_d;
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= per_exp * G.n_exp) return;
+    int e = (int)(idx / per_exp);
+    size_t w = idx % per_exp;
+    const bool is_d = w >= n_gu;
+    const TqSection& sec = is_d ? G.d : G.gu;
+    if (is_d) w -= n_gu;
+    int col = (int)(w & 31);
+    int tile = (int)((w >> 5) & 1);
+    size_t pg = w >> 6;
+    int grp = (int)(pg % sec.groups);
+    int pair = (int)(pg / sec.groups);
+    int p, n;
+    if (!is_d) { p = tile; n = 32 * pair + col; }
+    else       { p = 2;    n = 64 * pair + 32 * tile + col; }
+    const size_t HFg = (size_t)G.H * G.F / G.g;
+    size_t ci = ((size_t)e * 3 + p) * HFg + (size_t)n * sec.groups + grp;
+    uint32_t* dst = reinterpret_cast<uint32_t*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.sz) + w;
+    if (PACK) {
+        *dst = (uint32_t)scale[ci] | ((uint32_t)zero[ci] << 16);
+    } else {
+        uint32_t v = *dst;
+        scale[ci] = (uint16_t)(v & 0xFFFF);
+        zero[ci] = (uint16_t)(v >> 16);
+    }
+}
+
+// One thread per 8-element fragment of B.  Padding rows (rho >= r) are written as zero and skipped on unpack.
+template <bool PACK>
+__global__ void bfrag_kernel(PackGeom G, uint8_t* __restrict__ blob, uint16_t* __restrict__ B)
+{
+    const int steps = G.r16 / 16;
+    const size_t n_gu = (size_t)G.gu.pairs * steps * 128;
+    const size_t n_d = (size_t)G.d.pairs * steps * 128;
+    const size_t per_exp = n_gu + n_d;
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= per_exp * G.n_exp) return;
+    int e = (int)(idx / per_exp);
+    size_t w = idx % per_exp;
+    const bool is_d = w >= n_gu;
+    const TqSection& sec = is_d ? G.d : G.gu;
+    if (is_d) w -= n_gu;
+    int lane = (int)(w & 63);
+    int tile = (int)((w >> 6) & 1);
+    size_t ps = w >> 7;
+    int step = (int)(ps % steps);
+    int pair = (int)(ps / steps);
+    int col = lane & 31, hf = lane >> 5;
+    int p, n, N;
+    if (!is_d) { p = tile; n = 32 * pair + col; N = G.F; }
+    else       { p = 2;    n = 64 * pair + 32 * tile + col; N = G.H; }
+    const size_t b_per_exp = (2 * (size_t)G.F + G.H) * G.r;
+    const size_t b_off = (p == 0) ? 0 : (p == 1) ? (size_t)G.F * G.r : 2 * (size_t)G.F * G.r;
+    uint16_t* src = B + (size_t)e * b_per_exp + b_off;
+    uint16_t* dst = reinterpret_cast<uint16_t*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.bfrag) + w * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int rho = 16 * step + 8 * hf + i;
+        if (PACK) dst[i] = (rho < G.r) ? src[(size_t)rho * N + n] : (uint16_t)0;
+        else if (rho < G.r) src[(size_t)rho * N + n] = dst[i];
+    }
+}
+
+// One thread per 8-element fragment of A.
+template <bool PACK>
+__global__ void afrag_kernel(PackGeom G, uint8_t* __restrict__ blob, uint16_t* __restrict__ A)
+{
+    const size_t n_gu = (size_t)G.gu.na_tiles * (G.gu.K / 16) * 64;
+    const size_t n_d = (size_t)G.d.na_tiles * (G.d.K / 16) * 64;
+    const size_t per_exp = n_gu + n_d;
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= per_exp * G.n_exp) return;
+    int e = (int)(idx / per_exp);
+    size_t w = idx % per_exp;
+    const bool is_d = w >= n_gu;
+    const TqSection& sec = is_d ? G.d : G.gu;
+    if (is_d) w -= n_gu;
+    int lane = (int)(w & 63);
+    size_t ts = w >> 6;
+    int ksteps = sec.K / 16;
+    int step = (int)(ts % ksteps);
+    int ta = (int)(ts / ksteps);
+    int c = 32 * ta + (lane & 31), hf = lane >> 5;
+    int na = is_d ? G.r16 : 2 * G.r16;
+    int p = is_d ? 2 : (c / G.r16);
+    int rho = c % G.r16;
+    const bool live = (c < na) && (rho < G.r);
+    const size_t a_per_exp = (2 * (size_t)G.H + G.F) * G.r;
+    const size_t a_off = (p == 0) ? 0 : (p == 1) ? (size_t)G.H * G.r : 2 * (size_t)G.H * G.r;
+    uint16_t* src = A + (size_t)e * a_per_exp + a_off;
+    uint16_t* dst = reinterpret_cast<uint16_t*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.afrag) + w * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int kk = 16 * step + 8 * hf + i;
+        if (PACK) dst[i] = live ? src[(size_t)kk * G.r + rho] : (uint16_t)0;
+        else if (live) src[(size_t)kk * G.r + rho] = dst[i];
+    }
+}
+
+inline PackGeom make_geom(const TqLayout& L)
+{
+    PackGeom G;
+    G.n_exp = L.E + L.S; G.H = L.H; G.F = L.F; G.g = L.g; G.r = L.r; G.r16 = L.r16;
+    G.qmax = (1 << L.bits) - 1;
+    G.gu = L.gu; G.d = L.d; G.expert_stride = L.expert_stride;
+    return G;
+}
+
+inline unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
+
+template <bool PACK>
+tq_status run(const TqLayout& L, uint8_t* blob, uint8_t* codes, uint16_t* scale, uint16_t* zero,
+              uint16_t* A, uint16_t* B, int32_t* err_flag, hipStream_t st)
+{
+    PackGeom G = make_geom(L);
+    const size_t ne = G.n_exp;
+    size_t n_codes = ((size_t)L.gu.pairs * L.gu.chunks + (size_t)L.d.pairs * L.d.chunks) * 512 * ne;
+    size_t n_sz = ((size_t)L.gu.pairs * L.gu.groups + (size_t)L.d.pairs * L.d.groups) * 64 * ne;
+    if (n_codes / 256 > 0x7FFFFFFFull) return TQ_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(codes_kernel<PACK>, dim3(blocks_for(n_codes)), dim3(256), 0, st, G, blob, codes, err_flag);
+    TQ_CHECK_LAUNCH();
+    hipLaunchKernelGGL(sz_kernel<PACK>, dim3(blocks_for(n_sz)), dim3(256), 0, st, G, blob, scale, zero);
+    TQ_CHECK_LAUNCH();
+    if (L.r > 0) {
+        size_t n_b = ((size_t)L.gu.pairs + L.d.pairs) * (L.r16 / 16) * 128 * ne;
+        size_t n_a = ((size_t)L.gu.na_tiles * (L.gu.K / 16) + (size_t)L.d.na_tiles * (L.d.K / 16)) * 64 * ne;
+        hipLaunchKernelGGL(bfrag_kernel<PACK>, dim3(blocks_for(n_b)), dim3(256), 0, st, G, blob, B);
+        TQ_CHECK_LAUNCH();
+        hipLaunchKernelGGL(afrag_kernel<PACK>, dim3(blocks_for(n_a)), dim3(256), 0, st, G, blob, A);
+        TQ_CHECK_LAUNCH();
+    }
+    return TQ_OK;
+}
+
+inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
+
+}  // namespace
+
+extern "C" size_t tq_packed_size(const tq_layer_desc* desc)
+{
+    TqLayout L;
+    if (!tq_make_layout(desc, &L)) return 0;
+    return L.total_bytes;
+}
+
+extern "C" tq_status tq_pack_weights(const tq_layer_desc* desc, const tq_weights_src* src, void* packed,
+                                     size_t packed_bytes, int32_t* err_flag, void* stream)
+{
+    if (!desc || !src || !packed || !src->codes || !src->scale || !src->zero) return TQ_ERR_NULL;
+    TqLayout L;
+    if (!tq_make_layout(desc, &L)) return TQ_ERR_SHAPE;
+    if (L.r > 0 && (!src->A || !src->B)) return TQ_ERR_NULL;
+    if (packed_bytes < L.total_bytes) return TQ_ERR_WORKSPACE;
+    if (misaligned(packed, 256) || misaligned(src->codes, 16) || misaligned(src->scale, 16) ||
+        misaligned(src->zero, 16) || (L.r > 0 && (misaligned(src->A, 16) || misaligned(src->B, 16))) ||
+        misaligned(err_flag, 4))
+        return TQ_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    TqBlobHeader hdr = {};
+    hdr.magic = TQ_BLOB_MAGIC; hdr.version = TQ_BLOB_VERSION;
+    hdr.n_experts = L.E; hdr.n_shared = L.S; hdr.hidden = L.H; hdr.ffn = L.F; hdr.group = L.g;
+    hdr.bits = L.bits; hdr.rank = L.r; hdr.r16 = L.r16;
+    hdr.expert_stride = L.expert_stride; hdr.total_bytes = L.total_bytes;
+    hdr.off[0] = L.gu.codes; hdr.off[1] = L.gu.sz; hdr.off[2] = L.gu.bfrag; hdr.off[3] = L.gu.afrag;
+    hdr.off[4] = L.d.codes; hdr.off[5] = L.d.sz; hdr.off[6] = L.d.bfrag; hdr.off[7] = L.d.afrag;
+    hipLaunchKernelGGL(write_header_kernel, dim3(1), dim3(64), 0, st, hdr, (uint8_t*)packed);
+    TQ_CHECK_LAUNCH();
+    return run<true>(L, (uint8_t*)packed, const_cast<uint8_t*>(src->codes), const_cast<uint16_t*>(src->scale),
+                     const_cast<uint16_t*>(src->zero), const_cast<uint16_t*>(src->A),
+                     const_cast<uint16_t*>(src->B), err_flag, st);
+}
+
+extern "C" tq_status tq_unpack_weights(const tq_layer_desc* desc, const void* packed, const tq_weights_dst* dst,
+                                       void* stream)
+{
+    if (!desc || !dst || !packed || !dst->codes || !dst->scale || !dst->zero) return TQ_ERR_NULL;
+    TqLayout L;
+    if (!tq_make_layout(desc, &L)) return TQ_ERR_SHAPE;
+    if (L.r > 0 && (!dst->A || !dst->B)) return TQ_ERR_NULL;
+    if (misaligned(packed, 256) || misaligned(dst->codes, 16) || misaligned(dst->scale, 16) ||
+        misaligned(dst->zero, 16) || (L.r > 0 && (misaligned(dst->A, 16) || misaligned(dst->B, 16))))
+        return TQ_ERR_ALIGN;
+    return run<false>(L, const_cast<uint8_t*>((const uint8_t*)packed), dst->codes, dst->scale, dst->zero, dst->A,
+                      dst->B, nullptr, (hipStream_t)stream);
+}

@@ -1,0 +1,277 @@
+// tq_route (top-k selection and routing weights) and the token -> expert permutation with
+// prefix-sum offsets (histogram, scan, stable scatter) that tq_permute exports and tq_moe_forward
+// runs as its first step.
+#include "tq_common.h"
+
+namespace {
+
+constexpr int kMaxPerLane = 16;  // E <= 64 * 16
+
+// One wavefront per token.  Lane l holds the scores of experts l, l+64, l+128, ...
+// Each of the k rounds takes the wave-wide maximum under the order (score desc, index asc).
+__global__ void __launch_bounds__(256) route_kernel(const float* __restrict__ logits,
+                                                    const float* __restrict__ bias, int T, int E, int k,
+                                                    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w)
+{
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (t >= T) return;
+    float v[kMaxPerLane];
+    uint32_t taken = 0;
+    const int per_lane = (E + 63) >> 6;
+#pragma unroll
+    for (int i = 0; i < kMaxPerLane; ++i) {
+        int e = lane + 64 * i;
+        float s = -INFINITY;
+        if (i < per_lane && e < E) {
+            s = logits[(size_t)t * E + e];
+            if (bias) s = s + bias[e];
+        } else {
+            taken |= 1u << i;
+        }
+        v[i] = s;
+    }
+    float first = 0.f, denom = 0.f, my_p = 0.f;
+    for (int j = 0; j < k; ++j) {
+        // best candidate of this lane: ascending index scan with a strict compare keeps the lowest index
+        float bv = 0.f;
+        int be = 0x7FFFFFFF;
+#pragma unroll
+        for (int i = 0; i < kMaxPerLane; ++i) {
+            if (!((taken >> i) & 1u)) {
+                if (be == 0x7FFFFFFF || v[i] > bv) { bv = v[i]; be = lane + 64 * i; }
+            }
+        }
+        // wave-wide arg-max under (score desc, index asc); lanes with nothing left carry index INT_MAX
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            float ov = __shfl_xor(bv, off);
+            int oe = __shfl_xor(be, off);
+            bool take = (oe != 0x7FFFFFFF) && (be == 0x7FFFFFFF || ov > bv || (ov == bv && oe < be));
+            if (take) { bv = ov; be = oe; }
+        }
+        if ((be & 63) == lane) taken |= 1u << (be >> 6);
+        if (j == 0) first = bv;
+        float p = expf(bv - first);       // the same value in every lane
+        denom += p;
+        if (lane == j) my_p = p;          // lane j keeps the unnormalised weight of slot j (k <= 64)
+        if (lane == 0) topk_idx[(size_t)t * k + j] = be;
+    }
+    if (lane < k) topk_w[(size_t)t * k + lane] = my_p / denom;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Permutation.  Assignments are cut into chunks of TQ_PERM_CHUNK; one wavefront per chunk.
+//   hist_kernel:   per-chunk histogram over experts (also clears/validates the control block)
+//   scan_kernel:   per expert, exclusive scan over chunks; offsets; row-tile tables
+//   scatter_kernel: stable placement, chunk by chunk, 64 assignments per round in order
+__global__ void __launch_bounds__(64) hist_kernel(const int32_t* __restrict__ idx, int64_t n_assign, int E,
+                                                  int32_t* __restrict__ hist, int32_t* __restrict__ err_flag,
+                                                  const TqBlobHeader* __restrict__ hdr, TqBlobHeader expect,
+                                                  int check_blob)
+{
+    extern __shared__ int32_t cnt[];
+    const int lane = threadIdx.x;
+    for (int e = lane; e < E; e += 64) cnt[e] = 0;
+    __syncthreads();
+    const int64_t a0 = (int64_t)blockIdx.x * TQ_PERM_CHUNK;
+    bool bad = false;
+    for (int i = lane; i < TQ_PERM_CHUNK; i += 64) {
+        int64_t a = a0 + i;
+        if (a < n_assign) {
+            int e = idx[a];
+            if (e >= 0 && e < E) atomicAdd(&cnt[e], 1); else bad = true;
+        }
+    }
+    __syncthreads();
+    for (int e = lane; e < E; e += 64) hist[(size_t)blockIdx.x * E + e] = cnt[e];
+    if (bad && err_flag) atomicOr(err_flag, TQ_FLAG_BIT_RANGE);
+    if (check_blob && blockIdx.x == 0 && lane == 0) {
+        bool ok = hdr->magic == expect.magic && hdr->version == expect.version &&
+                  hdr->n_experts == expect.n_experts && hdr->n_shared == expect.n_shared &&
+                  hdr->hidden == expect.hidden && hdr->ffn == expect.ffn && hdr->group == expect.group &&
+                  hdr->bits == expect.bits && hdr->rank == expect.rank &&
+                  hdr->expert_stride == expect.expert_stride;
+        if (!ok && err_flag) atomicOr(err_flag, TQ_FLAG_BIT_BLOB);
+    }
+}
+
+// Single block.  hist[b][e] becomes the number of assignments of expert e in chunks before b.
+__global__ void __launch_bounds__(256) scan_kernel(int32_t* __restrict__ hist, int nblk, int E, int S, int T,
+                                                   int32_t* __restrict__ offsets, int32_t* __restrict__ tile_e,
+                                                   int32_t* __restrict__ tile_row0, int rt_max,
+                                                   int32_t* __restrict__ ctrl)
+{
+    extern __shared__ int32_t sm[];   // counts[E+S], then scratch
+    int32_t* counts = sm;
+    const int ne = E + S;
+    for (int e = threadIdx.x; e < E; e += blockDim.x) {
+        int run = 0;
+        for (int b = 0; b < nblk; ++b) {
+            int c = hist[(size_t)b * E + e];
+            hist[(size_t)b * E + e] = run;
+            run += c;
+        }
+        counts[e] = run;
+    }
+    for (int s = threadIdx.x; s < S; s += blockDim.x) counts[E + s] = T;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int e = 0; e < ne; ++e) { offsets[e] = run; run += counts[e]; }
+        offsets[ne] = run;
+        if (ctrl) ctrl[3] = run;
+    }
+    __syncthreads();
+    if (tile_e && threadIdx.x < 2) {
+        // row-tile tables for the 32-row (index 0) and 128-row (index 1) tilings
+        const int which = threadIdx.x;
+        const int bm = which ? 128 : 32;
+        int32_t* te = tile_e + (size_t)which * rt_max;
+        int32_t* tr = tile_row0 + (size_t)which * rt_max;
+        int n = 0;
+        for (int e = 0; e < ne; ++e) {
+            int o = offsets[e], c = counts[e];
+            for (int r0 = 0; r0 < c && n < rt_max; r0 += bm) { te[n] = e; tr[n] = o + r0; ++n; }
+        }
+        ctrl[1 + which] = n;
+    }
+}
+
+__global__ void __launch_bounds__(64) scatter_kernel(const int32_t* __restrict__ idx, const float* __restrict__ w,
+                                                     int64_t n_assign, int E, int S, int T, int k,
+                                                     const int32_t* __restrict__ hist,
+                                                     const int32_t* __restrict__ offsets,
+                                                     int32_t* __restrict__ slot_of, int slot_stride,
+                                                     int32_t* __restrict__ src_of, int32_t* __restrict__ row_token,
+                                                     float* __restrict__ row_w)
+{
+    extern __shared__ int32_t cursor[];   // next free slot of each expert for this chunk
+    const int lane = threadIdx.x;
+    for (int e = lane; e < E; e += 64) cursor[e] = offsets[e] + hist[(size_t)blockIdx.x * E + e];
+    __syncthreads();
+    const int64_t a0 = (int64_t)blockIdx.x * TQ_PERM_CHUNK;
+    for (int i0 = 0; i0 < TQ_PERM_CHUNK; i0 += 64) {
+        int64_t a = a0 + i0 + lane;
+        int e = -1;
+        if (a < n_assign) {
+            e = idx[a];
+            if (e < 0 || e >= E) e = -1;
+        }
+        // rank of this lane among the lanes of the round that hold the same expert and come before it
+        int slot = -1;
+        uint64_t todo = __ballot(e >= 0);
+        while (todo) {
+            int leader = __ffsll((unsigned long long)todo) - 1;
+            int le = __shfl(e, leader);
+            uint64_t same = __ballot(e == le);
+            if (e == le) {
+                uint64_t before = same & ((1ull << lane) - 1ull);
+                slot = cursor[le] + __popcll(before);
+            }
+            __syncthreads();
+            if (lane == leader) cursor[le] += __popcll(same);
+            __syncthreads();
+            todo &= ~same;
+        }
+        if (a < n_assign) {
+            int t = (int)(a / k), j = (int)(a % k);
+            if (slot_of) slot_of[(size_t)t * slot_stride + j] = slot;
+            if (slot >= 0) {
+                if (src_of) src_of[slot] = (int32_t)a;
+                if (row_token) row_token[slot] = t;
+                if (row_w) row_w[slot] = w ? w[a] : 1.0f;
+            }
+        }
+    }
+    // shared experts: every token, weight 1, identity order
+    if (S > 0) {
+        const int64_t total = (int64_t)S * T;
+        for (int64_t i = (int64_t)blockIdx.x * 64 + lane; i < total; i += (int64_t)gridDim.x * 64) {
+            int s = (int)(i / T), t = (int)(i % T);
+            int slot = offsets[E + s] + t;
+            if (slot_of) slot_of[(size_t)t * slot_stride + k + s] = slot;
+            if (row_token) row_token[slot] = t;
+            if (row_w) row_w[slot] = 1.0f;
+        }
+    }
+}
+
+__global__ void clear_ctrl_kernel(int32_t* ctrl, int32_t* err_flag)
+{
+    if (threadIdx.x < 64 && ctrl) ctrl[threadIdx.x] = 0;
+    if (threadIdx.x == 0 && err_flag && err_flag != ctrl) *err_flag = 0;
+}
+
+}  // namespace
+
+tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32_t T, int32_t E, int32_t S,
+                             int32_t k, int32_t* offsets, int32_t* slot_of, int32_t slot_stride,
+                             int32_t* src_of, int32_t* row_token, float* row_w, int32_t* tile_e,
+                             int32_t* tile_row0, int32_t rt_max, int32_t* ctrl, int32_t* err_flag,
+                             int32_t* hist, int32_t nblk, const void* blob, const TqLayout* L,
+                             hipStream_t stream)
+{
+    const int64_t n_assign = (int64_t)T * k;
+    TqBlobHeader expect = {};
+    int check = 0;
+    if (blob && L) {
+        check = 1;
+        expect.magic = TQ_BLOB_MAGIC; expect.version = TQ_BLOB_VERSION;
+        expect.n_experts = L->E; expect.n_shared = L->S; expect.hidden = L->H; expect.ffn = L->F;
+        expect.group = L->g; expect.bits = L->bits; expect.rank = L->r; expect.expert_stride = L->expert_stride;
+    }
+    if (ctrl) {
+        hipLaunchKernelGGL(clear_ctrl_kernel, dim3(1), dim3(64), 0, stream, ctrl, err_flag);
+        TQ_CHECK_LAUNCH();
+    }
+    hipLaunchKernelGGL(hist_kernel, dim3(nblk), dim3(64), (size_t)E * 4, stream, topk_idx, n_assign, E, hist,
+                       err_flag, (const TqBlobHeader*)blob, expect, check);
+    TQ_CHECK_LAUNCH();
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), (size_t)(E + S) * 4, stream, hist, nblk, E, S, T, offsets,
+                       tile_e, tile_row0, rt_max, ctrl);
+    TQ_CHECK_LAUNCH();
+    hipLaunchKernelGGL(scatter_kernel, dim3(nblk), dim3(64), (size_t)E * 4, stream, topk_idx, topk_w, n_assign, E,
+                       S, T, k, hist, offsets, slot_of, slot_stride, src_of, row_token, row_w);
+    TQ_CHECK_LAUNCH();
+    return TQ_OK;
+}
+
+extern "C" tq_status tq_route(const float* logits, const float* bias, int32_t T, int32_t E, int32_t k,
+                              int32_t* topk_idx, float* topk_w, void* stream)
+{
+    if (!logits || !topk_idx || !topk_w) return TQ_ERR_NULL;
+    if (T < 0 || E < 1 || k < 1 || k > E) return TQ_ERR_SHAPE;
+    if (E > 64 * kMaxPerLane || k > 64) return TQ_ERR_UNSUPPORTED;
+    if (((uintptr_t)logits | (uintptr_t)topk_idx | (uintptr_t)topk_w | (uintptr_t)bias) & 3) return TQ_ERR_ALIGN;
+    if (T == 0) return TQ_OK;
+    hipLaunchKernelGGL(route_kernel, dim3((T + 3) / 4), dim3(256), 0, (hipStream_t)stream, logits, bias, T, E, k,
+                       topk_idx, topk_w);
+    TQ_CHECK_LAUNCH();
+    return TQ_OK;
+}
+
+extern "C" size_t tq_permute_workspace_size(int32_t T, int32_t E, int32_t k)
+{
+    if (T < 0 || E < 1 || k < 1) return 0;
+    int64_t nblk = ((int64_t)T * k + TQ_PERM_CHUNK - 1) / TQ_PERM_CHUNK;
+    if (nblk < 1) nblk = 1;
+    return tq_align256((size_t)nblk * E * 4);
+}
+
+extern "C" tq_status tq_permute(const int32_t* topk_idx, int32_t T, int32_t E, int32_t k, int32_t* offsets,
+                                int32_t* slot_of, int32_t* src_of, int32_t* err_flag, void* workspace,
+                                size_t workspace_bytes, void* stream)
+{
+    if (!topk_idx || !offsets || !slot_of || !src_of || !workspace) return TQ_ERR_NULL;
+    if (T < 0 || E < 1 || E > 1024 || k < 1 || k > E) return TQ_ERR_SHAPE;
+    if (workspace_bytes < tq_permute_workspace_size(T, E, k)) return TQ_ERR_WORKSPACE;
+    if (((uintptr_t)topk_idx | (uintptr_t)offsets | (uintptr_t)slot_of | (uintptr_t)src_of |
+         (uintptr_t)err_flag | (uintptr_t)workspace) & 3)
+        return TQ_ERR_ALIGN;
+    int64_t nblk = ((int64_t)T * k + TQ_PERM_CHUNK - 1) / TQ_PERM_CHUNK;
+    if (nblk < 1) nblk = 1;
+    return tqi_launch_permute(topk_idx, nullptr, T, E, 0, k, offsets, slot_of, k, src_of, nullptr, nullptr,
+                              nullptr, nullptr, 0, nullptr, err_flag, (int32_t*)workspace, (int32_t)nblk, nullptr,
+                              nullptr, (hipStream_t)stream);
+}

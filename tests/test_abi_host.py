@@ -1,0 +1,98 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, and its host-side
+argument checks and size accounting behave as include/tileq.h says (no kernel is launched)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_09281_amd.binding as tq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    hdr = open(os.path.join(ROOT, "include", "tileq.h")).read()
+    declared = sorted(set(re.findall(r"^(?:const char \*|size_t |tq_status )(tq_[a-z_0-9]+)\(", hdr, flags=re.M)))
+    assert set(declared) == set(tq.EXPORTS), declared
+    L = tq.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_status_strings():
+    assert tq.tq_status_str(0) == "ok"
+    for s in range(1, 9):
+        assert tq.tq_status_str(s) not in ("ok", "unknown status")
+
+
+@pytest.mark.parametrize("E,S,H,F,g,r", [(8, 0, 4096, 14336, 128, 32), (60, 0, 2048, 1408, 64, 64),
+                                         (128, 0, 4096, 1536, 128, 32), (4, 1, 256, 512, 64, 32)])
+def test_packed_size_closed_form(E, S, H, F, g, r):
+    """Appendix A.3, per-expert low-rank storage: d = d_basic + r d_fp (1/i + 1/o) bits per weight, here with
+    4-bit codes, a 16-bit scale and a 16-bit zero per group and 16-bit factors (no Sigma is stored)."""
+    n = tq.tq_packed_size(tq.make_desc(E, S, 2, H, F, g, 4, r))
+    bits = 8.0 * (n - 256) / (3 * H * F * (E + S))
+    assert abs(bits - (4 + 32 / g + 16 * r * (1 / H + 1 / F))) < 1e-9
+    with open(os.path.join(ROOT, "tests", "golden", "bits_per_weight.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            h, ff, gg, rr, val = line.split()
+            if (int(h), int(ff), int(gg), int(rr)) == (H, F, g, r):
+                assert abs(bits - float(val)) < 5e-7
+
+
+def test_packed_size_rank_padding_and_zero_rank():
+    base = tq.tq_packed_size(tq.make_desc(4, 0, 2, 256, 512, 64, 4, 0))
+    assert (base - 256) * 8 == 4 * 3 * 256 * 512 * (4 + 32 / 64)
+    n8 = tq.tq_packed_size(tq.make_desc(4, 0, 2, 256, 512, 64, 4, 8))
+    n16 = tq.tq_packed_size(tq.make_desc(4, 0, 2, 256, 512, 64, 4, 16))
+    assert n8 == n16 > base          # the rank is stored padded to a multiple of 16
+
+
+@pytest.mark.parametrize("kw", [dict(E=0), dict(k=9), dict(H=100), dict(F=96), dict(g=48), dict(g=512), dict(bits=5),
+                                dict(r=-1), dict(r=300), dict(S=-1), dict(H=192, g=128)])
+def test_invalid_descriptors(kw):
+    base = dict(E=8, S=0, k=2, H=256, F=512, g=64, bits=4, r=8)
+    base.update(kw)
+    d = tq.make_desc(base["E"], base["S"], base["k"], base["H"], base["F"], base["g"], base["bits"], base["r"])
+    assert tq.tq_packed_size(d) == 0
+    assert tq.tq_moe_workspace_size(d, 16) == 0
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    L = tq.lib()
+    d = tq.make_desc(8, 0, 2, 256, 512, 64, 4, 8)
+    fake = ctypes.c_void_p(0x10000)       # aligned, never dereferenced on these paths
+    odd = ctypes.c_void_p(0x10004)
+    src = tq._WeightsPtrs(0x10000, 0x10000, 0x10000, 0x10000, 0x10000)
+    assert L.tq_pack_weights(ctypes.byref(d), ctypes.byref(src), None, 1 << 30, None, None) == 1
+    assert L.tq_pack_weights(ctypes.byref(d), ctypes.byref(src), fake, 16, None, None) == 5
+    assert L.tq_pack_weights(ctypes.byref(d), ctypes.byref(src), odd, 1 << 30, None, None) == 3
+    src_noA = tq._WeightsPtrs(0x10000, 0x10000, 0x10000, None, None)
+    assert L.tq_pack_weights(ctypes.byref(d), ctypes.byref(src_noA), fake, 1 << 30, None, None) == 1
+    bad = tq.make_desc(8, 0, 2, 250, 512, 64, 4, 8)
+    assert L.tq_pack_weights(ctypes.byref(bad), ctypes.byref(src), fake, 1 << 30, None, None) == 2
+    # route
+    assert L.tq_route(None, None, 4, 8, 2, fake, fake, None) == 1
+    assert L.tq_route(fake, None, 4, 8, 9, fake, fake, None) == 2
+    assert L.tq_route(fake, None, 4, 2048, 2, fake, fake, None) == 6
+    assert L.tq_route(fake, None, 0, 8, 2, fake, fake, None) == 0        # T == 0: nothing to do
+    # forward
+    ws = tq.tq_moe_workspace_size(d, 16)
+    assert ws > 0 and ws % 256 == 0
+    assert L.tq_moe_forward(ctypes.byref(d), fake, fake, fake, fake, 16, fake, None, ws, None) == 1
+    assert L.tq_moe_forward(ctypes.byref(d), fake, fake, fake, fake, 16, fake, fake, ws - 1, None) == 5
+    assert L.tq_moe_forward(ctypes.byref(d), fake, odd, fake, fake, 16, fake, fake, ws, None) == 3
+    assert L.tq_moe_forward(ctypes.byref(d), fake, fake, fake, fake, -1, fake, fake, ws, None) == 2
+    assert L.tq_moe_forward(ctypes.byref(d), fake, fake, fake, fake, 0, fake, fake, ws, None) == 0
+    # permute
+    assert L.tq_permute(fake, 4, 8, 2, fake, fake, fake, None, fake, 0, None) == 5
+    assert L.tq_permute(fake, 4, 8, 9, fake, fake, fake, None, fake, 1 << 20, None) == 2
+
+
+def test_workspace_grows_with_tokens():
+    d = tq.make_desc(8, 0, 2, 256, 512, 64, 4, 8)
+    a, b = tq.tq_moe_workspace_size(d, 16), tq.tq_moe_workspace_size(d, 4096)
+    assert 0 < a < b
