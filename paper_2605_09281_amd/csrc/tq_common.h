@@ -103,9 +103,13 @@ struct TqWorkspace {
 
 __host__ __device__ inline int tq_pad64(int v) { return (v + 63) / 64 * 64; }
 // augmented-K length: three bf16 split terms per quantisation group (zero-point correction) followed by
-// the rank-r intermediate, each region padded to 16, the whole to 64
+// the rank-r intermediate, each region padded to 16, the whole to one staging unit (max(g, 64))
 __host__ __device__ inline int tq_zero_terms(int K, int g) { return (3 * (K / g) + 15) / 16 * 16; }
-__host__ __device__ inline int tq_aug_len(int K, int g, int n_lr) { return tq_pad64(tq_zero_terms(K, g) + n_lr); }
+__host__ __device__ inline int tq_aug_len(int K, int g, int n_lr)
+{
+    const int unit = g < 64 ? 64 : g;
+    return (tq_zero_terms(K, g) + n_lr + unit - 1) / unit * unit;
+}
 
 __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t T, TqWorkspace* W)
 {

@@ -8,7 +8,6 @@ namespace {
 
 struct F32Geom {
     int32_t ne, H, F, g, r, r16, k, S;
-    TqSection gu, d;
     size_t expert_stride;
 };
 
@@ -17,14 +16,13 @@ __device__ inline float silu_f32(float v) { return v / (1.0f + expf(-v)); }
 // STAGE 0: gate/up + SwiGLU (input x gathered by token, output h32[slot][F])
 // STAGE 1: down (input h32[slot][F], output yd[slot][H])
 template <int STAGE>
-__global__ void __launch_bounds__(256) f32_proj_kernel(F32Geom G, const uint8_t* __restrict__ blob,
+__global__ void __launch_bounds__(256) f32_proj_kernel(F32Geom G, TqSection sec, const uint8_t* __restrict__ blob,
                                                        const float* __restrict__ xin,
                                                        const int32_t* __restrict__ row_token,
                                                        const int32_t* __restrict__ offsets,
                                                        const int32_t* __restrict__ ctrl, float* __restrict__ out)
 {
     extern __shared__ float smem[];
-    const TqSection& sec = STAGE == 0 ? G.gu : G.d;
     const int K = sec.K;
     const int NA = STAGE == 0 ? 2 * G.r16 : G.r16;
     float* xs = smem;        // [K]
@@ -142,7 +140,7 @@ tq_status tqi_forward_f32(const TqLayout& L, const TqWorkspace& W, const uint8_t
 {
     F32Geom G;
     G.ne = L.E + L.S; G.H = L.H; G.F = L.F; G.g = L.g; G.r = L.r; G.r16 = L.r16; G.k = L.k; G.S = L.S;
-    G.gu = L.gu; G.d = L.d; G.expert_stride = L.expert_stride;
+    G.expert_stride = L.expert_stride;
     const int32_t* ctrl = reinterpret_cast<const int32_t*>(ws + W.ctrl);
     const int32_t* offsets = reinterpret_cast<const int32_t*>(ws + W.offsets);
     const int32_t* slot_of = reinterpret_cast<const int32_t*>(ws + W.slot_of);
@@ -155,10 +153,10 @@ tq_status tqi_forward_f32(const TqLayout& L, const TqWorkspace& W, const uint8_t
         if (hipFuncSetAttribute((const void*)f32_proj_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm0) != hipSuccess) return TQ_ERR_HIP;
     if (sm1 > 48 * 1024)
         if (hipFuncSetAttribute((const void*)f32_proj_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm1) != hipSuccess) return TQ_ERR_HIP;
-    hipLaunchKernelGGL(f32_proj_kernel<0>, dim3(W.a_tot, (L.gu.pairs + 3) / 4), dim3(256), sm0, stream, G, blob, x,
+    hipLaunchKernelGGL(f32_proj_kernel<0>, dim3(W.a_tot, (L.gu.pairs + 3) / 4), dim3(256), sm0, stream, G, L.gu, blob, x,
                        row_token, offsets, ctrl, h32);
     TQ_CHECK_LAUNCH();
-    hipLaunchKernelGGL(f32_proj_kernel<1>, dim3(W.a_tot, (L.d.pairs + 3) / 4), dim3(256), sm1, stream, G, blob, h32,
+    hipLaunchKernelGGL(f32_proj_kernel<1>, dim3(W.a_tot, (L.d.pairs + 3) / 4), dim3(256), sm1, stream, G, L.d, blob, h32,
                        row_token, offsets, ctrl, yd);
     TQ_CHECK_LAUNCH();
     hipLaunchKernelGGL(f32_combine_kernel, dim3(T, (L.H + 255) / 256), dim3(256), 0, stream, T, L.H, L.k, L.S,

@@ -1,7 +1,570 @@
+// bf16 path of tq_moe_forward for gfx950: fused int4 dequant x bf16 MFMA grouped GEMM with the
+// rank-r correction and the zero-point correction folded into the same tile loop.
+//
+// How a projection out[m][n] = sum_kk x[m][kk] (q[n][kk] - z[n][G]) s[n][G] + (x A)[m][:] B[:][n] is evaluated:
+//   * the 4-bit codes are turned into bf16 values 128 + q with one and-or per pair (0x4300 | q is
+//     exactly 128 + q in bf16), fed to v_mfma_f32_32x32x16_bf16 against the bf16 activations, and the
+//     fp32 partial sum of one quantisation group is scaled by s[n][G] on the accumulator;
+//   * what that leaves, -(128 + z) s times the group sum of x, is a rank-(K/g) term.  The group sums are
+//     computed once per row by aug_kernel, split into bf16 hi + lo parts (the coefficient likewise), and
+//     contracted by three extra MFMA steps per 16 groups;
+//   * the low-rank term is r/16 more MFMA steps on t = x A (computed by aug_kernel with MFMA as well)
+//     against B converted fp16 -> bf16 on the fly.
+// Activations are staged through LDS (shared by the four waves of a workgroup); the packed codes are
+// already in MFMA fragment order and go straight from global memory to registers.
 #include "tq_common.h"
+
+#include <type_traits>
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct MGeom {
+    int32_t ne, H, F, g, r, r16, k, S, a_tot;
+    size_t expert_stride;
+};
+
+union Frag {
+    bf16x8 v;
+    uint32_t u[4];
+    u32x4 q;
+};
+
+__device__ inline uint32_t f2bf_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ inline uint32_t pack_bf2(float a, float b) { return f2bf_bits(a) | (f2bf_bits(b) << 16); }
+__device__ inline float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ inline float bf_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// 8 codes of one packed word -> bf16 values 128 + q, in contraction order
+__device__ inline bf16x8 unpack_word(uint32_t w)
+{
+    Frag f;
+    f.u[0] = (w & 0x000F000Fu) | 0x43004300u;
+    f.u[1] = ((w >> 4) & 0x000F000Fu) | 0x43004300u;
+    f.u[2] = ((w >> 8) & 0x000F000Fu) | 0x43004300u;
+    f.u[3] = ((w >> 12) & 0x000F000Fu) | 0x43004300u;
+    return f.v;
+}
+
+__device__ inline bf16x8 half8_to_bf8(u32x4 q)
+{
+    Frag f;
+    const uint32_t in[4] = {q[0], q[1], q[2], q[3]};
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        f.u[j] = pack_bf2(tq_half_bits_to_float((uint16_t)(in[j] & 0xFFFF)), tq_half_bits_to_float((uint16_t)(in[j] >> 16)));
+    return f.v;
+}
+
+__device__ inline uint32_t word_of(const u32x4& q, int w) { return q[w]; }
+
+// ------------------------------------------------------------------------------------------------
+// aug_kernel: per 32-row tile, the augmented activation row
+//   xaug[slot] = [ hi(xsum_0..G-1) | lo(xsum) | hi(xsum) | 0.. (to a multiple of 16) | t = x A (NA values) | 0.. ]
+// STAGE 0: x rows gathered by token, A = [gate | up] factors (NA = 2 r16).  STAGE 1: h rows, down factors.
+template <int STAGE>
+__global__ void __launch_bounds__(256) aug_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
+                                                  const uint16_t* __restrict__ xin,
+                                                  const int32_t* __restrict__ row_token,
+                                                  const int32_t* __restrict__ tile_e,
+                                                  const int32_t* __restrict__ tile_row0,
+                                                  const int32_t* __restrict__ offsets,
+                                                  const int32_t* __restrict__ ctrl, uint16_t* __restrict__ xaug,
+                                                  int ka)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int tile = blockIdx.x * 4 + wave;
+    if (tile >= ctrl[1]) return;
+    const int e = tile_e[tile], slot0 = tile_row0[tile];
+    const int rows = min(32, offsets[e + 1] - slot0);
+    const int col = lane & 31, hf = lane >> 5;
+    const int K = sec.K, NA = STAGE == 0 ? 2 * G.r16 : G.r16;
+    const int groups = sec.groups, GS = G.g / 16, ksteps = K / 16;
+    const int ZT = tq_zero_terms(K, G.g);
+    const int m = min(col, rows - 1);
+    const uint16_t* xrow = STAGE == 0 ? xin + (size_t)row_token[slot0 + m] * K : xin + (size_t)(slot0 + m) * K;
+    const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
+    const u32x4* af = reinterpret_cast<const u32x4*>(rec + sec.afrag);
+    uint16_t* orow = xaug + (size_t)(slot0 + col) * ka;
+    const bool writer = (hf == 0) && (col < rows);
+
+    const int na_tiles = (G.r > 0) ? sec.na_tiles : 0;
+    for (int ta0 = 0; ta0 == 0 || ta0 < na_tiles; ta0 += 4) {
+        f32x16 acc[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+        float gsum = 0.f;
+        for (int s = 0; s < ksteps; ++s) {
+            Frag xa;
+            xa.q = *reinterpret_cast<const u32x4*>(xrow + 16 * s + 8 * hf);
+            if (ta0 == 0) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) gsum += bf_lo(xa.u[j]) + bf_hi(xa.u[j]);
+                if ((s + 1) % GS == 0) {
+                    float tot = gsum + __shfl_xor(gsum, 32);
+                    if (writer) {
+                        int gi = s / GS;
+                        uint32_t hi = f2bf_bits(tot);
+                        uint32_t lo = f2bf_bits(tot - __uint_as_float(hi << 16));
+                        orow[gi] = (uint16_t)hi;
+                        orow[groups + gi] = (uint16_t)lo;
+                        orow[2 * groups + gi] = (uint16_t)hi;
+                    }
+                    gsum = 0.f;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (ta0 + j < na_tiles) {
+                    u32x4 aq = af[((size_t)(ta0 + j) * ksteps + s) * 64 + lane];
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa.v, half8_to_bf8(aq), acc[j], 0, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (ta0 + j < na_tiles) {
+                const int c = 32 * (ta0 + j) + col;
+                if (c < NA) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        int m2 = 8 * (v / 4) + 4 * hf + (v % 4);
+                        if (m2 < rows) xaug[(size_t)(slot0 + m2) * ka + ZT + c] = (uint16_t)f2bf_bits(acc[j][v]);
+                    }
+                }
+            }
+        }
+    }
+    // the padding must be finite (it meets zero weights in the MFMA): write zeros
+    if (writer) {
+        for (int kk = 3 * groups; kk < ZT; ++kk) orow[kk] = 0;
+        for (int kk = ZT + ((G.r > 0) ? NA : 0); kk < ka; ++kk) orow[kk] = 0;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// The grouped GEMM.  Workgroup = 4 waves sharing one row tile of BM = 32*MT rows; wave w owns column-tile
+// pair 4*blockIdx.x + w (64 output columns; in stage 0 that is 32 gate + the matching 32 up columns).
+//   STAGE 0: out = h[slot][F] bf16 = silu(gate) * up
+//   STAGE 1: out = yd[split][slot][H] fp32, split = blockIdx.z covering a slice of K
+// GS = quantisation group in MFMA steps (g/16).  A "unit" is max(g, 64) contraction indices.
+template <int MT, int STAGE, int GS>
+__global__ void __launch_bounds__(256) moe_mfma_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
+                                                       const uint16_t* __restrict__ xin,
+                                                       const uint16_t* __restrict__ xaug,
+                                                       const int32_t* __restrict__ row_token,
+                                                       const int32_t* __restrict__ tile_e,
+                                                       const int32_t* __restrict__ tile_row0,
+                                                       const int32_t* __restrict__ offsets,
+                                                       const int32_t* __restrict__ ctrl, int ctrl_idx,
+                                                       void* __restrict__ out, int ka, int nsplit)
+{
+    constexpr int BM = 32 * MT;
+    constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
+    constexpr int UC = UNIT_K / 64;     // 64-wide chunks (one u32x4 of codes per lane and tile) per unit
+    constexpr int US = UNIT_K / 16;     // MFMA steps per unit
+    constexpr int NG = US / GS;         // quantisation groups per unit
+    constexpr int ROWB = UNIT_K * 2 + 16;   // LDS bytes per activation row (16 B pad: conflict-free b128 reads)
+    constexpr int BUFB = BM * ROWB;
+    constexpr int TPR = UNIT_K / 8;     // threads (16-byte segments) per row when loading a unit
+    constexpr int RPP = 256 / TPR;      // rows per pass
+    constexpr int NP = BM / RPP;        // passes
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    int32_t* tokx = reinterpret_cast<int32_t*>(lds + 2 * BUFB);   // [BM] source row of the main operand
+    int32_t* toka = tokx + BM;                                    // [BM] row in xaug
+
+    const int K = sec.K;
+    const int rt = blockIdx.y;
+    if (rt >= ctrl[ctrl_idx]) return;
+    const int e = tile_e[rt], slot0 = tile_row0[rt];
+    const int rows = min(BM, offsets[e + 1] - slot0);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int pair_raw = blockIdx.x * 4 + wave;
+    const bool active = pair_raw < sec.pairs;
+    const int pair = active ? pair_raw : sec.pairs - 1;
+    const int split = blockIdx.z;
+
+    if (tid < BM) {
+        int r = min(tid, rows - 1);
+        tokx[tid] = STAGE == 0 ? row_token[slot0 + r] : slot0 + r;
+        toka[tid] = slot0 + r;
+    }
+    __syncthreads();
+
+    const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
+    const u32x4* codes = reinterpret_cast<const u32x4*>(rec + sec.codes) + (size_t)pair * sec.chunks * 128 + lane;
+    const uint32_t* szp = reinterpret_cast<const uint32_t*>(rec + sec.sz) + (size_t)pair * sec.groups * 64 + col;
+    const u32x4* bfr = reinterpret_cast<const u32x4*>(rec + sec.bfrag) + (size_t)pair * (G.r16 / 16) * 128 + lane;
+
+    const int NU = K / UNIT_K;
+    const int u0 = (int)((long)split * NU / nsplit), u1 = (int)((long)(split + 1) * NU / nsplit);
+    const int nmain = u1 - u0;
+    const int naug = (split == 0) ? ka / UNIT_K : 0;
+    const int nsteps = nmain + naug;
+
+    u32x4 xr[NP];
+    // ---- staging helpers: step st < nmain is main unit u0 + st, later steps are units of the augmented rows ----
+    auto load_step = [&](int st) {
+        const bool is_main = st < nmain;
+        const uint16_t* base = is_main ? xin : xaug;
+        const int32_t* tok = is_main ? tokx : toka;
+        const size_t stride = is_main ? (size_t)K : (size_t)ka;
+        const size_t koff = (size_t)(is_main ? u0 + st : st - nmain) * UNIT_K;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            int row = p * RPP + tid / TPR, seg = tid % TPR;
+            xr[p] = *reinterpret_cast<const u32x4*>(base + (size_t)tok[row] * stride + koff + seg * 8);
+        }
+    };
+    auto store_step = [&](int st) {
+        const int buf = st & 1;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            int row = p * RPP + tid / TPR, seg = tid % TPR;
+            *reinterpret_cast<u32x4*>(lds + buf * BUFB + row * ROWB + seg * 16) = xr[p];
+        }
+    };
+    auto load_w = [&](u32x4 (&dst)[2][UC], int u) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int c = 0; c < UC; ++c) dst[t][c] = codes[((size_t)(u * UC + c) * 2 + t) * 64];
+    };
+    auto load_sz = [&](uint32_t (&dst)[NG][2], int u) {
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) dst[gi][t] = szp[((size_t)(u * NG + gi) * 2 + t) * 32];
+    };
+
+    f32x16 acc[MT][2];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mt][t][v] = 0.f;
+
+    u32x4 wq[2][2][UC];
+    uint32_t szq[2][NG][2];
+
+    // ---- prologue ---------------------------------------------------------------------------------
+    load_step(0);
+    if (active && nmain > 0) { load_w(wq[0], u0); load_sz(szq[0], u0); }
+    if (active && nmain > 1) { load_w(wq[1], u0 + 1); load_sz(szq[1], u0 + 1); }
+    store_step(0);
+    __syncthreads();
+
+    auto lds_frag = [&](int buf, int mt, int kstep) -> bf16x8 {
+        Frag f;
+        f.q = *reinterpret_cast<const u32x4*>(lds + buf * BUFB + (32 * mt + col) * ROWB + (kstep * 16 + 8 * hf) * 2);
+        return f.v;
+    };
+
+    // ---- main units ---------------------------------------------------------------------------------
+    auto main_unit = [&](int st, auto slot_tag) {
+        constexpr int SLOT = decltype(slot_tag)::value;
+        if (st + 1 < nsteps) load_step(st + 1);
+        u32x4 wc[2][UC];
+        uint32_t szc[NG][2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int c = 0; c < UC; ++c) wc[t][c] = wq[SLOT][t][c];
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) szc[gi][t] = szq[SLOT][gi][t];
+        if (active && st + 2 < nmain) { load_w(wq[SLOT], u0 + st + 2); load_sz(szq[SLOT], u0 + st + 2); }
+        const int buf = st & 1;
+        if (active) {
+#pragma unroll
+            for (int gi = 0; gi < NG; ++gi) {
+                f32x16 part[MT][2];
+#pragma unroll
+                for (int ks = 0; ks < GS; ++ks) {
+                    const int kidx = gi * GS + ks;
+                    bf16x8 bw[2];
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) bw[t] = unpack_word(word_of(wc[t][kidx / 4], kidx % 4));
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        bf16x8 xa = lds_frag(buf, mt, kidx);
+#pragma unroll
+                        for (int t = 0; t < 2; ++t) {
+                            if (ks == 0) {
+                                f32x16 zero;
+#pragma unroll
+                                for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+                                part[mt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, bw[t], zero, 0, 0, 0);
+                            } else {
+                                part[mt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, bw[t], part[mt][t], 0, 0, 0);
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const float s = tq_half_bits_to_float((uint16_t)(szc[gi][t] & 0xFFFF));
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[mt][t][v] = fmaf(s, part[mt][t][v], acc[mt][t][v]);
+                }
+            }
+        }
+        if (st + 1 < nsteps) store_step(st + 1);
+        __syncthreads();
+    };
+
+    int st = 0;
+    for (; st + 1 < nmain; st += 2) {
+        main_unit(st, std::integral_constant<int, 0>{});
+        main_unit(st + 1, std::integral_constant<int, 1>{});
+    }
+    if (st < nmain) { main_unit(st, std::integral_constant<int, 0>{}); ++st; }
+
+    // ---- augmented steps: zero-point correction and the low-rank term ------------------------------
+    const int ZT = tq_zero_terms(K, G.g);
+    const int groups = sec.groups;
+    for (; st < nsteps; ++st) {
+        if (st + 1 < nsteps) load_step(st + 1);
+        const int a = st - nmain, buf = st & 1;
+        if (active) {
+#pragma unroll
+            for (int w = 0; w < US; ++w) {
+                const int k0 = UNIT_K * a + 16 * w;
+                bf16x8 bw[2];
+                bool use[2] = {false, false};
+                if (k0 < ZT) {
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        Frag f;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            float cv[2];
+#pragma unroll
+                            for (int h2 = 0; h2 < 2; ++h2) {
+                                const int kz = k0 + 8 * hf + 2 * j + h2;
+                                float val = 0.f;
+                                if (kz < 3 * groups) {
+                                    const int which = kz / groups, grp = kz - which * groups;
+                                    const uint32_t sz = szp[((size_t)grp * 2 + t) * 32];
+                                    const float s = tq_half_bits_to_float((uint16_t)(sz & 0xFFFF));
+                                    const float z = tq_half_bits_to_float((uint16_t)(sz >> 16));
+                                    const float c = -s * (128.f + z);
+                                    const float ch = __uint_as_float(f2bf_bits(c) << 16);
+                                    val = which < 2 ? ch : c - ch;
+                                }
+                                cv[h2] = val;
+                            }
+                            f.u[j] = pack_bf2(cv[0], cv[1]);
+                        }
+                        bw[t] = f.v;
+                        use[t] = true;
+                    }
+                } else if (G.r > 0 && k0 < ZT + G.r16) {
+                    const int step = (k0 - ZT) / 16;
+                    bw[0] = half8_to_bf8(bfr[((size_t)step * 2 + 0) * 64]);
+                    use[0] = true;
+                    if (STAGE == 1) { bw[1] = half8_to_bf8(bfr[((size_t)step * 2 + 1) * 64]); use[1] = true; }
+                } else if (STAGE == 0 && G.r > 0 && k0 < ZT + 2 * G.r16) {
+                    const int step = (k0 - ZT - G.r16) / 16;
+                    bw[1] = half8_to_bf8(bfr[((size_t)step * 2 + 1) * 64]);
+                    use[1] = true;
+                }
+                if (use[0] || use[1]) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        bf16x8 xa = lds_frag(buf, mt, w);
+                        if (use[0]) acc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, bw[0], acc[mt][0], 0, 0, 0);
+                        if (use[1]) acc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, bw[1], acc[mt][1], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        if (st + 1 < nsteps) store_step(st + 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue -----------------------------------------------------------------------------------
+    if (!active) return;
+    if (STAGE == 0) {
+        uint16_t* h = reinterpret_cast<uint16_t*>(out);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = 32 * mt + 8 * (v / 4) + 4 * hf + (v % 4);
+                if (m < rows) {
+                    const float gte = acc[mt][0][v], up = acc[mt][1][v];
+                    const float hv = gte / (1.0f + __expf(-gte)) * up;
+                    h[(size_t)(slot0 + m) * G.F + 32 * pair + col] = (uint16_t)f2bf_bits(hv);
+                }
+            }
+    } else {
+        float* yd = reinterpret_cast<float*>(out) + (size_t)split * G.a_tot * G.H;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = 32 * mt + 8 * (v / 4) + 4 * hf + (v % 4);
+                if (m < rows) {
+#pragma unroll
+                    for (int t = 0; t < 2; ++t)
+                        yd[(size_t)(slot0 + m) * G.H + 64 * pair + 32 * t + col] = acc[mt][t][v];
+                }
+            }
+    }
+}
+
+// y[t][c] = bf16( sum_j w[t][j] * sum_s yd[s][slot_of[t][j]][c] + shared ), terms in slot order
+__global__ void __launch_bounds__(256) combine_bf16_kernel(int T, int H, int k, int S, int nsplit, size_t plane,
+                                                           const int32_t* __restrict__ slot_of,
+                                                           const float* __restrict__ w,
+                                                           const float* __restrict__ yd, uint16_t* __restrict__ y)
+{
+    const int t = blockIdx.x;
+    const int c = (blockIdx.y * 256 + threadIdx.x) * 4;
+    if (c >= H) return;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    for (int j = 0; j < k + S; ++j) {
+        const int slot = slot_of[(size_t)t * (k + S) + j];
+        if (slot < 0) continue;
+        const float wj = j < k ? w[(size_t)t * k + j] : 1.0f;
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        for (int sp = 0; sp < nsplit; ++sp) {
+            const float4 v = *reinterpret_cast<const float4*>(yd + (size_t)sp * plane + (size_t)slot * H + c);
+            s0 += v.x; s1 += v.y; s2 += v.z; s3 += v.w;
+        }
+        a0 = fmaf(wj, s0, a0); a1 = fmaf(wj, s1, a1); a2 = fmaf(wj, s2, a2); a3 = fmaf(wj, s3, a3);
+    }
+    uint2 o;
+    o.x = pack_bf2(a0, a1);
+    o.y = pack_bf2(a2, a3);
+    *reinterpret_cast<uint2*>(y + (size_t)t * H + c) = o;
+}
+
+template <int MT, int STAGE, int GS>
+tq_status launch_main(const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin, const uint16_t* xaug,
+                      const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
+                      const int32_t* offsets, const int32_t* ctrl, int ctrl_idx, void* out, int ka, int nsplit,
+                      int row_tiles, hipStream_t st)
+{
+    constexpr int BM = 32 * MT;
+    constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
+    constexpr int ROWB = UNIT_K * 2 + 16;
+    const size_t smem = (size_t)2 * BM * ROWB + (size_t)2 * BM * 4;
+    auto kern = moe_mfma_kernel<MT, STAGE, GS>;
+    if (smem > 64 * 1024) {
+        static bool done = false;   // per instantiation
+        if (!done) {
+            if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+                return TQ_ERR_HIP;
+            done = true;
+        }
+    }
+    dim3 grid((sec.pairs + 3) / 4, row_tiles, nsplit);
+    if (grid.y > 65535) return TQ_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl,
+                       ctrl_idx, out, ka, nsplit);
+    TQ_CHECK_LAUNCH();
+    return TQ_OK;
+}
+
+template <int MT, int STAGE>
+tq_status launch_main_gs(int gs, const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin, const uint16_t* xaug,
+                         const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
+                         const int32_t* offsets, const int32_t* ctrl, int ctrl_idx, void* out, int ka, int nsplit,
+                         int row_tiles, hipStream_t st)
+{
+#define TQ_CASE(GSV)                                                                                              \
+    case GSV:                                                                                                     \
+        return launch_main<MT, STAGE, GSV>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl, ctrl_idx, \
+                                           out, ka, nsplit, row_tiles, st)
+    switch (gs) {
+        TQ_CASE(2);
+        TQ_CASE(4);
+        TQ_CASE(8);
+        TQ_CASE(16);
+    }
+#undef TQ_CASE
+    return TQ_ERR_UNSUPPORTED;
+}
+
+}  // namespace
+
 tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, const uint8_t* blob,
                            const uint16_t* x, int32_t T, uint16_t* y, uint8_t* ws, hipStream_t stream,
                            const float* topk_w)
 {
-    return TQ_ERR_UNSUPPORTED;
+    if (L.r16 > 128) return TQ_ERR_UNSUPPORTED;
+    MGeom G;
+    G.ne = L.E + L.S; G.H = L.H; G.F = L.F; G.g = L.g; G.r = L.r; G.r16 = L.r16; G.k = L.k; G.S = L.S;
+    G.a_tot = W.a_tot; G.expert_stride = L.expert_stride;
+    const int32_t* ctrl = reinterpret_cast<const int32_t*>(ws + W.ctrl);
+    const int32_t* offsets = reinterpret_cast<const int32_t*>(ws + W.offsets);
+    const int32_t* slot_of = reinterpret_cast<const int32_t*>(ws + W.slot_of);
+    const int32_t* row_token = reinterpret_cast<const int32_t*>(ws + W.row_token);
+    const int32_t* tile_e = reinterpret_cast<const int32_t*>(ws + W.tile_e);
+    const int32_t* tile_row0 = reinterpret_cast<const int32_t*>(ws + W.tile_row0);
+    uint16_t* xaug_gu = reinterpret_cast<uint16_t*>(ws + W.xaug_gu);
+    uint16_t* xaug_d = reinterpret_cast<uint16_t*>(ws + W.xaug_d);
+    uint16_t* h = reinterpret_cast<uint16_t*>(ws + W.h);
+    float* yd = reinterpret_cast<float*>(ws + W.yd);
+
+    // tile choice: rows per expert on average decide between the 32-row and the 128-row tile
+    const int64_t avg_rows = (int64_t)W.a_tot / (L.E + L.S);
+    bool large = avg_rows > 48;
+    if (flags & TQ_FLAG_FORCE_SMALL_TILE) large = false;
+    if (flags & TQ_FLAG_FORCE_LARGE_TILE) large = true;
+    const int rt32 = W.a_tot / 32 + L.E + L.S;     // upper bounds on the number of row tiles
+    const int rt128 = W.a_tot / 128 + L.E + L.S;
+    const int gs = L.g / 16;
+
+    hipLaunchKernelGGL(aug_kernel<0>, dim3((rt32 + 3) / 4), dim3(256), 0, stream, G, L.gu, blob, x, row_token, tile_e,
+                       tile_row0, offsets, ctrl, xaug_gu, W.ka_gu);
+    TQ_CHECK_LAUNCH();
+    tq_status rc;
+    if (large)
+        rc = launch_main_gs<4, 0>(gs, G, L.gu, blob, x, xaug_gu, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max, offsets,
+                                  ctrl, 2, h, W.ka_gu, 1, rt128, stream);
+    else
+        rc = launch_main_gs<1, 0>(gs, G, L.gu, blob, x, xaug_gu, row_token, tile_e, tile_row0, offsets, ctrl, 1, h, W.ka_gu, 1,
+                                  rt32, stream);
+    if (rc != TQ_OK) return rc;
+    hipLaunchKernelGGL(aug_kernel<1>, dim3((rt32 + 3) / 4), dim3(256), 0, stream, G, L.d, blob, h, row_token, tile_e,
+                       tile_row0, offsets, ctrl, xaug_d, W.ka_d);
+    TQ_CHECK_LAUNCH();
+    int nsplit = 1;
+    if (!large && W.a_tot <= 4096) {
+        // few rows: split the long contraction of the down projection so the grid fills the chip
+        const int unit_k = L.g < 64 ? 64 : L.g;
+        const int nu = L.F / unit_k;
+        const int64_t base = (int64_t)((L.d.pairs + 3) / 4) * (rt32 < L.E + L.S ? rt32 : L.E + L.S);
+        int want = (int)((1024 + base - 1) / base);
+        nsplit = want < 1 ? 1 : want > TQ_MAX_SPLIT ? TQ_MAX_SPLIT : want;
+        if (nsplit > nu) nsplit = nu;
+    }
+    if (large)
+        rc = launch_main_gs<4, 1>(gs, G, L.d, blob, h, xaug_d, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max, offsets,
+                                  ctrl, 2, yd, W.ka_d, 1, rt128, stream);
+    else
+        rc = launch_main_gs<1, 1>(gs, G, L.d, blob, h, xaug_d, row_token, tile_e, tile_row0, offsets, ctrl, 1, yd, W.ka_d,
+                                  nsplit, rt32, stream);
+    if (rc != TQ_OK) return rc;
+    hipLaunchKernelGGL(combine_bf16_kernel, dim3(T, (L.H / 4 + 255) / 256), dim3(256), 0, stream, T, L.H, L.k, L.S,
+                       nsplit, (size_t)W.a_tot * L.H, slot_of, topk_w, yd, y);
+    TQ_CHECK_LAUNCH();
+    return TQ_OK;
 }

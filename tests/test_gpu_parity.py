@@ -191,3 +191,27 @@ def test_forward_fp32_debug_path(name):
 def test_forward_fp32_config1():
     got, ref = run_forward(CONFIGS[1], tq.TQ_ACT_FP32)
     assert rel_err(got, ref) <= TOL_FP32
+
+
+@pytest.mark.parametrize("flags", [tq.TQ_FLAG_FORCE_SMALL_TILE, tq.TQ_FLAG_FORCE_LARGE_TILE, 0],
+                         ids=["tile32", "tile128", "auto"])
+@pytest.mark.parametrize("name", list(SMALL))
+def test_forward_bf16_small_layers(name, flags):
+    got, ref = run_forward(SMALL[name], tq.TQ_ACT_BF16, flags)
+    assert rel_err(got, ref) <= TOL_BF16
+
+
+@pytest.mark.parametrize("flags", [tq.TQ_FLAG_FORCE_SMALL_TILE, tq.TQ_FLAG_FORCE_LARGE_TILE],
+                         ids=["tile32", "tile128"])
+def test_forward_bf16_config1(flags):
+    got, ref = run_forward(CONFIGS[1], tq.TQ_ACT_BF16, flags)
+    err = rel_err(got, ref)
+    print(f"config 1 bf16 flags={flags}: rel err {err:.3e}")
+    assert err <= TOL_BF16
+
+
+def test_forward_bf16_is_run_to_run_deterministic():
+    cfg = SMALL["ragged"]
+    a, _ = run_forward(cfg, tq.TQ_ACT_BF16, tq.TQ_FLAG_FORCE_SMALL_TILE)
+    b, _ = run_forward(cfg, tq.TQ_ACT_BF16, tq.TQ_FLAG_FORCE_SMALL_TILE)
+    assert np.array_equal(a, b)
