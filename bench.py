@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantised-expert MoE forward (route + tq_moe_forward) on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of seeded synthetic tokens whose inputs
+(activations, router logits, packed weights) are already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1..5]
+
+The default workload is the Mixtral-shaped decode layer (benchmark config 2).
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12          # B/s, MI355X published
+MFMA_BF16_PEAK = 2.5e15    # FLOP/s dense bf16, MI355X published
+STAGES = ["permute", "aug_gate_up", "gate_up", "aug_down", "down", "combine"]
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+class HipEvents:
+    """Raw HIP events (ctypes on libamdhip64) so that they can be recorded on the library's stream."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.ev = []
+        for _ in range(n):
+            e = ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(e)) == 0
+            self.ev.append(e)
+
+    def handles(self):
+        return [e.value for e in self.ev]
+
+    def record(self, i, stream):
+        assert self.hip.hipEventRecord(self.ev[i], ctypes.c_void_p(stream)) == 0
+
+    def sync(self, i):
+        assert self.hip.hipEventSynchronize(self.ev[i]) == 0
+
+    def elapsed_ms(self, a, b):
+        ms = ctypes.c_float()
+        assert self.hip.hipEventElapsedTime(ctypes.byref(ms), self.ev[a], self.ev[b]) == 0
+        return float(ms.value)
+
+
+def algorithmic_work(cfg, idx_np):
+    """Algorithmic bytes and flops of one forward, whole path and per dominant kernel."""
+    import numpy as np
+    H, F, g, r, T = cfg.H, cfg.F, cfg.g, cfg.r, cfg.T
+    touched = int(np.unique(idx_np).size) + cfg.S
+    a_tot = cfg.a_tot
+    gu_w = F * H + 2 * F * (H // g) * 4 + 2 * r * F * 2            # codes (2 matrices, 4 bit) + scale/zero + B factors
+    gu_a = 2 * H * r * 2                                           # A factors (read by the pre-pass)
+    d_w = H * F // 2 + H * (F // g) * 4 + r * H * 2
+    d_a = F * r * 2
+    w_bytes = touched * (gu_w + gu_a + d_w + d_a)
+    act_bytes = T * H * 2 * 2                                      # x in, y out
+    flops_gu = a_tot * (4 * H * F + 4 * r * (H + F))               # gate+up: 2 matrices x 2 flop, plus low-rank
+    flops_d = a_tot * (2 * H * F + 2 * r * (H + F))
+    return dict(touched=touched,
+                path_bytes=w_bytes + act_bytes,
+                gate_up_bytes=touched * gu_w + a_tot * H * 2 + a_tot * F * 2,
+                down_bytes=touched * d_w + a_tot * F * 2 + a_tot * H * 4,
+                path_flops=flops_gu + flops_d, gate_up_flops=flops_gu, down_flops=flops_d)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the path is a single-GPU kernel library; "
+              "see DESIGN.md for how it would shard). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from synth import CONFIGS, make_layer, make_x, make_logits, f32_to_bf16_bits
+    import paper_2605_09281_amd.binding as tq
+
+    cfg = CONFIGS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    t0 = time.time()
+    layer = make_layer(cfg, workers=min(16, os.cpu_count() or 8))
+    x = make_x(cfg)
+    logits, bias = make_logits(cfg)
+    log(f"workload {cfg.cfg_id} ({cfg.name}): inputs generated in {time.time() - t0:.1f}s")
+
+    def dev16(a):
+        return torch.from_numpy(a.view(np.int16)).to(dev)
+
+    desc = tq.make_desc(cfg.E, cfg.S, cfg.k, cfg.H, cfg.F, cfg.g, cfg.bits, cfg.r, tq.TQ_ACT_BF16)
+    codes_d = torch.from_numpy(layer.codes).to(dev)
+    sc_d, ze_d = dev16(layer.scale), dev16(layer.zero)
+    A_d = dev16(layer.A) if cfg.r else None
+    B_d = dev16(layer.B) if cfg.r else None
+    n_copies = 2      # rotate weight copies so that no step finds its weights warm in the last-level cache
+    packed = [tq.tq_pack_weights(desc, codes_d, sc_d, ze_d, A_d, B_d) for _ in range(n_copies)]
+    torch.cuda.synchronize()
+    del codes_d, sc_d, ze_d, A_d, B_d
+    torch.cuda.empty_cache()
+    logits_d = torch.from_numpy(logits).to(dev)
+    bias_d = None if bias is None else torch.from_numpy(bias).to(dev)
+    x_d = torch.from_numpy(f32_to_bf16_bits(x).view(np.int16)).to(dev).view(torch.bfloat16)
+    idx_d = torch.empty((cfg.T, cfg.k), dtype=torch.int32, device=dev)
+    w_d = torch.empty((cfg.T, cfg.k), dtype=torch.float32, device=dev)
+    y_d = torch.empty_like(x_d)
+    ws = torch.empty(tq.tq_moe_workspace_size(desc, cfg.T), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step(i):
+        tq.tq_route(logits_d, bias_d, cfg.k, idx_d, w_d)
+        tq.tq_moe_forward(desc, packed[i % n_copies], x_d, idx_d, w_d, y=y_d, workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev = HipEvents(2 + 7)
+    ev.record(0, stream)
+    t_host = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    ev.record(1, stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_host) * 1e3
+    ms_total = ev.elapsed_ms(0, 1)
+    ms_per_step = ms_total / args.steps
+    log(f"timed {args.steps} steps: {ms_per_step * 1e3:.1f} us/step (events), {wall_ms / args.steps * 1e3:.1f} us/step (host clock)")
+    assert int(ws[:4].view(torch.int32).item()) == 0, "device error flag set"
+
+    # per-stage kernel durations: the library records events at its stage boundaries on the same stream
+    stage_ev = ev.handles()[2:]
+    tq.tq_set_profile_events(stage_ev)
+    n_prof = max(1, min(args.steps, 50))
+    stage_ms = [0.0] * 6
+    for i in range(n_prof):
+        step(i)
+        ev.sync(2 + 6)
+        for s in range(6):
+            stage_ms[s] += ev.elapsed_ms(2 + s, 3 + s)
+    tq.tq_set_profile_events([])
+    stage_us = {name: stage_ms[s] / n_prof * 1e3 for s, name in enumerate(STAGES)}
+    log("stage durations (us): " + ", ".join(f"{k}={v:.1f}" for k, v in stage_us.items()))
+
+    idx_np = idx_d.cpu().numpy()
+    work = algorithmic_work(cfg, idx_np)
+    hbm_bound = work["path_flops"] / max(work["path_bytes"], 1) < MFMA_BF16_PEAK / HBM_PEAK
+    t_gu = stage_us["gate_up"] * 1e-6
+    if hbm_bound:
+        ach = work["gate_up_bytes"] / t_gu / 1e9
+        roofline = dict(bound="hbm", kernel="moe_mfma_kernel (gate/up stage)", achieved=round(ach, 1), peak=HBM_PEAK / 1e9,
+                        unit="GB/s", frac=round(ach / (HBM_PEAK / 1e9), 4), traffic=None,
+                        path_achieved=round(work["path_bytes"] / (ms_per_step * 1e-3) / 1e9, 1),
+                        path_frac=round(work["path_bytes"] / (ms_per_step * 1e-3) / HBM_PEAK, 4))
+    else:
+        ach = work["gate_up_flops"] / t_gu / 1e12
+        roofline = dict(bound="mfma", kernel="moe_mfma_kernel (gate/up stage)", achieved=round(ach, 1),
+                        peak=MFMA_BF16_PEAK / 1e12, unit="TFLOP/s", frac=round(ach / (MFMA_BF16_PEAK / 1e12), 4),
+                        traffic=None,
+                        path_achieved=round(work["path_flops"] / (ms_per_step * 1e-3) / 1e12, 1),
+                        path_frac=round(work["path_flops"] / (ms_per_step * 1e-3) / MFMA_BF16_PEAK, 4))
+    roofline["stage_us"] = {k: round(v, 2) for k, v in stage_us.items()}
+
+    # the oracle beside it: a bounded token sample of the same workload, timed on this machine's host cores
+    cpu_baseline = None
+    max_rel_err = None
+    if not args.no_cpu_baseline:
+        import oracle
+        ridx, rw = oracle.route(logits, bias, cfg.k)
+        assert np.array_equal(ridx, idx_np), "routing indices differ from the oracle"
+        pair_cost = 3.0 * cfg.H * cfg.F * (cfg.k + cfg.S)          # MACs per token
+        n_tok = int(max(1, min(cfg.T, 1.5e11 // pair_cost)))       # about 10-30 s of host work
+        tok = np.linspace(0, cfg.T - 1, n_tok).astype(np.int32)
+        w_np = w_d.cpu().numpy()
+        t1 = time.perf_counter()
+        y_ref = oracle.moe_forward_layer(layer, x, ridx, w_np, tokens=tok)
+        cpu_s = time.perf_counter() - t1
+        got = y_d.float().cpu().numpy()[tok].astype(np.float64)
+        max_rel_err = float(np.max(np.abs(got - y_ref)) / np.max(np.abs(y_ref)))
+        cpu_baseline = dict(value=round(n_tok / cpu_s, 3), unit="tokens/s", cores=oracle.num_threads(), kind="oracle",
+                            sample=f"{n_tok} of {cfg.T} tokens of the same workload, {cpu_s:.1f} s")
+        log(f"oracle: {n_tok} tokens in {cpu_s:.1f}s on {oracle.num_threads()} threads; max rel err {max_rel_err:.3e}")
+        assert max_rel_err <= 2e-2, max_rel_err
+
+    out = {
+        "metric": "MoE-layer tokens/s at 1 GPU (route + quantised-expert forward)",
+        "value": round(cfg.T / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"config {cfg.cfg_id}: {cfg.name}", "experts": cfg.E, "shared": cfg.S, "top_k": cfg.k,
+                   "hidden": cfg.H, "ffn": cfg.F, "tokens": cfg.T, "group": cfg.g, "rank": cfg.r, "bits": cfg.bits,
+                   "touched_experts": work["touched"]},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "max_rel_err_vs_oracle": max_rel_err,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

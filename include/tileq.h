@@ -157,6 +157,14 @@ tq_status tq_moe_forward(const tq_layer_desc *desc, const void *packed, const vo
                          const int32_t *topk_idx, const float *topk_w, int32_t T, void *y,
                          void *workspace, size_t workspace_bytes, void *stream);
 
+/* Profiling aid (not part of the method).  Registers up to TQ_N_STAGE_EVENTS hipEvent_t handles (host
+ * array, copied) that tq_moe_forward records on its stream at the stage boundaries:
+ *   0 entry, 1 after the permutation, 2 after the gate/up pre-pass (group sums and x A), 3 after gate/up,
+ *   4 after the down pre-pass, 5 after down, 6 after the combination.
+ * n == 0 switches it off.  Process-wide and not thread-safe: meant for one benchmark thread. */
+#define TQ_N_STAGE_EVENTS 7
+tq_status tq_set_profile_events(void *const *events, int32_t n);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,8 @@ STATUS_NAMES = {0: "TQ_OK", 1: "TQ_ERR_NULL", 2: "TQ_ERR_SHAPE", 3: "TQ_ERR_ALIG
                 5: "TQ_ERR_WORKSPACE", 6: "TQ_ERR_UNSUPPORTED", 7: "TQ_ERR_HIP", 8: "TQ_ERR_BLOB"}
 
 EXPORTS = ["tq_status_str", "tq_packed_size", "tq_pack_weights", "tq_unpack_weights", "tq_route",
-           "tq_permute_workspace_size", "tq_permute", "tq_moe_workspace_size", "tq_moe_forward"]
+           "tq_permute_workspace_size", "tq_permute", "tq_moe_workspace_size", "tq_moe_forward",
+           "tq_set_profile_events"]
 
 
 class TqError(RuntimeError):
@@ -74,6 +75,8 @@ def lib():
         L.tq_moe_forward.argtypes = [ctypes.POINTER(LayerDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_size_t, ctypes.c_void_p]
+        L.tq_set_profile_events.restype = ctypes.c_int
+        L.tq_set_profile_events.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32]
         _lib = L
     return _lib
 
@@ -162,3 +165,10 @@ def tq_moe_forward(desc: LayerDesc, packed, x, topk_idx, topk_w, y=None, workspa
     _check(lib().tq_moe_forward(ctypes.byref(desc), _ptr(packed), _ptr(x), _ptr(topk_idx), _ptr(topk_w), T, _ptr(y),
                                 _ptr(workspace), workspace.numel(), _stream()), "tq_moe_forward")
     return y
+
+
+def tq_set_profile_events(events) -> None:
+    """events: list of raw hipEvent_t handles (ints), or an empty list to switch stage events off."""
+    n = len(events)
+    arr = (ctypes.c_void_p * max(n, 1))(*events)
+    _check(lib().tq_set_profile_events(arr, n), "tq_set_profile_events")

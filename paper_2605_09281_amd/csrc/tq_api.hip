@@ -18,6 +18,25 @@ extern "C" const char* tq_status_str(tq_status s)
     return "unknown status";
 }
 
+namespace {
+hipEvent_t g_stage_events[TQ_N_STAGE_EVENTS];
+int g_n_stage_events = 0;
+}  // namespace
+
+void tqi_record_stage(int stage, hipStream_t stream)
+{
+    if (stage < g_n_stage_events && g_stage_events[stage]) (void)hipEventRecord(g_stage_events[stage], stream);
+}
+
+extern "C" tq_status tq_set_profile_events(void* const* events, int32_t n)
+{
+    if (n < 0 || n > TQ_N_STAGE_EVENTS) return TQ_ERR_SHAPE;
+    if (n > 0 && !events) return TQ_ERR_NULL;
+    for (int i = 0; i < n; ++i) g_stage_events[i] = (hipEvent_t)events[i];
+    g_n_stage_events = n;
+    return TQ_OK;
+}
+
 extern "C" size_t tq_moe_workspace_size(const tq_layer_desc* desc, int32_t T)
 {
     TqLayout L;
@@ -45,12 +64,14 @@ extern "C" tq_status tq_moe_forward(const tq_layer_desc* desc, const void* packe
     hipStream_t st = (hipStream_t)stream;
     uint8_t* ws = (uint8_t*)workspace;
     int32_t* ctrl = (int32_t*)(ws + W.ctrl);
+    tqi_record_stage(0, st);
     tq_status rc = tqi_launch_permute(topk_idx, topk_w, T, L.E, L.S, L.k, (int32_t*)(ws + W.offsets),
                                       (int32_t*)(ws + W.slot_of), L.k + L.S, nullptr,
                                       (int32_t*)(ws + W.row_token), (float*)(ws + W.row_w),
                                       (int32_t*)(ws + W.tile_e), (int32_t*)(ws + W.tile_row0), W.rt_max, ctrl,
                                       ctrl, (int32_t*)(ws + W.hist), W.nblk, packed, &L, st);
     if (rc != TQ_OK) return rc;
+    tqi_record_stage(1, st);
     if (desc->act_dtype == TQ_ACT_FP32)
         return tqi_forward_f32(L, W, (const uint8_t*)packed, (const float*)x, T, (float*)y, ws, st, topk_w);
     return tqi_forward_bf16(L, W, desc->flags, (const uint8_t*)packed, (const uint16_t*)x, T, (uint16_t*)y, ws, st,

@@ -178,6 +178,9 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
                            const uint16_t* x, int32_t T, uint16_t* y, uint8_t* ws, hipStream_t stream,
                            const float* topk_w);
 
+// profiling aid: stage-boundary events registered through tq_set_profile_events (nullptr when off)
+void tqi_record_stage(int stage, hipStream_t stream);
+
 #define TQ_CHECK_LAUNCH()                                         \
     do {                                                          \
         if (hipGetLastError() != hipSuccess) return TQ_ERR_HIP;   \

@@ -156,11 +156,14 @@ tq_status tqi_forward_f32(const TqLayout& L, const TqWorkspace& W, const uint8_t
     hipLaunchKernelGGL(f32_proj_kernel<0>, dim3(W.a_tot, (L.gu.pairs + 3) / 4), dim3(256), sm0, stream, G, L.gu, blob, x,
                        row_token, offsets, ctrl, h32);
     TQ_CHECK_LAUNCH();
+    tqi_record_stage(3, stream);
     hipLaunchKernelGGL(f32_proj_kernel<1>, dim3(W.a_tot, (L.d.pairs + 3) / 4), dim3(256), sm1, stream, G, L.d, blob, h32,
                        row_token, offsets, ctrl, yd);
     TQ_CHECK_LAUNCH();
+    tqi_record_stage(5, stream);
     hipLaunchKernelGGL(f32_combine_kernel, dim3(T, (L.H + 255) / 256), dim3(256), 0, stream, T, L.H, L.k, L.S,
                        slot_of, topk_w, yd, y);
     TQ_CHECK_LAUNCH();
+    tqi_record_stage(6, stream);
     return TQ_OK;
 }

@@ -535,6 +535,7 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     hipLaunchKernelGGL(aug_kernel<0>, dim3((rt32 + 3) / 4), dim3(256), 0, stream, G, L.gu, blob, x, row_token, tile_e,
                        tile_row0, offsets, ctrl, xaug_gu, W.ka_gu);
     TQ_CHECK_LAUNCH();
+    tqi_record_stage(2, stream);
     tq_status rc;
     if (large)
         rc = launch_main_gs<4, 0>(gs, G, L.gu, blob, x, xaug_gu, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max, offsets,
@@ -543,9 +544,11 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
         rc = launch_main_gs<1, 0>(gs, G, L.gu, blob, x, xaug_gu, row_token, tile_e, tile_row0, offsets, ctrl, 1, h, W.ka_gu, 1,
                                   rt32, stream);
     if (rc != TQ_OK) return rc;
+    tqi_record_stage(3, stream);
     hipLaunchKernelGGL(aug_kernel<1>, dim3((rt32 + 3) / 4), dim3(256), 0, stream, G, L.d, blob, h, row_token, tile_e,
                        tile_row0, offsets, ctrl, xaug_d, W.ka_d);
     TQ_CHECK_LAUNCH();
+    tqi_record_stage(4, stream);
     int nsplit = 1;
     if (!large && W.a_tot <= 4096) {
         // few rows: split the long contraction of the down projection so the grid fills the chip
@@ -563,8 +566,10 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
         rc = launch_main_gs<1, 1>(gs, G, L.d, blob, h, xaug_d, row_token, tile_e, tile_row0, offsets, ctrl, 1, yd, W.ka_d,
                                   nsplit, rt32, stream);
     if (rc != TQ_OK) return rc;
+    tqi_record_stage(5, stream);
     hipLaunchKernelGGL(combine_bf16_kernel, dim3(T, (L.H / 4 + 255) / 256), dim3(256), 0, stream, T, L.H, L.k, L.S,
                        nsplit, (size_t)W.a_tot * L.H, slot_of, topk_w, yd, y);
     TQ_CHECK_LAUNCH();
+    tqi_record_stage(6, stream);
     return TQ_OK;
 }

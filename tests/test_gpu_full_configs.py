@@ -1,0 +1,69 @@
+"""The five benchmark layers at their full sizes, in the launch configuration bench.py times (flags = 0).
+Routing indices are compared in full; the forward on a seeded token sample the oracle can afford (rows are
+independent, so each sampled output row is the oracle's exact row)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from synth import CONFIGS, make_layer, make_x, make_logits
+import paper_2605_09281_amd.binding as tq
+from gpu_util import DEV, desc_of, pack_layer_gpu, x_device, rel_err
+
+pytestmark = pytest.mark.gpu
+
+SAMPLE = {1: 64, 2: 16, 3: 24, 4: 48, 5: 16}
+
+
+@pytest.mark.parametrize("cfg_id", [1, 2, 3, 4, 5])
+def test_full_config_bf16(cfg_id):
+    cfg = CONFIGS[cfg_id]
+    print(f"config {cfg_id}: generating", flush=True)
+    layer = make_layer(cfg, workers=16)
+    x = make_x(cfg)
+    logits, bias = make_logits(cfg)
+    packed = pack_layer_gpu(layer)
+    idx, w = tq.tq_route(torch.from_numpy(logits).to(DEV), None if bias is None else torch.from_numpy(bias).to(DEV), cfg.k)
+    desc = desc_of(cfg, tq.TQ_ACT_BF16)
+    ws = torch.empty(tq.tq_moe_workspace_size(desc, cfg.T), dtype=torch.uint8, device=DEV)
+    print(f"config {cfg_id}: forward", flush=True)
+    y = tq.tq_moe_forward(desc, packed, x_device(x, tq.TQ_ACT_BF16), idx, w, workspace=ws)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32).item()) == 0
+    ridx, rw = oracle.route(logits, bias, cfg.k)
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+    w_np = w.cpu().numpy()
+    assert np.max(np.abs(w_np - rw)) <= 1e-6
+    rng = np.random.default_rng(1000 + cfg_id)
+    tok = np.sort(rng.choice(cfg.T, size=min(SAMPLE[cfg_id], cfg.T), replace=False)).astype(np.int32)
+    ref = oracle.moe_forward_layer(layer, x, ridx, w_np, tokens=tok)
+    got = y.float().cpu().numpy()[tok]
+    err = rel_err(got, ref)
+    print(f"config {cfg_id}: bf16 rel err {err:.3e} on {tok.size} tokens", flush=True)
+    assert err <= 2e-2
+    # every output row is finite and a second run is bit-identical
+    yf = y.float()
+    assert bool(torch.isfinite(yf).all())
+    y2 = tq.tq_moe_forward(desc, packed, x_device(x, tq.TQ_ACT_BF16), idx, w, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+
+
+@pytest.mark.parametrize("cfg_id", [2, 4])
+def test_full_config_fp32_debug(cfg_id):
+    cfg = CONFIGS[cfg_id]
+    layer = make_layer(cfg, workers=16)
+    x = make_x(cfg)
+    logits, bias = make_logits(cfg)
+    packed = pack_layer_gpu(layer)
+    idx, w = tq.tq_route(torch.from_numpy(logits).to(DEV), None if bias is None else torch.from_numpy(bias).to(DEV), cfg.k)
+    desc = desc_of(cfg, tq.TQ_ACT_FP32)
+    y = tq.tq_moe_forward(desc, packed, x_device(x, tq.TQ_ACT_FP32), idx, w)
+    torch.cuda.synchronize()
+    ridx, _ = oracle.route(logits, bias, cfg.k)
+    rng = np.random.default_rng(2000 + cfg_id)
+    tok = np.sort(rng.choice(cfg.T, size=min(8, cfg.T), replace=False)).astype(np.int32)
+    ref = oracle.moe_forward_layer(layer, x, ridx, w.cpu().numpy(), tokens=tok)
+    err = rel_err(y.cpu().numpy()[tok], ref)
+    print(f"config {cfg_id}: fp32 rel err {err:.3e}", flush=True)
+    assert err <= 1e-5
