@@ -82,13 +82,13 @@ __host__ __device__ inline int tq_nibble_pos(int i) { return (i >> 1) + 4 * (i &
 // ------------------------------------------------------------------------------------------------
 // Workspace of tq_moe_forward.  All offsets are multiples of 256 bytes.
 struct TqWorkspace {
-    size_t ctrl;        // int32[64]: [0] error flag, [1] row tiles (32-row), [2] row tiles (128-row), [3] rows
+    size_t ctrl;        // int32[64]: [0] error flag, [1] row tiles (32-row), [2] (128-row), [3] rows, [4] (16-row)
     size_t offsets;     // int32 [E+S+1]
     size_t slot_of;     // int32 [T*(k+S)]
     size_t row_token;   // int32 [A_tot]
     size_t row_w;       // float [A_tot]
-    size_t tile_e;      // int32 [2][RT]  expert of each row tile, for the 32- and the 128-row tiling
-    size_t tile_row0;   // int32 [2][RT]  first slot of each row tile
+    size_t tile_e;      // int32 [3][RT]  expert of each row tile, for the 32-, 128- and 16-row tilings
+    size_t tile_row0;   // int32 [3][RT]  first slot of each row tile
     size_t hist;        // int32 [nblk][E] permutation scratch
     size_t xaug_gu;     // bf16 [A_tot][ka_gu]   (bf16 path)
     size_t xaug_d;      // bf16 [A_tot][ka_d]
@@ -98,7 +98,7 @@ struct TqWorkspace {
     int32_t a_tot, rt_max, nblk, ka_gu, ka_d, nsplit_max;
 };
 
-#define TQ_PERM_CHUNK 1024  // assignments handled by one permutation block
+#define TQ_PERM_CHUNK 256   // assignments handled by one permutation block
 #define TQ_MAX_SPLIT 8      // K-splits of the down projection on the small-tile path
 
 __host__ __device__ inline int tq_pad64(int v) { return (v + 63) / 64 * 64; }
@@ -117,7 +117,7 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
     auto take = [&](size_t bytes) { size_t o = off; off += tq_align256(bytes); return o; };
     int64_t a_tot = (int64_t)T * (L.k + L.S);
     W->a_tot = (int32_t)a_tot;
-    W->rt_max = (int32_t)(a_tot / 32 + L.E + L.S + 1);
+    W->rt_max = (int32_t)(a_tot / 16 + L.E + L.S + 1);
     W->nblk = (int32_t)(((int64_t)T * L.k + TQ_PERM_CHUNK - 1) / TQ_PERM_CHUNK);
     if (W->nblk < 1) W->nblk = 1;
     W->ka_gu = tq_aug_len(L.H, L.g, 2 * L.r16);
@@ -128,8 +128,8 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
     W->slot_of = take((size_t)a_tot * 4);
     W->row_token = take((size_t)a_tot * 4);
     W->row_w = take((size_t)a_tot * 4);
-    W->tile_e = take((size_t)2 * W->rt_max * 4);
-    W->tile_row0 = take((size_t)2 * W->rt_max * 4);
+    W->tile_e = take((size_t)3 * W->rt_max * 4);
+    W->tile_row0 = take((size_t)3 * W->rt_max * 4);
     W->hist = take((size_t)W->nblk * L.E * 4);
     if (act_dtype == TQ_ACT_BF16) {
         W->xaug_gu = take((size_t)a_tot * W->ka_gu * 2);

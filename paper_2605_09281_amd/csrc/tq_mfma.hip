@@ -24,6 +24,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 struct MGeom {
     int32_t ne, H, F, g, r, r16, k, S, a_tot;
+    uint32_t unpack_mask, unpack_magic;   // 0x000F000F, 0x43004300 (see unpack_word)
     size_t expert_stride;
 };
 
@@ -42,14 +43,17 @@ __device__ inline uint32_t pack_bf2(float a, float b) { return f2bf_bits(a) | (f
 __device__ inline float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ inline float bf_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-// 8 codes of one packed word -> bf16 values 128 + q, in contraction order
-__device__ inline bf16x8 unpack_word(uint32_t w)
+// 8 codes of one packed word -> bf16 values 128 + q, in contraction order.  mask = 0x000F000F and
+// magic = 0x43004300 arrive as kernel arguments rather than literals: the three-operand and-or encoding
+// takes no literal on this target, and with register operands the compiler selects it (7 VALU
+// instructions per word instead of 11).
+__device__ inline bf16x8 unpack_word(uint32_t w, uint32_t mask, uint32_t magic)
 {
     Frag f;
-    f.u[0] = (w & 0x000F000Fu) | 0x43004300u;
-    f.u[1] = ((w >> 4) & 0x000F000Fu) | 0x43004300u;
-    f.u[2] = ((w >> 8) & 0x000F000Fu) | 0x43004300u;
-    f.u[3] = ((w >> 12) & 0x000F000Fu) | 0x43004300u;
+    f.u[0] = (w & mask) | magic;
+    f.u[1] = ((w >> 4) & mask) | magic;
+    f.u[2] = ((w >> 8) & mask) | magic;
+    f.u[3] = ((w >> 12) & mask) | magic;
     return f.v;
 }
 
@@ -103,31 +107,40 @@ __global__ void __launch_bounds__(256) aug_kernel(MGeom G, TqSection sec, const 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
         float gsum = 0.f;
-        for (int s = 0; s < ksteps; ++s) {
-            Frag xa;
-            xa.q = *reinterpret_cast<const u32x4*>(xrow + 16 * s + 8 * hf);
-            if (ta0 == 0) {
+        constexpr int UNR = 4;   // steps whose loads are issued together (K is a multiple of 64)
+        for (int s0 = 0; s0 < ksteps; s0 += UNR) {
+            Frag xa[UNR];
+            u32x4 aq[UNR][4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) gsum += bf_lo(xa.u[j]) + bf_hi(xa.u[j]);
-                if ((s + 1) % GS == 0) {
-                    float tot = gsum + __shfl_xor(gsum, 32);
-                    if (writer) {
-                        int gi = s / GS;
-                        uint32_t hi = f2bf_bits(tot);
-                        uint32_t lo = f2bf_bits(tot - __uint_as_float(hi << 16));
-                        orow[gi] = (uint16_t)hi;
-                        orow[groups + gi] = (uint16_t)lo;
-                        orow[2 * groups + gi] = (uint16_t)hi;
+            for (int u = 0; u < UNR; ++u) xa[u].q = *reinterpret_cast<const u32x4*>(xrow + 16 * (s0 + u) + 8 * hf);
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (ta0 + j < na_tiles) aq[u][j] = af[((size_t)(ta0 + j) * ksteps + s0 + u) * 64 + lane];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const int s = s0 + u;
+                if (ta0 == 0) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) gsum += bf_lo(xa[u].u[j]) + bf_hi(xa[u].u[j]);
+                    if ((s + 1) % GS == 0) {
+                        float tot = gsum + __shfl_xor(gsum, 32);
+                        if (writer) {
+                            int gi = s / GS;
+                            uint32_t hi = f2bf_bits(tot);
+                            uint32_t lo = f2bf_bits(tot - __uint_as_float(hi << 16));
+                            orow[gi] = (uint16_t)hi;
+                            orow[groups + gi] = (uint16_t)lo;
+                            orow[2 * groups + gi] = (uint16_t)hi;
+                        }
+                        gsum = 0.f;
                     }
-                    gsum = 0.f;
                 }
-            }
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (ta0 + j < na_tiles) {
-                    u32x4 aq = af[((size_t)(ta0 + j) * ksteps + s) * 64 + lane];
-                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa.v, half8_to_bf8(aq), acc[j], 0, 0, 0);
-                }
+                for (int j = 0; j < 4; ++j)
+                    if (ta0 + j < na_tiles)
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[u].v, half8_to_bf8(aq[u][j]), acc[j], 0, 0, 0);
             }
         }
 #pragma unroll
@@ -288,27 +301,34 @@ __global__ void __launch_bounds__(256) moe_mfma_kernel(MGeom G, TqSection sec, c
         if (active && st + 2 < nmain) { load_w(wq[SLOT], u0 + st + 2); load_sz(szq[SLOT], u0 + st + 2); }
         const int buf = st & 1;
         if (active) {
+            bf16x8 xa[2][MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) xa[0][mt] = lds_frag(buf, mt, 0);
 #pragma unroll
             for (int gi = 0; gi < NG; ++gi) {
                 f32x16 part[MT][2];
 #pragma unroll
                 for (int ks = 0; ks < GS; ++ks) {
                     const int kidx = gi * GS + ks;
+                    // fragments of the next step are requested before this step's MFMAs are issued
+                    if (kidx + 1 < US) {
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt) xa[(kidx + 1) & 1][mt] = lds_frag(buf, mt, kidx + 1);
+                    }
                     bf16x8 bw[2];
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) bw[t] = unpack_word(word_of(wc[t][kidx / 4], kidx % 4));
+                    for (int t = 0; t < 2; ++t) bw[t] = unpack_word(word_of(wc[t][kidx / 4], kidx % 4), G.unpack_mask, G.unpack_magic);
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
-                        bf16x8 xa = lds_frag(buf, mt, kidx);
 #pragma unroll
                         for (int t = 0; t < 2; ++t) {
                             if (ks == 0) {
                                 f32x16 zero;
 #pragma unroll
                                 for (int v = 0; v < 16; ++v) zero[v] = 0.f;
-                                part[mt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, bw[t], zero, 0, 0, 0);
+                                part[mt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[kidx & 1][mt], bw[t], zero, 0, 0, 0);
                             } else {
-                                part[mt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, bw[t], part[mt][t], 0, 0, 0);
+                                part[mt][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[kidx & 1][mt], bw[t], part[mt][t], 0, 0, 0);
                             }
                         }
                     }
@@ -512,6 +532,7 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     MGeom G;
     G.ne = L.E + L.S; G.H = L.H; G.F = L.F; G.g = L.g; G.r = L.r; G.r16 = L.r16; G.k = L.k; G.S = L.S;
     G.a_tot = W.a_tot; G.expert_stride = L.expert_stride;
+    G.unpack_mask = 0x000F000Fu; G.unpack_magic = 0x43004300u;
     const int32_t* ctrl = reinterpret_cast<const int32_t*>(ws + W.ctrl);
     const int32_t* offsets = reinterpret_cast<const int32_t*>(ws + W.offsets);
     const int32_t* slot_of = reinterpret_cast<const int32_t*>(ws + W.slot_of);

@@ -62,9 +62,50 @@ __global__ void __launch_bounds__(256) route_kernel(const float* __restrict__ lo
 
 // ---------------------------------------------------------------------------------------------
 // Permutation.  Assignments are cut into chunks of TQ_PERM_CHUNK; one wavefront per chunk.
-//   hist_kernel:   per-chunk histogram over experts (also clears/validates the control block)
-//   scan_kernel:   per expert, exclusive scan over chunks; offsets; row-tile tables
+//   hist_kernel:    per-chunk histogram over experts (also validates the blob header)
+//   scan_kernel:    per expert, exclusive scan over chunks; offsets; row-tile tables
 //   scatter_kernel: stable placement, chunk by chunk, 64 assignments per round in order
+// permute_small_kernel does all of it in one wavefront when there is a single chunk (decode batches).
+//
+// Row-tile tables: for each tiling (32, 128, 16 rows) the list of (expert, first slot) of every tile,
+// expert-major; their lengths go to ctrl[1], ctrl[2], ctrl[4]; ctrl[3] = number of rows in total.
+__device__ inline int tile_rows_of(int which) { return which == 0 ? 32 : which == 1 ? 128 : 16; }
+__device__ inline int tile_ctrl_of(int which) { return which == 0 ? 1 : which == 1 ? 2 : 4; }
+
+__device__ inline int wave_incl_scan(int v, int lane)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int o = __shfl_up(v, off);
+        if (lane >= off) v += o;
+    }
+    return v;
+}
+
+// One wavefront: out[0..n] = exclusive prefix sum of f(in[i]); returns the total.  in/out live in LDS.
+template <typename F>
+__device__ inline int wave_excl_scan(const int32_t* in, int32_t* out, int n, int lane, F f)
+{
+    int carry = 0;
+    for (int i0 = 0; i0 < n; i0 += 64) {
+        int i = i0 + lane;
+        int v = i < n ? f(in[i]) : 0;
+        int inc = wave_incl_scan(v, lane);
+        if (i < n) out[i] = carry + inc - v;
+        carry += __shfl(inc, 63);
+    }
+    if (lane == 0) out[n] = carry;
+    return carry;
+}
+
+__device__ inline bool blob_header_ok(const TqBlobHeader* hdr, const TqBlobHeader& expect)
+{
+    return hdr->magic == expect.magic && hdr->version == expect.version && hdr->n_experts == expect.n_experts &&
+           hdr->n_shared == expect.n_shared && hdr->hidden == expect.hidden && hdr->ffn == expect.ffn &&
+           hdr->group == expect.group && hdr->bits == expect.bits && hdr->rank == expect.rank &&
+           hdr->expert_stride == expect.expert_stride;
+}
+
 __global__ void __launch_bounds__(64) hist_kernel(const int32_t* __restrict__ idx, int64_t n_assign, int E,
                                                   int32_t* __restrict__ hist, int32_t* __restrict__ err_flag,
                                                   const TqBlobHeader* __restrict__ hdr, TqBlobHeader expect,
@@ -87,71 +128,83 @@ __global__ void __launch_bounds__(64) hist_kernel(const int32_t* __restrict__ id
     for (int e = lane; e < E; e += 64) hist[(size_t)blockIdx.x * E + e] = cnt[e];
     if (bad && err_flag) atomicOr(err_flag, TQ_FLAG_BIT_RANGE);
     if (check_blob && blockIdx.x == 0 && lane == 0) {
-        bool ok = hdr->magic == expect.magic && hdr->version == expect.version &&
-                  hdr->n_experts == expect.n_experts && hdr->n_shared == expect.n_shared &&
-                  hdr->hidden == expect.hidden && hdr->ffn == expect.ffn && hdr->group == expect.group &&
-                  hdr->bits == expect.bits && hdr->rank == expect.rank &&
-                  hdr->expert_stride == expect.expert_stride;
-        if (!ok && err_flag) atomicOr(err_flag, TQ_FLAG_BIT_BLOB);
+        if (!blob_header_ok(hdr, expect) && err_flag) atomicOr(err_flag, TQ_FLAG_BIT_BLOB);
     }
 }
 
-// Single block.  hist[b][e] becomes the number of assignments of expert e in chunks before b.
-__global__ void __launch_bounds__(256) scan_kernel(int32_t* __restrict__ hist, int nblk, int E, int S, int T,
-                                                   int32_t* __restrict__ offsets, int32_t* __restrict__ tile_e,
-                                                   int32_t* __restrict__ tile_row0, int rt_max,
-                                                   int32_t* __restrict__ ctrl)
+// writes the three row-tile tables from offs[0..ne] (LDS); `sm_base` is LDS scratch of 3*(ne+1) ints
+__device__ inline void build_tile_tables(const int32_t* offs, int32_t* sm_base, int ne, int32_t* tile_e,
+                                         int32_t* tile_row0, int rt_max, int32_t* ctrl, int tid, int nthreads)
 {
-    extern __shared__ int32_t sm[];   // counts[E+S], then scratch
-    int32_t* counts = sm;
-    const int ne = E + S;
-    for (int e = threadIdx.x; e < E; e += blockDim.x) {
-        int run = 0;
-        for (int b = 0; b < nblk; ++b) {
-            int c = hist[(size_t)b * E + e];
-            hist[(size_t)b * E + e] = run;
-            run += c;
+    // per tiling: tiles of expert e = ceil(count/bm); scan by wavefront `which` (or by wave 0 in turn)
+    const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
+    for (int which = wave; which < 3; which += nwaves) {
+        const int bm = tile_rows_of(which);
+        int32_t* base = sm_base + which * (ne + 1);
+        int carry = 0;
+        for (int i0 = 0; i0 < ne; i0 += 64) {
+            int i = i0 + lane;
+            int v = i < ne ? (offs[i + 1] - offs[i] + bm - 1) / bm : 0;
+            int inc = wave_incl_scan(v, lane);
+            if (i < ne) base[i] = carry + inc - v;
+            carry += __shfl(inc, 63);
         }
-        counts[e] = run;
-    }
-    for (int s = threadIdx.x; s < S; s += blockDim.x) counts[E + s] = T;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int e = 0; e < ne; ++e) { offsets[e] = run; run += counts[e]; }
-        offsets[ne] = run;
-        if (ctrl) ctrl[3] = run;
+        if (lane == 0) { base[ne] = carry; ctrl[tile_ctrl_of(which)] = carry < rt_max ? carry : rt_max; }
     }
     __syncthreads();
-    if (tile_e && threadIdx.x < 2) {
-        // row-tile tables for the 32-row (index 0) and 128-row (index 1) tilings
-        const int which = threadIdx.x;
-        const int bm = which ? 128 : 32;
+    for (int i = tid; i < 3 * ne; i += nthreads) {
+        const int which = i / ne, e = i - which * ne;
+        const int bm = tile_rows_of(which);
+        int n = sm_base[which * (ne + 1) + e];
+        const int o = offs[e], c = offs[e + 1] - o;
         int32_t* te = tile_e + (size_t)which * rt_max;
         int32_t* tr = tile_row0 + (size_t)which * rt_max;
-        int n = 0;
-        for (int e = 0; e < ne; ++e) {
-            int o = offsets[e], c = counts[e];
-            for (int r0 = 0; r0 < c && n < rt_max; r0 += bm) { te[n] = e; tr[n] = o + r0; ++n; }
-        }
-        ctrl[1 + which] = n;
+        for (int r0 = 0; r0 < c && n < rt_max; r0 += bm, ++n) { te[n] = e; tr[n] = o + r0; }
     }
 }
 
-__global__ void __launch_bounds__(64) scatter_kernel(const int32_t* __restrict__ idx, const float* __restrict__ w,
-                                                     int64_t n_assign, int E, int S, int T, int k,
-                                                     const int32_t* __restrict__ hist,
-                                                     const int32_t* __restrict__ offsets,
-                                                     int32_t* __restrict__ slot_of, int slot_stride,
-                                                     int32_t* __restrict__ src_of, int32_t* __restrict__ row_token,
-                                                     float* __restrict__ row_w)
+// Single block of 1024 threads.  hist[b][e] becomes the number of assignments of expert e in chunks before b.
+__global__ void __launch_bounds__(1024) scan_kernel(int32_t* __restrict__ hist, int nblk, int E, int S, int T,
+                                                    int32_t* __restrict__ offsets, int32_t* __restrict__ tile_e,
+                                                    int32_t* __restrict__ tile_row0, int rt_max,
+                                                    int32_t* __restrict__ ctrl)
 {
-    extern __shared__ int32_t cursor[];   // next free slot of each expert for this chunk
-    const int lane = threadIdx.x;
-    for (int e = lane; e < E; e += 64) cursor[e] = offsets[e] + hist[(size_t)blockIdx.x * E + e];
+    extern __shared__ int32_t sm[];   // counts[ne] | offs[ne+1] | tile scratch 3*(ne+1)
+    const int ne = E + S;
+    int32_t* counts = sm;
+    int32_t* offs = sm + ne;
+    int32_t* tsm = offs + ne + 1;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int e = wave; e < E; e += 16) {
+        int run = 0;
+        for (int b0 = 0; b0 < nblk; b0 += 64) {
+            int b = b0 + lane;
+            int v = b < nblk ? hist[(size_t)b * E + e] : 0;
+            int inc = wave_incl_scan(v, lane);
+            if (b < nblk) hist[(size_t)b * E + e] = run + inc - v;
+            run += __shfl(inc, 63);
+        }
+        if (lane == 0) counts[e] = run;
+    }
+    for (int s = tid; s < S; s += 1024) counts[E + s] = T;
     __syncthreads();
-    const int64_t a0 = (int64_t)blockIdx.x * TQ_PERM_CHUNK;
+    if (wave == 0) {
+        int total = wave_excl_scan(counts, offs, ne, lane, [](int v) { return v; });
+        if (lane == 0 && ctrl) ctrl[3] = total;
+    }
+    __syncthreads();
+    for (int e = tid; e <= ne; e += 1024) offsets[e] = offs[e];
+    if (tile_e) build_tile_tables(offs, tsm, ne, tile_e, tile_row0, rt_max, ctrl, tid, 1024);
+}
+
+// stable placement of one chunk of assignments by one wavefront; cursor[e] (LDS) = next free slot of expert e
+__device__ inline void scatter_chunk(const int32_t* __restrict__ idx, const float* __restrict__ w, int64_t a0,
+                                     int64_t n_assign, int E, int k, int32_t* cursor, int lane,
+                                     int32_t* __restrict__ slot_of, int slot_stride, int32_t* __restrict__ src_of,
+                                     int32_t* __restrict__ row_token, float* __restrict__ row_w)
+{
     for (int i0 = 0; i0 < TQ_PERM_CHUNK; i0 += 64) {
+        if (a0 + i0 >= n_assign) break;
         int64_t a = a0 + i0 + lane;
         int e = -1;
         if (a < n_assign) {
@@ -184,6 +237,22 @@ __global__ void __launch_bounds__(64) scatter_kernel(const int32_t* __restrict__
             }
         }
     }
+}
+
+__global__ void __launch_bounds__(64) scatter_kernel(const int32_t* __restrict__ idx, const float* __restrict__ w,
+                                                     int64_t n_assign, int E, int S, int T, int k,
+                                                     const int32_t* __restrict__ hist,
+                                                     const int32_t* __restrict__ offsets,
+                                                     int32_t* __restrict__ slot_of, int slot_stride,
+                                                     int32_t* __restrict__ src_of, int32_t* __restrict__ row_token,
+                                                     float* __restrict__ row_w)
+{
+    extern __shared__ int32_t cursor[];   // next free slot of each expert for this chunk
+    const int lane = threadIdx.x;
+    for (int e = lane; e < E; e += 64) cursor[e] = offsets[e] + hist[(size_t)blockIdx.x * E + e];
+    __syncthreads();
+    scatter_chunk(idx, w, (int64_t)blockIdx.x * TQ_PERM_CHUNK, n_assign, E, k, cursor, lane, slot_of, slot_stride,
+                  src_of, row_token, row_w);
     // shared experts: every token, weight 1, identity order
     if (S > 0) {
         const int64_t total = (int64_t)S * T;
@@ -195,6 +264,54 @@ __global__ void __launch_bounds__(64) scatter_kernel(const int32_t* __restrict__
             if (row_w) row_w[slot] = 1.0f;
         }
     }
+}
+
+// The whole permutation for at most TQ_PERM_CHUNK assignments in ONE wavefront (one launch instead of four).
+__global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __restrict__ idx, const float* __restrict__ w,
+                                                           int n_assign, int E, int S, int T, int k,
+                                                           int32_t* __restrict__ offsets, int32_t* __restrict__ slot_of,
+                                                           int slot_stride, int32_t* __restrict__ src_of,
+                                                           int32_t* __restrict__ row_token, float* __restrict__ row_w,
+                                                           int32_t* __restrict__ tile_e, int32_t* __restrict__ tile_row0,
+                                                           int rt_max, int32_t* __restrict__ ctrl,
+                                                           int32_t* __restrict__ err_flag,
+                                                           const TqBlobHeader* __restrict__ hdr, TqBlobHeader expect,
+                                                           int check_blob)
+{
+    extern __shared__ int32_t sm[];   // counts[ne] | offs[ne+1] | cursor[E] | tile scratch 3*(ne+1)
+    const int ne = E + S, lane = threadIdx.x;
+    int32_t* counts = sm;
+    int32_t* offs = counts + ne;
+    int32_t* cursor = offs + ne + 1;
+    int32_t* tsm = cursor + E;
+    if (ctrl) ctrl[lane] = 0;
+    for (int e = lane; e < ne; e += 64) counts[e] = e < E ? 0 : T;
+    __syncthreads();
+    bool bad = false;
+    for (int a = lane; a < n_assign; a += 64) {
+        int e = idx[a];
+        if (e >= 0 && e < E) atomicAdd(&counts[e], 1); else bad = true;
+    }
+    __syncthreads();
+    int flags = __ballot(bad) ? TQ_FLAG_BIT_RANGE : 0;
+    if (check_blob && !blob_header_ok(hdr, expect)) flags |= TQ_FLAG_BIT_BLOB;
+    int total = wave_excl_scan(counts, offs, ne, lane, [](int v) { return v; });
+    __syncthreads();
+    for (int e = lane; e <= ne; e += 64) offsets[e] = offs[e];
+    for (int e = lane; e < E; e += 64) cursor[e] = offs[e];
+    __syncthreads();
+    if (ctrl && lane == 0) ctrl[3] = total;
+    if (tile_e) build_tile_tables(offs, tsm, ne, tile_e, tile_row0, rt_max, ctrl, lane, 64);
+    __syncthreads();
+    scatter_chunk(idx, w, 0, n_assign, E, k, cursor, lane, slot_of, slot_stride, src_of, row_token, row_w);
+    for (int i = lane; i < S * T; i += 64) {
+        int s = i / T, t = i % T;
+        int slot = offs[E + s] + t;
+        if (slot_of) slot_of[(size_t)t * slot_stride + k + s] = slot;
+        if (row_token) row_token[slot] = t;
+        if (row_w) row_w[slot] = 1.0f;
+    }
+    if (flags && lane == 0 && err_flag) atomicOr(err_flag, flags);
 }
 
 __global__ void clear_ctrl_kernel(int32_t* ctrl, int32_t* err_flag)
@@ -221,6 +338,15 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
         expect.n_experts = L->E; expect.n_shared = L->S; expect.hidden = L->H; expect.ffn = L->F;
         expect.group = L->g; expect.bits = L->bits; expect.rank = L->r; expect.expert_stride = L->expert_stride;
     }
+    const int ne = E + S;
+    if (nblk == 1 && (int64_t)S * T <= 4096) {
+        const size_t sm = ((size_t)ne + (ne + 1) + E + 3 * (ne + 1)) * 4;
+        hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(64), sm, stream, topk_idx, topk_w, (int)n_assign, E, S,
+                           T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e, tile_row0, rt_max,
+                           ctrl, err_flag, (const TqBlobHeader*)blob, expect, check);
+        TQ_CHECK_LAUNCH();
+        return TQ_OK;
+    }
     if (ctrl) {
         hipLaunchKernelGGL(clear_ctrl_kernel, dim3(1), dim3(64), 0, stream, ctrl, err_flag);
         TQ_CHECK_LAUNCH();
@@ -228,8 +354,9 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
     hipLaunchKernelGGL(hist_kernel, dim3(nblk), dim3(64), (size_t)E * 4, stream, topk_idx, n_assign, E, hist,
                        err_flag, (const TqBlobHeader*)blob, expect, check);
     TQ_CHECK_LAUNCH();
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), (size_t)(E + S) * 4, stream, hist, nblk, E, S, T, offsets,
-                       tile_e, tile_row0, rt_max, ctrl);
+    const size_t sm_scan = ((size_t)ne + (ne + 1) + 3 * (ne + 1)) * 4;
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), sm_scan, stream, hist, nblk, E, S, T, offsets, tile_e,
+                       tile_row0, rt_max, ctrl);
     TQ_CHECK_LAUNCH();
     hipLaunchKernelGGL(scatter_kernel, dim3(nblk), dim3(64), (size_t)E * 4, stream, topk_idx, topk_w, n_assign, E,
                        S, T, k, hist, offsets, slot_of, slot_stride, src_of, row_token, row_w);
