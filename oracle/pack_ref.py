@@ -8,6 +8,38 @@ from __future__ import annotations
 
 import numpy as np
 
+
+def _bf16_rne(a: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bits, round to nearest even (finite inputs)."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    return ((u + np.uint32(0x7FFF) + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def _zero_coeff_parts(scale_bits: np.ndarray, zero_bits: np.ndarray, g16: int):
+    """[N, G] fp16 bit patterns -> (hi, lo) bf16 bit patterns [N, 16*g16] of c = -scale * (128 + zero),
+    evaluated in fp32 as the header specifies; groups beyond G are zero."""
+    s = scale_bits.view(np.float16).astype(np.float32)
+    z = zero_bits.view(np.float16).astype(np.float32)
+    c = (-s) * (np.float32(128.0) + z)
+    hi = _bf16_rne(c)
+    hi_f = (hi.astype(np.uint32) << 16).view(np.float32)
+    lo = _bf16_rne(c - hi_f)
+    N, G = s.shape
+    out_hi = np.zeros((N, 16 * g16), dtype=np.uint16)
+    out_lo = np.zeros_like(out_hi)
+    out_hi[:, :G] = hi
+    out_lo[:, :G] = lo
+    return out_hi, out_lo
+
+
+def _zc_part(hi: np.ndarray, lo: np.ndarray) -> np.ndarray:
+    """[N, 16*g16] -> [N, g16 (block), 3 (which), 2 (hf), 8 (i)]: which 0, 1 = hi, which 2 = lo."""
+    N = hi.shape[0]
+    h = hi.reshape(N, -1, 2, 8)
+    l = lo.reshape(N, -1, 2, 8)
+    return np.stack([h, h, l], axis=2)
+
+
 _NIBBLE_POS = [(i // 2) + 4 * (i % 2) for i in range(8)]
 
 
@@ -52,6 +84,11 @@ def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r) -> bytes:
             sz = np.stack([(scale3[p].astype(np.uint32) | (zero3[p].astype(np.uint32) << 16)).reshape(pairs, 32, K // g)
                            for p in (0, 1)], axis=0)          # [tile, pairs, col, G]
             parts.append(np.ascontiguousarray(sz.transpose(1, 3, 0, 2)).tobytes())
+            g16 = (K // g + 15) // 16
+            zc = np.stack([_zc_part(*_zero_coeff_parts(scale3[p], zero3[p], g16)).reshape(pairs, 32, g16, 3, 2, 8)
+                           for p in (0, 1)], axis=0)
+            # [tile, pairs, col, block, which, hf, i] -> [pairs, step = 3*block + which, tile, hf, col, i]
+            parts.append(np.ascontiguousarray(zc.transpose(1, 3, 4, 0, 5, 2, 6)).tobytes())
             if r > 0:
                 b = np.stack([_pad_rows(B3[p], r16).reshape(r16 // 16, 2, 8, pairs, 32) for p in (0, 1)], axis=0)
                 # [tile, step, hf, i, pairs, col] -> [pairs, step, tile, hf, col, i]
@@ -68,6 +105,10 @@ def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r) -> bytes:
             parts.append(np.ascontiguousarray(w.transpose(0, 3, 1, 5, 2, 4)).tobytes())
             sz = (scale3[2].astype(np.uint32) | (zero3[2].astype(np.uint32) << 16)).reshape(pairs, 2, 32, K // g)
             parts.append(np.ascontiguousarray(sz.transpose(0, 3, 1, 2)).tobytes())
+            g16 = (K // g + 15) // 16
+            zc = _zc_part(*_zero_coeff_parts(scale3[2], zero3[2], g16)).reshape(pairs, 2, 32, g16, 3, 2, 8)
+            # [pairs, tile, col, block, which, hf, i] -> [pairs, step, tile, hf, col, i]
+            parts.append(np.ascontiguousarray(zc.transpose(0, 3, 4, 1, 5, 2, 6)).tobytes())
             if r > 0:
                 b = _pad_rows(B3[2], r16).reshape(r16 // 16, 2, 8, pairs, 2, 32)
                 # [step, hf, i, pairs, tile, col] -> [pairs, step, tile, hf, col, i]

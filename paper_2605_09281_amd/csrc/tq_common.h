@@ -24,8 +24,9 @@ struct TqSection {
     int32_t chunks;  // K / 64
     int32_t groups;  // K / g
     int32_t na_tiles;  // 32-wide tiles of the A-factor columns
+    int32_t zsteps;    // 16-wide steps of the zero-point coefficient part: 3 * ceil(groups / 16)
     // byte offsets from the start of the expert record
-    size_t codes, sz, bfrag, afrag, end;
+    size_t codes, sz, zc, bfrag, afrag, end;
 };
 
 struct TqLayout {
@@ -39,7 +40,7 @@ struct TqBlobHeader {
     uint32_t magic, version;
     int32_t n_experts, n_shared, hidden, ffn, group, bits, rank, r16;
     uint64_t expert_stride, total_bytes;
-    uint64_t off[8];  // gu.codes, gu.sz, gu.bfrag, gu.afrag, d.codes, d.sz, d.bfrag, d.afrag
+    uint64_t off[10];  // gu.codes, gu.sz, gu.zc, gu.bfrag, gu.afrag, then the same five of d
 };
 static_assert(sizeof(TqBlobHeader) <= TQ_HEADER_BYTES, "header too large");
 
@@ -65,6 +66,8 @@ __host__ inline bool tq_make_layout(const tq_layer_desc* d, TqLayout* L)
         s.pairs = pairs; s.K = K; s.chunks = K / 64; s.groups = K / L->g; s.na_tiles = (na + 31) / 32;
         s.codes = off; off += (size_t)pairs * s.chunks * 2048;
         s.sz = off;    off += (size_t)pairs * s.groups * 256;
+        s.zsteps = 3 * ((s.groups + 15) / 16);
+        s.zc = off;    off += (size_t)pairs * s.zsteps * 2048;
         s.bfrag = off; off += (size_t)pairs * (L->r16 / 16) * 2048;
         s.afrag = off; off += (size_t)s.na_tiles * (K / 16) * 1024;
         s.end = off;
@@ -102,9 +105,10 @@ struct TqWorkspace {
 #define TQ_MAX_SPLIT 8      // K-splits of the down projection on the small-tile path
 
 __host__ __device__ inline int tq_pad64(int v) { return (v + 63) / 64 * 64; }
-// augmented-K length: three bf16 split terms per quantisation group (zero-point correction) followed by
-// the rank-r intermediate, each region padded to 16, the whole to one staging unit (max(g, 64))
-__host__ __device__ inline int tq_zero_terms(int K, int g) { return (3 * (K / g) + 15) / 16 * 16; }
+// augmented-K length: three bf16 split terms per quantisation group (zero-point correction; groups in blocks
+// of 16, each block laid out hi | lo | hi) followed by the rank-r intermediate, the whole padded to one
+// staging unit (max(g, 64))
+__host__ __device__ inline int tq_zero_terms(int K, int g) { return 48 * ((K / g + 15) / 16); }
 __host__ __device__ inline int tq_aug_len(int K, int g, int n_lr)
 {
     const int unit = g < 64 ? 64 : g;

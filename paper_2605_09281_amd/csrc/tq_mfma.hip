@@ -130,9 +130,10 @@ __global__ void __launch_bounds__(256) aug_kernel(MGeom G, TqSection sec, const 
                             int gi = s / GS;
                             uint32_t hi = f2bf_bits(tot);
                             uint32_t lo = f2bf_bits(tot - __uint_as_float(hi << 16));
-                            orow[gi] = (uint16_t)hi;
-                            orow[groups + gi] = (uint16_t)lo;
-                            orow[2 * groups + gi] = (uint16_t)hi;
+                            uint16_t* zb = orow + 48 * (gi >> 4) + (gi & 15);   // block of 16 groups: hi | lo | hi
+                            zb[0] = (uint16_t)hi;
+                            zb[16] = (uint16_t)lo;
+                            zb[32] = (uint16_t)hi;
                         }
                         gsum = 0.f;
                     }
@@ -159,19 +160,23 @@ __global__ void __launch_bounds__(256) aug_kernel(MGeom G, TqSection sec, const 
     }
     // the padding must be finite (it meets zero weights in the MFMA): write zeros
     if (writer) {
-        for (int kk = 3 * groups; kk < ZT; ++kk) orow[kk] = 0;
+        for (int gi = groups; gi < 16 * ((groups + 15) / 16); ++gi) {
+            uint16_t* zb = orow + 48 * (gi >> 4) + (gi & 15);
+            zb[0] = 0; zb[16] = 0; zb[32] = 0;
+        }
         for (int kk = ZT + ((G.r > 0) ? NA : 0); kk < ka; ++kk) orow[kk] = 0;
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// The grouped GEMM.  Workgroup = 4 waves sharing one row tile of BM = 32*MT rows; wave w owns column-tile
-// pair 4*blockIdx.x + w (64 output columns; in stage 0 that is 32 gate + the matching 32 up columns).
+// The grouped GEMM.  Workgroup = 4*WM waves sharing one row tile of BM = 32*MT*WM rows; wave (wm, wn) owns
+// rows [32*MT*wm, 32*MT*(wm+1)) of the tile and column-tile pair 4*nb + wn (64 output columns; in
+// stage 0 that is 32 gate + the matching 32 up columns).
 //   STAGE 0: out = h[slot][F] bf16 = silu(gate) * up
 //   STAGE 1: out = yd[split][slot][H] fp32, split = blockIdx.z covering a slice of K
 // GS = quantisation group in MFMA steps (g/16).  A "unit" is max(g, 64) contraction indices.
-template <int MT, int STAGE, int GS>
-__global__ void __launch_bounds__(256) moe_mfma_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
+template <int MT, int WM, int STAGE, int GS>
+__global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
                                                        const uint16_t* __restrict__ xin,
                                                        const uint16_t* __restrict__ xaug,
                                                        const int32_t* __restrict__ row_token,
@@ -181,7 +186,8 @@ __global__ void __launch_bounds__(256) moe_mfma_kernel(MGeom G, TqSection sec, c
                                                        const int32_t* __restrict__ ctrl, int ctrl_idx,
                                                        void* __restrict__ out, int ka, int nsplit)
 {
-    constexpr int BM = 32 * MT;
+    constexpr int BM = 32 * MT * WM;
+    constexpr int NTHR = 256 * WM;
     constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
     constexpr int UC = UNIT_K / 64;     // 64-wide chunks (one u32x4 of codes per lane and tile) per unit
     constexpr int US = UNIT_K / 16;     // MFMA steps per unit
@@ -189,7 +195,7 @@ __global__ void __launch_bounds__(256) moe_mfma_kernel(MGeom G, TqSection sec, c
     constexpr int ROWB = UNIT_K * 2 + 16;   // LDS bytes per activation row (16 B pad: conflict-free b128 reads)
     constexpr int BUFB = BM * ROWB;
     constexpr int TPR = UNIT_K / 8;     // threads (16-byte segments) per row when loading a unit
-    constexpr int RPP = 256 / TPR;      // rows per pass
+    constexpr int RPP = NTHR / TPR;     // rows per pass
     constexpr int NP = BM / RPP;        // passes
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -197,12 +203,20 @@ __global__ void __launch_bounds__(256) moe_mfma_kernel(MGeom G, TqSection sec, c
     int32_t* toka = tokx + BM;                                    // [BM] row in xaug
 
     const int K = sec.K;
-    const int rt = blockIdx.y;
+    // XCD-aware mapping: consecutive workgroup ids go to the 8 XCDs in turn, each with its own L2.  Ids are
+    // laid out so that XCD x works on row tiles x, x+8, ... and walks through all column blocks of a row
+    // tile itself: the activation tile is then re-read from that XCD's L2 instead of from memory by all 8.
+    const int nb_count = (sec.pairs + 3) / 4;
+    const int wg = blockIdx.x;
+    const int grp = wg / (8 * nb_count), rem = wg - grp * (8 * nb_count);
+    const int nb = rem >> 3;
+    const int rt = grp * 8 + (rem & 7);
     if (rt >= ctrl[ctrl_idx]) return;
     const int e = tile_e[rt], slot0 = tile_row0[rt];
     const int rows = min(BM, offsets[e + 1] - slot0);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
-    const int pair_raw = blockIdx.x * 4 + wave;
+    const int wn = wave & 3, wm = wave >> 2;
+    const int pair_raw = nb * 4 + wn;
     const bool active = pair_raw < sec.pairs;
     const int pair = active ? pair_raw : sec.pairs - 1;
     const int split = blockIdx.z;
@@ -217,6 +231,7 @@ __global__ void __launch_bounds__(256) moe_mfma_kernel(MGeom G, TqSection sec, c
     const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
     const u32x4* codes = reinterpret_cast<const u32x4*>(rec + sec.codes) + (size_t)pair * sec.chunks * 128 + lane;
     const uint32_t* szp = reinterpret_cast<const uint32_t*>(rec + sec.sz) + (size_t)pair * sec.groups * 64 + col;
+    const u32x4* zcp = reinterpret_cast<const u32x4*>(rec + sec.zc) + (size_t)pair * sec.zsteps * 128 + lane;
     const u32x4* bfr = reinterpret_cast<const u32x4*>(rec + sec.bfrag) + (size_t)pair * (G.r16 / 16) * 128 + lane;
 
     const int NU = K / UNIT_K;
@@ -268,6 +283,11 @@ __global__ void __launch_bounds__(256) moe_mfma_kernel(MGeom G, TqSection sec, c
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mt][t][v] = 0.f;
 
+    // the or-operand of the unpack lives in a vector register (only one scalar operand fits the and-or
+    // encoding); the move is opaque to the compiler so that it does not fold the value back into a literal
+    uint32_t magic_v;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(magic_v) : "s"(G.unpack_magic));
+
     u32x4 wq[2][2][UC];
     uint32_t szq[2][NG][2];
 
@@ -280,7 +300,7 @@ __global__ void __launch_bounds__(256) moe_mfma_kernel(MGeom G, TqSection sec, c
 
     auto lds_frag = [&](int buf, int mt, int kstep) -> bf16x8 {
         Frag f;
-        f.q = *reinterpret_cast<const u32x4*>(lds + buf * BUFB + (32 * mt + col) * ROWB + (kstep * 16 + 8 * hf) * 2);
+        f.q = *reinterpret_cast<const u32x4*>(lds + buf * BUFB + (32 * (MT * wm + mt) + col) * ROWB + (kstep * 16 + 8 * hf) * 2);
         return f.v;
     };
 
@@ -317,7 +337,7 @@ __global__ void __launch_bounds__(256) moe_mfma_kernel(MGeom G, TqSection sec, c
                     }
                     bf16x8 bw[2];
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) bw[t] = unpack_word(word_of(wc[t][kidx / 4], kidx % 4), G.unpack_mask, G.unpack_magic);
+                    for (int t = 0; t < 2; ++t) bw[t] = unpack_word(word_of(wc[t][kidx / 4], kidx % 4), G.unpack_mask, magic_v);
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
@@ -367,29 +387,11 @@ __global__ void __launch_bounds__(256) moe_mfma_kernel(MGeom G, TqSection sec, c
                 bf16x8 bw[2];
                 bool use[2] = {false, false};
                 if (k0 < ZT) {
+                    const int step = k0 / 16;
 #pragma unroll
                     for (int t = 0; t < 2; ++t) {
                         Frag f;
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            float cv[2];
-#pragma unroll
-                            for (int h2 = 0; h2 < 2; ++h2) {
-                                const int kz = k0 + 8 * hf + 2 * j + h2;
-                                float val = 0.f;
-                                if (kz < 3 * groups) {
-                                    const int which = kz / groups, grp = kz - which * groups;
-                                    const uint32_t sz = szp[((size_t)grp * 2 + t) * 32];
-                                    const float s = tq_half_bits_to_float((uint16_t)(sz & 0xFFFF));
-                                    const float z = tq_half_bits_to_float((uint16_t)(sz >> 16));
-                                    const float c = -s * (128.f + z);
-                                    const float ch = __uint_as_float(f2bf_bits(c) << 16);
-                                    val = which < 2 ? ch : c - ch;
-                                }
-                                cv[h2] = val;
-                            }
-                            f.u[j] = pack_bf2(cv[0], cv[1]);
-                        }
+                        f.q = zcp[((size_t)step * 2 + t) * 64];
                         bw[t] = f.v;
                         use[t] = true;
                     }
@@ -425,7 +427,7 @@ __global__ void __launch_bounds__(256) moe_mfma_kernel(MGeom G, TqSection sec, c
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int m = 32 * mt + 8 * (v / 4) + 4 * hf + (v % 4);
+                const int m = 32 * (MT * wm + mt) + 8 * (v / 4) + 4 * hf + (v % 4);
                 if (m < rows) {
                     const float gte = acc[mt][0][v], up = acc[mt][1][v];
                     const float hv = gte / (1.0f + __expf(-gte)) * up;
@@ -438,7 +440,7 @@ __global__ void __launch_bounds__(256) moe_mfma_kernel(MGeom G, TqSection sec, c
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int m = 32 * mt + 8 * (v / 4) + 4 * hf + (v % 4);
+                const int m = 32 * (MT * wm + mt) + 8 * (v / 4) + 4 * hf + (v % 4);
                 if (m < rows) {
 #pragma unroll
                     for (int t = 0; t < 2; ++t)
@@ -475,17 +477,17 @@ __global__ void __launch_bounds__(256) combine_bf16_kernel(int T, int H, int k, 
     *reinterpret_cast<uint2*>(y + (size_t)t * H + c) = o;
 }
 
-template <int MT, int STAGE, int GS>
+template <int MT, int WM, int STAGE, int GS>
 tq_status launch_main(const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin, const uint16_t* xaug,
                       const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
                       const int32_t* offsets, const int32_t* ctrl, int ctrl_idx, void* out, int ka, int nsplit,
                       int row_tiles, hipStream_t st)
 {
-    constexpr int BM = 32 * MT;
+    constexpr int BM = 32 * MT * WM;
     constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
     constexpr int ROWB = UNIT_K * 2 + 16;
     const size_t smem = (size_t)2 * BM * ROWB + (size_t)2 * BM * 4;
-    auto kern = moe_mfma_kernel<MT, STAGE, GS>;
+    auto kern = moe_mfma_kernel<MT, WM, STAGE, GS>;
     if (smem > 64 * 1024) {
         static bool done = false;   // per instantiation
         if (!done) {
@@ -494,15 +496,17 @@ tq_status launch_main(const MGeom& G, const TqSection& sec, const uint8_t* blob,
             done = true;
         }
     }
-    dim3 grid((sec.pairs + 3) / 4, row_tiles, nsplit);
-    if (grid.y > 65535) return TQ_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl,
+    const int nb_count = (sec.pairs + 3) / 4;
+    const long n_wg = (long)((row_tiles + 7) / 8) * 8 * nb_count;
+    if (n_wg > 0x7FFFFFFF || nb_count > 65535) return TQ_ERR_UNSUPPORTED;
+    dim3 grid((unsigned)n_wg, 1, nsplit);
+    hipLaunchKernelGGL(kern, grid, dim3(256 * WM), smem, st, G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl,
                        ctrl_idx, out, ka, nsplit);
     TQ_CHECK_LAUNCH();
     return TQ_OK;
 }
 
-template <int MT, int STAGE>
+template <int MT, int WM, int STAGE>
 tq_status launch_main_gs(int gs, const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin, const uint16_t* xaug,
                          const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
                          const int32_t* offsets, const int32_t* ctrl, int ctrl_idx, void* out, int ka, int nsplit,
@@ -510,7 +514,7 @@ tq_status launch_main_gs(int gs, const MGeom& G, const TqSection& sec, const uin
 {
 #define TQ_CASE(GSV)                                                                                              \
     case GSV:                                                                                                     \
-        return launch_main<MT, STAGE, GSV>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl, ctrl_idx, \
+        return launch_main<MT, WM, STAGE, GSV>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl, ctrl_idx, \
                                            out, ka, nsplit, row_tiles, st)
     switch (gs) {
         TQ_CASE(2);
@@ -558,11 +562,16 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     TQ_CHECK_LAUNCH();
     tqi_record_stage(2, stream);
     tq_status rc;
-    if (large)
-        rc = launch_main_gs<4, 0>(gs, G, L.gu, blob, x, xaug_gu, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max, offsets,
+    // 128-row tiles: eight waves of 64x64 (two per SIMD, accumulators in VGPRs); groups of 256 need too many
+    // registers for that and run as four waves of 128x64
+    if (large && gs == 16)
+        rc = launch_main<4, 1, 0, 16>(G, L.gu, blob, x, xaug_gu, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max,
+                                      offsets, ctrl, 2, h, W.ka_gu, 1, rt128, stream);
+    else if (large)
+        rc = launch_main_gs<2, 2, 0>(gs, G, L.gu, blob, x, xaug_gu, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max, offsets,
                                   ctrl, 2, h, W.ka_gu, 1, rt128, stream);
     else
-        rc = launch_main_gs<1, 0>(gs, G, L.gu, blob, x, xaug_gu, row_token, tile_e, tile_row0, offsets, ctrl, 1, h, W.ka_gu, 1,
+        rc = launch_main_gs<1, 1, 0>(gs, G, L.gu, blob, x, xaug_gu, row_token, tile_e, tile_row0, offsets, ctrl, 1, h, W.ka_gu, 1,
                                   rt32, stream);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(3, stream);
@@ -580,11 +589,14 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
         nsplit = want < 1 ? 1 : want > TQ_MAX_SPLIT ? TQ_MAX_SPLIT : want;
         if (nsplit > nu) nsplit = nu;
     }
-    if (large)
-        rc = launch_main_gs<4, 1>(gs, G, L.d, blob, h, xaug_d, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max, offsets,
+    if (large && gs == 16)
+        rc = launch_main<4, 1, 1, 16>(G, L.d, blob, h, xaug_d, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max,
+                                      offsets, ctrl, 2, yd, W.ka_d, 1, rt128, stream);
+    else if (large)
+        rc = launch_main_gs<2, 2, 1>(gs, G, L.d, blob, h, xaug_d, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max, offsets,
                                   ctrl, 2, yd, W.ka_d, 1, rt128, stream);
     else
-        rc = launch_main_gs<1, 1>(gs, G, L.d, blob, h, xaug_d, row_token, tile_e, tile_row0, offsets, ctrl, 1, yd, W.ka_d,
+        rc = launch_main_gs<1, 1, 1>(gs, G, L.d, blob, h, xaug_d, row_token, tile_e, tile_row0, offsets, ctrl, 1, yd, W.ka_d,
                                   nsplit, rt32, stream);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(5, stream);

@@ -103,6 +103,56 @@ __global__ void sz_kernel(PackGeom G, uint8_t* __restrict__ blob, uint16_t* __re
     }
 }
 
+
+// Derived part (pack only): bf16 hi/lo split of c = -scale * (128 + zero), the coefficient of the group sum
+// of the activations once the codes are fed to the MFMA as 128 + q.  One thread per 8-element fragment.
+__device__ inline uint32_t bf16_rne_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+__global__ void zc_kernel(PackGeom G, uint8_t* __restrict__ blob, const uint16_t* __restrict__ scale,
+                          const uint16_t* __restrict__ zero)
+{
+    const size_t n_gu = (size_t)G.gu.pairs * G.gu.zsteps * 128;
+    const size_t n_d = (size_t)G.d.pairs * G.d.zsteps * 128;
+    const size_t per_exp = n_gu + n_d;
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= per_exp * G.n_exp) return;
+    int e = (int)(idx / per_exp);
+    size_t w = idx % per_exp;
+    const bool is_d = w >= n_gu;
+    const TqSection& sec = is_d ? G.d : G.gu;
+    if (is_d) w -= n_gu;
+    int lane = (int)(w & 63);
+    int tile = (int)((w >> 6) & 1);
+    size_t ps = w >> 7;
+    int step = (int)(ps % sec.zsteps);
+    int pair = (int)(ps / sec.zsteps);
+    int col = lane & 31, hf = lane >> 5;
+    int p, n;
+    if (!is_d) { p = tile; n = 32 * pair + col; }
+    else       { p = 2;    n = 64 * pair + 32 * tile + col; }
+    const size_t HFg = (size_t)G.H * G.F / G.g;
+    const int which = step % 3, gblock = step / 3;
+    uint16_t* dst = reinterpret_cast<uint16_t*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.zc) + w * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int grp = 16 * gblock + 8 * hf + i;
+        uint16_t out = 0;
+        if (grp < sec.groups) {
+            size_t ci = ((size_t)e * 3 + p) * HFg + (size_t)n * sec.groups + grp;
+            const float s = __half2float(__ushort_as_half(scale[ci]));
+            const float z = __half2float(__ushort_as_half(zero[ci]));
+            const float c = -s * (128.0f + z);
+            const uint32_t hi = bf16_rne_bits(c);
+            out = which < 2 ? (uint16_t)hi : (uint16_t)bf16_rne_bits(c - __uint_as_float(hi << 16));
+        }
+        dst[i] = out;
+    }
+}
+
 // One thread per 8-element fragment of B.  Padding rows (rho >= r) are written as zero and skipped on unpack.
 template <bool PACK>
 __global__ void bfrag_kernel(PackGeom G, uint8_t* __restrict__ blob, uint16_t* __restrict__ B)
@@ -199,6 +249,11 @@ tq_status run(const TqLayout& L, uint8_t* blob, uint8_t* codes, uint16_t* scale,
     TQ_CHECK_LAUNCH();
     hipLaunchKernelGGL(sz_kernel<PACK>, dim3(blocks_for(n_sz)), dim3(256), 0, st, G, blob, scale, zero);
     TQ_CHECK_LAUNCH();
+    if (PACK) {
+        size_t n_zc = ((size_t)L.gu.pairs * L.gu.zsteps + (size_t)L.d.pairs * L.d.zsteps) * 128 * ne;
+        hipLaunchKernelGGL(zc_kernel, dim3(blocks_for(n_zc)), dim3(256), 0, st, G, blob, scale, zero);
+        TQ_CHECK_LAUNCH();
+    }
     if (L.r > 0) {
         size_t n_b = ((size_t)L.gu.pairs + L.d.pairs) * (L.r16 / 16) * 128 * ne;
         size_t n_a = ((size_t)L.gu.na_tiles * (L.gu.K / 16) + (size_t)L.d.na_tiles * (L.d.K / 16)) * 64 * ne;
@@ -239,8 +294,8 @@ extern "C" tq_status tq_pack_weights(const tq_layer_desc* desc, const tq_weights
     hdr.n_experts = L.E; hdr.n_shared = L.S; hdr.hidden = L.H; hdr.ffn = L.F; hdr.group = L.g;
     hdr.bits = L.bits; hdr.rank = L.r; hdr.r16 = L.r16;
     hdr.expert_stride = L.expert_stride; hdr.total_bytes = L.total_bytes;
-    hdr.off[0] = L.gu.codes; hdr.off[1] = L.gu.sz; hdr.off[2] = L.gu.bfrag; hdr.off[3] = L.gu.afrag;
-    hdr.off[4] = L.d.codes; hdr.off[5] = L.d.sz; hdr.off[6] = L.d.bfrag; hdr.off[7] = L.d.afrag;
+    hdr.off[0] = L.gu.codes; hdr.off[1] = L.gu.sz; hdr.off[2] = L.gu.zc; hdr.off[3] = L.gu.bfrag; hdr.off[4] = L.gu.afrag;
+    hdr.off[5] = L.d.codes; hdr.off[6] = L.d.sz; hdr.off[7] = L.d.zc; hdr.off[8] = L.d.bfrag; hdr.off[9] = L.d.afrag;
     hipLaunchKernelGGL(write_header_kernel, dim3(1), dim3(64), 0, st, hdr, (uint8_t*)packed);
     TQ_CHECK_LAUNCH();
     return run<true>(L, (uint8_t*)packed, const_cast<uint8_t*>(src->codes), const_cast<uint16_t*>(src->scale),
