@@ -97,12 +97,14 @@ struct TqWorkspace {
     size_t xaug_d;      // bf16 [A_tot][ka_d]
     size_t h;           // bf16 [A_tot][F]  or fp32 [A_tot][F]
     size_t yd;          // fp32 [nsplit][A_tot][H]
+    size_t tpart;       // fp32 partial low-rank intermediates of the decode path (only for small batches)
     size_t total;
     int32_t a_tot, rt_max, nblk, ka_gu, ka_d, nsplit_max;
 };
 
 #define TQ_PERM_CHUNK 256   // assignments handled by one permutation block
 #define TQ_MAX_SPLIT 8      // K-splits of the down projection on the small-tile path
+#define TQ_SKINNY_MAX_ROWS 1024   // assignment rows up to which the decode (16-row tile) path is considered
 
 __host__ __device__ inline int tq_pad64(int v) { return (v + 63) / 64 * 64; }
 // augmented-K length: three bf16 split terms per quantisation group (zero-point correction; groups in blocks
@@ -142,8 +144,15 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
         // the small-tile path may split the down projection's K; the large-tile path never does
         size_t planes = (a_tot <= 4096) ? TQ_MAX_SPLIT : 1;
         W->yd = take(planes * (size_t)a_tot * L.H * 4);
+        W->tpart = off;
+        if (a_tot <= TQ_SKINNY_MAX_ROWS && L.r > 0) {
+            const size_t slices = (size_t)((L.H > L.F ? L.H : L.F) + 511) / 512;
+            const size_t nat = (size_t)(2 * L.r16 + 31) / 32;
+            W->tpart = take((size_t)(a_tot / 16 + L.E + L.S) * slices * nat * 512 * 4);
+        }
     } else {
         W->xaug_gu = W->xaug_d = off;
+        W->tpart = off;
         W->h = take((size_t)a_tot * L.F * 4);
         W->yd = take((size_t)a_tot * L.H * 4);
     }
@@ -181,6 +190,10 @@ tq_status tqi_forward_f32(const TqLayout& L, const TqWorkspace& W, const uint8_t
 tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, const uint8_t* blob,
                            const uint16_t* x, int32_t T, uint16_t* y, uint8_t* ws, hipStream_t stream,
                            const float* topk_w);
+
+bool tqi_skinny_supported(const TqLayout& L);
+tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint8_t* blob, const uint16_t* x,
+                             int32_t T, uint8_t* ws, hipStream_t stream, int* nsplit_out);
 
 // profiling aid: stage-boundary events registered through tq_set_profile_events (nullptr when off)
 void tqi_record_stage(int stage, hipStream_t stream);

@@ -12,62 +12,13 @@
 //     against B converted fp16 -> bf16 on the fly.
 // Activations are staged through LDS (shared by the four waves of a workgroup); the packed codes are
 // already in MFMA fragment order and go straight from global memory to registers.
-#include "tq_common.h"
+#include "tq_device.h"
 
 #include <type_traits>
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-struct MGeom {
-    int32_t ne, H, F, g, r, r16, k, S, a_tot;
-    uint32_t unpack_mask, unpack_magic;   // 0x000F000F, 0x43004300 (see unpack_word)
-    size_t expert_stride;
-};
-
-union Frag {
-    bf16x8 v;
-    uint32_t u[4];
-    u32x4 q;
-};
-
-__device__ inline uint32_t f2bf_bits(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-__device__ inline uint32_t pack_bf2(float a, float b) { return f2bf_bits(a) | (f2bf_bits(b) << 16); }
-__device__ inline float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ inline float bf_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
-
-// 8 codes of one packed word -> bf16 values 128 + q, in contraction order.  mask = 0x000F000F and
-// magic = 0x43004300 arrive as kernel arguments rather than literals: the three-operand and-or encoding
-// takes no literal on this target, and with register operands the compiler selects it (7 VALU
-// instructions per word instead of 11).
-__device__ inline bf16x8 unpack_word(uint32_t w, uint32_t mask, uint32_t magic)
-{
-    Frag f;
-    f.u[0] = (w & mask) | magic;
-    f.u[1] = ((w >> 4) & mask) | magic;
-    f.u[2] = ((w >> 8) & mask) | magic;
-    f.u[3] = ((w >> 12) & mask) | magic;
-    return f.v;
-}
-
-__device__ inline bf16x8 half8_to_bf8(u32x4 q)
-{
-    Frag f;
-    const uint32_t in[4] = {q[0], q[1], q[2], q[3]};
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        f.u[j] = pack_bf2(tq_half_bits_to_float((uint16_t)(in[j] & 0xFFFF)), tq_half_bits_to_float((uint16_t)(in[j] >> 16)));
-    return f.v;
-}
-
-__device__ inline uint32_t word_of(const u32x4& q, int w) { return q[w]; }
+using namespace tqdev;
 
 // ------------------------------------------------------------------------------------------------
 // aug_kernel: per 32-row tile, the augmented activation row
@@ -556,6 +507,21 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     const int rt32 = W.a_tot / 32 + L.E + L.S;     // upper bounds on the number of row tiles
     const int rt128 = W.a_tot / 128 + L.E + L.S;
     const int gs = L.g / 16;
+
+    // decode batches (a handful of rows per expert): the weight-streaming 16-row path, no pre-pass over K
+    bool skinny = !large && avg_rows <= 12 && !(flags & TQ_FLAG_FORCE_SMALL_TILE);
+    if (flags & TQ_FLAG_FORCE_SKINNY) skinny = true;
+    if (skinny && W.a_tot <= TQ_SKINNY_MAX_ROWS && tqi_skinny_supported(L)) {
+        int nsplit_sk = 1;
+        tq_status rs = tqi_forward_skinny(L, W, blob, x, T, ws, stream, &nsplit_sk);
+        if (rs != TQ_OK) return rs;
+        tqi_record_stage(5, stream);
+        hipLaunchKernelGGL(combine_bf16_kernel, dim3(T, (L.H / 4 + 255) / 256), dim3(256), 0, stream, T, L.H, L.k, L.S,
+                           nsplit_sk, (size_t)W.a_tot * L.H, slot_of, topk_w, yd, y);
+        TQ_CHECK_LAUNCH();
+        tqi_record_stage(6, stream);
+        return TQ_OK;
+    }
 
     hipLaunchKernelGGL(aug_kernel<0>, dim3((rt32 + 3) / 4), dim3(256), 0, stream, G, L.gu, blob, x, row_token, tile_e,
                        tile_row0, offsets, ctrl, xaug_gu, W.ka_gu);

@@ -1,0 +1,482 @@
+// Decode path of tq_moe_forward (few rows per expert): the projection is bound by streaming the packed
+// weights from HBM once, so the kernel is built around that stream.
+//
+//   * A row tile holds at most 16 assignment rows of one expert.  Its activations for the whole
+//     contraction range of the workgroup (up to 4096 values per row) are staged in LDS ONCE.
+//   * A workgroup has 8 waves; wave w owns a 512-wide slice of the contraction range and walks over the
+//     workgroup's column-tile pairs, streaming its slice of the packed codes (already in MFMA fragment
+//     order) straight from global memory into registers, one pair ahead.  No barrier in that stream.
+//   * Codes go to v_mfma_f32_32x32x16_bf16 as 128 + q (rows 16..31 of the tile are padding); each
+//     quantisation group's fp32 partial sum is folded as  acc += s * part - s (128 + z) * xsum, with the
+//     group sums of the activations computed once per workgroup by an MFMA against a matrix of ones.
+//   * The 8 partial results of a pair are summed across the waves through LDS in a fixed order (the
+//     "wavefront reduction"), then SwiGLU (stage 0) or the store of the split-K plane (stage 1).
+//   * The low-rank intermediate t = x A is produced per 512-wide slice by skinny_pre_kernel; a workgroup
+//     adds the slices of its own range, so a split contraction needs no global reduction: the partial
+//     t of a split times B lands in that split's output plane, and the planes are summed by the combine.
+#include "tq_device.h"
+
+#include <type_traits>
+
+using namespace tqdev;
+
+namespace {
+
+constexpr int SK_NW = 8;        // waves per workgroup
+constexpr int SK_WAVE_K = 512;  // contraction indices per wave
+constexpr int SK_RED_BYTES = SK_NW * 7 * 2 * 64 * 4;   // per wave: 7 of its 8 row groups, 2 tiles, 64 lanes
+
+__device__ inline int row_of_v(int v, int hf) { return 8 * (v >> 2) + 4 * hf + (v & 3); }
+
+// Partial low-rank intermediate of one 16-row tile over one 512-wide slice of the contraction:
+//   tpart[tile][slice][ta][v][lane] = sum_{kk in slice} x[row(v, lane)][kk] * A[kk][32 ta + lane % 32]   (fp32)
+// One wave per (tile, slice).
+template <int STAGE>
+__global__ void __launch_bounds__(64) skinny_pre_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
+                                                        const uint16_t* __restrict__ xin,
+                                                        const int32_t* __restrict__ row_token,
+                                                        const int32_t* __restrict__ tile_e,
+                                                        const int32_t* __restrict__ tile_row0,
+                                                        const int32_t* __restrict__ offsets,
+                                                        const int32_t* __restrict__ ctrl, float* __restrict__ tpart,
+                                                        int n_slices, int na_tiles)
+{
+    const int tile = blockIdx.x, slice = blockIdx.y, lane = threadIdx.x;
+    if (tile >= ctrl[4]) return;
+    const int e = tile_e[tile], slot0 = tile_row0[tile];
+    const int rows = min(16, offsets[e + 1] - slot0);
+    const int col = lane & 31, hf = lane >> 5;
+    const int K = sec.K, ksteps = K / 16;
+    const int r = min(col & 15, rows - 1);
+    const uint16_t* xrow = STAGE == 0 ? xin + (size_t)row_token[slot0 + r] * K : xin + (size_t)(slot0 + r) * K;
+    const u32x4* af = reinterpret_cast<const u32x4*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.afrag);
+    const int s0 = slice * (SK_WAVE_K / 16);
+    const int s1 = min(ksteps, s0 + SK_WAVE_K / 16);
+    for (int ta0 = 0; ta0 < na_tiles; ta0 += 2) {
+        f32x16 acc[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+        constexpr int UNR = 8;
+        for (int sb = s0; sb < s1; sb += UNR) {      // K is a multiple of 64: whole batches of 4; 8 may overrun
+            Frag xa[UNR];
+            u32x4 aq[UNR][2];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+                if (sb + u < s1) xa[u].q = *reinterpret_cast<const u32x4*>(xrow + 16 * (sb + u) + 8 * hf);
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    if (sb + u < s1 && ta0 + j < na_tiles) aq[u][j] = af[((size_t)(ta0 + j) * ksteps + sb + u) * 64 + lane];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    if (sb + u < s1 && ta0 + j < na_tiles)
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[u].v, half8_to_bf8(aq[u][j]), acc[j], 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            if (ta0 + j < na_tiles) {
+                float* dst = tpart + (((size_t)tile * n_slices + slice) * na_tiles + ta0 + j) * 512 + lane;
+#pragma unroll
+                for (int v = 0; v < 8; ++v) dst[v * 64] = acc[j][v];
+            }
+    }
+}
+
+// STAGE 0: out = h[slot][F] bf16 = silu(gate) * up.   STAGE 1: out = yd[split][slot][H] fp32.
+template <int STAGE, int GS>
+__global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
+                                                         const uint16_t* __restrict__ xin,
+                                                         const int32_t* __restrict__ row_token,
+                                                         const int32_t* __restrict__ tile_e,
+                                                         const int32_t* __restrict__ tile_row0,
+                                                         const int32_t* __restrict__ offsets,
+                                                         const int32_t* __restrict__ ctrl,
+                                                         const float* __restrict__ tpart, int n_slices, int na_tiles,
+                                                         void* __restrict__ out, int pairs_per_wg,
+                                                         int units_per_split, int RB, int red_off, int xs_off)
+{
+    constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
+    constexpr int UC = UNIT_K / 64;
+    constexpr int US = UNIT_K / 16;
+    constexpr int NG = US / GS;
+    constexpr int UPW = SK_WAVE_K / UNIT_K;   // units per wave
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    float* red = reinterpret_cast<float*>(lds + red_off);
+    float* xs = reinterpret_cast<float*>(lds + xs_off);
+    uint16_t* tbuf = reinterpret_cast<uint16_t*>(lds + red_off);   // [16][NA] bf16; lives only before the pair loop
+
+    const int rt = blockIdx.y;
+    if (rt >= ctrl[4]) return;
+    const int e = tile_e[rt], slot0 = tile_row0[rt];
+    const int rows = min(16, offsets[e + 1] - slot0);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int K = sec.K, NU = K / UNIT_K;
+    const int split = blockIdx.z;
+    const int ub = split * units_per_split;
+    const int ue = min(NU, ub + units_per_split);
+    const int range_k = (ue - ub) * UNIT_K;
+    int nuw = min(UPW, ue - (ub + wave * UPW));     // units of this wave (0 for idle waves)
+    if (nuw < 0) nuw = 0;
+    const int wk0 = wave * UPW * US;                // first MFMA step of this wave inside the workgroup's range
+    const int p0 = blockIdx.x * pairs_per_wg;
+    const int p1 = min(sec.pairs, p0 + pairs_per_wg);
+    const int NA = STAGE == 0 ? 2 * G.r16 : G.r16;
+    const int n_lr = (G.r > 0) ? NA / 16 : 0;       // low-rank MFMA steps; step j is applied by wave j
+
+    const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
+    const u32x4* codes = reinterpret_cast<const u32x4*>(rec + sec.codes) + lane;
+    const uint32_t* szp = reinterpret_cast<const uint32_t*>(rec + sec.sz) + col;
+    const u32x4* bfr = reinterpret_cast<const u32x4*>(rec + sec.bfrag) + lane;
+
+    auto load_w = [&](u32x4 (&dst)[2][UC], int pair, int u) {       // unit u of this wave, both tiles
+        const int chunk0 = (ub + wave * UPW + u) * UC;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int c = 0; c < UC; ++c) dst[t][c] = codes[(((size_t)pair * sec.chunks + chunk0 + c) * 2 + t) * 64];
+    };
+    auto load_sz = [&](uint32_t (&dst)[NG][2], int pair, int u) {
+        const int g0 = (ub + wave * UPW + u) * NG;
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) dst[gi][t] = szp[(((size_t)pair * sec.groups + g0 + gi) * 2 + t) * 32];
+    };
+
+    // the first pair's codes are requested before anything else so that their latency hides behind the set-up
+    u32x4 wq[UPW][2][UC];
+    uint32_t szq[UPW][NG][2];
+#pragma unroll
+    for (int u = 0; u < UPW; ++u)
+        if (u < nuw) { load_w(wq[u], p0, u); load_sz(szq[u], p0, u); }
+
+    // ---- 1. activations of the tile for the workgroup's contraction range -> LDS (row stride RB = 2*range + 16 bytes:
+    //         the 16 rows read by one ds_read_b128 fall into 16 different bank groups)
+    {
+        const int gran = range_k / 8;
+        for (int row = 0; row < 16; ++row) {
+            const int r = min(row, rows - 1);
+            const size_t src_row = STAGE == 0 ? (size_t)row_token[slot0 + r] : (size_t)(slot0 + r);
+            const uint16_t* src = xin + src_row * K + (size_t)ub * UNIT_K;
+            for (int kg = tid; kg < gran; kg += 512)
+                *reinterpret_cast<u32x4*>(lds + row * RB + kg * 16) = *reinterpret_cast<const u32x4*>(src + kg * 8);
+        }
+    }
+    __syncthreads();
+    auto lds_x = [&](int kl) -> bf16x8 {       // fragment of MFMA step kl (relative to the workgroup's range)
+        Frag f;
+        f.q = *reinterpret_cast<const u32x4*>(lds + (col & 15) * RB + (kl * 16 + 8 * hf) * 2);
+        return f.v;
+    };
+
+    // ---- 2. group sums of the activations (MFMA against ones: every column of the result holds the row sums)
+    {
+        Frag ones;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ones.u[j] = 0x3F803F80u;
+#pragma unroll
+        for (int u = 0; u < UPW; ++u) {
+            if (u < nuw) {
+#pragma unroll
+                for (int gi = 0; gi < NG; ++gi) {
+                    f32x16 sD;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) sD[v] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < GS; ++ks)
+                        sD = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_x(wk0 + u * US + gi * GS + ks), ones.v, sD, 0, 0, 0);
+                    if (col == 0) {
+                        const int gl = (wave * UPW + u) * NG + gi;      // group index inside the workgroup's range
+#pragma unroll
+                        for (int v = 0; v < 8; ++v) xs[gl * 16 + row_of_v(v, hf)] = sD[v];
+                    }
+                }
+            }
+        }
+    }
+    // ---- 3. low-rank intermediate: add the slices of this range, round to bf16, keep it as MFMA fragments
+    Frag tf;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) tf.u[j] = 0;
+    if (n_lr > 0) {
+        const int sl0 = (ub * UNIT_K) / SK_WAVE_K;
+        const int nsl = (range_k + SK_WAVE_K - 1) / SK_WAVE_K;
+        const int m = row_of_v(wave, hf);          // wave w owns result rows row_of_v(w, hf)
+        for (int ta = 0; ta < na_tiles; ++ta) {
+            float sum = 0.f;
+            for (int sl = 0; sl < nsl; ++sl)
+                sum += tpart[(((size_t)rt * n_slices + sl0 + sl) * na_tiles + ta) * 512 + wave * 64 + lane];
+            const int c = 32 * ta + col;
+            if (c < NA) tbuf[m * NA + c] = (uint16_t)f2bf_bits(sum);
+        }
+        __syncthreads();
+        if (wave < n_lr) tf.q = *reinterpret_cast<const u32x4*>(tbuf + (col & 15) * NA + 16 * wave + 8 * hf);
+    }
+    __syncthreads();     // xs is complete; tbuf has been read: the reduction buffer may be reused
+
+    // ---- 4. the stream over this workgroup's column-tile pairs
+    for (int pair = p0; pair < p1; ++pair) {
+        float acc8[2][8];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int v = 0; v < 8; ++v) acc8[t][v] = 0.f;
+#pragma unroll
+        for (int u = 0; u < UPW; ++u) {
+            if (u < nuw) {
+                u32x4 wc[2][UC];
+                uint32_t szc[NG][2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int c = 0; c < UC; ++c) wc[t][c] = wq[u][t][c];
+#pragma unroll
+                for (int gi = 0; gi < NG; ++gi)
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) szc[gi][t] = szq[u][gi][t];
+                if (pair + 1 < p1) { load_w(wq[u], pair + 1, u); load_sz(szq[u], pair + 1, u); }
+#pragma unroll
+                for (int gi = 0; gi < NG; ++gi) {
+                    f32x16 part[2];
+#pragma unroll
+                    for (int ks = 0; ks < GS; ++ks) {
+                        const int kidx = gi * GS + ks;
+                        const bf16x8 xa = lds_x(wk0 + u * US + kidx);
+#pragma unroll
+                        for (int t = 0; t < 2; ++t) {
+                            const bf16x8 bw = unpack_word(word_of(wc[t][kidx / 4], kidx % 4), G.unpack_mask, G.unpack_magic);
+                            if (ks == 0) {
+                                f32x16 zero;
+#pragma unroll
+                                for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+                                part[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, bw, zero, 0, 0, 0);
+                            } else {
+                                part[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, bw, part[t], 0, 0, 0);
+                            }
+                        }
+                    }
+                    // fold the group: acc += s * part + c * xsum, c = -s (128 + z)
+                    const int gl = (wave * UPW + u) * NG + gi;
+                    const float4 x0 = *reinterpret_cast<const float4*>(xs + gl * 16 + 4 * hf);
+                    const float4 x1 = *reinterpret_cast<const float4*>(xs + gl * 16 + 8 + 4 * hf);
+                    const float xv[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        const float s = tq_half_bits_to_float((uint16_t)(szc[gi][t] & 0xFFFF));
+                        const float z = tq_half_bits_to_float((uint16_t)(szc[gi][t] >> 16));
+                        const float c = -s * (128.0f + z);
+#pragma unroll
+                        for (int v = 0; v < 8; ++v) acc8[t][v] = fmaf(c, xv[v], fmaf(s, part[t][v], acc8[t][v]));
+                    }
+                }
+            }
+        }
+        // low-rank step `wave` (stage 0: steps below r16/16 feed the gate tile, the others the up tile)
+        if (wave < n_lr) {
+            f32x16 zero;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+            const int steps_per_tile = G.r16 / 16;
+            if (STAGE == 0) {
+                const int t = wave >= steps_per_tile ? 1 : 0;
+                const int step = wave - t * steps_per_tile;
+                const bf16x8 bb = half8_to_bf8(bfr[(((size_t)pair * steps_per_tile + step) * 2 + t) * 64]);
+                const f32x16 lr = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf.v, bb, zero, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 8; ++v) {
+                    if (t == 0) acc8[0][v] += lr[v]; else acc8[1][v] += lr[v];
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const bf16x8 bb = half8_to_bf8(bfr[(((size_t)pair * steps_per_tile + wave) * 2 + t) * 64]);
+                    const f32x16 lr = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf.v, bb, zero, 0, 0, 0);
+#pragma unroll
+                    for (int v = 0; v < 8; ++v) acc8[t][v] += lr[v];
+                }
+            }
+        }
+        // ---- wavefront reduction: wave w keeps row group v = w and publishes its other seven
+        {
+            float* mine = red + wave * (7 * 2 * 64);
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int v = 0; v < 8; ++v) {
+                    if (v != wave) {
+                        const int slot = v < wave ? v : v - 1;
+                        mine[(t * 7 + slot) * 64 + lane] = acc8[t][v];
+                    }
+                }
+        }
+        __syncthreads();
+        {
+            float own[2] = {0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int v = 0; v < 8; ++v)
+                    if (v == wave) own[t] = acc8[t][v];
+            float tot[2] = {0.f, 0.f};
+            for (int ww = 0; ww < SK_NW; ++ww) {           // fixed order: run-to-run identical sums
+                if (ww == wave) {
+                    tot[0] += own[0];
+                    tot[1] += own[1];
+                } else {
+                    const int slot = wave < ww ? wave : wave - 1;
+                    const float* src = red + ww * (7 * 2 * 64);
+                    tot[0] += src[(0 * 7 + slot) * 64 + lane];
+                    tot[1] += src[(1 * 7 + slot) * 64 + lane];
+                }
+            }
+            const int m = row_of_v(wave, hf);
+            if (m < rows) {
+                if (STAGE == 0) {
+                    const float hv = tot[0] / (1.0f + __expf(-tot[0])) * tot[1];
+                    reinterpret_cast<uint16_t*>(out)[(size_t)(slot0 + m) * G.F + 32 * pair + col] = (uint16_t)f2bf_bits(hv);
+                } else {
+                    float* yd = reinterpret_cast<float*>(out) + (size_t)split * G.a_tot * G.H + (size_t)(slot0 + m) * G.H + 64 * pair + col;
+                    yd[0] = tot[0];
+                    yd[32] = tot[1];
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <int STAGE, int GS>
+tq_status launch_skinny(const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin,
+                        const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
+                        const int32_t* offsets, const int32_t* ctrl, float* tpart, int n_slices, int na_tiles,
+                        void* out, int row_tiles, int nsplit, int units_per_split, int tiles_est, hipStream_t st)
+{
+    constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
+    const int range_k = units_per_split * UNIT_K;
+    const int RB = range_k * 2 + 16;
+    const int red_off = 16 * RB;
+    const int xs_off = red_off + SK_RED_BYTES;
+    const size_t smem = (size_t)xs_off + (size_t)(range_k / G.g) * 16 * 4;
+    if (smem > 160 * 1024) return TQ_ERR_UNSUPPORTED;
+    auto kern = moe_skinny_kernel<STAGE, GS>;
+    static bool done = false;
+    if (!done) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+            return TQ_ERR_HIP;
+        done = true;
+    }
+    // about two workgroups per CU over the tiles that are expected to exist
+    long total = (long)sec.pairs * tiles_est * nsplit;
+    int ppw = (int)((total + 511) / 512);
+    if (ppw < 1) ppw = 1;
+    if (ppw > sec.pairs) ppw = sec.pairs;
+    dim3 grid((sec.pairs + ppw - 1) / ppw, row_tiles, nsplit);
+    if (grid.y > 65535) return TQ_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl,
+                       (const float*)tpart, n_slices, na_tiles, out, ppw, units_per_split, RB, red_off, xs_off);
+    TQ_CHECK_LAUNCH();
+    return TQ_OK;
+}
+
+template <int STAGE>
+tq_status launch_skinny_gs(int gs, const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin,
+                           const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
+                           const int32_t* offsets, const int32_t* ctrl, float* tpart, int n_slices, int na_tiles,
+                           void* out, int row_tiles, int nsplit, int units_per_split, int tiles_est, hipStream_t st)
+{
+    switch (gs) {
+        case 2: return launch_skinny<STAGE, 2>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, row_tiles, nsplit, units_per_split, tiles_est, st);
+        case 4: return launch_skinny<STAGE, 4>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, row_tiles, nsplit, units_per_split, tiles_est, st);
+        case 8: return launch_skinny<STAGE, 8>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, row_tiles, nsplit, units_per_split, tiles_est, st);
+        case 16: return launch_skinny<STAGE, 16>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, row_tiles, nsplit, units_per_split, tiles_est, st);
+    }
+    return TQ_ERR_UNSUPPORTED;
+}
+
+// contraction split of one stage: nsplit workgroups along K, each a whole number of 512-wide wave slices
+inline void plan_split(int K, int g, int* nsplit, int* units_per_split)
+{
+    const int unit_k = g < 64 ? 64 : g;
+    const int upw = SK_WAVE_K / unit_k;
+    const int nu = K / unit_k;
+    const int max_units = SK_NW * upw;
+    int ns = (nu + max_units - 1) / max_units;
+    int ups = (nu + ns - 1) / ns;
+    ups = (ups + upw - 1) / upw * upw;
+    *nsplit = (nu + ups - 1) / ups;
+    *units_per_split = ups;
+}
+
+}  // namespace
+
+// Whether the decode path can run this layer (LDS budget, one workgroup must span the whole hidden size).
+bool tqi_skinny_supported(const TqLayout& L)
+{
+    if (L.r16 > 64) return false;
+    int ns, ups;
+    plan_split(L.H, L.g, &ns, &ups);
+    if (ns != 1) return false;
+    const int unit_k = L.g < 64 ? 64 : L.g;
+    auto smem = [&](int units) {
+        const int range_k = units * unit_k;
+        return (size_t)16 * (range_k * 2 + 16) + SK_RED_BYTES + (size_t)(range_k / L.g) * 64;
+    };
+    if (smem(ups) > 160 * 1024) return false;
+    plan_split(L.F, L.g, &ns, &ups);
+    if (ns > TQ_MAX_SPLIT || smem(ups) > 160 * 1024) return false;
+    return true;
+}
+
+tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint8_t* blob, const uint16_t* x,
+                             int32_t T, uint8_t* ws, hipStream_t stream, int* nsplit_out)
+{
+    MGeom G;
+    G.ne = L.E + L.S; G.H = L.H; G.F = L.F; G.g = L.g; G.r = L.r; G.r16 = L.r16; G.k = L.k; G.S = L.S;
+    G.a_tot = W.a_tot; G.expert_stride = L.expert_stride;
+    G.unpack_mask = 0x000F000Fu; G.unpack_magic = 0x43004300u;
+    const int32_t* ctrl = reinterpret_cast<const int32_t*>(ws + W.ctrl);
+    const int32_t* offsets = reinterpret_cast<const int32_t*>(ws + W.offsets);
+    const int32_t* row_token = reinterpret_cast<const int32_t*>(ws + W.row_token);
+    const int32_t* tile_e = reinterpret_cast<const int32_t*>(ws + W.tile_e) + 2 * (size_t)W.rt_max;      // 16-row tiling
+    const int32_t* tile_row0 = reinterpret_cast<const int32_t*>(ws + W.tile_row0) + 2 * (size_t)W.rt_max;
+    uint16_t* h = reinterpret_cast<uint16_t*>(ws + W.h);
+    float* yd = reinterpret_cast<float*>(ws + W.yd);
+    float* tpart = reinterpret_cast<float*>(ws + W.tpart);
+    const int gs = L.g / 16;
+    const int rt16 = W.a_tot / 16 + L.E + L.S;
+    const int ne = L.E + L.S;
+    const int tiles_est = W.a_tot < ne ? W.a_tot : (ne > rt16 ? rt16 : ne);
+
+    int ns, ups;
+    plan_split(L.H, L.g, &ns, &ups);
+    const int sl_gu = (L.H + SK_WAVE_K - 1) / SK_WAVE_K, sl_d = (L.F + SK_WAVE_K - 1) / SK_WAVE_K;
+    const int nat_gu = L.r > 0 ? L.gu.na_tiles : 0, nat_d = L.r > 0 ? L.d.na_tiles : 0;
+    if (L.r > 0) {
+        hipLaunchKernelGGL(skinny_pre_kernel<0>, dim3(rt16, sl_gu), dim3(64), 0, stream, G, L.gu, blob, x, row_token, tile_e,
+                           tile_row0, offsets, ctrl, tpart, sl_gu, nat_gu);
+        TQ_CHECK_LAUNCH();
+    }
+    tqi_record_stage(2, stream);
+    tq_status rc = launch_skinny_gs<0>(gs, G, L.gu, blob, x, row_token, tile_e, tile_row0, offsets, ctrl, tpart, sl_gu, nat_gu,
+                                       h, rt16, 1, ups, tiles_est, stream);
+    if (rc != TQ_OK) return rc;
+    tqi_record_stage(3, stream);
+    if (L.r > 0) {
+        hipLaunchKernelGGL(skinny_pre_kernel<1>, dim3(rt16, sl_d), dim3(64), 0, stream, G, L.d, blob, h, row_token, tile_e,
+                           tile_row0, offsets, ctrl, tpart, sl_d, nat_d);
+        TQ_CHECK_LAUNCH();
+    }
+    tqi_record_stage(4, stream);
+    plan_split(L.F, L.g, &ns, &ups);
+    rc = launch_skinny_gs<1>(gs, G, L.d, blob, h, row_token, tile_e, tile_row0, offsets, ctrl, tpart, sl_d, nat_d, yd, rt16,
+                             ns, ups, tiles_est, stream);
+    if (rc != TQ_OK) return rc;
+    *nsplit_out = ns;
+    return TQ_OK;
+}

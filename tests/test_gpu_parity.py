@@ -193,16 +193,16 @@ def test_forward_fp32_config1():
     assert rel_err(got, ref) <= TOL_FP32
 
 
-@pytest.mark.parametrize("flags", [tq.TQ_FLAG_FORCE_SMALL_TILE, tq.TQ_FLAG_FORCE_LARGE_TILE, 0],
-                         ids=["tile32", "tile128", "auto"])
+@pytest.mark.parametrize("flags", [tq.TQ_FLAG_FORCE_SMALL_TILE, tq.TQ_FLAG_FORCE_LARGE_TILE, tq.TQ_FLAG_FORCE_SKINNY, 0],
+                         ids=["tile32", "tile128", "tile16", "auto"])
 @pytest.mark.parametrize("name", list(SMALL))
 def test_forward_bf16_small_layers(name, flags):
     got, ref = run_forward(SMALL[name], tq.TQ_ACT_BF16, flags)
     assert rel_err(got, ref) <= TOL_BF16
 
 
-@pytest.mark.parametrize("flags", [tq.TQ_FLAG_FORCE_SMALL_TILE, tq.TQ_FLAG_FORCE_LARGE_TILE],
-                         ids=["tile32", "tile128"])
+@pytest.mark.parametrize("flags", [tq.TQ_FLAG_FORCE_SMALL_TILE, tq.TQ_FLAG_FORCE_LARGE_TILE, tq.TQ_FLAG_FORCE_SKINNY],
+                         ids=["tile32", "tile128", "tile16"])
 def test_forward_bf16_config1(flags):
     got, ref = run_forward(CONFIGS[1], tq.TQ_ACT_BF16, flags)
     err = rel_err(got, ref)
@@ -210,8 +210,10 @@ def test_forward_bf16_config1(flags):
     assert err <= TOL_BF16
 
 
-def test_forward_bf16_is_run_to_run_deterministic():
+@pytest.mark.parametrize("flags", [tq.TQ_FLAG_FORCE_SMALL_TILE, tq.TQ_FLAG_FORCE_LARGE_TILE, tq.TQ_FLAG_FORCE_SKINNY],
+                         ids=["tile32", "tile128", "tile16"])
+def test_forward_bf16_is_run_to_run_deterministic(flags):
     cfg = SMALL["ragged"]
-    a, _ = run_forward(cfg, tq.TQ_ACT_BF16, tq.TQ_FLAG_FORCE_SMALL_TILE)
-    b, _ = run_forward(cfg, tq.TQ_ACT_BF16, tq.TQ_FLAG_FORCE_SMALL_TILE)
+    a, _ = run_forward(cfg, tq.TQ_ACT_BF16, flags)
+    b, _ = run_forward(cfg, tq.TQ_ACT_BF16, flags)
     assert np.array_equal(a, b)
