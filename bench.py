@@ -85,6 +85,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="launch every step eagerly instead of replaying a captured HIP graph")
+    ap.add_argument("--stream-probe", action="store_true",
+                    help="instead of the workload: time a plain 1 GiB streaming copy and read (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the path is a single-GPU kernel library; "
@@ -99,6 +103,27 @@ def main():
     cfg = CONFIGS[args.workload]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.stream_probe:
+        nbytes = 1 << 30
+        bufs = [torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(3)]
+        dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        stream = torch.cuda.current_stream().cuda_stream
+        ev = HipEvents(2)
+        res = {}
+        for mode, name in ((0, "copy"), (1, "read")):
+            for i in range(3):
+                tq.tq_debug_stream(bufs[i % 3], dst, nbytes, mode)
+            torch.cuda.synchronize()
+            ev.record(0, stream)
+            for i in range(args.steps):
+                tq.tq_debug_stream(bufs[i % 3], dst, nbytes, mode)
+            ev.record(1, stream)
+            torch.cuda.synchronize()
+            us = ev.elapsed_ms(0, 1) / args.steps * 1e3
+            moved = nbytes * (2 if mode == 0 else 1)
+            res[name] = {"us": round(us, 1), "GB/s": round(moved / us / 1e3, 1)}
+        print(json.dumps({"stream_probe": res, "bytes": nbytes}), flush=True)
+        return
     t0 = time.time()
     layer = make_layer(cfg, workers=min(16, os.cpu_count() or 8))
     x = make_x(cfg)
@@ -131,16 +156,41 @@ def main():
         tq.tq_route(logits_d, bias_d, cfg.k, idx_d, w_d)
         tq.tq_moe_forward(desc, packed[i % n_copies], x_d, idx_d, w_d, y=y_d, workspace=ws)
 
-    for i in range(args.warmup):
+    for i in range(max(args.warmup, n_copies)):
         step(i)
     torch.cuda.synchronize()
+    y_eager = y_d.clone()
     ev = HipEvents(2 + 7)
+    use_graph = not args.no_graph
+    if use_graph:
+        # the step is a short chain of kernels: replaying a captured HIP graph (one per weight copy) removes the
+        # launch gaps between them.  The library records no memset nodes; every replay is checked below.
+        graphs = []
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for c in range(n_copies):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    step(c)
+                graphs.append(g)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        for i in range(args.warmup):
+            graphs[i % n_copies].replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y_d.view(torch.int16), y_eager.view(torch.int16)), "graph replay differs from eager"
+        run = lambda i: graphs[i % n_copies].replay()
+    else:
+        run = step
+    stream = torch.cuda.current_stream().cuda_stream
     ev.record(0, stream)
     t_host = time.perf_counter()
     for i in range(args.steps):
-        step(i)
+        run(i)
     ev.record(1, stream)
     torch.cuda.synchronize()
+    assert torch.equal(y_d.view(torch.int16), y_eager.view(torch.int16)), "timed run differs from the eager result"
     wall_ms = (time.perf_counter() - t_host) * 1e3
     ms_total = ev.elapsed_ms(0, 1)
     ms_per_step = ms_total / args.steps
@@ -208,7 +258,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16", "data": "synthetic", "launch": "hip_graph" if use_graph else "eager",
         "config": {"workload": f"config {cfg.cfg_id}: {cfg.name}", "experts": cfg.E, "shared": cfg.S, "top_k": cfg.k,
                    "hidden": cfg.H, "ffn": cfg.F, "tokens": cfg.T, "group": cfg.g, "rank": cfg.r, "bits": cfg.bits,
                    "touched_experts": work["touched"]},

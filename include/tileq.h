@@ -174,6 +174,12 @@ tq_status tq_moe_forward(const tq_layer_desc *desc, const void *packed, const vo
 #define TQ_N_STAGE_EVENTS 7
 tq_status tq_set_profile_events(void *const *events, int32_t n);
 
+/* Measurement aid (not part of the method): streams `bytes` (a multiple of 16) from src with 16-byte
+ * accesses.  mode 0 copies them to dst (dst holds `bytes`); mode 1 only reads them (dst needs 16 bytes and
+ * is practically never written).  Used to calibrate hardware byte counters against a transfer of known
+ * size and to measure the streaming rate the memory system attains. */
+tq_status tq_debug_stream(const void *src, void *dst, size_t bytes, int32_t mode, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ STATUS_NAMES = {0: "TQ_OK", 1: "TQ_ERR_NULL", 2: "TQ_ERR_SHAPE", 3: "TQ_ERR_ALIG
 
 EXPORTS = ["tq_status_str", "tq_packed_size", "tq_pack_weights", "tq_unpack_weights", "tq_route",
            "tq_permute_workspace_size", "tq_permute", "tq_moe_workspace_size", "tq_moe_forward",
-           "tq_set_profile_events"]
+           "tq_set_profile_events", "tq_debug_stream"]
 
 
 class TqError(RuntimeError):
@@ -75,6 +75,8 @@ def lib():
         L.tq_moe_forward.argtypes = [ctypes.POINTER(LayerDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_size_t, ctypes.c_void_p]
+        L.tq_debug_stream.restype = ctypes.c_int
+        L.tq_debug_stream.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_void_p]
         L.tq_set_profile_events.restype = ctypes.c_int
         L.tq_set_profile_events.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32]
         _lib = L
@@ -172,3 +174,8 @@ def tq_set_profile_events(events) -> None:
     n = len(events)
     arr = (ctypes.c_void_p * max(n, 1))(*events)
     _check(lib().tq_set_profile_events(arr, n), "tq_set_profile_events")
+
+
+def tq_debug_stream(src, dst, nbytes: int, mode: int) -> None:
+    """Streaming copy (mode 0) or read (mode 1) of nbytes with 16-byte accesses: a measurement aid."""
+    _check(lib().tq_debug_stream(_ptr(src), _ptr(dst), nbytes, mode, _stream()), "tq_debug_stream")

@@ -146,7 +146,7 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
         W->yd = take(planes * (size_t)a_tot * L.H * 4);
         W->tpart = off;
         if (a_tot <= TQ_SKINNY_MAX_ROWS && L.r > 0) {
-            const size_t slices = (size_t)((L.H > L.F ? L.H : L.F) + 511) / 512;
+            const size_t slices = (size_t)((L.H > L.F ? L.H : L.F) + 255) / 256;
             const size_t nat = (size_t)(2 * L.r16 + 31) / 32;
             W->tpart = take((size_t)(a_tot / 16 + L.E + L.S) * slices * nat * 512 * 4);
         }

@@ -28,9 +28,11 @@ constexpr int SK_RED_BYTES = SK_NW * 7 * 2 * 64 * 4;   // per wave: 7 of its 8 r
 
 __device__ inline int row_of_v(int v, int hf) { return 8 * (v >> 2) + 4 * hf + (v & 3); }
 
-// Partial low-rank intermediate of one 16-row tile over one 512-wide slice of the contraction:
+// Partial low-rank intermediate of one 16-row tile over one 256-wide slice of the contraction:
 //   tpart[tile][slice][ta][v][lane] = sum_{kk in slice} x[row(v, lane)][kk] * A[kk][32 ta + lane % 32]   (fp32)
-// One wave per (tile, slice).
+// One wave per (tile, slice, ta); all of its loads are in flight at once.
+constexpr int SK_PRE_K = 256;
+
 template <int STAGE>
 __global__ void __launch_bounds__(64) skinny_pre_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
                                                         const uint16_t* __restrict__ xin,
@@ -41,7 +43,7 @@ __global__ void __launch_bounds__(64) skinny_pre_kernel(MGeom G, TqSection sec, 
                                                         const int32_t* __restrict__ ctrl, float* __restrict__ tpart,
                                                         int n_slices, int na_tiles)
 {
-    const int tile = blockIdx.x, slice = blockIdx.y, lane = threadIdx.x;
+    const int tile = blockIdx.x, slice = blockIdx.y, ta = blockIdx.z, lane = threadIdx.x;
     if (tile >= ctrl[4]) return;
     const int e = tile_e[tile], slot0 = tile_row0[tile];
     const int rows = min(16, offsets[e + 1] - slot0);
@@ -50,41 +52,26 @@ __global__ void __launch_bounds__(64) skinny_pre_kernel(MGeom G, TqSection sec, 
     const int r = min(col & 15, rows - 1);
     const uint16_t* xrow = STAGE == 0 ? xin + (size_t)row_token[slot0 + r] * K : xin + (size_t)(slot0 + r) * K;
     const u32x4* af = reinterpret_cast<const u32x4*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.afrag);
-    const int s0 = slice * (SK_WAVE_K / 16);
-    const int s1 = min(ksteps, s0 + SK_WAVE_K / 16);
-    for (int ta0 = 0; ta0 < na_tiles; ta0 += 2) {
-        f32x16 acc[2];
+    constexpr int NS = SK_PRE_K / 16;
+    const int s0 = slice * NS;
+    const int n = min(NS, ksteps - s0);
+    Frag xa[NS];
+    u32x4 aq[NS];
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
-        constexpr int UNR = 8;
-        for (int sb = s0; sb < s1; sb += UNR) {      // K is a multiple of 64: whole batches of 4; 8 may overrun
-            Frag xa[UNR];
-            u32x4 aq[UNR][2];
-#pragma unroll
-            for (int u = 0; u < UNR; ++u)
-                if (sb + u < s1) xa[u].q = *reinterpret_cast<const u32x4*>(xrow + 16 * (sb + u) + 8 * hf);
-#pragma unroll
-            for (int u = 0; u < UNR; ++u)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    if (sb + u < s1 && ta0 + j < na_tiles) aq[u][j] = af[((size_t)(ta0 + j) * ksteps + sb + u) * 64 + lane];
-#pragma unroll
-            for (int u = 0; u < UNR; ++u)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    if (sb + u < s1 && ta0 + j < na_tiles)
-                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[u].v, half8_to_bf8(aq[u][j]), acc[j], 0, 0, 0);
+    for (int u = 0; u < NS; ++u)
+        if (u < n) {
+            xa[u].q = *reinterpret_cast<const u32x4*>(xrow + 16 * (s0 + u) + 8 * hf);
+            aq[u] = af[((size_t)ta * ksteps + s0 + u) * 64 + lane];
         }
+    f32x16 acc;
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-            if (ta0 + j < na_tiles) {
-                float* dst = tpart + (((size_t)tile * n_slices + slice) * na_tiles + ta0 + j) * 512 + lane;
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
 #pragma unroll
-                for (int v = 0; v < 8; ++v) dst[v * 64] = acc[j][v];
-            }
-    }
+    for (int u = 0; u < NS; ++u)
+        if (u < n) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[u].v, half8_to_bf8(aq[u]), acc, 0, 0, 0);
+    float* dst = tpart + (((size_t)tile * n_slices + slice) * na_tiles + ta) * 512 + lane;
+#pragma unroll
+    for (int v = 0; v < 8; ++v) dst[v * 64] = acc[v];
 }
 
 // STAGE 0: out = h[slot][F] bf16 = silu(gate) * up.   STAGE 1: out = yd[split][slot][H] fp32.
@@ -149,6 +136,10 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
             for (int t = 0; t < 2; ++t) dst[gi][t] = szp[(((size_t)pair * sec.groups + g0 + gi) * 2 + t) * 32];
     };
 
+    // the or-operand of the unpack in a vector register (see unpack_word): opaque move, not folded to a literal
+    uint32_t magic_v;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(magic_v) : "s"(G.unpack_magic));
+
     // the first pair's codes are requested before anything else so that their latency hides behind the set-up
     u32x4 wq[UPW][2][UC];
     uint32_t szq[UPW][NG][2];
@@ -205,8 +196,8 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
 #pragma unroll
     for (int j = 0; j < 4; ++j) tf.u[j] = 0;
     if (n_lr > 0) {
-        const int sl0 = (ub * UNIT_K) / SK_WAVE_K;
-        const int nsl = (range_k + SK_WAVE_K - 1) / SK_WAVE_K;
+        const int sl0 = (ub * UNIT_K) / SK_PRE_K;
+        const int nsl = (range_k + SK_PRE_K - 1) / SK_PRE_K;
         const int m = row_of_v(wave, hf);          // wave w owns result rows row_of_v(w, hf)
         for (int ta = 0; ta < na_tiles; ++ta) {
             float sum = 0.f;
@@ -241,16 +232,19 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
 #pragma unroll
                     for (int t = 0; t < 2; ++t) szc[gi][t] = szq[u][gi][t];
                 if (pair + 1 < p1) { load_w(wq[u], pair + 1, u); load_sz(szq[u], pair + 1, u); }
+                bf16x8 xq[2];
+                xq[0] = lds_x(wk0 + u * US);
 #pragma unroll
                 for (int gi = 0; gi < NG; ++gi) {
                     f32x16 part[2];
 #pragma unroll
                     for (int ks = 0; ks < GS; ++ks) {
                         const int kidx = gi * GS + ks;
-                        const bf16x8 xa = lds_x(wk0 + u * US + kidx);
+                        if (kidx + 1 < US) xq[(kidx + 1) & 1] = lds_x(wk0 + u * US + kidx + 1);   // next step's fragment
+                        const bf16x8 xa = xq[kidx & 1];
 #pragma unroll
                         for (int t = 0; t < 2; ++t) {
-                            const bf16x8 bw = unpack_word(word_of(wc[t][kidx / 4], kidx % 4), G.unpack_mask, G.unpack_magic);
+                            const bf16x8 bw = unpack_word(word_of(wc[t][kidx / 4], kidx % 4), G.unpack_mask, magic_v);
                             if (ks == 0) {
                                 f32x16 zero;
 #pragma unroll
@@ -371,9 +365,18 @@ tq_status launch_skinny(const MGeom& G, const TqSection& sec, const uint8_t* blo
             return TQ_ERR_HIP;
         done = true;
     }
-    // about two workgroups per CU over the tiles that are expected to exist
+    // one workgroup per compute unit over the tiles that are expected to exist: a workgroup fills a CU (LDS),
+    // and fewer, longer workgroups amortise the set-up (activation staging, group sums) over more pairs
+    static int target = 0;
+    if (!target) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+            cus = 256;
+        target = cus;
+    }
     long total = (long)sec.pairs * tiles_est * nsplit;
-    int ppw = (int)((total + 511) / 512);
+    int ppw = (int)((total + target - 1) / target);
     if (ppw < 1) ppw = 1;
     if (ppw > sec.pairs) ppw = sec.pairs;
     dim3 grid((sec.pairs + ppw - 1) / ppw, row_tiles, nsplit);
@@ -455,10 +458,10 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
 
     int ns, ups;
     plan_split(L.H, L.g, &ns, &ups);
-    const int sl_gu = (L.H + SK_WAVE_K - 1) / SK_WAVE_K, sl_d = (L.F + SK_WAVE_K - 1) / SK_WAVE_K;
+    const int sl_gu = (L.H + SK_PRE_K - 1) / SK_PRE_K, sl_d = (L.F + SK_PRE_K - 1) / SK_PRE_K;
     const int nat_gu = L.r > 0 ? L.gu.na_tiles : 0, nat_d = L.r > 0 ? L.d.na_tiles : 0;
     if (L.r > 0) {
-        hipLaunchKernelGGL(skinny_pre_kernel<0>, dim3(rt16, sl_gu), dim3(64), 0, stream, G, L.gu, blob, x, row_token, tile_e,
+        hipLaunchKernelGGL(skinny_pre_kernel<0>, dim3(rt16, sl_gu, nat_gu), dim3(64), 0, stream, G, L.gu, blob, x, row_token, tile_e,
                            tile_row0, offsets, ctrl, tpart, sl_gu, nat_gu);
         TQ_CHECK_LAUNCH();
     }
@@ -468,7 +471,7 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     if (rc != TQ_OK) return rc;
     tqi_record_stage(3, stream);
     if (L.r > 0) {
-        hipLaunchKernelGGL(skinny_pre_kernel<1>, dim3(rt16, sl_d), dim3(64), 0, stream, G, L.d, blob, h, row_token, tile_e,
+        hipLaunchKernelGGL(skinny_pre_kernel<1>, dim3(rt16, sl_d, nat_d), dim3(64), 0, stream, G, L.d, blob, h, row_token, tile_e,
                            tile_row0, offsets, ctrl, tpart, sl_d, nat_d);
         TQ_CHECK_LAUNCH();
     }
