@@ -21,6 +21,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK = 8.0e12          # B/s, MI355X published
 MFMA_BF16_PEAK = 2.5e15    # FLOP/s dense bf16, MI355X published
+# HBM bytes per launch of the dominant kernel from the rocprofv3 FETCH_SIZE + WRITE_SIZE passes (scaled by the
+# streaming-copy calibration), see profiles/hbm_traffic_config2_skinny_kernels.txt.  Only the decode workload
+# has been counted; other workloads report null.
+MEASURED_TRAFFIC_BYTES = {2: 519.3e6 + 1.0e6}
 STAGES = ["permute", "aug_gate_up", "gate_up", "aug_down", "down", "combine"]
 
 
@@ -217,13 +221,15 @@ def main():
     t_gu = stage_us["gate_up"] * 1e-6
     if hbm_bound:
         ach = work["gate_up_bytes"] / t_gu / 1e9
-        roofline = dict(bound="hbm", kernel="moe_mfma_kernel (gate/up stage)", achieved=round(ach, 1), peak=HBM_PEAK / 1e9,
-                        unit="GB/s", frac=round(ach / (HBM_PEAK / 1e9), 4), traffic=None,
+        roofline = dict(bound="hbm", kernel="gate/up stage (moe_skinny_kernel<0> on decode batches)",
+                        achieved=round(ach, 1), peak=HBM_PEAK / 1e9,
+                        unit="GB/s", frac=round(ach / (HBM_PEAK / 1e9), 4),
+                        traffic=MEASURED_TRAFFIC_BYTES.get(cfg.cfg_id), algorithmic_bytes=work["gate_up_bytes"],
                         path_achieved=round(work["path_bytes"] / (ms_per_step * 1e-3) / 1e9, 1),
                         path_frac=round(work["path_bytes"] / (ms_per_step * 1e-3) / HBM_PEAK, 4))
     else:
         ach = work["gate_up_flops"] / t_gu / 1e12
-        roofline = dict(bound="mfma", kernel="moe_mfma_kernel (gate/up stage)", achieved=round(ach, 1),
+        roofline = dict(bound="mfma", kernel="gate/up stage (moe_mfma_kernel<.,.,0,.>)", achieved=round(ach, 1),
                         peak=MFMA_BF16_PEAK / 1e12, unit="TFLOP/s", frac=round(ach / (MFMA_BF16_PEAK / 1e12), 4),
                         traffic=None,
                         path_achieved=round(work["path_flops"] / (ms_per_step * 1e-3) / 1e12, 1),
