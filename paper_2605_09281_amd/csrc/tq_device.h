@@ -57,4 +57,22 @@ __device__ inline bf16x8 half8_to_bf8(u32x4 q)
 
 __device__ inline uint32_t word_of(const u32x4& q, int w) { return q[w]; }
 
+// silu(g) * u with the hardware exp2 and reciprocal (about 1 ulp each; the result is rounded to bf16 anyway):
+// a plain division expands to a ten-instruction sequence per element
+__device__ inline float silu_mul(float g, float u)
+{
+    const float e = __builtin_amdgcn_exp2f(g * -1.4426950408889634f);
+    return g * __builtin_amdgcn_rcpf(1.0f + e) * u;
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding global
+// load (one counter covers loads and stores on this target), which would drain the register prefetch of the
+// packed codes at every barrier.  All cross-thread traffic of the kernels that use this goes through LDS.
+__device__ inline void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 }  // namespace tqdev

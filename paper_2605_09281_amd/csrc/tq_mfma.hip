@@ -177,7 +177,7 @@ __global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection s
         tokx[tid] = STAGE == 0 ? row_token[slot0 + r] : slot0 + r;
         toka[tid] = slot0 + r;
     }
-    __syncthreads();
+    lds_barrier();
 
     const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
     const u32x4* codes = reinterpret_cast<const u32x4*>(rec + sec.codes) + (size_t)pair * sec.chunks * 128 + lane;
@@ -243,11 +243,15 @@ __global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection s
     uint32_t szq[2][NG][2];
 
     // ---- prologue ---------------------------------------------------------------------------------
+    // Prefetches are issued unconditionally with clamped indices (a repeated, unused load at the tail): a load
+    // under a condition makes the compiler wait for ALL outstanding loads at every later use, which would
+    // drain the prefetch queue once per unit.
+    const int ulast = u1 - 1;
     load_step(0);
-    if (active && nmain > 0) { load_w(wq[0], u0); load_sz(szq[0], u0); }
-    if (active && nmain > 1) { load_w(wq[1], u0 + 1); load_sz(szq[1], u0 + 1); }
+    load_w(wq[0], min(u0, ulast)); load_sz(szq[0], min(u0, ulast));
+    load_w(wq[1], min(u0 + 1, ulast)); load_sz(szq[1], min(u0 + 1, ulast));
     store_step(0);
-    __syncthreads();
+    lds_barrier();
 
     auto lds_frag = [&](int buf, int mt, int kstep) -> bf16x8 {
         Frag f;
@@ -258,7 +262,7 @@ __global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection s
     // ---- main units ---------------------------------------------------------------------------------
     auto main_unit = [&](int st, auto slot_tag) {
         constexpr int SLOT = decltype(slot_tag)::value;
-        if (st + 1 < nsteps) load_step(st + 1);
+        load_step(min(st + 1, nsteps - 1));
         u32x4 wc[2][UC];
         uint32_t szc[NG][2];
 #pragma unroll
@@ -269,7 +273,7 @@ __global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection s
         for (int gi = 0; gi < NG; ++gi)
 #pragma unroll
             for (int t = 0; t < 2; ++t) szc[gi][t] = szq[SLOT][gi][t];
-        if (active && st + 2 < nmain) { load_w(wq[SLOT], u0 + st + 2); load_sz(szq[SLOT], u0 + st + 2); }
+        load_w(wq[SLOT], min(u0 + st + 2, ulast)); load_sz(szq[SLOT], min(u0 + st + 2, ulast));
         const int buf = st & 1;
         if (active) {
             bf16x8 xa[2][MT];
@@ -314,8 +318,8 @@ __global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection s
                 }
             }
         }
-        if (st + 1 < nsteps) store_step(st + 1);
-        __syncthreads();
+        store_step(st + 1);      // at the very last step this refills the idle buffer with the same step: harmless
+        lds_barrier();
     };
 
     int st = 0;
@@ -329,7 +333,7 @@ __global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection s
     const int ZT = tq_zero_terms(K, G.g);
     const int groups = sec.groups;
     for (; st < nsteps; ++st) {
-        if (st + 1 < nsteps) load_step(st + 1);
+        load_step(min(st + 1, nsteps - 1));
         const int a = st - nmain, buf = st & 1;
         if (active) {
 #pragma unroll
@@ -366,8 +370,8 @@ __global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection s
                 }
             }
         }
-        if (st + 1 < nsteps) store_step(st + 1);
-        __syncthreads();
+        store_step(st + 1);
+        lds_barrier();
     }
 
     // ---- epilogue -----------------------------------------------------------------------------------
@@ -381,7 +385,7 @@ __global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection s
                 const int m = 32 * (MT * wm + mt) + 8 * (v / 4) + 4 * hf + (v % 4);
                 if (m < rows) {
                     const float gte = acc[mt][0][v], up = acc[mt][1][v];
-                    const float hv = gte / (1.0f + __expf(-gte)) * up;
+                    const float hv = silu_mul(gte, up);
                     h[(size_t)(slot0 + m) * G.F + 32 * pair + col] = (uint16_t)f2bf_bits(hv);
                 }
             }

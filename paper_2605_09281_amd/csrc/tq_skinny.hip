@@ -121,15 +121,18 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     const uint32_t* szp = reinterpret_cast<const uint32_t*>(rec + sec.sz) + col;
     const u32x4* bfr = reinterpret_cast<const u32x4*>(rec + sec.bfrag) + lane;
 
+    // Unit and pair indices are clamped into the valid range instead of guarding the loads: a load under a
+    // condition makes the compiler wait for ALL outstanding loads at every later use, which would drain the
+    // one-pair-ahead prefetch at every unit.  Clamped loads repeat a neighbour's line (cache hit) and are unused.
     auto load_w = [&](u32x4 (&dst)[2][UC], int pair, int u) {       // unit u of this wave, both tiles
-        const int chunk0 = (ub + wave * UPW + u) * UC;
+        const int chunk0 = min(ub + wave * UPW + u, ue - 1) * UC;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int c = 0; c < UC; ++c) dst[t][c] = codes[(((size_t)pair * sec.chunks + chunk0 + c) * 2 + t) * 64];
     };
     auto load_sz = [&](uint32_t (&dst)[NG][2], int pair, int u) {
-        const int g0 = (ub + wave * UPW + u) * NG;
+        const int g0 = min(ub + wave * UPW + u, ue - 1) * NG;
 #pragma unroll
         for (int gi = 0; gi < NG; ++gi)
 #pragma unroll
@@ -144,8 +147,25 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     u32x4 wq[UPW][2][UC];
     uint32_t szq[UPW][NG][2];
 #pragma unroll
-    for (int u = 0; u < UPW; ++u)
-        if (u < nuw) { load_w(wq[u], p0, u); load_sz(szq[u], p0, u); }
+    for (int u = 0; u < UPW; ++u) { load_w(wq[u], p0, u); load_sz(szq[u], p0, u); }
+    // low-rank B fragments ride in the same prefetch (one pair ahead); waves without a low-rank step, and layers
+    // without factors, read a valid dummy location
+    const int steps_per_tile = G.r16 / 16;
+    const int lr_t = (STAGE == 0 && wave >= steps_per_tile) ? 1 : 0;
+    const int lr_step = (G.r > 0) ? min(wave - lr_t * steps_per_tile, steps_per_tile - 1) : 0;
+    const u32x4* bsrc = (G.r > 0) ? bfr : codes;
+    const size_t bstride = (G.r > 0) ? (size_t)steps_per_tile * 128 : (size_t)sec.chunks * 128;
+    auto load_b = [&](u32x4 (&dst)[2], int pair) {
+        if (STAGE == 0) {
+            dst[0] = bsrc[(size_t)pair * bstride + ((size_t)lr_step * 2 + lr_t) * 64];
+            dst[1] = dst[0];
+        } else {
+            dst[0] = bsrc[(size_t)pair * bstride + ((size_t)lr_step * 2 + 0) * 64];
+            dst[1] = bsrc[(size_t)pair * bstride + ((size_t)lr_step * 2 + 1) * 64];
+        }
+    };
+    u32x4 bq[2];
+    load_b(bq, p0);
 
     // ---- 1. activations of the tile for the workgroup's contraction range -> LDS (row stride RB = 2*range + 16 bytes:
     //         the 16 rows read by one ds_read_b128 fall into 16 different bank groups)
@@ -159,7 +179,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
                 *reinterpret_cast<u32x4*>(lds + row * RB + kg * 16) = *reinterpret_cast<const u32x4*>(src + kg * 8);
         }
     }
-    __syncthreads();
+    lds_barrier();
     auto lds_x = [&](int kl) -> bf16x8 {       // fragment of MFMA step kl (relative to the workgroup's range)
         Frag f;
         f.q = *reinterpret_cast<const u32x4*>(lds + (col & 15) * RB + (kl * 16 + 8 * hf) * 2);
@@ -206,13 +226,14 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
             const int c = 32 * ta + col;
             if (c < NA) tbuf[m * NA + c] = (uint16_t)f2bf_bits(sum);
         }
-        __syncthreads();
+        lds_barrier();
         if (wave < n_lr) tf.q = *reinterpret_cast<const u32x4*>(tbuf + (col & 15) * NA + 16 * wave + 8 * hf);
     }
-    __syncthreads();     // xs is complete; tbuf has been read: the reduction buffer may be reused
+    lds_barrier();     // xs is complete; tbuf has been read: the reduction buffer may be reused
 
     // ---- 4. the stream over this workgroup's column-tile pairs
     for (int pair = p0; pair < p1; ++pair) {
+        const int pnext = min(pair + 1, p1 - 1);
         float acc8[2][8];
 #pragma unroll
         for (int t = 0; t < 2; ++t)
@@ -220,18 +241,19 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
             for (int v = 0; v < 8; ++v) acc8[t][v] = 0.f;
 #pragma unroll
         for (int u = 0; u < UPW; ++u) {
+            u32x4 wc[2][UC];
+            uint32_t szc[NG][2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int c = 0; c < UC; ++c) wc[t][c] = wq[u][t][c];
+#pragma unroll
+            for (int gi = 0; gi < NG; ++gi)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) szc[gi][t] = szq[u][gi][t];
+            load_w(wq[u], pnext, u);
+            load_sz(szq[u], pnext, u);
             if (u < nuw) {
-                u32x4 wc[2][UC];
-                uint32_t szc[NG][2];
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int c = 0; c < UC; ++c) wc[t][c] = wq[u][t][c];
-#pragma unroll
-                for (int gi = 0; gi < NG; ++gi)
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) szc[gi][t] = szq[u][gi][t];
-                if (pair + 1 < p1) { load_w(wq[u], pair + 1, u); load_sz(szq[u], pair + 1, u); }
                 bf16x8 xq[2];
                 xq[0] = lds_x(wk0 + u * US);
 #pragma unroll
@@ -272,27 +294,26 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
             }
         }
         // low-rank step `wave` (stage 0: steps below r16/16 feed the gate tile, the others the up tile)
-        if (wave < n_lr) {
-            f32x16 zero;
+        {
+            u32x4 bc[2] = {bq[0], bq[1]};
+            load_b(bq, pnext);
+            if (wave < n_lr) {
+                f32x16 zero;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) zero[v] = 0.f;
-            const int steps_per_tile = G.r16 / 16;
-            if (STAGE == 0) {
-                const int t = wave >= steps_per_tile ? 1 : 0;
-                const int step = wave - t * steps_per_tile;
-                const bf16x8 bb = half8_to_bf8(bfr[(((size_t)pair * steps_per_tile + step) * 2 + t) * 64]);
-                const f32x16 lr = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf.v, bb, zero, 0, 0, 0);
+                for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+                if (STAGE == 0) {
+                    const f32x16 lr = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf.v, half8_to_bf8(bc[0]), zero, 0, 0, 0);
 #pragma unroll
-                for (int v = 0; v < 8; ++v) {
-                    if (t == 0) acc8[0][v] += lr[v]; else acc8[1][v] += lr[v];
-                }
-            } else {
+                    for (int v = 0; v < 8; ++v) {
+                        if (lr_t == 0) acc8[0][v] += lr[v]; else acc8[1][v] += lr[v];
+                    }
+                } else {
 #pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const bf16x8 bb = half8_to_bf8(bfr[(((size_t)pair * steps_per_tile + wave) * 2 + t) * 64]);
-                    const f32x16 lr = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf.v, bb, zero, 0, 0, 0);
+                    for (int t = 0; t < 2; ++t) {
+                        const f32x16 lr = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf.v, half8_to_bf8(bc[t]), zero, 0, 0, 0);
 #pragma unroll
-                    for (int v = 0; v < 8; ++v) acc8[t][v] += lr[v];
+                        for (int v = 0; v < 8; ++v) acc8[t][v] += lr[v];
+                    }
                 }
             }
         }
@@ -309,7 +330,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
                     }
                 }
         }
-        __syncthreads();
+        lds_barrier();
         {
             float own[2] = {0.f, 0.f};
 #pragma unroll
@@ -332,7 +353,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
             const int m = row_of_v(wave, hf);
             if (m < rows) {
                 if (STAGE == 0) {
-                    const float hv = tot[0] / (1.0f + __expf(-tot[0])) * tot[1];
+                    const float hv = silu_mul(tot[0], tot[1]);
                     reinterpret_cast<uint16_t*>(out)[(size_t)(slot0 + m) * G.F + 32 * pair + col] = (uint16_t)f2bf_bits(hv);
                 } else {
                     float* yd = reinterpret_cast<float*>(out) + (size_t)split * G.a_tot * G.H + (size_t)(slot0 + m) * G.H + 64 * pair + col;
@@ -341,7 +362,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
                 }
             }
         }
-        __syncthreads();
+        lds_barrier();
     }
 }
 
