@@ -85,13 +85,13 @@ __host__ __device__ inline int tq_nibble_pos(int i) { return (i >> 1) + 4 * (i &
 // ------------------------------------------------------------------------------------------------
 // Workspace of tq_moe_forward.  All offsets are multiples of 256 bytes.
 struct TqWorkspace {
-    size_t ctrl;        // int32[64]: [0] error flag, [1] row tiles (32-row), [2] (128-row), [3] rows, [4] (16-row)
+    size_t ctrl;        // int32[64]: [0] error flag, [1] row tiles (32-row), [2] (128-row), [3] rows, [4] (16-row), [5] (64-row)
     size_t offsets;     // int32 [E+S+1]
     size_t slot_of;     // int32 [T*(k+S)]
     size_t row_token;   // int32 [A_tot]
     size_t row_w;       // float [A_tot]
-    size_t tile_e;      // int32 [3][RT]  expert of each row tile, for the 32-, 128- and 16-row tilings
-    size_t tile_row0;   // int32 [3][RT]  first slot of each row tile
+    size_t tile_e;      // int32 [4][RT]  expert of each row tile, for the 32-, 128-, 16- and 64-row tilings
+    size_t tile_row0;   // int32 [4][RT]  first slot of each row tile
     size_t hist;        // int32 [nblk][E] permutation scratch
     size_t xaug_gu;     // bf16 [A_tot][ka_gu]   (bf16 path)
     size_t xaug_d;      // bf16 [A_tot][ka_d]
@@ -102,6 +102,7 @@ struct TqWorkspace {
     int32_t a_tot, rt_max, nblk, ka_gu, ka_d, nsplit_max;
 };
 
+#define TQ_N_TILINGS 4      // row tilings with a tile table: 32, 128, 16, 64 rows (in this order)
 #define TQ_PERM_CHUNK 256   // assignments handled by one permutation block
 #define TQ_MAX_SPLIT 8      // K-splits of the down projection on the small-tile path
 #define TQ_SKINNY_MAX_ROWS 1024   // assignment rows up to which the decode (16-row tile) path is considered
@@ -134,8 +135,8 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
     W->slot_of = take((size_t)a_tot * 4);
     W->row_token = take((size_t)a_tot * 4);
     W->row_w = take((size_t)a_tot * 4);
-    W->tile_e = take((size_t)3 * W->rt_max * 4);
-    W->tile_row0 = take((size_t)3 * W->rt_max * 4);
+    W->tile_e = take((size_t)TQ_N_TILINGS * W->rt_max * 4);
+    W->tile_row0 = take((size_t)TQ_N_TILINGS * W->rt_max * 4);
     W->hist = take((size_t)W->nblk * L.E * 4);
     if (act_dtype == TQ_ACT_BF16) {
         W->xaug_gu = take((size_t)a_tot * W->ka_gu * 2);

@@ -14,7 +14,16 @@
 // already in MFMA fragment order and go straight from global memory to registers.
 #include "tq_device.h"
 
+#include <cstdlib>
 #include <type_traits>
+
+#ifdef TQ_TIMING
+__device__ unsigned long long g_timing[8 * 8192];
+extern "C" int tq_debug_read_timing(void* dst, size_t bytes) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_timing), bytes); }
+#define TQ_T(i) do { if (STAGE == 0 && MT == 2 && tid == 0 && wg < 8192) g_timing[wg * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define TQ_T(i) do { } while (0)
+#endif
 
 namespace {
 
@@ -127,7 +136,7 @@ __global__ void __launch_bounds__(256) aug_kernel(MGeom G, TqSection sec, const 
 //   STAGE 1: out = yd[split][slot][H] fp32, split = blockIdx.z covering a slice of K
 // GS = quantisation group in MFMA steps (g/16).  A "unit" is max(g, 64) contraction indices.
 template <int MT, int WM, int STAGE, int GS>
-__global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
+__global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mfma_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
                                                        const uint16_t* __restrict__ xin,
                                                        const uint16_t* __restrict__ xaug,
                                                        const int32_t* __restrict__ row_token,
@@ -162,10 +171,12 @@ __global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection s
     const int grp = wg / (8 * nb_count), rem = wg - grp * (8 * nb_count);
     const int nb = rem >> 3;
     const int rt = grp * 8 + (rem & 7);
+    const int tid = threadIdx.x;
+    TQ_T(0);
     if (rt >= ctrl[ctrl_idx]) return;
     const int e = tile_e[rt], slot0 = tile_row0[rt];
     const int rows = min(BM, offsets[e + 1] - slot0);
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wn = wave & 3, wm = wave >> 2;
     const int pair_raw = nb * 4 + wn;
     const bool active = pair_raw < sec.pairs;
@@ -192,13 +203,15 @@ __global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection s
     const int nsteps = nmain + naug;
 
     u32x4 xr[NP];
-    // ---- staging helpers: step st < nmain is main unit u0 + st, later steps are units of the augmented rows ----
+    // ---- staging helpers: steps 0..naug-1 are units of the augmented rows (zero-point and low-rank terms; they go
+    //      first so that the latency of their operands overlaps with the start-up of the main stream), the
+    //      remaining steps are the main units u0, u0+1, ...
     auto load_step = [&](int st) {
-        const bool is_main = st < nmain;
+        const bool is_main = st >= naug;
         const uint16_t* base = is_main ? xin : xaug;
         const int32_t* tok = is_main ? tokx : toka;
         const size_t stride = is_main ? (size_t)K : (size_t)ka;
-        const size_t koff = (size_t)(is_main ? u0 + st : st - nmain) * UNIT_K;
+        const size_t koff = (size_t)(is_main ? u0 + st - naug : st) * UNIT_K;
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             int row = p * RPP + tid / TPR, seg = tid % TPR;
@@ -252,6 +265,7 @@ __global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection s
     load_w(wq[1], min(u0 + 1, ulast)); load_sz(szq[1], min(u0 + 1, ulast));
     store_step(0);
     lds_barrier();
+    TQ_T(1);
 
     auto lds_frag = [&](int buf, int mt, int kstep) -> bf16x8 {
         Frag f;
@@ -260,8 +274,9 @@ __global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection s
     };
 
     // ---- main units ---------------------------------------------------------------------------------
-    auto main_unit = [&](int st, auto slot_tag) {
+    auto main_unit = [&](int mu, auto slot_tag) {      // mu: index of the main unit inside this split
         constexpr int SLOT = decltype(slot_tag)::value;
+        const int st = naug + mu;
         load_step(min(st + 1, nsteps - 1));
         u32x4 wc[2][UC];
         uint32_t szc[NG][2];
@@ -273,7 +288,7 @@ __global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection s
         for (int gi = 0; gi < NG; ++gi)
 #pragma unroll
             for (int t = 0; t < 2; ++t) szc[gi][t] = szq[SLOT][gi][t];
-        load_w(wq[SLOT], min(u0 + st + 2, ulast)); load_sz(szq[SLOT], min(u0 + st + 2, ulast));
+        load_w(wq[SLOT], min(u0 + mu + 2, ulast)); load_sz(szq[SLOT], min(u0 + mu + 2, ulast));
         const int buf = st & 1;
         if (active) {
             bf16x8 xa[2][MT];
@@ -322,51 +337,52 @@ __global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection s
         lds_barrier();
     };
 
-    int st = 0;
-    for (; st + 1 < nmain; st += 2) {
-        main_unit(st, std::integral_constant<int, 0>{});
-        main_unit(st + 1, std::integral_constant<int, 1>{});
-    }
-    if (st < nmain) { main_unit(st, std::integral_constant<int, 0>{}); ++st; }
-
-    // ---- augmented steps: zero-point correction and the low-rank term ------------------------------
+    // ---- augmented units: zero-point correction and the low-rank term ----------------------------------
+    // All weight-side fragments of a unit are requested before its first MFMA: one exposed latency per unit
+    // instead of one per step (and the first one coincides with the start-up of the main stream).
     const int ZT = tq_zero_terms(K, G.g);
-    const int groups = sec.groups;
-    for (; st < nsteps; ++st) {
+    for (int st = 0; st < naug; ++st) {
         load_step(min(st + 1, nsteps - 1));
-        const int a = st - nmain, buf = st & 1;
+        const int buf = st & 1;
         if (active) {
+            u32x4 fq[US][2];
+            int kind[US];          // 0 skip, 1 zero-point step (both tiles), 2 low-rank tile 0, 3 low-rank tile 1, 4 both tiles
 #pragma unroll
             for (int w = 0; w < US; ++w) {
-                const int k0 = UNIT_K * a + 16 * w;
-                bf16x8 bw[2];
-                bool use[2] = {false, false};
+                const int k0 = UNIT_K * st + 16 * w;
+                kind[w] = 0;
                 if (k0 < ZT) {
                     const int step = k0 / 16;
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        Frag f;
-                        f.q = zcp[((size_t)step * 2 + t) * 64];
-                        bw[t] = f.v;
-                        use[t] = true;
-                    }
+                    fq[w][0] = zcp[((size_t)step * 2 + 0) * 64];
+                    fq[w][1] = zcp[((size_t)step * 2 + 1) * 64];
+                    kind[w] = 1;
                 } else if (G.r > 0 && k0 < ZT + G.r16) {
                     const int step = (k0 - ZT) / 16;
-                    bw[0] = half8_to_bf8(bfr[((size_t)step * 2 + 0) * 64]);
-                    use[0] = true;
-                    if (STAGE == 1) { bw[1] = half8_to_bf8(bfr[((size_t)step * 2 + 1) * 64]); use[1] = true; }
+                    fq[w][0] = bfr[((size_t)step * 2 + 0) * 64];
+                    if (STAGE == 1) { fq[w][1] = bfr[((size_t)step * 2 + 1) * 64]; kind[w] = 4; } else kind[w] = 2;
                 } else if (STAGE == 0 && G.r > 0 && k0 < ZT + 2 * G.r16) {
                     const int step = (k0 - ZT - G.r16) / 16;
-                    bw[1] = half8_to_bf8(bfr[((size_t)step * 2 + 1) * 64]);
-                    use[1] = true;
+                    fq[w][1] = bfr[((size_t)step * 2 + 1) * 64];
+                    kind[w] = 3;
                 }
-                if (use[0] || use[1]) {
+            }
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        bf16x8 xa = lds_frag(buf, mt, w);
-                        if (use[0]) acc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, bw[0], acc[mt][0], 0, 0, 0);
-                        if (use[1]) acc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, bw[1], acc[mt][1], 0, 0, 0);
-                    }
+            for (int w = 0; w < US; ++w) {
+                if (kind[w] == 0) continue;
+                bf16x8 bw[2];
+                if (kind[w] == 1) {
+                    Frag f0, f1;
+                    f0.q = fq[w][0]; f1.q = fq[w][1];
+                    bw[0] = f0.v; bw[1] = f1.v;
+                } else {
+                    if (kind[w] != 3) bw[0] = half8_to_bf8(fq[w][0]);
+                    if (kind[w] != 2) bw[1] = half8_to_bf8(fq[w][1]);
+                }
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    bf16x8 xa = lds_frag(buf, mt, w);
+                    if (kind[w] != 3) acc[mt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, bw[0], acc[mt][0], 0, 0, 0);
+                    if (kind[w] != 2) acc[mt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, bw[1], acc[mt][1], 0, 0, 0);
                 }
             }
         }
@@ -374,34 +390,52 @@ __global__ void __launch_bounds__(256 * WM) moe_mfma_kernel(MGeom G, TqSection s
         lds_barrier();
     }
 
-    // ---- epilogue -----------------------------------------------------------------------------------
+    TQ_T(2);
+    int mu = 0;
+    for (; mu + 1 < nmain; mu += 2) {
+        main_unit(mu, std::integral_constant<int, 0>{});
+        main_unit(mu + 1, std::integral_constant<int, 1>{});
+    }
+    if (mu < nmain) main_unit(mu, std::integral_constant<int, 0>{});
+
+    // ---- epilogue (full tiles take a path without per-row tests) ----------------------------------------
+    TQ_T(3);
     if (!active) return;
+    const bool full = rows == BM;
     if (STAGE == 0) {
-        uint16_t* h = reinterpret_cast<uint16_t*>(out);
+        uint16_t* h = reinterpret_cast<uint16_t*>(out) + (size_t)slot0 * G.F + 32 * pair + col;
+        auto emit = [&](auto full_tag) {
+            constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = 32 * (MT * wm + mt) + 8 * (v / 4) + 4 * hf + (v % 4);
-                if (m < rows) {
-                    const float gte = acc[mt][0][v], up = acc[mt][1][v];
-                    const float hv = silu_mul(gte, up);
-                    h[(size_t)(slot0 + m) * G.F + 32 * pair + col] = (uint16_t)f2bf_bits(hv);
+                for (int v = 0; v < 16; ++v) {
+                    const int m = 32 * (MT * wm + mt) + 8 * (v / 4) + 4 * hf + (v % 4);
+                    if (FULL || m < rows)
+                        h[(size_t)m * G.F] = (uint16_t)f2bf_bits(silu_mul(acc[mt][0][v], acc[mt][1][v]));
                 }
-            }
+        };
+        if (full) emit(std::true_type{}); else emit(std::false_type{});
+        TQ_T(4);
+#ifdef TQ_TIMING
+        if (tid == 0 && wg < 8192) { g_timing[wg * 8 + 5] = rows; g_timing[wg * 8 + 6] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11)); }
+#endif
     } else {
-        float* yd = reinterpret_cast<float*>(out) + (size_t)split * G.a_tot * G.H;
+        float* yd = reinterpret_cast<float*>(out) + (size_t)split * G.a_tot * G.H + (size_t)slot0 * G.H + 64 * pair + col;
+        auto emit = [&](auto full_tag) {
+            constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = 32 * (MT * wm + mt) + 8 * (v / 4) + 4 * hf + (v % 4);
-                if (m < rows) {
-#pragma unroll
-                    for (int t = 0; t < 2; ++t)
-                        yd[(size_t)(slot0 + m) * G.H + 64 * pair + 32 * t + col] = acc[mt][t][v];
+                for (int v = 0; v < 16; ++v) {
+                    const int m = 32 * (MT * wm + mt) + 8 * (v / 4) + 4 * hf + (v % 4);
+                    if (FULL || m < rows) {
+                        yd[(size_t)m * G.H] = acc[mt][0][v];
+                        yd[(size_t)m * G.H + 32] = acc[mt][1][v];
+                    }
                 }
-            }
+        };
+        if (full) emit(std::true_type{}); else emit(std::false_type{});
     }
 }
 
@@ -510,6 +544,7 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     if (flags & TQ_FLAG_FORCE_LARGE_TILE) large = true;
     const int rt32 = W.a_tot / 32 + L.E + L.S;     // upper bounds on the number of row tiles
     const int rt128 = W.a_tot / 128 + L.E + L.S;
+    const int rt64 = W.a_tot / 64 + L.E + L.S;
     const int gs = L.g / 16;
 
     // decode batches (a handful of rows per expert): the weight-streaming 16-row path, no pre-pass over K
@@ -537,6 +572,11 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     if (large && gs == 16)
         rc = launch_main<4, 1, 0, 16>(G, L.gu, blob, x, xaug_gu, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max,
                                       offsets, ctrl, 2, h, W.ka_gu, 1, rt128, stream);
+    else if (large && !getenv("TQ_TILE128"))
+        // 64-row tiles, four waves of 64x64: two such workgroups share a CU and run out of phase, so one's
+        // per-unit tail (fold, staging store, barrier) overlaps the other's MFMAs
+        rc = launch_main_gs<2, 1, 0>(gs, G, L.gu, blob, x, xaug_gu, row_token, tile_e + 3 * (size_t)W.rt_max,
+                                     tile_row0 + 3 * (size_t)W.rt_max, offsets, ctrl, 5, h, W.ka_gu, 1, rt64, stream);
     else if (large)
         rc = launch_main_gs<2, 2, 0>(gs, G, L.gu, blob, x, xaug_gu, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max, offsets,
                                   ctrl, 2, h, W.ka_gu, 1, rt128, stream);
@@ -562,6 +602,9 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     if (large && gs == 16)
         rc = launch_main<4, 1, 1, 16>(G, L.d, blob, h, xaug_d, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max,
                                       offsets, ctrl, 2, yd, W.ka_d, 1, rt128, stream);
+    else if (large && !getenv("TQ_TILE128"))
+        rc = launch_main_gs<2, 1, 1>(gs, G, L.d, blob, h, xaug_d, row_token, tile_e + 3 * (size_t)W.rt_max,
+                                     tile_row0 + 3 * (size_t)W.rt_max, offsets, ctrl, 5, yd, W.ka_d, 1, rt64, stream);
     else if (large)
         rc = launch_main_gs<2, 2, 1>(gs, G, L.d, blob, h, xaug_d, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max, offsets,
                                   ctrl, 2, yd, W.ka_d, 1, rt128, stream);

@@ -67,10 +67,10 @@ __global__ void __launch_bounds__(256) route_kernel(const float* __restrict__ lo
 //   scatter_kernel: stable placement, chunk by chunk, 64 assignments per round in order
 // permute_small_kernel does all of it in one wavefront when there is a single chunk (decode batches).
 //
-// Row-tile tables: for each tiling (32, 128, 16 rows) the list of (expert, first slot) of every tile,
-// expert-major; their lengths go to ctrl[1], ctrl[2], ctrl[4]; ctrl[3] = number of rows in total.
-__device__ inline int tile_rows_of(int which) { return which == 0 ? 32 : which == 1 ? 128 : 16; }
-__device__ inline int tile_ctrl_of(int which) { return which == 0 ? 1 : which == 1 ? 2 : 4; }
+// Row-tile tables: for each tiling (32, 128, 16, 64 rows) the list of (expert, first slot) of every tile,
+// expert-major; their lengths go to ctrl[1], ctrl[2], ctrl[4], ctrl[5]; ctrl[3] = number of rows in total.
+__device__ inline int tile_rows_of(int which) { return which == 0 ? 32 : which == 1 ? 128 : which == 2 ? 16 : 64; }
+__device__ inline int tile_ctrl_of(int which) { return which == 0 ? 1 : which == 1 ? 2 : which == 2 ? 4 : 5; }
 
 __device__ inline int wave_incl_scan(int v, int lane)
 {
@@ -132,13 +132,13 @@ __global__ void __launch_bounds__(64) hist_kernel(const int32_t* __restrict__ id
     }
 }
 
-// writes the three row-tile tables from offs[0..ne] (LDS); `sm_base` is LDS scratch of 3*(ne+1) ints
+// writes the row-tile tables from offs[0..ne] (LDS); `sm_base` is LDS scratch of TQ_N_TILINGS*(ne+1) ints
 __device__ inline void build_tile_tables(const int32_t* offs, int32_t* sm_base, int ne, int32_t* tile_e,
                                          int32_t* tile_row0, int rt_max, int32_t* ctrl, int tid, int nthreads)
 {
     // per tiling: tiles of expert e = ceil(count/bm); scan by wavefront `which` (or by wave 0 in turn)
     const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
-    for (int which = wave; which < 3; which += nwaves) {
+    for (int which = wave; which < TQ_N_TILINGS; which += nwaves) {
         const int bm = tile_rows_of(which);
         int32_t* base = sm_base + which * (ne + 1);
         int carry = 0;
@@ -152,7 +152,7 @@ __device__ inline void build_tile_tables(const int32_t* offs, int32_t* sm_base, 
         if (lane == 0) { base[ne] = carry; ctrl[tile_ctrl_of(which)] = carry < rt_max ? carry : rt_max; }
     }
     __syncthreads();
-    for (int i = tid; i < 3 * ne; i += nthreads) {
+    for (int i = tid; i < TQ_N_TILINGS * ne; i += nthreads) {
         const int which = i / ne, e = i - which * ne;
         const int bm = tile_rows_of(which);
         int n = sm_base[which * (ne + 1) + e];
@@ -340,7 +340,7 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
     }
     const int ne = E + S;
     if (nblk == 1 && (int64_t)S * T <= 4096) {
-        const size_t sm = ((size_t)ne + (ne + 1) + E + 3 * (ne + 1)) * 4;
+        const size_t sm = ((size_t)ne + (ne + 1) + E + TQ_N_TILINGS * (ne + 1)) * 4;
         hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(64), sm, stream, topk_idx, topk_w, (int)n_assign, E, S,
                            T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e, tile_row0, rt_max,
                            ctrl, err_flag, (const TqBlobHeader*)blob, expect, check);
@@ -354,7 +354,7 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
     hipLaunchKernelGGL(hist_kernel, dim3(nblk), dim3(64), (size_t)E * 4, stream, topk_idx, n_assign, E, hist,
                        err_flag, (const TqBlobHeader*)blob, expect, check);
     TQ_CHECK_LAUNCH();
-    const size_t sm_scan = ((size_t)ne + (ne + 1) + 3 * (ne + 1)) * 4;
+    const size_t sm_scan = ((size_t)ne + (ne + 1) + TQ_N_TILINGS * (ne + 1)) * 4;
     hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), sm_scan, stream, hist, nblk, E, S, T, offsets, tile_e,
                        tile_row0, rt_max, ctrl);
     TQ_CHECK_LAUNCH();
