@@ -43,8 +43,11 @@ __global__ void __launch_bounds__(256) aug_kernel(MGeom G, TqSection sec, const 
                                                   const int32_t* __restrict__ ctrl, uint16_t* __restrict__ xaug,
                                                   int ka)
 {
+    // One workgroup per 32-row tile; its four waves split the contraction at unit (= group) boundaries so
+    // that enough loads are in flight, and their partial t tiles are summed through LDS.
+    __shared__ float red[4][16][64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int tile = blockIdx.x * 4 + wave;
+    const int tile = blockIdx.x;
     if (tile >= ctrl[1]) return;
     const int e = tile_e[tile], slot0 = tile_row0[tile];
     const int rows = min(32, offsets[e + 1] - slot0);
@@ -58,6 +61,9 @@ __global__ void __launch_bounds__(256) aug_kernel(MGeom G, TqSection sec, const 
     const u32x4* af = reinterpret_cast<const u32x4*>(rec + sec.afrag);
     uint16_t* orow = xaug + (size_t)(slot0 + col) * ka;
     const bool writer = (hf == 0) && (col < rows);
+    const int unit_steps = (G.g < 64 ? 64 : G.g) / 16;
+    const int NU = ksteps / unit_steps;
+    const int sb = (wave * NU / 4) * unit_steps, se = ((wave + 1) * NU / 4) * unit_steps;
 
     const int na_tiles = (G.r > 0) ? sec.na_tiles : 0;
     for (int ta0 = 0; ta0 == 0 || ta0 < na_tiles; ta0 += 4) {
@@ -67,8 +73,8 @@ __global__ void __launch_bounds__(256) aug_kernel(MGeom G, TqSection sec, const 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
         float gsum = 0.f;
-        constexpr int UNR = 4;   // steps whose loads are issued together (K is a multiple of 64)
-        for (int s0 = 0; s0 < ksteps; s0 += UNR) {
+        constexpr int UNR = 4;   // steps whose loads are issued together (a unit is a multiple of 4 steps)
+        for (int s0 = sb; s0 < se; s0 += UNR) {
             Frag xa[UNR];
             u32x4 aq[UNR][4];
 #pragma unroll
@@ -106,20 +112,24 @@ __global__ void __launch_bounds__(256) aug_kernel(MGeom G, TqSection sec, const 
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            if (ta0 + j < na_tiles) {
-                const int c = 32 * (ta0 + j) + col;
-                if (c < NA) {
+            if (ta0 + j < na_tiles) {      // uniform over the workgroup
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        int m2 = 8 * (v / 4) + 4 * hf + (v % 4);
-                        if (m2 < rows) xaug[(size_t)(slot0 + m2) * ka + ZT + c] = (uint16_t)f2bf_bits(acc[j][v]);
-                    }
+                for (int v = 0; v < 16; ++v) red[wave][v][lane] = acc[j][v];
+                __syncthreads();
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int v = 4 * q + wave;
+                    const float sum = (red[0][v][lane] + red[1][v][lane]) + (red[2][v][lane] + red[3][v][lane]);
+                    const int c = 32 * (ta0 + j) + col;
+                    const int m2 = 8 * (v / 4) + 4 * hf + (v % 4);
+                    if (c < NA && m2 < rows) xaug[(size_t)(slot0 + m2) * ka + ZT + c] = (uint16_t)f2bf_bits(sum);
                 }
+                __syncthreads();
             }
         }
     }
     // the padding must be finite (it meets zero weights in the MFMA): write zeros
-    if (writer) {
+    if (writer && wave == 0) {
         for (int gi = groups; gi < 16 * ((groups + 15) / 16); ++gi) {
             uint16_t* zb = orow + 48 * (gi >> 4) + (gi & 15);
             zb[0] = 0; zb[16] = 0; zb[32] = 0;
@@ -562,7 +572,7 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
         return TQ_OK;
     }
 
-    hipLaunchKernelGGL(aug_kernel<0>, dim3((rt32 + 3) / 4), dim3(256), 0, stream, G, L.gu, blob, x, row_token, tile_e,
+    hipLaunchKernelGGL(aug_kernel<0>, dim3(rt32), dim3(256), 0, stream, G, L.gu, blob, x, row_token, tile_e,
                        tile_row0, offsets, ctrl, xaug_gu, W.ka_gu);
     TQ_CHECK_LAUNCH();
     tqi_record_stage(2, stream);
@@ -585,7 +595,7 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
                                   rt32, stream);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(3, stream);
-    hipLaunchKernelGGL(aug_kernel<1>, dim3((rt32 + 3) / 4), dim3(256), 0, stream, G, L.d, blob, h, row_token, tile_e,
+    hipLaunchKernelGGL(aug_kernel<1>, dim3(rt32), dim3(256), 0, stream, G, L.d, blob, h, row_token, tile_e,
                        tile_row0, offsets, ctrl, xaug_d, W.ka_d);
     TQ_CHECK_LAUNCH();
     tqi_record_stage(4, stream);

@@ -152,41 +152,55 @@ __device__ inline void build_tile_tables(const int32_t* offs, int32_t* sm_base, 
         if (lane == 0) { base[ne] = carry; ctrl[tile_ctrl_of(which)] = carry < rt_max ? carry : rt_max; }
     }
     __syncthreads();
-    for (int i = tid; i < TQ_N_TILINGS * ne; i += nthreads) {
-        const int which = i / ne, e = i - which * ne;
+    // one entry per thread: the expert of tile n is found by bisection over the per-expert first tiles
+    for (int which = 0; which < TQ_N_TILINGS; ++which) {
         const int bm = tile_rows_of(which);
-        int n = sm_base[which * (ne + 1) + e];
-        const int o = offs[e], c = offs[e + 1] - o;
+        const int32_t* base = sm_base + which * (ne + 1);
+        const int total = base[ne] < rt_max ? base[ne] : rt_max;
         int32_t* te = tile_e + (size_t)which * rt_max;
         int32_t* tr = tile_row0 + (size_t)which * rt_max;
-        for (int r0 = 0; r0 < c && n < rt_max; r0 += bm, ++n) { te[n] = e; tr[n] = o + r0; }
+        for (int n = tid; n < total; n += nthreads) {
+            int lo = 0, hi = ne - 1;          // largest e with base[e] <= n (experts without rows share a base)
+            while (lo < hi) {
+                int mid = (lo + hi + 1) >> 1;
+                if (base[mid] <= n) lo = mid; else hi = mid - 1;
+            }
+            te[n] = lo;
+            tr[n] = offs[lo] + (n - base[lo]) * bm;
+        }
     }
 }
 
-// Single block of 1024 threads.  hist[b][e] becomes the number of assignments of expert e in chunks before b.
-__global__ void __launch_bounds__(1024) scan_kernel(int32_t* __restrict__ hist, int nblk, int E, int S, int T,
-                                                    int32_t* __restrict__ offsets, int32_t* __restrict__ tile_e,
-                                                    int32_t* __restrict__ tile_row0, int rt_max,
-                                                    int32_t* __restrict__ ctrl)
+// One wavefront per routed expert: hist[b][e] becomes the number of assignments of expert e in chunks
+// before b, and counts[e] their total.
+__global__ void __launch_bounds__(64) chunk_scan_kernel(int32_t* __restrict__ hist, int nblk, int E,
+                                                        int32_t* __restrict__ counts)
 {
-    extern __shared__ int32_t sm[];   // counts[ne] | offs[ne+1] | tile scratch 3*(ne+1)
+    const int e = blockIdx.x, lane = threadIdx.x;
+    int run = 0;
+    for (int b0 = 0; b0 < nblk; b0 += 64) {
+        int b = b0 + lane;
+        int v = b < nblk ? hist[(size_t)b * E + e] : 0;
+        int inc = wave_incl_scan(v, lane);
+        if (b < nblk) hist[(size_t)b * E + e] = run + inc - v;
+        run += __shfl(inc, 63);
+    }
+    if (lane == 0) counts[e] = run;
+}
+
+// Single block of 1024 threads: expert offsets from the counts (left in offsets[1..E] by chunk_scan_kernel)
+// and the row-tile tables.
+__global__ void __launch_bounds__(1024) scan_kernel(int E, int S, int T, int32_t* __restrict__ offsets,
+                                                    int32_t* __restrict__ tile_e, int32_t* __restrict__ tile_row0,
+                                                    int rt_max, int32_t* __restrict__ ctrl)
+{
+    extern __shared__ int32_t sm[];   // counts[ne] | offs[ne+1] | tile scratch TQ_N_TILINGS*(ne+1)
     const int ne = E + S;
     int32_t* counts = sm;
     int32_t* offs = sm + ne;
     int32_t* tsm = offs + ne + 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int e = wave; e < E; e += 16) {
-        int run = 0;
-        for (int b0 = 0; b0 < nblk; b0 += 64) {
-            int b = b0 + lane;
-            int v = b < nblk ? hist[(size_t)b * E + e] : 0;
-            int inc = wave_incl_scan(v, lane);
-            if (b < nblk) hist[(size_t)b * E + e] = run + inc - v;
-            run += __shfl(inc, 63);
-        }
-        if (lane == 0) counts[e] = run;
-    }
-    for (int s = tid; s < S; s += 1024) counts[E + s] = T;
+    for (int e = tid; e < ne; e += 1024) counts[e] = e < E ? offsets[e + 1] : T;
     __syncthreads();
     if (wave == 0) {
         int total = wave_excl_scan(counts, offs, ne, lane, [](int v) { return v; });
@@ -212,21 +226,17 @@ __device__ inline void scatter_chunk(const int32_t* __restrict__ idx, const floa
             if (e < 0 || e >= E) e = -1;
         }
         // rank of this lane among the lanes of the round that hold the same expert and come before it
-        int slot = -1;
-        uint64_t todo = __ballot(e >= 0);
-        while (todo) {
-            int leader = __ffsll((unsigned long long)todo) - 1;
-            int le = __shfl(e, leader);
-            uint64_t same = __ballot(e == le);
-            if (e == le) {
-                uint64_t before = same & ((1ull << lane) - 1ull);
-                slot = cursor[le] + __popcll(before);
-            }
-            __syncthreads();
-            if (lane == leader) cursor[le] += __popcll(same);
-            __syncthreads();
-            todo &= ~same;
+        int before = 0, after = 0;
+#pragma unroll 8
+        for (int j = 0; j < 64; ++j) {
+            const int ej = __shfl(e, j);
+            before += (ej == e) & (j < lane);
+            after += (ej == e) & (j > lane);
         }
+        const int slot = e >= 0 ? cursor[e] + before : -1;
+        __syncthreads();
+        if (e >= 0 && after == 0) cursor[e] = slot + 1;   // the last lane of each expert moves its cursor
+        __syncthreads();
         if (a < n_assign) {
             int t = (int)(a / k), j = (int)(a % k);
             if (slot_of) slot_of[(size_t)t * slot_stride + j] = slot;
@@ -355,8 +365,10 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
                        err_flag, (const TqBlobHeader*)blob, expect, check);
     TQ_CHECK_LAUNCH();
     const size_t sm_scan = ((size_t)ne + (ne + 1) + TQ_N_TILINGS * (ne + 1)) * 4;
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), sm_scan, stream, hist, nblk, E, S, T, offsets, tile_e,
-                       tile_row0, rt_max, ctrl);
+    hipLaunchKernelGGL(chunk_scan_kernel, dim3(E), dim3(64), 0, stream, hist, nblk, E, offsets + 1);
+    TQ_CHECK_LAUNCH();
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), sm_scan, stream, E, S, T, offsets, tile_e, tile_row0, rt_max,
+                       ctrl);
     TQ_CHECK_LAUNCH();
     hipLaunchKernelGGL(scatter_kernel, dim3(nblk), dim3(64), (size_t)E * 4, stream, topk_idx, topk_w, n_assign, E,
                        S, T, k, hist, offsets, slot_of, slot_stride, src_of, row_token, row_w);
