@@ -33,108 +33,136 @@ using namespace tqdev;
 // aug_kernel: per 32-row tile, the augmented activation row
 //   xaug[slot] = [ hi(xsum_0..G-1) | lo(xsum) | hi(xsum) | 0.. (to a multiple of 16) | t = x A (NA values) | 0.. ]
 // STAGE 0: x rows gathered by token, A = [gate | up] factors (NA = 2 r16).  STAGE 1: h rows, down factors.
-template <int STAGE>
+// NAT = column tiles of t per pass over x, UNR = steps whose loads are issued together.
+template <int STAGE, int NAT, int UNR>
 __global__ void __launch_bounds__(256) aug_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
                                                   const uint16_t* __restrict__ xin,
                                                   const int32_t* __restrict__ row_token,
                                                   const int32_t* __restrict__ tile_e,
                                                   const int32_t* __restrict__ tile_row0,
                                                   const int32_t* __restrict__ offsets,
-                                                  const int32_t* __restrict__ ctrl, uint16_t* __restrict__ xaug,
-                                                  int ka)
+                                                  const int32_t* __restrict__ ctrl, int ctrl_idx,
+                                                  uint16_t* __restrict__ xaug, int ka)
 {
-    // One workgroup per 32-row tile; its four waves split the contraction at unit (= group) boundaries so
-    // that enough loads are in flight, and their partial t tiles are summed through LDS.
+    constexpr int MT = 1;
+    // One workgroup per tile of 32 rows; its four waves split the contraction at unit (= group)
+    // boundaries so that enough loads are in flight, and their partial t tiles are summed through LDS.
     __shared__ float red[4][16][64];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int tile = blockIdx.x;
-    if (tile >= ctrl[1]) return;
+    if (tile >= ctrl[ctrl_idx]) return;
     const int e = tile_e[tile], slot0 = tile_row0[tile];
-    const int rows = min(32, offsets[e + 1] - slot0);
+    const int rows = min(32 * MT, offsets[e + 1] - slot0);
     const int col = lane & 31, hf = lane >> 5;
     const int K = sec.K, NA = STAGE == 0 ? 2 * G.r16 : G.r16;
     const int groups = sec.groups, GS = G.g / 16, ksteps = K / 16;
     const int ZT = tq_zero_terms(K, G.g);
-    const int m = min(col, rows - 1);
-    const uint16_t* xrow = STAGE == 0 ? xin + (size_t)row_token[slot0 + m] * K : xin + (size_t)(slot0 + m) * K;
+    const uint16_t* xrow[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        const int m = min(32 * i + col, rows - 1);
+        xrow[i] = STAGE == 0 ? xin + (size_t)row_token[slot0 + m] * K : xin + (size_t)(slot0 + m) * K;
+    }
     const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
     const u32x4* af = reinterpret_cast<const u32x4*>(rec + sec.afrag);
-    uint16_t* orow = xaug + (size_t)(slot0 + col) * ka;
-    const bool writer = (hf == 0) && (col < rows);
+    uint16_t* orow = xaug + (size_t)(slot0 + col) * ka;     // row 32 i + col is at orow + 32 i ka
     const int unit_steps = (G.g < 64 ? 64 : G.g) / 16;
     const int NU = ksteps / unit_steps;
     const int sb = (wave * NU / 4) * unit_steps, se = ((wave + 1) * NU / 4) * unit_steps;
 
     const int na_tiles = (G.r > 0) ? sec.na_tiles : 0;
-    for (int ta0 = 0; ta0 == 0 || ta0 < na_tiles; ta0 += 4) {
-        f32x16 acc[4];
+    for (int ta0 = 0; ta0 == 0 || ta0 < na_tiles; ta0 += NAT) {
+        f32x16 acc[MT][NAT];
+        float gsum[MT];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int i = 0; i < MT; ++i) {
+            gsum[i] = 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
-        float gsum = 0.f;
-        constexpr int UNR = 4;   // steps whose loads are issued together (a unit is a multiple of 4 steps)
+            for (int j = 0; j < NAT; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        }
         for (int s0 = sb; s0 < se; s0 += UNR) {
-            Frag xa[UNR];
-            u32x4 aq[UNR][4];
+            Frag xa[MT][UNR];
+            u32x4 aq[UNR][NAT];
 #pragma unroll
-            for (int u = 0; u < UNR; ++u) xa[u].q = *reinterpret_cast<const u32x4*>(xrow + 16 * (s0 + u) + 8 * hf);
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int u = 0; u < UNR; ++u)
+                    xa[i][u].q = *reinterpret_cast<const u32x4*>(xrow[i] + 16 * (s0 + u) + 8 * hf);
 #pragma unroll
             for (int u = 0; u < UNR; ++u)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < NAT; ++j)
                     if (ta0 + j < na_tiles) aq[u][j] = af[((size_t)(ta0 + j) * ksteps + s0 + u) * 64 + lane];
 #pragma unroll
             for (int u = 0; u < UNR; ++u) {
                 const int s = s0 + u;
                 if (ta0 == 0) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) gsum += bf_lo(xa[u].u[j]) + bf_hi(xa[u].u[j]);
+                    for (int i = 0; i < MT; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) gsum[i] += bf_lo(xa[i][u].u[j]) + bf_hi(xa[i][u].u[j]);
                     if ((s + 1) % GS == 0) {
-                        float tot = gsum + __shfl_xor(gsum, 32);
-                        if (writer) {
-                            int gi = s / GS;
-                            uint32_t hi = f2bf_bits(tot);
-                            uint32_t lo = f2bf_bits(tot - __uint_as_float(hi << 16));
-                            uint16_t* zb = orow + 48 * (gi >> 4) + (gi & 15);   // block of 16 groups: hi | lo | hi
-                            zb[0] = (uint16_t)hi;
-                            zb[16] = (uint16_t)lo;
-                            zb[32] = (uint16_t)hi;
+                        const int gi = s / GS;
+#pragma unroll
+                        for (int i = 0; i < MT; ++i) {
+                            float tot = gsum[i] + __shfl_xor(gsum[i], 32);
+                            if (hf == 0 && 32 * i + col < rows) {
+                                uint32_t hi = f2bf_bits(tot);
+                                uint32_t lo = f2bf_bits(tot - __uint_as_float(hi << 16));
+                                // block of 16 groups: hi | lo | hi
+                                uint16_t* zb = orow + (size_t)32 * i * ka + 48 * (gi >> 4) + (gi & 15);
+                                zb[0] = (uint16_t)hi;
+                                zb[16] = (uint16_t)lo;
+                                zb[32] = (uint16_t)hi;
+                            }
+                            gsum[i] = 0.f;
                         }
-                        gsum = 0.f;
                     }
                 }
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (ta0 + j < na_tiles)
-                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[u].v, half8_to_bf8(aq[u][j]), acc[j], 0, 0, 0);
+                for (int j = 0; j < NAT; ++j)
+                    if (ta0 + j < na_tiles) {
+                        const bf16x8 a8 = half8_to_bf8(aq[u][j]);
+#pragma unroll
+                        for (int i = 0; i < MT; ++i)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i][u].v, a8, acc[i][j], 0, 0, 0);
+                    }
             }
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (ta0 + j < na_tiles) {      // uniform over the workgroup
+        for (int i = 0; i < MT; ++i)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) red[wave][v][lane] = acc[j][v];
-                __syncthreads();
+            for (int j = 0; j < NAT; ++j) {
+                if (ta0 + j < na_tiles) {      // uniform over the workgroup
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int v = 4 * q + wave;
-                    const float sum = (red[0][v][lane] + red[1][v][lane]) + (red[2][v][lane] + red[3][v][lane]);
-                    const int c = 32 * (ta0 + j) + col;
-                    const int m2 = 8 * (v / 4) + 4 * hf + (v % 4);
-                    if (c < NA && m2 < rows) xaug[(size_t)(slot0 + m2) * ka + ZT + c] = (uint16_t)f2bf_bits(sum);
+                    for (int v = 0; v < 16; ++v) red[wave][v][lane] = acc[i][j][v];
+                    __syncthreads();
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int v = 4 * q + wave;
+                        const float sum = (red[0][v][lane] + red[1][v][lane]) + (red[2][v][lane] + red[3][v][lane]);
+                        const int c = 32 * (ta0 + j) + col;
+                        const int m2 = 32 * i + 8 * (v / 4) + 4 * hf + (v % 4);
+                        if (c < NA && m2 < rows) xaug[(size_t)(slot0 + m2) * ka + ZT + c] = (uint16_t)f2bf_bits(sum);
+                    }
+                    __syncthreads();
                 }
-                __syncthreads();
             }
-        }
     }
     // the padding must be finite (it meets zero weights in the MFMA): write zeros
-    if (writer && wave == 0) {
-        for (int gi = groups; gi < 16 * ((groups + 15) / 16); ++gi) {
-            uint16_t* zb = orow + 48 * (gi >> 4) + (gi & 15);
-            zb[0] = 0; zb[16] = 0; zb[32] = 0;
+    if (hf == 0 && wave == 0) {
+#pragma unroll
+        for (int i = 0; i < MT; ++i) {
+            if (32 * i + col >= rows) continue;
+            uint16_t* o = orow + (size_t)32 * i * ka;
+            for (int gi = groups; gi < 16 * ((groups + 15) / 16); ++gi) {
+                uint16_t* zb = o + 48 * (gi >> 4) + (gi & 15);
+                zb[0] = 0; zb[16] = 0; zb[32] = 0;
+            }
+            for (int kk = ZT + ((G.r > 0) ? NA : 0); kk < ka; ++kk) o[kk] = 0;
         }
-        for (int kk = ZT + ((G.r > 0) ? NA : 0); kk < ka; ++kk) orow[kk] = 0;
     }
 }
 
@@ -431,7 +459,11 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
         if (tid == 0 && wg < 8192) { g_timing[wg * 8 + 5] = rows; g_timing[wg * 8 + 6] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11)); }
 #endif
     } else {
-        float* yd = reinterpret_cast<float*>(out) + (size_t)split * G.a_tot * G.H + (size_t)slot0 * G.H + 64 * pair + col;
+        // tiles of 64 rows and more are never split over K: their result goes out as bf16, halving the traffic
+        // of this store and of the combine pass; the split-K planes of the 32-row path stay fp32
+        constexpr bool YD16 = MT >= 2;
+        using YT = std::conditional_t<YD16, uint16_t, float>;
+        YT* yd = reinterpret_cast<YT*>(out) + (size_t)split * G.a_tot * G.H + (size_t)slot0 * G.H + 64 * pair + col;
         auto emit = [&](auto full_tag) {
             constexpr bool FULL = decltype(full_tag)::value;
 #pragma unroll
@@ -440,8 +472,13 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
                 for (int v = 0; v < 16; ++v) {
                     const int m = 32 * (MT * wm + mt) + 8 * (v / 4) + 4 * hf + (v % 4);
                     if (FULL || m < rows) {
-                        yd[(size_t)m * G.H] = acc[mt][0][v];
-                        yd[(size_t)m * G.H + 32] = acc[mt][1][v];
+                        if constexpr (YD16) {
+                            yd[(size_t)m * G.H] = (uint16_t)f2bf_bits(acc[mt][0][v]);
+                            yd[(size_t)m * G.H + 32] = (uint16_t)f2bf_bits(acc[mt][1][v]);
+                        } else {
+                            yd[(size_t)m * G.H] = acc[mt][0][v];
+                            yd[(size_t)m * G.H + 32] = acc[mt][1][v];
+                        }
                     }
                 }
         };
@@ -449,31 +486,53 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
     }
 }
 
-// y[t][c] = bf16( sum_j w[t][j] * sum_s yd[s][slot_of[t][j]][c] + shared ), terms in slot order
+// y[t][c] = bf16( sum_j w[t][j] * sum_s yd[s][slot_of[t][j]][c] + shared ), terms in slot order.
+// YD16: yd is one plane of bf16 (written by the 64-row and larger tiles), else nsplit planes of fp32.
+template <bool YD16>
 __global__ void __launch_bounds__(256) combine_bf16_kernel(int T, int H, int k, int S, int nsplit, size_t plane,
                                                            const int32_t* __restrict__ slot_of,
                                                            const float* __restrict__ w,
-                                                           const float* __restrict__ yd, uint16_t* __restrict__ y)
+                                                           const void* __restrict__ ydv, uint16_t* __restrict__ y)
 {
     const int t = blockIdx.x;
-    const int c = (blockIdx.y * 256 + threadIdx.x) * 4;
+    constexpr int VW = YD16 ? 8 : 4;
+    const int c = (blockIdx.y * 256 + threadIdx.x) * VW;
     if (c >= H) return;
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    float a[VW];
+#pragma unroll
+    for (int i = 0; i < VW; ++i) a[i] = 0.f;
     for (int j = 0; j < k + S; ++j) {
         const int slot = slot_of[(size_t)t * (k + S) + j];
         if (slot < 0) continue;
         const float wj = j < k ? w[(size_t)t * k + j] : 1.0f;
-        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-        for (int sp = 0; sp < nsplit; ++sp) {
-            const float4 v = *reinterpret_cast<const float4*>(yd + (size_t)sp * plane + (size_t)slot * H + c);
-            s0 += v.x; s1 += v.y; s2 += v.z; s3 += v.w;
+        if constexpr (YD16) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(ydv) + (size_t)slot * H + c);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                a[2 * i] = fmaf(wj, bf_lo(v[i]), a[2 * i]);
+                a[2 * i + 1] = fmaf(wj, bf_hi(v[i]), a[2 * i + 1]);
+            }
+        } else {
+            const float* yd = reinterpret_cast<const float*>(ydv);
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+            for (int sp = 0; sp < nsplit; ++sp) {
+                const float4 v = *reinterpret_cast<const float4*>(yd + (size_t)sp * plane + (size_t)slot * H + c);
+                s0 += v.x; s1 += v.y; s2 += v.z; s3 += v.w;
+            }
+            a[0] = fmaf(wj, s0, a[0]); a[1] = fmaf(wj, s1, a[1]); a[2] = fmaf(wj, s2, a[2]); a[3] = fmaf(wj, s3, a[3]);
         }
-        a0 = fmaf(wj, s0, a0); a1 = fmaf(wj, s1, a1); a2 = fmaf(wj, s2, a2); a3 = fmaf(wj, s3, a3);
     }
-    uint2 o;
-    o.x = pack_bf2(a0, a1);
-    o.y = pack_bf2(a2, a3);
-    *reinterpret_cast<uint2*>(y + (size_t)t * H + c) = o;
+    if constexpr (YD16) {
+        u32x4 o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = pack_bf2(a[2 * i], a[2 * i + 1]);
+        *reinterpret_cast<u32x4*>(y + (size_t)t * H + c) = o;
+    } else {
+        uint2 o;
+        o.x = pack_bf2(a[0], a[1]);
+        o.y = pack_bf2(a[2], a[3]);
+        *reinterpret_cast<uint2*>(y + (size_t)t * H + c) = o;
+    }
 }
 
 template <int MT, int WM, int STAGE, int GS>
@@ -525,6 +584,25 @@ tq_status launch_main_gs(int gs, const MGeom& G, const TqSection& sec, const uin
     return TQ_ERR_UNSUPPORTED;
 }
 
+template <int STAGE>
+void launch_aug(const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin, const int32_t* row_token,
+                const int32_t* tile_e, const int32_t* tile_row0, const int32_t* offsets, const int32_t* ctrl,
+                uint16_t* xaug, int ka, int rt32, hipStream_t st)
+{
+    // fewer column tiles leave registers for more loads in flight; eight steps at a time need units of 128
+    const int nat = G.r > 0 ? sec.na_tiles : 0;
+    const bool deep = (G.g < 64 ? 64 : G.g) % 128 == 0;
+#define TQ_AUG(NATV, UNRV)                                                                                        \
+    hipLaunchKernelGGL((aug_kernel<STAGE, NATV, UNRV>), dim3(rt32), dim3(256), 0, st, G, sec, blob, xin, row_token, \
+                       tile_e, tile_row0, offsets, ctrl, 1, xaug, ka)
+    if (nat <= 1 && deep) TQ_AUG(1, 8);
+    else if (nat <= 1) TQ_AUG(1, 4);
+    else if (nat == 2 && deep) TQ_AUG(2, 8);
+    else if (nat == 2) TQ_AUG(2, 4);
+    else TQ_AUG(4, 4);
+#undef TQ_AUG
+}
+
 }  // namespace
 
 tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, const uint8_t* blob,
@@ -565,15 +643,14 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
         tq_status rs = tqi_forward_skinny(L, W, blob, x, T, ws, stream, &nsplit_sk);
         if (rs != TQ_OK) return rs;
         tqi_record_stage(5, stream);
-        hipLaunchKernelGGL(combine_bf16_kernel, dim3(T, (L.H / 4 + 255) / 256), dim3(256), 0, stream, T, L.H, L.k, L.S,
+        hipLaunchKernelGGL(combine_bf16_kernel<false>, dim3(T, (L.H / 4 + 255) / 256), dim3(256), 0, stream, T, L.H, L.k, L.S,
                            nsplit_sk, (size_t)W.a_tot * L.H, slot_of, topk_w, yd, y);
         TQ_CHECK_LAUNCH();
         tqi_record_stage(6, stream);
         return TQ_OK;
     }
 
-    hipLaunchKernelGGL(aug_kernel<0>, dim3(rt32), dim3(256), 0, stream, G, L.gu, blob, x, row_token, tile_e,
-                       tile_row0, offsets, ctrl, xaug_gu, W.ka_gu);
+    launch_aug<0>(G, L.gu, blob, x, row_token, tile_e, tile_row0, offsets, ctrl, xaug_gu, W.ka_gu, rt32, stream);
     TQ_CHECK_LAUNCH();
     tqi_record_stage(2, stream);
     tq_status rc;
@@ -595,8 +672,7 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
                                   rt32, stream);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(3, stream);
-    hipLaunchKernelGGL(aug_kernel<1>, dim3(rt32), dim3(256), 0, stream, G, L.d, blob, h, row_token, tile_e,
-                       tile_row0, offsets, ctrl, xaug_d, W.ka_d);
+    launch_aug<1>(G, L.d, blob, h, row_token, tile_e, tile_row0, offsets, ctrl, xaug_d, W.ka_d, rt32, stream);
     TQ_CHECK_LAUNCH();
     tqi_record_stage(4, stream);
     int nsplit = 1;
@@ -623,8 +699,12 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
                                   nsplit, rt32, stream);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(5, stream);
-    hipLaunchKernelGGL(combine_bf16_kernel, dim3(T, (L.H / 4 + 255) / 256), dim3(256), 0, stream, T, L.H, L.k, L.S,
-                       nsplit, (size_t)W.a_tot * L.H, slot_of, topk_w, yd, y);
+    if (large)
+        hipLaunchKernelGGL(combine_bf16_kernel<true>, dim3(T, (L.H / 8 + 255) / 256), dim3(256), 0, stream, T, L.H, L.k,
+                           L.S, 1, (size_t)0, slot_of, topk_w, yd, y);
+    else
+        hipLaunchKernelGGL(combine_bf16_kernel<false>, dim3(T, (L.H / 4 + 255) / 256), dim3(256), 0, stream, T, L.H, L.k,
+                           L.S, nsplit, (size_t)W.a_tot * L.H, slot_of, topk_w, yd, y);
     TQ_CHECK_LAUNCH();
     tqi_record_stage(6, stream);
     return TQ_OK;

@@ -188,9 +188,10 @@ __global__ void __launch_bounds__(64) chunk_scan_kernel(int32_t* __restrict__ hi
     if (lane == 0) counts[e] = run;
 }
 
-// Single block of 1024 threads: expert offsets from the counts (left in offsets[1..E] by chunk_scan_kernel)
-// and the row-tile tables.
-__global__ void __launch_bounds__(1024) scan_kernel(int E, int S, int T, int32_t* __restrict__ offsets,
+// Single block of 1024 threads: expert offsets from the counts (left in offsets[1..E] by chunk_scan_kernel
+// when hist is null, else computed here from the few chunks of hist) and the row-tile tables.
+__global__ void __launch_bounds__(1024) scan_kernel(int32_t* __restrict__ hist, int nblk, int E, int S, int T,
+                                                    int32_t* __restrict__ offsets,
                                                     int32_t* __restrict__ tile_e, int32_t* __restrict__ tile_row0,
                                                     int rt_max, int32_t* __restrict__ ctrl)
 {
@@ -200,7 +201,23 @@ __global__ void __launch_bounds__(1024) scan_kernel(int E, int S, int T, int32_t
     int32_t* offs = sm + ne;
     int32_t* tsm = offs + ne + 1;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int e = tid; e < ne; e += 1024) counts[e] = e < E ? offsets[e + 1] : T;
+    if (hist) {
+        // few chunks: the per-expert scan over chunks is one wave round per expert, done here
+        for (int e = wave; e < E; e += 16) {
+            int run = 0;
+            for (int b0 = 0; b0 < nblk; b0 += 64) {
+                int b = b0 + lane;
+                int v = b < nblk ? hist[(size_t)b * E + e] : 0;
+                int inc = wave_incl_scan(v, lane);
+                if (b < nblk) hist[(size_t)b * E + e] = run + inc - v;
+                run += __shfl(inc, 63);
+            }
+            if (lane == 0) counts[e] = run;
+        }
+        for (int s = tid; s < S; s += 1024) counts[E + s] = T;
+    } else {
+        for (int e = tid; e < ne; e += 1024) counts[e] = e < E ? offsets[e + 1] : T;
+    }
     __syncthreads();
     if (wave == 0) {
         int total = wave_excl_scan(counts, offs, ne, lane, [](int v) { return v; });
@@ -226,16 +243,17 @@ __device__ inline void scatter_chunk(const int32_t* __restrict__ idx, const floa
             if (e < 0 || e >= E) e = -1;
         }
         // rank of this lane among the lanes of the round that hold the same expert and come before it
-        int before = 0, after = 0;
-#pragma unroll 8
-        for (int j = 0; j < 64; ++j) {
-            const int ej = __shfl(e, j);
-            before += (ej == e) & (j < lane);
-            after += (ej == e) & (j > lane);
+        // lanes holding the same expert: intersect, bit by bit of e, the ballots that agree with this lane
+        uint64_t same = __ballot(e >= 0);
+        for (int bit = 0; (1 << bit) < E; ++bit) {
+            const uint64_t bal = __ballot((e >> bit) & 1);
+            same &= ((e >> bit) & 1) ? bal : ~bal;
         }
+        const int before = __popcll(same & ((1ull << lane) - 1ull));
+        const bool last = (same >> lane) <= 1ull;      // no higher lane with this expert
         const int slot = e >= 0 ? cursor[e] + before : -1;
         __syncthreads();
-        if (e >= 0 && after == 0) cursor[e] = slot + 1;   // the last lane of each expert moves its cursor
+        if (e >= 0 && last) cursor[e] = slot + 1;   // the last lane of each expert moves its cursor
         __syncthreads();
         if (a < n_assign) {
             int t = (int)(a / k), j = (int)(a % k);
@@ -276,7 +294,7 @@ __global__ void __launch_bounds__(64) scatter_kernel(const int32_t* __restrict__
     }
 }
 
-// The whole permutation for at most TQ_PERM_CHUNK assignments in ONE wavefront (one launch instead of four).
+// The whole permutation for a few chunks of assignments in ONE wavefront (one launch instead of five).
 __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __restrict__ idx, const float* __restrict__ w,
                                                            int n_assign, int E, int S, int T, int k,
                                                            int32_t* __restrict__ offsets, int32_t* __restrict__ slot_of,
@@ -313,7 +331,8 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
     if (ctrl && lane == 0) ctrl[3] = total;
     if (tile_e) build_tile_tables(offs, tsm, ne, tile_e, tile_row0, rt_max, ctrl, lane, 64);
     __syncthreads();
-    scatter_chunk(idx, w, 0, n_assign, E, k, cursor, lane, slot_of, slot_stride, src_of, row_token, row_w);
+    for (int a0 = 0; a0 < n_assign; a0 += TQ_PERM_CHUNK)
+        scatter_chunk(idx, w, a0, n_assign, E, k, cursor, lane, slot_of, slot_stride, src_of, row_token, row_w);
     for (int i = lane; i < S * T; i += 64) {
         int s = i / T, t = i % T;
         int slot = offs[E + s] + t;
@@ -365,10 +384,13 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
                        err_flag, (const TqBlobHeader*)blob, expect, check);
     TQ_CHECK_LAUNCH();
     const size_t sm_scan = ((size_t)ne + (ne + 1) + TQ_N_TILINGS * (ne + 1)) * 4;
-    hipLaunchKernelGGL(chunk_scan_kernel, dim3(E), dim3(64), 0, stream, hist, nblk, E, offsets + 1);
-    TQ_CHECK_LAUNCH();
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), sm_scan, stream, E, S, T, offsets, tile_e, tile_row0, rt_max,
-                       ctrl);
+    const bool split_scan = nblk > 64;
+    if (split_scan) {
+        hipLaunchKernelGGL(chunk_scan_kernel, dim3(E), dim3(64), 0, stream, hist, nblk, E, offsets + 1);
+        TQ_CHECK_LAUNCH();
+    }
+    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), sm_scan, stream, split_scan ? nullptr : hist, nblk, E, S, T,
+                       offsets, tile_e, tile_row0, rt_max, ctrl);
     TQ_CHECK_LAUNCH();
     hipLaunchKernelGGL(scatter_kernel, dim3(nblk), dim3(64), (size_t)E * 4, stream, topk_idx, topk_w, n_assign, E,
                        S, T, k, hist, offsets, slot_of, slot_stride, src_of, row_token, row_w);
