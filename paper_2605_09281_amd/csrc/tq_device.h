@@ -76,3 +76,11 @@ __device__ inline void lds_barrier()
 }
 
 }  // namespace tqdev
+
+// persistent-workgroup prefill kernels: one projection stage (0: gate/up + SwiGLU -> h, 1: down -> bf16 rows)
+bool tqi_prefill_supported(const TqLayout& L, const TqWorkspace& W, int32_t T);
+tq_status tqi_forward_prefill_stage(int stage, const TqLayout& L, const TqWorkspace& W, const tqdev::MGeom& G,
+                                    const uint8_t* blob, const uint16_t* xin, const uint16_t* xaug,
+                                    const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
+                                    const int32_t* offsets, const int32_t* ctrl, int ctrl_idx, void* out,
+                                    hipStream_t st);

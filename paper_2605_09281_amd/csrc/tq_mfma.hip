@@ -634,6 +634,7 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     const int rt128 = W.a_tot / 128 + L.E + L.S;
     const int rt64 = W.a_tot / 64 + L.E + L.S;
     const int gs = L.g / 16;
+    const bool persist = tqi_prefill_supported(L, W, T) && !getenv("TQ_NO_PERSIST");
 
     // decode batches (a handful of rows per expert): the weight-streaming 16-row path, no pre-pass over K
     bool skinny = !large && avg_rows <= 12 && !(flags & TQ_FLAG_FORCE_SMALL_TILE);
@@ -659,6 +660,9 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     if (large && gs == 16)
         rc = launch_main<4, 1, 0, 16>(G, L.gu, blob, x, xaug_gu, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max,
                                       offsets, ctrl, 2, h, W.ka_gu, 1, rt128, stream);
+    else if (large && persist)
+        rc = tqi_forward_prefill_stage(0, L, W, G, blob, x, xaug_gu, row_token, tile_e + 3 * (size_t)W.rt_max,
+                                       tile_row0 + 3 * (size_t)W.rt_max, offsets, ctrl, 5, h, stream);
     else if (large && !getenv("TQ_TILE128"))
         // 64-row tiles, four waves of 64x64: two such workgroups share a CU and run out of phase, so one's
         // per-unit tail (fold, staging store, barrier) overlaps the other's MFMAs
@@ -688,6 +692,9 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     if (large && gs == 16)
         rc = launch_main<4, 1, 1, 16>(G, L.d, blob, h, xaug_d, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max,
                                       offsets, ctrl, 2, yd, W.ka_d, 1, rt128, stream);
+    else if (large && persist)
+        rc = tqi_forward_prefill_stage(1, L, W, G, blob, h, xaug_d, row_token, tile_e + 3 * (size_t)W.rt_max,
+                                       tile_row0 + 3 * (size_t)W.rt_max, offsets, ctrl, 5, yd, stream);
     else if (large && !getenv("TQ_TILE128"))
         rc = launch_main_gs<2, 1, 1>(gs, G, L.d, blob, h, xaug_d, row_token, tile_e + 3 * (size_t)W.rt_max,
                                      tile_row0 + 3 * (size_t)W.rt_max, offsets, ctrl, 5, yd, W.ka_d, 1, rt64, stream);
