@@ -101,10 +101,11 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     const int rt = blockIdx.y;
     if (rt >= ctrl[4]) return;
     const int e = tile_e[rt], slot0 = tile_row0[rt];
-    const int rows = min(16, offsets[e + 1] - slot0);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int K = sec.K, NU = K / UNIT_K;
     const int split = blockIdx.z;
+    const int NA = STAGE == 0 ? 2 * G.r16 : G.r16;
+    const int n_lr = (G.r > 0) ? NA / 16 : 0;       // low-rank MFMA steps; step j is applied by wave j
     const int ub = split * units_per_split;
     const int ue = min(NU, ub + units_per_split);
     const int range_k = (ue - ub) * UNIT_K;
@@ -113,8 +114,6 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     const int wk0 = wave * UPW * US;                // first MFMA step of this wave inside the workgroup's range
     const int p0 = blockIdx.x * pairs_per_wg;
     const int p1 = min(sec.pairs, p0 + pairs_per_wg);
-    const int NA = STAGE == 0 ? 2 * G.r16 : G.r16;
-    const int n_lr = (G.r > 0) ? NA / 16 : 0;       // low-rank MFMA steps; step j is applied by wave j
 
     const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
     const u32x4* codes = reinterpret_cast<const u32x4*>(rec + sec.codes) + lane;
@@ -167,22 +166,51 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     u32x4 bq[2];
     load_b(bq, p0);
 
+    // ---- 0. the slices of the low-rank intermediate are requested right away (they depend on the tile index only);
+    //         up to 16 slices per workgroup range, summed per column tile of t
+    float tsum[4] = {0.f, 0.f, 0.f, 0.f};
+    if (n_lr > 0) {
+        const int sl0 = (ub * UNIT_K) / SK_PRE_K;
+        const int nsl = (range_k + SK_PRE_K - 1) / SK_PRE_K;
+#pragma unroll
+        for (int ta = 0; ta < 4; ++ta) {
+            if (ta < na_tiles) {
+                float v[16];
+#pragma unroll
+                for (int sl = 0; sl < 16; ++sl)
+                    v[sl] = tpart[(((size_t)rt * n_slices + sl0 + min(sl, nsl - 1)) * na_tiles + ta) * 512 + wave * 64 + lane];
+#pragma unroll
+                for (int sl = 0; sl < 16; ++sl) tsum[ta] += sl < nsl ? v[sl] : 0.f;
+            }
+        }
+    }
     // ---- 1. activations of the tile for the workgroup's contraction range -> LDS (row stride RB = 2*range + 16 bytes:
-    //         the 16 rows read by one ds_read_b128 fall into 16 different bank groups)
+    //         the rows read by one ds_read_b128 fall into different bank groups).  Only the rows that exist are
+    //         staged; the MFMA rows beyond them re-read the last one and their results are never stored.
+    const int rows = min(16, offsets[e + 1] - slot0);
     {
-        const int gran = range_k / 8;
-        for (int row = 0; row < 16; ++row) {
-            const int r = min(row, rows - 1);
-            const size_t src_row = STAGE == 0 ? (size_t)row_token[slot0 + r] : (size_t)(slot0 + r);
-            const uint16_t* src = xin + src_row * K + (size_t)ub * UNIT_K;
-            for (int kg = tid; kg < gran; kg += 512)
-                *reinterpret_cast<u32x4*>(lds + row * RB + kg * 16) = *reinterpret_cast<const u32x4*>(src + kg * 8);
+        const int gran = range_k / 8;                 // 16-byte chunks per row
+        const int total = rows * gran;
+        for (int c0 = 0; c0 < total; c0 += 4 * 512) {
+            u32x4 v[4];
+            int dst[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int c = min(c0 + j * 512 + tid, total - 1);
+                const int row = c / gran, kg = c - row * gran;
+                const size_t src_row = STAGE == 0 ? (size_t)row_token[slot0 + row] : (size_t)(slot0 + row);
+                v[j] = *reinterpret_cast<const u32x4*>(xin + src_row * K + (size_t)ub * UNIT_K + (size_t)kg * 8);
+                dst[j] = row * RB + kg * 16;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4*>(lds + dst[j]) = v[j];
         }
     }
     lds_barrier();
+    const int xrow_off = min(col & 15, rows - 1) * RB;
     auto lds_x = [&](int kl) -> bf16x8 {       // fragment of MFMA step kl (relative to the workgroup's range)
         Frag f;
-        f.q = *reinterpret_cast<const u32x4*>(lds + (col & 15) * RB + (kl * 16 + 8 * hf) * 2);
+        f.q = *reinterpret_cast<const u32x4*>(lds + xrow_off + (kl * 16 + 8 * hf) * 2);
         return f.v;
     };
 
@@ -216,15 +244,11 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
 #pragma unroll
     for (int j = 0; j < 4; ++j) tf.u[j] = 0;
     if (n_lr > 0) {
-        const int sl0 = (ub * UNIT_K) / SK_PRE_K;
-        const int nsl = (range_k + SK_PRE_K - 1) / SK_PRE_K;
         const int m = row_of_v(wave, hf);          // wave w owns result rows row_of_v(w, hf)
-        for (int ta = 0; ta < na_tiles; ++ta) {
-            float sum = 0.f;
-            for (int sl = 0; sl < nsl; ++sl)
-                sum += tpart[(((size_t)rt * n_slices + sl0 + sl) * na_tiles + ta) * 512 + wave * 64 + lane];
+#pragma unroll
+        for (int ta = 0; ta < 4; ++ta) {
             const int c = 32 * ta + col;
-            if (c < NA) tbuf[m * NA + c] = (uint16_t)f2bf_bits(sum);
+            if (ta < na_tiles && c < NA) tbuf[m * NA + c] = (uint16_t)f2bf_bits(tsum[ta]);
         }
         lds_barrier();
         if (wave < n_lr) tf.q = *reinterpret_cast<const u32x4*>(tbuf + (col & 15) * NA + 16 * wave + 8 * hf);
