@@ -142,7 +142,65 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     uint32_t magic_v;
     asm volatile("v_mov_b32 %0, %1" : "=v"(magic_v) : "s"(G.unpack_magic));
 
-    // the first pair's codes are requested before anything else so that their latency hides behind the set-up
+    // ---- 1. activations of the tile for the workgroup's contraction range -> LDS (row stride RB = 2*range + 16 bytes:
+    //         the rows read by one ds_read_b128 fall into different bank groups).  Only the rows that exist are
+    //         staged; the MFMA rows beyond them re-read the last one and their results are never stored.
+    //         Everything the set-up needs (these rows, the low-rank slices) is requested and awaited BEFORE the first
+    //         weights are asked for: at kernel start every workgroup asks for its first pair at once, and small
+    //         loads queued behind that burst would arrive only after it.
+    const int rows = min(16, offsets[e + 1] - slot0);
+    const int gran = range_k / 8;                 // 16-byte chunks per row
+    const int total = rows * gran;
+    auto stage_load = [&](int c0, u32x4 (&v)[4], int (&dst)[4]) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = min(c0 + j * 512 + tid, total - 1);
+            const int row = c / gran, kg = c - row * gran;
+            const size_t src_row = STAGE == 0 ? (size_t)row_token[slot0 + row] : (size_t)(slot0 + row);
+            v[j] = *reinterpret_cast<const u32x4*>(xin + src_row * K + (size_t)ub * UNIT_K + (size_t)kg * 8);
+            dst[j] = row * RB + kg * 16;
+        }
+    };
+    u32x4 xv0[4];
+    int xd0[4];
+    stage_load(0, xv0, xd0);
+
+    // ---- the slices of the low-rank intermediate: up to 16 per workgroup range and column tile of t.  Requested
+    //         before the weights as well, and unconditionally (layers without factors read a valid dummy word with
+    //         weight zero).
+    float tv[4][16];
+    {
+        const int sl0 = (ub * UNIT_K) / SK_PRE_K;
+        const int nsl = (range_k + SK_PRE_K - 1) / SK_PRE_K;
+        const float* tp = n_lr > 0 ? tpart : reinterpret_cast<const float*>(ctrl);
+        const size_t live = n_lr > 0 ? 1 : 0;
+#pragma unroll
+        for (int ta = 0; ta < 4; ++ta)
+#pragma unroll
+            for (int sl = 0; sl < 16; ++sl) {
+                const size_t idx = (((size_t)rt * n_slices + sl0 + min(sl, nsl - 1)) * na_tiles + min(ta, max(na_tiles, 1) - 1)) * 512 + wave * 64 + lane;
+                tv[ta][sl] = tp[idx * live];
+            }
+    }
+
+#pragma unroll
+    for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4*>(lds + xd0[j]) = xv0[j];
+    for (int c0 = 4 * 512; c0 < total; c0 += 4 * 512) {      // more than four chunks per thread: the rare tall tiles
+        u32x4 v[4];
+        int dst[4];
+        stage_load(c0, v, dst);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4*>(lds + dst[j]) = v[j];
+    }
+    float tsum[4] = {0.f, 0.f, 0.f, 0.f};
+    {
+        const int nsl = (range_k + SK_PRE_K - 1) / SK_PRE_K;
+#pragma unroll
+        for (int ta = 0; ta < 4; ++ta)
+#pragma unroll
+            for (int sl = 0; sl < 16; ++sl) tsum[ta] += sl < nsl ? tv[ta][sl] : 0.f;
+    }
+    // the first pair's codes: their latency hides behind the rest of the set-up (group sums, t fragments)
     u32x4 wq[UPW][2][UC];
     uint32_t szq[UPW][NG][2];
 #pragma unroll
@@ -166,46 +224,6 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     u32x4 bq[2];
     load_b(bq, p0);
 
-    // ---- 0. the slices of the low-rank intermediate are requested right away (they depend on the tile index only);
-    //         up to 16 slices per workgroup range, summed per column tile of t
-    float tsum[4] = {0.f, 0.f, 0.f, 0.f};
-    if (n_lr > 0) {
-        const int sl0 = (ub * UNIT_K) / SK_PRE_K;
-        const int nsl = (range_k + SK_PRE_K - 1) / SK_PRE_K;
-#pragma unroll
-        for (int ta = 0; ta < 4; ++ta) {
-            if (ta < na_tiles) {
-                float v[16];
-#pragma unroll
-                for (int sl = 0; sl < 16; ++sl)
-                    v[sl] = tpart[(((size_t)rt * n_slices + sl0 + min(sl, nsl - 1)) * na_tiles + ta) * 512 + wave * 64 + lane];
-#pragma unroll
-                for (int sl = 0; sl < 16; ++sl) tsum[ta] += sl < nsl ? v[sl] : 0.f;
-            }
-        }
-    }
-    // ---- 1. activations of the tile for the workgroup's contraction range -> LDS (row stride RB = 2*range + 16 bytes:
-    //         the rows read by one ds_read_b128 fall into different bank groups).  Only the rows that exist are
-    //         staged; the MFMA rows beyond them re-read the last one and their results are never stored.
-    const int rows = min(16, offsets[e + 1] - slot0);
-    {
-        const int gran = range_k / 8;                 // 16-byte chunks per row
-        const int total = rows * gran;
-        for (int c0 = 0; c0 < total; c0 += 4 * 512) {
-            u32x4 v[4];
-            int dst[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int c = min(c0 + j * 512 + tid, total - 1);
-                const int row = c / gran, kg = c - row * gran;
-                const size_t src_row = STAGE == 0 ? (size_t)row_token[slot0 + row] : (size_t)(slot0 + row);
-                v[j] = *reinterpret_cast<const u32x4*>(xin + src_row * K + (size_t)ub * UNIT_K + (size_t)kg * 8);
-                dst[j] = row * RB + kg * 16;
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4*>(lds + dst[j]) = v[j];
-        }
-    }
     lds_barrier();
     const int xrow_off = min(col & 15, rows - 1) * RB;
     auto lds_x = [&](int kl) -> bf16x8 {       // fragment of MFMA step kl (relative to the workgroup's range)
