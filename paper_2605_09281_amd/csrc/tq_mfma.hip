@@ -167,6 +167,143 @@ __global__ void __launch_bounds__(256) aug_kernel(MGeom G, TqSection sec, const 
 }
 
 // ------------------------------------------------------------------------------------------------
+// aug_staged_kernel: the same result as aug_kernel for groups of at most 128, with the activation rows read in
+// whole 4-group chunks by all threads (each row's chunk is one contiguous run of up to 1 KB instead of
+// 16 bytes per lane and step) and staged through LDS; wave w of the workgroup owns group w of every chunk.
+template <int STAGE, int NAT, int GS>
+__global__ void __launch_bounds__(256, 2) aug_staged_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
+                                                            const uint16_t* __restrict__ xin,
+                                                            const int32_t* __restrict__ row_token,
+                                                            const int32_t* __restrict__ tile_e,
+                                                            const int32_t* __restrict__ tile_row0,
+                                                            const int32_t* __restrict__ offsets,
+                                                            const int32_t* __restrict__ ctrl,
+                                                            uint16_t* __restrict__ xaug, int ka)
+{
+    constexpr int CK = 4 * GS * 16;        // contraction indices per chunk (four groups)
+    constexpr int CKB = CK * 2;            // bytes of one row's chunk
+    constexpr int ROWB = CKB + 16;         // padded LDS row
+    constexpr int SPR = CKB / 16;          // 16-byte segments per row
+    constexpr int RPP = 256 / SPR;         // rows per pass
+    constexpr int NP = 32 / RPP;           // passes
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];     // 2 x 32 x ROWB; reused for the reduction
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tile = blockIdx.x;
+    if (tile >= ctrl[1]) return;
+    const int e = tile_e[tile], slot0 = tile_row0[tile];
+    const int rows = min(32, offsets[e + 1] - slot0);
+    const int col = lane & 31, hf = lane >> 5;
+    const int K = sec.K, NA = STAGE == 0 ? 2 * G.r16 : G.r16;
+    const int groups = sec.groups, ksteps = K / 16;
+    const int ZT = tq_zero_terms(K, G.g);
+    const int nchunks = (groups + 3) / 4;
+    const int na_tiles = (G.r > 0) ? sec.na_tiles : 0;
+    const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
+    const u32x4* af = reinterpret_cast<const u32x4*>(rec + sec.afrag) + lane;
+    uint16_t* orow = xaug + (size_t)(slot0 + col) * ka;
+    const bool writer = (hf == 0) && (col < rows);
+
+    const int prow = tid / SPR, seg = tid % SPR;
+    uint32_t roff[NP];                     // byte offset of this thread's rows in xin
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int m = min(p * RPP + prow, rows - 1);
+        const uint32_t src = STAGE == 0 ? (uint32_t)row_token[slot0 + m] : (uint32_t)(slot0 + m);
+        roff[p] = src * (uint32_t)(K * 2);
+    }
+    const uint8_t* xb = reinterpret_cast<const uint8_t*>(xin);
+    u32x4 xr[NP];
+    auto load_chunk = [&](int c) {
+        // the last chunk may be short: segments past the row end re-read the last valid one (never used)
+        const int kb = min(c * CKB + seg * 16, K * 2 - 16);
+#pragma unroll
+        for (int p = 0; p < NP; ++p) xr[p] = *reinterpret_cast<const u32x4*>(xb + roff[p] + (uint32_t)kb);
+    };
+    auto store_chunk = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+            *reinterpret_cast<u32x4*>(lds + buf * 32 * ROWB + (p * RPP + prow) * ROWB + seg * 16) = xr[p];
+    };
+
+    f32x16 acc[NAT];
+#pragma unroll
+    for (int j = 0; j < NAT; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+
+    load_chunk(0);
+    store_chunk(0);
+    lds_barrier();
+    for (int c = 0; c < nchunks; ++c) {
+        load_chunk(min(c + 1, nchunks - 1));
+        const int gi = 4 * c + wave;
+        const int buf = c & 1;
+        if (gi < groups) {
+            u32x4 aq[GS][NAT];
+#pragma unroll
+            for (int ks = 0; ks < GS; ++ks)
+#pragma unroll
+                for (int j = 0; j < NAT; ++j)
+                    aq[ks][j] = af[((size_t)min(j, max(na_tiles, 1) - 1) * ksteps + gi * GS + ks) * 64];
+            Frag xa[GS];
+#pragma unroll
+            for (int ks = 0; ks < GS; ++ks)
+                xa[ks].q = *reinterpret_cast<const u32x4*>(lds + buf * 32 * ROWB + col * ROWB + (wave * GS + ks) * 32 + hf * 16);
+            float gsum = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < GS; ++ks)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) gsum += bf_lo(xa[ks].u[j]) + bf_hi(xa[ks].u[j]);
+            const float tot = gsum + __shfl_xor(gsum, 32);
+            if (writer) {
+                const uint32_t hi = f2bf_bits(tot);
+                const uint32_t lo = f2bf_bits(tot - __uint_as_float(hi << 16));
+                uint16_t* zb = orow + 48 * (gi >> 4) + (gi & 15);        // block of 16 groups: hi | lo | hi
+                zb[0] = (uint16_t)hi;
+                zb[16] = (uint16_t)lo;
+                zb[32] = (uint16_t)hi;
+            }
+#pragma unroll
+            for (int ks = 0; ks < GS; ++ks)
+#pragma unroll
+                for (int j = 0; j < NAT; ++j)
+                    if (j < na_tiles)
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[ks].v, half8_to_bf8(aq[ks][j]), acc[j], 0, 0, 0);
+        }
+        store_chunk((c + 1) & 1);
+        lds_barrier();
+    }
+    // sum the four waves' partial t tiles through LDS (the staging buffers are free now) and write them out
+    float* red = reinterpret_cast<float*>(lds);       // [4][16][64]
+#pragma unroll
+    for (int j = 0; j < NAT; ++j) {
+        if (j < na_tiles) {                           // uniform over the workgroup
+#pragma unroll
+            for (int v = 0; v < 16; ++v) red[(wave * 16 + v) * 64 + lane] = acc[j][v];
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int v = 4 * q + wave;
+                const float sum = (red[(0 * 16 + v) * 64 + lane] + red[(1 * 16 + v) * 64 + lane]) +
+                                  (red[(2 * 16 + v) * 64 + lane] + red[(3 * 16 + v) * 64 + lane]);
+                const int cc = 32 * j + col;
+                const int m2 = 8 * (v / 4) + 4 * hf + (v % 4);
+                if (cc < NA && m2 < rows) xaug[(size_t)(slot0 + m2) * ka + ZT + cc] = (uint16_t)f2bf_bits(sum);
+            }
+            __syncthreads();
+        }
+    }
+    // the padding must be finite (it meets zero weights in the MFMA): write zeros
+    if (writer && wave == 0) {
+        for (int gi = groups; gi < 16 * ((groups + 15) / 16); ++gi) {
+            uint16_t* zb = orow + 48 * (gi >> 4) + (gi & 15);
+            zb[0] = 0; zb[16] = 0; zb[32] = 0;
+        }
+        for (int kk = ZT + ((G.r > 0) ? NA : 0); kk < ka; ++kk) orow[kk] = 0;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // The grouped GEMM.  Workgroup = 4*WM waves sharing one row tile of BM = 32*MT*WM rows; wave (wm, wn) owns
 // rows [32*MT*wm, 32*MT*(wm+1)) of the tile and column-tile pair 4*nb + wn (64 output columns; in
 // stage 0 that is 32 gate + the matching 32 up columns).
@@ -591,6 +728,18 @@ void launch_aug(const MGeom& G, const TqSection& sec, const uint8_t* blob, const
 {
     // fewer column tiles leave registers for more loads in flight; eight steps at a time need units of 128
     const int nat = G.r > 0 ? sec.na_tiles : 0;
+    const int gs = G.g / 16;
+    // the staged variant: groups up to 128, at most two column tiles of t, 32-bit byte offsets of the rows
+    const uint64_t span = (uint64_t)(STAGE == 0 ? G.a_tot / (G.k + G.S) : G.a_tot) * sec.K * 2;
+    if (gs <= 8 && nat <= 2 && span < (1ull << 32)) {
+#define TQ_AUGS(NATV, GSV)                                                                                          \
+    hipLaunchKernelGGL((aug_staged_kernel<STAGE, NATV, GSV>), dim3(rt32), dim3(256), (size_t)2 * 32 * (4 * GSV * 32 + 16), \
+                       st, G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, xaug, ka)
+        if (nat <= 1) { if (gs == 8) TQ_AUGS(1, 8); else if (gs == 4) TQ_AUGS(1, 4); else TQ_AUGS(1, 2); }
+        else { if (gs == 8) TQ_AUGS(2, 8); else if (gs == 4) TQ_AUGS(2, 4); else TQ_AUGS(2, 2); }
+#undef TQ_AUGS
+        return;
+    }
     const bool deep = (G.g < 64 ? 64 : G.g) % 128 == 0;
 #define TQ_AUG(NATV, UNRV)                                                                                        \
     hipLaunchKernelGGL((aug_kernel<STAGE, NATV, UNRV>), dim3(rt32), dim3(256), 0, st, G, sec, blob, xin, row_token, \
