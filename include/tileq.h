@@ -84,7 +84,7 @@ enum { TQ_ACT_BF16 = 0, TQ_ACT_FP32 = 1 };
 /* flags of tq_layer_desc (test hooks; 0 in production) */
 enum {
     TQ_FLAG_FORCE_SMALL_TILE = 1, /* bf16 path: always the 32-row tile */
-    TQ_FLAG_FORCE_LARGE_TILE = 2, /* bf16 path: always the 128-row (prefill) tile */
+    TQ_FLAG_FORCE_LARGE_TILE = 2, /* bf16 path: always the large (64/128-row, prefill) tiles */
     TQ_FLAG_FORCE_SKINNY = 4      /* bf16 path: the 16-row weight-streaming (decode) kernels whenever the layer
                                      and the batch (at most 1024 assignment rows) allow them */
 };

@@ -14,16 +14,7 @@
 // already in MFMA fragment order and go straight from global memory to registers.
 #include "tq_device.h"
 
-#include <cstdlib>
 #include <type_traits>
-
-#ifdef TQ_TIMING
-__device__ unsigned long long g_timing[8 * 8192];
-extern "C" int tq_debug_read_timing(void* dst, size_t bytes) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_timing), bytes); }
-#define TQ_T(i) do { if (STAGE == 0 && MT == 2 && tid == 0 && wg < 8192) g_timing[wg * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define TQ_T(i) do { } while (0)
-#endif
 
 namespace {
 
@@ -347,7 +338,6 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
     const int nb = rem >> 3;
     const int rt = grp * 8 + (rem & 7);
     const int tid = threadIdx.x;
-    TQ_T(0);
     if (rt >= ctrl[ctrl_idx]) return;
     const int e = tile_e[rt], slot0 = tile_row0[rt];
     const int rows = min(BM, offsets[e + 1] - slot0);
@@ -440,7 +430,6 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
     load_w(wq[1], min(u0 + 1, ulast)); load_sz(szq[1], min(u0 + 1, ulast));
     store_step(0);
     lds_barrier();
-    TQ_T(1);
 
     auto lds_frag = [&](int buf, int mt, int kstep) -> bf16x8 {
         Frag f;
@@ -565,7 +554,6 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
         lds_barrier();
     }
 
-    TQ_T(2);
     int mu = 0;
     for (; mu + 1 < nmain; mu += 2) {
         main_unit(mu, std::integral_constant<int, 0>{});
@@ -574,7 +562,6 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
     if (mu < nmain) main_unit(mu, std::integral_constant<int, 0>{});
 
     // ---- epilogue (full tiles take a path without per-row tests) ----------------------------------------
-    TQ_T(3);
     if (!active) return;
     const bool full = rows == BM;
     if (STAGE == 0) {
@@ -591,10 +578,6 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
                 }
         };
         if (full) emit(std::true_type{}); else emit(std::false_type{});
-        TQ_T(4);
-#ifdef TQ_TIMING
-        if (tid == 0 && wg < 8192) { g_timing[wg * 8 + 5] = rows; g_timing[wg * 8 + 6] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11)); }
-#endif
     } else {
         // tiles of 64 rows and more are never split over K: their result goes out as bf16, halving the traffic
         // of this store and of the combine pass; the split-K planes of the 32-row path stay fp32
@@ -715,7 +698,12 @@ tq_status launch_main_gs(int gs, const MGeom& G, const TqSection& sec, const uin
         TQ_CASE(2);
         TQ_CASE(4);
         TQ_CASE(8);
-        TQ_CASE(16);
+        case 16:
+            if constexpr (MT == 1) {
+                return launch_main<MT, WM, STAGE, 16>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl, ctrl_idx,
+                                                      out, ka, nsplit, row_tiles, st);
+            }
+            break;      // groups of 256 with large tiles go through the <4, 1> instantiation
     }
 #undef TQ_CASE
     return TQ_ERR_UNSUPPORTED;
@@ -774,7 +762,7 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     uint16_t* h = reinterpret_cast<uint16_t*>(ws + W.h);
     float* yd = reinterpret_cast<float*>(ws + W.yd);
 
-    // tile choice: rows per expert on average decide between the 32-row and the 128-row tile
+    // tile choice: rows per expert on average decide between the 32-row tile and the large (64/128-row) tiles
     const int64_t avg_rows = (int64_t)W.a_tot / (L.E + L.S);
     bool large = avg_rows > 48;
     if (flags & TQ_FLAG_FORCE_SMALL_TILE) large = false;
@@ -783,7 +771,7 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     const int rt128 = W.a_tot / 128 + L.E + L.S;
     const int rt64 = W.a_tot / 64 + L.E + L.S;
     const int gs = L.g / 16;
-    const bool persist = tqi_prefill_supported(L, W, T) && !getenv("TQ_NO_PERSIST");
+    const bool persist = tqi_prefill_supported(L, W, T);
 
     // decode batches (a handful of rows per expert): the weight-streaming 16-row path, no pre-pass over K
     bool skinny = !large && avg_rows <= 12 && !(flags & TQ_FLAG_FORCE_SMALL_TILE);
@@ -804,22 +792,20 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     TQ_CHECK_LAUNCH();
     tqi_record_stage(2, stream);
     tq_status rc;
-    // 128-row tiles: eight waves of 64x64 (two per SIMD, accumulators in VGPRs); groups of 256 need too many
-    // registers for that and run as four waves of 128x64
+    // many rows per expert: persistent 64-row-tile workgroups (tq_prefill.hip) when the layer qualifies, else one
+    // workgroup per 64-row tile; groups of 256 need more registers than two workgroups per CU leave and run
+    // as four waves of 128x64 on 128-row tiles
     if (large && gs == 16)
         rc = launch_main<4, 1, 0, 16>(G, L.gu, blob, x, xaug_gu, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max,
                                       offsets, ctrl, 2, h, W.ka_gu, 1, rt128, stream);
     else if (large && persist)
         rc = tqi_forward_prefill_stage(0, L, W, G, blob, x, xaug_gu, row_token, tile_e + 3 * (size_t)W.rt_max,
                                        tile_row0 + 3 * (size_t)W.rt_max, offsets, ctrl, 5, h, stream);
-    else if (large && !getenv("TQ_TILE128"))
+    else if (large)
         // 64-row tiles, four waves of 64x64: two such workgroups share a CU and run out of phase, so one's
         // per-unit tail (fold, staging store, barrier) overlaps the other's MFMAs
         rc = launch_main_gs<2, 1, 0>(gs, G, L.gu, blob, x, xaug_gu, row_token, tile_e + 3 * (size_t)W.rt_max,
                                      tile_row0 + 3 * (size_t)W.rt_max, offsets, ctrl, 5, h, W.ka_gu, 1, rt64, stream);
-    else if (large)
-        rc = launch_main_gs<2, 2, 0>(gs, G, L.gu, blob, x, xaug_gu, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max, offsets,
-                                  ctrl, 2, h, W.ka_gu, 1, rt128, stream);
     else
         rc = launch_main_gs<1, 1, 0>(gs, G, L.gu, blob, x, xaug_gu, row_token, tile_e, tile_row0, offsets, ctrl, 1, h, W.ka_gu, 1,
                                   rt32, stream);
@@ -844,12 +830,9 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     else if (large && persist)
         rc = tqi_forward_prefill_stage(1, L, W, G, blob, h, xaug_d, row_token, tile_e + 3 * (size_t)W.rt_max,
                                        tile_row0 + 3 * (size_t)W.rt_max, offsets, ctrl, 5, yd, stream);
-    else if (large && !getenv("TQ_TILE128"))
+    else if (large)
         rc = launch_main_gs<2, 1, 1>(gs, G, L.d, blob, h, xaug_d, row_token, tile_e + 3 * (size_t)W.rt_max,
                                      tile_row0 + 3 * (size_t)W.rt_max, offsets, ctrl, 5, yd, W.ka_d, 1, rt64, stream);
-    else if (large)
-        rc = launch_main_gs<2, 2, 1>(gs, G, L.d, blob, h, xaug_d, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max, offsets,
-                                  ctrl, 2, yd, W.ka_d, 1, rt128, stream);
     else
         rc = launch_main_gs<1, 1, 1>(gs, G, L.d, blob, h, xaug_d, row_token, tile_e, tile_row0, offsets, ctrl, 1, yd, W.ka_d,
                                   nsplit, rt32, stream);

@@ -16,14 +16,6 @@
 
 #include <type_traits>
 
-#ifdef TQ_TIMING
-__device__ unsigned long long g_ptiming[512 * 64];
-extern "C" int tq_debug_read_ptiming(void* dst, size_t bytes) { return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_ptiming), bytes); }
-#define TQ_PT(k) do { if (STAGE == 0 && tid == 0 && item_no < 15) g_ptiming[blockIdx.x * 64 + item_no * 4 + (k)] = wall_clock64(); } while (0)
-#else
-#define TQ_PT(k) do { } while (0)
-#endif
-
 namespace {
 
 using namespace tqdev;
@@ -209,9 +201,7 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
     int gstep = 0;      // steps done so far; step s reads LDS buffer s & 1
     int par = 0;        // parity of the current item (selects its row ids in LDS)
 
-    int item_no = 0;
     for (;;) {
-        TQ_PT(0);
         const int qn = q + wgx;
         const bool has_next = qn < items_x;
         // next item: its tile header was fetched one item ago, its row ids are requested now and written to
@@ -269,7 +259,6 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
             ++gstep;
         }
 
-        TQ_PT(1);
         // row ids of the next item (visible to everyone after the next barrier; first used at the last unit)
         if (tid < BM) {
             tok[((par ^ 1) * 2 + 0) * BM + tid] = ntx;
@@ -383,7 +372,6 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
         }
         if (mu < nmain) main_unit(mu, std::integral_constant<int, 0>{});
 
-        TQ_PT(2);
         // the first augmented unit of the next item and its correction operands travel during the epilogue
         // (when there is no next item this reloads the current one: harmless)
         set_rows(has_next ? par ^ 1 : par, 1, (uint32_t)ka * 2u);
@@ -424,11 +412,6 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
             };
             if (full) emit(std::true_type{}); else emit(std::false_type{});
         }
-        TQ_PT(3);
-        ++item_no;
-#ifdef TQ_TIMING
-        if (STAGE == 0 && tid == 0) { g_ptiming[blockIdx.x * 64 + 60] = item_no; g_ptiming[blockIdx.x * 64 + 61] = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11)); g_ptiming[blockIdx.x * 64 + 62] = wall_clock64(); }
-#endif
         if (!has_next) break;
         clear_acc();
         store_x((gstep + 1) & 1);

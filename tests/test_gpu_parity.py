@@ -194,7 +194,7 @@ def test_forward_fp32_config1():
 
 
 @pytest.mark.parametrize("flags", [tq.TQ_FLAG_FORCE_SMALL_TILE, tq.TQ_FLAG_FORCE_LARGE_TILE, tq.TQ_FLAG_FORCE_SKINNY, 0],
-                         ids=["tile32", "tile128", "tile16", "auto"])
+                         ids=["tile32", "tile_large", "tile16", "auto"])
 @pytest.mark.parametrize("name", list(SMALL))
 def test_forward_bf16_small_layers(name, flags):
     got, ref = run_forward(SMALL[name], tq.TQ_ACT_BF16, flags)
@@ -202,7 +202,7 @@ def test_forward_bf16_small_layers(name, flags):
 
 
 @pytest.mark.parametrize("flags", [tq.TQ_FLAG_FORCE_SMALL_TILE, tq.TQ_FLAG_FORCE_LARGE_TILE, tq.TQ_FLAG_FORCE_SKINNY],
-                         ids=["tile32", "tile128", "tile16"])
+                         ids=["tile32", "tile_large", "tile16"])
 def test_forward_bf16_config1(flags):
     got, ref = run_forward(CONFIGS[1], tq.TQ_ACT_BF16, flags)
     err = rel_err(got, ref)
@@ -211,7 +211,7 @@ def test_forward_bf16_config1(flags):
 
 
 @pytest.mark.parametrize("flags", [tq.TQ_FLAG_FORCE_SMALL_TILE, tq.TQ_FLAG_FORCE_LARGE_TILE, tq.TQ_FLAG_FORCE_SKINNY],
-                         ids=["tile32", "tile128", "tile16"])
+                         ids=["tile32", "tile_large", "tile16"])
 def test_forward_bf16_is_run_to_run_deterministic(flags):
     cfg = SMALL["ragged"]
     a, _ = run_forward(cfg, tq.TQ_ACT_BF16, flags)
