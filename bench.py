@@ -24,7 +24,7 @@ MFMA_BF16_PEAK = 2.5e15    # FLOP/s dense bf16, MI355X published
 # HBM bytes per launch of the dominant kernel from the rocprofv3 FETCH_SIZE + WRITE_SIZE passes (scaled by the
 # streaming-copy calibration), see profiles/hbm_traffic_config2_skinny_kernels.txt.  Only the decode workload
 # has been counted; other workloads report null.
-MEASURED_TRAFFIC_BYTES = {2: 519.3e6 + 1.0e6}
+MEASURED_TRAFFIC_BYTES = {2: 538.5e6 + 1.0e6}
 STAGES = ["permute", "aug_gate_up", "gate_up", "aug_down", "down", "combine"]
 
 
@@ -229,7 +229,7 @@ def main():
                         path_frac=round(work["path_bytes"] / (ms_per_step * 1e-3) / HBM_PEAK, 4))
     else:
         ach = work["gate_up_flops"] / t_gu / 1e12
-        roofline = dict(bound="mfma", kernel="gate/up stage (moe_mfma_kernel<.,.,0,.>)", achieved=round(ach, 1),
+        roofline = dict(bound="mfma", kernel="gate/up stage (moe_prefill_kernel<0,.>, or moe_mfma_kernel<.,.,0,.> where the layer does not qualify)", achieved=round(ach, 1),
                         peak=MFMA_BF16_PEAK / 1e12, unit="TFLOP/s", frac=round(ach / (MFMA_BF16_PEAK / 1e12), 4),
                         traffic=None,
                         path_achieved=round(work["path_flops"] / (ms_per_step * 1e-3) / 1e12, 1),

@@ -312,17 +312,33 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
     int32_t* offs = counts + ne;
     int32_t* cursor = offs + ne + 1;
     int32_t* tsm = cursor + E;
+    // everything this wave reads from memory is requested first (one round trip instead of three): the
+    // assignments and weights of up to four rounds of 64, and the blob header
+    constexpr int NR = TQ_PERM_CHUNK / 64;
+    int ev[NR];
+    float wv[NR];
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {
+        const int a = j * 64 + lane;
+        const int ac = min(a, n_assign - 1);
+        ev[j] = idx[ac];
+        wv[j] = w ? w[ac] : 1.0f;
+        if (a >= n_assign) ev[j] = -2;               // past the end: neither counted nor flagged
+    }
+    TqBlobHeader hv = expect;
+    if (check_blob) hv = *hdr;
     if (ctrl) ctrl[lane] = 0;
     for (int e = lane; e < ne; e += 64) counts[e] = e < E ? 0 : T;
     __syncthreads();
     bool bad = false;
-    for (int a = lane; a < n_assign; a += 64) {
-        int e = idx[a];
-        if (e >= 0 && e < E) atomicAdd(&counts[e], 1); else bad = true;
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {
+        if (ev[j] >= 0 && ev[j] < E) atomicAdd(&counts[ev[j]], 1);
+        else if (ev[j] != -2) { bad = true; ev[j] = -1; }
     }
     __syncthreads();
     int flags = __ballot(bad) ? TQ_FLAG_BIT_RANGE : 0;
-    if (check_blob && !blob_header_ok(hdr, expect)) flags |= TQ_FLAG_BIT_BLOB;
+    if (check_blob && !blob_header_ok(&hv, expect)) flags |= TQ_FLAG_BIT_BLOB;
     int total = wave_excl_scan(counts, offs, ne, lane, [](int v) { return v; });
     __syncthreads();
     for (int e = lane; e <= ne; e += 64) offsets[e] = offs[e];
@@ -331,8 +347,33 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
     if (ctrl && lane == 0) ctrl[3] = total;
     if (tile_e) build_tile_tables(offs, tsm, ne, tile_e, tile_row0, rt_max, ctrl, lane, 64);
     __syncthreads();
-    for (int a0 = 0; a0 < n_assign; a0 += TQ_PERM_CHUNK)
-        scatter_chunk(idx, w, a0, n_assign, E, k, cursor, lane, slot_of, slot_stride, src_of, row_token, row_w);
+    // stable placement, 64 assignments per round in order (same ranking as scatter_chunk, from registers)
+#pragma unroll
+    for (int j = 0; j < NR; ++j) {
+        if (j * 64 >= n_assign) break;
+        const int a = j * 64 + lane;
+        const int e = ev[j] >= 0 ? ev[j] : -1;
+        uint64_t same = __ballot(e >= 0);
+        for (int bit = 0; (1 << bit) < E; ++bit) {
+            const uint64_t bal = __ballot((e >> bit) & 1);
+            same &= ((e >> bit) & 1) ? bal : ~bal;
+        }
+        const int before = __popcll(same & ((1ull << lane) - 1ull));
+        const bool last = (same >> lane) <= 1ull;
+        const int slot = e >= 0 ? cursor[e] + before : -1;
+        __syncthreads();
+        if (e >= 0 && last) cursor[e] = slot + 1;
+        __syncthreads();
+        if (a < n_assign) {
+            const int t = a / k, jj = a % k;
+            if (slot_of) slot_of[(size_t)t * slot_stride + jj] = slot;
+            if (slot >= 0) {
+                if (src_of) src_of[slot] = (int32_t)a;
+                if (row_token) row_token[slot] = t;
+                if (row_w) row_w[slot] = wv[j];
+            }
+        }
+    }
     for (int i = lane; i < S * T; i += 64) {
         int s = i / T, t = i % T;
         int slot = offs[E + s] + t;
