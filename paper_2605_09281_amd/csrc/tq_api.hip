@@ -107,7 +107,8 @@ extern "C" tq_status tq_moe_forward(const tq_layer_desc* desc, const void* packe
                                       (int32_t*)(ws + W.slot_of), L.k + L.S, nullptr,
                                       (int32_t*)(ws + W.row_token), (float*)(ws + W.row_w),
                                       (int32_t*)(ws + W.tile_e), (int32_t*)(ws + W.tile_row0), W.rt_max, ctrl,
-                                      ctrl, (int32_t*)(ws + W.hist), W.nblk, packed, &L, st);
+                                      ctrl, (int32_t*)(ws + W.hist), W.nblk, packed, &L,
+                                      (int32_t*)(ws + W.sk_cnt), W.sk_cnt_n, st);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(1, st);
     if (desc->act_dtype == TQ_ACT_FP32)

@@ -98,6 +98,8 @@ struct TqWorkspace {
     size_t h;           // bf16 [A_tot][F]  or fp32 [A_tot][F]
     size_t yd;          // fp32 [nsplit][A_tot][H]
     size_t tpart;       // fp32 partial low-rank intermediates of the decode path (only for small batches)
+    size_t sk_cnt;      // decode path: next-pair counters [2 stages][rt_max][TQ_MAX_SPLIT], cleared by the permutation
+    int32_t sk_cnt_n;   // their number (0 when the batch is too large for the decode path)
     size_t total;
     int32_t a_tot, rt_max, nblk, ka_gu, ka_d, nsplit_max;
 };
@@ -151,9 +153,17 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
             const size_t nat = (size_t)(2 * L.r16 + 31) / 32;
             W->tpart = take((size_t)(a_tot / 16 + L.E + L.S) * slices * nat * 512 * 4);
         }
+        W->sk_cnt = off;
+        W->sk_cnt_n = 0;
+        if (a_tot <= TQ_SKINNY_MAX_ROWS) {
+            W->sk_cnt_n = 2 * W->rt_max * TQ_MAX_SPLIT;
+            W->sk_cnt = take((size_t)W->sk_cnt_n * 4);
+        }
     } else {
         W->xaug_gu = W->xaug_d = off;
         W->tpart = off;
+        W->sk_cnt = off;
+        W->sk_cnt_n = 0;
         W->h = take((size_t)a_tot * L.F * 4);
         W->yd = take((size_t)a_tot * L.H * 4);
     }
@@ -185,7 +195,7 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
                              int32_t* src_of, int32_t* row_token, float* row_w, int32_t* tile_e,
                              int32_t* tile_row0, int32_t rt_max, int32_t* ctrl, int32_t* err_flag,
                              int32_t* hist, int32_t nblk, const void* blob, const TqLayout* L,
-                             hipStream_t stream);
+                             int32_t* zero_buf, int32_t zero_n, hipStream_t stream);
 tq_status tqi_forward_f32(const TqLayout& L, const TqWorkspace& W, const uint8_t* blob, const float* x,
                           int32_t T, float* y, uint8_t* ws, hipStream_t stream, const float* topk_w);
 tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, const uint8_t* blob,

@@ -304,7 +304,7 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
                                                            int rt_max, int32_t* __restrict__ ctrl,
                                                            int32_t* __restrict__ err_flag,
                                                            const TqBlobHeader* __restrict__ hdr, TqBlobHeader expect,
-                                                           int check_blob)
+                                                           int check_blob, int32_t* __restrict__ zero_buf, int zero_n)
 {
     extern __shared__ int32_t sm[];   // counts[ne] | offs[ne+1] | cursor[E] | tile scratch 3*(ne+1)
     const int ne = E + S, lane = threadIdx.x;
@@ -328,6 +328,7 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
     TqBlobHeader hv = expect;
     if (check_blob) hv = *hdr;
     if (ctrl) ctrl[lane] = 0;
+    for (int i = lane; i < zero_n; i += 64) zero_buf[i] = 0;
     for (int e = lane; e < ne; e += 64) counts[e] = e < E ? 0 : T;
     __syncthreads();
     bool bad = false;
@@ -384,9 +385,10 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
     if (flags && lane == 0 && err_flag) atomicOr(err_flag, flags);
 }
 
-__global__ void clear_ctrl_kernel(int32_t* ctrl, int32_t* err_flag)
+__global__ void clear_ctrl_kernel(int32_t* ctrl, int32_t* err_flag, int32_t* zero_buf, int zero_n)
 {
     if (threadIdx.x < 64 && ctrl) ctrl[threadIdx.x] = 0;
+    for (int i = threadIdx.x; i < zero_n; i += blockDim.x) zero_buf[i] = 0;
     if (threadIdx.x == 0 && err_flag && err_flag != ctrl) *err_flag = 0;
 }
 
@@ -397,7 +399,7 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
                              int32_t* src_of, int32_t* row_token, float* row_w, int32_t* tile_e,
                              int32_t* tile_row0, int32_t rt_max, int32_t* ctrl, int32_t* err_flag,
                              int32_t* hist, int32_t nblk, const void* blob, const TqLayout* L,
-                             hipStream_t stream)
+                             int32_t* zero_buf, int32_t zero_n, hipStream_t stream)
 {
     const int64_t n_assign = (int64_t)T * k;
     TqBlobHeader expect = {};
@@ -413,12 +415,12 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
         const size_t sm = ((size_t)ne + (ne + 1) + E + TQ_N_TILINGS * (ne + 1)) * 4;
         hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(64), sm, stream, topk_idx, topk_w, (int)n_assign, E, S,
                            T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e, tile_row0, rt_max,
-                           ctrl, err_flag, (const TqBlobHeader*)blob, expect, check);
+                           ctrl, err_flag, (const TqBlobHeader*)blob, expect, check, zero_buf, (int)zero_n);
         TQ_CHECK_LAUNCH();
         return TQ_OK;
     }
     if (ctrl) {
-        hipLaunchKernelGGL(clear_ctrl_kernel, dim3(1), dim3(64), 0, stream, ctrl, err_flag);
+        hipLaunchKernelGGL(clear_ctrl_kernel, dim3(1), dim3(64), 0, stream, ctrl, err_flag, zero_buf, (int)zero_n);
         TQ_CHECK_LAUNCH();
     }
     hipLaunchKernelGGL(hist_kernel, dim3(nblk), dim3(64), (size_t)E * 4, stream, topk_idx, n_assign, E, hist,
@@ -475,5 +477,5 @@ extern "C" tq_status tq_permute(const int32_t* topk_idx, int32_t T, int32_t E, i
     if (nblk < 1) nblk = 1;
     return tqi_launch_permute(topk_idx, nullptr, T, E, 0, k, offsets, slot_of, k, src_of, nullptr, nullptr,
                               nullptr, nullptr, 0, nullptr, err_flag, (int32_t*)workspace, (int32_t)nblk, nullptr,
-                              nullptr, (hipStream_t)stream);
+                              nullptr, nullptr, 0, (hipStream_t)stream);
 }

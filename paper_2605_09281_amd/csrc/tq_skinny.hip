@@ -84,8 +84,8 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
                                                          const int32_t* __restrict__ offsets,
                                                          const int32_t* __restrict__ ctrl,
                                                          const float* __restrict__ tpart, int n_slices, int na_tiles,
-                                                         void* __restrict__ out, int pairs_per_wg,
-                                                         int units_per_split, int RB, int red_off, int xs_off)
+                                                         void* __restrict__ out, int32_t* __restrict__ pair_cnt,
+                                                         int units_per_split, int RB, int red_off, int xs_off, int mb_off)
 {
     constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
     constexpr int UC = UNIT_K / 64;
@@ -112,8 +112,16 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     int nuw = min(UPW, ue - (ub + wave * UPW));     // units of this wave (0 for idle waves)
     if (nuw < 0) nuw = 0;
     const int wk0 = wave * UPW * US;                // first MFMA step of this wave inside the workgroup's range
-    const int p0 = blockIdx.x * pairs_per_wg;
-    const int p1 = min(sec.pairs, p0 + pairs_per_wg);
+    // Column-tile pairs are dealt out dynamically among the workgroups of this (tile, split): the first one is the
+    // workgroup's index, every further one comes from a counter (cleared by the permutation), fetched one pair
+    // ahead of its use so that the weight prefetch knows where to go.  Workgroups that get a better share of the
+    // memory system take more pairs, and all of them finish together.
+    const int npairs = sec.pairs;
+    const int p0 = blockIdx.x;
+    int32_t* cnt = pair_cnt + (size_t)rt * TQ_MAX_SPLIT + split;
+    int* pq = reinterpret_cast<int*>(lds + mb_off);            // two mailbox words
+    int got_v = 0;
+    if (tid == 0) got_v = (int)gridDim.x + atomicAdd(cnt, 1);
 
     const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
     const u32x4* codes = reinterpret_cast<const u32x4*>(rec + sec.codes) + lane;
@@ -224,6 +232,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     u32x4 bq[2];
     load_b(bq, p0);
 
+    if (tid == 0) pq[0] = got_v;
     lds_barrier();
     const int xrow_off = min(col & 15, rows - 1) * RB;
     auto lds_x = [&](int kl) -> bf16x8 {       // fragment of MFMA step kl (relative to the workgroup's range)
@@ -274,8 +283,12 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     lds_barrier();     // xs is complete; tbuf has been read: the reduction buffer may be reused
 
     // ---- 4. the stream over this workgroup's column-tile pairs
-    for (int pair = p0; pair < p1; ++pair) {
-        const int pnext = min(pair + 1, p1 - 1);
+    int pnext_raw = pq[0];
+    int it = 0;
+    for (int pair = p0; pair < npairs;) {
+        const int pnext = min(pnext_raw, npairs - 1);
+        int fetched = 0;
+        if (tid == 0) fetched = (int)gridDim.x + atomicAdd(cnt, 1);       // the pair after the next one
         float acc8[2][8];
 #pragma unroll
         for (int t = 0; t < 2; ++t)
@@ -371,6 +384,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
                         mine[(t * 7 + slot) * 64 + lane] = acc8[t][v];
                     }
                 }
+            if (tid == 0) pq[(it + 1) & 1] = fetched;
         }
         lds_barrier();
         {
@@ -405,6 +419,9 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
             }
         }
         lds_barrier();
+        pair = pnext_raw;
+        pnext_raw = pq[(it + 1) & 1];
+        ++it;
     }
 }
 
@@ -412,14 +429,16 @@ template <int STAGE, int GS>
 tq_status launch_skinny(const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin,
                         const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
                         const int32_t* offsets, const int32_t* ctrl, float* tpart, int n_slices, int na_tiles,
-                        void* out, int row_tiles, int nsplit, int units_per_split, int tiles_est, hipStream_t st)
+                        void* out, int32_t* pair_cnt, int row_tiles, int nsplit, int units_per_split, int tiles_est,
+                        hipStream_t st)
 {
     constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
     const int range_k = units_per_split * UNIT_K;
     const int RB = range_k * 2 + 16;
     const int red_off = 16 * RB;
     const int xs_off = red_off + SK_RED_BYTES;
-    const size_t smem = (size_t)xs_off + (size_t)(range_k / G.g) * 16 * 4;
+    const int mb_off = xs_off + (range_k / G.g) * 16 * 4;      // mailbox of the pair scheduler
+    const size_t smem = (size_t)mb_off + 16;
     if (smem > 160 * 1024) return TQ_ERR_UNSUPPORTED;
     auto kern = moe_skinny_kernel<STAGE, GS>;
     static bool done = false;
@@ -445,7 +464,7 @@ tq_status launch_skinny(const MGeom& G, const TqSection& sec, const uint8_t* blo
     dim3 grid((sec.pairs + ppw - 1) / ppw, row_tiles, nsplit);
     if (grid.y > 65535) return TQ_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl,
-                       (const float*)tpart, n_slices, na_tiles, out, ppw, units_per_split, RB, red_off, xs_off);
+                       (const float*)tpart, n_slices, na_tiles, out, pair_cnt, units_per_split, RB, red_off, xs_off, mb_off);
     TQ_CHECK_LAUNCH();
     return TQ_OK;
 }
@@ -454,13 +473,14 @@ template <int STAGE>
 tq_status launch_skinny_gs(int gs, const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin,
                            const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
                            const int32_t* offsets, const int32_t* ctrl, float* tpart, int n_slices, int na_tiles,
-                           void* out, int row_tiles, int nsplit, int units_per_split, int tiles_est, hipStream_t st)
+                           void* out, int32_t* pair_cnt, int row_tiles, int nsplit, int units_per_split, int tiles_est,
+                           hipStream_t st)
 {
     switch (gs) {
-        case 2: return launch_skinny<STAGE, 2>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, row_tiles, nsplit, units_per_split, tiles_est, st);
-        case 4: return launch_skinny<STAGE, 4>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, row_tiles, nsplit, units_per_split, tiles_est, st);
-        case 8: return launch_skinny<STAGE, 8>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, row_tiles, nsplit, units_per_split, tiles_est, st);
-        case 16: return launch_skinny<STAGE, 16>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, row_tiles, nsplit, units_per_split, tiles_est, st);
+        case 2: return launch_skinny<STAGE, 2>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, pair_cnt, row_tiles, nsplit, units_per_split, tiles_est, st);
+        case 4: return launch_skinny<STAGE, 4>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, pair_cnt, row_tiles, nsplit, units_per_split, tiles_est, st);
+        case 8: return launch_skinny<STAGE, 8>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, pair_cnt, row_tiles, nsplit, units_per_split, tiles_est, st);
+        case 16: return launch_skinny<STAGE, 16>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, pair_cnt, row_tiles, nsplit, units_per_split, tiles_est, st);
     }
     return TQ_ERR_UNSUPPORTED;
 }
@@ -491,7 +511,7 @@ bool tqi_skinny_supported(const TqLayout& L)
     const int unit_k = L.g < 64 ? 64 : L.g;
     auto smem = [&](int units) {
         const int range_k = units * unit_k;
-        return (size_t)16 * (range_k * 2 + 16) + SK_RED_BYTES + (size_t)(range_k / L.g) * 64;
+        return (size_t)16 * (range_k * 2 + 16) + SK_RED_BYTES + (size_t)(range_k / L.g) * 64 + 16;
     };
     if (smem(ups) > 160 * 1024) return false;
     plan_split(L.F, L.g, &ns, &ups);
@@ -529,8 +549,10 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
         TQ_CHECK_LAUNCH();
     }
     tqi_record_stage(2, stream);
+    int32_t* pair_cnt = reinterpret_cast<int32_t*>(ws + W.sk_cnt);
+    if (W.sk_cnt_n < 2 * W.rt_max * TQ_MAX_SPLIT) return TQ_ERR_UNSUPPORTED;
     tq_status rc = launch_skinny_gs<0>(gs, G, L.gu, blob, x, row_token, tile_e, tile_row0, offsets, ctrl, tpart, sl_gu, nat_gu,
-                                       h, rt16, 1, ups, tiles_est, stream);
+                                       h, pair_cnt, rt16, 1, ups, tiles_est, stream);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(3, stream);
     if (L.r > 0) {
@@ -540,8 +562,8 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     }
     tqi_record_stage(4, stream);
     plan_split(L.F, L.g, &ns, &ups);
-    rc = launch_skinny_gs<1>(gs, G, L.d, blob, h, row_token, tile_e, tile_row0, offsets, ctrl, tpart, sl_d, nat_d, yd, rt16,
-                             ns, ups, tiles_est, stream);
+    rc = launch_skinny_gs<1>(gs, G, L.d, blob, h, row_token, tile_e, tile_row0, offsets, ctrl, tpart, sl_d, nat_d, yd,
+                             pair_cnt + (size_t)W.rt_max * TQ_MAX_SPLIT, rt16, ns, ups, tiles_est, stream);
     if (rc != TQ_OK) return rc;
     *nsplit_out = ns;
     return TQ_OK;
