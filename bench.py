@@ -24,7 +24,7 @@ MFMA_BF16_PEAK = 2.5e15    # FLOP/s dense bf16, MI355X published
 # HBM bytes per launch of the dominant kernel from the rocprofv3 FETCH_SIZE + WRITE_SIZE passes (scaled by the
 # streaming-copy calibration), see profiles/hbm_traffic_config2_skinny_kernels.txt.  Only the decode workload
 # has been counted; other workloads report null.
-MEASURED_TRAFFIC_BYTES = {2: 538.5e6 + 1.0e6}
+MEASURED_TRAFFIC_BYTES = {2: 538.3e6 + 1.0e6}
 STAGES = ["permute", "aug_gate_up", "gate_up", "aug_down", "down", "combine"]
 
 

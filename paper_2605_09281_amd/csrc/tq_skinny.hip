@@ -286,7 +286,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     int pnext_raw = pq[0];
     int it = 0;
     for (int pair = p0; pair < npairs;) {
-        const int pnext = min(pnext_raw, npairs - 1);
+        const int pnext = pnext_raw < npairs ? pnext_raw : pair;     // nothing left: re-request this pair (cache hits)
         int fetched = 0;
         if (tid == 0) fetched = (int)gridDim.x + atomicAdd(cnt, 1);       // the pair after the next one
         float acc8[2][8];
