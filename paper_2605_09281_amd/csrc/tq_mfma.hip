@@ -226,16 +226,22 @@ __global__ void __launch_bounds__(256, 2) aug_staged_kernel(MGeom G, TqSection s
     store_chunk(0);
     lds_barrier();
     for (int c = 0; c < nchunks; ++c) {
-        load_chunk(min(c + 1, nchunks - 1));
         const int gi = 4 * c + wave;
         const int buf = c & 1;
-        if (gi < groups) {
-            u32x4 aq[GS][NAT];
+        // The factor fragments of this chunk are requested BEFORE the next chunk's rows: loads return in order, and
+        // behind the gathered rows (memory-side cache or HBM) these L2 hits would wait for them.  Unconditional
+        // with a clamped group, so that the compiler can count them.
+        u32x4 aq[GS][NAT];
+        {
+            const int gic = min(gi, groups - 1);
 #pragma unroll
             for (int ks = 0; ks < GS; ++ks)
 #pragma unroll
                 for (int j = 0; j < NAT; ++j)
-                    aq[ks][j] = af[((size_t)min(j, max(na_tiles, 1) - 1) * ksteps + gi * GS + ks) * 64];
+                    aq[ks][j] = af[((size_t)min(j, max(na_tiles, 1) - 1) * ksteps + gic * GS + ks) * 64];
+        }
+        load_chunk(min(c + 1, nchunks - 1));
+        if (gi < groups) {
             Frag xa[GS];
 #pragma unroll
             for (int ks = 0; ks < GS; ++ks)
