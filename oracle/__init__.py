@@ -175,3 +175,27 @@ def moe_forward_layer(layer, x: np.ndarray, idx: np.ndarray, w: np.ndarray,
     c = layer.cfg
     return moe_forward(c.E, c.S, c.k, c.H, c.F, c.g, c.bits, c.r, layer.codes, layer.scale, layer.zero,
                        layer.A if c.r else None, layer.B if c.r else None, x, idx, w, tokens)
+
+
+def lotile_forward(x: np.ndarray, us_bits: np.ndarray, v_bits: np.ndarray, phi: np.ndarray,
+                   idx: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """LoTileMoE of Section 3.2 (three-dimensional accumulator form).  x [T, in] fp32; us_bits [M, in, r] and
+    v_bits [N, r, out] fp16 bit patterns; phi [E, 2] int32; idx, w [T, k].  Returns y [T, out] fp64."""
+    L = lib()
+    if not getattr(L, "_lotile_ready", False):
+        L.orc_lotile_forward.restype = None
+        L.orc_lotile_forward.argtypes = [ctypes.c_int32] * 7 + [ctypes.c_void_p] * 7
+        L._lotile_ready = True
+    x = _c(x, np.float32)
+    us_bits = _c(us_bits, np.uint16)
+    v_bits = _c(v_bits, np.uint16)
+    phi = _c(phi, np.int32)
+    idx = _c(idx, np.int32)
+    w = _c(w, np.float32)
+    T, n_in = x.shape
+    M, _, r = us_bits.shape
+    N, _, n_out = v_bits.shape
+    k = idx.shape[1]
+    y = np.zeros((T, n_out), dtype=np.float64)
+    L.orc_lotile_forward(T, n_in, n_out, M, N, r, k, _p(x), _p(us_bits), _p(v_bits), _p(phi), _p(idx), _p(w), _p(y))
+    return y

@@ -16,7 +16,10 @@
  *     ("element-wise") form of Appendix A.3 / A.4, with the input-side scaling s_k and Sigma
  *     already folded into the left factor offline (Algorithm 1);
  *   - group-wise scalar quantisation with one scale per group of g weights: Appendix A.3
- *     ("Basic Quantization").
+ *     ("Basic Quantization");
+ *   - orc_lotile_forward: the fused low-rank path over shared 2D-tiled factors, LoTileMoE of
+ *     Section 3.2 in its defining three-dimensional accumulator form (the construction that ends
+ *     in Eq. 15), NOT the compact buffer of Eq. 16 that an implementation would use.
  * Readings taken where the paper is silent (stated once more in the repository's design notes):
  *   - routing weights are the softmax over the k selected logits (equal to softmax over all
  *     experts renormalised over the selected ones);
@@ -251,3 +254,58 @@ void orc_set_num_threads(int32_t n) { omp_set_num_threads(n); }
 int32_t orc_num_threads(void) { return 1; }
 void orc_set_num_threads(int32_t n) { (void)n; }
 #endif
+
+/*
+ * LoTileMoE (Section 3.2, the construction ending in Eq. 15; complexity in Appendix A.4), one linear
+ * map with an input shared by all experts:
+ *   x     [T][in]            activations (fp32 holding the values)
+ *   us    [M][in][r]  fp16   row-tile factors U_m Sigma  (the "(U Sigma)_reshape" of step one is us
+ *                            viewed as [in][M r])
+ *   v     [N][r][out] fp16   column-tile factors V_n     ("V_flat" is v viewed as [N r][out])
+ *   phi   [E][2]             expert -> (m, n)
+ *   idx,w [T][k]             selected experts and routing weights g_{b,t}
+ *   y     [T][out]           LoTileMoE(x)
+ * Steps, in the paper's order: X_proj = x (U Sigma)_reshape; X_tile = X_proj reshaped [T][M][r] and
+ * repeated N times along the last axis; the accumulator A [T][M][r N] is zero except that, for every
+ * (b, t), block n_{b,t} of row m_{b,t} receives g_{b,t} times the same block of X_tile (a second
+ * selection of the same tile by the same token adds to it - the paper's arrow leaves this open;
+ * with distinct top-k experts it cannot happen); Y3 = A V_reshape per row tile; y = sum over m.
+ */
+void orc_lotile_forward(int32_t T, int32_t n_in, int32_t n_out, int32_t M, int32_t N, int32_t r, int32_t k,
+                        const float *x, const uint16_t *us, const uint16_t *v, const int32_t *phi,
+                        const int32_t *idx, const float *w, double *y)
+{
+    const size_t Mr = (size_t)M * r, rN = (size_t)r * N;
+    double *xproj = (double *)malloc(sizeof(double) * Mr);
+    double *acc = (double *)malloc(sizeof(double) * (size_t)M * rN);
+    for (int32_t b = 0; b < T; ++b) {
+        /* step one: projection on every row tile's factor */
+        for (int32_t m = 0; m < M; ++m)
+            for (int32_t rho = 0; rho < r; ++rho) {
+                double a = 0.0;
+                for (int32_t i = 0; i < n_in; ++i)
+                    a += (double)x[(size_t)b * n_in + i] * orc_half_to_double(us[((size_t)m * n_in + i) * r + rho]);
+                xproj[(size_t)m * r + rho] = a;
+            }
+        /* the accumulator: routing-weighted copies of X_tile at the active tiles only */
+        memset(acc, 0, sizeof(double) * (size_t)M * rN);
+        for (int32_t t = 0; t < k; ++t) {
+            const int32_t e = idx[(size_t)b * k + t];
+            const int32_t m = phi[2 * e], n = phi[2 * e + 1];
+            for (int32_t rho = 0; rho < r; ++rho)
+                acc[(size_t)m * rN + (size_t)n * r + rho] += (double)w[(size_t)b * k + t] * xproj[(size_t)m * r + rho];
+        }
+        /* batched product with the reshaped V, then the sum over row tiles */
+        for (int32_t o = 0; o < n_out; ++o) y[(size_t)b * n_out + o] = 0.0;
+        for (int32_t m = 0; m < M; ++m)
+            for (int32_t n = 0; n < N; ++n)
+                for (int32_t rho = 0; rho < r; ++rho) {
+                    const double a = acc[(size_t)m * rN + (size_t)n * r + rho];
+                    if (a == 0.0) continue;       /* zero entries add nothing (keeps the brute force usable) */
+                    for (int32_t o = 0; o < n_out; ++o)
+                        y[(size_t)b * n_out + o] += a * orc_half_to_double(v[((size_t)n * r + rho) * n_out + o]);
+                }
+    }
+    free(xproj);
+    free(acc);
+}

@@ -240,3 +240,29 @@ def make_layer(cfg: LayerConfig, workers: int = 8) -> Layer:
         for e in range(ne):
             one(e)
     return Layer(cfg, codes, scale, zero, A, B)
+
+
+# ----------------------------------------------------------------------------- shared 2D-tiled factors
+_TID_LOTILE = 11
+
+
+def lotile_grid(E: int):
+    """The paper's near-square tile grid for E experts: M = round(sqrt(E)), N = ceil(E / M)."""
+    M = max(1, int(round(float(np.sqrt(E)))))
+    N = (E + M - 1) // M
+    return M, N
+
+
+def make_lotile(cfg: LayerConfig, n_in: int, n_out: int, M: Optional[int] = None, N: Optional[int] = None):
+    """Shared factors for one linear map of a layer shaped like `cfg`: us [M, n_in, r] and v [N, r, n_out] as fp16
+    bit patterns (values ~N(0, f_std)), and a placement phi [E, 2] that puts every expert on its own tile of the
+    M x N grid (a seeded permutation of the tiles).  Inputs only: no forward arithmetic."""
+    if M is None or N is None:
+        M, N = lotile_grid(cfg.E)
+    assert M * N >= cfg.E
+    rng = _rng(cfg.cfg_id, _TID_LOTILE)
+    us = (rng.standard_normal((M, n_in, cfg.r), dtype=np.float32) * cfg.f_std).astype(np.float16).view(np.uint16)
+    v = (rng.standard_normal((N, cfg.r, n_out), dtype=np.float32) * cfg.f_std).astype(np.float16).view(np.uint16)
+    tiles = rng.permutation(M * N)[:cfg.E]
+    phi = np.stack([tiles // N, tiles % N], axis=1).astype(np.int32)
+    return us, v, phi

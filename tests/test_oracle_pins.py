@@ -357,3 +357,112 @@ def test_benchmark_config_1_against_dense():
     y = oracle.moe_forward_layer(layer, x, idx, w, tokens=tok)
     ref = dense_moe(layer, x[tok], idx[tok], w[tok])
     assert rel_err(y, ref) < 1e-12
+
+
+# ------------------------------------------------------------------ LoTileMoE (Section 3.2)
+def _lotile_case(seed, T=7, E=6, k=3, n_in=20, n_out=12, r=5, M=2, N=3, distinct=True):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, n_in)).astype(np.float32)
+    us = (rng.standard_normal((M, n_in, r)) * 0.3).astype(np.float16)
+    v = (rng.standard_normal((N, r, n_out)) * 0.3).astype(np.float16)
+    tiles = rng.permutation(M * N)[:E]
+    phi = np.stack([tiles // N, tiles % N], axis=1).astype(np.int32)
+    if distinct:
+        idx = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    else:
+        idx = rng.integers(0, E, size=(T, k)).astype(np.int32)
+    w = rng.random((T, k)).astype(np.float32)
+    return x, us, v, phi, idx, w
+
+
+@pytest.mark.parametrize("seed,M,N,E", [(0, 2, 3, 6), (1, 3, 3, 7), (2, 1, 5, 5), (3, 4, 1, 4), (4, 3, 4, 12)])
+def test_lotile_equals_per_expert_definition(seed, M, N, E):
+    """Eq. 4 + Eq. 3: y_b = sum_t g_bt * x_b (U_m Sigma) V_n with (m, n) = phi(e_bt), one expert at a time."""
+    x, us, v, phi, idx, w = _lotile_case(seed, E=E, M=M, N=N, k=min(3, E))
+    got = oracle.lotile_forward(x, us.view(np.uint16), v.view(np.uint16), phi, idx, w)
+    usd, vd, xd = us.astype(np.float64), v.astype(np.float64), x.astype(np.float64)
+    ref = np.zeros_like(got)
+    for b in range(x.shape[0]):
+        for t in range(idx.shape[1]):
+            m, n = phi[idx[b, t]]
+            ref[b] += float(w[b, t]) * (xd[b] @ usd[m]) @ vd[n]
+    assert np.max(np.abs(got - ref)) <= 1e-12 * max(1.0, np.max(np.abs(ref)))
+
+
+def test_lotile_repeated_selection_adds():
+    """A token that lists the same expert twice: Eq. 3 sums over the selections, so the accumulator adds (the
+    assignment arrow in the construction of Eq. 15 is read as accumulation)."""
+    x, us, v, phi, idx, w = _lotile_case(21, T=6, E=3, k=4, M=2, N=2, distinct=False)
+    got = oracle.lotile_forward(x, us.view(np.uint16), v.view(np.uint16), phi, idx, w)
+    ref = np.zeros_like(got)
+    for b in range(x.shape[0]):
+        for t in range(idx.shape[1]):
+            m, n = phi[idx[b, t]]
+            ref[b] += float(w[b, t]) * (x[b].astype(np.float64) @ us[m].astype(np.float64)) @ v[n].astype(np.float64)
+    assert np.max(np.abs(got - ref)) <= 1e-12 * max(1.0, np.max(np.abs(ref)))
+
+
+def test_lotile_equals_compact_buffer_form():
+    """Eq. 16: S[b]^(n) = sum_{t: n_bt = n} g_bt X_proj[b]^(m_bt); Y = S V_flat - two dense products and a scatter."""
+    x, us, v, phi, idx, w = _lotile_case(11, T=9, E=9, k=4, M=3, N=3, r=4)
+    got = oracle.lotile_forward(x, us.view(np.uint16), v.view(np.uint16), phi, idx, w)
+    M, n_in, r = us.shape
+    N, _, n_out = v.shape
+    us_reshape = us.astype(np.float64).transpose(1, 0, 2).reshape(n_in, M * r)      # [in, M r]
+    v_flat = v.astype(np.float64).reshape(N * r, n_out)                               # [N r, out]
+    xproj = x.astype(np.float64) @ us_reshape
+    S = np.zeros((x.shape[0], N * r))
+    for b in range(x.shape[0]):
+        for t in range(idx.shape[1]):
+            m, n = phi[idx[b, t]]
+            S[b, n * r:(n + 1) * r] += float(w[b, t]) * xproj[b, m * r:(m + 1) * r]
+    ref = S @ v_flat
+    assert np.max(np.abs(got - ref)) <= 1e-12 * max(1.0, np.max(np.abs(ref)))
+
+
+def test_lotile_one_tile_per_expert_is_the_per_expert_lowrank_projection():
+    """M = N = E with phi(e) = (e, e) has no sharing: each term is the pinned per-expert low-rank chain
+    (oracle.project with a zero quantised part)."""
+    E, n_in, n_out, r, g = 4, 32, 8, 3, 16
+    x, us, v, _, idx, w = _lotile_case(5, T=5, E=E, k=2, n_in=n_in, n_out=n_out, r=r, M=E, N=E)
+    phi = np.stack([np.arange(E), np.arange(E)], axis=1).astype(np.int32)
+    got = oracle.lotile_forward(x, us.view(np.uint16), v.view(np.uint16), phi, idx, w)
+    codes = np.zeros((n_out, n_in), dtype=np.uint8)
+    zero_scale = np.zeros((n_out, n_in // g), dtype=np.float16).view(np.uint16)
+    ref = np.zeros_like(got)
+    for b in range(x.shape[0]):
+        for t in range(idx.shape[1]):
+            e = idx[b, t]
+            ref[b] += float(w[b, t]) * oracle.project(x[b].astype(np.float64), codes, zero_scale, zero_scale,
+                                                      us[e].view(np.uint16), v[e].view(np.uint16), g)
+    assert np.max(np.abs(got - ref)) <= 1e-12 * max(1.0, np.max(np.abs(ref)))
+
+
+def test_lotile_closed_forms():
+    x, us, v, phi, idx, w = _lotile_case(8, T=4, E=6, k=2, M=2, N=3)
+    # one-hot input, one selected expert: a row of U_m Sigma times V_n, scaled by g
+    xo = np.zeros_like(x)
+    xo[:, 3] = 1.0
+    i1 = idx[:, :1].copy()
+    w1 = w[:, :1].copy()
+    got = oracle.lotile_forward(xo, us.view(np.uint16), v.view(np.uint16), phi, i1, w1)
+    for b in range(4):
+        m, n = phi[i1[b, 0]]
+        ref = float(w1[b, 0]) * us[m, 3].astype(np.float64) @ v[n].astype(np.float64)
+        assert np.allclose(got[b], ref, rtol=0, atol=1e-14)
+    # linear in the routing weights and in x; independent of the order of the selected experts
+    y = oracle.lotile_forward(x, us.view(np.uint16), v.view(np.uint16), phi, idx, w)
+    y2 = oracle.lotile_forward(x, us.view(np.uint16), v.view(np.uint16), phi, idx, 2 * w)
+    assert np.allclose(y2, 2 * y, rtol=1e-13, atol=0)
+    yr = oracle.lotile_forward(x, us.view(np.uint16), v.view(np.uint16), phi, idx[:, ::-1].copy(), w[:, ::-1].copy())
+    assert np.allclose(yr, y, rtol=1e-13, atol=1e-15)
+    # two experts that share a column tile accumulate in the same block of the buffer; sharing a row tile reuses
+    # the same projection: with M = 1 every expert projects with U_0, with N = 1 every expert ends in V_0
+    x1, us1, v1, phi1, idx1, w1 = _lotile_case(9, T=3, E=4, k=4, M=1, N=4)
+    y1 = oracle.lotile_forward(x1, us1.view(np.uint16), v1.view(np.uint16), phi1, idx1, w1)
+    t = x1.astype(np.float64) @ us1[0].astype(np.float64)
+    ref = np.zeros_like(y1)
+    for b in range(3):
+        for j in range(4):
+            ref[b] += float(w1[b, j]) * t[b] @ v1[phi1[idx1[b, j], 1]].astype(np.float64)
+    assert np.allclose(y1, ref, rtol=1e-13, atol=1e-15)
