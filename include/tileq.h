@@ -180,6 +180,49 @@ tq_status tq_set_profile_events(void *const *events, int32_t n);
  * size and to measure the streaming rate the memory system attains. */
 tq_status tq_debug_stream(const void *src, void *dst, size_t bytes, int32_t mode, void *stream);
 
+/* ---------------------------------------------------------------------------------------------------
+ * LoTileMoE: the fused low-rank path over SHARED 2D-tiled factors (Section 3.2: Eq. 14 splits the layer into
+ * QMoE + LoTileMoE; the construction ending in Eq. 15 defines it, Eq. 16 is the compact buffer used here,
+ * Appendix A.4 its three steps).  One linear map whose input is shared by all experts:
+ *     y[b] = sum_t g[b,t] * ( x[b] (U_m Sigma) ) V_n ,   (m, n) = phi(e[b,t])
+ * evaluated as  X_proj = x (U Sigma)_reshape  [T, M r],  S[b]^(n) = sum_{t: n(b,t) = n} g[b,t] X_proj[b]^(m(b,t))
+ * [T, N r],  y = S V_flat  [T, out]: two dense products and one gather-scale-accumulate, no per-expert loop.
+ * Canonical inputs (device): us fp16 [M][n_in][r] = U_m Sigma, v fp16 [N][r][n_out] = V_n, phi int32 [E][2].
+ * n_in and n_out are multiples of 32, 1 <= r <= 256, M N >= E is not required (phi may share tiles).
+ * The packed form holds phi and both factors as bf16 (round to nearest even) in MFMA B-operand fragment
+ * order: element i of (column tile ct, step s, lane) = B[kk = 16 s + 8 (lane / 32) + i][32 ct + lane % 32],
+ * for B1 = (U Sigma)_reshape with every tile's r columns padded to rp = 16 ceil(r / 16) (zero), and for
+ * B2 = V_flat with its N r rows padded likewise. */
+typedef struct tq_lotile_desc {
+    int32_t n_experts; /* E */
+    int32_t tiles_m;   /* M row tiles (shared left factors) */
+    int32_t tiles_n;   /* N column tiles (shared right factors) */
+    int32_t n_in;      /* i */
+    int32_t n_out;     /* o */
+    int32_t rank;      /* r */
+    int32_t top_k;     /* experts per token */
+    int32_t flags;     /* 0 */
+} tq_lotile_desc;
+
+/* Bytes of the packed factors.  Host only; 0 if desc is invalid. */
+size_t tq_lotile_packed_size(const tq_lotile_desc *desc);
+
+/* Packs us, v, phi (device) into `packed` (device, 256-byte aligned).  err_flag (device int32, may be
+ * NULL): bit 0 is set when a phi entry is outside the M x N grid (it is then clamped into it). */
+tq_status tq_lotile_pack(const tq_lotile_desc *desc, const uint16_t *us, const uint16_t *v, const int32_t *phi,
+                         void *packed, size_t packed_bytes, int32_t *err_flag, void *stream);
+
+/* Bytes of workspace tq_lotile_forward needs for up to T tokens.  Host only; 0 if desc is invalid. */
+size_t tq_lotile_workspace_size(const tq_lotile_desc *desc, int32_t T);
+
+/* y[T, n_out] bf16 = LoTileMoE(x[T, n_in] bf16) for topk_idx / topk_w [T, top_k] as produced by tq_route.
+ * y is overwritten.  An expert index outside [0, E) contributes nothing and sets the first int32 of
+ * `workspace` (cleared at the start of the call).  Sums run in a fixed order: results are reproducible.
+ * T == 0 is a no-op. */
+tq_status tq_lotile_forward(const tq_lotile_desc *desc, const void *packed, const void *x,
+                            const int32_t *topk_idx, const float *topk_w, int32_t T, void *y,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

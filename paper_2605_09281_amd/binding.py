@@ -21,7 +21,8 @@ STATUS_NAMES = {0: "TQ_OK", 1: "TQ_ERR_NULL", 2: "TQ_ERR_SHAPE", 3: "TQ_ERR_ALIG
 
 EXPORTS = ["tq_status_str", "tq_packed_size", "tq_pack_weights", "tq_unpack_weights", "tq_route",
            "tq_permute_workspace_size", "tq_permute", "tq_moe_workspace_size", "tq_moe_forward",
-           "tq_set_profile_events", "tq_debug_stream"]
+           "tq_set_profile_events", "tq_debug_stream", "tq_lotile_packed_size", "tq_lotile_pack",
+           "tq_lotile_workspace_size", "tq_lotile_forward"]
 
 
 class TqError(RuntimeError):
@@ -33,6 +34,11 @@ class TqError(RuntimeError):
 class LayerDesc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("n_experts", "n_shared", "top_k", "hidden", "ffn", "group", "bits", "rank", "act_dtype", "flags")]
+
+
+class LoTileDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("n_experts", "tiles_m", "tiles_n", "n_in", "n_out", "rank", "top_k", "flags")]
 
 
 class _WeightsPtrs(ctypes.Structure):
@@ -79,6 +85,17 @@ def lib():
         L.tq_debug_stream.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_void_p]
         L.tq_set_profile_events.restype = ctypes.c_int
         L.tq_set_profile_events.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32]
+        L.tq_lotile_packed_size.restype = ctypes.c_size_t
+        L.tq_lotile_packed_size.argtypes = [ctypes.POINTER(LoTileDesc)]
+        L.tq_lotile_workspace_size.restype = ctypes.c_size_t
+        L.tq_lotile_workspace_size.argtypes = [ctypes.POINTER(LoTileDesc), ctypes.c_int32]
+        L.tq_lotile_pack.restype = ctypes.c_int
+        L.tq_lotile_pack.argtypes = [ctypes.POINTER(LoTileDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                     ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+        L.tq_lotile_forward.restype = ctypes.c_int
+        L.tq_lotile_forward.argtypes = [ctypes.POINTER(LoTileDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.c_size_t, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -179,3 +196,38 @@ def tq_set_profile_events(events) -> None:
 def tq_debug_stream(src, dst, nbytes: int, mode: int) -> None:
     """Streaming copy (mode 0) or read (mode 1) of nbytes with 16-byte accesses: a measurement aid."""
     _check(lib().tq_debug_stream(_ptr(src), _ptr(dst), nbytes, mode, _stream()), "tq_debug_stream")
+
+
+def make_lotile_desc(E, M, N, n_in, n_out, r, k, flags=0) -> LoTileDesc:
+    return LoTileDesc(E, M, N, n_in, n_out, r, k, flags)
+
+
+def tq_lotile_packed_size(desc: LoTileDesc) -> int:
+    return int(lib().tq_lotile_packed_size(ctypes.byref(desc)))
+
+
+def tq_lotile_workspace_size(desc: LoTileDesc, T: int) -> int:
+    return int(lib().tq_lotile_workspace_size(ctypes.byref(desc), T))
+
+
+def tq_lotile_pack(desc: LoTileDesc, us, v, phi, packed=None, err_flag=None):
+    """us [M, in, r], v [N, r, out] (fp16 bit patterns, int16/uint16), phi int32 [E, 2] -> packed uint8 blob."""
+    n = tq_lotile_packed_size(desc)
+    if n == 0:
+        raise TqError(2, "tq_lotile_packed_size")
+    if packed is None:
+        packed = torch.empty(n, dtype=torch.uint8, device=us.device)
+    _check(lib().tq_lotile_pack(ctypes.byref(desc), _ptr(us), _ptr(v), _ptr(phi), _ptr(packed), packed.numel(),
+                                _ptr(err_flag), _stream()), "tq_lotile_pack")
+    return packed
+
+
+def tq_lotile_forward(desc: LoTileDesc, packed, x, topk_idx, topk_w, y=None, workspace=None):
+    T = x.shape[0]
+    if y is None:
+        y = torch.empty((T, desc.n_out), dtype=x.dtype, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(tq_lotile_workspace_size(desc, T), 256), dtype=torch.uint8, device=x.device)
+    _check(lib().tq_lotile_forward(ctypes.byref(desc), _ptr(packed), _ptr(x), _ptr(topk_idx), _ptr(topk_w), T,
+                                   _ptr(y), _ptr(workspace), workspace.numel(), _stream()), "tq_lotile_forward")
+    return y

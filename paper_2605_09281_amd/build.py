@@ -6,7 +6,7 @@ import subprocess
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_DIR)
-SOURCES = ["tq_api.hip", "tq_pack.hip", "tq_route.hip", "tq_f32.hip", "tq_mfma.hip", "tq_skinny.hip", "tq_prefill.hip"]
+SOURCES = ["tq_api.hip", "tq_pack.hip", "tq_route.hip", "tq_f32.hip", "tq_mfma.hip", "tq_skinny.hip", "tq_prefill.hip", "tq_lotile.hip"]
 
 
 def library_path() -> str:

@@ -256,13 +256,13 @@ def lotile_grid(E: int):
 def make_lotile(cfg: LayerConfig, n_in: int, n_out: int, M: Optional[int] = None, N: Optional[int] = None):
     """Shared factors for one linear map of a layer shaped like `cfg`: us [M, n_in, r] and v [N, r, n_out] as fp16
     bit patterns (values ~N(0, f_std)), and a placement phi [E, 2] that puts every expert on its own tile of the
-    M x N grid (a seeded permutation of the tiles).  Inputs only: no forward arithmetic."""
+    M x N grid (a seeded permutation of the tiles); with fewer tiles than experts the placement draws tiles with
+    replacement, so experts share them.  Inputs only: no forward arithmetic."""
     if M is None or N is None:
         M, N = lotile_grid(cfg.E)
-    assert M * N >= cfg.E
     rng = _rng(cfg.cfg_id, _TID_LOTILE)
     us = (rng.standard_normal((M, n_in, cfg.r), dtype=np.float32) * cfg.f_std).astype(np.float16).view(np.uint16)
     v = (rng.standard_normal((N, cfg.r, n_out), dtype=np.float32) * cfg.f_std).astype(np.float16).view(np.uint16)
-    tiles = rng.permutation(M * N)[:cfg.E]
+    tiles = rng.permutation(M * N)[:cfg.E] if M * N >= cfg.E else rng.integers(0, M * N, cfg.E)
     phi = np.stack([tiles // N, tiles % N], axis=1).astype(np.int32)
     return us, v, phi

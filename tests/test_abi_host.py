@@ -100,3 +100,46 @@ def test_workspace_grows_with_tokens():
     d = tq.make_desc(8, 0, 2, 256, 512, 64, 4, 8)
     a, b = tq.tq_moe_workspace_size(d, 16), tq.tq_moe_workspace_size(d, 4096)
     assert 0 < a < b
+
+
+# ------------------------------------------------------------------ shared-factor low-rank operator (host side)
+def test_lotile_packed_size_closed_form():
+    """Appendix A.3, shared tiled factors: M in r + N r out 16-bit values (with r padded to a multiple of 16 and the
+    reshaped left factor to whole 32-column tiles), plus the placement table and a header."""
+    al = lambda n: (n + 255) // 256 * 256
+    for E, M, N, n_in, n_out, r in [(8, 3, 3, 4096, 14336, 32), (64, 8, 8, 1408, 2048, 16), (6, 2, 3, 128, 192, 20)]:
+        rp = (r + 15) // 16 * 16
+        n = tq.tq_lotile_packed_size(tq.make_lotile_desc(E, M, N, n_in, n_out, r, 2))
+        b1 = -(-(M * rp) // 32) * 32 * n_in * 2
+        b2 = N * rp * n_out * 2
+        assert n == 256 + al(E * 8) + al(b1) + al(b2)
+
+
+@pytest.mark.parametrize("kw", [dict(E=0), dict(M=0), dict(N=0), dict(n_in=100), dict(n_out=16), dict(r=0), dict(r=257),
+                                dict(k=0), dict(k=9), dict(flags=1)])
+def test_lotile_invalid_descriptors(kw):
+    a = dict(E=8, M=3, N=3, n_in=128, n_out=64, r=8, k=2, flags=0)
+    a.update(kw)
+    d = tq.make_lotile_desc(a["E"], a["M"], a["N"], a["n_in"], a["n_out"], a["r"], a["k"], a["flags"])
+    assert tq.tq_lotile_packed_size(d) == 0
+    assert tq.tq_lotile_workspace_size(d, 16) == 0
+    L = tq.lib()
+    assert L.tq_lotile_forward(ctypes.byref(d), 256, 256, 256, 256, 4, 256, 256, 1 << 20, None) == 2
+
+
+def test_lotile_host_argument_checks():
+    L = tq.lib()
+    d = tq.make_lotile_desc(8, 3, 3, 128, 64, 8, 2)
+    need = tq.tq_lotile_workspace_size(d, 4)
+    assert need > 0 and need % 256 == 0
+    assert tq.tq_lotile_workspace_size(d, -1) == 0
+    assert L.tq_lotile_forward(ctypes.byref(d), None, 256, 256, 256, 4, 256, 256, need, None) == 1
+    assert L.tq_lotile_forward(ctypes.byref(d), 256, 256, 256, 256, -1, 256, 256, need, None) == 2
+    assert L.tq_lotile_forward(ctypes.byref(d), 128, 256, 256, 256, 4, 256, 256, need, None) == 3
+    assert L.tq_lotile_forward(ctypes.byref(d), 256, 8, 256, 256, 4, 256, 256, need, None) == 3
+    assert L.tq_lotile_forward(ctypes.byref(d), 256, 256, 256, 256, 4, 256, 256, need - 1, None) == 5
+    assert L.tq_lotile_forward(ctypes.byref(d), 256, 256, 256, 256, 0, 256, 256, need, None) == 0     # T == 0: no-op
+    assert L.tq_lotile_pack(ctypes.byref(d), 256, 256, None, 256, 1 << 30, None, None) == 1
+    assert L.tq_lotile_pack(ctypes.byref(d), 256, 256, 256, 256, 16, None, None) == 5
+    # the workspace grows with T and never shrinks
+    assert tq.tq_lotile_workspace_size(d, 4096) > need
