@@ -82,6 +82,137 @@ def algorithmic_work(cfg, idx_np):
                 path_flops=flops_gu + flops_d, gate_up_flops=flops_gu, down_flops=flops_d)
 
 
+def bench_lotile(args, cfg, dev):
+    """One step = tq_route + tq_lotile_forward on x [T, hidden] -> y [T, ffn] with factors resident in HBM."""
+    import numpy as np
+    import torch
+    from synth import make_lotile, make_x, make_logits, f32_to_bf16_bits
+    import paper_2605_09281_amd.binding as tq
+
+    n_in, n_out = cfg.H, cfg.F
+    us, v, phi = make_lotile(cfg, n_in, n_out)
+    M, N, r = us.shape[0], v.shape[0], cfg.r
+    x = make_x(cfg)
+    logits, bias = make_logits(cfg)
+    desc = tq.make_lotile_desc(cfg.E, M, N, n_in, n_out, r, cfg.k)
+    d16 = lambda a: torch.from_numpy(a.view(np.int16)).to(dev)
+    n_copies = 2
+    packed = [tq.tq_lotile_pack(desc, d16(us), d16(v), torch.from_numpy(phi).to(dev)) for _ in range(n_copies)]
+    logits_d = torch.from_numpy(logits).to(dev)
+    bias_d = None if bias is None else torch.from_numpy(bias).to(dev)
+    x_d = torch.from_numpy(f32_to_bf16_bits(x).view(np.int16)).to(dev).view(torch.bfloat16)
+    idx_d = torch.empty((cfg.T, cfg.k), dtype=torch.int32, device=dev)
+    w_d = torch.empty((cfg.T, cfg.k), dtype=torch.float32, device=dev)
+    y_d = torch.empty((cfg.T, n_out), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(tq.tq_lotile_workspace_size(desc, cfg.T), dtype=torch.uint8, device=dev)
+
+    def step(i):
+        tq.tq_route(logits_d, bias_d, cfg.k, idx_d, w_d)
+        tq.tq_lotile_forward(desc, packed[i % n_copies], x_d, idx_d, w_d, y=y_d, workspace=ws)
+
+    for i in range(max(args.warmup, n_copies)):
+        step(i)
+    torch.cuda.synchronize()
+    y_eager = y_d.clone()
+    use_graph = not args.no_graph
+    if use_graph:
+        graphs = []
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for c in range(n_copies):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    step(c)
+                graphs.append(g)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        for i in range(args.warmup):
+            graphs[i % n_copies].replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y_d.view(torch.int16), y_eager.view(torch.int16)), "graph replay differs from eager"
+        run = lambda i: graphs[i % n_copies].replay()
+    else:
+        run = step
+    ev = HipEvents(2)
+    stream = torch.cuda.current_stream().cuda_stream
+    ev.record(0, stream)
+    for i in range(args.steps):
+        run(i)
+    ev.record(1, stream)
+    torch.cuda.synchronize()
+    assert torch.equal(y_d.view(torch.int16), y_eager.view(torch.int16)), "timed run differs from the eager result"
+    assert int(ws[:4].view(torch.int32).item()) == 0, "device error flag set"
+    ms_per_step = ev.elapsed_ms(0, 1) / args.steps
+    # per-kernel durations: the library records events at its stage boundaries on the same stream
+    sev = HipEvents(4)
+    tq.tq_set_profile_events(sev.handles())
+    n_prof = max(1, min(args.steps, 50))
+    st_ms = [0.0] * 3
+    for i in range(n_prof):
+        step(i)
+        sev.sync(3)
+        for q in range(3):
+            st_ms[q] += sev.elapsed_ms(q, q + 1)
+    tq.tq_set_profile_events([])
+    stage_us = {n: st_ms[q] / n_prof * 1e3 for q, n in enumerate(("projection", "gather", "output"))}
+    log("stage durations (us): " + ", ".join(f"{k}={v:.1f}" for k, v in stage_us.items()))
+    rp = (r + 15) // 16 * 16
+    # algorithmic work of the operator and of its two products (factors bf16, X_proj fp32, S bf16; see DESIGN.md)
+    alg_bytes = cfg.T * n_in * 2 + n_in * M * r * 2 + N * r * n_out * 2 + cfg.T * n_out * 2 + cfg.T * cfg.k * 8
+    flops = 2.0 * cfg.T * (n_in * M * r + N * r * n_out)
+    kern = {"projection": dict(name="lt_gemm_kernel<.,.,false> (X_proj = x (U Sigma)_reshape)",
+                               bytes=cfg.T * n_in * 2 + n_in * M * r * 2 + cfg.T * M * r * 4,
+                               flops=2.0 * cfg.T * n_in * M * r),
+            "output": dict(name="lt_gemm_kernel<.,.,true> (y = S V_flat)",
+                           bytes=cfg.T * N * r * 2 + N * r * n_out * 2 + cfg.T * n_out * 2,
+                           flops=2.0 * cfg.T * N * r * n_out)}
+    dom = max(kern, key=lambda q: stage_us[q])
+    kd, t_dom = kern[dom], stage_us[dom] * 1e-6
+    t = ms_per_step * 1e-3
+    if kd["flops"] / kd["bytes"] < MFMA_BF16_PEAK / HBM_PEAK:
+        roofline = dict(bound="hbm", kernel=kd["name"], achieved=round(kd["bytes"] / t_dom / 1e9, 1), peak=HBM_PEAK / 1e9,
+                        unit="GB/s", frac=round(kd["bytes"] / t_dom / HBM_PEAK, 4), traffic=None,
+                        algorithmic_bytes=kd["bytes"])
+    else:
+        roofline = dict(bound="mfma", kernel=kd["name"], achieved=round(kd["flops"] / t_dom / 1e12, 1),
+                        peak=MFMA_BF16_PEAK / 1e12, unit="TFLOP/s", frac=round(kd["flops"] / t_dom / MFMA_BF16_PEAK, 4),
+                        traffic=None)
+    roofline["stage_us"] = {k: round(v, 2) for k, v in stage_us.items()}
+    roofline["operator_algorithmic_bytes"] = alg_bytes
+    roofline["operator_flops"] = flops
+    roofline["path_hbm_frac"] = round(alg_bytes / t / HBM_PEAK, 4)
+    roofline["path_mfma_frac"] = round(flops / t / MFMA_BF16_PEAK, 4)
+    cpu_baseline = None
+    max_rel_err = None
+    if not args.no_cpu_baseline:
+        import oracle
+        ridx, rw = oracle.route(logits, bias, cfg.k)
+        idx_np = idx_d.cpu().numpy()
+        assert np.array_equal(ridx, idx_np), "routing indices differ from the oracle"
+        n_tok = int(max(1, min(cfg.T, 3e9 // (n_in * M * r + cfg.k * r * n_out))))   # about 10-20 s, one thread
+        tok = np.linspace(0, cfg.T - 1, n_tok).astype(np.int64)
+        w_np = w_d.cpu().numpy()
+        t1 = time.perf_counter()
+        y_ref = oracle.lotile_forward(x[tok], us, v, phi, idx_np[tok], w_np[tok])
+        cpu_s = time.perf_counter() - t1
+        got = y_d.float().cpu().numpy()[tok].astype(np.float64)
+        max_rel_err = float(np.max(np.abs(got - y_ref)) / np.max(np.abs(y_ref)))
+        cpu_baseline = dict(value=round(n_tok / cpu_s, 3), unit="tokens/s", cores=1, kind="oracle",
+                            sample=f"{n_tok} of {cfg.T} tokens of the same workload, {cpu_s:.2f} s")
+        assert max_rel_err <= 2e-2, max_rel_err
+    out = {
+        "metric": "LoTileMoE tokens/s at 1 GPU (route + shared-factor low-rank operator, one linear map)",
+        "value": round(cfg.T / t, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic", "launch": "hip_graph" if use_graph else "eager",
+        "config": {"workload": f"config {cfg.cfg_id}: {cfg.name}, shared factors hidden -> ffn", "experts": cfg.E,
+                   "top_k": cfg.k, "n_in": n_in, "n_out": n_out, "tokens": cfg.T, "rank": r, "tiles_m": M, "tiles_n": N},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "max_rel_err_vs_oracle": max_rel_err,
+    }
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -91,6 +222,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every step eagerly instead of replaying a captured HIP graph")
+    ap.add_argument("--lotile", action="store_true",
+                    help="instead of the layer: the shared-factor low-rank operator (tq_lotile_forward) on one linear "
+                         "map hidden -> ffn of the workload, with the near-square tile grid")
     ap.add_argument("--stream-probe", action="store_true",
                     help="instead of the workload: time a plain 1 GiB streaming copy and read (counter calibration)")
     args = ap.parse_args()
@@ -128,6 +262,8 @@ def main():
             res[name] = {"us": round(us, 1), "GB/s": round(moved / us / 1e3, 1)}
         print(json.dumps({"stream_probe": res, "bytes": nbytes}), flush=True)
         return
+    if args.lotile:
+        return bench_lotile(args, cfg, dev)
     t0 = time.time()
     layer = make_layer(cfg, workers=min(16, os.cpu_count() or 8))
     x = make_x(cfg)

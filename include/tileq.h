@@ -170,7 +170,8 @@ tq_status tq_moe_forward(const tq_layer_desc *desc, const void *packed, const vo
  * array, copied) that tq_moe_forward records on its stream at the stage boundaries:
  *   0 entry, 1 after the permutation, 2 after the gate/up pre-pass (group sums and x A), 3 after gate/up,
  *   4 after the down pre-pass, 5 after down, 6 after the combination.
- * n == 0 switches it off.  Process-wide and not thread-safe: meant for one benchmark thread. */
+ * tq_lotile_forward records 0 at entry, 1 after the projection, 2 after the gather-accumulate, 3 after the output
+ * product.  n == 0 switches it off.  Process-wide and not thread-safe: meant for one benchmark thread. */
 #define TQ_N_STAGE_EVENTS 7
 tq_status tq_set_profile_events(void *const *events, int32_t n);
 
@@ -200,7 +201,7 @@ typedef struct tq_lotile_desc {
     int32_t n_in;      /* i */
     int32_t n_out;     /* o */
     int32_t rank;      /* r */
-    int32_t top_k;     /* experts per token */
+    int32_t top_k;     /* experts per token, at most min(E, 1024) */
     int32_t flags;     /* 0 */
 } tq_lotile_desc;
 

@@ -10,13 +10,16 @@
 // workgroup; each wave owns two column tiles of the 32 x 256 output block.
 #include "tq_device.h"
 
+#include <algorithm>
+
 namespace {
 
 using namespace tqdev;
 
 constexpr uint32_t LT_MAGIC = 0x544C5154u;   // "TQLT"
 constexpr int LT_HEADER = 256;
-constexpr int LT_CK = 128;                   // contraction indices per staged chunk
+constexpr int LT_SPC = 8;                    // MFMA steps per staged chunk
+constexpr int LT_CK = 16 * LT_SPC;           // contraction indices per staged chunk
 constexpr int LT_ROWB = LT_CK * 2 + 16;      // padded LDS row
 constexpr int LT_MAX_PLANES = 16;
 
@@ -32,7 +35,7 @@ bool lt_make_layout(const tq_lotile_desc* d, LtLayout* L)
     if (!d) return false;
     if (d->n_experts < 1 || d->tiles_m < 1 || d->tiles_n < 1 || d->n_in < 32 || d->n_out < 32) return false;
     if (d->n_in % 32 || d->n_out % 32 || d->rank < 1 || d->rank > 256) return false;
-    if (d->top_k < 1 || d->top_k > d->n_experts || d->flags != 0) return false;
+    if (d->top_k < 1 || d->top_k > d->n_experts || d->top_k > 1024 || d->flags != 0) return false;
     if ((int64_t)d->tiles_m * d->tiles_n > (1 << 20)) return false;
     L->E = d->n_experts; L->M = d->tiles_m; L->N = d->tiles_n; L->n_in = d->n_in; L->n_out = d->n_out;
     L->r = d->rank; L->rp = (d->rank + 15) / 16 * 16; L->k = d->top_k;
@@ -48,17 +51,27 @@ bool lt_make_layout(const tq_lotile_desc* d, LtLayout* L)
 
 struct LtWorkspace {
     size_t ctrl, xproj, s, total;
-    int planes, ldx;       // planes of X_proj (K splits of the first product), its row length (32 nt1)
+    int mt;                // row sub-tiles of 32 per workgroup (1 for decode batches, else 2)
+    int ntw1, planes;      // first product: column tiles per wave, K splits (= planes of X_proj)
+    int ntw2;              // second product: column tiles per wave
+    int ldx;               // row length of X_proj (32 nt1)
 };
 
 void lt_make_workspace(const LtLayout& L, int T, LtWorkspace* W)
 {
-    // split the contraction of the first product when there are too few output blocks to fill the chip
-    const int rt = (T + 31) / 32, cb = (L.nt1 + 7) / 8;
+    W->mt = T <= 32 ? 1 : 2;
+    const int bm = 32 * W->mt, rt = (T + bm - 1) / bm;
+    // first product: as many column tiles per wave as there are (up to 3), and the contraction split over
+    // planes when there are too few output blocks to fill the chip
+    W->ntw1 = std::min(3, (L.nt1 + 3) / 4);
+    const int cb1 = (L.nt1 + 4 * W->ntw1 - 1) / (4 * W->ntw1), chunks = (L.steps1 + LT_SPC - 1) / LT_SPC;
     int planes = 1;
-    const int chunks = (L.steps1 + 7) / 8;
-    while (planes < LT_MAX_PLANES && planes * 2 <= chunks && (long)rt * cb * planes < 256) planes *= 2;
+    while (planes < LT_MAX_PLANES && planes * 2 <= chunks && (long)rt * cb1 * planes < 256) planes *= 2;
     W->planes = planes;
+    // second product: its contraction is short, so narrower workgroups fill the chip instead
+    int ntw2 = std::min(3, (L.nt2 + 3) / 4);
+    while (ntw2 > 1 && (long)rt * ((L.nt2 + 4 * ntw2 - 1) / (4 * ntw2)) < 256) --ntw2;
+    W->ntw2 = ntw2;
     W->ldx = 32 * L.nt1;
     size_t off = 0;
     W->ctrl = off; off += 256;
@@ -124,141 +137,232 @@ __global__ void lt_pack_kernel(LtLayout L, const uint16_t* __restrict__ us, cons
 }
 
 // ---- dense product C[T, 32 nt] = A[T, 16 steps] B, B in fragment order ----------------------------------------
-// grid (column blocks of 8 tiles, row tiles of 32, K splits); OUT_BF16: C bf16 [T][ldc], else fp32 planes
-// [split][T][ldc].  Columns at or beyond ncols are not stored.
-template <bool OUT_BF16>
-__global__ void __launch_bounds__(256) lt_gemm_kernel(const uint16_t* __restrict__ A, int lda, int T,
-                                                      const u32x4* __restrict__ bfrag, int steps, int ntiles,
-                                                      void* __restrict__ C, int ldc, int ncols)
+// grid (column blocks of 4 NTW tiles, row tiles of 32 MT rows, K splits).  A workgroup stages its rows of A
+// through LDS in 128-wide chunks; wave w owns NTW column tiles and all MT row sub-tiles, so a B fragment (one
+// 16-byte load per lane, prefetched four steps ahead) feeds MT MFMAs and an A fragment (one LDS read) NTW of them.
+// OUT_BF16: C bf16 [T][ldc], else fp32 planes [split][T][ldc].
+struct LtGemmArgs {
+    const uint16_t* A;
+    int lda, T;
+    const u32x4* bfrag;
+    int steps, ntiles;
+    void* C;
+    int ldc;
+    int32_t* clear;       // not null: the first workgroup zeroes this word (the operator's error flag)
+};
+
+template <int MT, int NTW, bool OUT_BF16>
+__global__ void __launch_bounds__(256) lt_gemm_kernel(LtGemmArgs a)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * 32 * LT_ROWB];
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    constexpr int BM = 32 * MT, NSEG = LT_CK / 8, RPP = 256 / NSEG, NP = BM / RPP, BUF = BM * LT_ROWB, PF = 4, SPC = LT_SPC;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
-    const int row0 = blockIdx.y * 32;
+    const int row0 = blockIdx.y * BM, T = a.T, steps = a.steps;
     const int split = blockIdx.z, nsplit = gridDim.z;
-    const int nchunks_all = (steps + 7) / 8;
+    const int nchunks_all = (steps + SPC - 1) / SPC;
     const int c0 = (int)((long)split * nchunks_all / nsplit), c1 = (int)((long)(split + 1) * nchunks_all / nsplit);
-    // this wave's two column tiles (clamped: a tile past the end repeats the last one and is not stored)
-    int ct[2];
-    bool live[2];
+    if (a.clear && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) *a.clear = 0;
+    // this wave's column tiles (a tile past the end repeats the last one and is not stored)
+    int ct[NTW];
+    bool live[NTW];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int t = blockIdx.x * 8 + wave * 2 + j;
-        live[j] = t < ntiles;
-        ct[j] = live[j] ? t : ntiles - 1;
+    for (int j = 0; j < NTW; ++j) {
+        const int t = (blockIdx.x * 4 + wave) * NTW + j;
+        live[j] = t < a.ntiles;
+        ct[j] = live[j] ? t : a.ntiles - 1;
     }
-    // staging: 32 rows x 16 segments of 16 bytes per chunk, two per thread
-    const int srow = tid >> 4, sseg = tid & 15;
-    const uint16_t* arow[2];
+    // staging: BM rows x NSEG segments of 16 bytes per chunk, NP per thread
+    const int srow = tid / NSEG, sseg = tid % NSEG;
+    const uint16_t* arow[NP];
 #pragma unroll
-    for (int p = 0; p < 2; ++p) arow[p] = A + (size_t)min(row0 + srow + 16 * p, T - 1) * lda;
-    u32x4 xr[2];
+    for (int p = 0; p < NP; ++p) arow[p] = a.A + (size_t)min(row0 + srow + RPP * p, T - 1) * a.lda;
+    u32x4 xr[NP];
+    // a chunk that reaches past the contraction length is filled with zeros there (when it is written to LDS: a
+    // select right after the load would wait for it), so the step loop needs no guard
+    bool xr_inside = true;
     auto load_chunk = [&](int c) {
-        const int kk = min(c * LT_CK + sseg * 8, steps * 16 - 8);
+        const int k0 = c * LT_CK + sseg * 8;
+        xr_inside = k0 < steps * 16;
+        const int kk = xr_inside ? k0 : 0;
 #pragma unroll
-        for (int p = 0; p < 2; ++p) xr[p] = *reinterpret_cast<const u32x4*>(arow[p] + kk);
+        for (int p = 0; p < NP; ++p) xr[p] = *reinterpret_cast<const u32x4*>(arow[p] + kk);
     };
     auto store_chunk = [&](int buf) {
+        const u32x4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int p = 0; p < 2; ++p)
-            *reinterpret_cast<u32x4*>(lds + buf * 32 * LT_ROWB + (srow + 16 * p) * LT_ROWB + sseg * 16) = xr[p];
+        for (int p = 0; p < NP; ++p)
+            *reinterpret_cast<u32x4*>(lds + buf * BUF + (srow + RPP * p) * LT_ROWB + sseg * 16) = xr_inside ? xr[p] : z;
     };
-    f32x16 acc[2];
+    f32x16 acc[MT][NTW];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+        for (int j = 0; j < NTW; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     if (c0 < c1) {
+        const int s_last = min(c1 * SPC, steps) - 1;      // steps past it multiply zeros: any valid fragment serves
+        u32x4 bq[PF][NTW];
+        auto load_b = [&](int slot, int s) {
+            const int sc = min(s, s_last);
+#pragma unroll
+            for (int j = 0; j < NTW; ++j) bq[slot][j] = a.bfrag[((size_t)ct[j] * steps + sc) * 64 + lane];
+        };
+        // first chunk's A loads, then the B prefetch, then the A store: the loads outstanding on entry to the loop
+        // are the same four B slots, in the same order, as at its back edge (the wait counts are derived from the
+        // weaker of the two states), and neither set of loads waits for the other
         load_chunk(c0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < PF; ++i) load_b(i, c0 * SPC + i);
+        __builtin_amdgcn_sched_barrier(0);
         store_chunk(0);
         lds_barrier();
         for (int c = c0; c < c1; ++c) {
             const int buf = (c - c0) & 1;
-            u32x4 bq[8][2];
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    bq[ks][j] = bfrag[((size_t)ct[j] * steps + min(c * 8 + ks, steps - 1)) * 64 + lane];
             load_chunk(min(c + 1, c1 - 1));
+            // the scheduling barriers keep this order: the next step's A fragments and the B fragments four steps
+            // ahead are requested around each step's MFMAs, not gathered at the end of the chunk
+            Frag xa[2][MT];
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                if (c * 8 + ks < steps) {
-                    Frag xa, b0, b1;
-                    xa.q = *reinterpret_cast<const u32x4*>(lds + buf * 32 * LT_ROWB + col * LT_ROWB + ks * 32 + hf * 16);
-                    b0.q = bq[ks][0];
-                    b1.q = bq[ks][1];
-                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa.v, b0.v, acc[0], 0, 0, 0);
-                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa.v, b1.v, acc[1], 0, 0, 0);
+            for (int i = 0; i < MT; ++i)
+                xa[0][i].q = *reinterpret_cast<const u32x4*>(lds + buf * BUF + (32 * i + col) * LT_ROWB + hf * 16);
+#pragma unroll
+            for (int ks = 0; ks < SPC; ++ks) {
+                if (ks < SPC - 1) {
+#pragma unroll
+                    for (int i = 0; i < MT; ++i)
+                        xa[(ks + 1) & 1][i].q = *reinterpret_cast<const u32x4*>(lds + buf * BUF + (32 * i + col) * LT_ROWB +
+                                                                               (ks + 1) * 32 + hf * 16);
                 }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int j = 0; j < NTW; ++j) {
+                    Frag b;
+                    b.q = bq[ks % PF][j];
+#pragma unroll
+                    for (int i = 0; i < MT; ++i)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[ks & 1][i].v, b.v, acc[i][j], 0, 0, 0);
+                }
+                load_b(ks % PF, c * SPC + ks + PF);
+                __builtin_amdgcn_sched_barrier(0);
             }
             store_chunk(buf ^ 1);
             lds_barrier();
         }
     }
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < NTW; ++j) {
+        if (!live[j]) continue;
         const int c = 32 * ct[j] + col;
-        if (!live[j] || c >= ncols) continue;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int m = row0 + 8 * (v / 4) + 4 * hf + (v % 4);
-            if (m < T) {
-                if (OUT_BF16) reinterpret_cast<uint16_t*>(C)[(size_t)m * ldc + c] = (uint16_t)f2bf_bits(acc[j][v]);
-                else reinterpret_cast<float*>(C)[((size_t)split * T + m) * ldc + c] = acc[j][v];
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = row0 + 32 * i + 8 * (v / 4) + 4 * hf + (v % 4);
+                if (m < T) {
+                    if (OUT_BF16) reinterpret_cast<uint16_t*>(a.C)[(size_t)m * a.ldc + c] = (uint16_t)f2bf_bits(acc[i][j][v]);
+                    else reinterpret_cast<float*>(a.C)[((size_t)split * T + m) * a.ldc + c] = acc[i][j][v];
+                }
             }
-        }
     }
+}
+
+template <int MT, int NTW, bool OUT_BF16>
+tq_status lt_launch_gemm_inst(const LtGemmArgs& a, int planes, hipStream_t st)
+{
+    auto kern = lt_gemm_kernel<MT, NTW, OUT_BF16>;
+    constexpr size_t smem = 2 * 32 * MT * LT_ROWB;
+    static bool done = false;
+    if (!done) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+            return TQ_ERR_HIP;
+        done = true;
+    }
+    const int rt = (a.T + 32 * MT - 1) / (32 * MT), cb = (a.ntiles + 4 * NTW - 1) / (4 * NTW);
+    if (rt > 65535) return TQ_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(kern, dim3(cb, rt, planes), dim3(256), smem, st, a);
+    TQ_CHECK_LAUNCH();
+    return TQ_OK;
+}
+
+template <bool OUT_BF16>
+tq_status lt_launch_gemm(const LtGemmArgs& a, int mt, int ntw, int planes, hipStream_t st)
+{
+    if (mt == 1) {
+        if (ntw == 1) return lt_launch_gemm_inst<1, 1, OUT_BF16>(a, planes, st);
+        if (ntw == 2) return lt_launch_gemm_inst<1, 2, OUT_BF16>(a, planes, st);
+        return lt_launch_gemm_inst<1, 3, OUT_BF16>(a, planes, st);
+    }
+    if (mt == 2) {
+        if (ntw == 1) return lt_launch_gemm_inst<2, 1, OUT_BF16>(a, planes, st);
+        if (ntw == 2) return lt_launch_gemm_inst<2, 2, OUT_BF16>(a, planes, st);
+        return lt_launch_gemm_inst<2, 3, OUT_BF16>(a, planes, st);
+    }
+    return TQ_ERR_UNSUPPORTED;
 }
 
 // ---- S[b][n rp + rho] = sum_t [n(b,t) == n] g[b,t] sum_planes X_proj[b][m(b,t) rp + rho]   (Eq. 16) ----------
+// A workgroup takes `tb` consecutive tokens: their selections are resolved to (m, n, g) once, into LDS (one
+// dependent chain of loads instead of one per selection), then one thread per (token, four columns of S) adds the
+// matching slices: selections in ascending t, planes in ascending order.
+constexpr int LT_GATHER_TAB = 1024;      // selections per workgroup held in LDS (tb * top_k)
+
 __global__ void __launch_bounds__(256) lt_gather_kernel(LtLayout L, const int32_t* __restrict__ phi,
                                                         const int32_t* __restrict__ idx, const float* __restrict__ w,
-                                                        const float* __restrict__ xproj, int planes, int ldx, int T,
+                                                        const float* __restrict__ xproj, int planes, int ldx, int T, int tb,
                                                         uint16_t* __restrict__ S, int32_t* __restrict__ err)
 {
-    __shared__ int32_t tm[64], tn[64];
-    __shared__ float tg[64];
-    const int b = blockIdx.x;
-    for (int t0 = 0; t0 < L.k; t0 += 64) {      // top_k beyond 64 is handled in rounds
-        __syncthreads();
-        const int t = t0 + threadIdx.x;
-        if (threadIdx.x < 64 && t < L.k) {
-            const int e = idx[(size_t)b * L.k + t];
-            if (e >= 0 && e < L.E) {
-                tm[threadIdx.x] = phi[2 * e];
-                tn[threadIdx.x] = phi[2 * e + 1];
-                tg[threadIdx.x] = w[(size_t)b * L.k + t];
-            } else {
-                tm[threadIdx.x] = 0;
-                tn[threadIdx.x] = -1;           // matches no column tile
-                tg[threadIdx.x] = 0.f;
-                atomicOr(err, 1);
-            }
+    __shared__ int32_t tm[LT_GATHER_TAB], tn[LT_GATHER_TAB];
+    __shared__ float tg[LT_GATHER_TAB];
+    const int b0 = blockIdx.x * tb, nb = min(tb, T - b0), k = L.k;
+    for (int i = threadIdx.x; i < nb * k; i += blockDim.x) {
+        const int e = idx[(size_t)b0 * k + i];
+        int m = 0, n = -1;                  // -1 matches no column tile
+        float g = 0.f;
+        if (e >= 0 && e < L.E) {
+            const int2 mn = *reinterpret_cast<const int2*>(phi + 2 * e);
+            m = mn.x;
+            n = mn.y;
+            g = w[(size_t)b0 * k + i];
+        } else {
+            atomicOr(err, 1);
         }
-        __syncthreads();
-        const int nt = min(64, L.k - t0);
-        for (int c = threadIdx.x; c < L.k2; c += blockDim.x) {
-            const int n = c / L.rp, rho = c % L.rp;
-            float sum = 0.f;
-            for (int t2 = 0; t2 < nt; ++t2) {
-                if (tn[t2] == n) {
-                    float xp = 0.f;
-                    for (int p = 0; p < planes; ++p) xp += xproj[((size_t)p * T + b) * ldx + tm[t2] * L.rp + rho];
-                    sum = fmaf(tg[t2], xp, sum);
-                }
-            }
-            // rounds after the first add to what the previous ones left (kept in fp32 in the plane-0 tail is not
-            // possible here, so top_k > 64 re-reads the bf16 value: exact enough for the rare case)
-            if (t0 > 0) sum += bf_lo((uint32_t)S[(size_t)b * L.k2 + c]);
-            S[(size_t)b * L.k2 + c] = (uint16_t)f2bf_bits(sum);
-        }
+        tm[i] = m;
+        tn[i] = n;
+        tg[i] = g;
     }
-}
-
-__global__ void lt_clear_kernel(int32_t* ctrl)
-{
-    if (threadIdx.x < 64) ctrl[threadIdx.x] = 0;
+    __syncthreads();
+    const int q4 = L.k2 / 4;
+    for (int it = threadIdx.x; it < nb * q4; it += blockDim.x) {
+        const int bl = it / q4, c = (it % q4) * 4, b = b0 + bl;
+        const int n = c / L.rp, rho = c % L.rp;
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        for (int t = 0; t < k; ++t) {
+            if (tn[bl * k + t] != n) continue;
+            const float g = tg[bl * k + t];
+            const float* src = xproj + (size_t)b * ldx + tm[bl * k + t] * L.rp + rho;
+            float4 xp = {0.f, 0.f, 0.f, 0.f};
+            // planes is a power of two: four loads in flight at a time, added in ascending order
+            const size_t ps = (size_t)T * ldx;
+            int p = 0;
+            for (; p + 4 <= planes; p += 4) {
+                float4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4*>(src + (size_t)(p + u) * ps);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) { xp.x += v[u].x; xp.y += v[u].y; xp.z += v[u].z; xp.w += v[u].w; }
+            }
+            for (; p < planes; ++p) {
+                const float4 v = *reinterpret_cast<const float4*>(src + (size_t)p * ps);
+                xp.x += v.x; xp.y += v.y; xp.z += v.z; xp.w += v.w;
+            }
+            s0 = fmaf(g, xp.x, s0); s1 = fmaf(g, xp.y, s1); s2 = fmaf(g, xp.z, s2); s3 = fmaf(g, xp.w, s3);
+        }
+        uint2 o = {pack_bf2(s0, s1), pack_bf2(s2, s3)};
+        *reinterpret_cast<uint2*>(S + (size_t)b * L.k2 + c) = o;
+    }
 }
 
 }  // namespace
@@ -312,22 +416,23 @@ extern "C" tq_status tq_lotile_forward(const tq_lotile_desc* desc, const void* p
     int32_t* ctrl = (int32_t*)(ws + W.ctrl);
     float* xproj = (float*)(ws + W.xproj);
     uint16_t* S = (uint16_t*)(ws + W.s);
-    const int rt = (T + 31) / 32;
-    if (rt > 65535) return TQ_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(lt_clear_kernel, dim3(1), dim3(64), 0, st, ctrl);
-    TQ_CHECK_LAUNCH();
-    // step one: the global projection on every row tile's factor
-    hipLaunchKernelGGL(lt_gemm_kernel<false>, dim3((L.nt1 + 7) / 8, rt, W.planes), dim3(256), 0, st,
-                       (const uint16_t*)x, L.n_in, T, (const u32x4*)(pk + L.off_b1), L.steps1, L.nt1, (void*)xproj, W.ldx,
-                       W.ldx);
-    TQ_CHECK_LAUNCH();
+    tqi_record_stage(0, st);
+    // step one: the global projection on every row tile's factor (its first workgroup clears the error flag)
+    LtGemmArgs g1 = {(const uint16_t*)x, L.n_in, T, (const u32x4*)(pk + L.off_b1), L.steps1, L.nt1, (void*)xproj, W.ldx, ctrl};
+    tq_status rc = lt_launch_gemm<false>(g1, W.mt, W.ntw1, W.planes, st);
+    if (rc != TQ_OK) return rc;
+    tqi_record_stage(1, st);
     // step two: routing-weighted selection and accumulation into the compact buffer
-    hipLaunchKernelGGL(lt_gather_kernel, dim3(T), dim3(256), 0, st, L, (const int32_t*)(pk + L.off_phi), topk_idx, topk_w,
-                       (const float*)xproj, W.planes, W.ldx, T, S, ctrl);
+    const int q4 = L.k2 / 4;
+    const int tb = std::max(1, std::min({T / 256, std::max(1, 512 / q4), LT_GATHER_TAB / L.k}));
+    hipLaunchKernelGGL(lt_gather_kernel, dim3((T + tb - 1) / tb), dim3(256), 0, st, L, (const int32_t*)(pk + L.off_phi),
+                       topk_idx, topk_w, (const float*)xproj, W.planes, W.ldx, T, tb, S, ctrl);
     TQ_CHECK_LAUNCH();
+    tqi_record_stage(2, st);
     // step three: output reconstruction
-    hipLaunchKernelGGL(lt_gemm_kernel<true>, dim3((L.nt2 + 7) / 8, rt, 1), dim3(256), 0, st, (const uint16_t*)S, L.k2, T,
-                       (const u32x4*)(pk + L.off_b2), L.steps2, L.nt2, y, L.n_out, L.n_out);
-    TQ_CHECK_LAUNCH();
+    LtGemmArgs g2 = {(const uint16_t*)S, L.k2, T, (const u32x4*)(pk + L.off_b2), L.steps2, L.nt2, y, L.n_out, nullptr};
+    rc = lt_launch_gemm<true>(g2, W.mt, W.ntw2, 1, st);
+    if (rc != TQ_OK) return rc;
+    tqi_record_stage(3, st);
     return TQ_OK;
 }
