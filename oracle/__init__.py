@@ -199,3 +199,37 @@ def lotile_forward(x: np.ndarray, us_bits: np.ndarray, v_bits: np.ndarray, phi: 
     y = np.zeros((T, n_out), dtype=np.float64)
     L.orc_lotile_forward(T, n_in, n_out, M, N, r, k, _p(x), _p(us_bits), _p(v_bits), _p(phi), _p(idx), _p(w), _p(y))
     return y
+
+
+def fp8_e4m3_to_double(bits: int) -> float:
+    L = lib()
+    L.orc_fp8_e4m3_to_double.restype = ctypes.c_double
+    L.orc_fp8_e4m3_to_double.argtypes = [ctypes.c_uint8]
+    return float(L.orc_fp8_e4m3_to_double(ctypes.c_uint8(bits)))
+
+
+def lotile_forward_fp8(x: np.ndarray, u8: np.ndarray, sigma_bits: np.ndarray, v8: np.ndarray, phi: np.ndarray,
+                       idx: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """LoTileMoE on mixed-precision factors (end of Section 3.1): u8 [M, in, r] and v8 [N, r, out] fp8 E4M3 bytes,
+    sigma_bits [r] fp16 bit patterns.  Returns y [T, out] fp64."""
+    L = lib()
+    if not getattr(L, "_lotile_fp8_ready", False):
+        L.orc_lotile_forward_fp8.restype = None
+        L.orc_lotile_forward_fp8.argtypes = [ctypes.c_int32] * 7 + [ctypes.c_void_p] * 8
+        L._lotile_fp8_ready = True
+    x = _c(x, np.float32)
+    u8 = _c(u8, np.uint8)
+    v8 = _c(v8, np.uint8)
+    sigma_bits = _c(sigma_bits, np.uint16)
+    phi = _c(phi, np.int32)
+    idx = _c(idx, np.int32)
+    w = _c(w, np.float32)
+    T, n_in = x.shape
+    M, _, r = u8.shape
+    N, _, n_out = v8.shape
+    assert sigma_bits.shape == (r,)
+    k = idx.shape[1]
+    y = np.zeros((T, n_out), dtype=np.float64)
+    L.orc_lotile_forward_fp8(T, n_in, n_out, M, N, r, k, _p(x), _p(u8), _p(sigma_bits), _p(v8), _p(phi), _p(idx), _p(w),
+                             _p(y))
+    return y

@@ -19,7 +19,10 @@
  *     ("Basic Quantization");
  *   - orc_lotile_forward: the fused low-rank path over shared 2D-tiled factors, LoTileMoE of
  *     Section 3.2 in its defining three-dimensional accumulator form (the construction that ends
- *     in Eq. 15), NOT the compact buffer of Eq. 16 that an implementation would use.
+ *     in Eq. 15), NOT the compact buffer of Eq. 16 that an implementation would use;
+ *   - orc_lotile_forward_fp8: the same on mixed-precision factors, U and V in fp8 with Sigma kept
+ *     in fp16 (end of Section 3.1; Appendix A.3, d_low); the paper names no fp8 format: E4M3 of
+ *     the OCP specification is taken.
  * Readings taken where the paper is silent (stated once more in the repository's design notes):
  *   - routing weights are the softmax over the k selected logits (equal to softmax over all
  *     experts renormalised over the selected ones);
@@ -304,6 +307,67 @@ void orc_lotile_forward(int32_t T, int32_t n_in, int32_t n_out, int32_t M, int32
                     if (a == 0.0) continue;       /* zero entries add nothing (keeps the brute force usable) */
                     for (int32_t o = 0; o < n_out; ++o)
                         y[(size_t)b * n_out + o] += a * orc_half_to_double(v[((size_t)n * r + rho) * n_out + o]);
+                }
+    }
+    free(xproj);
+    free(acc);
+}
+
+
+/*
+ * fp8 E4M3 as published in the OCP 8-bit floating point specification ("E4M3", the variant without
+ * infinities): 1 sign, 4 exponent (bias 7), 3 mantissa bits; exponent 0 is subnormal (m / 8 * 2^-6);
+ * S.1111.111 is NaN; the largest finite value is 448.
+ */
+double orc_fp8_e4m3_to_double(uint8_t b)
+{
+    const int sign = b >> 7, e = (b >> 3) & 15, m = b & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0) v = ldexp((double)m, -9);
+    else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+/*
+ * LoTileMoE on mixed-precision factors (end of Section 3.1: U and V stored in fp8, Sigma kept in fp16;
+ * Appendix A.3 d_low = 8 bits).  Same construction and order as orc_lotile_forward with
+ *   u8    [M][in][r]  fp8    row-tile factors U_m
+ *   sigma [r]         fp16   the diagonal of the rank-r factorisation, shared by all tiles
+ *   v8    [N][r][out] fp8    column-tile factors V_n
+ * and U_m Sigma formed in fp64 from the decoded values: X_proj = x (U diag(sigma))_reshape.
+ */
+void orc_lotile_forward_fp8(int32_t T, int32_t n_in, int32_t n_out, int32_t M, int32_t N, int32_t r, int32_t k,
+                            const float *x, const uint8_t *u8, const uint16_t *sigma, const uint8_t *v8,
+                            const int32_t *phi, const int32_t *idx, const float *w, double *y)
+{
+    const size_t Mr = (size_t)M * r, rN = (size_t)r * N;
+    double *xproj = (double *)malloc(sizeof(double) * Mr);
+    double *acc = (double *)malloc(sizeof(double) * (size_t)M * rN);
+    for (int32_t b = 0; b < T; ++b) {
+        for (int32_t m = 0; m < M; ++m)
+            for (int32_t rho = 0; rho < r; ++rho) {
+                const double sg = orc_half_to_double(sigma[rho]);
+                double a = 0.0;
+                for (int32_t i = 0; i < n_in; ++i)
+                    a += (double)x[(size_t)b * n_in + i] * (orc_fp8_e4m3_to_double(u8[((size_t)m * n_in + i) * r + rho]) * sg);
+                xproj[(size_t)m * r + rho] = a;
+            }
+        memset(acc, 0, sizeof(double) * (size_t)M * rN);
+        for (int32_t t = 0; t < k; ++t) {
+            const int32_t e = idx[(size_t)b * k + t];
+            const int32_t m = phi[2 * e], n = phi[2 * e + 1];
+            for (int32_t rho = 0; rho < r; ++rho)
+                acc[(size_t)m * rN + (size_t)n * r + rho] += (double)w[(size_t)b * k + t] * xproj[(size_t)m * r + rho];
+        }
+        for (int32_t o = 0; o < n_out; ++o) y[(size_t)b * n_out + o] = 0.0;
+        for (int32_t m = 0; m < M; ++m)
+            for (int32_t n = 0; n < N; ++n)
+                for (int32_t rho = 0; rho < r; ++rho) {
+                    const double a = acc[(size_t)m * rN + (size_t)n * r + rho];
+                    if (a == 0.0) continue;
+                    for (int32_t o = 0; o < n_out; ++o)
+                        y[(size_t)b * n_out + o] += a * orc_fp8_e4m3_to_double(v8[((size_t)n * r + rho) * n_out + o]);
                 }
     }
     free(xproj);

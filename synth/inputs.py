@@ -266,3 +266,25 @@ def make_lotile(cfg: LayerConfig, n_in: int, n_out: int, M: Optional[int] = None
     tiles = rng.permutation(M * N)[:cfg.E] if M * N >= cfg.E else rng.integers(0, M * N, cfg.E)
     phi = np.stack([tiles // N, tiles % N], axis=1).astype(np.int32)
     return us, v, phi
+
+
+def fp8_e4m3_encode(a: np.ndarray) -> np.ndarray:
+    """fp32 -> fp8 E4M3 bytes (round to nearest even; the library conversion of torch on the CPU).  Input
+    generation only."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+
+
+def make_lotile_fp8(cfg: LayerConfig, n_in: int, n_out: int, M: Optional[int] = None, N: Optional[int] = None):
+    """Mixed-precision shared factors: u8 [M, n_in, r] and v8 [N, r, n_out] fp8 E4M3 bytes of N(0, 1) draws (unit
+    scale, as the columns of a normalised factorisation would be stored), sigma [r] fp16 bit patterns carrying the
+    magnitude (f_std^2 / (1 + rho / 4): a decaying spectrum), and phi as make_lotile."""
+    if M is None or N is None:
+        M, N = lotile_grid(cfg.E)
+    rng = _rng(cfg.cfg_id, _TID_LOTILE + 1)
+    u8 = fp8_e4m3_encode(rng.standard_normal((M, n_in, cfg.r), dtype=np.float32))
+    v8 = fp8_e4m3_encode(rng.standard_normal((N, cfg.r, n_out), dtype=np.float32))
+    sigma = (cfg.f_std ** 2 / (1.0 + np.arange(cfg.r) / 4.0)).astype(np.float16).view(np.uint16)
+    tiles = rng.permutation(M * N)[:cfg.E] if M * N >= cfg.E else rng.integers(0, M * N, cfg.E)
+    phi = np.stack([tiles // N, tiles % N], axis=1).astype(np.int32)
+    return u8, sigma, v8, phi

@@ -466,3 +466,77 @@ def test_lotile_closed_forms():
         for j in range(4):
             ref[b] += float(w1[b, j]) * t[b] @ v1[phi1[idx1[b, j], 1]].astype(np.float64)
     assert np.allclose(y1, ref, rtol=1e-13, atol=1e-15)
+
+
+# ------------------------------------------------------------------ mixed-precision shared factors (fp8 U, V; fp16 Sigma)
+def test_fp8_e4m3_decode_matches_published_values_and_library():
+    """The format's landmark values (smallest subnormal 2^-9, smallest normal 2^-6, 1, largest finite 448) and every
+    one of the 256 codes against the CPU library conversion."""
+    import torch
+    with open(os.path.join(os.path.dirname(__file__), "golden", "fp8_e4m3_values.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            b, val = line.split()
+            assert oracle.fp8_e4m3_to_double(int(b, 16)) == float(val)
+    lib = torch.arange(256, dtype=torch.int32).to(torch.uint8).view(torch.float8_e4m3fn).double().numpy()
+    for b in range(256):
+        got = oracle.fp8_e4m3_to_double(b)
+        if np.isnan(lib[b]):
+            assert np.isnan(got) and (b & 0x7F) == 0x7F
+        else:
+            assert got == lib[b] and np.signbit(got) == np.signbit(lib[b])
+
+
+def _lotile_fp8_case(seed, T=7, E=6, k=3, n_in=20, n_out=12, r=5, M=2, N=3):
+    import torch
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, n_in)).astype(np.float32)
+    enc = lambda a: torch.from_numpy(a.astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    dec = lambda b: torch.from_numpy(b).view(torch.float8_e4m3fn).double().numpy()
+    u8 = enc(rng.standard_normal((M, n_in, r)))
+    v8 = enc(rng.standard_normal((N, r, n_out)))
+    sigma = (0.5 / (1 + np.arange(r))).astype(np.float16)
+    tiles = rng.permutation(M * N)[:E]
+    phi = np.stack([tiles // N, tiles % N], axis=1).astype(np.int32)
+    idx = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    w = rng.random((T, k)).astype(np.float32)
+    return x, u8, sigma, v8, phi, idx, w, dec
+
+
+@pytest.mark.parametrize("seed,M,N,E", [(0, 2, 3, 6), (1, 3, 3, 7), (2, 1, 4, 4)])
+def test_lotile_fp8_equals_per_expert_definition(seed, M, N, E):
+    """y_b = sum_t g_bt * x_b (U_m diag(sigma)) V_n with the factors decoded by the library conversion."""
+    x, u8, sigma, v8, phi, idx, w, dec = _lotile_fp8_case(seed, E=E, M=M, N=N, k=min(3, E))
+    got = oracle.lotile_forward_fp8(x, u8, sigma.view(np.uint16), v8, phi, idx, w)
+    ud, vd, sd = dec(u8), dec(v8), sigma.astype(np.float64)
+    ref = np.zeros_like(got)
+    for b in range(x.shape[0]):
+        for t in range(idx.shape[1]):
+            m, n = phi[idx[b, t]]
+            ref[b] += float(w[b, t]) * ((x[b].astype(np.float64) @ ud[m]) * sd) @ vd[n]
+    assert np.max(np.abs(got - ref)) <= 1e-12 * max(1.0, np.max(np.abs(ref)))
+
+
+def test_lotile_fp8_with_unit_sigma_is_the_fp16_operator_on_the_same_values():
+    """Every fp8 value is an fp16 value: with sigma = 1 the mixed-precision operator is the pinned fp16 one."""
+    x, u8, sigma, v8, phi, idx, w, dec = _lotile_fp8_case(4)
+    ones = np.ones_like(sigma)
+    got = oracle.lotile_forward_fp8(x, u8, ones.view(np.uint16), v8, phi, idx, w)
+    ref = oracle.lotile_forward(x, dec(u8).astype(np.float16).view(np.uint16), dec(v8).astype(np.float16).view(np.uint16),
+                                phi, idx, w)
+    assert np.max(np.abs(got - ref)) <= 1e-12 * max(1.0, np.max(np.abs(ref)))
+
+
+def test_lotile_fp8_sigma_scales_its_rank_component():
+    """Doubling sigma doubles y; zeroing all but one sigma leaves the rank-1 term of that component."""
+    x, u8, sigma, v8, phi, idx, w, dec = _lotile_fp8_case(6)
+    y1 = oracle.lotile_forward_fp8(x, u8, sigma.view(np.uint16), v8, phi, idx, w)
+    y2 = oracle.lotile_forward_fp8(x, u8, (sigma * 2).astype(np.float16).view(np.uint16), v8, phi, idx, w)
+    assert np.max(np.abs(y2 - 2 * y1)) <= 1e-12 * np.max(np.abs(y1))
+    parts = np.zeros_like(y1)
+    for rho in range(sigma.size):
+        one = np.zeros_like(sigma)
+        one[rho] = sigma[rho]
+        parts += oracle.lotile_forward_fp8(x, u8, one.view(np.uint16), v8, phi, idx, w)
+    assert np.max(np.abs(parts - y1)) <= 1e-12 * np.max(np.abs(y1))
