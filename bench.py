@@ -86,18 +86,27 @@ def bench_lotile(args, cfg, dev):
     """One step = tq_route + tq_lotile_forward on x [T, hidden] -> y [T, ffn] with factors resident in HBM."""
     import numpy as np
     import torch
-    from synth import make_lotile, make_x, make_logits, f32_to_bf16_bits
+    from synth import make_lotile, make_lotile_fp8, make_x, make_logits, f32_to_bf16_bits
     import paper_2605_09281_amd.binding as tq
 
     n_in, n_out = cfg.H, cfg.F
-    us, v, phi = make_lotile(cfg, n_in, n_out)
-    M, N, r = us.shape[0], v.shape[0], cfg.r
+    fp8 = args.lotile_fp8
+    d16 = lambda a: torch.from_numpy(a.view(np.int16)).to(dev)
     x = make_x(cfg)
     logits, bias = make_logits(cfg)
-    desc = tq.make_lotile_desc(cfg.E, M, N, n_in, n_out, r, cfg.k)
-    d16 = lambda a: torch.from_numpy(a.view(np.int16)).to(dev)
     n_copies = 2
-    packed = [tq.tq_lotile_pack(desc, d16(us), d16(v), torch.from_numpy(phi).to(dev)) for _ in range(n_copies)]
+    if fp8:
+        u8, sigma, v8, phi = make_lotile_fp8(cfg, n_in, n_out)
+        M, N, r = u8.shape[0], v8.shape[0], cfg.r
+        desc = tq.make_lotile_desc(cfg.E, M, N, n_in, n_out, r, cfg.k, tq.TQ_LOTILE_FP8)
+        packed = [tq.tq_lotile_pack_fp8(desc, torch.from_numpy(u8).to(dev), d16(sigma), torch.from_numpy(v8).to(dev),
+                                        torch.from_numpy(phi).to(dev)) for _ in range(n_copies)]
+    else:
+        us, v, phi = make_lotile(cfg, n_in, n_out)
+        M, N, r = us.shape[0], v.shape[0], cfg.r
+        desc = tq.make_lotile_desc(cfg.E, M, N, n_in, n_out, r, cfg.k)
+        packed = [tq.tq_lotile_pack(desc, d16(us), d16(v), torch.from_numpy(phi).to(dev)) for _ in range(n_copies)]
+    fb = 1 if fp8 else 2      # bytes per stored factor entry
     logits_d = torch.from_numpy(logits).to(dev)
     bias_d = None if bias is None else torch.from_numpy(bias).to(dev)
     x_d = torch.from_numpy(f32_to_bf16_bits(x).view(np.int16)).to(dev).view(torch.bfloat16)
@@ -159,13 +168,13 @@ def bench_lotile(args, cfg, dev):
     log("stage durations (us): " + ", ".join(f"{k}={v:.1f}" for k, v in stage_us.items()))
     rp = (r + 15) // 16 * 16
     # algorithmic work of the operator and of its two products (factors bf16, X_proj fp32, S bf16)
-    alg_bytes = cfg.T * n_in * 2 + n_in * M * r * 2 + N * r * n_out * 2 + cfg.T * n_out * 2 + cfg.T * cfg.k * 8
+    alg_bytes = cfg.T * n_in * 2 + n_in * M * r * fb + N * r * n_out * fb + cfg.T * n_out * 2 + cfg.T * cfg.k * 8
     flops = 2.0 * cfg.T * (n_in * M * r + N * r * n_out)
     kern = {"projection": dict(name="lt_gemm_kernel<.,.,false> (X_proj = x (U Sigma)_reshape)",
-                               bytes=cfg.T * n_in * 2 + n_in * M * r * 2 + cfg.T * M * r * 4,
+                               bytes=cfg.T * n_in * 2 + n_in * M * r * fb + cfg.T * M * r * 4,
                                flops=2.0 * cfg.T * n_in * M * r),
             "output": dict(name="lt_gemm_kernel<.,.,true> (y = S V_flat)",
-                           bytes=cfg.T * N * r * 2 + N * r * n_out * 2 + cfg.T * n_out * 2,
+                           bytes=cfg.T * N * r * 2 + N * r * n_out * fb + cfg.T * n_out * 2,
                            flops=2.0 * cfg.T * N * r * n_out)}
     dom = max(kern, key=lambda q: stage_us[q])
     kd, t_dom = kern[dom], stage_us[dom] * 1e-6
@@ -194,7 +203,10 @@ def bench_lotile(args, cfg, dev):
         tok = np.linspace(0, cfg.T - 1, n_tok).astype(np.int64)
         w_np = w_d.cpu().numpy()
         t1 = time.perf_counter()
-        y_ref = oracle.lotile_forward(x[tok], us, v, phi, idx_np[tok], w_np[tok])
+        if fp8:
+            y_ref = oracle.lotile_forward_fp8(x[tok], u8, sigma, v8, phi, idx_np[tok], w_np[tok])
+        else:
+            y_ref = oracle.lotile_forward(x[tok], us, v, phi, idx_np[tok], w_np[tok])
         cpu_s = time.perf_counter() - t1
         got = y_d.float().cpu().numpy()[tok].astype(np.float64)
         max_rel_err = float(np.max(np.abs(got - y_ref)) / np.max(np.abs(y_ref)))
@@ -207,7 +219,8 @@ def bench_lotile(args, cfg, dev):
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic", "launch": "hip_graph" if use_graph else "eager",
         "config": {"workload": f"config {cfg.cfg_id}: {cfg.name}, shared factors hidden -> ffn", "experts": cfg.E,
-                   "top_k": cfg.k, "n_in": n_in, "n_out": n_out, "tokens": cfg.T, "rank": r, "tiles_m": M, "tiles_n": N},
+                   "top_k": cfg.k, "n_in": n_in, "n_out": n_out, "tokens": cfg.T, "rank": r, "tiles_m": M, "tiles_n": N,
+                   "factors": "fp8 e4m3 + fp16 sigma" if fp8 else "bf16 (from fp16)"},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "max_rel_err_vs_oracle": max_rel_err,
     }
     print(json.dumps(out), flush=True)
@@ -225,6 +238,8 @@ def main():
     ap.add_argument("--lotile", action="store_true",
                     help="instead of the layer: the shared-factor low-rank operator (tq_lotile_forward) on one linear "
                          "map hidden -> ffn of the workload, with the near-square tile grid")
+    ap.add_argument("--lotile-fp8", action="store_true",
+                    help="as --lotile with mixed-precision factors (fp8 E4M3 U and V, fp16 Sigma)")
     ap.add_argument("--stream-probe", action="store_true",
                     help="instead of the workload: time a plain 1 GiB streaming copy and read (counter calibration)")
     args = ap.parse_args()
@@ -262,7 +277,7 @@ def main():
             res[name] = {"us": round(us, 1), "GB/s": round(moved / us / 1e3, 1)}
         print(json.dumps({"stream_probe": res, "bytes": nbytes}), flush=True)
         return
-    if args.lotile:
+    if args.lotile or args.lotile_fp8:
         return bench_lotile(args, cfg, dev)
     t0 = time.time()
     layer = make_layer(cfg, workers=min(16, os.cpu_count() or 8))

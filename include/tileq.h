@@ -194,6 +194,13 @@ tq_status tq_debug_stream(const void *src, void *dst, size_t bytes, int32_t mode
  * order: element i of (column tile ct, step s, lane) = B[kk = 16 s + 8 (lane / 32) + i][32 ct + lane % 32],
  * for B1 = (U Sigma)_reshape with every tile's r columns padded to rp = 16 ceil(r / 16) (zero), and for
  * B2 = V_flat with its N r rows padded likewise. */
+/* flags bit: mixed-precision factors (end of Section 3.1; Appendix A.3, d_low = 8): U_m and V_n are stored as fp8
+ * E4M3 (OCP 8-bit floating point, the variant without infinities: bias 7, S.1111.111 is NaN, largest finite 448)
+ * and the diagonal Sigma [r], shared by all tiles, as fp16.  The operator is then
+ *     y[b] = sum_t g[b,t] * ( (x[b] U_m) * Sigma ) V_n
+ * and the packed form keeps the fp8 bytes (two MFMA steps per 16-byte fragment) next to an fp32 copy of Sigma. */
+#define TQ_LOTILE_FP8 1
+
 typedef struct tq_lotile_desc {
     int32_t n_experts; /* E */
     int32_t tiles_m;   /* M row tiles (shared left factors) */
@@ -202,7 +209,7 @@ typedef struct tq_lotile_desc {
     int32_t n_out;     /* o */
     int32_t rank;      /* r */
     int32_t top_k;     /* experts per token, at most min(E, 1024) */
-    int32_t flags;     /* 0 */
+    int32_t flags;     /* 0, or TQ_LOTILE_FP8 */
 } tq_lotile_desc;
 
 /* Bytes of the packed factors.  Host only; 0 if desc is invalid. */
@@ -212,6 +219,12 @@ size_t tq_lotile_packed_size(const tq_lotile_desc *desc);
  * NULL): bit 0 is set when a phi entry is outside the M x N grid (it is then clamped into it). */
 tq_status tq_lotile_pack(const tq_lotile_desc *desc, const uint16_t *us, const uint16_t *v, const int32_t *phi,
                          void *packed, size_t packed_bytes, int32_t *err_flag, void *stream);
+
+/* As tq_lotile_pack for a descriptor with TQ_LOTILE_FP8: u8 [M][n_in][r] and v8 [N][r][n_out] are fp8 E4M3 bytes,
+ * sigma [r] fp16 bit patterns (all device).  The bytes are rearranged, never re-rounded.  tq_lotile_pack rejects a
+ * descriptor with the flag, this function one without it (TQ_ERR_SHAPE). */
+tq_status tq_lotile_pack_fp8(const tq_lotile_desc *desc, const uint8_t *u8, const uint16_t *sigma, const uint8_t *v8,
+                             const int32_t *phi, void *packed, size_t packed_bytes, int32_t *err_flag, void *stream);
 
 /* Bytes of workspace tq_lotile_forward needs for up to T tokens.  Host only; 0 if desc is invalid. */
 size_t tq_lotile_workspace_size(const tq_lotile_desc *desc, int32_t T);

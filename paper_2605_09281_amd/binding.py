@@ -16,12 +16,13 @@ from .build import library_path
 TQ_OK = 0
 TQ_ACT_BF16, TQ_ACT_FP32 = 0, 1
 TQ_FLAG_FORCE_SMALL_TILE, TQ_FLAG_FORCE_LARGE_TILE, TQ_FLAG_FORCE_SKINNY = 1, 2, 4
+TQ_LOTILE_FP8 = 1
 STATUS_NAMES = {0: "TQ_OK", 1: "TQ_ERR_NULL", 2: "TQ_ERR_SHAPE", 3: "TQ_ERR_ALIGN", 4: "TQ_ERR_RANGE",
                 5: "TQ_ERR_WORKSPACE", 6: "TQ_ERR_UNSUPPORTED", 7: "TQ_ERR_HIP", 8: "TQ_ERR_BLOB"}
 
 EXPORTS = ["tq_status_str", "tq_packed_size", "tq_pack_weights", "tq_unpack_weights", "tq_route",
            "tq_permute_workspace_size", "tq_permute", "tq_moe_workspace_size", "tq_moe_forward",
-           "tq_set_profile_events", "tq_debug_stream", "tq_lotile_packed_size", "tq_lotile_pack",
+           "tq_set_profile_events", "tq_debug_stream", "tq_lotile_packed_size", "tq_lotile_pack", "tq_lotile_pack_fp8",
            "tq_lotile_workspace_size", "tq_lotile_forward"]
 
 
@@ -92,6 +93,10 @@ def lib():
         L.tq_lotile_pack.restype = ctypes.c_int
         L.tq_lotile_pack.argtypes = [ctypes.POINTER(LoTileDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+        L.tq_lotile_pack_fp8.restype = ctypes.c_int
+        L.tq_lotile_pack_fp8.argtypes = [ctypes.POINTER(LoTileDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                         ctypes.c_void_p]
         L.tq_lotile_forward.restype = ctypes.c_int
         L.tq_lotile_forward.argtypes = [ctypes.POINTER(LoTileDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
@@ -219,6 +224,18 @@ def tq_lotile_pack(desc: LoTileDesc, us, v, phi, packed=None, err_flag=None):
         packed = torch.empty(n, dtype=torch.uint8, device=us.device)
     _check(lib().tq_lotile_pack(ctypes.byref(desc), _ptr(us), _ptr(v), _ptr(phi), _ptr(packed), packed.numel(),
                                 _ptr(err_flag), _stream()), "tq_lotile_pack")
+    return packed
+
+
+def tq_lotile_pack_fp8(desc: LoTileDesc, u8, sigma, v8, phi, packed=None, err_flag=None):
+    """u8 [M, in, r], v8 [N, r, out] fp8 E4M3 bytes (uint8), sigma [r] fp16 bit patterns -> packed uint8 blob."""
+    n = tq_lotile_packed_size(desc)
+    if n == 0:
+        raise TqError(2, "tq_lotile_packed_size")
+    if packed is None:
+        packed = torch.empty(n, dtype=torch.uint8, device=u8.device)
+    _check(lib().tq_lotile_pack_fp8(ctypes.byref(desc), _ptr(u8), _ptr(sigma), _ptr(v8), _ptr(phi), _ptr(packed),
+                                    packed.numel(), _ptr(err_flag), _stream()), "tq_lotile_pack_fp8")
     return packed
 
 

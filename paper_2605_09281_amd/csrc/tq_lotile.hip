@@ -27,7 +27,9 @@ struct LtLayout {
     int E, M, N, n_in, n_out, r, rp, k;
     int n1, nt1, steps1;      // B1 = (U Sigma)_reshape: n1 = M rp columns in nt1 tiles, steps1 = n_in / 16
     int k2, nt2, steps2;      // B2 = V_flat: k2 = N rp rows (steps2 = k2 / 16), nt2 = n_out / 32 column tiles
-    size_t off_phi, off_b1, off_b2, total;
+    size_t off_phi, off_sigma, off_b1, off_b2, total;
+    int fp8;                  // factors stored as fp8 E4M3 with an fp32 copy of the fp16 Sigma (else bf16, no Sigma)
+    int nsp1, nsp2;           // fp8: step pairs per column tile (one 16-byte lane load holds two steps)
 };
 
 bool lt_make_layout(const tq_lotile_desc* d, LtLayout* L)
@@ -35,7 +37,7 @@ bool lt_make_layout(const tq_lotile_desc* d, LtLayout* L)
     if (!d) return false;
     if (d->n_experts < 1 || d->tiles_m < 1 || d->tiles_n < 1 || d->n_in < 32 || d->n_out < 32) return false;
     if (d->n_in % 32 || d->n_out % 32 || d->rank < 1 || d->rank > 256) return false;
-    if (d->top_k < 1 || d->top_k > d->n_experts || d->top_k > 1024 || d->flags != 0) return false;
+    if (d->top_k < 1 || d->top_k > d->n_experts || d->top_k > 1024 || (d->flags & ~TQ_LOTILE_FP8)) return false;
     if ((int64_t)d->tiles_m * d->tiles_n > (1 << 20)) return false;
     L->E = d->n_experts; L->M = d->tiles_m; L->N = d->tiles_n; L->n_in = d->n_in; L->n_out = d->n_out;
     L->r = d->rank; L->rp = (d->rank + 15) / 16 * 16; L->k = d->top_k;
@@ -43,8 +45,11 @@ bool lt_make_layout(const tq_lotile_desc* d, LtLayout* L)
     L->k2 = L->N * L->rp; L->steps2 = L->k2 / 16; L->nt2 = L->n_out / 32;
     size_t off = LT_HEADER;
     L->off_phi = off; off += tq_align256((size_t)L->E * 2 * 4);
-    L->off_b1 = off; off += tq_align256((size_t)L->nt1 * L->steps1 * 64 * 16);
-    L->off_b2 = off; off += tq_align256((size_t)L->nt2 * L->steps2 * 64 * 16);
+    L->fp8 = (d->flags & TQ_LOTILE_FP8) != 0;
+    L->nsp1 = (L->steps1 + 1) / 2; L->nsp2 = (L->steps2 + 1) / 2;
+    L->off_sigma = off; off += L->fp8 ? tq_align256((size_t)L->rp * 4) : 0;
+    L->off_b1 = off; off += tq_align256((size_t)L->nt1 * (L->fp8 ? L->nsp1 : L->steps1) * 64 * 16);
+    L->off_b2 = off; off += tq_align256((size_t)L->nt2 * (L->fp8 ? L->nsp2 : L->steps2) * 64 * 16);
     L->total = off;
     return true;
 }
@@ -136,6 +141,77 @@ __global__ void lt_pack_kernel(LtLayout L, const uint16_t* __restrict__ us, cons
     }
 }
 
+// fp8 factors: bytes are only rearranged (two MFMA steps per 16-byte lane load), Sigma is widened to fp32
+__global__ void lt_pack_fp8_kernel(LtLayout L, const uint8_t* __restrict__ u8, const uint16_t* __restrict__ sigma,
+                                   const uint8_t* __restrict__ v8, const int32_t* __restrict__ phi,
+                                   uint8_t* __restrict__ packed, int32_t* __restrict__ err_flag)
+{
+    const size_t n_b1 = (size_t)L.nt1 * L.nsp1 * 64, n_b2 = (size_t)L.nt2 * L.nsp2 * 64;
+    const size_t total = n_b1 + n_b2 + (size_t)L.E + (size_t)L.rp;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        if (i < n_b1 + n_b2) {
+            const bool first = i < n_b1;
+            const size_t j = first ? i : i - n_b1;
+            const int nsp = first ? L.nsp1 : L.nsp2, steps = first ? L.steps1 : L.steps2;
+            const int lane = (int)(j % 64);
+            const int sp = (int)((j / 64) % nsp);
+            const int ct = (int)(j / 64 / nsp);
+            const int col = 32 * ct + (lane & 31);
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int b = 0; b < 16; ++b) {
+                const int s = 2 * sp + b / 8, kk = 16 * s + 8 * (lane >> 5) + (b & 7);
+                uint32_t byte = 0;
+                if (s < steps) {
+                    if (first) {          // B1[kk][col]: col = m rp + rho
+                        const int m = col / L.rp, rho = col % L.rp;
+                        if (col < L.n1 && rho < L.r) byte = u8[((size_t)m * L.n_in + kk) * L.r + rho];
+                    } else {              // B2[kk][col]: kk = n rp + rho
+                        const int n = kk / L.rp, rho = kk % L.rp;
+                        if (rho < L.r) byte = v8[((size_t)n * L.r + rho) * L.n_out + col];
+                    }
+                }
+                w[b / 4] |= byte << (8 * (b & 3));
+            }
+            u32x4 o = {w[0], w[1], w[2], w[3]};
+            *reinterpret_cast<u32x4*>(packed + (first ? L.off_b1 : L.off_b2) + j * 16) = o;
+        } else if (i < n_b1 + n_b2 + (size_t)L.E) {
+            const int e = (int)(i - n_b1 - n_b2);
+            int m = phi[2 * e], n = phi[2 * e + 1];
+            if (m < 0 || m >= L.M || n < 0 || n >= L.N) {
+                if (err_flag) atomicOr(err_flag, 1);
+                m = min(max(m, 0), L.M - 1);
+                n = min(max(n, 0), L.N - 1);
+            }
+            int32_t* dst = reinterpret_cast<int32_t*>(packed + L.off_phi) + 2 * e;
+            dst[0] = m;
+            dst[1] = n;
+        } else {
+            const int rho = (int)(i - n_b1 - n_b2 - (size_t)L.E);
+            reinterpret_cast<float*>(packed + L.off_sigma)[rho] = rho < L.r ? tq_half_bits_to_float(sigma[rho]) : 0.f;
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < 16) {
+        const int32_t hdr[16] = {(int32_t)LT_MAGIC, 1, L.E, L.M, L.N, L.n_in, L.n_out, L.r, L.rp, 1, 0, 0, 0, 0, 0, 0};
+        reinterpret_cast<int32_t*>(packed)[threadIdx.x] = hdr[threadIdx.x];
+    }
+}
+
+// eight fp8 E4M3 values (two dwords) -> the bf16 operand of one MFMA step; exact: E4M3 has three mantissa bits
+__device__ inline bf16x8 fp8x8_to_bf8(uint32_t d0, uint32_t d1)
+{
+    Frag f;
+    const uint32_t d[2] = {d0, d1};
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const auto lo = __builtin_amdgcn_cvt_pk_f32_fp8(d[q], false);
+        const auto hi = __builtin_amdgcn_cvt_pk_f32_fp8(d[q], true);
+        f.u[2 * q] = (__float_as_uint(lo[0]) >> 16) | (__float_as_uint(lo[1]) & 0xFFFF0000u);
+        f.u[2 * q + 1] = (__float_as_uint(hi[0]) >> 16) | (__float_as_uint(hi[1]) & 0xFFFF0000u);
+    }
+    return f.v;
+}
+
 // ---- dense product C[T, 32 nt] = A[T, 16 steps] B, B in fragment order ----------------------------------------
 // grid (column blocks of 4 NTW tiles, row tiles of 32 MT rows, K splits).  A workgroup stages its rows of A
 // through LDS in 128-wide chunks; wave w owns NTW column tiles and all MT row sub-tiles, so a B fragment (one
@@ -145,13 +221,14 @@ struct LtGemmArgs {
     const uint16_t* A;
     int lda, T;
     const u32x4* bfrag;
-    int steps, ntiles;
+    int steps, ntiles;    // MFMA steps of the contraction, column tiles of B
+    int nsp;              // fp8 only: step pairs per column tile
     void* C;
     int ldc;
     int32_t* clear;       // not null: the first workgroup zeroes this word (the operator's error flag)
 };
 
-template <int MT, int NTW, bool OUT_BF16>
+template <int MT, int NTW, bool OUT_BF16, bool FP8>
 __global__ void __launch_bounds__(256) lt_gemm_kernel(LtGemmArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
@@ -204,10 +281,13 @@ __global__ void __launch_bounds__(256) lt_gemm_kernel(LtGemmArgs a)
     if (c0 < c1) {
         const int s_last = min(c1 * SPC, steps) - 1;      // steps past it multiply zeros: any valid fragment serves
         u32x4 bq[PF][NTW];
+        // bf16 factors: slot = one step; fp8 factors: slot = a pair of steps in one 16-byte load
         auto load_b = [&](int slot, int s) {
             const int sc = min(s, s_last);
 #pragma unroll
-            for (int j = 0; j < NTW; ++j) bq[slot][j] = a.bfrag[((size_t)ct[j] * steps + sc) * 64 + lane];
+            for (int j = 0; j < NTW; ++j)
+                bq[slot][j] = FP8 ? a.bfrag[((size_t)ct[j] * a.nsp + (sc >> 1)) * 64 + lane]
+                                  : a.bfrag[((size_t)ct[j] * steps + sc) * 64 + lane];
         };
         // first chunk's A loads, then the B prefetch, then the A store: the loads outstanding on entry to the loop
         // are the same four B slots, in the same order, as at its back edge (the wait counts are derived from the
@@ -215,7 +295,7 @@ __global__ void __launch_bounds__(256) lt_gemm_kernel(LtGemmArgs a)
         load_chunk(c0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < PF; ++i) load_b(i, c0 * SPC + i);
+        for (int i = 0; i < PF; ++i) load_b(i, c0 * SPC + (FP8 ? 2 * i : i));
         __builtin_amdgcn_sched_barrier(0);
         store_chunk(0);
         lds_barrier();
@@ -240,12 +320,18 @@ __global__ void __launch_bounds__(256) lt_gemm_kernel(LtGemmArgs a)
 #pragma unroll
                 for (int j = 0; j < NTW; ++j) {
                     Frag b;
-                    b.q = bq[ks % PF][j];
+                    if (FP8) {
+                        const u32x4 raw = bq[(ks >> 1) % PF][j];
+                        b.v = (ks & 1) ? fp8x8_to_bf8(raw[2], raw[3]) : fp8x8_to_bf8(raw[0], raw[1]);
+                    } else {
+                        b.q = bq[ks % PF][j];
+                    }
 #pragma unroll
                     for (int i = 0; i < MT; ++i)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[ks & 1][i].v, b.v, acc[i][j], 0, 0, 0);
                 }
-                load_b(ks % PF, c * SPC + ks + PF);
+                if (!FP8) load_b(ks % PF, c * SPC + ks + PF);
+                else if (ks & 1) load_b((ks >> 1) % PF, c * SPC + ks - 1 + 2 * PF);
                 __builtin_amdgcn_sched_barrier(0);
             }
             store_chunk(buf ^ 1);
@@ -269,10 +355,10 @@ __global__ void __launch_bounds__(256) lt_gemm_kernel(LtGemmArgs a)
     }
 }
 
-template <int MT, int NTW, bool OUT_BF16>
+template <int MT, int NTW, bool OUT_BF16, bool FP8>
 tq_status lt_launch_gemm_inst(const LtGemmArgs& a, int planes, hipStream_t st)
 {
-    auto kern = lt_gemm_kernel<MT, NTW, OUT_BF16>;
+    auto kern = lt_gemm_kernel<MT, NTW, OUT_BF16, FP8>;
     constexpr size_t smem = 2 * 32 * MT * LT_ROWB;
     static bool done = false;
     if (!done) {
@@ -287,18 +373,18 @@ tq_status lt_launch_gemm_inst(const LtGemmArgs& a, int planes, hipStream_t st)
     return TQ_OK;
 }
 
-template <bool OUT_BF16>
+template <bool OUT_BF16, bool FP8>
 tq_status lt_launch_gemm(const LtGemmArgs& a, int mt, int ntw, int planes, hipStream_t st)
 {
     if (mt == 1) {
-        if (ntw == 1) return lt_launch_gemm_inst<1, 1, OUT_BF16>(a, planes, st);
-        if (ntw == 2) return lt_launch_gemm_inst<1, 2, OUT_BF16>(a, planes, st);
-        return lt_launch_gemm_inst<1, 3, OUT_BF16>(a, planes, st);
+        if (ntw == 1) return lt_launch_gemm_inst<1, 1, OUT_BF16, FP8>(a, planes, st);
+        if (ntw == 2) return lt_launch_gemm_inst<1, 2, OUT_BF16, FP8>(a, planes, st);
+        return lt_launch_gemm_inst<1, 3, OUT_BF16, FP8>(a, planes, st);
     }
     if (mt == 2) {
-        if (ntw == 1) return lt_launch_gemm_inst<2, 1, OUT_BF16>(a, planes, st);
-        if (ntw == 2) return lt_launch_gemm_inst<2, 2, OUT_BF16>(a, planes, st);
-        return lt_launch_gemm_inst<2, 3, OUT_BF16>(a, planes, st);
+        if (ntw == 1) return lt_launch_gemm_inst<2, 1, OUT_BF16, FP8>(a, planes, st);
+        if (ntw == 2) return lt_launch_gemm_inst<2, 2, OUT_BF16, FP8>(a, planes, st);
+        return lt_launch_gemm_inst<2, 3, OUT_BF16, FP8>(a, planes, st);
     }
     return TQ_ERR_UNSUPPORTED;
 }
@@ -312,7 +398,8 @@ constexpr int LT_GATHER_TAB = 1024;      // selections per workgroup held in LDS
 __global__ void __launch_bounds__(256) lt_gather_kernel(LtLayout L, const int32_t* __restrict__ phi,
                                                         const int32_t* __restrict__ idx, const float* __restrict__ w,
                                                         const float* __restrict__ xproj, int planes, int ldx, int T, int tb,
-                                                        uint16_t* __restrict__ S, int32_t* __restrict__ err)
+                                                        const float* __restrict__ sigma, uint16_t* __restrict__ S,
+                                                        int32_t* __restrict__ err)
 {
     __shared__ int32_t tm[LT_GATHER_TAB], tn[LT_GATHER_TAB];
     __shared__ float tg[LT_GATHER_TAB];
@@ -360,6 +447,10 @@ __global__ void __launch_bounds__(256) lt_gather_kernel(LtLayout L, const int32_
             }
             s0 = fmaf(g, xp.x, s0); s1 = fmaf(g, xp.y, s1); s2 = fmaf(g, xp.z, s2); s3 = fmaf(g, xp.w, s3);
         }
+        if (sigma) {      // mixed-precision factors: X_proj was formed on U alone, Sigma scales its rank components
+            const float4 sg = *reinterpret_cast<const float4*>(sigma + rho);
+            s0 *= sg.x; s1 *= sg.y; s2 *= sg.z; s3 *= sg.w;
+        }
         uint2 o = {pack_bf2(s0, s1), pack_bf2(s2, s3)};
         *reinterpret_cast<uint2*>(S + (size_t)b * L.k2 + c) = o;
     }
@@ -379,11 +470,26 @@ extern "C" tq_status tq_lotile_pack(const tq_lotile_desc* desc, const uint16_t* 
 {
     if (!desc || !us || !v || !phi || !packed) return TQ_ERR_NULL;
     LtLayout L;
-    if (!lt_make_layout(desc, &L)) return TQ_ERR_SHAPE;
+    if (!lt_make_layout(desc, &L) || L.fp8) return TQ_ERR_SHAPE;
     if (((uintptr_t)packed & 255) || (((uintptr_t)us | (uintptr_t)v | (uintptr_t)phi) & 15)) return TQ_ERR_ALIGN;
     if (packed_bytes < L.total) return TQ_ERR_WORKSPACE;
     hipLaunchKernelGGL(lt_pack_kernel, dim3(1024), dim3(256), 0, (hipStream_t)stream, L, us, v, phi, (uint8_t*)packed,
                        err_flag);
+    TQ_CHECK_LAUNCH();
+    return TQ_OK;
+}
+
+extern "C" tq_status tq_lotile_pack_fp8(const tq_lotile_desc* desc, const uint8_t* u8, const uint16_t* sigma,
+                                        const uint8_t* v8, const int32_t* phi, void* packed, size_t packed_bytes,
+                                        int32_t* err_flag, void* stream)
+{
+    if (!desc || !u8 || !sigma || !v8 || !phi || !packed) return TQ_ERR_NULL;
+    LtLayout L;
+    if (!lt_make_layout(desc, &L) || !L.fp8) return TQ_ERR_SHAPE;
+    if (((uintptr_t)packed & 255) || (((uintptr_t)u8 | (uintptr_t)v8 | (uintptr_t)sigma | (uintptr_t)phi) & 15)) return TQ_ERR_ALIGN;
+    if (packed_bytes < L.total) return TQ_ERR_WORKSPACE;
+    hipLaunchKernelGGL(lt_pack_fp8_kernel, dim3(1024), dim3(256), 0, (hipStream_t)stream, L, u8, sigma, v8, phi,
+                       (uint8_t*)packed, err_flag);
     TQ_CHECK_LAUNCH();
     return TQ_OK;
 }
@@ -418,20 +524,22 @@ extern "C" tq_status tq_lotile_forward(const tq_lotile_desc* desc, const void* p
     uint16_t* S = (uint16_t*)(ws + W.s);
     tqi_record_stage(0, st);
     // step one: the global projection on every row tile's factor (its first workgroup clears the error flag)
-    LtGemmArgs g1 = {(const uint16_t*)x, L.n_in, T, (const u32x4*)(pk + L.off_b1), L.steps1, L.nt1, (void*)xproj, W.ldx, ctrl};
-    tq_status rc = lt_launch_gemm<false>(g1, W.mt, W.ntw1, W.planes, st);
+    LtGemmArgs g1 = {(const uint16_t*)x, L.n_in, T, (const u32x4*)(pk + L.off_b1), L.steps1, L.nt1, L.nsp1, (void*)xproj, W.ldx, ctrl};
+    tq_status rc = L.fp8 ? lt_launch_gemm<false, true>(g1, W.mt, W.ntw1, W.planes, st)
+                         : lt_launch_gemm<false, false>(g1, W.mt, W.ntw1, W.planes, st);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(1, st);
     // step two: routing-weighted selection and accumulation into the compact buffer
     const int q4 = L.k2 / 4;
     const int tb = std::max(1, std::min({T / 256, std::max(1, 512 / q4), LT_GATHER_TAB / L.k}));
     hipLaunchKernelGGL(lt_gather_kernel, dim3((T + tb - 1) / tb), dim3(256), 0, st, L, (const int32_t*)(pk + L.off_phi),
-                       topk_idx, topk_w, (const float*)xproj, W.planes, W.ldx, T, tb, S, ctrl);
+                       topk_idx, topk_w, (const float*)xproj, W.planes, W.ldx, T, tb,
+                       L.fp8 ? (const float*)(pk + L.off_sigma) : nullptr, S, ctrl);
     TQ_CHECK_LAUNCH();
     tqi_record_stage(2, st);
     // step three: output reconstruction
-    LtGemmArgs g2 = {(const uint16_t*)S, L.k2, T, (const u32x4*)(pk + L.off_b2), L.steps2, L.nt2, y, L.n_out, nullptr};
-    rc = lt_launch_gemm<true>(g2, W.mt, W.ntw2, 1, st);
+    LtGemmArgs g2 = {(const uint16_t*)S, L.k2, T, (const u32x4*)(pk + L.off_b2), L.steps2, L.nt2, L.nsp2, y, L.n_out, nullptr};
+    rc = L.fp8 ? lt_launch_gemm<true, true>(g2, W.mt, W.ntw2, 1, st) : lt_launch_gemm<true, false>(g2, W.mt, W.ntw2, 1, st);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(3, st);
     return TQ_OK;

@@ -116,7 +116,7 @@ def test_lotile_packed_size_closed_form():
 
 
 @pytest.mark.parametrize("kw", [dict(E=0), dict(M=0), dict(N=0), dict(n_in=100), dict(n_out=16), dict(r=0), dict(r=257),
-                                dict(k=0), dict(k=9), dict(flags=1)])
+                                dict(k=0), dict(k=9), dict(flags=2)])
 def test_lotile_invalid_descriptors(kw):
     a = dict(E=8, M=3, N=3, n_in=128, n_out=64, r=8, k=2, flags=0)
     a.update(kw)
@@ -143,3 +143,25 @@ def test_lotile_host_argument_checks():
     assert L.tq_lotile_pack(ctypes.byref(d), 256, 256, 256, 256, 16, None, None) == 5
     # the workspace grows with T and never shrinks
     assert tq.tq_lotile_workspace_size(d, 4096) > need
+
+
+def test_lotile_fp8_packed_size_and_flag_checks():
+    """Appendix A.3 with d_low = 8: one byte per factor entry (rank padded to 16, contraction to pairs of MFMA steps),
+    an fp32 copy of Sigma, the placement table and a header; about half the bf16 form."""
+    al = lambda n: (n + 255) // 256 * 256
+    L = tq.lib()
+    for E, M, N, n_in, n_out, r in [(8, 3, 3, 4096, 14336, 32), (64, 8, 8, 1408, 2048, 16), (6, 2, 3, 96, 160, 20)]:
+        rp = (r + 15) // 16 * 16
+        d8 = tq.make_lotile_desc(E, M, N, n_in, n_out, r, 2, tq.TQ_LOTILE_FP8)
+        d16 = tq.make_lotile_desc(E, M, N, n_in, n_out, r, 2)
+        n8, n16 = tq.tq_lotile_packed_size(d8), tq.tq_lotile_packed_size(d16)
+        b1 = -(-(M * rp) // 32) * 32 * (-(-(n_in // 16) // 2) * 32)
+        b2 = n_out * (-(-(N * rp // 16) // 2) * 32)
+        assert n8 == 256 + al(E * 8) + al(rp * 4) + al(b1) + al(b2)
+        assert n8 < 0.6 * n16
+        assert tq.tq_lotile_workspace_size(d8, 64) == tq.tq_lotile_workspace_size(d16, 64)
+        # each pack entry point accepts only its own storage form
+        assert L.tq_lotile_pack(ctypes.byref(d8), 256, 256, 256, 256, 1 << 30, None, None) == 2
+        assert L.tq_lotile_pack_fp8(ctypes.byref(d16), 256, 256, 256, 256, 256, 1 << 30, None, None) == 2
+        assert L.tq_lotile_pack_fp8(ctypes.byref(d8), 256, None, 256, 256, 256, 1 << 30, None, None) == 1
+        assert L.tq_lotile_pack_fp8(ctypes.byref(d8), 256, 256, 256, 256, 256, 16, None, None) == 5
