@@ -7,8 +7,10 @@ namespace {
 
 constexpr int kMaxPerLane = 16;  // E <= 64 * 16
 
-// One wavefront per token.  Lane l holds the scores of experts l, l+64, l+128, ...
+// One wavefront per token.  Lane l holds the scores of experts l, l+64, l+128, ... (PL of them: the per-lane scans
+// are unrolled to the number of experts a lane can hold, not to the maximum).
 // Each of the k rounds takes the wave-wide maximum under the order (score desc, index asc).
+template <int PL>
 __global__ void __launch_bounds__(256) route_kernel(const float* __restrict__ logits,
                                                     const float* __restrict__ bias, int T, int E, int k,
                                                     int32_t* __restrict__ topk_idx, float* __restrict__ topk_w)
@@ -16,14 +18,13 @@ __global__ void __launch_bounds__(256) route_kernel(const float* __restrict__ lo
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (t >= T) return;
-    float v[kMaxPerLane];
+    float v[PL];
     uint32_t taken = 0;
-    const int per_lane = (E + 63) >> 6;
 #pragma unroll
-    for (int i = 0; i < kMaxPerLane; ++i) {
+    for (int i = 0; i < PL; ++i) {
         int e = lane + 64 * i;
         float s = -INFINITY;
-        if (i < per_lane && e < E) {
+        if (e < E) {
             s = logits[(size_t)t * E + e];
             if (bias) s = s + bias[e];
         } else {
@@ -37,7 +38,7 @@ __global__ void __launch_bounds__(256) route_kernel(const float* __restrict__ lo
         float bv = 0.f;
         int be = 0x7FFFFFFF;
 #pragma unroll
-        for (int i = 0; i < kMaxPerLane; ++i) {
+        for (int i = 0; i < PL; ++i) {
             if (!((taken >> i) & 1u)) {
                 if (be == 0x7FFFFFFF || v[i] > bv) { bv = v[i]; be = lane + 64 * i; }
             }
@@ -449,8 +450,13 @@ extern "C" tq_status tq_route(const float* logits, const float* bias, int32_t T,
     if (E > 64 * kMaxPerLane || k > 64) return TQ_ERR_UNSUPPORTED;
     if (((uintptr_t)logits | (uintptr_t)topk_idx | (uintptr_t)topk_w | (uintptr_t)bias) & 3) return TQ_ERR_ALIGN;
     if (T == 0) return TQ_OK;
-    hipLaunchKernelGGL(route_kernel, dim3((T + 3) / 4), dim3(256), 0, (hipStream_t)stream, logits, bias, T, E, k,
-                       topk_idx, topk_w);
+    const int per_lane = (E + 63) / 64;
+    const dim3 grid((T + 3) / 4), block(256);
+    hipStream_t st = (hipStream_t)stream;
+    if (per_lane == 1) hipLaunchKernelGGL(route_kernel<1>, grid, block, 0, st, logits, bias, T, E, k, topk_idx, topk_w);
+    else if (per_lane == 2) hipLaunchKernelGGL(route_kernel<2>, grid, block, 0, st, logits, bias, T, E, k, topk_idx, topk_w);
+    else if (per_lane <= 4) hipLaunchKernelGGL(route_kernel<4>, grid, block, 0, st, logits, bias, T, E, k, topk_idx, topk_w);
+    else hipLaunchKernelGGL(route_kernel<kMaxPerLane>, grid, block, 0, st, logits, bias, T, E, k, topk_idx, topk_w);
     TQ_CHECK_LAUNCH();
     return TQ_OK;
 }
