@@ -24,7 +24,7 @@ MFMA_BF16_PEAK = 2.5e15    # FLOP/s dense bf16, MI355X published
 # HBM bytes per launch of the dominant kernel from the rocprofv3 FETCH_SIZE + WRITE_SIZE passes (scaled by the
 # streaming-copy calibration), see profiles/hbm_traffic_config2_skinny_kernels.txt.  Only the decode workload
 # has been counted; other workloads report null.
-MEASURED_TRAFFIC_BYTES = {2: 538.3e6 + 1.0e6}
+MEASURED_TRAFFIC_BYTES = {2: 551.2e6 + 1.0e6}
 STAGES = ["permute", "aug_gate_up", "gate_up", "aug_down", "down", "combine"]
 
 
@@ -62,7 +62,8 @@ class HipEvents:
 
 
 def algorithmic_work(cfg, idx_np):
-    """Algorithmic bytes and flops of one forward, whole path and per dominant kernel."""
+    """Algorithmic bytes and flops of one forward, whole path and per dominant kernel: every expert that receives a
+    token is read once (codes, scales, zeros, factors), every activation row once per stage."""
     import numpy as np
     H, F, g, r, T = cfg.H, cfg.F, cfg.g, cfg.r, cfg.T
     touched = int(np.unique(idx_np).size) + cfg.S
@@ -167,7 +168,7 @@ def bench_lotile(args, cfg, dev):
     stage_us = {n: st_ms[q] / n_prof * 1e3 for q, n in enumerate(("projection", "gather", "output"))}
     log("stage durations (us): " + ", ".join(f"{k}={v:.1f}" for k, v in stage_us.items()))
     rp = (r + 15) // 16 * 16
-    # algorithmic work of the operator and of its two products (factors bf16, X_proj fp32, S bf16)
+    # algorithmic work of the operator and of its two products (factors as stored, X_proj fp32, S bf16, each read or written once)
     alg_bytes = cfg.T * n_in * 2 + n_in * M * r * fb + N * r * n_out * fb + cfg.T * n_out * 2 + cfg.T * cfg.k * 8
     flops = 2.0 * cfg.T * (n_in * M * r + N * r * n_out)
     kern = {"projection": dict(name="lt_gemm_kernel<.,.,false> (X_proj = x (U Sigma)_reshape)",
@@ -244,8 +245,8 @@ def main():
                     help="instead of the workload: time a plain 1 GiB streaming copy and read (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only (the path is a single-GPU kernel library; "
-              "see DESIGN.md for how it would shard). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the path is a single-GPU kernel library with no collectives). "
+              "Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
@@ -263,7 +264,7 @@ def main():
         stream = torch.cuda.current_stream().cuda_stream
         ev = HipEvents(2)
         res = {}
-        for mode, name in ((0, "copy"), (1, "read")):
+        for mode, name in ((0, "copy"), (1, "read"), (2, "read_nontemporal")):
             for i in range(3):
                 tq.tq_debug_stream(bufs[i % 3], dst, nbytes, mode)
             torch.cuda.synchronize()

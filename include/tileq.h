@@ -177,7 +177,8 @@ tq_status tq_set_profile_events(void *const *events, int32_t n);
 
 /* Measurement aid (not part of the method): streams `bytes` (a multiple of 16) from src with 16-byte
  * accesses.  mode 0 copies them to dst (dst holds `bytes`); mode 1 only reads them (dst needs 16 bytes and
- * is practically never written).  Used to calibrate hardware byte counters against a transfer of known
+ * is practically never written); mode 2 reads them with the non-temporal hint, one contiguous slab per
+ * workgroup (the access pattern of the decode kernels' weight stream).  Used to calibrate hardware byte counters against a transfer of known
  * size and to measure the streaming rate the memory system attains. */
 tq_status tq_debug_stream(const void *src, void *dst, size_t bytes, int32_t mode, void *stream);
 

@@ -199,7 +199,8 @@ def tq_set_profile_events(events) -> None:
 
 
 def tq_debug_stream(src, dst, nbytes: int, mode: int) -> None:
-    """Streaming copy (mode 0) or read (mode 1) of nbytes with 16-byte accesses: a measurement aid."""
+    """Streaming copy (mode 0), read (mode 1) or non-temporal read (mode 2) of nbytes with 16-byte accesses: a
+    measurement aid."""
     _check(lib().tq_debug_stream(_ptr(src), _ptr(dst), nbytes, mode, _stream()), "tq_debug_stream")
 
 

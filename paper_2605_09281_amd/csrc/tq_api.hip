@@ -58,19 +58,41 @@ __global__ void __launch_bounds__(512) debug_read_kernel(const uint4* __restrict
     for (; i < n; i += stride) { const uint4 v = src[i]; a.x ^= v.x; a.y ^= v.y; a.z ^= v.z; a.w ^= v.w; }
     if ((a.x ^ a.y ^ a.z ^ a.w) == 0x9E3779B9u) dst[0] = a;      // keeps the loads alive; practically never taken
 }
+// the same read with the non-temporal hint, one contiguous slab per workgroup, eight loads in flight per thread:
+// the pattern of a stream that is read once (the decode kernels' packed codes)
+typedef uint32_t dbg_u32x4 __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(256) debug_read_nt_kernel(const dbg_u32x4* __restrict__ src, dbg_u32x4* __restrict__ dst, size_t n)
+{
+    const size_t per = (n + gridDim.x - 1) / gridDim.x;
+    const size_t lo = (size_t)blockIdx.x * per, hi = lo + per < n ? lo + per : n;
+    dbg_u32x4 a = {0, 0, 0, 0};
+    size_t i = lo + threadIdx.x;
+    for (; i + 7 * 256 < hi; i += 8 * 256) {
+        dbg_u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + i + u * 256);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a ^= v[u];
+    }
+    for (; i < hi; i += 256) a ^= __builtin_nontemporal_load(src + i);
+    if ((a[0] ^ a[1] ^ a[2] ^ a[3]) == 0x9E3779B9u) dst[0] = a;
+}
 }  // namespace
 
 extern "C" tq_status tq_debug_stream(const void* src, void* dst, size_t bytes, int32_t mode, void* stream)
 {
     if (!src || !dst) return TQ_ERR_NULL;
     if ((((uintptr_t)src | (uintptr_t)dst) & 15) || (bytes & 15)) return TQ_ERR_ALIGN;
-    if (mode != 0 && mode != 1) return TQ_ERR_SHAPE;
+    if (mode < 0 || mode > 2) return TQ_ERR_SHAPE;
     if (bytes == 0) return TQ_OK;
     const size_t n = bytes / 16;
     if (mode == 0)
         hipLaunchKernelGGL(debug_copy_kernel, dim3(2048), dim3(512), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst, n);
-    else
+    else if (mode == 1)
         hipLaunchKernelGGL(debug_read_kernel, dim3(2048), dim3(512), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst, n);
+    else
+        hipLaunchKernelGGL(debug_read_nt_kernel, dim3(512), dim3(256), 0, (hipStream_t)stream, (const dbg_u32x4*)src,
+                           (dbg_u32x4*)dst, n);
     TQ_CHECK_LAUNCH();
     return TQ_OK;
 }

@@ -136,7 +136,8 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int c = 0; c < UC; ++c) dst[t][c] = codes[(((size_t)pair * sec.chunks + chunk0 + c) * 2 + t) * 64];
+            for (int c = 0; c < UC; ++c)      // read once, never again: the non-temporal hint keeps the stream out of the caches
+                dst[t][c] = __builtin_nontemporal_load(&codes[(((size_t)pair * sec.chunks + chunk0 + c) * 2 + t) * 64]);
     };
     auto load_sz = [&](uint32_t (&dst)[NG][2], int pair, int u) {
         const int g0 = min(ub + wave * UPW + u, ue - 1) * NG;
@@ -286,7 +287,9 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     int pnext_raw = pq[0];
     int it = 0;
     for (int pair = p0; pair < npairs;) {
-        const int pnext = pnext_raw < npairs ? pnext_raw : pair;     // nothing left: re-request this pair (cache hits)
+        const int pnext = pnext_raw < npairs ? pnext_raw : pair;     // nothing left: re-request this pair (its scales and
+                                                                     // factors hit the cache; the codes are fetched again, once
+                                                                     // per workgroup: measured cheaper than a guarded prefetch)
         int fetched = 0;
         if (tid == 0) fetched = (int)gridDim.x + atomicAdd(cnt, 1);       // the pair after the next one
         float acc8[2][8];
