@@ -632,7 +632,8 @@ __global__ void __launch_bounds__(256) combine_bf16_kernel(int T, int H, int k, 
         if (slot < 0) continue;
         const float wj = j < k ? w[(size_t)t * k + j] : 1.0f;
         if constexpr (YD16) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(ydv) + (size_t)slot * H + c);
+            // every row is read exactly once: non-temporal
+            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(ydv) + (size_t)slot * H + c));
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 a[2 * i] = fmaf(wj, bf_lo(v[i]), a[2 * i]);
