@@ -373,7 +373,10 @@ def main():
     t_gu = stage_us["gate_up"] * 1e-6
     if hbm_bound:
         ach = work["gate_up_bytes"] / t_gu / 1e9
-        roofline = dict(bound="hbm", kernel="gate/up stage (moe_skinny_kernel<0> on decode batches)",
+        # the library streams weights through its 16-row kernels up to 12 rows per expert, else it runs the tiled kernels
+        decode_path = cfg.a_tot / (cfg.E + cfg.S) <= 12 and cfg.a_tot <= 1024
+        roofline = dict(bound="hbm", kernel="gate/up stage (moe_skinny_kernel<0>)" if decode_path else
+                        "gate/up stage (moe_prefill_kernel<0,.>, or moe_mfma_kernel<.,.,0,.> where the layer does not qualify)",
                         achieved=round(ach, 1), peak=HBM_PEAK / 1e9,
                         unit="GB/s", frac=round(ach / (HBM_PEAK / 1e9), 4),
                         traffic=MEASURED_TRAFFIC_BYTES.get(cfg.cfg_id), algorithmic_bytes=work["gate_up_bytes"],
