@@ -22,12 +22,31 @@ union Frag {
     u32x4 q;
 };
 
-__device__ inline uint32_t f2bf_bits(float f)
+// fp32 -> bf16, round to nearest even.  Written as vector conversions so that the compiler selects the hardware
+// conversion of this target (one instruction per pair) instead of an integer rounding sequence.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t pack_bf2(float a, float b)
 {
-    uint32_t u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    const f32x2_t v = {a, b};
+    const bf16x2_t r = __builtin_convertvector(v, bf16x2_t);
+    uint32_t u;
+    __builtin_memcpy(&u, &r, 4);
+    return u;
 }
-__device__ inline uint32_t pack_bf2(float a, float b) { return f2bf_bits(a) | (f2bf_bits(b) << 16); }
+__device__ inline uint32_t f2bf_bits(float f) { return pack_bf2(f, 0.f) & 0xFFFFu; }
+// two fp16 values in one word -> two bf16 values in one word
+__device__ inline uint32_t half2_to_bf2(uint32_t w)
+{
+    f16x2_t h;
+    __builtin_memcpy(&h, &w, 4);
+    const f32x2_t f = __builtin_convertvector(h, f32x2_t);
+    const bf16x2_t r = __builtin_convertvector(f, bf16x2_t);
+    uint32_t u;
+    __builtin_memcpy(&u, &r, 4);
+    return u;
+}
 __device__ inline float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ inline float bf_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
@@ -48,10 +67,8 @@ __device__ inline bf16x8 unpack_word(uint32_t w, uint32_t mask, uint32_t magic)
 __device__ inline bf16x8 half8_to_bf8(u32x4 q)
 {
     Frag f;
-    const uint32_t in[4] = {q[0], q[1], q[2], q[3]};
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-        f.u[j] = pack_bf2(tq_half_bits_to_float((uint16_t)(in[j] & 0xFFFF)), tq_half_bits_to_float((uint16_t)(in[j] >> 16)));
+    for (int j = 0; j < 4; ++j) f.u[j] = half2_to_bf2(q[j]);
     return f.v;
 }
 
