@@ -260,12 +260,15 @@ __global__ void __launch_bounds__(256, 2) aug_staged_kernel(MGeom G, TqSection s
                 zb[16] = (uint16_t)lo;
                 zb[32] = (uint16_t)hi;
             }
+            // NAT is the number of column tiles of t whenever there are factors at all, so one uniform test covers
+            // the block (a test per MFMA turns into a copy of the accumulator per MFMA)
+            if (na_tiles > 0) {
 #pragma unroll
-            for (int ks = 0; ks < GS; ++ks)
+                for (int ks = 0; ks < GS; ++ks)
 #pragma unroll
-                for (int j = 0; j < NAT; ++j)
-                    if (j < na_tiles)
+                    for (int j = 0; j < NAT; ++j)
                         acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[ks].v, half8_to_bf8(aq[ks][j]), acc[j], 0, 0, 0);
+            }
         }
         store_chunk((c + 1) & 1);
         lds_barrier();
