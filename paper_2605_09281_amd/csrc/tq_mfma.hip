@@ -190,7 +190,10 @@ __global__ void __launch_bounds__(256, 2) aug_staged_kernel(MGeom G, TqSection s
     const int nchunks = (groups + 3) / 4;
     const int na_tiles = (G.r > 0) ? sec.na_tiles : 0;
     const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
-    const u32x4* af = reinterpret_cast<const u32x4*>(rec + sec.afrag) + lane;
+    // layers without factors have an empty fragment section: their (unconditional, unused) fragment loads all read
+    // the first kilobyte of the codes instead of running past the record
+    const u32x4* af = reinterpret_cast<const u32x4*>(rec + (na_tiles > 0 ? sec.afrag : sec.codes)) + lane;
+    const size_t af_live = na_tiles > 0 ? 1 : 0;
     uint16_t* orow = xaug + (size_t)(slot0 + col) * ka;
     const bool writer = (hf == 0) && (col < rows);
 
@@ -238,7 +241,7 @@ __global__ void __launch_bounds__(256, 2) aug_staged_kernel(MGeom G, TqSection s
             for (int ks = 0; ks < GS; ++ks)
 #pragma unroll
                 for (int j = 0; j < NAT; ++j)
-                    aq[ks][j] = af[((size_t)min(j, max(na_tiles, 1) - 1) * ksteps + gic * GS + ks) * 64];
+                    aq[ks][j] = af[((size_t)min(j, max(na_tiles, 1) - 1) * ksteps + gic * GS + ks) * 64 * af_live];
         }
         load_chunk(min(c + 1, nchunks - 1));
         if (gi < groups) {
