@@ -52,6 +52,8 @@ CASES = {
     "single_row_tile": (lt_cfg(307, T=33, E=5, k=5), 128, 128, 1, 5),
     "single_col_tile": (lt_cfg(308, T=33, E=4, k=2), 128, 128, 4, 1),
     "all_experts": (lt_cfg(309, T=40, E=6, k=6, r=4), 64, 32, None, None),
+    "many_selections": (lt_cfg(313, T=19, E=300, k=270, r=8, H=128), 128, 64, None, None),   # selection table: one token per workgroup
+    "many_selections_many_rows": (lt_cfg(314, T=700, E=40, k=33, r=16, H=128), 128, 96, None, None),
 }
 
 
