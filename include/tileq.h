@@ -238,6 +238,20 @@ tq_status tq_lotile_forward(const tq_lotile_desc *desc, const void *packed, cons
                             const int32_t *topk_idx, const float *topk_w, int32_t T, void *y,
                             void *workspace, size_t workspace_bytes, void *stream);
 
+/* Offline helpers for the shared-factor format (host only, no GPU work, host pointers).
+ *
+ * tq_lotile_grid: the near-square tile grid for E experts (Appendix B, Evaluation Details, "Tiling-size"): M = the integer closest to
+ * sqrt(E), N = ceil(E / M), so that M N >= E.
+ *
+ * tq_lotile_place: the greedy 2D-tiling placement (Section 3.1, Step 4, Eq. 9-10).  ideal [E][2] holds each
+ * expert's ideal tile (m_k, n_k) from the biclustering; experts are placed in index order; the anchor of an expert
+ * is its ideal tile clamped into the grid; the unoccupied cell of the smallest Chebyshev distance rho = 0, 1, 2, ...
+ * from the anchor is taken.  The paper leaves the order inside a ring open: here a ring is scanned row by row
+ * (m ascending, n ascending within a row).  phi [E][2] receives the placement: no two experts share a cell.
+ * TQ_ERR_SHAPE if M N < E. */
+tq_status tq_lotile_grid(int32_t n_experts, int32_t *tiles_m, int32_t *tiles_n);
+tq_status tq_lotile_place(const int32_t *ideal, int32_t n_experts, int32_t tiles_m, int32_t tiles_n, int32_t *phi);
+
 #ifdef __cplusplus
 }
 #endif

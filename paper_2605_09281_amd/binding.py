@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "TQ_OK", 1: "TQ_ERR_NULL", 2: "TQ_ERR_SHAPE", 3: "TQ_ERR_ALIG
 EXPORTS = ["tq_status_str", "tq_packed_size", "tq_pack_weights", "tq_unpack_weights", "tq_route",
            "tq_permute_workspace_size", "tq_permute", "tq_moe_workspace_size", "tq_moe_forward",
            "tq_set_profile_events", "tq_debug_stream", "tq_lotile_packed_size", "tq_lotile_pack", "tq_lotile_pack_fp8",
-           "tq_lotile_workspace_size", "tq_lotile_forward"]
+           "tq_lotile_workspace_size", "tq_lotile_forward", "tq_lotile_grid", "tq_lotile_place"]
 
 
 class TqError(RuntimeError):
@@ -101,6 +101,10 @@ def lib():
         L.tq_lotile_forward.argtypes = [ctypes.POINTER(LoTileDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_size_t, ctypes.c_void_p]
+        L.tq_lotile_grid.restype = ctypes.c_int
+        L.tq_lotile_grid.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+        L.tq_lotile_place.restype = ctypes.c_int
+        L.tq_lotile_place.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -249,3 +253,21 @@ def tq_lotile_forward(desc: LoTileDesc, packed, x, topk_idx, topk_w, y=None, wor
     _check(lib().tq_lotile_forward(ctypes.byref(desc), _ptr(packed), _ptr(x), _ptr(topk_idx), _ptr(topk_w), T,
                                    _ptr(y), _ptr(workspace), workspace.numel(), _stream()), "tq_lotile_forward")
     return y
+
+
+def tq_lotile_grid(n_experts: int):
+    """Host-only helper: the near-square tile grid (M, N) for n_experts."""
+    m, n = ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().tq_lotile_grid(n_experts, ctypes.byref(m), ctypes.byref(n)), "tq_lotile_grid")
+    return int(m.value), int(n.value)
+
+
+def tq_lotile_place(ideal, tiles_m: int, tiles_n: int):
+    """Host-only helper: greedy placement of experts on the M x N grid.  ideal: int32 numpy array [E, 2] (host)."""
+    import numpy as np
+    ideal = np.ascontiguousarray(ideal, dtype=np.int32)
+    phi = np.empty_like(ideal)
+    _check(lib().tq_lotile_place(ideal.ctypes.data_as(ctypes.c_void_p), ideal.shape[0], tiles_m, tiles_n,
+                                 phi.ctypes.data_as(ctypes.c_void_p)), "tq_lotile_place")
+    return phi
+

@@ -11,6 +11,7 @@
 #include "tq_device.h"
 
 #include <algorithm>
+#include <vector>
 
 namespace {
 
@@ -544,3 +545,50 @@ extern "C" tq_status tq_lotile_forward(const tq_lotile_desc* desc, const void* p
     tqi_record_stage(3, st);
     return TQ_OK;
 }
+
+// ---- offline helpers (host only) --------------------------------------------------------------------------------
+extern "C" tq_status tq_lotile_grid(int32_t n_experts, int32_t* tiles_m, int32_t* tiles_n)
+{
+    if (!tiles_m || !tiles_n) return TQ_ERR_NULL;
+    if (n_experts < 1) return TQ_ERR_SHAPE;
+    // the integer closest to sqrt(E): the m with m(m-1) < E <= m(m+1) (ties cannot occur: sqrt(E) = m + 1/2 has no
+    // integer solution)
+    int32_t m = 1;
+    while ((int64_t)m * (m + 1) < n_experts) ++m;
+    *tiles_m = m;
+    *tiles_n = (n_experts + m - 1) / m;
+    return TQ_OK;
+}
+
+extern "C" tq_status tq_lotile_place(const int32_t* ideal, int32_t n_experts, int32_t tiles_m, int32_t tiles_n,
+                                     int32_t* phi)
+{
+    if (!ideal || !phi) return TQ_ERR_NULL;
+    if (n_experts < 1 || tiles_m < 1 || tiles_n < 1) return TQ_ERR_SHAPE;
+    if ((int64_t)tiles_m * tiles_n < n_experts || (int64_t)tiles_m * tiles_n > (1 << 20)) return TQ_ERR_SHAPE;
+    const int M = tiles_m, N = tiles_n;
+    std::vector<uint8_t> taken((size_t)M * N, 0);
+    for (int k = 0; k < n_experts; ++k) {
+        const int am = std::min(std::max(ideal[2 * k], 0), M - 1), an = std::min(std::max(ideal[2 * k + 1], 0), N - 1);
+        bool placed = false;
+        // rings of growing Chebyshev distance around the anchor, each scanned row by row; the grid has a free cell
+        // (M N >= E), and every cell lies on a ring of distance below max(M, N)
+        for (int rho = 0; rho < std::max(M, N) && !placed; ++rho) {
+            for (int m = std::max(am - rho, 0); m <= std::min(am + rho, M - 1) && !placed; ++m) {
+                const bool edge_row = (m == am - rho) || (m == am + rho);
+                for (int n = std::max(an - rho, 0); n <= std::min(an + rho, N - 1); ++n) {
+                    if (!edge_row && n != an - rho && n != an + rho) continue;      // interior of the ring's square
+                    if (taken[(size_t)m * N + n]) continue;
+                    taken[(size_t)m * N + n] = 1;
+                    phi[2 * k] = m;
+                    phi[2 * k + 1] = n;
+                    placed = true;
+                    break;
+                }
+            }
+        }
+        if (!placed) return TQ_ERR_RANGE;       // cannot happen with M N >= E
+    }
+    return TQ_OK;
+}
+

@@ -165,3 +165,58 @@ def test_lotile_fp8_packed_size_and_flag_checks():
         assert L.tq_lotile_pack_fp8(ctypes.byref(d16), 256, 256, 256, 256, 256, 1 << 30, None, None) == 2
         assert L.tq_lotile_pack_fp8(ctypes.byref(d8), 256, None, 256, 256, 256, 1 << 30, None, None) == 1
         assert L.tq_lotile_pack_fp8(ctypes.byref(d8), 256, 256, 256, 256, 256, 16, None, None) == 5
+
+
+# ------------------------------------------------------------------ offline tiling helpers (host only)
+def test_lotile_grid_is_the_near_square_grid():
+    """Appendix B, "Tiling-size": M = the integer closest to sqrt(E), N = ceil(E / M).  Hand-computed for the expert
+    counts of the benchmark layers (8 -> 3 x 3, 60 -> 8 x 8, 64 -> 8 x 8, 128 -> 11 x 12), then the defining
+    properties (|M - sqrt(E)| <= 1/2, N the smallest with M N >= E) and the oracle for every E below 700."""
+    from oracle import placement
+    for E, want in [(8, (3, 3)), (60, (8, 8)), (64, (8, 8)), (128, (11, 12)), (1, (1, 1)), (2, (1, 2)), (3, (2, 2))]:
+        assert tq.tq_lotile_grid(E) == want
+    for E in range(1, 700):
+        M, N = tq.tq_lotile_grid(E)
+        assert (M, N) == placement.grid(E)
+        assert M * N >= E and abs(M - E ** 0.5) <= 0.5 + 1e-9 and (N - 1) * M < E
+
+
+def test_lotile_place_worked_example():
+    import numpy as np
+    rows = [list(map(int, l.split())) for l in open(os.path.join(ROOT, "tests", "golden", "placement_example.txt"))
+            if l.strip() and not l.startswith("#")]
+    ideal = np.array([r[:2] for r in rows], dtype=np.int32)
+    want = np.array([r[2:] for r in rows], dtype=np.int32)
+    from oracle import placement
+    assert placement.place(ideal, 3, 3) == [tuple(r) for r in want.tolist()]
+    assert np.array_equal(tq.tq_lotile_place(ideal, 3, 3), want)
+
+
+def test_lotile_place_matches_oracle_and_its_invariants():
+    import numpy as np
+    from oracle import placement
+    rng = np.random.default_rng(7)
+    for trial in range(60):
+        M, N = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+        E = int(rng.integers(1, M * N + 1))
+        ideal = np.stack([rng.integers(-1, M + 2, E), rng.integers(-1, N + 2, E)], axis=1).astype(np.int32)
+        phi = tq.tq_lotile_place(ideal, M, N)
+        assert [tuple(r) for r in phi.tolist()] == placement.place(ideal, M, N)
+        # no collisions, inside the grid; every expert sits at the smallest Chebyshev distance that was still free
+        cells = {tuple(r) for r in phi.tolist()}
+        assert len(cells) == E and all(0 <= m < M and 0 <= n < N for m, n in cells)
+        taken = set()
+        for k in range(E):
+            am, an = min(max(ideal[k, 0], 0), M - 1), min(max(ideal[k, 1], 0), N - 1)
+            d = max(abs(phi[k, 0] - am), abs(phi[k, 1] - an))
+            best = min(max(abs(m - am), abs(n - an)) for m in range(M) for n in range(N) if (m, n) not in taken)
+            assert d == best
+            taken.add((int(phi[k, 0]), int(phi[k, 1])))
+    # distinct ideal tiles inside the grid are kept: the objective of Eq. 9 is zero
+    M, N = 4, 5
+    perm = rng.permutation(M * N)[:13]
+    ideal = np.stack([perm // N, perm % N], axis=1).astype(np.int32)
+    assert np.array_equal(tq.tq_lotile_place(ideal, M, N), ideal)
+    # fewer cells than experts is refused
+    with pytest.raises(tq.TqError):
+        tq.tq_lotile_place(np.zeros((5, 2), dtype=np.int32), 2, 2)
