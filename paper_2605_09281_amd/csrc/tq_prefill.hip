@@ -60,7 +60,8 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
     const int nb_count = (sec.pairs + 3) / 4;
     const int xcd = blockIdx.x & 7, wgx = gridDim.x >> 3;
     const int ntiles = ctrl[ctrl_idx];
-    const int tiles_x = ntiles > xcd ? (ntiles - xcd + 7) >> 3 : 0;
+    const int per_x = (ntiles + 7) >> 3;
+    const int tiles_x = min(max(ntiles - xcd * per_x, 0), per_x);
     const int items_x = tiles_x * nb_count;
     int q = blockIdx.x >> 3;
     if (q >= items_x) return;
@@ -80,7 +81,7 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
     const int ZT = tq_zero_terms(K, G.g);
 
     // ---- item bookkeeping (everything wave-uniform) ---------------------------------------------------
-    auto tile_of = [&](int qq) { return ((qq / nb_count) << 3) + xcd; };
+    auto tile_of = [&](int qq) { return xcd * per_x + qq / nb_count; };
     auto make_src = [&](int e, int nb, bool& active) {
         const int pair_raw = nb * 4 + wn;
         active = pair_raw < sec.pairs;
