@@ -162,7 +162,7 @@ __global__ void __launch_bounds__(256) aug_kernel(MGeom G, TqSection sec, const 
 // whole 4-group chunks by all threads (each row's chunk is one contiguous run of up to 1 KB instead of
 // 16 bytes per lane and step) and staged through LDS; wave w of the workgroup owns group w of every chunk.
 template <int STAGE, int NAT, int GS>
-__global__ void __launch_bounds__(256, 2) aug_staged_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
+__global__ void __launch_bounds__(256, NAT == 1 ? 3 : 2) aug_staged_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
                                                             const uint16_t* __restrict__ xin,
                                                             const int32_t* __restrict__ row_token,
                                                             const int32_t* __restrict__ tile_e,
@@ -177,7 +177,8 @@ __global__ void __launch_bounds__(256, 2) aug_staged_kernel(MGeom G, TqSection s
     constexpr int SPR = CKB / 16;          // 16-byte segments per row
     constexpr int RPP = 256 / SPR;         // rows per pass
     constexpr int NP = 32 / RPP;           // passes
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];     // 2 x 32 x ROWB; reused for the reduction
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];     // 32 x ROWB (one buffer: the next chunk waits
+                                                                       // in registers); reused for the reduction
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int tile = blockIdx.x;
     if (tile >= ctrl[1]) return;
@@ -213,10 +214,10 @@ __global__ void __launch_bounds__(256, 2) aug_staged_kernel(MGeom G, TqSection s
 #pragma unroll
         for (int p = 0; p < NP; ++p) xr[p] = *reinterpret_cast<const u32x4*>(xb + roff[p] + (uint32_t)kb);
     };
-    auto store_chunk = [&](int buf) {
+    auto store_chunk = [&]() {
 #pragma unroll
         for (int p = 0; p < NP; ++p)
-            *reinterpret_cast<u32x4*>(lds + buf * 32 * ROWB + (p * RPP + prow) * ROWB + seg * 16) = xr[p];
+            *reinterpret_cast<u32x4*>(lds + (p * RPP + prow) * ROWB + seg * 16) = xr[p];
     };
 
     f32x16 acc[NAT];
@@ -226,11 +227,10 @@ __global__ void __launch_bounds__(256, 2) aug_staged_kernel(MGeom G, TqSection s
         for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
 
     load_chunk(0);
-    store_chunk(0);
+    store_chunk();
     lds_barrier();
     for (int c = 0; c < nchunks; ++c) {
         const int gi = 4 * c + wave;
-        const int buf = c & 1;
         // The factor fragments of this chunk are requested BEFORE the next chunk's rows: loads return in order, and
         // behind the gathered rows (memory-side cache or HBM) these L2 hits would wait for them.  Unconditional
         // with a clamped group, so that the compiler can count them.
@@ -244,11 +244,14 @@ __global__ void __launch_bounds__(256, 2) aug_staged_kernel(MGeom G, TqSection s
                     aq[ks][j] = af[((size_t)min(j, max(na_tiles, 1) - 1) * ksteps + gic * GS + ks) * 64 * af_live];
         }
         load_chunk(min(c + 1, nchunks - 1));
-        if (gi < groups) {
-            Frag xa[GS];
+        // every wave copies its group's fragments out of the one LDS buffer (clamped for a group past the end),
+        // then the buffer is free for the next chunk
+        Frag xa[GS];
 #pragma unroll
-            for (int ks = 0; ks < GS; ++ks)
-                xa[ks].q = *reinterpret_cast<const u32x4*>(lds + buf * 32 * ROWB + col * ROWB + (wave * GS + ks) * 32 + hf * 16);
+        for (int ks = 0; ks < GS; ++ks)
+            xa[ks].q = *reinterpret_cast<const u32x4*>(lds + col * ROWB + (wave * GS + ks) * 32 + hf * 16);
+        lds_barrier();
+        if (gi < groups) {
             float gsum = 0.f;
 #pragma unroll
             for (int ks = 0; ks < GS; ++ks)
@@ -273,7 +276,7 @@ __global__ void __launch_bounds__(256, 2) aug_staged_kernel(MGeom G, TqSection s
                         acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[ks].v, half8_to_bf8(aq[ks][j]), acc[j], 0, 0, 0);
             }
         }
-        store_chunk((c + 1) & 1);
+        store_chunk();
         lds_barrier();
     }
     // sum the four waves' partial t tiles through LDS (the staging buffers are free now) and write them out
@@ -734,7 +737,8 @@ void launch_aug(const MGeom& G, const TqSection& sec, const uint8_t* blob, const
     const uint64_t span = (uint64_t)(STAGE == 0 ? G.a_tot / (G.k + G.S) : G.a_tot) * sec.K * 2;
     if (gs <= 8 && nat <= 2 && span < (1ull << 32)) {
 #define TQ_AUGS(NATV, GSV)                                                                                          \
-    hipLaunchKernelGGL((aug_staged_kernel<STAGE, NATV, GSV>), dim3(rt32), dim3(256), (size_t)2 * 32 * (4 * GSV * 32 + 16), \
+    hipLaunchKernelGGL((aug_staged_kernel<STAGE, NATV, GSV>), dim3(rt32), dim3(256),                            \
+                       std::max<size_t>((size_t)32 * (4 * GSV * 32 + 16), 4 * 16 * 64 * sizeof(float)) /* staging | reduction */, \
                        st, G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, xaug, ka)
         if (nat <= 1) { if (gs == 8) TQ_AUGS(1, 8); else if (gs == 4) TQ_AUGS(1, 4); else TQ_AUGS(1, 2); }
         else { if (gs == 8) TQ_AUGS(2, 8); else if (gs == 4) TQ_AUGS(2, 4); else TQ_AUGS(2, 2); }
