@@ -97,3 +97,26 @@ def test_workspace_sized_for_a_large_batch_serves_smaller_ones():
         print(f"workspace reuse T={T}", flush=True)
         got, ref = forward(cfg, tq.TQ_ACT_BF16, 0, ws=ws, T=T)
         assert rel_err(got, ref) <= TOL_BF16
+
+
+def test_many_rows_small_layer():
+    """Tens of thousands of tokens on a small layer: thousands of row tiles per expert, multi-chunk permutation,
+    persistent workgroups walking long item lists; sampled tokens against the oracle, all tokens finite."""
+    cfg = corner(530, H=128, F=128, g=64, r=8, E=4, k=2, T=60000)
+    layer = make_layer(cfg, workers=8)
+    x = make_x(cfg)
+    logits, bias = make_logits(cfg)
+    packed = pack_layer_gpu(layer)
+    idx, w = tq.tq_route(torch.from_numpy(logits).to(DEV), None, cfg.k)
+    desc = desc_of(cfg, tq.TQ_ACT_BF16, 0)
+    ws = torch.empty(tq.tq_moe_workspace_size(desc, cfg.T), dtype=torch.uint8, device=DEV)
+    y = tq.tq_moe_forward(desc, packed, x_device(x, tq.TQ_ACT_BF16), idx, w, workspace=ws)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32).item()) == 0
+    assert bool(torch.isfinite(y.float()).all())
+    rng = np.random.default_rng(530)
+    tok = np.unique(np.concatenate([[0, cfg.T - 1], rng.integers(0, cfg.T, 400)])).astype(np.int32)
+    ref = oracle.moe_forward_layer(layer, x, idx.cpu().numpy(), w.cpu().numpy(), tokens=tok)
+    got = y[torch.from_numpy(tok.astype(np.int64)).to(DEV)].float().cpu().numpy()
+    assert rel_err(got, ref) <= TOL_BF16
+
