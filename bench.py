@@ -6,7 +6,9 @@ One "step" is one pass of the whole hot path over one batch of seeded synthetic 
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1..5]
 
-The default workload is the Mixtral-shaped decode layer (benchmark config 2).
+By default all five benchmark layers are timed in turn: the headline (`value`, `config`, `roofline`) is the
+largest one (config 5, MFMA-bound prefill), and `per_config` carries step time, roofline fractions (decode: HBM),
+error against the oracle and the oracle's own rate for each of configs 1-5.  --workload N times one layer only.
 """
 import argparse
 import ctypes
@@ -21,10 +23,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK = 8.0e12          # B/s, MI355X published
 MFMA_BF16_PEAK = 2.5e15    # FLOP/s dense bf16, MI355X published
-# HBM bytes per launch of the dominant kernel from the rocprofv3 FETCH_SIZE + WRITE_SIZE passes (scaled by the
-# streaming-copy calibration), see profiles/hbm_traffic_config2_skinny_kernels.txt.  Only the decode workload
-# has been counted; other workloads report null.
-MEASURED_TRAFFIC_BYTES = {2: 551.2e6 + 1.0e6}
+# HBM bytes per launch of the dominant kernel (gate/up) from separate rocprofv3 FETCH_SIZE and WRITE_SIZE passes
+# over this same command, scaled by the streaming-copy calibration: (bytes, file under profiles/ that holds the
+# counter readings).  These are profiler runs of their own, not measurements of the present run; workloads that
+# have not been counted report null.
+TRAFFIC_FROM_PROFILES = {2: (551.2e6 + 1.0e6, "profiles/hbm_traffic_config2_skinny_kernels.txt")}
 STAGES = ["permute", "aug_gate_up", "gate_up", "aug_down", "down", "combine"]
 
 
@@ -232,7 +235,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--workload", type=int, default=None, choices=[1, 2, 3, 4, 5],
+                    help="time one benchmark layer only; default: all five in turn, headline on config 5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every step eagerly instead of replaying a captured HIP graph")
@@ -254,7 +258,7 @@ def main():
     from synth import CONFIGS, make_layer, make_x, make_logits, f32_to_bf16_bits
     import paper_2605_09281_amd.binding as tq
 
-    cfg = CONFIGS[args.workload]
+    cfg = CONFIGS[args.workload if args.workload is not None else 5]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     if args.stream_probe:
@@ -280,6 +284,52 @@ def main():
         return
     if args.lotile or args.lotile_fp8:
         return bench_lotile(args, cfg, dev)
+    if args.workload is not None:
+        res = bench_layer(args, CONFIGS[args.workload], dev, oracle_macs=1.5e11)
+        print(json.dumps(headline(args, res, None)), flush=True)
+        return
+    # default: every benchmark layer in turn (configs 1-4 with a short oracle sample), the headline on the largest
+    per = []
+    for c in (1, 2, 3, 4):
+        per.append(bench_layer(args, CONFIGS[c], dev, oracle_macs=2.5e10))
+        torch.cuda.empty_cache()
+    res5 = bench_layer(args, CONFIGS[5], dev, oracle_macs=1.5e11)
+    per.append(res5)
+    print(json.dumps(headline(args, res5, per)), flush=True)
+
+
+def headline(args, res, per):
+    """The one JSON line: the contract's keys from `res`, and the list of per-config summaries when all were run."""
+    out = {
+        "metric": "MoE-layer tokens/s at 1 GPU (route + quantised-expert forward); decode HBM % peak; prefill MFMA % peak",
+        "value": res["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "ms_per_step_median": res["ms_per_step_median"],
+        "ms_per_step_min": res["ms_per_step_min"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic", "launch": res["launch"],
+        "config": res["config"], "roofline": res["roofline"], "cpu_baseline": res["cpu_baseline"],
+        "max_rel_err_vs_oracle": res["max_rel_err"],
+    }
+    if per is not None:
+        out["per_config"] = [
+            {"workload": r["config"]["workload"], "tokens": r["config"]["tokens"], "ms_per_step": r["ms_per_step"],
+             "ms_per_step_median": r["ms_per_step_median"], "ms_per_step_min": r["ms_per_step_min"],
+             "tokens_per_s": r["tokens_per_s"], "bound": r["roofline"]["bound"], "kernel": r["roofline"]["kernel"],
+             "frac": r["roofline"]["frac"], "path_frac": r["roofline"]["path_frac"],
+             "hbm_path_frac": r["roofline"]["hbm_path_frac"], "mfma_path_frac": r["roofline"]["mfma_path_frac"],
+             "stage_us": r["roofline"]["stage_us"], "max_rel_err_vs_oracle": r["max_rel_err"],
+             "cpu_baseline": r["cpu_baseline"]} for r in per]
+    return out
+
+
+def bench_layer(args, cfg, dev, oracle_macs):
+    """Times K steps of route + forward on one benchmark layer; returns a dict of results."""
+    import numpy as np
+    import torch
+    from synth import make_layer, make_x, make_logits, f32_to_bf16_bits
+    import paper_2605_09281_amd.binding as tq
+
     t0 = time.time()
     layer = make_layer(cfg, workers=min(16, os.cpu_count() or 8))
     x = make_x(cfg)
@@ -306,7 +356,7 @@ def main():
     w_d = torch.empty((cfg.T, cfg.k), dtype=torch.float32, device=dev)
     y_d = torch.empty_like(x_d)
     ws = torch.empty(tq.tq_moe_workspace_size(desc, cfg.T), dtype=torch.uint8, device=dev)
-    stream = torch.cuda.current_stream().cuda_stream
+    tq.tq_init()
 
     def step(i):
         tq.tq_route(logits_d, bias_d, cfg.k, idx_d, w_d)
@@ -316,7 +366,7 @@ def main():
         step(i)
     torch.cuda.synchronize()
     y_eager = y_d.clone()
-    ev = HipEvents(2 + 7)
+    ev = HipEvents(args.steps + 1 + 7)
     use_graph = not args.no_graph
     if use_graph:
         # the step is a short chain of kernels: replaying a captured HIP graph (one per weight copy) removes the
@@ -340,6 +390,7 @@ def main():
     else:
         run = step
     stream = torch.cuda.current_stream().cuda_stream
+    # the timed region: exactly K steps between two events (this gives `value`)
     ev.record(0, stream)
     t_host = time.perf_counter()
     for i in range(args.steps):
@@ -348,47 +399,60 @@ def main():
     torch.cuda.synchronize()
     assert torch.equal(y_d.view(torch.int16), y_eager.view(torch.int16)), "timed run differs from the eager result"
     wall_ms = (time.perf_counter() - t_host) * 1e3
-    ms_total = ev.elapsed_ms(0, 1)
-    ms_per_step = ms_total / args.steps
-    log(f"timed {args.steps} steps: {ms_per_step * 1e3:.1f} us/step (events), {wall_ms / args.steps * 1e3:.1f} us/step (host clock)")
+    ms_per_step = ev.elapsed_ms(0, 1) / args.steps
+    # a second pass of K steps with an event at every step boundary: median and minimum step time
+    ev.record(0, stream)
+    for i in range(args.steps):
+        run(i)
+        ev.record(i + 1, stream)
+    torch.cuda.synchronize()
+    per_step = sorted(ev.elapsed_ms(i, i + 1) for i in range(args.steps))
+    ms_median, ms_min = per_step[len(per_step) // 2], per_step[0]
+    log(f"timed {args.steps} steps: {ms_per_step * 1e3:.1f} us/step (events; median {ms_median * 1e3:.1f}, min "
+        f"{ms_min * 1e3:.1f}), {wall_ms / args.steps * 1e3:.1f} us/step (host clock)")
     assert int(ws[:4].view(torch.int32).item()) == 0, "device error flag set"
 
     # per-stage kernel durations: the library records events at its stage boundaries on the same stream
-    stage_ev = ev.handles()[2:]
-    tq.tq_set_profile_events(stage_ev)
+    so = args.steps + 1
+    tq.tq_set_profile_events(ev.handles()[so:])
     n_prof = max(1, min(args.steps, 50))
     stage_ms = [0.0] * 6
     for i in range(n_prof):
         step(i)
-        ev.sync(2 + 6)
-        for s in range(6):
-            stage_ms[s] += ev.elapsed_ms(2 + s, 3 + s)
+        ev.sync(so + 6)
+        for q in range(6):
+            stage_ms[q] += ev.elapsed_ms(so + q, so + q + 1)
     tq.tq_set_profile_events([])
-    stage_us = {name: stage_ms[s] / n_prof * 1e3 for s, name in enumerate(STAGES)}
+    stage_us = {name: stage_ms[q] / n_prof * 1e3 for q, name in enumerate(STAGES)}
     log("stage durations (us): " + ", ".join(f"{k}={v:.1f}" for k, v in stage_us.items()))
 
     idx_np = idx_d.cpu().numpy()
     work = algorithmic_work(cfg, idx_np)
+    t_step = ms_per_step * 1e-3
+    hbm_path = work["path_bytes"] / t_step / HBM_PEAK
+    mfma_path = work["path_flops"] / t_step / MFMA_BF16_PEAK
     hbm_bound = work["path_flops"] / max(work["path_bytes"], 1) < MFMA_BF16_PEAK / HBM_PEAK
     t_gu = stage_us["gate_up"] * 1e-6
+    decode_path = cfg.a_tot / (cfg.E + cfg.S) <= 12 and cfg.a_tot <= 1024
+    kname = ("gate/up stage (moe_skinny_kernel<0,.>)" if decode_path else
+             "gate/up stage (moe_prefill_kernel<0,.>, or moe_mfma_kernel<.,.,0,.> where the layer does not qualify)")
+    traffic, traffic_source = TRAFFIC_FROM_PROFILES.get(cfg.cfg_id, (None, None))
     if hbm_bound:
         ach = work["gate_up_bytes"] / t_gu / 1e9
-        # the library streams weights through its 16-row kernels up to 12 rows per expert, else it runs the tiled kernels
-        decode_path = cfg.a_tot / (cfg.E + cfg.S) <= 12 and cfg.a_tot <= 1024
-        roofline = dict(bound="hbm", kernel="gate/up stage (moe_skinny_kernel<0>)" if decode_path else
-                        "gate/up stage (moe_prefill_kernel<0,.>, or moe_mfma_kernel<.,.,0,.> where the layer does not qualify)",
-                        achieved=round(ach, 1), peak=HBM_PEAK / 1e9,
-                        unit="GB/s", frac=round(ach / (HBM_PEAK / 1e9), 4),
-                        traffic=MEASURED_TRAFFIC_BYTES.get(cfg.cfg_id), algorithmic_bytes=work["gate_up_bytes"],
-                        path_achieved=round(work["path_bytes"] / (ms_per_step * 1e-3) / 1e9, 1),
-                        path_frac=round(work["path_bytes"] / (ms_per_step * 1e-3) / HBM_PEAK, 4))
+        roofline = dict(bound="hbm", kernel=kname, achieved=round(ach, 1), peak=HBM_PEAK / 1e9, unit="GB/s",
+                        frac=round(ach / (HBM_PEAK / 1e9), 4), traffic=traffic, traffic_source=traffic_source,
+                        algorithmic_bytes=work["gate_up_bytes"],
+                        path_achieved=round(work["path_bytes"] / t_step / 1e9, 1), path_frac=round(hbm_path, 4))
     else:
         ach = work["gate_up_flops"] / t_gu / 1e12
-        roofline = dict(bound="mfma", kernel="gate/up stage (moe_prefill_kernel<0,.>, or moe_mfma_kernel<.,.,0,.> where the layer does not qualify)", achieved=round(ach, 1),
-                        peak=MFMA_BF16_PEAK / 1e12, unit="TFLOP/s", frac=round(ach / (MFMA_BF16_PEAK / 1e12), 4),
-                        traffic=None,
-                        path_achieved=round(work["path_flops"] / (ms_per_step * 1e-3) / 1e12, 1),
-                        path_frac=round(work["path_flops"] / (ms_per_step * 1e-3) / MFMA_BF16_PEAK, 4))
+        roofline = dict(bound="mfma", kernel=kname, achieved=round(ach, 1), peak=MFMA_BF16_PEAK / 1e12, unit="TFLOP/s",
+                        frac=round(ach / (MFMA_BF16_PEAK / 1e12), 4), traffic=traffic, traffic_source=traffic_source,
+                        algorithmic_flops=work["gate_up_flops"],
+                        path_achieved=round(work["path_flops"] / t_step / 1e12, 1), path_frac=round(mfma_path, 4))
+    roofline["hbm_path_frac"] = round(hbm_path, 4)
+    roofline["mfma_path_frac"] = round(mfma_path, 4)
+    roofline["gate_up_mfma_frac"] = round(work["gate_up_flops"] / t_gu / MFMA_BF16_PEAK, 4)
+    roofline["gate_up_hbm_frac"] = round(work["gate_up_bytes"] / t_gu / HBM_PEAK, 4)
     roofline["stage_us"] = {k: round(v, 2) for k, v in stage_us.items()}
 
     # the oracle beside it: a bounded token sample of the same workload, timed on this machine's host cores
@@ -399,7 +463,7 @@ def main():
         ridx, rw = oracle.route(logits, bias, cfg.k)
         assert np.array_equal(ridx, idx_np), "routing indices differ from the oracle"
         pair_cost = 3.0 * cfg.H * cfg.F * (cfg.k + cfg.S)          # MACs per token
-        n_tok = int(max(1, min(cfg.T, 1.5e11 // pair_cost)))       # about 10-30 s of host work
+        n_tok = int(max(1, min(cfg.T, oracle_macs // pair_cost)))
         tok = np.linspace(0, cfg.T - 1, n_tok).astype(np.int32)
         w_np = w_d.cpu().numpy()
         t1 = time.perf_counter()
@@ -411,23 +475,14 @@ def main():
                             sample=f"{n_tok} of {cfg.T} tokens of the same workload, {cpu_s:.1f} s")
         log(f"oracle: {n_tok} tokens in {cpu_s:.1f}s on {oracle.num_threads()} threads; max rel err {max_rel_err:.3e}")
         assert max_rel_err <= 2e-2, max_rel_err
-
-    out = {
-        "metric": "MoE-layer tokens/s at 1 GPU (route + quantised-expert forward)",
-        "value": round(cfg.T / (ms_per_step * 1e-3), 1),
-        "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic", "launch": "hip_graph" if use_graph else "eager",
-        "config": {"workload": f"config {cfg.cfg_id}: {cfg.name}", "experts": cfg.E, "shared": cfg.S, "top_k": cfg.k,
-                   "hidden": cfg.H, "ffn": cfg.F, "tokens": cfg.T, "group": cfg.g, "rank": cfg.r, "bits": cfg.bits,
-                   "touched_experts": work["touched"]},
-        "roofline": roofline,
-        "cpu_baseline": cpu_baseline,
-        "max_rel_err_vs_oracle": max_rel_err,
-    }
-    print(json.dumps(out), flush=True)
+    del packed, ws
+    return dict(tokens_per_s=round(cfg.T / t_step, 1), ms_per_step=round(ms_per_step, 5),
+                ms_per_step_median=round(ms_median, 5), ms_per_step_min=round(ms_min, 5),
+                launch="hip_graph" if use_graph else "eager",
+                config={"workload": f"config {cfg.cfg_id}: {cfg.name}", "experts": cfg.E, "shared": cfg.S, "top_k": cfg.k,
+                        "hidden": cfg.H, "ffn": cfg.F, "tokens": cfg.T, "group": cfg.g, "rank": cfg.r, "bits": cfg.bits,
+                        "touched_experts": work["touched"]},
+                roofline=roofline, cpu_baseline=cpu_baseline, max_rel_err=max_rel_err)
 
 
 if __name__ == "__main__":

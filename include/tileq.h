@@ -76,7 +76,10 @@ typedef enum {
     TQ_ERR_WORKSPACE = 5,   /* workspace or output buffer too small */
     TQ_ERR_UNSUPPORTED = 6, /* valid request this build has no kernel for */
     TQ_ERR_HIP = 7,         /* a HIP call or launch failed */
-    TQ_ERR_BLOB = 8         /* the packed blob's header does not match the descriptor */
+    TQ_ERR_BLOB = 8         /* the packed blob's header does not match the descriptor.  The header lives in device
+                               memory, so the forward finds this on the device: it is reported through bit 1 of the
+                               workspace's error flag (see tq_moe_forward), and host-side tools that hold a copy of
+                               the header may return this code */
 } tq_status;
 
 enum { TQ_ACT_BF16 = 0, TQ_ACT_FP32 = 1 };
@@ -97,7 +100,8 @@ typedef struct tq_layer_desc {
     int32_t ffn;       /* F  multiple of 64 and of group */
     int32_t group;     /* g  quantisation group along the contraction dim; 32, 64, 128 or 256 */
     int32_t bits;      /* 4, or 3 (codes 0..7 kept in 4-bit slots) */
-    int32_t rank;      /* r  in [0, 256]; 0 = no low-rank term */
+    int32_t rank;      /* r  in [0, 256]; 0 = no low-rank term.  The bf16 path carries at most 128 rank columns
+                          (TQ_ERR_UNSUPPORTED beyond); the fp32 debug path takes all of them */
     int32_t act_dtype; /* TQ_ACT_BF16: x, y bf16, MFMA path.  TQ_ACT_FP32: x, y fp32, exact-dequant debug path */
     int32_t flags;
 } tq_layer_desc;
@@ -117,6 +121,13 @@ typedef struct tq_weights_dst {
 /* Text for a status code (static storage, host). */
 const char *tq_status_str(tq_status s);
 
+/* Per-device set-up for the CURRENT device: reads the CU count and raises the dynamic-LDS limit of the kernels
+ * that need more than the default.  Idempotent and thread-safe.  Every entry point that launches kernels runs it
+ * by itself on its first call on a device, so calling it is optional — except for callers whose FIRST call on a
+ * device would be inside a stream capture: they call tq_init() once before capturing (the set-up makes
+ * host-side HIP calls that do not belong in a captured region). */
+tq_status tq_init(void);
+
 /* Bytes of the packed blob for this layer; 0 if the descriptor is invalid.  Host only.  With r a multiple
  * of 32 and K/g a multiple of 16 this is 256 + (E+S) * 3HF * (4 + 32/g + 48/g + 16 r (1/H + 1/F)) / 8:
  * the per-expert low-rank storage count of Appendix A.3 with a 16-bit scale and a 16-bit zero per group
@@ -129,7 +140,8 @@ size_t tq_packed_size(const tq_layer_desc *desc);
 tq_status tq_pack_weights(const tq_layer_desc *desc, const tq_weights_src *src, void *packed,
                           size_t packed_bytes, int32_t *err_flag, void *stream);
 
-/* Exact inverse of tq_pack_weights (bit for bit on codes, scale, zero, A, B).  For tests and tools. */
+/* Exact inverse of tq_pack_weights (bit for bit on codes, scale, zero, A, B): recovers the per-expert stored
+ * tuple of Algorithm 1 (quantised residual, effective factors) from the blob.  For tests and tools. */
 tq_status tq_unpack_weights(const tq_layer_desc *desc, const void *packed, const tq_weights_dst *dst,
                             void *stream);
 
@@ -143,7 +155,8 @@ tq_status tq_route(const float *logits, const float *bias, int32_t T, int32_t E,
 /* Bytes of scratch tq_permute needs. Host only. */
 size_t tq_permute_workspace_size(int32_t T, int32_t E, int32_t k);
 
-/* Token -> expert permutation with prefix-sum offsets: assignment a = t*k + j belongs to expert
+/* Token -> expert permutation with prefix-sum offsets (the per-token expert dispatch of Appendix A.4, "vs.
+ * Per-Token Expert Dispatch", done once for the whole batch): assignment a = t*k + j belongs to expert
  * topk_idx[a].  offsets int32 [E+1] = exclusive prefix sum of the per-expert counts; slot_of int32 [T*k]
  * = position of assignment a in expert-sorted order, stable (assignments of one expert keep their order
  * in a); src_of int32 [T*k] = its inverse.  err_flag as in tq_pack_weights, set when an index is outside
@@ -156,11 +169,14 @@ tq_status tq_permute(const int32_t *topk_idx, int32_t T, int32_t E, int32_t k, i
 /* Bytes of workspace tq_moe_forward needs for up to T tokens.  Host only; 0 if desc is invalid. */
 size_t tq_moe_workspace_size(const tq_layer_desc *desc, int32_t T);
 
-/* The expert forward: permutation, gate/up with fused dequant + low-rank term + SwiGLU, down with the
+/* The expert forward (Eq. 3 over experts whose projections are Eq. 2 / Eq. 4, evaluated as Eq. 14's quantised
+ * forward plus low-rank forward): permutation, gate/up with fused dequant + low-rank term + SwiGLU, down with the
  * same, routing-weighted combination.  x, y are [T,H] bf16 (act_dtype 0) or fp32 (act_dtype 1); y is
  * overwritten.  topk_idx / topk_w as produced by tq_route.  The first int32 of `workspace` is an error
- * flag the kernels set to 1 on an out-of-range expert index (such assignments contribute nothing); the
- * call clears it at its start and never reads it back — the caller may inspect it after synchronising.
+ * flag: the kernels set bit 0 (value 1) on an out-of-range expert index (such assignments contribute nothing)
+ * and bit 1 (value 2) when the blob's header does not match the descriptor (then no projection runs and y is
+ * undefined).  The call clears the flag at its start and never reads it back — the caller may inspect it after
+ * synchronising.  A workspace sized by tq_moe_workspace_size(desc, T) serves every batch of at most T tokens.
  * T == 0 is a no-op. */
 tq_status tq_moe_forward(const tq_layer_desc *desc, const void *packed, const void *x,
                          const int32_t *topk_idx, const float *topk_w, int32_t T, void *y,
@@ -238,7 +254,8 @@ tq_status tq_lotile_forward(const tq_lotile_desc *desc, const void *packed, cons
                             const int32_t *topk_idx, const float *topk_w, int32_t T, void *y,
                             void *workspace, size_t workspace_bytes, void *stream);
 
-/* Offline helpers for the shared-factor format (host only, no GPU work, host pointers).
+/* Offline helpers for the shared-factor format (host only, no GPU work, host pointers; unlike the GPU entry
+ * points these may use the host heap for their own bookkeeping).
  *
  * tq_lotile_grid: the near-square tile grid for E experts (Appendix B, Evaluation Details, "Tiling-size"): M = the integer closest to
  * sqrt(E), N = ceil(E / M), so that M N >= E.

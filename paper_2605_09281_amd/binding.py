@@ -20,7 +20,7 @@ TQ_LOTILE_FP8 = 1
 STATUS_NAMES = {0: "TQ_OK", 1: "TQ_ERR_NULL", 2: "TQ_ERR_SHAPE", 3: "TQ_ERR_ALIGN", 4: "TQ_ERR_RANGE",
                 5: "TQ_ERR_WORKSPACE", 6: "TQ_ERR_UNSUPPORTED", 7: "TQ_ERR_HIP", 8: "TQ_ERR_BLOB"}
 
-EXPORTS = ["tq_status_str", "tq_packed_size", "tq_pack_weights", "tq_unpack_weights", "tq_route",
+EXPORTS = ["tq_init", "tq_status_str", "tq_packed_size", "tq_pack_weights", "tq_unpack_weights", "tq_route",
            "tq_permute_workspace_size", "tq_permute", "tq_moe_workspace_size", "tq_moe_forward",
            "tq_set_profile_events", "tq_debug_stream", "tq_lotile_packed_size", "tq_lotile_pack", "tq_lotile_pack_fp8",
            "tq_lotile_workspace_size", "tq_lotile_forward", "tq_lotile_grid", "tq_lotile_place"]
@@ -57,6 +57,8 @@ def lib():
         if not os.path.exists(path):
             raise ImportError(f"{path} is not built: run __graft_entry__.build() (there is no fallback path)")
         L = ctypes.CDLL(path)
+        L.tq_init.restype = ctypes.c_int
+        L.tq_init.argtypes = []
         L.tq_status_str.restype = ctypes.c_char_p
         L.tq_status_str.argtypes = [ctypes.c_int]
         L.tq_packed_size.restype = ctypes.c_size_t
@@ -127,6 +129,11 @@ def _check(rc: int, where: str) -> None:
 
 def make_desc(E, S, k, H, F, g, bits, r, act_dtype=TQ_ACT_BF16, flags=0) -> LayerDesc:
     return LayerDesc(E, S, k, H, F, g, bits, r, act_dtype, flags)
+
+
+def tq_init() -> None:
+    """Per-device set-up for the current device (optional, see include/tileq.h)."""
+    _check(lib().tq_init(), "tq_init")
 
 
 def tq_status_str(status: int) -> str:

@@ -18,6 +18,42 @@ extern "C" const char* tq_status_str(tq_status s)
     return "unknown status";
 }
 
+#include <atomic>
+#include <mutex>
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_init_mu;
+std::atomic<int> g_dev_ready[kMaxDevices];
+TqDeviceState g_dev_state[kMaxDevices];
+}  // namespace
+
+tq_status tqi_device_state(const TqDeviceState** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TQ_ERR_HIP;
+    if (!g_dev_ready[dev].load(std::memory_order_acquire)) {
+        std::lock_guard<std::mutex> lock(g_init_mu);
+        if (!g_dev_ready[dev].load(std::memory_order_relaxed)) {
+            int cus = 0;
+            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+                return TQ_ERR_HIP;
+            g_dev_state[dev].n_cu = cus;
+            g_dev_state[dev].scratch = nullptr;
+            if (tqi_setup_mfma() != TQ_OK || tqi_setup_skinny() != TQ_OK) return TQ_ERR_HIP;
+            g_dev_ready[dev].store(1, std::memory_order_release);
+        }
+    }
+    *out = &g_dev_state[dev];
+    return TQ_OK;
+}
+
+extern "C" tq_status tq_init(void)
+{
+    const TqDeviceState* ds = nullptr;
+    return tqi_device_state(&ds);
+}
+
 namespace {
 hipEvent_t g_stage_events[TQ_N_STAGE_EVENTS];
 int g_n_stage_events = 0;
@@ -102,9 +138,21 @@ extern "C" size_t tq_moe_workspace_size(const tq_layer_desc* desc, int32_t T)
     TqLayout L;
     if (!tq_make_layout(desc, &L) || T < 0) return 0;
     if ((int64_t)T * (L.k + L.S) > 0x3FFFFFFF) return 0;
+    // The carve-up is not monotonic in T by itself (small batches keep split-K planes and decode scratch that large
+    // ones drop), and a workspace sized for T must serve every smaller batch: take the maximum over T and the
+    // largest batches below it that still qualify for those extras.
     TqWorkspace W;
     tq_make_workspace(L, desc->act_dtype, T, &W);
-    return W.total;
+    size_t need = W.total;
+    const int32_t per_tok = L.k + L.S;
+    const int32_t marks[2] = {TQ_SPLITK_MAX_ROWS / per_tok, TQ_SKINNY_MAX_ROWS / per_tok};
+    for (int i = 0; i < 2; ++i) {
+        if (marks[i] >= 1 && marks[i] < T) {
+            tq_make_workspace(L, desc->act_dtype, marks[i], &W);
+            if (W.total > need) need = W.total;
+        }
+    }
+    return need;
 }
 
 extern "C" tq_status tq_moe_forward(const tq_layer_desc* desc, const void* packed, const void* x,
@@ -121,6 +169,8 @@ extern "C" tq_status tq_moe_forward(const tq_layer_desc* desc, const void* packe
     tq_make_workspace(L, desc->act_dtype, T, &W);
     if (workspace_bytes < W.total) return TQ_ERR_WORKSPACE;
     if (T == 0) return TQ_OK;
+    const TqDeviceState* ds = nullptr;
+    if (tqi_device_state(&ds) != TQ_OK) return TQ_ERR_HIP;
     hipStream_t st = (hipStream_t)stream;
     uint8_t* ws = (uint8_t*)workspace;
     int32_t* ctrl = (int32_t*)(ws + W.ctrl);

@@ -108,6 +108,7 @@ struct TqWorkspace {
 #define TQ_PERM_CHUNK 256   // assignments handled by one permutation block
 #define TQ_MAX_SPLIT 8      // K-splits of the down projection on the small-tile path
 #define TQ_SKINNY_MAX_ROWS 1024   // assignment rows up to which the decode (16-row tile) path is considered
+#define TQ_SPLITK_MAX_ROWS 4096   // assignment rows up to which the 32-row path may split the down projection's K
 
 __host__ __device__ inline int tq_pad64(int v) { return (v + 63) / 64 * 64; }
 // augmented-K length: three bf16 split terms per quantisation group (zero-point correction; groups in blocks
@@ -145,7 +146,7 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
         W->xaug_d = take((size_t)a_tot * W->ka_d * 2);
         W->h = take((size_t)a_tot * L.F * 2);
         // the small-tile path may split the down projection's K; the large-tile path never does
-        size_t planes = (a_tot <= 4096) ? TQ_MAX_SPLIT : 1;
+        size_t planes = (a_tot <= TQ_SPLITK_MAX_ROWS) ? TQ_MAX_SPLIT : 1;
         W->yd = take(planes * (size_t)a_tot * L.H * 4);
         W->tpart = off;
         if (a_tot <= TQ_SKINNY_MAX_ROWS && L.r > 0) {
@@ -205,6 +206,18 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
 bool tqi_skinny_supported(const TqLayout& L);
 tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint8_t* blob, const uint16_t* x,
                              int32_t T, uint8_t* ws, hipStream_t stream, int* nsplit_out);
+
+// Per-device state, set up once per device under a lock by the first entry point that needs it (or by tq_init):
+// the CU count, the raised dynamic-LDS limits of the kernels that need more than the default, and the address of
+// the library's static scratch array on that device.
+struct TqDeviceState {
+    int n_cu;
+    void* scratch;          // device address of the static scratch array (each device holds its own copy)
+};
+tq_status tqi_device_state(const TqDeviceState** out);
+// each translation unit raises the dynamic-LDS limit of its own kernel instantiations (current device)
+tq_status tqi_setup_mfma();
+tq_status tqi_setup_skinny();
 
 // profiling aid: stage-boundary events registered through tq_set_profile_events (nullptr when off)
 void tqi_record_stage(int stage, hipStream_t stream);

@@ -360,13 +360,7 @@ template <int MT, int NTW, bool OUT_BF16, bool FP8>
 tq_status lt_launch_gemm_inst(const LtGemmArgs& a, int planes, hipStream_t st)
 {
     auto kern = lt_gemm_kernel<MT, NTW, OUT_BF16, FP8>;
-    constexpr size_t smem = 2 * 32 * MT * LT_ROWB;
-    static bool done = false;
-    if (!done) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-            return TQ_ERR_HIP;
-        done = true;
-    }
+    constexpr size_t smem = 2 * 32 * MT * LT_ROWB;      // at most 34 KB: inside the default dynamic-LDS limit
     const int rt = (a.T + 32 * MT - 1) / (32 * MT), cb = (a.ntiles + 4 * NTW - 1) / (4 * NTW);
     if (rt > 65535) return TQ_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, dim3(cb, rt, planes), dim3(256), smem, st, a);

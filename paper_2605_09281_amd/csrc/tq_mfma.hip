@@ -345,8 +345,9 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
 
     const int K = sec.K;
     // XCD-aware mapping: consecutive workgroup ids go to the 8 XCDs in turn, each with its own L2.  Ids are
-    // laid out so that XCD x works on row tiles x, x+8, ... and walks through all column blocks of a row
-    // tile itself: the activation tile is then re-read from that XCD's L2 instead of from memory by all 8.
+    // laid out so that, within a block of 8 row tiles, XCD x works on row tile x of the block and walks through
+    // all its column blocks itself: the activation tile is then re-read from that XCD's L2 instead of from memory
+    // by all 8.
     const int nb_count = (sec.pairs + 3) / 4;
     const int wg = blockIdx.x;
     const int grp = wg / (8 * nb_count), rem = wg - grp * (8 * nb_count);
@@ -681,15 +682,7 @@ tq_status launch_main(const MGeom& G, const TqSection& sec, const uint8_t* blob,
     constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
     constexpr int ROWB = UNIT_K * 2 + 16;
     const size_t smem = (size_t)2 * BM * ROWB + (size_t)2 * BM * 4;
-    auto kern = moe_mfma_kernel<MT, WM, STAGE, GS>;
-    if (smem > 64 * 1024) {
-        static bool done = false;   // per instantiation
-        if (!done) {
-            if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
-                return TQ_ERR_HIP;
-            done = true;
-        }
-    }
+    auto kern = moe_mfma_kernel<MT, WM, STAGE, GS>;      // dynamic-LDS limit: raised once per device by tqi_setup_mfma
     const int nb_count = (sec.pairs + 3) / 4;
     const long n_wg = (long)((row_tiles + 7) / 8) * 8 * nb_count;
     if (n_wg > 0x7FFFFFFF || nb_count > 65535) return TQ_ERR_UNSUPPORTED;
@@ -725,8 +718,20 @@ tq_status launch_main_gs(int gs, const MGeom& G, const TqSection& sec, const uin
     return TQ_ERR_UNSUPPORTED;
 }
 
+template <int MT, int WM, int STAGE, int GS>
+bool raise_lds_limit_main()
+{
+    constexpr int BM = 32 * MT * WM;
+    constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
+    constexpr int ROWB = UNIT_K * 2 + 16;
+    constexpr size_t smem = (size_t)2 * BM * ROWB + (size_t)2 * BM * 4;
+    if (smem <= 64 * 1024) return true;
+    return hipFuncSetAttribute((const void*)moe_mfma_kernel<MT, WM, STAGE, GS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)smem) == hipSuccess;
+}
+
 template <int STAGE>
-void launch_aug(const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin, const int32_t* row_token,
+tq_status launch_aug(const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin, const int32_t* row_token,
                 const int32_t* tile_e, const int32_t* tile_row0, const int32_t* offsets, const int32_t* ctrl,
                 uint16_t* xaug, int ka, int rt32, hipStream_t st)
 {
@@ -743,7 +748,8 @@ void launch_aug(const MGeom& G, const TqSection& sec, const uint8_t* blob, const
         if (nat <= 1) { if (gs == 8) TQ_AUGS(1, 8); else if (gs == 4) TQ_AUGS(1, 4); else TQ_AUGS(1, 2); }
         else { if (gs == 8) TQ_AUGS(2, 8); else if (gs == 4) TQ_AUGS(2, 4); else TQ_AUGS(2, 2); }
 #undef TQ_AUGS
-        return;
+        TQ_CHECK_LAUNCH();
+        return TQ_OK;
     }
     const bool deep = (G.g < 64 ? 64 : G.g) % 128 == 0;
 #define TQ_AUG(NATV, UNRV)                                                                                        \
@@ -755,9 +761,22 @@ void launch_aug(const MGeom& G, const TqSection& sec, const uint8_t* blob, const
     else if (nat == 2) TQ_AUG(2, 4);
     else TQ_AUG(4, 4);
 #undef TQ_AUG
+    TQ_CHECK_LAUNCH();
+    return TQ_OK;
 }
 
 }  // namespace
+
+tq_status tqi_setup_mfma()
+{
+    bool ok = true;
+#define TQ_BOTH(MT, GS) ok = ok && raise_lds_limit_main<MT, 1, 0, GS>() && raise_lds_limit_main<MT, 1, 1, GS>()
+    TQ_BOTH(1, 2); TQ_BOTH(1, 4); TQ_BOTH(1, 8); TQ_BOTH(1, 16);
+    TQ_BOTH(2, 2); TQ_BOTH(2, 4); TQ_BOTH(2, 8);
+    TQ_BOTH(4, 16);
+#undef TQ_BOTH
+    return ok ? TQ_OK : TQ_ERR_HIP;
+}
 
 tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, const uint8_t* blob,
                            const uint16_t* x, int32_t T, uint16_t* y, uint8_t* ws, hipStream_t stream,
@@ -805,10 +824,9 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
         return TQ_OK;
     }
 
-    launch_aug<0>(G, L.gu, blob, x, row_token, tile_e, tile_row0, offsets, ctrl, xaug_gu, W.ka_gu, rt32, stream);
-    TQ_CHECK_LAUNCH();
+    tq_status rc = launch_aug<0>(G, L.gu, blob, x, row_token, tile_e, tile_row0, offsets, ctrl, xaug_gu, W.ka_gu, rt32, stream);
+    if (rc != TQ_OK) return rc;
     tqi_record_stage(2, stream);
-    tq_status rc;
     // many rows per expert: persistent 64-row-tile workgroups (tq_prefill.hip) when the layer qualifies, else one
     // workgroup per 64-row tile; groups of 256 need more registers than two workgroups per CU leave and run
     // as four waves of 128x64 on 128-row tiles
@@ -828,11 +846,11 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
                                   rt32, stream);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(3, stream);
-    launch_aug<1>(G, L.d, blob, h, row_token, tile_e, tile_row0, offsets, ctrl, xaug_d, W.ka_d, rt32, stream);
-    TQ_CHECK_LAUNCH();
+    rc = launch_aug<1>(G, L.d, blob, h, row_token, tile_e, tile_row0, offsets, ctrl, xaug_d, W.ka_d, rt32, stream);
+    if (rc != TQ_OK) return rc;
     tqi_record_stage(4, stream);
     int nsplit = 1;
-    if (!large && W.a_tot <= 4096) {
+    if (!large && W.a_tot <= TQ_SPLITK_MAX_ROWS) {
         // few rows: split the long contraction of the down projection so the grid fills the chip
         const int unit_k = L.g < 64 ? 64 : L.g;
         const int nu = L.F / unit_k;

@@ -10,8 +10,9 @@
 // fetched an item earlier.
 //
 // Items are dealt out statically.  Workgroup ids go round-robin over the 8 XCDs (each with its own L2);
-// XCD x takes the row tiles x, x+8, ... and its workgroups walk (row tile, column block) in row-tile-major
-// order, so the workgroups of one XCD are on a few row tiles at any time and share their activations in L2.
+// XCD x takes the x-th eighth of the row tiles, a contiguous range, and its workgroups walk (row tile, column
+// block) in row-tile-major order, so the workgroups of one XCD are on a few neighbouring row tiles at any time:
+// they share their activations in that L2, and neighbouring tiles mostly share an expert's weights there too.
 #include "tq_device.h"
 
 #include <type_traits>
@@ -60,6 +61,7 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
     const int nb_count = (sec.pairs + 3) / 4;
     const int xcd = blockIdx.x & 7, wgx = gridDim.x >> 3;
     const int ntiles = ctrl[ctrl_idx];
+    const int last_row = ctrl[3] - 1;       // last assignment row the permutation filled in
     const int per_x = (ntiles + 7) >> 3;
     const int tiles_x = min(max(ntiles - xcd * per_x, 0), per_x);
     const int items_x = tiles_x * nb_count;
@@ -95,9 +97,10 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
         return s;
     };
     // row ids of a tile: rows past the end of the expert read the following (valid, finite) rows; their
-    // results are never stored
+    // results are never stored.  The clamp is the last row that exists: when the permutation dropped an invalid
+    // expert index there are fewer rows than assignments, and the row tables beyond them are not written.
     auto row_ids = [&](int slot0, int& tx, int& ta) {
-        ta = min(slot0 + (tid & (BM - 1)), G.a_tot - 1);
+        ta = min(slot0 + (tid & (BM - 1)), last_row);
         tx = STAGE == 0 ? row_token[ta] : ta;
     };
 
@@ -437,13 +440,9 @@ tq_status launch_prefill(const MGeom& G, const TqSection& sec, const uint8_t* bl
     constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
     constexpr int ROWB = UNIT_K * 2 + 16;
     const size_t smem = (size_t)2 * BM * ROWB + (size_t)4 * BM * 4;
-    static int n_cu = 0;
-    if (n_cu == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return TQ_ERR_HIP;
-        n_cu = prop.multiProcessorCount;
-    }
+    const TqDeviceState* ds = nullptr;
+    if (tqi_device_state(&ds) != TQ_OK) return TQ_ERR_HIP;
+    const int n_cu = ds->n_cu;
     const int grid = (2 * n_cu) / 8 * 8;     // two workgroups per CU, a whole number per XCD
     hipLaunchKernelGGL((moe_prefill_kernel<STAGE, GS>), dim3(grid), dim3(256), smem, st, G, sec, blob, xin, xaug, row_token,
                        tile_e, tile_row0, offsets, ctrl, ctrl_idx, out, ka);

@@ -194,7 +194,7 @@ __global__ void __launch_bounds__(64) chunk_scan_kernel(int32_t* __restrict__ hi
 __global__ void __launch_bounds__(1024) scan_kernel(int32_t* __restrict__ hist, int nblk, int E, int S, int T,
                                                     int32_t* __restrict__ offsets,
                                                     int32_t* __restrict__ tile_e, int32_t* __restrict__ tile_row0,
-                                                    int rt_max, int32_t* __restrict__ ctrl)
+                                                    int rt_max, int32_t* __restrict__ ctrl, int check_blob)
 {
     extern __shared__ int32_t sm[];   // counts[ne] | offs[ne+1] | tile scratch TQ_N_TILINGS*(ne+1)
     const int ne = E + S;
@@ -227,6 +227,10 @@ __global__ void __launch_bounds__(1024) scan_kernel(int32_t* __restrict__ hist, 
     __syncthreads();
     for (int e = tid; e <= ne; e += 1024) offsets[e] = offs[e];
     if (tile_e) build_tile_tables(offs, tsm, ne, tile_e, tile_row0, rt_max, ctrl, tid, 1024);
+    // blob / descriptor mismatch (found by hist_kernel, which ran before): no row tiles and no rows, so that every
+    // later kernel of the forward ends at once instead of indexing the blob with the wrong geometry
+    __syncthreads();
+    if (check_blob && ctrl && tid == 0 && (ctrl[0] & TQ_FLAG_BIT_BLOB)) { ctrl[1] = 0; ctrl[2] = 0; ctrl[3] = 0; ctrl[4] = 0; ctrl[5] = 0; }
 }
 
 // stable placement of one chunk of assignments by one wavefront; cursor[e] (LDS) = next free slot of expert e
@@ -320,11 +324,18 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
     float wv[NR];
 #pragma unroll
     for (int j = 0; j < NR; ++j) {
-        const int a = j * 64 + lane;
-        const int ac = min(a, n_assign - 1);
-        ev[j] = idx[ac];
-        wv[j] = w ? w[ac] : 1.0f;
-        if (a >= n_assign) ev[j] = -2;               // past the end: neither counted nor flagged
+        ev[j] = -2;                                  // past the end: neither counted nor flagged
+        wv[j] = 1.0f;
+    }
+    if (n_assign > 0) {                              // an empty batch has no first element to clamp to
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+            const int a = j * 64 + lane;
+            const int ac = min(a, n_assign - 1);
+            const int ej = idx[ac];
+            const float wj = w ? w[ac] : 1.0f;
+            if (a < n_assign) { ev[j] = ej; wv[j] = wj; }
+        }
     }
     TqBlobHeader hv = expect;
     if (check_blob) hv = *hdr;
@@ -384,6 +395,9 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
         if (row_w) row_w[slot] = 1.0f;
     }
     if (flags && lane == 0 && err_flag) atomicOr(err_flag, flags);
+    // a blob that does not belong to the descriptor must not be indexed with the descriptor's geometry: with no
+    // row tiles and no rows every later kernel of the forward ends at once
+    if ((flags & TQ_FLAG_BIT_BLOB) && ctrl && lane == 0) { ctrl[1] = 0; ctrl[2] = 0; ctrl[3] = 0; ctrl[4] = 0; ctrl[5] = 0; }
 }
 
 __global__ void clear_ctrl_kernel(int32_t* ctrl, int32_t* err_flag, int32_t* zero_buf, int zero_n)
@@ -434,7 +448,7 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
         TQ_CHECK_LAUNCH();
     }
     hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(1024), sm_scan, stream, split_scan ? nullptr : hist, nblk, E, S, T,
-                       offsets, tile_e, tile_row0, rt_max, ctrl);
+                       offsets, tile_e, tile_row0, rt_max, ctrl, check && err_flag == ctrl ? 1 : 0);
     TQ_CHECK_LAUNCH();
     hipLaunchKernelGGL(scatter_kernel, dim3(nblk), dim3(64), (size_t)E * 4, stream, topk_idx, topk_w, n_assign, E,
                        S, T, k, hist, offsets, slot_of, slot_stride, src_of, row_token, row_w);
@@ -480,7 +494,7 @@ extern "C" tq_status tq_permute(const int32_t* topk_idx, int32_t T, int32_t E, i
          (uintptr_t)err_flag | (uintptr_t)workspace) & 3)
         return TQ_ERR_ALIGN;
     int64_t nblk = ((int64_t)T * k + TQ_PERM_CHUNK - 1) / TQ_PERM_CHUNK;
-    if (nblk < 1) nblk = 1;
+    if (nblk < 1) nblk = 1;     // T == 0 runs the single-wave kernel with nothing to place: offsets become all zero
     return tqi_launch_permute(topk_idx, nullptr, T, E, 0, k, offsets, slot_of, k, src_of, nullptr, nullptr,
                               nullptr, nullptr, 0, nullptr, err_flag, (int32_t*)workspace, (int32_t)nblk, nullptr,
                               nullptr, nullptr, 0, (hipStream_t)stream);

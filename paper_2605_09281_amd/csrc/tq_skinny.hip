@@ -443,23 +443,12 @@ tq_status launch_skinny(const MGeom& G, const TqSection& sec, const uint8_t* blo
     const int mb_off = xs_off + (range_k / G.g) * 16 * 4;      // mailbox of the pair scheduler
     const size_t smem = (size_t)mb_off + 16;
     if (smem > 160 * 1024) return TQ_ERR_UNSUPPORTED;
-    auto kern = moe_skinny_kernel<STAGE, GS>;
-    static bool done = false;
-    if (!done) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
-            return TQ_ERR_HIP;
-        done = true;
-    }
+    auto kern = moe_skinny_kernel<STAGE, GS>;      // dynamic-LDS limit: raised once per device by tqi_setup_skinny
     // one workgroup per compute unit over the tiles that are expected to exist: a workgroup fills a CU (LDS),
     // and fewer, longer workgroups amortise the set-up (activation staging, group sums) over more pairs
-    static int target = 0;
-    if (!target) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-            cus = 256;
-        target = cus;
-    }
+    const TqDeviceState* ds = nullptr;
+    if (tqi_device_state(&ds) != TQ_OK) return TQ_ERR_HIP;
+    const int target = ds->n_cu;
     long total = (long)sec.pairs * tiles_est * nsplit;
     int ppw = (int)((total + target - 1) / target);
     if (ppw < 1) ppw = 1;
@@ -503,6 +492,16 @@ inline void plan_split(int K, int g, int* nsplit, int* units_per_split)
 }
 
 }  // namespace
+
+tq_status tqi_setup_skinny()
+{
+    bool ok = true;
+#define TQ_ONE(ST, GS) ok = ok && hipFuncSetAttribute((const void*)moe_skinny_kernel<ST, GS>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) == hipSuccess
+    TQ_ONE(0, 2); TQ_ONE(0, 4); TQ_ONE(0, 8); TQ_ONE(0, 16);
+    TQ_ONE(1, 2); TQ_ONE(1, 4); TQ_ONE(1, 8); TQ_ONE(1, 16);
+#undef TQ_ONE
+    return ok ? TQ_OK : TQ_ERR_HIP;
+}
 
 // Whether the decode path can run this layer (LDS budget, one workgroup must span the whole hidden size).
 bool tqi_skinny_supported(const TqLayout& L)

@@ -1,0 +1,144 @@
+"""GPU parity on inputs built to expose single terms of the projection (tests/variants.py): a pure low-rank
+layer, low-rank factors as large as the quantised term, irregular zero-points and scales; on every tile path of
+the bf16 kernels and on the fp32 debug path; plus a forward with an invalid expert index on each path.
+
+Bounds: the benchmark spec's 2e-2, and next to it REG, a regression bound near what the arithmetic gives: the bf16
+path rounds t = xA, B and h to bf16 (2^-9 relative each, fp32 accumulation), i.e. about 3e-3 of the output scale
+on the plain layers and up to about 5e-3 when the low-rank term dominates (t and B both rounded).  A lost MFMA
+step, a dropped term or a wrong fold shows up at 1e-1 and more on these inputs (tests/test_parity_power.py)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from synth import LayerConfig, make_layer, make_x, make_logits
+import paper_2605_09281_amd.binding as tq
+from gpu_util import DEV, desc_of, pack_layer_gpu, x_device, rel_err
+import variants
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+REG_BF16 = 8e-3
+TOL_FP32 = 1e-5
+FLAGS = {"auto": 0, "tile32": tq.TQ_FLAG_FORCE_SMALL_TILE, "tile_large": tq.TQ_FLAG_FORCE_LARGE_TILE,
+         "tile16": tq.TQ_FLAG_FORCE_SKINNY}
+
+
+def shape(cfg_id, **kw):
+    base = dict(name="pw", E=4, S=0, k=2, H=128, F=192, T=37, g=64, r=8, bits=4)
+    base.update(kw)
+    return LayerConfig(cfg_id, **base)
+
+
+SHAPES = {
+    "base": shape(701),
+    "ragged_r32": shape(702, E=16, k=4, H=256, F=320, T=150, g=64, r=32),
+    "g128_r64_shared": shape(703, H=256, F=384, g=128, r=64, E=5, S=1, k=3, T=90),
+    "int3_g32_r20": shape(704, bits=3, g=32, r=20, H=192, F=128, T=70),
+}
+KINDS = ["pure_lowrank", "amplified", "odd_quant", "amplified_odd_quant"]
+
+_base = {}
+
+
+def build(name, kind):
+    cfg = SHAPES[name]
+    if name not in _base:
+        _base[name] = (make_layer(cfg, workers=8), make_x(cfg), make_logits(cfg))
+    layer, x, (logits, bias) = _base[name]
+    if kind == "pure_lowrank":
+        layer = variants.pure_lowrank(layer)
+    elif kind == "amplified":
+        layer = variants.amplified(layer)
+    elif kind == "odd_quant":
+        layer = variants.odd_quant(layer, cfg.cfg_id)
+    elif kind == "amplified_odd_quant":
+        layer = variants.odd_quant(variants.amplified(layer), cfg.cfg_id + 1)
+    return layer, x, logits, bias
+
+
+def forward(layer, x, logits, bias, act, flags, poison=False):
+    cfg = layer.cfg
+    packed = pack_layer_gpu(layer, act)
+    idx, w = tq.tq_route(torch.from_numpy(logits).to(DEV), None if bias is None else torch.from_numpy(bias).to(DEV), cfg.k)
+    desc = desc_of(cfg, act, flags)
+    ws = torch.empty(tq.tq_moe_workspace_size(desc, x.shape[0]), dtype=torch.uint8, device=DEV)
+    if poison:
+        ws.fill_(0x7F)
+    y = tq.tq_moe_forward(desc, packed, x_device(x, act), idx, w, workspace=ws)
+    torch.cuda.synchronize()
+    return y, idx, w, ws
+
+
+@pytest.mark.parametrize("flag", list(FLAGS))
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_bf16_sees_every_term(name, kind, flag):
+    print(f"power {name} {kind} {flag}", flush=True)
+    layer, x, logits, bias = build(name, kind)
+    y, idx, w, ws = forward(layer, x, logits, bias, tq.TQ_ACT_BF16, FLAGS[flag])
+    assert int(ws[:4].view(torch.int32).item()) == 0
+    ref = oracle.moe_forward_layer(layer, x, idx.cpu().numpy(), w.cpu().numpy())
+    err = rel_err(y.float().cpu().numpy(), ref)
+    print(f"   rel err {err:.3e}", flush=True)
+    assert err <= TOL_BF16
+    assert err <= REG_BF16
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("name", ["base", "g128_r64_shared", "int3_g32_r20"])
+def test_fp32_sees_every_term(name, kind):
+    print(f"power fp32 {name} {kind}", flush=True)
+    layer, x, logits, bias = build(name, kind)
+    y, idx, w, ws = forward(layer, x, logits, bias, tq.TQ_ACT_FP32, 0)
+    ref = oracle.moe_forward_layer(layer, x, idx.cpu().numpy(), w.cpu().numpy())
+    assert rel_err(y.cpu().numpy(), ref) <= TOL_FP32
+
+
+@pytest.mark.parametrize("flag", list(FLAGS))
+@pytest.mark.parametrize("name", ["base", "ragged_r32"])
+def test_invalid_expert_index_is_flagged_and_contributes_nothing(name, flag):
+    """One routing entry outside [0, E): flag bit 0 is set, that assignment adds nothing, every other output equals the
+    oracle's.  The workspace is filled with a byte pattern first, so that row tables past the rows that exist do not
+    hold plausible values by accident."""
+    print(f"invalid index {name} {flag}", flush=True)
+    layer, x, logits, bias = build(name, "amplified")
+    cfg = layer.cfg
+    packed = pack_layer_gpu(layer)
+    idx, w = tq.tq_route(torch.from_numpy(logits).to(DEV), None, cfg.k)
+    idx_bad = idx.clone()
+    t_bad, j_bad = cfg.T // 2, cfg.k - 1
+    idx_bad[t_bad, j_bad] = cfg.E + 3
+    desc = desc_of(cfg, tq.TQ_ACT_BF16, FLAGS[flag])
+    ws = torch.empty(tq.tq_moe_workspace_size(desc, cfg.T), dtype=torch.uint8, device=DEV)
+    ws.fill_(0x7F)
+    y = tq.tq_moe_forward(desc, packed, x_device(x, tq.TQ_ACT_BF16), idx_bad, w, workspace=ws)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32).item()) == 1
+    # the oracle refuses invalid indices; "contributes nothing" is the same layer with that weight set to zero
+    idx_ref = idx.cpu().numpy().copy()
+    w_ref = w.cpu().numpy().copy()
+    w_ref[t_bad, j_bad] = 0.0
+    ref = oracle.moe_forward_layer(layer, x, idx_ref, w_ref)
+    err = rel_err(y.float().cpu().numpy(), ref)
+    assert err <= REG_BF16, err
+
+
+def test_blob_of_another_layer_is_flagged_and_nothing_runs():
+    """A packed blob whose header does not match the descriptor: flag bit 1, no kernel indexes the blob."""
+    layer, x, logits, bias = build("base", "amplified")
+    cfg = layer.cfg
+    packed = pack_layer_gpu(layer)
+    other = shape(799, F=256)
+    idx, w = tq.tq_route(torch.from_numpy(logits).to(DEV), None, cfg.k)
+    for act in (tq.TQ_ACT_BF16, tq.TQ_ACT_FP32):
+        desc = desc_of(other, act, 0)
+        big = torch.zeros(tq.tq_packed_size(desc), dtype=torch.uint8, device=DEV)
+        big[:packed.numel()] = packed                      # readable at the other layer's size, wrong header
+        y = tq.tq_moe_forward(desc, big, x_device(x, act), idx, w)     # workspace allocated by the binding
+        torch.cuda.synchronize()
+    ws = torch.empty(tq.tq_moe_workspace_size(desc_of(other, tq.TQ_ACT_BF16, 0), cfg.T), dtype=torch.uint8, device=DEV)
+    tq.tq_moe_forward(desc_of(other, tq.TQ_ACT_BF16, 0), big, x_device(x, tq.TQ_ACT_BF16), idx, w, workspace=ws)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32).item()) & 2

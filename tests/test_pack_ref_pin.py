@@ -1,0 +1,162 @@
+"""CPU pin of oracle/pack_ref.py (the independent packer that the GPU packer is compared with byte for byte).
+
+pack_ref builds the blob with numpy reshapes and transposes.  Here the same blob is written out element by
+element, one scalar loop per part, straight from the layout text in include/tileq.h ("word w of (pair, chunk c,
+tile, lane) carries the 8 codes of column (tile, lane%32) at kk = 64c + 16w + 8hf + i ..."), on the smallest
+layers the descriptor allows, and the two must agree on every byte.  A transposed axis, a wrong nibble order, a
+gate/up swap or a mis-sized part in pack_ref fails here without a GPU."""
+import struct
+
+import numpy as np
+import pytest
+
+from oracle import pack_ref
+from synth import LayerConfig, make_layer
+
+
+def _bf16_rne_scalar(f: float) -> int:
+    u = struct.unpack("<I", struct.pack("<f", np.float32(f)))[0]
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) & 0xFFFF
+
+
+def _bf16_to_f32(b: int) -> np.float32:
+    return np.float32(struct.unpack("<f", struct.pack("<I", b << 16))[0])
+
+
+def _align256(n):
+    return (n + 255) // 256 * 256
+
+
+def blob_by_definition(layer) -> bytes:
+    c = layer.cfg
+    H, F, g, r = c.H, c.F, c.g, c.r
+    r16 = (r + 15) // 16 * 16
+    out = bytearray()
+    for e in range(c.E + c.S):
+        rec = bytearray()
+        for sec in ("GU", "D"):
+            if sec == "GU":
+                K, pairs = H, F // 32
+                # pair j = (gate rows 32j..32j+31, up rows 32j..32j+31)
+                col_of = lambda pair, tile, cc: (tile, 32 * pair + cc)          # (projection, row of that matrix)
+                na = 2 * r16
+            else:
+                K, pairs = F, H // 64
+                col_of = lambda pair, tile, cc: (2, 64 * pair + 32 * tile + cc)
+                na = r16
+            G = K // g
+            codes = [layer.codes_matrix(e, p) for p in range(3)]
+            scale = [layer.scale_matrix(e, p).view(np.uint16) for p in range(3)]
+            zero = [layer.zero_matrix(e, p).view(np.uint16) for p in range(3)]
+            # ---- codes: uint32 [pairs][K/64][2 tiles][64 lanes][4]
+            part = bytearray()
+            for pair in range(pairs):
+                for ch in range(K // 64):
+                    for tile in range(2):
+                        for lane in range(64):
+                            p, n = col_of(pair, tile, lane % 32)
+                            hf = lane // 32
+                            for w in range(4):
+                                word = 0
+                                for i in range(8):
+                                    kk = 64 * ch + 16 * w + 8 * hf + i
+                                    word |= (int(codes[p][n, kk]) & 15) << (4 * ((i // 2) + 4 * (i % 2)))
+                                part += struct.pack("<I", word)
+            rec += part
+            # ---- sz: uint32 [pairs][K/g][2 tiles][32]  low half scale, high half zero
+            part = bytearray()
+            for pair in range(pairs):
+                for gi in range(G):
+                    for tile in range(2):
+                        for cc in range(32):
+                            p, n = col_of(pair, tile, cc)
+                            part += struct.pack("<I", int(scale[p][n, gi]) | (int(zero[p][n, gi]) << 16))
+            rec += part
+            # ---- zc: bf16 [pairs][3*ceil(G/16)][2 tiles][64 lanes][8]
+            part = bytearray()
+            for pair in range(pairs):
+                for s in range(3 * ((G + 15) // 16)):
+                    for tile in range(2):
+                        for lane in range(64):
+                            p, n = col_of(pair, tile, lane % 32)
+                            hf = lane // 32
+                            for i in range(8):
+                                gi = 16 * (s // 3) + 8 * hf + i
+                                v = 0
+                                if gi < G:
+                                    sc = np.float32(scale[p][n, gi:gi + 1].view(np.float16)[0])
+                                    ze = np.float32(zero[p][n, gi:gi + 1].view(np.float16)[0])
+                                    cf = np.float32(-sc) * np.float32(np.float32(128.0) + ze)
+                                    hi = _bf16_rne_scalar(cf)
+                                    v = hi if s % 3 in (0, 1) else _bf16_rne_scalar(np.float32(cf - _bf16_to_f32(hi)))
+                                part += struct.pack("<H", v)
+            rec += part
+            if r > 0:
+                A = [layer.a_matrix(e, p).view(np.uint16) for p in range(3)]
+                B = [layer.b_matrix(e, p).view(np.uint16) for p in range(3)]
+                # ---- bfrag: fp16 [pairs][r16/16][2 tiles][64 lanes][8]
+                part = bytearray()
+                for pair in range(pairs):
+                    for s in range(r16 // 16):
+                        for tile in range(2):
+                            for lane in range(64):
+                                p, n = col_of(pair, tile, lane % 32)
+                                hf = lane // 32
+                                for i in range(8):
+                                    rho = 16 * s + 8 * hf + i
+                                    part += struct.pack("<H", int(B[p][rho, n]) if rho < r else 0)
+                rec += part
+                # ---- afrag: fp16 [ceil(NA/32)][K/16][64 lanes][8]
+                part = bytearray()
+                for ta in range((na + 31) // 32):
+                    for s in range(K // 16):
+                        for lane in range(64):
+                            hf = lane // 32
+                            cc = 32 * ta + lane % 32
+                            for i in range(8):
+                                kk = 16 * s + 8 * hf + i
+                                v = 0
+                                if cc < na:
+                                    p, rho = (cc // r16, cc % r16) if sec == "GU" else (2, cc)
+                                    if rho < r:
+                                        v = int(A[p][kk, rho])
+                                part += struct.pack("<H", v)
+                rec += part
+        rec += b"\0" * (_align256(len(rec)) - len(rec))
+        out += rec
+    return bytes(out)
+
+
+CASES = {
+    "smallest_g32_r4": LayerConfig(901, "p", E=1, S=0, k=1, H=64, F=64, T=1, g=32, r=4, bits=4),
+    "rect_g64_r20_shared": LayerConfig(902, "p", E=2, S=1, k=1, H=128, F=64, T=1, g=64, r=20, bits=4),
+    "rank0_int3": LayerConfig(903, "p", E=1, S=0, k=1, H=64, F=128, T=1, g=64, r=0, bits=3),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_pack_ref_equals_the_layout_written_out_element_by_element(name):
+    layer = make_layer(CASES[name], workers=1)
+    # make the zero-points and scales irregular so that hi/lo parts and both halves of the sz word are exercised
+    rng = np.random.default_rng(CASES[name].cfg_id)
+    z = layer.zero.view(np.float16).astype(np.float32) + rng.uniform(-0.5, 0.5, layer.zero.shape).astype(np.float32)
+    layer.zero = z.astype(np.float16).view(np.uint16)
+    want = blob_by_definition(layer)
+    got = pack_ref.pack_layer(layer).tobytes()
+    assert len(got) == len(want)
+    assert got == want
+
+
+def test_pack_ref_size_is_the_storage_count_of_the_header():
+    """Sizes of the five parts per section as include/tileq.h states them."""
+    for cfg in CASES.values():
+        layer = make_layer(cfg, workers=1)
+        H, F, g, r = cfg.H, cfg.F, cfg.g, cfg.r
+        r16 = (r + 15) // 16 * 16
+        total = 0
+        for K, pairs, na in ((H, F // 32, 2 * r16), (F, H // 64, r16)):
+            G = K // g
+            total += pairs * (K // 64) * 2 * 64 * 16 + pairs * G * 2 * 32 * 4 + pairs * 3 * ((G + 15) // 16) * 2 * 64 * 16
+            if r:
+                total += pairs * (r16 // 16) * 2 * 64 * 16 + ((na + 31) // 32) * (K // 16) * 64 * 16
+        assert pack_ref.pack_layer(layer).size == (cfg.E + cfg.S) * _align256(total)
