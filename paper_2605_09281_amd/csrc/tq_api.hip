@@ -155,11 +155,32 @@ extern "C" size_t tq_moe_workspace_size(const tq_layer_desc* desc, int32_t T)
     return need;
 }
 
+namespace {
+__global__ void copy_flag_kernel(const int32_t* __restrict__ ctrl, int32_t* __restrict__ err_flag)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) *err_flag = ctrl[0];
+}
+
+// shared body of tq_moe_forward and tq_moe_forward_static; use_static: the workspace is this device's scratch array
+tq_status forward_impl(const tq_layer_desc* desc, const void* packed, const void* x, const int32_t* topk_idx,
+                       const float* topk_w, int32_t T, void* y, void* workspace, size_t workspace_bytes,
+                       bool use_static, int32_t* err_flag, void* stream);
+}  // namespace
+
 extern "C" tq_status tq_moe_forward(const tq_layer_desc* desc, const void* packed, const void* x,
                                     const int32_t* topk_idx, const float* topk_w, int32_t T, void* y,
                                     void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!desc || !packed || !x || !topk_idx || !topk_w || !y || !workspace) return TQ_ERR_NULL;
+    if (!workspace) return TQ_ERR_NULL;
+    return forward_impl(desc, packed, x, topk_idx, topk_w, T, y, workspace, workspace_bytes, false, nullptr, stream);
+}
+
+namespace {
+tq_status forward_impl(const tq_layer_desc* desc, const void* packed, const void* x, const int32_t* topk_idx,
+                       const float* topk_w, int32_t T, void* y, void* workspace, size_t workspace_bytes,
+                       bool use_static, int32_t* err_flag, void* stream)
+{
+    if (!desc || !packed || !x || !topk_idx || !topk_w || !y) return TQ_ERR_NULL;
     TqLayout L;
     if (!tq_make_layout(desc, &L) || T < 0) return TQ_ERR_SHAPE;
     if ((int64_t)T * (L.k + L.S) > 0x3FFFFFFF) return TQ_ERR_SHAPE;
@@ -167,10 +188,11 @@ extern "C" tq_status tq_moe_forward(const tq_layer_desc* desc, const void* packe
     if (((uintptr_t)x | (uintptr_t)y | (uintptr_t)topk_idx | (uintptr_t)topk_w) & 15) return TQ_ERR_ALIGN;
     TqWorkspace W;
     tq_make_workspace(L, desc->act_dtype, T, &W);
-    if (workspace_bytes < W.total) return TQ_ERR_WORKSPACE;
+    if (workspace_bytes < W.total) return TQ_ERR_WORKSPACE;      // static entry point: the batch needs more than the array holds
     if (T == 0) return TQ_OK;
     const TqDeviceState* ds = nullptr;
     if (tqi_device_state(&ds) != TQ_OK) return TQ_ERR_HIP;
+    if (use_static) workspace = ds->scratch;      // the address resolved for THIS device, never the array's name
     hipStream_t st = (hipStream_t)stream;
     uint8_t* ws = (uint8_t*)workspace;
     int32_t* ctrl = (int32_t*)(ws + W.ctrl);
@@ -184,7 +206,15 @@ extern "C" tq_status tq_moe_forward(const tq_layer_desc* desc, const void* packe
     if (rc != TQ_OK) return rc;
     tqi_record_stage(1, st);
     if (desc->act_dtype == TQ_ACT_FP32)
-        return tqi_forward_f32(L, W, (const uint8_t*)packed, (const float*)x, T, (float*)y, ws, st, topk_w);
-    return tqi_forward_bf16(L, W, desc->flags, (const uint8_t*)packed, (const uint16_t*)x, T, (uint16_t*)y, ws, st,
-                            topk_w);
+        rc = tqi_forward_f32(L, W, (const uint8_t*)packed, (const float*)x, T, (float*)y, ws, st, topk_w);
+    else
+        rc = tqi_forward_bf16(L, W, desc->flags, (const uint8_t*)packed, (const uint16_t*)x, T, (uint16_t*)y, ws, st,
+                              topk_w);
+    if (rc != TQ_OK) return rc;
+    if (err_flag) {
+        hipLaunchKernelGGL(copy_flag_kernel, dim3(1), dim3(64), 0, st, (const int32_t*)ctrl, err_flag);
+        TQ_CHECK_LAUNCH();
+    }
+    return TQ_OK;
 }
+}  // namespace

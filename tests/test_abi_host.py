@@ -102,6 +102,19 @@ def test_workspace_grows_with_tokens():
     assert 0 < a < b
 
 
+@pytest.mark.parametrize("E,S,k,H,F,g,r", [(16, 0, 8, 4096, 1536, 128, 32), (8, 0, 2, 4096, 14336, 128, 32),
+                                           (64, 2, 6, 2048, 1408, 128, 16), (4, 0, 1, 64, 64, 32, 0)])
+def test_workspace_size_never_shrinks_as_tokens_grow(E, S, k, H, F, g, r):
+    """A workspace sized for T tokens must serve every smaller batch: the size is non-decreasing in T, in particular
+    across the batch sizes where the split-K planes (4096 assignment rows) and the decode scratch (1024) are dropped."""
+    d = tq.make_desc(E, S, k, H, F, g, 4, r)
+    per = k + S
+    marks = sorted({1, 2, 1024 // per - 1, 1024 // per, 1024 // per + 1, 4096 // per - 1, 4096 // per, 4096 // per + 1,
+                    2 * 4096 // per, 8192, 20000} - {0})
+    sizes = [tq.tq_moe_workspace_size(d, T) for T in marks]
+    assert all(b >= a > 0 for a, b in zip(sizes, sizes[1:])), list(zip(marks, sizes))
+
+
 # ------------------------------------------------------------------ shared-factor low-rank operator (host side)
 def test_lotile_packed_size_closed_form():
     """Appendix A.3, shared tiled factors: M in r + N r out 16-bit values (with r padded to a multiple of 16 and the

@@ -99,6 +99,19 @@ def test_workspace_sized_for_a_large_batch_serves_smaller_ones():
         assert rel_err(got, ref) <= TOL_BF16
 
 
+def test_workspace_serves_smaller_batches_across_the_path_thresholds():
+    """Sized for a batch on the tiled path (more than 4096 assignment rows), then used for batches that take the
+    split-K planes (at most 4096 rows) and the decode scratch (at most 1024 rows)."""
+    cfg = corner(522, H=128, F=192, g=64, r=8, E=6, k=3, T=1500)
+    desc = desc_of(cfg, tq.TQ_ACT_BF16, 0)
+    ws = torch.empty(tq.tq_moe_workspace_size(desc, cfg.T), dtype=torch.uint8, device=DEV)
+    for T in (1500, 1300, 300, 5):
+        print(f"workspace reuse across thresholds T={T}", flush=True)
+        assert tq.tq_moe_workspace_size(desc, T) <= ws.numel()
+        got, ref = forward(cfg, tq.TQ_ACT_BF16, 0, ws=ws, T=T)
+        assert rel_err(got, ref) <= TOL_BF16
+
+
 def test_many_rows_small_layer():
     """Tens of thousands of tokens on a small layer: thousands of row tiles per expert, multi-chunk permutation,
     persistent workgroups walking long item lists; sampled tokens against the oracle, all tokens finite."""

@@ -14,7 +14,8 @@ import variants
 pytestmark = pytest.mark.gpu
 
 SAMPLE = {1: 64, 2: 16, 3: 24, 4: 48, 5: 16}      # random tokens, on top of the tokens at the segment edges
-REG_BF16 = 8e-3     # regression bound next to the benchmark spec's 2e-2 (see tests/test_gpu_power.py)
+REG_BF16 = 4 * 2.0 ** -9        # regression bounds next to the benchmark spec's 2e-2, derived in tests/test_gpu_power.py:
+REG_LR_BF16 = 7 * 2.0 ** -9     # plain layers, and layers whose output is dominated by the rank-r chain
 
 
 def sample_tokens(cfg, ridx, seed):
@@ -69,7 +70,7 @@ def test_full_config_bf16_sees_the_low_rank_and_zero_point_terms(cfg_id, kind):
     cfg = CONFIGS[cfg_id]
     print(f"config {cfg_id} {kind}: generating", flush=True)
     layer = make_layer(cfg, workers=16)
-    layer = {"amplified": variants.amplified, "pure_lowrank": variants.pure_lowrank,
+    layer = {"amplified": variants.amplified, "pure_lowrank": lambda l: variants.pure_lowrank(variants.amplified(l)),
              "odd_quant": lambda l: variants.odd_quant(l, 77)}[kind](layer)
     x = make_x(cfg)
     logits, bias = make_logits(cfg)
@@ -87,7 +88,7 @@ def test_full_config_bf16_sees_the_low_rank_and_zero_point_terms(cfg_id, kind):
     err = rel_err(y.float().cpu().numpy()[tok], ref)
     print(f"config {cfg_id} {kind}: bf16 rel err {err:.3e} on {tok.size} tokens", flush=True)
     assert err <= 2e-2
-    assert err <= REG_BF16
+    assert err <= (REG_BF16 if kind == "odd_quant" else REG_LR_BF16)
 
 
 @pytest.mark.parametrize("cfg_id", [2, 4])

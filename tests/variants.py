@@ -4,7 +4,11 @@ Input manufacture only (no forward arithmetic): each function returns a copy of 
 arrays were edited; the same arrays then feed the oracle and the GPU.
 
   pure_lowrank   codes := zero-point of their group (an integer in [0, qmax] from the RTN quantiser), so the
-                 dequantised matrix is exactly 0 and the output is the rank-r chain alone
+                 dequantised matrix is exactly 0 and the output is the rank-r chain alone.  Used on amplified
+                 factors: the bf16 kernels evaluate the quantised term as s * sum x (128 + q) - s (128 + z) * sum x,
+                 whose two halves cancel here only up to the rounding of the second (about 2^-17 of s (128 + z) sum x
+                 per group, a few 1e-5 in absolute terms), and the un-amplified rank-r output of a small layer
+                 (a few 1e-3) would be compared against that noise instead of against the kernels' low-rank steps
   amplified      A and B times 8 (exact on fp16 bit patterns): the rank-r term grows 64x, to the size of the
                  quantised term and beyond
   odd_quant      fractional zero-points, zero-points below 0 and above qmax, subnormal and large fp16 scales
