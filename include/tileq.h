@@ -182,6 +182,22 @@ tq_status tq_moe_forward(const tq_layer_desc *desc, const void *packed, const vo
                          const int32_t *topk_idx, const float *topk_w, int32_t T, void *y,
                          void *workspace, size_t workspace_bytes, void *stream);
 
+/* For callers that cannot allocate device memory — code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc: tq_moe_forward without a workspace argument.  The same kernels run on a scratch array
+ * of TQ_STATIC_SCRATCH_MAX bytes that lives inside the library (a static device array: every GPU the library runs
+ * on holds its own copy until the process ends); the call allocates nothing and frees nothing.  All other arguments
+ * as tq_moe_forward.  err_flag (device int32, 4-byte aligned, may be NULL) receives the error flag described there
+ * at the end of the call.  Returns TQ_ERR_WORKSPACE, before any launch, when the batch needs more scratch than the
+ * array holds, i.e. when tq_moe_workspace_size(desc, T) computed for exactly this T exceeds TQ_STATIC_SCRATCH_MAX
+ * (decode batches and small prefill batches fit; use tq_moe_forward beyond).  Every call on one GPU uses that
+ * GPU's single array: the call itself clears what must start at zero, but two calls that overlap in time on one
+ * GPU (different streams or threads) race and must be serialised by the caller.  Callers whose first call on a
+ * device is inside a stream capture call tq_init() before capturing. */
+#define TQ_STATIC_SCRATCH_MAX (32u << 20)
+tq_status tq_moe_forward_static(const tq_layer_desc *desc, const void *packed, const void *x,
+                                const int32_t *topk_idx, const float *topk_w, int32_t T, void *y,
+                                int32_t *err_flag, void *stream);
+
 /* Profiling aid (not part of the method).  Registers up to TQ_N_STAGE_EVENTS hipEvent_t handles (host
  * array, copied) that tq_moe_forward records on its stream at the stage boundaries:
  *   0 entry, 1 after the permutation, 2 after the gate/up pre-pass (group sums and x A), 3 after gate/up,

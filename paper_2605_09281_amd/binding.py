@@ -21,7 +21,7 @@ STATUS_NAMES = {0: "TQ_OK", 1: "TQ_ERR_NULL", 2: "TQ_ERR_SHAPE", 3: "TQ_ERR_ALIG
                 5: "TQ_ERR_WORKSPACE", 6: "TQ_ERR_UNSUPPORTED", 7: "TQ_ERR_HIP", 8: "TQ_ERR_BLOB"}
 
 EXPORTS = ["tq_init", "tq_status_str", "tq_packed_size", "tq_pack_weights", "tq_unpack_weights", "tq_route",
-           "tq_permute_workspace_size", "tq_permute", "tq_moe_workspace_size", "tq_moe_forward",
+           "tq_permute_workspace_size", "tq_permute", "tq_moe_workspace_size", "tq_moe_forward", "tq_moe_forward_static",
            "tq_set_profile_events", "tq_debug_stream", "tq_lotile_packed_size", "tq_lotile_pack", "tq_lotile_pack_fp8",
            "tq_lotile_workspace_size", "tq_lotile_forward", "tq_lotile_grid", "tq_lotile_place"]
 
@@ -84,6 +84,10 @@ def lib():
         L.tq_moe_forward.argtypes = [ctypes.POINTER(LayerDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_size_t, ctypes.c_void_p]
+        L.tq_moe_forward_static.restype = ctypes.c_int
+        L.tq_moe_forward_static.argtypes = [ctypes.POINTER(LayerDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                            ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                            ctypes.c_void_p]
         L.tq_debug_stream.restype = ctypes.c_int
         L.tq_debug_stream.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_void_p]
         L.tq_set_profile_events.restype = ctypes.c_int
@@ -199,6 +203,16 @@ def tq_moe_forward(desc: LayerDesc, packed, x, topk_idx, topk_w, y=None, workspa
         workspace = torch.empty(max(tq_moe_workspace_size(desc, T), 256), dtype=torch.uint8, device=x.device)
     _check(lib().tq_moe_forward(ctypes.byref(desc), _ptr(packed), _ptr(x), _ptr(topk_idx), _ptr(topk_w), T, _ptr(y),
                                 _ptr(workspace), workspace.numel(), _stream()), "tq_moe_forward")
+    return y
+
+
+TQ_STATIC_SCRATCH_MAX = 32 << 20
+
+
+def tq_moe_forward_static(desc: LayerDesc, packed, x, topk_idx, topk_w, y, err_flag=None):
+    """tq_moe_forward on the library's static scratch array: allocates nothing (y is the caller's)."""
+    _check(lib().tq_moe_forward_static(ctypes.byref(desc), _ptr(packed), _ptr(x), _ptr(topk_idx), _ptr(topk_w),
+                                       x.shape[0], _ptr(y), _ptr(err_flag), _stream()), "tq_moe_forward_static")
     return y
 
 

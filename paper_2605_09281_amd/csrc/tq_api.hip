@@ -21,6 +21,11 @@ extern "C" const char* tq_status_str(tq_status s)
 #include <atomic>
 #include <mutex>
 
+// Scratch memory of tq_moe_forward_static: one array per device that loads this library, held until the process
+// ends.  In host code the name below is only a handle for hipGetSymbolAddress; the device address it resolves to
+// is kept per device in TqDeviceState::scratch and is what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[TQ_STATIC_SCRATCH_BYTES];
+
 namespace {
 constexpr int kMaxDevices = 64;
 std::mutex g_init_mu;
@@ -39,7 +44,9 @@ tq_status tqi_device_state(const TqDeviceState** out)
             if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
                 return TQ_ERR_HIP;
             g_dev_state[dev].n_cu = cus;
-            g_dev_state[dev].scratch = nullptr;
+            void* sp = nullptr;
+            if (hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)) != hipSuccess || !sp) return TQ_ERR_HIP;
+            g_dev_state[dev].scratch = sp;
             if (tqi_setup_mfma() != TQ_OK || tqi_setup_skinny() != TQ_OK) return TQ_ERR_HIP;
             g_dev_ready[dev].store(1, std::memory_order_release);
         }
@@ -173,6 +180,14 @@ extern "C" tq_status tq_moe_forward(const tq_layer_desc* desc, const void* packe
 {
     if (!workspace) return TQ_ERR_NULL;
     return forward_impl(desc, packed, x, topk_idx, topk_w, T, y, workspace, workspace_bytes, false, nullptr, stream);
+}
+
+extern "C" tq_status tq_moe_forward_static(const tq_layer_desc* desc, const void* packed, const void* x,
+                                           const int32_t* topk_idx, const float* topk_w, int32_t T, void* y,
+                                           int32_t* err_flag, void* stream)
+{
+    if ((uintptr_t)err_flag & 3) return TQ_ERR_ALIGN;
+    return forward_impl(desc, packed, x, topk_idx, topk_w, T, y, nullptr, TQ_STATIC_SCRATCH_BYTES, true, err_flag, stream);
 }
 
 namespace {

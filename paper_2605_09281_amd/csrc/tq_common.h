@@ -12,6 +12,7 @@
 #define TQ_BLOB_MAGIC 0x31425154u /* "TQB1" */
 #define TQ_BLOB_VERSION 1u
 #define TQ_HEADER_BYTES 256
+#define TQ_STATIC_SCRATCH_BYTES TQ_STATIC_SCRATCH_MAX   /* size of the static scratch array (tileq.h) */
 
 // error-flag bits written by kernels into the first int32 of the workspace / into err_flag
 #define TQ_FLAG_BIT_RANGE 1
