@@ -27,16 +27,18 @@ def _run(cmd, verbose):
         raise RuntimeError("hipcc failed: " + " ".join(cmd[-3:]))
 
 
-def build_library(verbose: bool = False, jobs: int = 8) -> str:
-    """Compile every HIP source into paper_2605_09281_amd/libtileq.so.  Always recompiles (one hipcc per
-    translation unit, `jobs` at a time, objects in a temporary folder)."""
-    out = library_path()
+def build_library(verbose: bool = False, jobs: int = 8, extra_flags=(), out: str = None) -> str:
+    """Compile every HIP source into paper_2605_09281_amd/libtileq.so (or `out`).  Always recompiles (one hipcc per
+    translation unit, `jobs` at a time, objects in a temporary folder).  `extra_flags` are appended to the compile
+    line (e.g. -D switches of a kernel variant under measurement)."""
+    out = out or library_path()
     inc = ["-I", os.path.join(_ROOT, "include")]
     with tempfile.TemporaryDirectory(prefix="tileq_build_") as tmp:
         objs = [os.path.join(tmp, s.replace(".hip", ".o")) for s in SOURCES]
 
         def one(i):
-            _run(["hipcc"] + _FLAGS + inc + ["-c", "-o", objs[i], os.path.join(_DIR, "csrc", SOURCES[i])], verbose)
+            _run(["hipcc"] + _FLAGS + list(extra_flags) + inc + ["-c", "-o", objs[i], os.path.join(_DIR, "csrc", SOURCES[i])],
+                 verbose)
 
         with ThreadPoolExecutor(max_workers=max(1, jobs)) as ex:
             list(ex.map(one, range(len(SOURCES))))
