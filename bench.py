@@ -71,9 +71,10 @@ def algorithmic_work(cfg, idx_np):
     H, F, g, r, T = cfg.H, cfg.F, cfg.g, cfg.r, cfg.T
     touched = int(np.unique(idx_np).size) + cfg.S
     a_tot = cfg.a_tot
-    gu_w = F * H + 2 * F * (H // g) * 4 + 2 * r * F * 2            # codes (2 matrices, 4 bit) + scale/zero + B factors
+    cb = cfg.bits if cfg.dense else 4                              # bits each code occupies in the blob
+    gu_w = 2 * F * H * cb // 8 + 2 * F * (H // g) * 4 + 2 * r * F * 2   # codes (2 matrices) + scale/zero + B factors
     gu_a = 2 * H * r * 2                                           # A factors (read by the pre-pass)
-    d_w = H * F // 2 + H * (F // g) * 4 + r * H * 2
+    d_w = H * F * cb // 8 + H * (F // g) * 4 + r * H * 2
     d_a = F * r * 2
     w_bytes = touched * (gu_w + gu_a + d_w + d_a)
     act_bytes = T * H * 2 * 2                                      # x in, y out
@@ -237,6 +238,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=None, choices=[1, 2, 3, 4, 5],
                     help="time one benchmark layer only; default: all five in turn, headline on config 5")
+    ap.add_argument("--dense-bits", type=int, default=0, choices=[0, 2, 3],
+                    help="with --workload: re-quantise the layer's weights to 2 or 3 bits and store the codes densely "
+                         "(decode workloads only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every step eagerly instead of replaying a captured HIP graph")
@@ -285,7 +289,10 @@ def main():
     if args.lotile or args.lotile_fp8:
         return bench_lotile(args, cfg, dev)
     if args.workload is not None:
-        res = bench_layer(args, CONFIGS[args.workload], dev, oracle_macs=1.5e11)
+        wl = CONFIGS[args.workload]
+        if args.dense_bits:
+            wl = wl.replace(bits=args.dense_bits, dense=True)
+        res = bench_layer(args, wl, dev, oracle_macs=1.5e11)
         print(json.dumps(headline(args, res, None)), flush=True)
         return
     # default: every benchmark layer in turn (configs 1-4 with a short oracle sample), the headline on the largest
@@ -293,6 +300,9 @@ def main():
     for c in (1, 2, 3, 4):
         per.append(bench_layer(args, CONFIGS[c], dev, oracle_macs=2.5e10))
         torch.cuda.empty_cache()
+        if c == 2:      # the decode layer once more at the paper's headline bit-width, stored densely
+            per.append(bench_layer(args, CONFIGS[2].replace(bits=3, dense=True), dev, oracle_macs=2.5e10))
+            torch.cuda.empty_cache()
     res5 = bench_layer(args, CONFIGS[5], dev, oracle_macs=1.5e11)
     per.append(res5)
     print(json.dumps(headline(args, res5, per)), flush=True)
@@ -339,7 +349,8 @@ def bench_layer(args, cfg, dev, oracle_macs):
     def dev16(a):
         return torch.from_numpy(a.view(np.int16)).to(dev)
 
-    desc = tq.make_desc(cfg.E, cfg.S, cfg.k, cfg.H, cfg.F, cfg.g, cfg.bits, cfg.r, tq.TQ_ACT_BF16)
+    desc = tq.make_desc(cfg.E, cfg.S, cfg.k, cfg.H, cfg.F, cfg.g, cfg.bits, cfg.r, tq.TQ_ACT_BF16,
+                        tq.TQ_FLAG_DENSE_CODES if cfg.dense else 0)
     codes_d = torch.from_numpy(layer.codes).to(dev)
     sc_d, ze_d = dev16(layer.scale), dev16(layer.zero)
     A_d = dev16(layer.A) if cfg.r else None
@@ -479,7 +490,7 @@ def bench_layer(args, cfg, dev, oracle_macs):
     return dict(tokens_per_s=round(cfg.T / t_step, 1), ms_per_step=round(ms_per_step, 5),
                 ms_per_step_median=round(ms_median, 5), ms_per_step_min=round(ms_min, 5),
                 launch="hip_graph" if use_graph else "eager",
-                config={"workload": f"config {cfg.cfg_id}: {cfg.name}", "experts": cfg.E, "shared": cfg.S, "top_k": cfg.k,
+                config={"workload": f"config {cfg.cfg_id}: {cfg.name}" + (f", codes re-quantised to {cfg.bits} bits, stored densely" if cfg.dense else ""), "experts": cfg.E, "shared": cfg.S, "top_k": cfg.k,
                         "hidden": cfg.H, "ffn": cfg.F, "tokens": cfg.T, "group": cfg.g, "rank": cfg.r, "bits": cfg.bits,
                         "touched_experts": work["touched"]},
                 roofline=roofline, cpu_baseline=cpu_baseline, max_rel_err=max_rel_err)

@@ -56,6 +56,16 @@
  *          element i of (tile ta, step s, lane) = A_p[kk = 16s + 8hf + i][rho] with column
  *          c = 32ta + lane%32, p = c / r16, rho = c % r16; 0 where rho >= r or c >= NA
  * The blob is position independent (offsets only) and may be stored and reloaded byte for byte.
+ *
+ * Dense codes (TQ_FLAG_DENSE_CODES, bits = 3 or 2): the codes part becomes
+ *   codes  uint32 [pairs][K/64][2 tiles][cw][64 lanes]      cw = bits words per lane
+ * and there is no zc part.  The 32 codes of (pair, chunk c, tile, lane), q[w][i] at kk = 64c + 16w + 8hf + i
+ * (w = 0..3, i = 0..7), form 16 slots P = 4w + j holding the two codes lo = q[w][2j], hi = q[w][2j+1], always 16
+ * bit positions apart so that one shift and one and-or yield two bf16 values:
+ *   bits = 2:  slot P sits in word P / 8 at position p = 2 (P % 8): lo in bits [p+1 : p], hi in bits [p+17 : p+16].
+ *   bits = 3:  slots 0..14 sit in word P / 5 at position p = 3 (P % 5): lo in bits [p+2 : p], hi in bits
+ *              [p+18 : p+16]; slot 15 uses the two bits left in every word: bit b (0..2) of its lo code is bit 15
+ *              of word b, bit b of its hi code is bit 31 of word b.
  */
 #ifndef TILEQ_H
 #define TILEQ_H
@@ -88,8 +98,14 @@ enum { TQ_ACT_BF16 = 0, TQ_ACT_FP32 = 1 };
 enum {
     TQ_FLAG_FORCE_SMALL_TILE = 1, /* bf16 path: always the 32-row tile */
     TQ_FLAG_FORCE_LARGE_TILE = 2, /* bf16 path: always the large (64/128-row, prefill) tiles */
-    TQ_FLAG_FORCE_SKINNY = 4      /* bf16 path: the 16-row weight-streaming (decode) kernels whenever the layer
+    TQ_FLAG_FORCE_SKINNY = 4,     /* bf16 path: the 16-row weight-streaming (decode) kernels whenever the layer
                                      and the batch (at most 1024 assignment rows) allow them */
+    /* Not a test hook but part of the format: codes of `bits` = 2 or 3 bits stored densely (the bit-widths of
+       Table 1; Appendix A.3 with d = 2 or 3) instead of in 4-bit slots.  Groups of 64 and more.  The blob then
+       has no zc part and its size is the storage count of Appendix A.3 plus padding.  Kernels: the decode path
+       (bf16 activations, at most 1024 assignment rows, layers the decode kernels support) and the fp32 debug
+       path; a bf16 batch beyond that returns TQ_ERR_UNSUPPORTED before any launch. */
+    TQ_FLAG_DENSE_CODES = 32
 };
 
 typedef struct tq_layer_desc {
@@ -99,11 +115,11 @@ typedef struct tq_layer_desc {
     int32_t hidden;    /* H  multiple of 64 and of group */
     int32_t ffn;       /* F  multiple of 64 and of group */
     int32_t group;     /* g  quantisation group along the contraction dim; 32, 64, 128 or 256 */
-    int32_t bits;      /* 4, or 3 (codes 0..7 kept in 4-bit slots) */
+    int32_t bits;      /* 4, or 3 (codes 0..7 kept in 4-bit slots); with TQ_FLAG_DENSE_CODES: 3 or 2, stored densely */
     int32_t rank;      /* r  in [0, 256]; 0 = no low-rank term.  The bf16 path carries at most 128 rank columns
                           (TQ_ERR_UNSUPPORTED beyond); the fp32 debug path takes all of them */
     int32_t act_dtype; /* TQ_ACT_BF16: x, y bf16, MFMA path.  TQ_ACT_FP32: x, y fp32, exact-dequant debug path */
-    int32_t flags;
+    int32_t flags;     /* TQ_FLAG_DENSE_CODES and / or test hooks */
 } tq_layer_desc;
 
 typedef struct tq_weights_src { /* canonical layout above; A, B may be NULL when rank == 0 */

@@ -53,6 +53,27 @@ def _words(codes_nk: np.ndarray) -> np.ndarray:
     return out
 
 
+def _dense_words(codes_nk: np.ndarray, bits: int) -> np.ndarray:
+    """[N, K] codes -> [N, K/64 (chunk), bits (word), 2 (hf)] uint32: the dense 2- / 3-bit layout.  Slot P = 4 w + j of a
+    (lane, chunk) holds lo = q[w][2j] and hi = q[w][2j+1] sixteen bit positions apart."""
+    N, K = codes_nk.shape
+    fm = (1 << bits) - 1
+    c = codes_nk.reshape(N, K // 64, 4, 2, 4, 2).astype(np.uint32) & fm       # [n, chunk, w, hf, j, lo/hi]
+    slot = c[..., 0] | (c[..., 1] << np.uint32(16))                             # [n, chunk, w, hf, j]
+    slot = slot.transpose(0, 1, 3, 2, 4).reshape(N, K // 64, 2, 16)             # [n, chunk, hf, P]
+    out = np.zeros((N, K // 64, 2, bits), dtype=np.uint32)                      # [n, chunk, hf, word]
+    if bits == 2:
+        for P in range(16):
+            out[..., P // 8] |= slot[..., P] << np.uint32(2 * (P % 8))
+    else:
+        for P in range(15):
+            out[..., P // 5] |= slot[..., P] << np.uint32(3 * (P % 5))
+        last = slot[..., 15]
+        for b in range(3):
+            out[..., b] |= (((last >> np.uint32(b)) & 1) << np.uint32(15)) | (((last >> np.uint32(16 + b)) & 1) << np.uint32(31))
+    return out.transpose(0, 1, 3, 2)                                            # [n, chunk, word, hf]
+
+
 def _pad_rows(a: np.ndarray, rows: int) -> np.ndarray:
     if a.shape[0] == rows:
         return a
@@ -69,8 +90,9 @@ def _pad_cols(a: np.ndarray, cols: int) -> np.ndarray:
     return out
 
 
-def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r) -> bytes:
-    """codes3[p]: [N,K] uint8; scale3/zero3[p]: [N,K/g] uint16; A3[p]: [K,r] uint16; B3[p]: [r,N] uint16."""
+def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r, dense_bits=0) -> bytes:
+    """codes3[p]: [N,K] uint8; scale3/zero3[p]: [N,K/g] uint16; A3[p]: [K,r] uint16; B3[p]: [r,N] uint16.
+    dense_bits: 0 = codes in 4-bit slots; 2 or 3 = the dense layouts (no zc part)."""
     r16 = (r + 15) // 16 * 16
     parts = []
 
@@ -78,17 +100,23 @@ def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r) -> bytes:
         if not is_d:
             K, pairs = H, F // 32
             # codes: [pairs, chunks, tile, hf, col, word]
-            w = np.stack([_words(codes3[p]).reshape(pairs, 32, K // 64, 4, 2) for p in (0, 1)], axis=0)
-            # w: [tile, pairs, col, chunk, word, hf] -> [pairs, chunk, tile, hf, col, word]
-            parts.append(np.ascontiguousarray(w.transpose(1, 3, 0, 5, 2, 4)).tobytes())
+            if dense_bits:
+                w = np.stack([_dense_words(codes3[p], dense_bits).reshape(pairs, 32, K // 64, dense_bits, 2) for p in (0, 1)], axis=0)
+                # [tile, pairs, col, chunk, word, hf] -> [pairs, chunk, tile, word, hf, col]
+                parts.append(np.ascontiguousarray(w.transpose(1, 3, 0, 4, 5, 2)).tobytes())
+            else:
+                w = np.stack([_words(codes3[p]).reshape(pairs, 32, K // 64, 4, 2) for p in (0, 1)], axis=0)
+                # w: [tile, pairs, col, chunk, word, hf] -> [pairs, chunk, tile, hf, col, word]
+                parts.append(np.ascontiguousarray(w.transpose(1, 3, 0, 5, 2, 4)).tobytes())
             sz = np.stack([(scale3[p].astype(np.uint32) | (zero3[p].astype(np.uint32) << 16)).reshape(pairs, 32, K // g)
                            for p in (0, 1)], axis=0)          # [tile, pairs, col, G]
             parts.append(np.ascontiguousarray(sz.transpose(1, 3, 0, 2)).tobytes())
             g16 = (K // g + 15) // 16
-            zc = np.stack([_zc_part(*_zero_coeff_parts(scale3[p], zero3[p], g16)).reshape(pairs, 32, g16, 3, 2, 8)
-                           for p in (0, 1)], axis=0)
-            # [tile, pairs, col, block, which, hf, i] -> [pairs, step = 3*block + which, tile, hf, col, i]
-            parts.append(np.ascontiguousarray(zc.transpose(1, 3, 4, 0, 5, 2, 6)).tobytes())
+            if not dense_bits:
+                zc = np.stack([_zc_part(*_zero_coeff_parts(scale3[p], zero3[p], g16)).reshape(pairs, 32, g16, 3, 2, 8)
+                               for p in (0, 1)], axis=0)
+                # [tile, pairs, col, block, which, hf, i] -> [pairs, step = 3*block + which, tile, hf, col, i]
+                parts.append(np.ascontiguousarray(zc.transpose(1, 3, 4, 0, 5, 2, 6)).tobytes())
             if r > 0:
                 b = np.stack([_pad_rows(B3[p], r16).reshape(r16 // 16, 2, 8, pairs, 32) for p in (0, 1)], axis=0)
                 # [tile, step, hf, i, pairs, col] -> [pairs, step, tile, hf, col, i]
@@ -100,15 +128,21 @@ def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r) -> bytes:
                 parts.append(np.ascontiguousarray(acat.transpose(3, 0, 1, 4, 2)).tobytes())
         else:
             K, pairs = F, H // 64
-            w = _words(codes3[2]).reshape(pairs, 2, 32, K // 64, 4, 2)
-            # [pairs, tile, col, chunk, word, hf] -> [pairs, chunk, tile, hf, col, word]
-            parts.append(np.ascontiguousarray(w.transpose(0, 3, 1, 5, 2, 4)).tobytes())
+            if dense_bits:
+                w = _dense_words(codes3[2], dense_bits).reshape(pairs, 2, 32, K // 64, dense_bits, 2)
+                # [pairs, tile, col, chunk, word, hf] -> [pairs, chunk, tile, word, hf, col]
+                parts.append(np.ascontiguousarray(w.transpose(0, 3, 1, 4, 5, 2)).tobytes())
+            else:
+                w = _words(codes3[2]).reshape(pairs, 2, 32, K // 64, 4, 2)
+                # [pairs, tile, col, chunk, word, hf] -> [pairs, chunk, tile, hf, col, word]
+                parts.append(np.ascontiguousarray(w.transpose(0, 3, 1, 5, 2, 4)).tobytes())
             sz = (scale3[2].astype(np.uint32) | (zero3[2].astype(np.uint32) << 16)).reshape(pairs, 2, 32, K // g)
             parts.append(np.ascontiguousarray(sz.transpose(0, 3, 1, 2)).tobytes())
             g16 = (K // g + 15) // 16
-            zc = _zc_part(*_zero_coeff_parts(scale3[2], zero3[2], g16)).reshape(pairs, 2, 32, g16, 3, 2, 8)
-            # [pairs, tile, col, block, which, hf, i] -> [pairs, step, tile, hf, col, i]
-            parts.append(np.ascontiguousarray(zc.transpose(0, 3, 4, 1, 5, 2, 6)).tobytes())
+            if not dense_bits:
+                zc = _zc_part(*_zero_coeff_parts(scale3[2], zero3[2], g16)).reshape(pairs, 2, 32, g16, 3, 2, 8)
+                # [pairs, tile, col, block, which, hf, i] -> [pairs, step, tile, hf, col, i]
+                parts.append(np.ascontiguousarray(zc.transpose(0, 3, 4, 1, 5, 2, 6)).tobytes())
             if r > 0:
                 b = _pad_rows(B3[2], r16).reshape(r16 // 16, 2, 8, pairs, 2, 32)
                 # [step, hf, i, pairs, tile, col] -> [pairs, step, tile, hf, col, i]
@@ -134,5 +168,6 @@ def pack_layer(layer) -> np.ndarray:
         zero3 = [layer.zero_matrix(e, p).view(np.uint16) for p in range(3)]
         A3 = [layer.a_matrix(e, p).view(np.uint16) for p in range(3)] if c.r else [None] * 3
         B3 = [layer.b_matrix(e, p).view(np.uint16) for p in range(3)] if c.r else [None] * 3
-        out.append(pack_expert(codes3, scale3, zero3, A3, B3, c.H, c.F, c.g, c.r))
+        out.append(pack_expert(codes3, scale3, zero3, A3, B3, c.H, c.F, c.g, c.r,
+                               dense_bits=c.bits if getattr(c, "dense", False) else 0))
     return np.frombuffer(b"".join(out), dtype=np.uint8)

@@ -16,6 +16,7 @@ from .build import library_path
 TQ_OK = 0
 TQ_ACT_BF16, TQ_ACT_FP32 = 0, 1
 TQ_FLAG_FORCE_SMALL_TILE, TQ_FLAG_FORCE_LARGE_TILE, TQ_FLAG_FORCE_SKINNY = 1, 2, 4
+TQ_FLAG_DENSE_CODES = 32
 TQ_LOTILE_FP8 = 1
 STATUS_NAMES = {0: "TQ_OK", 1: "TQ_ERR_NULL", 2: "TQ_ERR_SHAPE", 3: "TQ_ERR_ALIGN", 4: "TQ_ERR_RANGE",
                 5: "TQ_ERR_WORKSPACE", 6: "TQ_ERR_UNSUPPORTED", 7: "TQ_ERR_HIP", 8: "TQ_ERR_BLOB"}

@@ -204,6 +204,10 @@ tq_status forward_impl(const tq_layer_desc* desc, const void* packed, const void
     TqWorkspace W;
     tq_make_workspace(L, desc->act_dtype, T, &W);
     if (workspace_bytes < W.total) return TQ_ERR_WORKSPACE;      // static entry point: the batch needs more than the array holds
+    // dense 2- / 3-bit codes are read by the decode kernels and the fp32 debug path only
+    if (L.cw != 4 && desc->act_dtype == TQ_ACT_BF16 &&
+        !(W.a_tot <= TQ_SKINNY_MAX_ROWS && tqi_skinny_supported(L) && !(desc->flags & (TQ_FLAG_FORCE_SMALL_TILE | TQ_FLAG_FORCE_LARGE_TILE))))
+        return TQ_ERR_UNSUPPORTED;
     if (T == 0) return TQ_OK;
     const TqDeviceState* ds = nullptr;
     if (tqi_device_state(&ds) != TQ_OK) return TQ_ERR_HIP;

@@ -10,7 +10,7 @@
 #include "tileq.h"
 
 #define TQ_BLOB_MAGIC 0x31425154u /* "TQB1" */
-#define TQ_BLOB_VERSION 1u
+#define TQ_BLOB_VERSION 2u
 #define TQ_HEADER_BYTES 256
 #define TQ_STATIC_SCRATCH_BYTES TQ_STATIC_SCRATCH_MAX   /* size of the static scratch array (tileq.h) */
 
@@ -32,6 +32,7 @@ struct TqSection {
 
 struct TqLayout {
     int32_t E, S, k, H, F, g, bits, r, r16;
+    int32_t cw;      // 32-bit words of codes per (lane, 64-wide chunk, tile): 4 (4-bit slots), 3 or 2 (dense 3- / 2-bit)
     TqSection gu, d;
     size_t expert_stride;
     size_t total_bytes;
@@ -40,6 +41,7 @@ struct TqLayout {
 struct TqBlobHeader {
     uint32_t magic, version;
     int32_t n_experts, n_shared, hidden, ffn, group, bits, rank, r16;
+    int32_t code_words, reserved;       // TqLayout::cw
     uint64_t expert_stride, total_bytes;
     uint64_t off[10];  // gu.codes, gu.sz, gu.zc, gu.bfrag, gu.afrag, then the same five of d
 };
@@ -57,17 +59,20 @@ __host__ inline bool tq_make_layout(const tq_layer_desc* d, TqLayout* L)
     if (d->hidden > (1 << 16) || d->ffn > (1 << 17)) return false;
     if (!(d->group == 32 || d->group == 64 || d->group == 128 || d->group == 256)) return false;
     if (d->hidden % d->group || d->ffn % d->group) return false;
-    if (d->bits != 3 && d->bits != 4) return false;
+    const bool dense = (d->flags & TQ_FLAG_DENSE_CODES) != 0;
+    if (dense ? (d->bits != 2 && d->bits != 3) : (d->bits != 3 && d->bits != 4)) return false;
+    if (dense && d->group < 64) return false;       // dense codes: groups of 64 and more
     if (d->rank < 0 || d->rank > 256) return false;
     if (d->act_dtype != TQ_ACT_BF16 && d->act_dtype != TQ_ACT_FP32) return false;
     L->E = d->n_experts; L->S = d->n_shared; L->k = d->top_k; L->H = d->hidden; L->F = d->ffn;
     L->g = d->group; L->bits = d->bits; L->r = d->rank; L->r16 = (d->rank + 15) / 16 * 16;
+    L->cw = dense ? d->bits : 4;
     size_t off = 0;
     auto fill = [&](TqSection& s, int pairs, int K, int na) {
         s.pairs = pairs; s.K = K; s.chunks = K / 64; s.groups = K / L->g; s.na_tiles = (na + 31) / 32;
-        s.codes = off; off += (size_t)pairs * s.chunks * 2048;
+        s.codes = off; off += (size_t)pairs * s.chunks * 512 * L->cw;
         s.sz = off;    off += (size_t)pairs * s.groups * 256;
-        s.zsteps = 3 * ((s.groups + 15) / 16);
+        s.zsteps = dense ? 0 : 3 * ((s.groups + 15) / 16);     // only the MFMA prefill kernels read this part
         s.zc = off;    off += (size_t)pairs * s.zsteps * 2048;
         s.bfrag = off; off += (size_t)pairs * (L->r16 / 16) * 2048;
         s.afrag = off; off += (size_t)s.na_tiles * (K / 16) * 1024;

@@ -64,6 +64,29 @@ __device__ inline bf16x8 unpack_word(uint32_t w, uint32_t mask, uint32_t magic)
     return f.v;
 }
 
+// Dense 2- or 3-bit codes (CW = bits = words per lane and 64-wide chunk): the four bf16 pairs of k-step `w` (0..3) of
+// the chunk held in d[0..CW-1].  Slot P = 4 w + j holds two codes 16 bit positions apart; mask = 0x00030003 or
+// 0x00070007.  `w` is a constant at every call site (unrolled loops), so the word and shift of each slot fold.
+template <int CW>
+__device__ inline bf16x8 unpack_dense(const uint32_t* d, int w, uint32_t mask, uint32_t magic)
+{
+    Frag f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int P = 4 * w + j;
+        if (CW == 2) {
+            const int p = 2 * (P % 8);
+            f.u[j] = ((p ? d[P / 8] >> p : d[P / 8]) & mask) | magic;
+        } else if (P < 15) {
+            const int p = 3 * (P % 5);
+            f.u[j] = ((p ? d[P / 5] >> p : d[P / 5]) & mask) | magic;
+        } else {        // the last slot of a 3-bit chunk is spread over the spare bits 15 and 31 of the three words
+            f.u[j] = ((d[0] >> 15) & 0x00010001u) | ((d[1 % CW] >> 14) & 0x00020002u) | ((d[2 % CW] >> 13) & 0x00040004u) | magic;
+        }
+    }
+    return f.v;
+}
+
 __device__ inline bf16x8 half8_to_bf8(u32x4 q)
 {
     Frag f;

@@ -7,11 +7,22 @@
 namespace {
 
 struct F32Geom {
-    int32_t ne, H, F, g, r, r16, k, S;
+    int32_t ne, H, F, g, r, r16, k, S, cw;
     size_t expert_stride;
 };
 
 __device__ inline float silu_f32(float v) { return v / (1.0f + expf(-v)); }
+
+// code i (0..7) of k-step w (0..3) of a chunk whose words are d[0..cw-1]: 4-bit slots (cw = 4) or dense 3- / 2-bit
+// codes, as the layout text of the public header states them
+__device__ inline uint32_t code_of_chunk(const uint32_t* d, int cw, int w, int i)
+{
+    if (cw == 4) return (d[w] >> (4 * tq_nibble_pos(i))) & 15u;
+    const int P = 4 * w + (i >> 1), half = 16 * (i & 1);
+    if (cw == 2) return (d[P / 8] >> (2 * (P % 8) + half)) & 3u;
+    if (P < 15) return (d[P / 5] >> (3 * (P % 5) + half)) & 7u;
+    return ((d[0] >> (15 + half)) & 1u) | (((d[1] >> (15 + half)) & 1u) << 1) | (((d[2] >> (15 + half)) & 1u) << 2);
+}
 
 // STAGE 0: gate/up + SwiGLU (input x gathered by token, output h32[slot][F])
 // STAGE 1: down (input h32[slot][F], output yd[slot][H])
@@ -59,13 +70,21 @@ __global__ void __launch_bounds__(256) f32_proj_kernel(F32Geom G, TqSection sec,
     float res[2];
 #pragma unroll
     for (int tile = 0; tile < 2; ++tile) {
-        const uint4* cw = reinterpret_cast<const uint4*>(rec + sec.codes) + ((size_t)pair * sec.chunks * 2 + tile) * 64 + lane;
+        const uint32_t* cwp = reinterpret_cast<const uint32_t*>(rec + sec.codes);
         const uint32_t* szp = reinterpret_cast<const uint32_t*>(rec + sec.sz) + ((size_t)pair * sec.groups * 2 + tile) * 32 + col;
         float acc = 0.f, part = 0.f, s = 0.f, z = 0.f;
         int cur = -1;
         for (int c = 0; c < sec.chunks; ++c) {
-            uint4 v = cw[(size_t)c * 128];
-            uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+            uint32_t wd[4] = {0, 0, 0, 0};
+            {
+                const size_t blk = ((size_t)pair * sec.chunks + c) * 2 + tile;      // (pair, chunk, tile)
+                if (G.cw == 4) {
+                    const uint4 v = reinterpret_cast<const uint4*>(cwp)[blk * 64 + lane];
+                    wd[0] = v.x; wd[1] = v.y; wd[2] = v.z; wd[3] = v.w;
+                } else {
+                    for (int d = 0; d < G.cw; ++d) wd[d] = cwp[(blk * G.cw + d) * 64 + lane];
+                }
+            }
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
                 int gi = (64 * c + 16 * w) / G.g;
@@ -80,7 +99,7 @@ __global__ void __launch_bounds__(256) f32_proj_kernel(F32Geom G, TqSection sec,
                 const int kk0 = 64 * c + 16 * w + 8 * hf;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    float q = (float)((wd[w] >> (4 * tq_nibble_pos(i))) & 15u);
+                    float q = (float)code_of_chunk(wd, G.cw, w, i);
                     part = fmaf(xs[kk0 + i], q - z, part);
                 }
             }
@@ -140,7 +159,7 @@ tq_status tqi_forward_f32(const TqLayout& L, const TqWorkspace& W, const uint8_t
 {
     F32Geom G;
     G.ne = L.E + L.S; G.H = L.H; G.F = L.F; G.g = L.g; G.r = L.r; G.r16 = L.r16; G.k = L.k; G.S = L.S;
-    G.expert_stride = L.expert_stride;
+    G.expert_stride = L.expert_stride; G.cw = L.cw;
     const int32_t* ctrl = reinterpret_cast<const int32_t*>(ws + W.ctrl);
     const int32_t* offsets = reinterpret_cast<const int32_t*>(ws + W.offsets);
     const int32_t* slot_of = reinterpret_cast<const int32_t*>(ws + W.slot_of);

@@ -811,7 +811,7 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
 
     // decode batches (a handful of rows per expert): the weight-streaming 16-row path, no pre-pass over K
     bool skinny = !large && avg_rows <= 12 && !(flags & TQ_FLAG_FORCE_SMALL_TILE);
-    if (flags & TQ_FLAG_FORCE_SKINNY) skinny = true;
+    if ((flags & TQ_FLAG_FORCE_SKINNY) || L.cw != 4) skinny = true;      // dense codes: decode kernels only (checked by the caller)
     if (skinny && W.a_tot <= TQ_SKINNY_MAX_ROWS && tqi_skinny_supported(L)) {
         int nsplit_sk = 1;
         tq_status rs = tqi_forward_skinny(L, W, blob, x, T, ws, stream, &nsplit_sk);

@@ -5,7 +5,7 @@
 namespace {
 
 struct PackGeom {
-    int32_t n_exp, H, F, g, r, r16, qmax;
+    int32_t n_exp, H, F, g, r, r16, qmax, cw;
     TqSection gu, d;
     size_t expert_stride;
 };
@@ -65,6 +65,93 @@ __global__ void codes_kernel(PackGeom G, uint8_t* __restrict__ blob, uint8_t* __
 #pragma unroll
         for (int i = 0; i < 8; ++i) v |= (uint64_t)((in >> (4 * tq_nibble_pos(i))) & 15u) << (8 * i);
         *reinterpret_cast<uint64_t*>(src) = v;
+    }
+}
+
+// Dense codes (2 or 3 bits): one thread per (pair, chunk, tile, lane); it moves the lane's 32 codes between the
+// canonical bytes and its CW words, which sit CW x 64 lanes apart ([cw][64 lanes] inside the tile's block).
+template <bool PACK, int CW>
+__global__ void dense_codes_kernel(PackGeom G, uint8_t* __restrict__ blob, uint8_t* __restrict__ codes,
+                                   int32_t* __restrict__ err_flag)
+{
+    const size_t lanes_gu = (size_t)G.gu.pairs * G.gu.chunks * 128;   // 2 tiles * 64 lanes
+    const size_t lanes_d = (size_t)G.d.pairs * G.d.chunks * 128;
+    const size_t per_exp = lanes_gu + lanes_d;
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= per_exp * G.n_exp) return;
+    int e = (int)(idx / per_exp);
+    size_t w = idx % per_exp;
+    const bool is_d = w >= lanes_gu;
+    const TqSection& sec = is_d ? G.d : G.gu;
+    if (is_d) w -= lanes_gu;
+    int lane = (int)(w & 63);
+    int tile = (int)((w >> 6) & 1);
+    size_t pc = w >> 7;
+    int chunk = (int)(pc % sec.chunks);
+    int pair = (int)(pc / sec.chunks);
+    int col = lane & 31, hf = lane >> 5;
+    int p, n, K = sec.K;
+    if (!is_d) { p = tile; n = 32 * pair + col; }
+    else       { p = 2;    n = 64 * pair + 32 * tile + col; }
+    const size_t HF = (size_t)G.H * G.F;
+    uint8_t* src = codes + ((size_t)e * 3 + p) * HF + (size_t)n * K + 64 * chunk + 8 * hf;      // + 16 w + i
+    uint32_t* dst = reinterpret_cast<uint32_t*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.codes) +
+                    (pc * 2 + tile) * (size_t)(CW * 64) + lane;                                  // + 64 d
+    constexpr uint32_t FM = (1u << CW) - 1;       // CW is also the number of bits per code
+    uint32_t word[CW];
+    if (PACK) {
+#pragma unroll
+        for (int d = 0; d < CW; ++d) word[d] = 0;
+        bool bad = false;
+#pragma unroll
+        for (int ws = 0; ws < 4; ++ws) {
+            const uint64_t v = *reinterpret_cast<const uint64_t*>(src + 16 * ws);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t lo = (uint32_t)(v >> (16 * j)) & 0xFF, hi = (uint32_t)(v >> (16 * j + 8)) & 0xFF;
+                bad |= lo > FM || hi > FM;
+                const int P = 4 * ws + j;
+                if (CW == 2) {
+                    word[P / 8] |= ((lo & FM) | ((hi & FM) << 16)) << (2 * (P % 8));
+                } else if (P < 15) {
+                    word[P / 5] |= ((lo & FM) | ((hi & FM) << 16)) << (3 * (P % 5));
+                } else {
+#pragma unroll
+                    for (int b = 0; b < 3; ++b) word[b % CW] |= (((lo >> b) & 1u) << 15) | (((hi >> b) & 1u) << 31);
+                }
+            }
+        }
+#pragma unroll
+        for (int d = 0; d < CW; ++d) dst[64 * d] = word[d];
+        if (bad && err_flag) atomicOr(err_flag, TQ_FLAG_BIT_RANGE);
+    } else {
+#pragma unroll
+        for (int d = 0; d < CW; ++d) word[d] = dst[64 * d];
+#pragma unroll
+        for (int ws = 0; ws < 4; ++ws) {
+            uint64_t v = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int P = 4 * ws + j;
+                uint32_t lo, hi;
+                if (CW == 2) {
+                    const uint32_t t = word[P / 8] >> (2 * (P % 8));
+                    lo = t & FM; hi = (t >> 16) & FM;
+                } else if (P < 15) {
+                    const uint32_t t = word[P / 5] >> (3 * (P % 5));
+                    lo = t & FM; hi = (t >> 16) & FM;
+                } else {
+                    lo = hi = 0;
+#pragma unroll
+                    for (int b = 0; b < 3; ++b) {
+                        lo |= ((word[b % CW] >> 15) & 1u) << b;
+                        hi |= ((word[b % CW] >> 31) & 1u) << b;
+                    }
+                }
+                v |= (uint64_t)lo << (16 * j) | (uint64_t)hi << (16 * j + 8);
+            }
+            *reinterpret_cast<uint64_t*>(src + 16 * ws) = v;
+        }
     }
 }
 
@@ -230,6 +317,7 @@ inline PackGeom make_geom(const TqLayout& L)
     PackGeom G;
     G.n_exp = L.E + L.S; G.H = L.H; G.F = L.F; G.g = L.g; G.r = L.r; G.r16 = L.r16;
     G.qmax = (1 << L.bits) - 1;
+    G.cw = L.cw;
     G.gu = L.gu; G.d = L.d; G.expert_stride = L.expert_stride;
     return G;
 }
@@ -245,11 +333,16 @@ tq_status run(const TqLayout& L, uint8_t* blob, uint8_t* codes, uint16_t* scale,
     size_t n_codes = ((size_t)L.gu.pairs * L.gu.chunks + (size_t)L.d.pairs * L.d.chunks) * 512 * ne;
     size_t n_sz = ((size_t)L.gu.pairs * L.gu.groups + (size_t)L.d.pairs * L.d.groups) * 64 * ne;
     if (n_codes / 256 > 0x7FFFFFFFull) return TQ_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(codes_kernel<PACK>, dim3(blocks_for(n_codes)), dim3(256), 0, st, G, blob, codes, err_flag);
+    if (L.cw == 4)
+        hipLaunchKernelGGL(codes_kernel<PACK>, dim3(blocks_for(n_codes)), dim3(256), 0, st, G, blob, codes, err_flag);
+    else if (L.cw == 3)
+        hipLaunchKernelGGL((dense_codes_kernel<PACK, 3>), dim3(blocks_for(n_codes / 4)), dim3(256), 0, st, G, blob, codes, err_flag);
+    else
+        hipLaunchKernelGGL((dense_codes_kernel<PACK, 2>), dim3(blocks_for(n_codes / 4)), dim3(256), 0, st, G, blob, codes, err_flag);
     TQ_CHECK_LAUNCH();
     hipLaunchKernelGGL(sz_kernel<PACK>, dim3(blocks_for(n_sz)), dim3(256), 0, st, G, blob, scale, zero);
     TQ_CHECK_LAUNCH();
-    if (PACK) {
+    if (PACK && L.cw == 4) {
         size_t n_zc = ((size_t)L.gu.pairs * L.gu.zsteps + (size_t)L.d.pairs * L.d.zsteps) * 128 * ne;
         hipLaunchKernelGGL(zc_kernel, dim3(blocks_for(n_zc)), dim3(256), 0, st, G, blob, scale, zero);
         TQ_CHECK_LAUNCH();
@@ -292,7 +385,7 @@ extern "C" tq_status tq_pack_weights(const tq_layer_desc* desc, const tq_weights
     TqBlobHeader hdr = {};
     hdr.magic = TQ_BLOB_MAGIC; hdr.version = TQ_BLOB_VERSION;
     hdr.n_experts = L.E; hdr.n_shared = L.S; hdr.hidden = L.H; hdr.ffn = L.F; hdr.group = L.g;
-    hdr.bits = L.bits; hdr.rank = L.r; hdr.r16 = L.r16;
+    hdr.bits = L.bits; hdr.rank = L.r; hdr.r16 = L.r16; hdr.code_words = L.cw;
     hdr.expert_stride = L.expert_stride; hdr.total_bytes = L.total_bytes;
     hdr.off[0] = L.gu.codes; hdr.off[1] = L.gu.sz; hdr.off[2] = L.gu.zc; hdr.off[3] = L.gu.bfrag; hdr.off[4] = L.gu.afrag;
     hdr.off[5] = L.d.codes; hdr.off[6] = L.d.sz; hdr.off[7] = L.d.zc; hdr.off[8] = L.d.bfrag; hdr.off[9] = L.d.afrag;

@@ -104,6 +104,7 @@ __device__ inline bool blob_header_ok(const TqBlobHeader* hdr, const TqBlobHeade
     return hdr->magic == expect.magic && hdr->version == expect.version && hdr->n_experts == expect.n_experts &&
            hdr->n_shared == expect.n_shared && hdr->hidden == expect.hidden && hdr->ffn == expect.ffn &&
            hdr->group == expect.group && hdr->bits == expect.bits && hdr->rank == expect.rank &&
+           hdr->code_words == expect.code_words &&
            hdr->expert_stride == expect.expert_stride;
 }
 
@@ -424,6 +425,7 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
         expect.magic = TQ_BLOB_MAGIC; expect.version = TQ_BLOB_VERSION;
         expect.n_experts = L->E; expect.n_shared = L->S; expect.hidden = L->H; expect.ffn = L->F;
         expect.group = L->g; expect.bits = L->bits; expect.rank = L->r; expect.expert_stride = L->expert_stride;
+        expect.code_words = L->cw;
     }
     const int ne = E + S;
     if (nblk == 1 && (int64_t)S * T <= 4096) {

@@ -75,7 +75,8 @@ __global__ void __launch_bounds__(64) skinny_pre_kernel(MGeom G, TqSection sec, 
 }
 
 // STAGE 0: out = h[slot][F] bf16 = silu(gate) * up.   STAGE 1: out = yd[split][slot][H] fp32.
-template <int STAGE, int GS>
+// CW: 32-bit words of codes per lane, tile and 64-wide chunk: 4 (4-bit slots), 3 or 2 (dense 3- / 2-bit codes).
+template <int STAGE, int GS, int CW>
 __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
                                                          const uint16_t* __restrict__ xin,
                                                          const int32_t* __restrict__ row_token,
@@ -92,6 +93,8 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     constexpr int US = UNIT_K / 16;
     constexpr int NG = US / GS;
     constexpr int UPW = SK_WAVE_K / UNIT_K;   // units per wave
+    using WT = std::conditional_t<CW == 4, u32x4, uint32_t>;      // register type of the packed codes
+    constexpr int WN = CW == 4 ? UC : UC * CW;                    // and how many of them one tile of a unit takes
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     float* red = reinterpret_cast<float*>(lds + red_off);
@@ -131,13 +134,22 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     // Unit and pair indices are clamped into the valid range instead of guarding the loads: a load under a
     // condition makes the compiler wait for ALL outstanding loads at every later use, which would drain the
     // one-pair-ahead prefetch at every unit.  Clamped loads repeat a neighbour's line (cache hit) and are unused.
-    auto load_w = [&](u32x4 (&dst)[2][UC], int pair, int u) {       // unit u of this wave, both tiles
+    const uint32_t* codes32 = reinterpret_cast<const uint32_t*>(rec + sec.codes) + lane;      // dense layouts
+    auto load_w = [&](WT (&dst)[2][WN], int pair, int u) {       // unit u of this wave, both tiles
         const int chunk0 = min(ub + wave * UPW + u, ue - 1) * UC;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int c = 0; c < UC; ++c)      // read once, never again: the non-temporal hint keeps the stream out of the caches
-                dst[t][c] = __builtin_nontemporal_load(&codes[(((size_t)pair * sec.chunks + chunk0 + c) * 2 + t) * 64]);
+            for (int c = 0; c < UC; ++c) {    // read once, never again: the non-temporal hint keeps the stream out of the caches
+                if constexpr (CW == 4) {
+                    dst[t][c] = __builtin_nontemporal_load(&codes[(((size_t)pair * sec.chunks + chunk0 + c) * 2 + t) * 64]);
+                } else {
+#pragma unroll
+                    for (int d = 0; d < CW; ++d)
+                        dst[t][c * CW + d] = __builtin_nontemporal_load(
+                            &codes32[((((size_t)pair * sec.chunks + chunk0 + c) * 2 + t) * CW + d) * 64]);
+                }
+            }
     };
     auto load_sz = [&](uint32_t (&dst)[NG][2], int pair, int u) {
         const int g0 = min(ub + wave * UPW + u, ue - 1) * NG;
@@ -210,7 +222,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
             for (int sl = 0; sl < 16; ++sl) tsum[ta] += sl < nsl ? tv[ta][sl] : 0.f;
     }
     // the first pair's codes: their latency hides behind the rest of the set-up (group sums, t fragments)
-    u32x4 wq[UPW][2][UC];
+    WT wq[UPW][2][WN];
     uint32_t szq[UPW][NG][2];
 #pragma unroll
     for (int u = 0; u < UPW; ++u) { load_w(wq[u], p0, u); load_sz(szq[u], p0, u); }
@@ -220,7 +232,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     const int lr_t = (STAGE == 0 && wave >= steps_per_tile) ? 1 : 0;
     const int lr_step = (G.r > 0) ? min(wave - lr_t * steps_per_tile, steps_per_tile - 1) : 0;
     const u32x4* bsrc = (G.r > 0) ? bfr : codes;
-    const size_t bstride = (G.r > 0) ? (size_t)steps_per_tile * 128 : (size_t)sec.chunks * 128;
+    const size_t bstride = (G.r > 0) ? (size_t)steps_per_tile * 128 : (size_t)0;      // dummy reads stay in the first 2 KB of the codes
     auto load_b = [&](u32x4 (&dst)[2], int pair) {
         if (STAGE == 0) {
             dst[0] = bsrc[(size_t)pair * bstride + ((size_t)lr_step * 2 + lr_t) * 64];
@@ -299,12 +311,12 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
             for (int v = 0; v < 8; ++v) acc8[t][v] = 0.f;
 #pragma unroll
         for (int u = 0; u < UPW; ++u) {
-            u32x4 wc[2][UC];
+            WT wc[2][WN];
             uint32_t szc[NG][2];
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int c = 0; c < UC; ++c) wc[t][c] = wq[u][t][c];
+                for (int c = 0; c < WN; ++c) wc[t][c] = wq[u][t][c];
 #pragma unroll
             for (int gi = 0; gi < NG; ++gi)
 #pragma unroll
@@ -324,7 +336,9 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
                         const bf16x8 xa = xq[kidx & 1];
 #pragma unroll
                         for (int t = 0; t < 2; ++t) {
-                            const bf16x8 bw = unpack_word(word_of(wc[t][kidx / 4], kidx % 4), G.unpack_mask, magic_v);
+                            bf16x8 bw;
+                            if constexpr (CW == 4) bw = unpack_word(word_of(wc[t][kidx / 4], kidx % 4), G.unpack_mask, magic_v);
+                            else bw = unpack_dense<CW>(&wc[t][(kidx / 4) * CW], kidx % 4, G.unpack_mask, magic_v);
                             if (ks == 0) {
                                 f32x16 zero;
 #pragma unroll
@@ -428,7 +442,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     }
 }
 
-template <int STAGE, int GS>
+template <int STAGE, int GS, int CW>
 tq_status launch_skinny(const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin,
                         const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
                         const int32_t* offsets, const int32_t* ctrl, float* tpart, int n_slices, int na_tiles,
@@ -443,7 +457,7 @@ tq_status launch_skinny(const MGeom& G, const TqSection& sec, const uint8_t* blo
     const int mb_off = xs_off + (range_k / G.g) * 16 * 4;      // mailbox of the pair scheduler
     const size_t smem = (size_t)mb_off + 16;
     if (smem > 160 * 1024) return TQ_ERR_UNSUPPORTED;
-    auto kern = moe_skinny_kernel<STAGE, GS>;      // dynamic-LDS limit: raised once per device by tqi_setup_skinny
+    auto kern = moe_skinny_kernel<STAGE, GS, CW>;      // dynamic-LDS limit: raised once per device by tqi_setup_skinny
     // one workgroup per compute unit over the tiles that are expected to exist: a workgroup fills a CU (LDS),
     // and fewer, longer workgroups amortise the set-up (activation staging, group sums) over more pairs
     const TqDeviceState* ds = nullptr;
@@ -462,18 +476,30 @@ tq_status launch_skinny(const MGeom& G, const TqSection& sec, const uint8_t* blo
 }
 
 template <int STAGE>
-tq_status launch_skinny_gs(int gs, const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin,
+tq_status launch_skinny_gs(int gs, int cw, const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin,
                            const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
                            const int32_t* offsets, const int32_t* ctrl, float* tpart, int n_slices, int na_tiles,
                            void* out, int32_t* pair_cnt, int row_tiles, int nsplit, int units_per_split, int tiles_est,
                            hipStream_t st)
 {
-    switch (gs) {
-        case 2: return launch_skinny<STAGE, 2>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, pair_cnt, row_tiles, nsplit, units_per_split, tiles_est, st);
-        case 4: return launch_skinny<STAGE, 4>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, pair_cnt, row_tiles, nsplit, units_per_split, tiles_est, st);
-        case 8: return launch_skinny<STAGE, 8>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, pair_cnt, row_tiles, nsplit, units_per_split, tiles_est, st);
-        case 16: return launch_skinny<STAGE, 16>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, pair_cnt, row_tiles, nsplit, units_per_split, tiles_est, st);
+#define TQ_SK(GSV, CWV)                                                                                                   \
+    return launch_skinny<STAGE, GSV, CWV>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, \
+                                          na_tiles, out, pair_cnt, row_tiles, nsplit, units_per_split, tiles_est, st)
+    if (cw == 4) {
+        switch (gs) {
+            case 2: TQ_SK(2, 4);
+            case 4: TQ_SK(4, 4);
+            case 8: TQ_SK(8, 4);
+            case 16: TQ_SK(16, 4);
+        }
+    } else if (cw == 3) {      // dense codes: groups of 64 and 128
+        if (gs == 4) TQ_SK(4, 3);
+        if (gs == 8) TQ_SK(8, 3);
+    } else if (cw == 2) {
+        if (gs == 4) TQ_SK(4, 2);
+        if (gs == 8) TQ_SK(8, 2);
     }
+#undef TQ_SK
     return TQ_ERR_UNSUPPORTED;
 }
 
@@ -496,9 +522,11 @@ inline void plan_split(int K, int g, int* nsplit, int* units_per_split)
 tq_status tqi_setup_skinny()
 {
     bool ok = true;
-#define TQ_ONE(ST, GS) ok = ok && hipFuncSetAttribute((const void*)moe_skinny_kernel<ST, GS>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) == hipSuccess
-    TQ_ONE(0, 2); TQ_ONE(0, 4); TQ_ONE(0, 8); TQ_ONE(0, 16);
-    TQ_ONE(1, 2); TQ_ONE(1, 4); TQ_ONE(1, 8); TQ_ONE(1, 16);
+#define TQ_ONE(ST, GS, CW) ok = ok && hipFuncSetAttribute((const void*)moe_skinny_kernel<ST, GS, CW>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) == hipSuccess
+    TQ_ONE(0, 2, 4); TQ_ONE(0, 4, 4); TQ_ONE(0, 8, 4); TQ_ONE(0, 16, 4);
+    TQ_ONE(1, 2, 4); TQ_ONE(1, 4, 4); TQ_ONE(1, 8, 4); TQ_ONE(1, 16, 4);
+    TQ_ONE(0, 4, 3); TQ_ONE(0, 8, 3); TQ_ONE(1, 4, 3); TQ_ONE(1, 8, 3);
+    TQ_ONE(0, 4, 2); TQ_ONE(0, 8, 2); TQ_ONE(1, 4, 2); TQ_ONE(1, 8, 2);
 #undef TQ_ONE
     return ok ? TQ_OK : TQ_ERR_HIP;
 }
@@ -507,6 +535,7 @@ tq_status tqi_setup_skinny()
 bool tqi_skinny_supported(const TqLayout& L)
 {
     if (L.r16 > 64) return false;
+    if (L.cw != 4 && L.g != 64 && L.g != 128) return false;
     int ns, ups;
     plan_split(L.H, L.g, &ns, &ups);
     if (ns != 1) return false;
@@ -527,7 +556,8 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     MGeom G;
     G.ne = L.E + L.S; G.H = L.H; G.F = L.F; G.g = L.g; G.r = L.r; G.r16 = L.r16; G.k = L.k; G.S = L.S;
     G.a_tot = W.a_tot; G.expert_stride = L.expert_stride;
-    G.unpack_mask = 0x000F000Fu; G.unpack_magic = 0x43004300u;
+    G.unpack_mask = L.cw == 4 ? 0x000F000Fu : L.cw == 3 ? 0x00070007u : 0x00030003u;
+    G.unpack_magic = 0x43004300u;
     const int32_t* ctrl = reinterpret_cast<const int32_t*>(ws + W.ctrl);
     const int32_t* offsets = reinterpret_cast<const int32_t*>(ws + W.offsets);
     const int32_t* row_token = reinterpret_cast<const int32_t*>(ws + W.row_token);
@@ -553,7 +583,7 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     tqi_record_stage(2, stream);
     int32_t* pair_cnt = reinterpret_cast<int32_t*>(ws + W.sk_cnt);
     if (W.sk_cnt_n < 2 * W.rt_max * TQ_MAX_SPLIT) return TQ_ERR_UNSUPPORTED;
-    tq_status rc = launch_skinny_gs<0>(gs, G, L.gu, blob, x, row_token, tile_e, tile_row0, offsets, ctrl, tpart, sl_gu, nat_gu,
+    tq_status rc = launch_skinny_gs<0>(gs, L.cw, G, L.gu, blob, x, row_token, tile_e, tile_row0, offsets, ctrl, tpart, sl_gu, nat_gu,
                                        h, pair_cnt, rt16, 1, ups, tiles_est, stream);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(3, stream);
@@ -564,7 +594,7 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     }
     tqi_record_stage(4, stream);
     plan_split(L.F, L.g, &ns, &ups);
-    rc = launch_skinny_gs<1>(gs, G, L.d, blob, h, row_token, tile_e, tile_row0, offsets, ctrl, tpart, sl_d, nat_d, yd,
+    rc = launch_skinny_gs<1>(gs, L.cw, G, L.d, blob, h, row_token, tile_e, tile_row0, offsets, ctrl, tpart, sl_d, nat_d, yd,
                              pair_cnt + (size_t)W.rt_max * TQ_MAX_SPLIT, rt16, ns, ups, tiles_est, stream);
     if (rc != TQ_OK) return rc;
     *nsplit_out = ns;

@@ -42,11 +42,12 @@ class LayerConfig:
     T: int          # tokens
     g: int          # quantisation group size along the contraction dim
     r: int          # rank of the low-rank factors
-    bits: int       # 4, or 3 (codes 0..7 stored in 4-bit slots)
+    bits: int       # 4, or 3 (codes 0..7 stored in 4-bit slots); with dense: 3 or 2, stored densely
     outlier_frac: float = 0.0   # fraction of input channels drawn heavy-tailed (Student-t, df=3)
     zipf_s: float = 0.0         # expert bias -s*ln(rank) added to the router logits
     w_std: float = 0.02
     f_std: float = 0.01
+    dense: bool = False         # codes stored at `bits` bits each (the packed format's dense layouts)
 
     @property
     def qmax(self) -> int:

@@ -14,6 +14,8 @@ def dev16(a: np.ndarray) -> torch.Tensor:
 
 
 def desc_of(cfg, act=tq.TQ_ACT_BF16, flags=0):
+    if getattr(cfg, "dense", False):
+        flags |= tq.TQ_FLAG_DENSE_CODES
     return tq.make_desc(cfg.E, cfg.S, cfg.k, cfg.H, cfg.F, cfg.g, cfg.bits, cfg.r, act, flags)
 
 

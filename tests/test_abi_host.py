@@ -46,6 +46,25 @@ def test_packed_size_closed_form(E, S, H, F, g, r):
                 assert abs(bits - float(val)) < 5e-7
 
 
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("E,S,H,F,g,r", [(8, 0, 4096, 14336, 128, 32), (60, 0, 2048, 1408, 64, 64)])
+def test_packed_size_of_dense_codes_is_the_papers_count(bits, E, S, H, F, g, r):
+    """Appendix A.3 with d = 2 or 3: d + 2 * 16 / g (scale and zero) + 16 r (1/i + 1/o) bits per weight, nothing else."""
+    n = tq.tq_packed_size(tq.make_desc(E, S, 2, H, F, g, bits, r, flags=tq.TQ_FLAG_DENSE_CODES))
+    bpw = 8.0 * (n - 256) / (3 * H * F * (E + S))
+    assert abs(bpw - (bits + 32 / g + 16 * r * (1 / H + 1 / F))) < 1e-9
+
+
+def test_dense_descriptor_limits():
+    D = tq.TQ_FLAG_DENSE_CODES
+    assert tq.tq_packed_size(tq.make_desc(4, 0, 2, 128, 128, 64, 4, 8, flags=D)) == 0       # 4 bits are not dense
+    assert tq.tq_packed_size(tq.make_desc(4, 0, 2, 128, 128, 32, 3, 8, flags=D)) == 0       # groups of 64 and more
+    assert tq.tq_packed_size(tq.make_desc(4, 0, 2, 128, 128, 64, 2, 8)) == 0                # 2 bits only densely
+    a = tq.tq_packed_size(tq.make_desc(4, 0, 2, 128, 128, 64, 3, 8, flags=D))
+    b = tq.tq_packed_size(tq.make_desc(4, 0, 2, 128, 128, 64, 3, 8))
+    assert 0 < a < b
+
+
 def test_packed_size_rank_padding_and_zero_rank():
     base = tq.tq_packed_size(tq.make_desc(4, 0, 2, 256, 512, 64, 4, 0))
     derived = 4 * 2 * (2 * 512 * 48 + 256 * 48)       # H/g = 4 and F/g = 8 groups: one block of 16 each

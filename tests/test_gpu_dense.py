@@ -1,0 +1,152 @@
+"""Dense 2- and 3-bit codes (TQ_FLAG_DENSE_CODES: the bit-widths of Table 1, Appendix A.3 with d = 2 or 3): the
+packed blob byte for byte against oracle/pack_ref.py, unpack as its exact inverse, and the forward on the decode
+kernels (bf16) and the fp32 debug path against the oracle, same bars as the 4-bit layouts."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import pack_ref
+from synth import CONFIGS, LayerConfig, make_layer, make_x, make_logits
+import paper_2605_09281_amd.binding as tq
+from gpu_util import DEV, dev16, desc_of, pack_layer_gpu, x_device, rel_err
+import variants
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+REG_BF16 = 4 * 2.0 ** -9
+REG_LR_BF16 = 7 * 2.0 ** -9
+TOL_FP32 = 1e-5
+
+
+def dcfg(cfg_id, **kw):
+    base = dict(name="dn", E=4, S=0, k=2, H=128, F=192, T=9, g=64, r=8, bits=3, dense=True)
+    base.update(kw)
+    return LayerConfig(cfg_id, **base)
+
+
+CASES = {
+    "d3_g64": dcfg(801),
+    "d2_g64": dcfg(802, bits=2),
+    "d3_g128_r32_shared": dcfg(803, H=256, F=384, g=128, r=32, E=6, S=1, k=3, T=13),
+    "d2_g128_rank0": dcfg(804, bits=2, H=256, F=256, g=128, r=0, T=5),
+    "d3_min_dims": dcfg(805, H=64, F=64, r=4, T=3),
+    "d3_many_tiles": dcfg(806, E=3, k=2, T=60),           # 40 rows per expert: several 16-row tiles each
+}
+_layers = {}
+
+
+def get(name):
+    if name not in _layers:
+        cfg = CASES[name]
+        _layers[name] = (make_layer(cfg, workers=8), make_x(cfg), make_logits(cfg))
+    return _layers[name]
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_dense_pack_is_byte_exact_and_unpack_inverts(name):
+    layer, _, _ = get(name)
+    cfg = layer.cfg
+    packed = pack_layer_gpu(layer)
+    desc = desc_of(cfg)
+    ref = pack_ref.pack_layer(layer)
+    body = packed.cpu().numpy()[256:]
+    assert body.size == ref.size == tq.tq_packed_size(desc) - 256
+    assert np.array_equal(body, ref)
+    codes = torch.full(layer.codes.shape, 255, dtype=torch.uint8, device=DEV)
+    scale = torch.zeros(layer.scale.shape, dtype=torch.int16, device=DEV)
+    zero = torch.zeros_like(scale)
+    A = torch.zeros(layer.A.shape, dtype=torch.int16, device=DEV) if cfg.r else None
+    B = torch.zeros(layer.B.shape, dtype=torch.int16, device=DEV) if cfg.r else None
+    tq.tq_unpack_weights(desc, packed, codes, scale, zero, A, B)
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy(), layer.codes)
+    assert np.array_equal(scale.cpu().numpy().view(np.uint16), layer.scale)
+    assert np.array_equal(zero.cpu().numpy().view(np.uint16), layer.zero)
+
+
+def test_dense_every_position_sees_every_code_and_range_flag():
+    for bits in (2, 3):
+        cfg = dcfg(810 + bits, bits=bits, E=1, k=1, H=64, F=64, r=0)
+        layer = make_layer(cfg, workers=1)
+        import dataclasses
+        n = layer.codes.size
+        codes = ((np.arange(n) * 5 + np.arange(n) // 64 + np.arange(n) // 4096) % (1 << bits)).astype(np.uint8).reshape(layer.codes.shape)
+        l2 = dataclasses.replace(layer, codes=codes)
+        packed = pack_layer_gpu(l2)
+        assert np.array_equal(packed.cpu().numpy()[256:], pack_ref.pack_layer(l2))
+        bad = codes.copy()
+        bad.reshape(-1)[1234] = 1 << bits
+        err = torch.zeros(1, dtype=torch.int32, device=DEV)
+        tq.tq_pack_weights(desc_of(cfg), torch.from_numpy(bad).to(DEV), dev16(layer.scale), dev16(layer.zero), err_flag=err)
+        torch.cuda.synchronize()
+        assert int(err.item()) & 1
+
+
+def forward(layer, x, logits, bias, act, flags=0):
+    cfg = layer.cfg
+    packed = pack_layer_gpu(layer, act)
+    idx, w = tq.tq_route(torch.from_numpy(logits).to(DEV), None if bias is None else torch.from_numpy(bias).to(DEV), cfg.k)
+    desc = desc_of(cfg, act, flags)
+    ws = torch.empty(tq.tq_moe_workspace_size(desc, x.shape[0]), dtype=torch.uint8, device=DEV)
+    y = tq.tq_moe_forward(desc, packed, x_device(x, act), idx, w, workspace=ws)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32).item()) == 0
+    ref = oracle.moe_forward_layer(layer, x, idx.cpu().numpy(), w.cpu().numpy())
+    return y.float().cpu().numpy(), ref
+
+
+@pytest.mark.parametrize("kind", ["plain", "amplified", "odd_quant"])
+@pytest.mark.parametrize("name", list(CASES))
+def test_dense_forward_bf16_decode_kernels(name, kind):
+    print(f"dense bf16 {name} {kind}", flush=True)
+    layer, x, (logits, bias) = get(name)
+    if kind == "amplified":
+        if layer.cfg.r == 0:
+            pytest.skip("no factors")
+        layer = variants.amplified(layer)
+    elif kind == "odd_quant":
+        layer = variants.odd_quant(layer, layer.cfg.cfg_id)
+    got, ref = forward(layer, x, logits, bias, tq.TQ_ACT_BF16)
+    err = rel_err(got, ref)
+    print(f"   rel err {err:.3e}", flush=True)
+    assert err <= TOL_BF16
+    assert err <= (REG_LR_BF16 if kind == "amplified" else REG_BF16)
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_dense_forward_fp32(name):
+    layer, x, (logits, bias) = get(name)
+    got, ref = forward(layer, x, logits, bias, tq.TQ_ACT_FP32)
+    assert rel_err(got, ref) <= TOL_FP32
+
+
+def test_dense_beyond_the_decode_kernels_is_refused_before_any_launch():
+    cfg = dcfg(820, T=600)              # 1200 assignment rows: more than the decode kernels take
+    desc = desc_of(cfg)
+    x = torch.zeros((cfg.T, cfg.H), dtype=torch.bfloat16, device=DEV)
+    idx = torch.zeros((cfg.T, cfg.k), dtype=torch.int32, device=DEV)
+    w = torch.zeros((cfg.T, cfg.k), dtype=torch.float32, device=DEV)
+    blob = torch.zeros(tq.tq_packed_size(desc), dtype=torch.uint8, device=DEV)
+    with pytest.raises(tq.TqError) as ei:
+        tq.tq_moe_forward(desc, blob, x, idx, w)
+    assert ei.value.status == 6
+    small = dcfg(821, T=8)
+    with pytest.raises(tq.TqError) as ei:
+        tq.tq_moe_forward(desc_of(small, flags=tq.TQ_FLAG_FORCE_LARGE_TILE), blob, x[:8], idx[:8], w[:8])
+    assert ei.value.status == 6
+
+
+@pytest.mark.parametrize("bits", [3, 2])
+def test_dense_decode_full_shape(bits):
+    """The Mixtral-shaped decode layer (benchmark config 2) with its codes re-quantised to 3 and 2 bits, stored densely."""
+    cfg = CONFIGS[2].replace(bits=bits, dense=True, cfg_id=830 + bits)
+    print(f"dense config 2 at {bits} bits: generating", flush=True)
+    layer = make_layer(cfg, workers=16)
+    x = make_x(cfg)
+    logits, bias = make_logits(cfg)
+    got, ref = forward(layer, x, logits, bias, tq.TQ_ACT_BF16)
+    err = rel_err(got, ref)
+    print(f"dense config 2 at {bits} bits: rel err {err:.3e}", flush=True)
+    assert err <= REG_BF16

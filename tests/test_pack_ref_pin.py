@@ -48,9 +48,32 @@ def blob_by_definition(layer) -> bytes:
             codes = [layer.codes_matrix(e, p) for p in range(3)]
             scale = [layer.scale_matrix(e, p).view(np.uint16) for p in range(3)]
             zero = [layer.zero_matrix(e, p).view(np.uint16) for p in range(3)]
-            # ---- codes: uint32 [pairs][K/64][2 tiles][64 lanes][4]
+            dense_bits = c.bits if c.dense else 0
+            # ---- codes: uint32 [pairs][K/64][2 tiles][64 lanes][4], or dense [pairs][K/64][2 tiles][bits][64 lanes]
             part = bytearray()
-            for pair in range(pairs):
+            for pair in range(pairs if dense_bits else 0):
+                for ch in range(K // 64):
+                    for tile in range(2):
+                        for d in range(dense_bits):
+                            for lane in range(64):
+                                p, n = col_of(pair, tile, lane % 32)
+                                hf = lane // 32
+                                word = 0
+                                for w in range(4):
+                                    for j in range(4):
+                                        P = 4 * w + j
+                                        lo = int(codes[p][n, 64 * ch + 16 * w + 8 * hf + 2 * j])
+                                        hi = int(codes[p][n, 64 * ch + 16 * w + 8 * hf + 2 * j + 1])
+                                        if dense_bits == 2:
+                                            if P // 8 == d:
+                                                word |= (lo | (hi << 16)) << (2 * (P % 8))
+                                        elif P < 15:
+                                            if P // 5 == d:
+                                                word |= (lo | (hi << 16)) << (3 * (P % 5))
+                                        else:
+                                            word |= (((lo >> d) & 1) << 15) | (((hi >> d) & 1) << 31)
+                                part += struct.pack("<I", word)
+            for pair in range(0 if dense_bits else pairs):
                 for ch in range(K // 64):
                     for tile in range(2):
                         for lane in range(64):
@@ -74,7 +97,7 @@ def blob_by_definition(layer) -> bytes:
             rec += part
             # ---- zc: bf16 [pairs][3*ceil(G/16)][2 tiles][64 lanes][8]
             part = bytearray()
-            for pair in range(pairs):
+            for pair in range(0 if dense_bits else pairs):          # dense blobs carry no zc part
                 for s in range(3 * ((G + 15) // 16)):
                     for tile in range(2):
                         for lane in range(64):
@@ -131,6 +154,8 @@ CASES = {
     "smallest_g32_r4": LayerConfig(901, "p", E=1, S=0, k=1, H=64, F=64, T=1, g=32, r=4, bits=4),
     "rect_g64_r20_shared": LayerConfig(902, "p", E=2, S=1, k=1, H=128, F=64, T=1, g=64, r=20, bits=4),
     "rank0_int3": LayerConfig(903, "p", E=1, S=0, k=1, H=64, F=128, T=1, g=64, r=0, bits=3),
+    "dense3_r4": LayerConfig(904, "p", E=1, S=1, k=1, H=64, F=128, T=1, g=64, r=4, bits=3, dense=True),
+    "dense2_rank0": LayerConfig(905, "p", E=2, S=0, k=1, H=128, F=64, T=1, g=64, r=0, bits=2, dense=True),
 }
 
 
@@ -156,7 +181,10 @@ def test_pack_ref_size_is_the_storage_count_of_the_header():
         total = 0
         for K, pairs, na in ((H, F // 32, 2 * r16), (F, H // 64, r16)):
             G = K // g
-            total += pairs * (K // 64) * 2 * 64 * 16 + pairs * G * 2 * 32 * 4 + pairs * 3 * ((G + 15) // 16) * 2 * 64 * 16
+            if cfg.dense:
+                total += pairs * (K // 64) * 2 * 64 * 4 * cfg.bits + pairs * G * 2 * 32 * 4
+            else:
+                total += pairs * (K // 64) * 2 * 64 * 16 + pairs * G * 2 * 32 * 4 + pairs * 3 * ((G + 15) // 16) * 2 * 64 * 16
             if r:
                 total += pairs * (r16 // 16) * 2 * 64 * 16 + ((na + 31) // 32) * (K // 16) * 64 * 16
         assert pack_ref.pack_layer(layer).size == (cfg.E + cfg.S) * _align256(total)

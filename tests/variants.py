@@ -51,7 +51,7 @@ def odd_quant(layer, seed: int):
     z[pick > 0.97] = c.qmax + 5.5
     s = layer.scale.view(np.float16).astype(np.float32)
     pick = rng.random(s.shape)
-    s = np.where(pick < 0.03, s * np.float32(2.0 ** -8), s)       # fp16 subnormals (below 6.1e-5)
+    s = np.where(pick < 0.03, s * np.float32(2.0 ** -10), s)      # fp16 subnormals (below 6.1e-5)
     s = np.where(pick > 0.97, s * np.float32(16.0), s)
     s16 = s.astype(np.float16)
     assert np.any((s16 != 0) & (np.abs(s16.astype(np.float32)) < 6.1e-5))
