@@ -216,12 +216,23 @@ tq_status forward_impl(const tq_layer_desc* desc, const void* packed, const void
     uint8_t* ws = (uint8_t*)workspace;
     int32_t* ctrl = (int32_t*)(ws + W.ctrl);
     tqi_record_stage(0, st);
+    // decode batches: the gate/up low-rank pre-pass rides in the permutation's launch
+    TqPreByAssign pre = {};
+    const bool with_pre = desc->act_dtype == TQ_ACT_BF16 && tqi_bf16_takes_skinny(L, W, desc->flags) && tqi_pre_by_assign(L, W);
+    if (with_pre) {
+        pre.x = (const uint16_t*)x; pre.blob = (const uint8_t*)packed; pre.expert_stride = L.expert_stride;
+        pre.afrag_off = L.gu.afrag; pre.tpart = (float*)(ws + W.tpart); pre.H = L.H;
+        pre.n_slices = (L.H + 255) / 256; pre.na_tiles = L.gu.na_tiles; pre.a_tot = W.a_tot;
+    }
     tq_status rc = tqi_launch_permute(topk_idx, topk_w, T, L.E, L.S, L.k, (int32_t*)(ws + W.offsets),
-                                      (int32_t*)(ws + W.slot_of), L.k + L.S, nullptr,
+                                      (int32_t*)(ws + W.slot_of), L.k + L.S, (int32_t*)(ws + W.row_src),
                                       (int32_t*)(ws + W.row_token), (float*)(ws + W.row_w),
                                       (int32_t*)(ws + W.tile_e), (int32_t*)(ws + W.tile_row0), W.rt_max, ctrl,
                                       ctrl, (int32_t*)(ws + W.hist), W.nblk, packed, &L,
-                                      (int32_t*)(ws + W.sk_cnt), W.sk_cnt_n, st);
+                                      (int32_t*)(ws + W.sk_cnt), W.sk_cnt_n, st, with_pre ? &pre : nullptr,
+                                      // the single-wave permutation of decode batches builds only the 16-row tiling
+                                      desc->act_dtype == TQ_ACT_BF16 && tqi_bf16_takes_skinny(L, W, desc->flags)
+                                          ? (1 << 2) : (1 << TQ_N_TILINGS) - 1);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(1, st);
     if (desc->act_dtype == TQ_ACT_FP32)

@@ -96,6 +96,7 @@ struct TqWorkspace {
     size_t slot_of;     // int32 [T*(k+S)]
     size_t row_token;   // int32 [A_tot]
     size_t row_w;       // float [A_tot]
+    size_t row_src;     // int32 [A_tot]  assignment behind each slot: t * k + j (routed), T * k + s * T + t (shared expert s)
     size_t tile_e;      // int32 [4][RT]  expert of each row tile, for the 32-, 128-, 16- and 64-row tilings
     size_t tile_row0;   // int32 [4][RT]  first slot of each row tile
     size_t hist;        // int32 [nblk][E] permutation scratch
@@ -144,6 +145,7 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
     W->slot_of = take((size_t)a_tot * 4);
     W->row_token = take((size_t)a_tot * 4);
     W->row_w = take((size_t)a_tot * 4);
+    W->row_src = take((size_t)a_tot * 4);
     W->tile_e = take((size_t)TQ_N_TILINGS * W->rt_max * 4);
     W->tile_row0 = take((size_t)TQ_N_TILINGS * W->rt_max * 4);
     W->hist = take((size_t)W->nblk * L.E * 4);
@@ -196,13 +198,30 @@ __device__ inline int tq_find_expert(const int32_t* __restrict__ offsets, int n,
 }
 #endif
 
+// Decode batches: the low-rank intermediate of gate/up, t = x A_e, computed per ASSIGNMENT (it needs the routing
+// table only, not the permutation) so that it can share the permutation's launch:
+//   tpart[v][slice][ta][c] = sum over the 256-wide slice of x[token(v)][kk] * A_e(v)[kk][32 ta + c]   (fp32)
+// v = t * k + j for routed assignments, T * k + s * T + t for shared expert s.
+#define TQ_PRE_ASSIGN_MAX_ROWS 64     // assignment rows up to which the decode path takes this form (A_e is read per row)
+struct TqPreByAssign {
+    const uint16_t* x;       // [T][H] bf16
+    const uint8_t* blob;
+    size_t expert_stride, afrag_off;
+    float* tpart;
+    int32_t H, n_slices, na_tiles, a_tot;
+};
+
 // internal entry points implemented across the translation units (host side)
 tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32_t T, int32_t E, int32_t S,
                              int32_t k, int32_t* offsets, int32_t* slot_of, int32_t slot_stride,
                              int32_t* src_of, int32_t* row_token, float* row_w, int32_t* tile_e,
                              int32_t* tile_row0, int32_t rt_max, int32_t* ctrl, int32_t* err_flag,
                              int32_t* hist, int32_t nblk, const void* blob, const TqLayout* L,
-                             int32_t* zero_buf, int32_t zero_n, hipStream_t stream);
+                             int32_t* zero_buf, int32_t zero_n, hipStream_t stream,
+                             const TqPreByAssign* pre = nullptr, int tilings = (1 << TQ_N_TILINGS) - 1);
+// whether the bf16 forward of this batch runs on the decode kernels, and whether its gate/up pre-pass is by assignment
+bool tqi_bf16_takes_skinny(const TqLayout& L, const TqWorkspace& W, int flags);
+inline bool tqi_pre_by_assign(const TqLayout& L, const TqWorkspace& W) { return L.r > 0 && W.a_tot <= TQ_PRE_ASSIGN_MAX_ROWS; }
 tq_status tqi_forward_f32(const TqLayout& L, const TqWorkspace& W, const uint8_t* blob, const float* x,
                           int32_t T, float* y, uint8_t* ws, hipStream_t stream, const float* topk_w);
 tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, const uint8_t* blob,

@@ -778,6 +778,25 @@ tq_status tqi_setup_mfma()
     return ok ? TQ_OK : TQ_ERR_HIP;
 }
 
+// Tile choice of the bf16 forward: rows per expert on average decide between the 32-row tile and the large tiles;
+// decode batches (a handful of rows per expert) take the weight-streaming 16-row path when the layer allows it.
+static bool bf16_large_tiles(const TqLayout& L, const TqWorkspace& W, int flags)
+{
+    const int64_t avg_rows = (int64_t)W.a_tot / (L.E + L.S);
+    bool large = avg_rows > 48;
+    if (flags & TQ_FLAG_FORCE_SMALL_TILE) large = false;
+    if (flags & TQ_FLAG_FORCE_LARGE_TILE) large = true;
+    return large;
+}
+
+bool tqi_bf16_takes_skinny(const TqLayout& L, const TqWorkspace& W, int flags)
+{
+    const int64_t avg_rows = (int64_t)W.a_tot / (L.E + L.S);
+    bool skinny = !bf16_large_tiles(L, W, flags) && avg_rows <= 12 && !(flags & TQ_FLAG_FORCE_SMALL_TILE);
+    if ((flags & TQ_FLAG_FORCE_SKINNY) || L.cw != 4) skinny = true;      // dense codes: decode kernels only (checked by the caller)
+    return skinny && W.a_tot <= TQ_SKINNY_MAX_ROWS && tqi_skinny_supported(L);
+}
+
 tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, const uint8_t* blob,
                            const uint16_t* x, int32_t T, uint16_t* y, uint8_t* ws, hipStream_t stream,
                            const float* topk_w)
@@ -798,11 +817,7 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     uint16_t* h = reinterpret_cast<uint16_t*>(ws + W.h);
     float* yd = reinterpret_cast<float*>(ws + W.yd);
 
-    // tile choice: rows per expert on average decide between the 32-row tile and the large (64/128-row) tiles
-    const int64_t avg_rows = (int64_t)W.a_tot / (L.E + L.S);
-    bool large = avg_rows > 48;
-    if (flags & TQ_FLAG_FORCE_SMALL_TILE) large = false;
-    if (flags & TQ_FLAG_FORCE_LARGE_TILE) large = true;
+    const bool large = bf16_large_tiles(L, W, flags);
     const int rt32 = W.a_tot / 32 + L.E + L.S;     // upper bounds on the number of row tiles
     const int rt128 = W.a_tot / 128 + L.E + L.S;
     const int rt64 = W.a_tot / 64 + L.E + L.S;
@@ -810,9 +825,7 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     const bool persist = tqi_prefill_supported(L, W, T);
 
     // decode batches (a handful of rows per expert): the weight-streaming 16-row path, no pre-pass over K
-    bool skinny = !large && avg_rows <= 12 && !(flags & TQ_FLAG_FORCE_SMALL_TILE);
-    if ((flags & TQ_FLAG_FORCE_SKINNY) || L.cw != 4) skinny = true;      // dense codes: decode kernels only (checked by the caller)
-    if (skinny && W.a_tot <= TQ_SKINNY_MAX_ROWS && tqi_skinny_supported(L)) {
+    if (tqi_bf16_takes_skinny(L, W, flags)) {
         int nsplit_sk = 1;
         tq_status rs = tqi_forward_skinny(L, W, blob, x, T, ws, stream, &nsplit_sk);
         if (rs != TQ_OK) return rs;

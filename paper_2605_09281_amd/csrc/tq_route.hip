@@ -136,11 +136,13 @@ __global__ void __launch_bounds__(64) hist_kernel(const int32_t* __restrict__ id
 
 // writes the row-tile tables from offs[0..ne] (LDS); `sm_base` is LDS scratch of TQ_N_TILINGS*(ne+1) ints
 __device__ inline void build_tile_tables(const int32_t* offs, int32_t* sm_base, int ne, int32_t* tile_e,
-                                         int32_t* tile_row0, int rt_max, int32_t* ctrl, int tid, int nthreads)
+                                         int32_t* tile_row0, int rt_max, int32_t* ctrl, int tid, int nthreads,
+                                         int tilings = (1 << TQ_N_TILINGS) - 1)
 {
     // per tiling: tiles of expert e = ceil(count/bm); scan by wavefront `which` (or by wave 0 in turn)
     const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
     for (int which = wave; which < TQ_N_TILINGS; which += nwaves) {
+        if (!((tilings >> which) & 1)) continue;       // tilings no kernel of this forward reads (their counts stay 0)
         const int bm = tile_rows_of(which);
         int32_t* base = sm_base + which * (ne + 1);
         int carry = 0;
@@ -156,6 +158,7 @@ __device__ inline void build_tile_tables(const int32_t* offs, int32_t* sm_base, 
     __syncthreads();
     // one entry per thread: the expert of tile n is found by bisection over the per-expert first tiles
     for (int which = 0; which < TQ_N_TILINGS; ++which) {
+        if (!((tilings >> which) & 1)) continue;
         const int bm = tile_rows_of(which);
         const int32_t* base = sm_base + which * (ne + 1);
         const int total = base[ne] < rt_max ? base[ne] : rt_max;
@@ -294,14 +297,14 @@ __global__ void __launch_bounds__(64) scatter_kernel(const int32_t* __restrict__
             int s = (int)(i / T), t = (int)(i % T);
             int slot = offsets[E + s] + t;
             if (slot_of) slot_of[(size_t)t * slot_stride + k + s] = slot;
+            if (src_of) src_of[slot] = (int32_t)(n_assign + i);
             if (row_token) row_token[slot] = t;
             if (row_w) row_w[slot] = 1.0f;
         }
     }
 }
 
-// The whole permutation for a few chunks of assignments in ONE wavefront (one launch instead of five).
-__global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __restrict__ idx, const float* __restrict__ w,
+__device__ inline void permute_small_body(const int32_t* __restrict__ idx, const float* __restrict__ w,
                                                            int n_assign, int E, int S, int T, int k,
                                                            int32_t* __restrict__ offsets, int32_t* __restrict__ slot_of,
                                                            int slot_stride, int32_t* __restrict__ src_of,
@@ -310,7 +313,8 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
                                                            int rt_max, int32_t* __restrict__ ctrl,
                                                            int32_t* __restrict__ err_flag,
                                                            const TqBlobHeader* __restrict__ hdr, TqBlobHeader expect,
-                                                           int check_blob, int32_t* __restrict__ zero_buf, int zero_n)
+                                                           int check_blob, int32_t* __restrict__ zero_buf, int zero_n,
+                                                           int tilings)
 {
     extern __shared__ int32_t sm[];   // counts[ne] | offs[ne+1] | cursor[E] | tile scratch 3*(ne+1)
     const int ne = E + S, lane = threadIdx.x;
@@ -359,7 +363,7 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
     for (int e = lane; e < E; e += 64) cursor[e] = offs[e];
     __syncthreads();
     if (ctrl && lane == 0) ctrl[3] = total;
-    if (tile_e) build_tile_tables(offs, tsm, ne, tile_e, tile_row0, rt_max, ctrl, lane, 64);
+    if (tile_e) build_tile_tables(offs, tsm, ne, tile_e, tile_row0, rt_max, ctrl, lane, 64, tilings);
     __syncthreads();
     // stable placement, 64 assignments per round in order (same ranking as scatter_chunk, from registers)
 #pragma unroll
@@ -392,6 +396,7 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
         int s = i / T, t = i % T;
         int slot = offs[E + s] + t;
         if (slot_of) slot_of[(size_t)t * slot_stride + k + s] = slot;
+        if (src_of) src_of[slot] = n_assign + i;
         if (row_token) row_token[slot] = t;
         if (row_w) row_w[slot] = 1.0f;
     }
@@ -399,6 +404,76 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
     // a blob that does not belong to the descriptor must not be indexed with the descriptor's geometry: with no
     // row tiles and no rows every later kernel of the forward ends at once
     if ((flags & TQ_FLAG_BIT_BLOB) && ctrl && lane == 0) { ctrl[1] = 0; ctrl[2] = 0; ctrl[3] = 0; ctrl[4] = 0; ctrl[5] = 0; }
+}
+
+// One wavefront per (assignment v, 256-wide slice, 32-column tile of t): see TqPreByAssign.  Plain fp32 FMAs on the
+// exact values of x (bf16) and A (fp16), the two halves of a 16-wide step in the two halves of the wave.
+__device__ inline void pre_by_assign_block(const TqPreByAssign& P, const int32_t* __restrict__ idx, int T, int E, int k,
+                                           int b, int lane)
+{
+    const int ta = b % P.na_tiles;
+    const int slice = (b / P.na_tiles) % P.n_slices;
+    const int v = b / (P.na_tiles * P.n_slices);
+    if (v >= P.a_tot) return;
+    int e, t;
+    if (v < T * k) { e = idx[v]; t = v / k; if (e < 0 || e >= E) return; }      // dropped assignments have no row
+    else { const int q = v - T * k; e = E + q / T; t = q % T; }
+    const int col = lane & 31, hf = lane >> 5;
+    const int ksteps = P.H / 16;
+    const uint16_t* xrow = P.x + (size_t)t * P.H;
+    const uint4* af = reinterpret_cast<const uint4*>(P.blob + TQ_HEADER_BYTES + (size_t)e * P.expert_stride + P.afrag_off);
+    constexpr int NS = 16;                       // steps per slice
+    const int s0 = slice * NS;
+    uint4 xa[NS], aq[NS];
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+        const int sidx = min(s0 + u, ksteps - 1);
+        xa[u] = *reinterpret_cast<const uint4*>(xrow + 16 * sidx + 8 * hf);
+        aq[u] = af[((size_t)ta * ksteps + sidx) * 64 + lane];
+    }
+    float acc = 0.f;
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+        if (s0 + u < ksteps) {
+            const uint32_t xw[4] = {xa[u].x, xa[u].y, xa[u].z, xa[u].w};
+            const uint32_t aw[4] = {aq[u].x, aq[u].y, aq[u].z, aq[u].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc = fmaf(__uint_as_float(xw[j] << 16), tq_half_bits_to_float((uint16_t)(aw[j] & 0xFFFF)), acc);
+                acc = fmaf(__uint_as_float(xw[j] & 0xFFFF0000u), tq_half_bits_to_float((uint16_t)(aw[j] >> 16)), acc);
+            }
+        }
+    }
+    acc += __shfl_xor(acc, 32);
+    if (hf == 0) P.tpart[(((size_t)v * P.n_slices + slice) * P.na_tiles + ta) * 32 + col] = acc;
+}
+
+__global__ void __launch_bounds__(64) pre_by_assign_kernel(TqPreByAssign P, const int32_t* __restrict__ idx, int T, int E, int k)
+{
+    pre_by_assign_block(P, idx, T, E, k, blockIdx.x, threadIdx.x);
+}
+
+// The whole permutation for a few chunks of assignments in ONE wavefront (one launch instead of five); with
+// HAS_PRE the other workgroups of the launch compute the gate/up low-rank intermediate by assignment.
+template <bool HAS_PRE>
+__global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __restrict__ idx, const float* __restrict__ w,
+                                                           int n_assign, int E, int S, int T, int k,
+                                                           int32_t* __restrict__ offsets, int32_t* __restrict__ slot_of,
+                                                           int slot_stride, int32_t* __restrict__ src_of,
+                                                           int32_t* __restrict__ row_token, float* __restrict__ row_w,
+                                                           int32_t* __restrict__ tile_e, int32_t* __restrict__ tile_row0,
+                                                           int rt_max, int32_t* __restrict__ ctrl,
+                                                           int32_t* __restrict__ err_flag,
+                                                           const TqBlobHeader* __restrict__ hdr, TqBlobHeader expect,
+                                                           int check_blob, int32_t* __restrict__ zero_buf, int zero_n,
+                                                           TqPreByAssign P, int tilings)
+{
+    if (HAS_PRE && blockIdx.x > 0) {
+        pre_by_assign_block(P, idx, T, E, k, blockIdx.x - 1, threadIdx.x);
+        return;
+    }
+    permute_small_body(idx, w, n_assign, E, S, T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e,
+                       tile_row0, rt_max, ctrl, err_flag, hdr, expect, check_blob, zero_buf, zero_n, tilings);
 }
 
 __global__ void clear_ctrl_kernel(int32_t* ctrl, int32_t* err_flag, int32_t* zero_buf, int zero_n)
@@ -415,9 +490,11 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
                              int32_t* src_of, int32_t* row_token, float* row_w, int32_t* tile_e,
                              int32_t* tile_row0, int32_t rt_max, int32_t* ctrl, int32_t* err_flag,
                              int32_t* hist, int32_t nblk, const void* blob, const TqLayout* L,
-                             int32_t* zero_buf, int32_t zero_n, hipStream_t stream)
+                             int32_t* zero_buf, int32_t zero_n, hipStream_t stream, const TqPreByAssign* pre, int tilings)
 {
     const int64_t n_assign = (int64_t)T * k;
+    const int64_t n_pre = pre ? (int64_t)pre->a_tot * pre->n_slices * pre->na_tiles : 0;
+    if (n_pre > 0x3FFFFFFF) return TQ_ERR_UNSUPPORTED;
     TqBlobHeader expect = {};
     int check = 0;
     if (blob && L) {
@@ -430,11 +507,22 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
     const int ne = E + S;
     if (nblk == 1 && (int64_t)S * T <= 4096) {
         const size_t sm = ((size_t)ne + (ne + 1) + E + TQ_N_TILINGS * (ne + 1)) * 4;
-        hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(64), sm, stream, topk_idx, topk_w, (int)n_assign, E, S,
-                           T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e, tile_row0, rt_max,
-                           ctrl, err_flag, (const TqBlobHeader*)blob, expect, check, zero_buf, (int)zero_n);
+        if (n_pre > 0)
+            hipLaunchKernelGGL(permute_small_kernel<true>, dim3(1 + (unsigned)n_pre), dim3(64), sm, stream, topk_idx, topk_w,
+                               (int)n_assign, E, S, T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e,
+                               tile_row0, rt_max, ctrl, err_flag, (const TqBlobHeader*)blob, expect, check, zero_buf,
+                               (int)zero_n, *pre, tilings);
+        else
+            hipLaunchKernelGGL(permute_small_kernel<false>, dim3(1), dim3(64), sm, stream, topk_idx, topk_w, (int)n_assign,
+                               E, S, T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e, tile_row0,
+                               rt_max, ctrl, err_flag, (const TqBlobHeader*)blob, expect, check, zero_buf, (int)zero_n,
+                               TqPreByAssign{}, tilings);
         TQ_CHECK_LAUNCH();
         return TQ_OK;
+    }
+    if (n_pre > 0) {      // the permutation takes several launches: the pre-pass gets its own
+        hipLaunchKernelGGL(pre_by_assign_kernel, dim3((unsigned)n_pre), dim3(64), 0, stream, *pre, topk_idx, T, E, k);
+        TQ_CHECK_LAUNCH();
     }
     if (ctrl) {
         hipLaunchKernelGGL(clear_ctrl_kernel, dim3(1), dim3(64), 0, stream, ctrl, err_flag, zero_buf, (int)zero_n);

@@ -86,7 +86,8 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
                                                          const int32_t* __restrict__ ctrl,
                                                          const float* __restrict__ tpart, int n_slices, int na_tiles,
                                                          void* __restrict__ out, int32_t* __restrict__ pair_cnt,
-                                                         int units_per_split, int RB, int red_off, int xs_off, int mb_off)
+                                                         int units_per_split, int RB, int red_off, int xs_off, int mb_off,
+                                                         const int32_t* __restrict__ row_src)
 {
     constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
     constexpr int UC = UNIT_K / 64;
@@ -195,13 +196,27 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
         const int nsl = (range_k + SK_PRE_K - 1) / SK_PRE_K;
         const float* tp = n_lr > 0 ? tpart : reinterpret_cast<const float*>(ctrl);
         const size_t live = n_lr > 0 ? 1 : 0;
+        if (STAGE == 0 && row_src) {
+            // slices stored per assignment (they came with the permutation's launch): this lane's value of step
+            // `wave` belongs to row row_of_v(wave, hf) of the tile; padding rows repeat the last one
+            const int m = min(row_of_v(wave, hf), rows - 1);
+            const size_t v = (size_t)row_src[slot0 + m];
 #pragma unroll
-        for (int ta = 0; ta < 4; ++ta)
+            for (int ta = 0; ta < 4; ++ta)
 #pragma unroll
-            for (int sl = 0; sl < 16; ++sl) {
-                const size_t idx = (((size_t)rt * n_slices + sl0 + min(sl, nsl - 1)) * na_tiles + min(ta, max(na_tiles, 1) - 1)) * 512 + wave * 64 + lane;
-                tv[ta][sl] = tp[idx * live];
-            }
+                for (int sl = 0; sl < 16; ++sl) {
+                    const size_t idx = ((v * n_slices + sl0 + min(sl, nsl - 1)) * na_tiles + min(ta, max(na_tiles, 1) - 1)) * 32 + col;
+                    tv[ta][sl] = tp[idx * live];
+                }
+        } else {
+#pragma unroll
+            for (int ta = 0; ta < 4; ++ta)
+#pragma unroll
+                for (int sl = 0; sl < 16; ++sl) {
+                    const size_t idx = (((size_t)rt * n_slices + sl0 + min(sl, nsl - 1)) * na_tiles + min(ta, max(na_tiles, 1) - 1)) * 512 + wave * 64 + lane;
+                    tv[ta][sl] = tp[idx * live];
+                }
+        }
     }
 
 #pragma unroll
@@ -447,7 +462,7 @@ tq_status launch_skinny(const MGeom& G, const TqSection& sec, const uint8_t* blo
                         const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
                         const int32_t* offsets, const int32_t* ctrl, float* tpart, int n_slices, int na_tiles,
                         void* out, int32_t* pair_cnt, int row_tiles, int nsplit, int units_per_split, int tiles_est,
-                        hipStream_t st)
+                        hipStream_t st, const int32_t* row_src)
 {
     constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
     const int range_k = units_per_split * UNIT_K;
@@ -470,7 +485,8 @@ tq_status launch_skinny(const MGeom& G, const TqSection& sec, const uint8_t* blo
     dim3 grid((sec.pairs + ppw - 1) / ppw, row_tiles, nsplit);
     if (grid.y > 65535) return TQ_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl,
-                       (const float*)tpart, n_slices, na_tiles, out, pair_cnt, units_per_split, RB, red_off, xs_off, mb_off);
+                       (const float*)tpart, n_slices, na_tiles, out, pair_cnt, units_per_split, RB, red_off, xs_off, mb_off,
+                       row_src);
     TQ_CHECK_LAUNCH();
     return TQ_OK;
 }
@@ -480,11 +496,11 @@ tq_status launch_skinny_gs(int gs, int cw, const MGeom& G, const TqSection& sec,
                            const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
                            const int32_t* offsets, const int32_t* ctrl, float* tpart, int n_slices, int na_tiles,
                            void* out, int32_t* pair_cnt, int row_tiles, int nsplit, int units_per_split, int tiles_est,
-                           hipStream_t st)
+                           hipStream_t st, const int32_t* row_src)
 {
 #define TQ_SK(GSV, CWV)                                                                                                   \
     return launch_skinny<STAGE, GSV, CWV>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, \
-                                          na_tiles, out, pair_cnt, row_tiles, nsplit, units_per_split, tiles_est, st)
+                                          na_tiles, out, pair_cnt, row_tiles, nsplit, units_per_split, tiles_est, st, row_src)
     if (cw == 4) {
         switch (gs) {
             case 2: TQ_SK(2, 4);
@@ -575,7 +591,10 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     plan_split(L.H, L.g, &ns, &ups);
     const int sl_gu = (L.H + SK_PRE_K - 1) / SK_PRE_K, sl_d = (L.F + SK_PRE_K - 1) / SK_PRE_K;
     const int nat_gu = L.r > 0 ? L.gu.na_tiles : 0, nat_d = L.r > 0 ? L.d.na_tiles : 0;
-    if (L.r > 0) {
+    // decode batches proper: the gate/up slices were computed per assignment in the permutation's launch
+    const bool by_assign = tqi_pre_by_assign(L, W);
+    const int32_t* row_src = by_assign ? reinterpret_cast<const int32_t*>(ws + W.row_src) : nullptr;
+    if (L.r > 0 && !by_assign) {
         hipLaunchKernelGGL(skinny_pre_kernel<0>, dim3(rt16, sl_gu, nat_gu), dim3(64), 0, stream, G, L.gu, blob, x, row_token, tile_e,
                            tile_row0, offsets, ctrl, tpart, sl_gu, nat_gu);
         TQ_CHECK_LAUNCH();
@@ -584,7 +603,7 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     int32_t* pair_cnt = reinterpret_cast<int32_t*>(ws + W.sk_cnt);
     if (W.sk_cnt_n < 2 * W.rt_max * TQ_MAX_SPLIT) return TQ_ERR_UNSUPPORTED;
     tq_status rc = launch_skinny_gs<0>(gs, L.cw, G, L.gu, blob, x, row_token, tile_e, tile_row0, offsets, ctrl, tpart, sl_gu, nat_gu,
-                                       h, pair_cnt, rt16, 1, ups, tiles_est, stream);
+                                       h, pair_cnt, rt16, 1, ups, tiles_est, stream, row_src);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(3, stream);
     if (L.r > 0) {
@@ -595,7 +614,7 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     tqi_record_stage(4, stream);
     plan_split(L.F, L.g, &ns, &ups);
     rc = launch_skinny_gs<1>(gs, L.cw, G, L.d, blob, h, row_token, tile_e, tile_row0, offsets, ctrl, tpart, sl_d, nat_d, yd,
-                             pair_cnt + (size_t)W.rt_max * TQ_MAX_SPLIT, rt16, ns, ups, tiles_est, stream);
+                             pair_cnt + (size_t)W.rt_max * TQ_MAX_SPLIT, rt16, ns, ups, tiles_est, stream, nullptr);
     if (rc != TQ_OK) return rc;
     *nsplit_out = ns;
     return TQ_OK;
