@@ -120,6 +120,9 @@ typedef struct tq_layer_desc {
                           (TQ_ERR_UNSUPPORTED beyond); the fp32 debug path takes all of them */
     int32_t act_dtype; /* TQ_ACT_BF16: x, y bf16, MFMA path.  TQ_ACT_FP32: x, y fp32, exact-dequant debug path */
     int32_t flags;     /* TQ_FLAG_DENSE_CODES and / or test hooks */
+    int32_t tiles_m;   /* 0: per-expert factors A_e, B_e.  M >= 1: shared 2D-tiled factors (Eq. 4): M left factors    */
+    int32_t tiles_n;   /*    U_m Sigma and N right factors V_n per projection and a placement table phi (both 0 or   */
+                       /*    both >= 1; see tq_pack_weights_shared)                                                   */
 } tq_layer_desc;
 
 typedef struct tq_weights_src { /* canonical layout above; A, B may be NULL when rank == 0 */
@@ -155,6 +158,34 @@ size_t tq_packed_size(const tq_layer_desc *desc);
  * code is stored masked to 4 bits.  Returns TQ_ERR_WORKSPACE if packed_bytes < tq_packed_size(). */
 tq_status tq_pack_weights(const tq_layer_desc *desc, const tq_weights_src *src, void *packed,
                           size_t packed_bytes, int32_t *err_flag, void *stream);
+
+/* Shared 2D-tiled factors of a layer (Section 3.1, Eq. 4: W_k = U_p Sigma V_q + quantised residual, {p, q} = phi(k);
+ * Algorithm 1 stores per expert the residual and phi(k), and the factors once).  For each projection p in
+ * {0 gate, 1 up, 2 down} with contraction length K_p (H, H, F) and output width N_p (F, F, H):
+ *     us[p]  fp16 [M][K_p][r]     U_m Sigma, any per-row input scaling folded in
+ *     v[p]   fp16 [N][r][N_p]     V_n
+ *     phi    int32 [E+S][2]       expert -> (m, n), 0 <= m < M, 0 <= n < N (shared experts included)
+ * All device pointers.  The layer then computes exactly what tq_pack_weights computes with the effective factors
+ * A_e = us[p][m(e)], B_e = v[p][n(e)]. */
+typedef struct tq_shared_factors {
+    const uint16_t *us[3];
+    const uint16_t *v[3];
+    const int32_t *phi;
+} tq_shared_factors;
+
+/* As tq_pack_weights for a descriptor with tiles_m, tiles_n >= 1: src->codes / scale / zero as there (src->A, src->B
+ * are ignored), the factors from `shared`.  The blob keeps one record of codes, scales and zero-points per expert
+ * (parts codes, sz, zc only) and, behind the records, in this order: the placement table int32 [E+S][2] padded to
+ * 256 bytes; for section GU (gate and up side by side) M blocks in the afrag layout, block m built from us[0][m]
+ * and us[1][m], then N blocks in the bfrag layout from v[0][n] and v[1][n]; for section D M afrag blocks from
+ * us[2][m] and N bfrag blocks from v[2][n]; the whole padded to 256 bytes.  Every block has exactly the layout
+ * and size of that part of a per-expert record.  Its size is tq_packed_size(desc): with r a multiple of 32 the factors cost
+ * 16 r (M (2 H + F) + N (2 F + H)) bits in total instead of 16 r (E+S) (3 H + 3 F), the shared count of Appendix A.3.
+ * err_flag bit 0 is also set when a phi entry is outside the grid (it is then clamped into it).
+ * Every kernel of tq_moe_forward finds an expert's factors through phi, so the forward accepts such a blob under
+ * the same descriptor on every path (tiled bf16, decode, fp32). */
+tq_status tq_pack_weights_shared(const tq_layer_desc *desc, const tq_weights_src *src, const tq_shared_factors *shared,
+                                 void *packed, size_t packed_bytes, int32_t *err_flag, void *stream);
 
 /* Exact inverse of tq_pack_weights (bit for bit on codes, scale, zero, A, B): recovers the per-expert stored
  * tuple of Algorithm 1 (quantised residual, effective factors) from the blob.  For tests and tools. */

@@ -177,6 +177,45 @@ def moe_forward_layer(layer, x: np.ndarray, idx: np.ndarray, w: np.ndarray,
                        layer.A if c.r else None, layer.B if c.r else None, x, idx, w, tokens)
 
 
+class OrcShared(ctypes.Structure):
+    _fields_ = [("us", ctypes.c_void_p * 3), ("v", ctypes.c_void_p * 3), ("phi", ctypes.c_void_p),
+                ("M", ctypes.c_int32), ("N", ctypes.c_int32)]
+
+
+def moe_forward_shared(slayer, x: np.ndarray, idx: np.ndarray, w: np.ndarray,
+                       tokens: Optional[np.ndarray] = None) -> np.ndarray:
+    """The layer on shared 2D-tiled factors.  slayer: object with .cfg, canonical .codes/.scale/.zero, .us / .v
+    (3-lists of fp16-bit arrays [M, K_p, r] / [N, r, N_p]) and .phi int32 [E+S, 2].  Returns float64 [n_tokens, H]."""
+    c = slayer.cfg
+    x = _c(x, np.float32)
+    T = x.shape[0]
+    idx = _c(idx, np.int32)
+    w = _c(w, np.float32)
+    assert x.shape == (T, c.H) and idx.shape == (T, c.k) and w.shape == (T, c.k) and c.r > 0
+    codes, scale, zero = _c(slayer.codes, np.uint8), _c(slayer.scale, np.uint16), _c(slayer.zero, np.uint16)
+    us = [_c(a, np.uint16) for a in slayer.us]
+    v = [_c(a, np.uint16) for a in slayer.v]
+    phi = _c(slayer.phi, np.int32)
+    M, N = us[0].shape[0], v[0].shape[0]
+    for p, (K, Nout) in enumerate(((c.H, c.F), (c.H, c.F), (c.F, c.H))):
+        assert us[p].shape == (M, K, c.r) and v[p].shape == (N, c.r, Nout)
+    assert phi.shape == (c.E + c.S, 2)
+    tok = None if tokens is None else _c(tokens, np.int32)
+    n = T if tok is None else tok.size
+    y = np.empty((n, c.H), dtype=np.float64)
+    L = OrcLayer(c.E, c.S, c.k, c.H, c.F, c.g, c.bits, c.r)
+    Wt = OrcWeights(_p(codes), _p(scale), _p(zero), None, None)
+    Sh = OrcShared((ctypes.c_void_p * 3)(*[a.ctypes.data for a in us]), (ctypes.c_void_p * 3)(*[a.ctypes.data for a in v]),
+                   _p(phi), M, N)
+    lb = lib()
+    lb.orc_moe_forward_shared.restype = ctypes.c_int32
+    rc = lb.orc_moe_forward_shared(ctypes.byref(L), ctypes.byref(Wt), ctypes.byref(Sh), _p(x), _p(idx), _p(w),
+                                   ctypes.c_int32(T), _p(tok), ctypes.c_int32(n), _p(y))
+    if rc != 0:
+        raise ValueError("oracle: expert, token or tile index out of range")
+    return y
+
+
 def lotile_forward(x: np.ndarray, us_bits: np.ndarray, v_bits: np.ndarray, phi: np.ndarray,
                    idx: np.ndarray, w: np.ndarray) -> np.ndarray:
     """LoTileMoE of Section 3.2 (three-dimensional accumulator form).  x [T, in] fp32; us_bits [M, in, r] and

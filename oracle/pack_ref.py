@@ -90,9 +90,38 @@ def _pad_cols(a: np.ndarray, cols: int) -> np.ndarray:
     return out
 
 
-def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r, dense_bits=0) -> bytes:
+def _bfrag_gu(B0, B1, r16, pairs) -> bytes:
+    """Right factors of gate and up, [r, F] each -> [pairs, step, tile, hf, col, i]."""
+    b = np.stack([_pad_rows(Bp, r16).reshape(r16 // 16, 2, 8, pairs, 32) for Bp in (B0, B1)], axis=0)
+    # [tile, step, hf, i, pairs, col] -> [pairs, step, tile, hf, col, i]
+    return np.ascontiguousarray(b.transpose(4, 1, 0, 2, 5, 3)).tobytes()
+
+
+def _afrag_gu(A0, A1, r16, K) -> bytes:
+    """Left factors of gate and up, [H, r] each, side by side -> [ta, step, hf, col, i]."""
+    acat = np.concatenate([_pad_cols(A0, r16), _pad_cols(A1, r16)], axis=1)   # [K, 2*r16]
+    nat = (2 * r16 + 31) // 32
+    acat = _pad_cols(acat, 32 * nat).reshape(K // 16, 2, 8, nat, 32)
+    # [step, hf, i, ta, col] -> [ta, step, hf, col, i]
+    return np.ascontiguousarray(acat.transpose(3, 0, 1, 4, 2)).tobytes()
+
+
+def _bfrag_d(B2, r16, pairs) -> bytes:
+    b = _pad_rows(B2, r16).reshape(r16 // 16, 2, 8, pairs, 2, 32)
+    # [step, hf, i, pairs, tile, col] -> [pairs, step, tile, hf, col, i]
+    return np.ascontiguousarray(b.transpose(3, 0, 4, 1, 5, 2)).tobytes()
+
+
+def _afrag_d(A2, r16, K) -> bytes:
+    nat = (r16 + 31) // 32
+    a = _pad_cols(_pad_cols(A2, r16), 32 * nat).reshape(K // 16, 2, 8, nat, 32)
+    return np.ascontiguousarray(a.transpose(3, 0, 1, 4, 2)).tobytes()
+
+
+def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r, dense_bits=0, factors=True) -> bytes:
     """codes3[p]: [N,K] uint8; scale3/zero3[p]: [N,K/g] uint16; A3[p]: [K,r] uint16; B3[p]: [r,N] uint16.
-    dense_bits: 0 = codes in 4-bit slots; 2 or 3 = the dense layouts (no zc part)."""
+    dense_bits: 0 = codes in 4-bit slots; 2 or 3 = the dense layouts (no zc part).  factors=False: a record of the
+    shared-factor format (no bfrag / afrag parts)."""
     r16 = (r + 15) // 16 * 16
     parts = []
 
@@ -117,15 +146,9 @@ def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r, dense_bits=0) -> byte
                                for p in (0, 1)], axis=0)
                 # [tile, pairs, col, block, which, hf, i] -> [pairs, step = 3*block + which, tile, hf, col, i]
                 parts.append(np.ascontiguousarray(zc.transpose(1, 3, 4, 0, 5, 2, 6)).tobytes())
-            if r > 0:
-                b = np.stack([_pad_rows(B3[p], r16).reshape(r16 // 16, 2, 8, pairs, 32) for p in (0, 1)], axis=0)
-                # [tile, step, hf, i, pairs, col] -> [pairs, step, tile, hf, col, i]
-                parts.append(np.ascontiguousarray(b.transpose(4, 1, 0, 2, 5, 3)).tobytes())
-                acat = np.concatenate([_pad_cols(A3[0], r16), _pad_cols(A3[1], r16)], axis=1)   # [K, 2*r16]
-                nat = (2 * r16 + 31) // 32
-                acat = _pad_cols(acat, 32 * nat).reshape(K // 16, 2, 8, nat, 32)
-                # [step, hf, i, ta, col] -> [ta, step, hf, col, i]
-                parts.append(np.ascontiguousarray(acat.transpose(3, 0, 1, 4, 2)).tobytes())
+            if r > 0 and factors:
+                parts.append(_bfrag_gu(B3[0], B3[1], r16, pairs))
+                parts.append(_afrag_gu(A3[0], A3[1], r16, K))
         else:
             K, pairs = F, H // 64
             if dense_bits:
@@ -143,13 +166,9 @@ def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r, dense_bits=0) -> byte
                 zc = _zc_part(*_zero_coeff_parts(scale3[2], zero3[2], g16)).reshape(pairs, 2, 32, g16, 3, 2, 8)
                 # [pairs, tile, col, block, which, hf, i] -> [pairs, step, tile, hf, col, i]
                 parts.append(np.ascontiguousarray(zc.transpose(0, 3, 4, 1, 5, 2, 6)).tobytes())
-            if r > 0:
-                b = _pad_rows(B3[2], r16).reshape(r16 // 16, 2, 8, pairs, 2, 32)
-                # [step, hf, i, pairs, tile, col] -> [pairs, step, tile, hf, col, i]
-                parts.append(np.ascontiguousarray(b.transpose(3, 0, 4, 1, 5, 2)).tobytes())
-                nat = (r16 + 31) // 32
-                a = _pad_cols(_pad_cols(A3[2], r16), 32 * nat).reshape(K // 16, 2, 8, nat, 32)
-                parts.append(np.ascontiguousarray(a.transpose(3, 0, 1, 4, 2)).tobytes())
+            if r > 0 and factors:
+                parts.append(_bfrag_d(B3[2], r16, pairs))
+                parts.append(_afrag_d(A3[2], r16, K))
 
     section(False)
     section(True)
@@ -171,3 +190,28 @@ def pack_layer(layer) -> np.ndarray:
         out.append(pack_expert(codes3, scale3, zero3, A3, B3, c.H, c.F, c.g, c.r,
                                dense_bits=c.bits if getattr(c, "dense", False) else 0))
     return np.frombuffer(b"".join(out), dtype=np.uint8)
+
+
+def pack_layer_shared(sl) -> np.ndarray:
+    """Blob body for a layer on shared 2D-tiled factors (object with .cfg, .codes/.scale/.zero, .us, .v, .phi): the
+    per-expert records without factor parts, then the placement table int32 [E+S][2] (padded to 256 bytes), then
+    for section GU the M left blocks (gate and up side by side, afrag layout) and the N right blocks (bfrag layout),
+    then the same for section D; the whole padded to 256 bytes."""
+    c = sl.cfg
+    r16 = (c.r + 15) // 16 * 16
+    out = []
+    for e in range(c.E + c.S):
+        codes3 = [sl.codes[e, p].reshape((c.F, c.H) if p < 2 else (c.H, c.F)) for p in range(3)]
+        scale3 = [sl.scale[e, p].reshape(codes3[p].shape[0], -1) for p in range(3)]
+        zero3 = [sl.zero[e, p].reshape(codes3[p].shape[0], -1) for p in range(3)]
+        out.append(pack_expert(codes3, scale3, zero3, [None] * 3, [None] * 3, c.H, c.F, c.g, c.r,
+                               dense_bits=c.bits if getattr(c, "dense", False) else 0, factors=False))
+    phi = np.ascontiguousarray(sl.phi, dtype=np.int32).tobytes()
+    out.append(phi + b"\0" * ((-len(phi)) % 256))
+    M, N = sl.us[0].shape[0], sl.v[0].shape[0]
+    out += [_afrag_gu(sl.us[0][m], sl.us[1][m], r16, c.H) for m in range(M)]
+    out += [_bfrag_gu(sl.v[0][n], sl.v[1][n], r16, c.F // 32) for n in range(N)]
+    out += [_afrag_d(sl.us[2][m], r16, c.F) for m in range(M)]
+    out += [_bfrag_d(sl.v[2][n], r16, c.H // 64) for n in range(N)]
+    body = b"".join(out)
+    return np.frombuffer(body + b"\0" * ((-len(body)) % 256), dtype=np.uint8)

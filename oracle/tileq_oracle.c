@@ -17,6 +17,8 @@
  *     already folded into the left factor offline (Algorithm 1);
  *   - group-wise scalar quantisation with one scale per group of g weights: Appendix A.3
  *     ("Basic Quantization");
+ *   - orc_moe_forward_shared: the same layer on SHARED 2D-tiled factors (Eq. 4 with the placement table phi),
+ *     every projection's low-rank term in the accumulator form of Section 3.2;
  *   - orc_lotile_forward: the fused low-rank path over shared 2D-tiled factors, LoTileMoE of
  *     Section 3.2 in its defining three-dimensional accumulator form (the construction that ends
  *     in Eq. 15), NOT the compact buffer of Eq. 16 that an implementation would use;
@@ -246,6 +248,97 @@ int32_t orc_moe_forward(const orc_layer *L, const orc_weights *Wt, const float *
     free(xv);
     free(ye);
     free(scratch);
+    return rc;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * The layer on SHARED 2D-tiled factors (Section 3.1, Eq. 4: W_k = U_p Sigma V_q + quantised residual,
+ * {p, q} = phi(k)), each projection's low-rank term evaluated the way Section 3.2 defines the fused path
+ * (the construction ending in Eq. 15), for one vector and one selected expert at a time:
+ *   X_proj = v (U Sigma)_reshape, i.e. the vector projected on EVERY row tile's factor   [M][r]
+ *   accumulator A [M][r N]: zero, except block n of row m, (m, n) = phi(e), which receives X_proj[m]
+ *   out_lr = sum over m of A[m] V_reshape, V_reshape = the N right factors stacked   [r N][N_out]
+ * (the routing weight of the selection is applied by the caller, Eq. 3, exactly as for per-expert factors).
+ * us is [M][K][r], vv is [N][r][N_out], fp16 bit patterns.
+ */
+typedef struct {
+    const uint16_t *us[3]; /* per projection (gate, up, down): [M][K_p][r] */
+    const uint16_t *v[3];  /* per projection: [N][r][N_p] */
+    const int32_t *phi;    /* [E+S][2] */
+    int32_t M, N;
+} orc_shared;
+
+void orc_project_shared(const double *v, const uint8_t *q, const uint16_t *scale, const uint16_t *zero,
+                        const uint16_t *us, const uint16_t *vv, int32_t M, int32_t Nt, int32_t m_e, int32_t n_e,
+                        int32_t Nout, int32_t K, int32_t g, int32_t r, double *out)
+{
+    int32_t G = K / g;
+    const size_t rN = (size_t)r * Nt;
+    double *xproj = (double *)malloc(sizeof(double) * (size_t)M * r);
+    double *acc = (double *)calloc((size_t)M * rN, sizeof(double));
+    for (int32_t m = 0; m < M; ++m)
+        for (int32_t rho = 0; rho < r; ++rho) {
+            double a = 0.0;
+            for (int32_t kk = 0; kk < K; ++kk) a += v[kk] * orc_half_to_double(us[((size_t)m * K + kk) * r + rho]);
+            xproj[(size_t)m * r + rho] = a;
+        }
+    for (int32_t rho = 0; rho < r; ++rho) acc[(size_t)m_e * rN + (size_t)n_e * r + rho] += xproj[(size_t)m_e * r + rho];
+#pragma omp parallel for schedule(static)
+    for (int32_t n = 0; n < Nout; ++n) {
+        double a = 0.0;
+        for (int32_t gi = 0; gi < G; ++gi) {
+            double s = orc_half_to_double(scale[(size_t)n * G + gi]);
+            double z = orc_half_to_double(zero[(size_t)n * G + gi]);
+            for (int32_t kk = gi * g; kk < (gi + 1) * g; ++kk)
+                a += v[kk] * (((double)q[(size_t)n * K + kk] - z) * s);
+        }
+        double lr = 0.0;
+        for (int32_t m = 0; m < M; ++m)
+            for (int32_t nt = 0; nt < Nt; ++nt)
+                for (int32_t rho = 0; rho < r; ++rho)
+                    lr += acc[(size_t)m * rN + (size_t)nt * r + rho] * orc_half_to_double(vv[((size_t)nt * r + rho) * Nout + n]);
+        out[n] = a + lr;
+    }
+    free(xproj);
+    free(acc);
+}
+
+/* Eq. 3 over experts whose three projections use the shared factors; same conventions as orc_moe_forward
+ * (Wt->A and Wt->B are not read). */
+int32_t orc_moe_forward_shared(const orc_layer *L, const orc_weights *Wt, const orc_shared *Sh, const float *x,
+                               const int32_t *idx, const float *w, int32_t T, const int32_t *tokens,
+                               int32_t n_tokens, double *y)
+{
+    int32_t H = L->hidden, F = L->ffn, k = L->top_k, E = L->n_experts, S = L->n_shared, g = L->group, r = L->rank;
+    size_t HF = (size_t)H * F, HFg = HF / g;
+    double *xv = (double *)malloc(sizeof(double) * (size_t)H);
+    double *ye = (double *)malloc(sizeof(double) * (size_t)H);
+    double *Gv = (double *)malloc(sizeof(double) * 3 * (size_t)F), *Uv = Gv + F, *hv = Gv + 2 * (size_t)F;
+    int32_t rc = 0;
+    for (int32_t i = 0; i < n_tokens && rc == 0; ++i) {
+        int32_t t = tokens ? tokens[i] : i;
+        if (t < 0 || t >= T) { rc = -1; break; }
+        for (int32_t c = 0; c < H; ++c) xv[c] = (double)x[(size_t)t * H + c];
+        double *yt = y + (size_t)i * H;
+        for (int32_t c = 0; c < H; ++c) yt[c] = 0.0;
+        for (int32_t j = 0; j < k + S; ++j) {
+            int32_t e = j < k ? idx[(size_t)t * k + j] : E + (j - k);
+            if (j < k && (e < 0 || e >= E)) { rc = -1; break; }
+            int32_t m_e = Sh->phi[2 * e], n_e = Sh->phi[2 * e + 1];
+            if (m_e < 0 || m_e >= Sh->M || n_e < 0 || n_e >= Sh->N) { rc = -1; break; }
+            const uint8_t *cq = Wt->codes + (size_t)e * 3 * HF;
+            const uint16_t *cs = Wt->scale + (size_t)e * 3 * HFg, *cz = Wt->zero + (size_t)e * 3 * HFg;
+            orc_project_shared(xv, cq, cs, cz, Sh->us[0], Sh->v[0], Sh->M, Sh->N, m_e, n_e, F, H, g, r, Gv);
+            orc_project_shared(xv, cq + HF, cs + HFg, cz + HFg, Sh->us[1], Sh->v[1], Sh->M, Sh->N, m_e, n_e, F, H, g, r, Uv);
+            for (int32_t f = 0; f < F; ++f) hv[f] = orc_silu(Gv[f]) * Uv[f];
+            orc_project_shared(hv, cq + 2 * HF, cs + 2 * HFg, cz + 2 * HFg, Sh->us[2], Sh->v[2], Sh->M, Sh->N, m_e, n_e, H, F, g, r, ye);
+            double wj = j < k ? (double)w[(size_t)t * k + j] : 1.0;
+            for (int32_t c = 0; c < H; ++c) yt[c] += wj * ye[c];
+        }
+    }
+    free(xv);
+    free(ye);
+    free(Gv);
     return rc;
 }
 

@@ -21,7 +21,7 @@ TQ_LOTILE_FP8 = 1
 STATUS_NAMES = {0: "TQ_OK", 1: "TQ_ERR_NULL", 2: "TQ_ERR_SHAPE", 3: "TQ_ERR_ALIGN", 4: "TQ_ERR_RANGE",
                 5: "TQ_ERR_WORKSPACE", 6: "TQ_ERR_UNSUPPORTED", 7: "TQ_ERR_HIP", 8: "TQ_ERR_BLOB"}
 
-EXPORTS = ["tq_init", "tq_status_str", "tq_packed_size", "tq_pack_weights", "tq_unpack_weights", "tq_route",
+EXPORTS = ["tq_init", "tq_status_str", "tq_packed_size", "tq_pack_weights", "tq_pack_weights_shared", "tq_unpack_weights", "tq_route",
            "tq_permute_workspace_size", "tq_permute", "tq_moe_workspace_size", "tq_moe_forward", "tq_moe_forward_static",
            "tq_set_profile_events", "tq_debug_stream", "tq_lotile_packed_size", "tq_lotile_pack", "tq_lotile_pack_fp8",
            "tq_lotile_workspace_size", "tq_lotile_forward", "tq_lotile_grid", "tq_lotile_place"]
@@ -35,7 +35,8 @@ class TqError(RuntimeError):
 
 class LayerDesc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("n_experts", "n_shared", "top_k", "hidden", "ffn", "group", "bits", "rank", "act_dtype", "flags")]
+                ("n_experts", "n_shared", "top_k", "hidden", "ffn", "group", "bits", "rank", "act_dtype", "flags",
+                 "tiles_m", "tiles_n")]
 
 
 class LoTileDesc(ctypes.Structure):
@@ -46,6 +47,10 @@ class LoTileDesc(ctypes.Structure):
 class _WeightsPtrs(ctypes.Structure):
     _fields_ = [("codes", ctypes.c_void_p), ("scale", ctypes.c_void_p), ("zero", ctypes.c_void_p),
                 ("A", ctypes.c_void_p), ("B", ctypes.c_void_p)]
+
+
+class _SharedPtrs(ctypes.Structure):
+    _fields_ = [("us", ctypes.c_void_p * 3), ("v", ctypes.c_void_p * 3), ("phi", ctypes.c_void_p)]
 
 
 _lib = None
@@ -71,6 +76,10 @@ def lib():
         L.tq_pack_weights.restype = ctypes.c_int
         L.tq_pack_weights.argtypes = [ctypes.POINTER(LayerDesc), ctypes.POINTER(_WeightsPtrs), ctypes.c_void_p,
                                       ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+        L.tq_pack_weights_shared.restype = ctypes.c_int
+        L.tq_pack_weights_shared.argtypes = [ctypes.POINTER(LayerDesc), ctypes.POINTER(_WeightsPtrs),
+                                             ctypes.POINTER(_SharedPtrs), ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                             ctypes.c_void_p]
         L.tq_unpack_weights.restype = ctypes.c_int
         L.tq_unpack_weights.argtypes = [ctypes.POINTER(LayerDesc), ctypes.c_void_p, ctypes.POINTER(_WeightsPtrs),
                                         ctypes.c_void_p]
@@ -132,8 +141,8 @@ def _check(rc: int, where: str) -> None:
         raise TqError(rc, where)
 
 
-def make_desc(E, S, k, H, F, g, bits, r, act_dtype=TQ_ACT_BF16, flags=0) -> LayerDesc:
-    return LayerDesc(E, S, k, H, F, g, bits, r, act_dtype, flags)
+def make_desc(E, S, k, H, F, g, bits, r, act_dtype=TQ_ACT_BF16, flags=0, tiles_m=0, tiles_n=0) -> LayerDesc:
+    return LayerDesc(E, S, k, H, F, g, bits, r, act_dtype, flags, tiles_m, tiles_n)
 
 
 def tq_init() -> None:
@@ -164,6 +173,22 @@ def tq_pack_weights(desc: LayerDesc, codes, scale, zero, A=None, B=None, packed=
     rc = lib().tq_pack_weights(ctypes.byref(desc), ctypes.byref(src), _ptr(packed), packed.numel(),
                                _ptr(err_flag), _stream())
     _check(rc, "tq_pack_weights")
+    return packed
+
+
+def tq_pack_weights_shared(desc: LayerDesc, codes, scale, zero, us, v, phi, packed=None, err_flag=None):
+    """As tq_pack_weights for shared 2D-tiled factors: us / v are 3-lists (gate, up, down) of fp16-bit tensors
+    [M, K_p, r] / [N, r, N_p], phi int32 [E+S, 2]."""
+    n = tq_packed_size(desc)
+    if n == 0:
+        raise TqError(2, "tq_packed_size")
+    if packed is None:
+        packed = torch.empty(n, dtype=torch.uint8, device=codes.device)
+    src = _WeightsPtrs(_ptr(codes), _ptr(scale), _ptr(zero), None, None)
+    sh = _SharedPtrs((ctypes.c_void_p * 3)(*[_ptr(t) for t in us]), (ctypes.c_void_p * 3)(*[_ptr(t) for t in v]), _ptr(phi))
+    rc = lib().tq_pack_weights_shared(ctypes.byref(desc), ctypes.byref(src), ctypes.byref(sh), _ptr(packed), packed.numel(),
+                                      _ptr(err_flag), _stream())
+    _check(rc, "tq_pack_weights_shared")
     return packed
 
 

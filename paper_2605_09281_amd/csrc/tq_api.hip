@@ -221,7 +221,7 @@ tq_status forward_impl(const tq_layer_desc* desc, const void* packed, const void
     const bool with_pre = desc->act_dtype == TQ_ACT_BF16 && tqi_bf16_takes_skinny(L, W, desc->flags) && tqi_pre_by_assign(L, W);
     if (with_pre) {
         pre.x = (const uint16_t*)x; pre.blob = (const uint8_t*)packed; pre.expert_stride = L.expert_stride;
-        pre.afrag_off = L.gu.afrag; pre.tpart = (float*)(ws + W.tpart); pre.H = L.H;
+        pre.sec = L.gu; pre.fm = L.fm; pre.tpart = (float*)(ws + W.tpart); pre.H = L.H;
         pre.n_slices = (L.H + 255) / 256; pre.na_tiles = L.gu.na_tiles; pre.a_tot = W.a_tot;
     }
     tq_status rc = tqi_launch_permute(topk_idx, topk_w, T, L.E, L.S, L.k, (int32_t*)(ws + W.offsets),

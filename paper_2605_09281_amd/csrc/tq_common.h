@@ -30,8 +30,18 @@ struct TqSection {
     size_t codes, sz, zc, bfrag, afrag, end;
 };
 
+// Where the factor fragments of an expert live: inside its record, or (shared 2D-tiled factors) in per-tile blocks
+// behind the records, found through the placement table.  Index 0: section GU, 1: section D.
+struct TqFactorMap {
+    int32_t shared, M, N, pad;
+    size_t phi_off;                       // byte offsets from the start of the blob
+    size_t apool[2], astride[2];          // block m of the left factors at apool + m * astride (afrag layout)
+    size_t bpool[2], bstride[2];          // block n of the right factors at bpool + n * bstride (bfrag layout)
+};
+
 struct TqLayout {
     int32_t E, S, k, H, F, g, bits, r, r16;
+    TqFactorMap fm;
     int32_t cw;      // 32-bit words of codes per (lane, 64-wide chunk, tile): 4 (4-bit slots), 3 or 2 (dense 3- / 2-bit)
     TqSection gu, d;
     size_t expert_stride;
@@ -42,6 +52,7 @@ struct TqBlobHeader {
     uint32_t magic, version;
     int32_t n_experts, n_shared, hidden, ffn, group, bits, rank, r16;
     int32_t code_words, reserved;       // TqLayout::cw
+    int32_t tiles_m, tiles_n;           // 0, 0: per-expert factors
     uint64_t expert_stride, total_bytes;
     uint64_t off[10];  // gu.codes, gu.sz, gu.zc, gu.bfrag, gu.afrag, then the same five of d
 };
@@ -64,6 +75,9 @@ __host__ inline bool tq_make_layout(const tq_layer_desc* d, TqLayout* L)
     if (dense && d->group < 64) return false;       // dense codes: groups of 64 and more
     if (d->rank < 0 || d->rank > 256) return false;
     if (d->act_dtype != TQ_ACT_BF16 && d->act_dtype != TQ_ACT_FP32) return false;
+    const bool shared = d->tiles_m > 0 || d->tiles_n > 0;
+    if (d->tiles_m < 0 || d->tiles_n < 0 || (shared && (d->tiles_m < 1 || d->tiles_n < 1))) return false;
+    if (shared && (d->rank < 1 || d->tiles_m > 4096 || d->tiles_n > 4096)) return false;
     L->E = d->n_experts; L->S = d->n_shared; L->k = d->top_k; L->H = d->hidden; L->F = d->ffn;
     L->g = d->group; L->bits = d->bits; L->r = d->rank; L->r16 = (d->rank + 15) / 16 * 16;
     L->cw = dense ? d->bits : 4;
@@ -74,14 +88,30 @@ __host__ inline bool tq_make_layout(const tq_layer_desc* d, TqLayout* L)
         s.sz = off;    off += (size_t)pairs * s.groups * 256;
         s.zsteps = dense ? 0 : 3 * ((s.groups + 15) / 16);     // only the MFMA prefill kernels read this part
         s.zc = off;    off += (size_t)pairs * s.zsteps * 2048;
-        s.bfrag = off; off += (size_t)pairs * (L->r16 / 16) * 2048;
-        s.afrag = off; off += (size_t)s.na_tiles * (K / 16) * 1024;
+        // shared factors: the records hold no factor parts (their geometry, na_tiles, still describes the blocks)
+        s.bfrag = off; off += shared ? 0 : (size_t)pairs * (L->r16 / 16) * 2048;
+        s.afrag = off; off += shared ? 0 : (size_t)s.na_tiles * (K / 16) * 1024;
         s.end = off;
     };
     fill(L->gu, L->F / 32, L->H, 2 * L->r16);
     fill(L->d, L->H / 64, L->F, L->r16);
     L->expert_stride = tq_align256(off);
     L->total_bytes = TQ_HEADER_BYTES + (size_t)(L->E + L->S) * L->expert_stride;
+    TqFactorMap& fm = L->fm;
+    fm = TqFactorMap{};
+    if (shared) {
+        fm.shared = 1; fm.M = d->tiles_m; fm.N = d->tiles_n;
+        size_t o = L->total_bytes;
+        fm.phi_off = o; o += tq_align256((size_t)(L->E + L->S) * 8);
+        const TqSection* secs[2] = {&L->gu, &L->d};
+        for (int i = 0; i < 2; ++i) {
+            fm.astride[i] = (size_t)secs[i]->na_tiles * (secs[i]->K / 16) * 1024;
+            fm.bstride[i] = (size_t)secs[i]->pairs * (L->r16 / 16) * 2048;
+            fm.apool[i] = o; o += (size_t)fm.M * fm.astride[i];
+            fm.bpool[i] = o; o += (size_t)fm.N * fm.bstride[i];
+        }
+        L->total_bytes = tq_align256(o);
+    }
     return true;
 }
 
@@ -186,6 +216,22 @@ __device__ inline float tq_half_bits_to_float(uint16_t h)
     return __half2float(__ushort_as_half(h));
 }
 
+// base of the left (afrag layout) / right (bfrag layout) factor fragments of expert e in section sec_id (0 GU, 1 D)
+__device__ inline const uint8_t* tq_afrag_base(const uint8_t* blob, size_t expert_stride, const TqSection& sec,
+                                               const TqFactorMap& fm, int sec_id, int e)
+{
+    if (!fm.shared) return blob + TQ_HEADER_BYTES + (size_t)e * expert_stride + sec.afrag;
+    const int m = reinterpret_cast<const int32_t*>(blob + fm.phi_off)[2 * e];
+    return blob + fm.apool[sec_id] + (size_t)m * fm.astride[sec_id];
+}
+__device__ inline const uint8_t* tq_bfrag_base(const uint8_t* blob, size_t expert_stride, const TqSection& sec,
+                                               const TqFactorMap& fm, int sec_id, int e)
+{
+    if (!fm.shared) return blob + TQ_HEADER_BYTES + (size_t)e * expert_stride + sec.bfrag;
+    const int n = reinterpret_cast<const int32_t*>(blob + fm.phi_off)[2 * e + 1];
+    return blob + fm.bpool[sec_id] + (size_t)n * fm.bstride[sec_id];
+}
+
 // expert owning slot `s`: largest e with offsets[e] <= s (offsets is non-decreasing, n+1 entries)
 __device__ inline int tq_find_expert(const int32_t* __restrict__ offsets, int n, int s)
 {
@@ -206,7 +252,9 @@ __device__ inline int tq_find_expert(const int32_t* __restrict__ offsets, int n,
 struct TqPreByAssign {
     const uint16_t* x;       // [T][H] bf16
     const uint8_t* blob;
-    size_t expert_stride, afrag_off;
+    size_t expert_stride;
+    TqSection sec;           // section GU
+    TqFactorMap fm;
     float* tpart;
     int32_t H, n_slices, na_tiles, a_tot;
 };

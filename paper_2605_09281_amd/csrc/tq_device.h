@@ -14,6 +14,7 @@ struct MGeom {
     int32_t ne, H, F, g, r, r16, k, S, a_tot;
     uint32_t unpack_mask, unpack_magic;   // 0x000F000F, 0x43004300 (see unpack_word)
     size_t expert_stride;
+    TqFactorMap fm;
 };
 
 union Frag {

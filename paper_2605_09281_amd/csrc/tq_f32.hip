@@ -9,6 +9,7 @@ namespace {
 struct F32Geom {
     int32_t ne, H, F, g, r, r16, k, S, cw;
     size_t expert_stride;
+    TqFactorMap fm;
 };
 
 __device__ inline float silu_f32(float v) { return v / (1.0f + expf(-v)); }
@@ -49,7 +50,7 @@ __global__ void __launch_bounds__(256) f32_proj_kernel(F32Geom G, TqSection sec,
     const int col = lane & 31, hf = lane >> 5;
     // t[c] = sum_kk x[kk] * A[kk][c]
     if (G.r > 0) {
-        const uint16_t* af = reinterpret_cast<const uint16_t*>(rec + sec.afrag);
+        const uint16_t* af = reinterpret_cast<const uint16_t*>(tq_afrag_base(blob, G.expert_stride, sec, G.fm, STAGE, e));
         const int ksteps = K / 16;
         for (int c = wave; c < NA; c += 4) {
             const int ta = c >> 5, cl = c & 31;
@@ -106,7 +107,8 @@ __global__ void __launch_bounds__(256) f32_proj_kernel(F32Geom G, TqSection sec,
         }
         acc = fmaf(part, s, acc);
         if (G.r > 0) {
-            const uint4* bf = reinterpret_cast<const uint4*>(rec + sec.bfrag) + ((size_t)pair * (G.r16 / 16) * 2 + tile) * 64 + lane;
+            const uint4* bf = reinterpret_cast<const uint4*>(tq_bfrag_base(blob, G.expert_stride, sec, G.fm, STAGE, e)) +
+                              ((size_t)pair * (G.r16 / 16) * 2 + tile) * 64 + lane;
             const float* tp = ts + (STAGE == 0 ? tile * G.r16 : 0);
             float lr = 0.f;
             for (int st = 0; st < G.r16 / 16; ++st) {
@@ -159,7 +161,7 @@ tq_status tqi_forward_f32(const TqLayout& L, const TqWorkspace& W, const uint8_t
 {
     F32Geom G;
     G.ne = L.E + L.S; G.H = L.H; G.F = L.F; G.g = L.g; G.r = L.r; G.r16 = L.r16; G.k = L.k; G.S = L.S;
-    G.expert_stride = L.expert_stride; G.cw = L.cw;
+    G.expert_stride = L.expert_stride; G.cw = L.cw; G.fm = L.fm;
     const int32_t* ctrl = reinterpret_cast<const int32_t*>(ws + W.ctrl);
     const int32_t* offsets = reinterpret_cast<const int32_t*>(ws + W.offsets);
     const int32_t* slot_of = reinterpret_cast<const int32_t*>(ws + W.slot_of);

@@ -54,8 +54,7 @@ __global__ void __launch_bounds__(256) aug_kernel(MGeom G, TqSection sec, const 
         const int m = min(32 * i + col, rows - 1);
         xrow[i] = STAGE == 0 ? xin + (size_t)row_token[slot0 + m] * K : xin + (size_t)(slot0 + m) * K;
     }
-    const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
-    const u32x4* af = reinterpret_cast<const u32x4*>(rec + sec.afrag);
+    const u32x4* af = reinterpret_cast<const u32x4*>(tq_afrag_base(blob, G.expert_stride, sec, G.fm, STAGE, e));
     uint16_t* orow = xaug + (size_t)(slot0 + col) * ka;     // row 32 i + col is at orow + 32 i ka
     const int unit_steps = (G.g < 64 ? 64 : G.g) / 16;
     const int NU = ksteps / unit_steps;
@@ -193,7 +192,8 @@ __global__ void __launch_bounds__(256, NAT == 1 ? 3 : 2) aug_staged_kernel(MGeom
     const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
     // layers without factors have an empty fragment section: their (unconditional, unused) fragment loads all read
     // the first kilobyte of the codes instead of running past the record
-    const u32x4* af = reinterpret_cast<const u32x4*>(rec + (na_tiles > 0 ? sec.afrag : sec.codes)) + lane;
+    const u32x4* af = reinterpret_cast<const u32x4*>(na_tiles > 0 ? tq_afrag_base(blob, G.expert_stride, sec, G.fm, STAGE, e)
+                                                                  : rec + sec.codes) + lane;
     const size_t af_live = na_tiles > 0 ? 1 : 0;
     uint16_t* orow = xaug + (size_t)(slot0 + col) * ka;
     const bool writer = (hf == 0) && (col < rows);
@@ -375,7 +375,8 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
     const u32x4* codes = reinterpret_cast<const u32x4*>(rec + sec.codes) + (size_t)pair * sec.chunks * 128 + lane;
     const uint32_t* szp = reinterpret_cast<const uint32_t*>(rec + sec.sz) + (size_t)pair * sec.groups * 64 + col;
     const u32x4* zcp = reinterpret_cast<const u32x4*>(rec + sec.zc) + (size_t)pair * sec.zsteps * 128 + lane;
-    const u32x4* bfr = reinterpret_cast<const u32x4*>(rec + sec.bfrag) + (size_t)pair * (G.r16 / 16) * 128 + lane;
+    const u32x4* bfr = reinterpret_cast<const u32x4*>(G.r > 0 ? tq_bfrag_base(blob, G.expert_stride, sec, G.fm, STAGE, e)
+                                                               : rec + sec.bfrag) + (size_t)pair * (G.r16 / 16) * 128 + lane;
 
     const int NU = K / UNIT_K;
     const int u0 = (int)((long)split * NU / nsplit), u1 = (int)((long)(split + 1) * NU / nsplit);
@@ -804,7 +805,7 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     if (L.r16 > 128) return TQ_ERR_UNSUPPORTED;
     MGeom G;
     G.ne = L.E + L.S; G.H = L.H; G.F = L.F; G.g = L.g; G.r = L.r; G.r16 = L.r16; G.k = L.k; G.S = L.S;
-    G.a_tot = W.a_tot; G.expert_stride = L.expert_stride;
+    G.a_tot = W.a_tot; G.expert_stride = L.expert_stride; G.fm = L.fm;
     G.unpack_mask = 0x000F000Fu; G.unpack_magic = 0x43004300u;
     const int32_t* ctrl = reinterpret_cast<const int32_t*>(ws + W.ctrl);
     const int32_t* offsets = reinterpret_cast<const int32_t*>(ws + W.offsets);

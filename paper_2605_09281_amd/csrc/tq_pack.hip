@@ -312,6 +312,91 @@ __global__ void afrag_kernel(PackGeom G, uint8_t* __restrict__ blob, uint16_t* _
     }
 }
 
+// Shared 2D-tiled factors.  Left factors: one thread per 8-element fragment of block (section, m); the block has the
+// afrag layout, its columns being [gate factor | up factor] (r16 each) in section GU and the down factor in D.
+__global__ void pool_afrag_kernel(PackGeom G, TqFactorMap fm, uint8_t* __restrict__ blob,
+                                  const uint16_t* __restrict__ us_g, const uint16_t* __restrict__ us_u,
+                                  const uint16_t* __restrict__ us_d)
+{
+    const size_t n_gu = (size_t)G.gu.na_tiles * (G.gu.K / 16) * 64;     // fragments per block
+    const size_t n_d = (size_t)G.d.na_tiles * (G.d.K / 16) * 64;
+    const size_t per_m = n_gu + n_d;
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= per_m * fm.M) return;
+    const int m = (int)(idx / per_m);
+    size_t w = idx % per_m;
+    const bool is_d = w >= n_gu;
+    const TqSection& sec = is_d ? G.d : G.gu;
+    if (is_d) w -= n_gu;
+    const int lane = (int)(w & 63);
+    const size_t ts = w >> 6;
+    const int ksteps = sec.K / 16;
+    const int step = (int)(ts % ksteps), ta = (int)(ts / ksteps);
+    const int c = 32 * ta + (lane & 31), hf = lane >> 5;
+    const int na = is_d ? G.r16 : 2 * G.r16;
+    const int p = is_d ? 2 : (c / G.r16);
+    const int rho = c % G.r16;
+    const bool live = (c < na) && (rho < G.r);
+    const uint16_t* src = (p == 0 ? us_g : p == 1 ? us_u : us_d) + (size_t)m * sec.K * G.r;      // [K][r] of tile row m
+    uint16_t* dst = reinterpret_cast<uint16_t*>(blob + fm.apool[is_d] + (size_t)m * fm.astride[is_d]) + w * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int kk = 16 * step + 8 * hf + i;
+        dst[i] = live ? src[(size_t)kk * G.r + rho] : (uint16_t)0;
+    }
+}
+
+// Right factors: one thread per 8-element fragment of block (section, n), in the bfrag layout (tile 0 / 1 of a pair:
+// gate / up factor in section GU, the two 32-column halves of the down factor's 64 columns in D).
+__global__ void pool_bfrag_kernel(PackGeom G, TqFactorMap fm, uint8_t* __restrict__ blob,
+                                  const uint16_t* __restrict__ v_g, const uint16_t* __restrict__ v_u,
+                                  const uint16_t* __restrict__ v_d)
+{
+    const int steps = G.r16 / 16;
+    const size_t n_gu = (size_t)G.gu.pairs * steps * 128;
+    const size_t n_d = (size_t)G.d.pairs * steps * 128;
+    const size_t per_n = n_gu + n_d;
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= per_n * fm.N) return;
+    const int nt = (int)(idx / per_n);
+    size_t w = idx % per_n;
+    const bool is_d = w >= n_gu;
+    if (is_d) w -= n_gu;
+    const int lane = (int)(w & 63), tile = (int)((w >> 6) & 1);
+    const size_t ps = w >> 7;
+    const int step = (int)(ps % steps), pair = (int)(ps / steps);
+    const int col = lane & 31, hf = lane >> 5;
+    int p, n, N;
+    if (!is_d) { p = tile; n = 32 * pair + col; N = G.F; }
+    else       { p = 2;    n = 64 * pair + 32 * tile + col; N = G.H; }
+    const uint16_t* src = (p == 0 ? v_g : p == 1 ? v_u : v_d) + (size_t)nt * G.r * N;              // [r][N] of tile column nt
+    uint16_t* dst = reinterpret_cast<uint16_t*>(blob + fm.bpool[is_d] + (size_t)nt * fm.bstride[is_d]) + w * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int rho = 16 * step + 8 * hf + i;
+        dst[i] = (rho < G.r) ? src[(size_t)rho * N + n] : (uint16_t)0;
+    }
+}
+
+__global__ void phi_kernel(TqFactorMap fm, int n_exp, int n_padded, uint8_t* __restrict__ blob, const int32_t* __restrict__ phi,
+                           int32_t* __restrict__ err_flag)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n_padded) return;
+    int m = 0, n = 0;                    // entries of the padding behind the table are written as zeros
+    if (e < n_exp) {
+        m = phi[2 * e]; n = phi[2 * e + 1];
+        if (m < 0 || m >= fm.M || n < 0 || n >= fm.N) {
+            if (err_flag) atomicOr(err_flag, TQ_FLAG_BIT_RANGE);
+            m = min(max(m, 0), fm.M - 1);
+            n = min(max(n, 0), fm.N - 1);
+        }
+    }
+    int32_t* dst = reinterpret_cast<int32_t*>(blob + fm.phi_off);
+    dst[2 * e] = m;
+    dst[2 * e + 1] = n;
+}
+
 inline PackGeom make_geom(const TqLayout& L)
 {
     PackGeom G;
@@ -347,7 +432,7 @@ tq_status run(const TqLayout& L, uint8_t* blob, uint8_t* codes, uint16_t* scale,
         hipLaunchKernelGGL(zc_kernel, dim3(blocks_for(n_zc)), dim3(256), 0, st, G, blob, scale, zero);
         TQ_CHECK_LAUNCH();
     }
-    if (L.r > 0) {
+    if (L.r > 0 && !L.fm.shared) {
         size_t n_b = ((size_t)L.gu.pairs + L.d.pairs) * (L.r16 / 16) * 128 * ne;
         size_t n_a = ((size_t)L.gu.na_tiles * (L.gu.K / 16) + (size_t)L.d.na_tiles * (L.d.K / 16)) * 64 * ne;
         hipLaunchKernelGGL(bfrag_kernel<PACK>, dim3(blocks_for(n_b)), dim3(256), 0, st, G, blob, B);
@@ -369,16 +454,44 @@ extern "C" size_t tq_packed_size(const tq_layer_desc* desc)
     return L.total_bytes;
 }
 
+namespace {
+tq_status pack_impl(const tq_layer_desc* desc, const tq_weights_src* src, const tq_shared_factors* shared, void* packed,
+                    size_t packed_bytes, int32_t* err_flag, void* stream);
+}
+
 extern "C" tq_status tq_pack_weights(const tq_layer_desc* desc, const tq_weights_src* src, void* packed,
                                      size_t packed_bytes, int32_t* err_flag, void* stream)
+{
+    if (desc && (desc->tiles_m || desc->tiles_n)) return TQ_ERR_SHAPE;      // shared factors: tq_pack_weights_shared
+    return pack_impl(desc, src, nullptr, packed, packed_bytes, err_flag, stream);
+}
+
+extern "C" tq_status tq_pack_weights_shared(const tq_layer_desc* desc, const tq_weights_src* src,
+                                            const tq_shared_factors* shared, void* packed, size_t packed_bytes,
+                                            int32_t* err_flag, void* stream)
+{
+    if (!shared) return TQ_ERR_NULL;
+    if (desc && !(desc->tiles_m > 0 && desc->tiles_n > 0)) return TQ_ERR_SHAPE;
+    for (int p = 0; p < 3; ++p) {
+        if (!shared->us[p] || !shared->v[p]) return TQ_ERR_NULL;
+        if ((((uintptr_t)shared->us[p]) | ((uintptr_t)shared->v[p])) & 15) return TQ_ERR_ALIGN;
+    }
+    if (!shared->phi) return TQ_ERR_NULL;
+    if ((uintptr_t)shared->phi & 3) return TQ_ERR_ALIGN;
+    return pack_impl(desc, src, shared, packed, packed_bytes, err_flag, stream);
+}
+
+namespace {
+tq_status pack_impl(const tq_layer_desc* desc, const tq_weights_src* src, const tq_shared_factors* shared, void* packed,
+                    size_t packed_bytes, int32_t* err_flag, void* stream)
 {
     if (!desc || !src || !packed || !src->codes || !src->scale || !src->zero) return TQ_ERR_NULL;
     TqLayout L;
     if (!tq_make_layout(desc, &L)) return TQ_ERR_SHAPE;
-    if (L.r > 0 && (!src->A || !src->B)) return TQ_ERR_NULL;
+    if (L.r > 0 && !L.fm.shared && (!src->A || !src->B)) return TQ_ERR_NULL;
     if (packed_bytes < L.total_bytes) return TQ_ERR_WORKSPACE;
     if (misaligned(packed, 256) || misaligned(src->codes, 16) || misaligned(src->scale, 16) ||
-        misaligned(src->zero, 16) || (L.r > 0 && (misaligned(src->A, 16) || misaligned(src->B, 16))) ||
+        misaligned(src->zero, 16) || (L.r > 0 && !L.fm.shared && (misaligned(src->A, 16) || misaligned(src->B, 16))) ||
         misaligned(err_flag, 4))
         return TQ_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
@@ -386,15 +499,32 @@ extern "C" tq_status tq_pack_weights(const tq_layer_desc* desc, const tq_weights
     hdr.magic = TQ_BLOB_MAGIC; hdr.version = TQ_BLOB_VERSION;
     hdr.n_experts = L.E; hdr.n_shared = L.S; hdr.hidden = L.H; hdr.ffn = L.F; hdr.group = L.g;
     hdr.bits = L.bits; hdr.rank = L.r; hdr.r16 = L.r16; hdr.code_words = L.cw;
+    hdr.tiles_m = L.fm.M; hdr.tiles_n = L.fm.N;
     hdr.expert_stride = L.expert_stride; hdr.total_bytes = L.total_bytes;
     hdr.off[0] = L.gu.codes; hdr.off[1] = L.gu.sz; hdr.off[2] = L.gu.zc; hdr.off[3] = L.gu.bfrag; hdr.off[4] = L.gu.afrag;
     hdr.off[5] = L.d.codes; hdr.off[6] = L.d.sz; hdr.off[7] = L.d.zc; hdr.off[8] = L.d.bfrag; hdr.off[9] = L.d.afrag;
     hipLaunchKernelGGL(write_header_kernel, dim3(1), dim3(64), 0, st, hdr, (uint8_t*)packed);
     TQ_CHECK_LAUNCH();
-    return run<true>(L, (uint8_t*)packed, const_cast<uint8_t*>(src->codes), const_cast<uint16_t*>(src->scale),
-                     const_cast<uint16_t*>(src->zero), const_cast<uint16_t*>(src->A),
-                     const_cast<uint16_t*>(src->B), err_flag, st);
+    tq_status rc = run<true>(L, (uint8_t*)packed, const_cast<uint8_t*>(src->codes), const_cast<uint16_t*>(src->scale),
+                             const_cast<uint16_t*>(src->zero), const_cast<uint16_t*>(src->A),
+                             const_cast<uint16_t*>(src->B), err_flag, st);
+    if (rc != TQ_OK || !L.fm.shared) return rc;
+    const PackGeom G = make_geom(L);
+    const size_t n_a = ((size_t)L.gu.na_tiles * (L.gu.K / 16) + (size_t)L.d.na_tiles * (L.d.K / 16)) * 64 * L.fm.M;
+    const size_t n_b = ((size_t)L.gu.pairs + L.d.pairs) * (L.r16 / 16) * 128 * L.fm.N;
+    hipLaunchKernelGGL(pool_afrag_kernel, dim3(blocks_for(n_a)), dim3(256), 0, st, G, L.fm, (uint8_t*)packed, shared->us[0],
+                       shared->us[1], shared->us[2]);
+    TQ_CHECK_LAUNCH();
+    hipLaunchKernelGGL(pool_bfrag_kernel, dim3(blocks_for(n_b)), dim3(256), 0, st, G, L.fm, (uint8_t*)packed, shared->v[0],
+                       shared->v[1], shared->v[2]);
+    TQ_CHECK_LAUNCH();
+    const int n_padded = (int)(tq_align256((size_t)(L.E + L.S) * 8) / 8);
+    hipLaunchKernelGGL(phi_kernel, dim3(blocks_for((size_t)n_padded)), dim3(256), 0, st, L.fm, L.E + L.S, n_padded,
+                       (uint8_t*)packed, shared->phi, err_flag);
+    TQ_CHECK_LAUNCH();
+    return TQ_OK;
 }
+}  // namespace
 
 extern "C" tq_status tq_unpack_weights(const tq_layer_desc* desc, const void* packed, const tq_weights_dst* dst,
                                        void* stream)
@@ -402,9 +532,9 @@ extern "C" tq_status tq_unpack_weights(const tq_layer_desc* desc, const void* pa
     if (!desc || !dst || !packed || !dst->codes || !dst->scale || !dst->zero) return TQ_ERR_NULL;
     TqLayout L;
     if (!tq_make_layout(desc, &L)) return TQ_ERR_SHAPE;
-    if (L.r > 0 && (!dst->A || !dst->B)) return TQ_ERR_NULL;
+    if (L.r > 0 && !L.fm.shared && (!dst->A || !dst->B)) return TQ_ERR_NULL;      // shared factors: codes, scale, zero only
     if (misaligned(packed, 256) || misaligned(dst->codes, 16) || misaligned(dst->scale, 16) ||
-        misaligned(dst->zero, 16) || (L.r > 0 && (misaligned(dst->A, 16) || misaligned(dst->B, 16))))
+        misaligned(dst->zero, 16) || (L.r > 0 && !L.fm.shared && (misaligned(dst->A, 16) || misaligned(dst->B, 16))))
         return TQ_ERR_ALIGN;
     return run<false>(L, const_cast<uint8_t*>((const uint8_t*)packed), dst->codes, dst->scale, dst->zero, dst->A,
                       dst->B, nullptr, (hipStream_t)stream);

@@ -93,7 +93,8 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
         s.codes = reinterpret_cast<const u32x4*>(rec + sec.codes) + (size_t)pair * sec.chunks * 128;
         s.sz = reinterpret_cast<const uint32_t*>(rec + sec.sz) + (size_t)pair * sec.groups * 64;
         s.zc = reinterpret_cast<const u32x4*>(rec + sec.zc) + (size_t)pair * sec.zsteps * 128;
-        s.bf = reinterpret_cast<const u32x4*>(rec + sec.bfrag) + (size_t)pair * (G.r16 / 16) * 128;
+        s.bf = reinterpret_cast<const u32x4*>(G.r > 0 ? tq_bfrag_base(blob, G.expert_stride, sec, G.fm, STAGE, e) : rec + sec.bfrag) +
+               (size_t)pair * (G.r16 / 16) * 128;
         return s;
     };
     // row ids of a tile: rows past the end of the expert read the following (valid, finite) rows; their

@@ -104,7 +104,7 @@ __device__ inline bool blob_header_ok(const TqBlobHeader* hdr, const TqBlobHeade
     return hdr->magic == expect.magic && hdr->version == expect.version && hdr->n_experts == expect.n_experts &&
            hdr->n_shared == expect.n_shared && hdr->hidden == expect.hidden && hdr->ffn == expect.ffn &&
            hdr->group == expect.group && hdr->bits == expect.bits && hdr->rank == expect.rank &&
-           hdr->code_words == expect.code_words &&
+           hdr->code_words == expect.code_words && hdr->tiles_m == expect.tiles_m && hdr->tiles_n == expect.tiles_n &&
            hdr->expert_stride == expect.expert_stride;
 }
 
@@ -421,7 +421,7 @@ __device__ inline void pre_by_assign_block(const TqPreByAssign& P, const int32_t
     const int col = lane & 31, hf = lane >> 5;
     const int ksteps = P.H / 16;
     const uint16_t* xrow = P.x + (size_t)t * P.H;
-    const uint4* af = reinterpret_cast<const uint4*>(P.blob + TQ_HEADER_BYTES + (size_t)e * P.expert_stride + P.afrag_off);
+    const uint4* af = reinterpret_cast<const uint4*>(tq_afrag_base(P.blob, P.expert_stride, P.sec, P.fm, 0, e));
     constexpr int NS = 16;                       // steps per slice
     const int s0 = slice * NS;
     uint4 xa[NS], aq[NS];
@@ -448,8 +448,11 @@ __device__ inline void pre_by_assign_block(const TqPreByAssign& P, const int32_t
     if (hf == 0) P.tpart[(((size_t)v * P.n_slices + slice) * P.na_tiles + ta) * 32 + col] = acc;
 }
 
-__global__ void __launch_bounds__(64) pre_by_assign_kernel(TqPreByAssign P, const int32_t* __restrict__ idx, int T, int E, int k)
+__global__ void __launch_bounds__(64) pre_by_assign_kernel(TqPreByAssign P, const int32_t* __restrict__ idx, int T, int E, int k,
+                                                           const TqBlobHeader* __restrict__ hdr, TqBlobHeader expect,
+                                                           int check_blob)
 {
+    if (check_blob && !blob_header_ok(hdr, expect)) return;      // a blob of another layer is not indexed
     pre_by_assign_block(P, idx, T, E, k, blockIdx.x, threadIdx.x);
 }
 
@@ -469,6 +472,7 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
                                                            TqPreByAssign P, int tilings)
 {
     if (HAS_PRE && blockIdx.x > 0) {
+        if (check_blob && !blob_header_ok(hdr, expect)) return;      // a blob of another layer is not indexed
         pre_by_assign_block(P, idx, T, E, k, blockIdx.x - 1, threadIdx.x);
         return;
     }
@@ -502,7 +506,7 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
         expect.magic = TQ_BLOB_MAGIC; expect.version = TQ_BLOB_VERSION;
         expect.n_experts = L->E; expect.n_shared = L->S; expect.hidden = L->H; expect.ffn = L->F;
         expect.group = L->g; expect.bits = L->bits; expect.rank = L->r; expect.expert_stride = L->expert_stride;
-        expect.code_words = L->cw;
+        expect.code_words = L->cw; expect.tiles_m = L->fm.M; expect.tiles_n = L->fm.N;
     }
     const int ne = E + S;
     if (nblk == 1 && (int64_t)S * T <= 4096) {
@@ -521,7 +525,8 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
         return TQ_OK;
     }
     if (n_pre > 0) {      // the permutation takes several launches: the pre-pass gets its own
-        hipLaunchKernelGGL(pre_by_assign_kernel, dim3((unsigned)n_pre), dim3(64), 0, stream, *pre, topk_idx, T, E, k);
+        hipLaunchKernelGGL(pre_by_assign_kernel, dim3((unsigned)n_pre), dim3(64), 0, stream, *pre, topk_idx, T, E, k,
+                           (const TqBlobHeader*)blob, expect, check);
         TQ_CHECK_LAUNCH();
     }
     if (ctrl) {

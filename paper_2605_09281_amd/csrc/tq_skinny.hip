@@ -51,7 +51,7 @@ __global__ void __launch_bounds__(64) skinny_pre_kernel(MGeom G, TqSection sec, 
     const int K = sec.K, ksteps = K / 16;
     const int r = min(col & 15, rows - 1);
     const uint16_t* xrow = STAGE == 0 ? xin + (size_t)row_token[slot0 + r] * K : xin + (size_t)(slot0 + r) * K;
-    const u32x4* af = reinterpret_cast<const u32x4*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.afrag);
+    const u32x4* af = reinterpret_cast<const u32x4*>(tq_afrag_base(blob, G.expert_stride, sec, G.fm, STAGE, e));
     constexpr int NS = SK_PRE_K / 16;
     const int s0 = slice * NS;
     const int n = min(NS, ksteps - s0);
@@ -130,7 +130,8 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
     const u32x4* codes = reinterpret_cast<const u32x4*>(rec + sec.codes) + lane;
     const uint32_t* szp = reinterpret_cast<const uint32_t*>(rec + sec.sz) + col;
-    const u32x4* bfr = reinterpret_cast<const u32x4*>(rec + sec.bfrag) + lane;
+    const u32x4* bfr = reinterpret_cast<const u32x4*>(G.r > 0 ? tq_bfrag_base(blob, G.expert_stride, sec, G.fm, STAGE, e)
+                                                               : rec + sec.bfrag) + lane;
 
     // Unit and pair indices are clamped into the valid range instead of guarding the loads: a load under a
     // condition makes the compiler wait for ALL outstanding loads at every later use, which would drain the
@@ -571,7 +572,7 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
 {
     MGeom G;
     G.ne = L.E + L.S; G.H = L.H; G.F = L.F; G.g = L.g; G.r = L.r; G.r16 = L.r16; G.k = L.k; G.S = L.S;
-    G.a_tot = W.a_tot; G.expert_stride = L.expert_stride;
+    G.a_tot = W.a_tot; G.expert_stride = L.expert_stride; G.fm = L.fm;
     G.unpack_mask = L.cw == 4 ? 0x000F000Fu : L.cw == 3 ? 0x00070007u : 0x00030003u;
     G.unpack_magic = 0x43004300u;
     const int32_t* ctrl = reinterpret_cast<const int32_t*>(ws + W.ctrl);

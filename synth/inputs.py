@@ -245,6 +245,61 @@ def make_layer(cfg: LayerConfig, workers: int = 8) -> Layer:
 
 # ----------------------------------------------------------------------------- shared 2D-tiled factors
 _TID_LOTILE = 11
+_TID_SHARED_LAYER = 13
+
+
+@dataclasses.dataclass
+class SharedLayer:
+    """A layer whose low-rank factors are shared over a 2D grid of tiles: codes / scale / zero as in Layer, and per
+    projection p (gate, up, down) us[p] [M, K_p, r], v[p] [N, r, N_p] (fp16 bit patterns), phi [E+S, 2] -> (m, n)."""
+    cfg: LayerConfig
+    codes: np.ndarray
+    scale: np.ndarray
+    zero: np.ndarray
+    us: list
+    v: list
+    phi: np.ndarray
+
+    @property
+    def M(self) -> int:
+        return self.us[0].shape[0]
+
+    @property
+    def N(self) -> int:
+        return self.v[0].shape[0]
+
+    def expanded(self) -> "Layer":
+        """The same layer with the factors copied out per expert (A_e = us[m(e)], B_e = v[n(e)]): array gathers only."""
+        c = self.cfg
+        m, n = self.phi[:, 0], self.phi[:, 1]
+        A = np.concatenate([self.us[p][m].reshape(c.n_exp, -1) for p in range(3)], axis=1)
+        B = np.concatenate([self.v[p][n].reshape(c.n_exp, -1) for p in range(3)], axis=1)
+        return Layer(c, self.codes, self.scale, self.zero, np.ascontiguousarray(A), np.ascontiguousarray(B))
+
+
+def make_shared_layer(cfg: LayerConfig, M: Optional[int] = None, N: Optional[int] = None, layer: Optional["Layer"] = None,
+                      degenerate: bool = False, workers: int = 8) -> SharedLayer:
+    """Codes as make_layer (or taken from `layer`), factors ~N(0, f_std) per tile on the near-square grid of the
+    paper (M = round(sqrt(E+S)), N = ceil((E+S) / M)) unless given, phi a seeded permutation of the tiles (drawn
+    with replacement when there are fewer tiles than experts).  degenerate: M = N = E+S, phi(e) = (e, e), and the
+    factors of tile e are the per-expert factors of `layer` (the per-expert format as a special case)."""
+    if layer is None:
+        layer = make_layer(cfg, workers=workers)
+    ne = cfg.n_exp
+    dims = ((cfg.H, cfg.F), (cfg.H, cfg.F), (cfg.F, cfg.H))
+    if degenerate:
+        us = [np.stack([layer.a_matrix(e, p).view(np.uint16) for e in range(ne)]) for p in range(3)]
+        v = [np.stack([layer.b_matrix(e, p).view(np.uint16) for e in range(ne)]) for p in range(3)]
+        phi = np.stack([np.arange(ne), np.arange(ne)], axis=1).astype(np.int32)
+        return SharedLayer(cfg, layer.codes, layer.scale, layer.zero, us, v, phi)
+    if M is None or N is None:
+        M, N = lotile_grid(ne)
+    rng = _rng(cfg.cfg_id, _TID_SHARED_LAYER)
+    us = [(rng.standard_normal((M, K, cfg.r), dtype=np.float32) * cfg.f_std).astype(np.float16).view(np.uint16) for K, _ in dims]
+    v = [(rng.standard_normal((N, cfg.r, No), dtype=np.float32) * cfg.f_std).astype(np.float16).view(np.uint16) for _, No in dims]
+    tiles = rng.permutation(M * N)[:ne] if M * N >= ne else rng.integers(0, M * N, ne)
+    phi = np.stack([tiles // N, tiles % N], axis=1).astype(np.int32)
+    return SharedLayer(cfg, layer.codes, layer.scale, layer.zero, us, v, phi)
 
 
 def lotile_grid(E: int):

@@ -27,7 +27,45 @@ def _align256(n):
     return (n + 255) // 256 * 256
 
 
-def blob_by_definition(layer) -> bytes:
+def factor_parts_by_definition(sec, A, B, H, F, r):
+    """(bfrag, afrag) of one section from A[p] [K, r] and B[p] [r, N] (fp16 bit patterns), element by element."""
+    r16 = (r + 15) // 16 * 16
+    if sec == "GU":
+        K, pairs, na = H, F // 32, 2 * r16
+        col_of = lambda pair, tile, cc: (tile, 32 * pair + cc)
+    else:
+        K, pairs, na = F, H // 64, r16
+        col_of = lambda pair, tile, cc: (2, 64 * pair + 32 * tile + cc)
+    # ---- bfrag: fp16 [pairs][r16/16][2 tiles][64 lanes][8]
+    bpart = bytearray()
+    for pair in range(pairs):
+        for s in range(r16 // 16):
+            for tile in range(2):
+                for lane in range(64):
+                    p, n = col_of(pair, tile, lane % 32)
+                    hf = lane // 32
+                    for i in range(8):
+                        rho = 16 * s + 8 * hf + i
+                        bpart += struct.pack("<H", int(B[p][rho, n]) if rho < r else 0)
+    # ---- afrag: fp16 [ceil(NA/32)][K/16][64 lanes][8]
+    apart = bytearray()
+    for ta in range((na + 31) // 32):
+        for s in range(K // 16):
+            for lane in range(64):
+                hf = lane // 32
+                cc = 32 * ta + lane % 32
+                for i in range(8):
+                    kk = 16 * s + 8 * hf + i
+                    v = 0
+                    if cc < na:
+                        p, rho = (cc // r16, cc % r16) if sec == "GU" else (2, cc)
+                        if rho < r:
+                            v = int(A[p][kk, rho])
+                    apart += struct.pack("<H", v)
+    return bytes(bpart), bytes(apart)
+
+
+def blob_by_definition(layer, with_factors=True) -> bytes:
     c = layer.cfg
     H, F, g, r = c.H, c.F, c.g, c.r
     r16 = (r + 15) // 16 * 16
@@ -114,37 +152,12 @@ def blob_by_definition(layer) -> bytes:
                                     v = hi if s % 3 in (0, 1) else _bf16_rne_scalar(np.float32(cf - _bf16_to_f32(hi)))
                                 part += struct.pack("<H", v)
             rec += part
-            if r > 0:
+            if r > 0 and with_factors:
                 A = [layer.a_matrix(e, p).view(np.uint16) for p in range(3)]
                 B = [layer.b_matrix(e, p).view(np.uint16) for p in range(3)]
-                # ---- bfrag: fp16 [pairs][r16/16][2 tiles][64 lanes][8]
-                part = bytearray()
-                for pair in range(pairs):
-                    for s in range(r16 // 16):
-                        for tile in range(2):
-                            for lane in range(64):
-                                p, n = col_of(pair, tile, lane % 32)
-                                hf = lane // 32
-                                for i in range(8):
-                                    rho = 16 * s + 8 * hf + i
-                                    part += struct.pack("<H", int(B[p][rho, n]) if rho < r else 0)
-                rec += part
-                # ---- afrag: fp16 [ceil(NA/32)][K/16][64 lanes][8]
-                part = bytearray()
-                for ta in range((na + 31) // 32):
-                    for s in range(K // 16):
-                        for lane in range(64):
-                            hf = lane // 32
-                            cc = 32 * ta + lane % 32
-                            for i in range(8):
-                                kk = 16 * s + 8 * hf + i
-                                v = 0
-                                if cc < na:
-                                    p, rho = (cc // r16, cc % r16) if sec == "GU" else (2, cc)
-                                    if rho < r:
-                                        v = int(A[p][kk, rho])
-                                part += struct.pack("<H", v)
-                rec += part
+                bpart, apart = factor_parts_by_definition(sec, A, B, H, F, r)
+                rec += bpart
+                rec += apart
         rec += b"\0" * (_align256(len(rec)) - len(rec))
         out += rec
     return bytes(out)
@@ -188,3 +201,49 @@ def test_pack_ref_size_is_the_storage_count_of_the_header():
             if r:
                 total += pairs * (r16 // 16) * 2 * 64 * 16 + ((na + 31) // 32) * (K // 16) * 64 * 16
         assert pack_ref.pack_layer(layer).size == (cfg.E + cfg.S) * _align256(total)
+
+
+def shared_blob_by_definition(sl) -> bytes:
+    """The shared-factor blob as include/tileq.h orders it: records without factor parts, the placement table,
+    then per section the M left blocks and the N right blocks."""
+    c = sl.cfg
+    out = bytearray(blob_by_definition(sl.expanded(), with_factors=False))
+    for e in range(c.E + c.S):
+        out += struct.pack("<ii", int(sl.phi[e, 0]), int(sl.phi[e, 1]))
+    out += b"\0" * (_align256(len(out)) - len(out))
+    M, N = sl.us[0].shape[0], sl.v[0].shape[0]
+    for sec in ("GU", "D"):
+        # a left block reads only A, a right block only B: the other operand is a dummy of the right shape
+        for m in range(M):
+            A = [sl.us[p][m] for p in range(3)]
+            out += factor_parts_by_definition(sec, A, [sl.v[p][0] for p in range(3)], c.H, c.F, c.r)[1]
+        for n in range(N):
+            B = [sl.v[p][n] for p in range(3)]
+            out += factor_parts_by_definition(sec, [sl.us[p][0] for p in range(3)], B, c.H, c.F, c.r)[0]
+    out += b"\0" * (_align256(len(out)) - len(out))
+    return bytes(out)
+
+
+SHARED_CASES = {
+    "grid2x3_r4": (LayerConfig(911, "p", E=3, S=1, k=1, H=64, F=128, T=1, g=32, r=4, bits=4), 2, 3),
+    "grid1x2_r20": (LayerConfig(912, "p", E=2, S=0, k=1, H=128, F=64, T=1, g=64, r=20, bits=4), 1, 2),
+    "grid2x2_dense3": (LayerConfig(913, "p", E=3, S=0, k=1, H=64, F=64, T=1, g=64, r=8, bits=3, dense=True), 2, 2),
+}
+
+
+@pytest.mark.parametrize("name", list(SHARED_CASES))
+def test_shared_pack_ref_equals_the_layout_written_out_element_by_element(name):
+    from synth import make_shared_layer
+    cfg, M, N = SHARED_CASES[name]
+    sl = make_shared_layer(cfg, M, N, workers=1)
+    want = shared_blob_by_definition(sl)
+    got = pack_ref.pack_layer_shared(sl).tobytes()
+    assert len(got) == len(want)
+    assert got == want
+    # the factors are stored once per tile: r16-padded fp16 blocks, counted from the header's part sizes
+    r16 = (cfg.r + 15) // 16 * 16
+    fact = 0
+    for K, pairs, na in ((cfg.H, cfg.F // 32, 2 * r16), (cfg.F, cfg.H // 64, r16)):
+        fact += M * ((na + 31) // 32) * (K // 16) * 1024 + N * pairs * (r16 // 16) * 2048
+    rec = len(blob_by_definition(sl.expanded(), with_factors=False))
+    assert len(got) == _align256(rec + _align256(8 * (cfg.E + cfg.S)) + fact)
