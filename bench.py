@@ -27,7 +27,9 @@ MFMA_BF16_PEAK = 2.5e15    # FLOP/s dense bf16, MI355X published
 # over this same command, scaled by the streaming-copy calibration: (bytes, file under profiles/ that holds the
 # counter readings).  These are profiler runs of their own, not measurements of the present run; workloads that
 # have not been counted report null.
-TRAFFIC_FROM_PROFILES = {2: (551.2e6 + 1.0e6, "profiles/hbm_traffic_config2_skinny_kernels.txt")}
+TRAFFIC_FROM_PROFILES = {2: (548.1e6 + 1.0e6, "profiles/hbm_traffic_config2_skinny_kernels.txt"),
+                         3: (757.1e6 + 92.3e6, "profiles/hbm_traffic_config3_config5_prefill_kernels.txt"),
+                         5: (4928.0e6 + 201.3e6, "profiles/hbm_traffic_config3_config5_prefill_kernels.txt")}
 STAGES = ["permute", "aug_gate_up", "gate_up", "aug_down", "down", "combine"]
 
 
@@ -460,7 +462,7 @@ def bench_layer(args, cfg, dev, oracle_macs):
     decode_path = cfg.a_tot / (cfg.E + cfg.S) <= 12 and cfg.a_tot <= 1024
     kname = ("gate/up stage (moe_skinny_kernel<0,.>)" if decode_path else
              "gate/up stage (moe_prefill_kernel<0,.>, or moe_mfma_kernel<.,.,0,.> where the layer does not qualify)")
-    traffic, traffic_source = TRAFFIC_FROM_PROFILES.get(cfg.cfg_id, (None, None))
+    traffic, traffic_source = (None, None) if cfg.dense else TRAFFIC_FROM_PROFILES.get(cfg.cfg_id, (None, None))
     if hbm_bound:
         ach = work["gate_up_bytes"] / t_gu / 1e9
         roofline = dict(bound="hbm", kernel=kname, achieved=round(ach, 1), peak=HBM_PEAK / 1e9, unit="GB/s",
