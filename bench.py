@@ -253,6 +253,9 @@ def main():
                     help="as --lotile with mixed-precision factors (fp8 E4M3 U and V, fp16 Sigma)")
     ap.add_argument("--stream-probe", action="store_true",
                     help="instead of the workload: time a plain 1 GiB streaming copy and read (counter calibration)")
+    ap.add_argument("--issue-probe", action="store_true",
+                    help="instead of the workload: the prefill main loop's instruction mix without memory traffic "
+                         "(tq_debug_issue_probe), level by level")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the path is a single-GPU kernel library with no collectives). "
@@ -287,6 +290,34 @@ def main():
             moved = nbytes * (2 if mode == 0 else 1)
             res[name] = {"us": round(us, 1), "GB/s": round(moved / us / 1e3, 1)}
         print(json.dumps({"stream_probe": res, "bytes": nbytes}), flush=True)
+        return
+    if args.issue_probe:
+        scratch = torch.zeros(4096, dtype=torch.uint8, device=dev)
+        scratch[256:512].view(torch.float32).copy_(torch.linspace(0.001, 0.064, 64))
+        stream = torch.cuda.current_stream().cuda_stream
+        ev = HipEvents(2)
+        iters = 4000
+        n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
+        names = {0: "mfma only", 1: "+ lds reads of A", 2: "+ unpack of B", 3: "+ fold (full mix)"}
+        res = {}
+        for rep in range(max(1, args.steps)):
+            for level in range(4):
+                tq.tq_debug_issue_probe(level, 200, scratch)            # spin-up
+                torch.cuda.synchronize()
+                ev.record(0, stream)
+                tq.tq_debug_issue_probe(level, iters, scratch)
+                ev.record(1, stream)
+                torch.cuda.synchronize()
+                ms = ev.elapsed_ms(0, 1)
+                clk = scratch[:16].view(torch.int64).cpu().tolist()
+                ns = ms * 1e6 / (iters * 32 * 2)                         # per MFMA and SIMD: two waves per SIMD
+                ghz = clk[0] / (clk[1] * 10.0)
+                pf = n_cu * 4 * 32768.0 / ns * 1e9 / 1e15
+                r = res.setdefault(names[level], [])
+                r.append({"ns_per_mfma_per_simd": round(ns, 2), "shader_clock_ghz": round(ghz, 3),
+                          "cycles_per_mfma": round(ns * ghz, 1), "pflops": round(pf, 3),
+                          "frac_of_2.5": round(pf / 2.5, 3)})
+        print(json.dumps({"issue_probe": res, "mfmas_per_wave": iters * 32, "waves_per_simd": 2}), flush=True)
         return
     if args.lotile or args.lotile_fp8:
         return bench_lotile(args, cfg, dev)

@@ -261,6 +261,15 @@ tq_status tq_set_profile_events(void *const *events, int32_t n);
  * size and to measure the streaming rate the memory system attains. */
 tq_status tq_debug_stream(const void *src, void *dst, size_t bytes, int32_t mode, void *stream);
 
+/* Measurement aid (not part of the method): runs the instruction mix of the prefill kernels' main loop with no
+ * global memory traffic, on every compute unit at the kernels' occupancy.  level 0: MFMAs alone (operands in
+ * registers); 1: + the A fragments read from LDS; 2: + the B fragments unpacked from 4-bit codes; 3: + the fold of
+ * each group of 8 steps into the accumulators (the full mix).  Each wave issues 32 * iters MFMAs
+ * (v_mfma_f32_32x32x16_bf16, 32768 flops each).  scratch (device, 256-byte aligned, at least 4096 bytes): on
+ * return of the kernel its first two uint64 hold the shader-clock cycles and the 100 MHz wall-clock ticks one wave
+ * spent in the loop; bytes [256, 512) are read as 64 fp32 scale values (any finite contents). */
+tq_status tq_debug_issue_probe(int32_t level, int32_t iters, void *scratch, size_t scratch_bytes, void *stream);
+
 /* ---------------------------------------------------------------------------------------------------
  * LoTileMoE: the fused low-rank path over SHARED 2D-tiled factors (Section 3.2: Eq. 14 splits the layer into
  * QMoE + LoTileMoE; the construction ending in Eq. 15 defines it, Eq. 16 is the compact buffer used here,

@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "TQ_OK", 1: "TQ_ERR_NULL", 2: "TQ_ERR_SHAPE", 3: "TQ_ERR_ALIG
 
 EXPORTS = ["tq_init", "tq_status_str", "tq_packed_size", "tq_pack_weights", "tq_pack_weights_shared", "tq_unpack_weights", "tq_route",
            "tq_permute_workspace_size", "tq_permute", "tq_moe_workspace_size", "tq_moe_forward", "tq_moe_forward_static",
-           "tq_set_profile_events", "tq_debug_stream", "tq_lotile_packed_size", "tq_lotile_pack", "tq_lotile_pack_fp8",
+           "tq_set_profile_events", "tq_debug_stream", "tq_debug_issue_probe", "tq_lotile_packed_size", "tq_lotile_pack", "tq_lotile_pack_fp8",
            "tq_lotile_workspace_size", "tq_lotile_forward", "tq_lotile_grid", "tq_lotile_place"]
 
 
@@ -98,6 +98,8 @@ def lib():
         L.tq_moe_forward_static.argtypes = [ctypes.POINTER(LayerDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                             ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                             ctypes.c_void_p]
+        L.tq_debug_issue_probe.restype = ctypes.c_int
+        L.tq_debug_issue_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.tq_debug_stream.restype = ctypes.c_int
         L.tq_debug_stream.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_void_p]
         L.tq_set_profile_events.restype = ctypes.c_int
@@ -247,6 +249,12 @@ def tq_set_profile_events(events) -> None:
     n = len(events)
     arr = (ctypes.c_void_p * max(n, 1))(*events)
     _check(lib().tq_set_profile_events(arr, n), "tq_set_profile_events")
+
+
+def tq_debug_issue_probe(level: int, iters: int, scratch) -> None:
+    """Measurement aid: see include/tileq.h.  scratch: uint8 device tensor of at least 4096 bytes."""
+    _check(lib().tq_debug_issue_probe(level, iters, _ptr(scratch), scratch.numel() * scratch.element_size(), _stream()),
+           "tq_debug_issue_probe")
 
 
 def tq_debug_stream(src, dst, nbytes: int, mode: int) -> None:
