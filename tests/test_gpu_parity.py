@@ -153,6 +153,49 @@ def test_permute_bit_exact(T, E, k, seed):
     assert np.array_equal(src_of.cpu().numpy(), rsrc)
 
 
+@pytest.mark.parametrize("T,E,k,S_unused,seed", [(129, 8, 2, 0, 10), (1024, 60, 4, 0, 11), (4096, 64, 6, 0, 12), (4097, 64, 8, 0, 13),
+                                                 (2731, 100, 12, 0, 14), (2000, 700, 2, 0, 15), (300, 1024, 1, 0, 16),
+                                                 (5000, 1024, 3, 0, 17), (32768, 5, 1, 0, 18), (33, 128, 8, 0, 19)])
+def test_permute_mid_sized_batches_bit_exact(T, E, k, S_unused, seed):
+    """Batches of 2 to 129 chunks of 256 assignments on the multi-kernel permutation (per-chunk histograms, chunk scan
+    in the offsets kernel up to 64 chunks and in a kernel of its own beyond): ragged last chunks, empty experts,
+    skewed loads, few and many experts."""
+    print(f"permute T={T} E={E} k={k}", flush=True)
+    rng = np.random.default_rng(seed)
+    p = rng.random(E) ** 3
+    p[rng.integers(0, E)] = 0.0          # one empty expert
+    p /= p.sum()
+    if k == 1:
+        idx = rng.choice(E, size=(T, 1), p=p).astype(np.int32)
+    else:
+        idx = np.stack([rng.choice(E, size=k, replace=False, p=None if np.count_nonzero(p) < k else p) for _ in range(T)]).astype(np.int32)
+    offsets, slot_of, src_of = tq.tq_permute(torch.from_numpy(idx).to(DEV), E)
+    torch.cuda.synchronize()
+    ro, rs, rsrc = oracle.permute(idx, E)
+    assert np.array_equal(offsets.cpu().numpy(), ro)
+    assert np.array_equal(slot_of.cpu().numpy(), rs)
+    assert np.array_equal(src_of.cpu().numpy(), rsrc)
+
+
+def test_permute_mid_sized_batch_flags_out_of_range_index():
+    rng = np.random.default_rng(20)
+    idx = rng.integers(0, 16, size=(1500, 2)).astype(np.int32)
+    idx[777, 1] = 16
+    idx[3, 0] = -5
+    err = torch.zeros(1, dtype=torch.int32, device=DEV)
+    offsets, slot_of, src_of = tq.tq_permute(torch.from_numpy(idx).to(DEV), 16, err_flag=err)
+    torch.cuda.synchronize()
+    assert int(err.item()) & 1
+    so = slot_of.cpu().numpy().reshape(1500, 2)
+    assert so[777, 1] == -1 and so[3, 0] == -1
+    good = idx.copy().reshape(-1)
+    keep = (good >= 0) & (good < 16)
+    assert int(offsets.cpu().numpy()[-1]) == int(keep.sum())
+    # the valid assignments are placed as in a batch without the two bad ones (stable within each expert)
+    order = np.argsort(np.where(keep, good, 99), kind="stable")[:keep.sum()]
+    assert np.array_equal(src_of.cpu().numpy()[:keep.sum()], order.astype(np.int32))
+
+
 def test_permute_flags_out_of_range_index():
     idx = np.array([[0, 1], [2, 9], [1, 0]], dtype=np.int32)
     err = torch.zeros(1, dtype=torch.int32, device=DEV)
