@@ -253,6 +253,9 @@ def main():
                     help="as --lotile with mixed-precision factors (fp8 E4M3 U and V, fp16 Sigma)")
     ap.add_argument("--stream-probe", action="store_true",
                     help="instead of the workload: time a plain 1 GiB streaming copy and read (counter calibration)")
+    ap.add_argument("--sketch", action="store_true",
+                    help="instead of the layer: the offline sketch decomposition (tq_sketch_lowrank) of the workload's tiled "
+                         "gate matrix on the near-square grid, rank = the workload's, 2 power iterations")
     ap.add_argument("--issue-probe", action="store_true",
                     help="instead of the workload: the prefill main loop's instruction mix without memory traffic "
                          "(tq_debug_issue_probe), level by level")
@@ -290,6 +293,34 @@ def main():
             moved = nbytes * (2 if mode == 0 else 1)
             res[name] = {"us": round(us, 1), "GB/s": round(moved / us / 1e3, 1)}
         print(json.dumps({"stream_probe": res, "bytes": nbytes}), flush=True)
+        return
+    if args.sketch:
+        from synth import lotile_grid
+        M, N = lotile_grid(cfg.n_exp)
+        rows, cols, r, it = M * cfg.H, N * cfg.F, max(cfg.r, 1), 2
+        gen = torch.Generator(device=dev).manual_seed(1234)
+        W0 = torch.randn((rows, cols), dtype=torch.float32, device=dev, generator=gen) * 0.02
+        S = torch.randn((r, cols), dtype=torch.float32, device=dev, generator=gen)
+        ws = torch.empty(tq.lib().tq_sketch_workspace_size(rows, cols), dtype=torch.uint8, device=dev)
+        stream = torch.cuda.current_stream().cuda_stream
+        ev = HipEvents(2)
+        times = []
+        for i in range(1 + max(1, min(args.steps, 5))):
+            W = W0.clone()
+            torch.cuda.synchronize()
+            ev.record(0, stream)
+            tq.tq_sketch_lowrank(W, r, it, S, workspace=ws)
+            ev.record(1, stream)
+            torch.cuda.synchronize()
+            if i:
+                times.append(ev.elapsed_ms(0, 1))
+        ms = sum(times) / len(times)
+        moved = rows * cols * 4.0 * r * (2 * it + 3)           # per rank: 2 it + 2 reads and one write of the matrix
+        print(json.dumps({"sketch": {"rows": rows, "cols": cols, "rank": r, "power_iterations": it, "ms": round(ms, 3),
+                                     "ms_per_rank": round(ms / r, 3),
+                                     "roofline": {"bound": "hbm", "achieved": round(moved / ms / 1e6, 1), "peak": 8000.0,
+                                                  "unit": "GB/s", "frac": round(moved / ms / 1e6 / 8000.0, 4),
+                                                  "algorithmic_bytes": moved}}}), flush=True)
         return
     if args.issue_probe:
         scratch = torch.zeros(4096, dtype=torch.uint8, device=dev)

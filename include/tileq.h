@@ -341,6 +341,23 @@ tq_status tq_lotile_forward(const tq_lotile_desc *desc, const void *packed, cons
 tq_status tq_lotile_grid(int32_t n_experts, int32_t *tiles_m, int32_t *tiles_n);
 tq_status tq_lotile_place(const int32_t *ideal, int32_t n_experts, int32_t tiles_m, int32_t tiles_n, int32_t *phi);
 
+/* Offline helper on the GPU (Section 3.1, "Plug-in", Eq. 13): rank-r approximation of a dense matrix by r
+ * Gaussian-sketch rank-1 deflations, the replacement for the SVD of the tiled matrix W_big (Eq. 11).  For rank rho,
+ * with the sketch vector s = sketch[rho] (standard normal draws, supplied by the caller so that the routine draws no
+ * random numbers of its own):
+ *     Q = (W W^T)^it W s,   U = Q / |Q|,   Sigma = |Q^T W| / |Q|,   V = Q^T W / |Q^T W|,   W <- W - U Sigma V.
+ * W      fp32 [rows][cols], row-major, device, 16-byte aligned; cols a multiple of 4.  OVERWRITTEN: on return it
+ *        holds the residual W - sum_rho U_rho Sigma_rho V_rho.
+ * sketch fp32 [r][cols] device.   it >= 0 power iterations (Q is renormalised after each one, which changes none of
+ *        U, Sigma, V).
+ * U      fp32 [r][rows] (unit vectors), sigma fp32 [r], V fp32 [r][cols] (unit vectors), device.  A matrix that runs
+ *        out of rank yields zero vectors and Sigma = 0 from there on.
+ * workspace: tq_sketch_workspace_size(rows, cols) bytes, device, 256-byte aligned (0 = unsupported shape).
+ * 1 <= r <= 4096, it <= 64.  Asynchronous on `stream`; all sums have a fixed order. */
+size_t tq_sketch_workspace_size(int64_t rows, int64_t cols);
+tq_status tq_sketch_lowrank(float *W, int64_t rows, int64_t cols, int32_t r, int32_t it, const float *sketch, float *U,
+                            float *sigma, float *V, void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

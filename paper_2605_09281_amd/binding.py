@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "TQ_OK", 1: "TQ_ERR_NULL", 2: "TQ_ERR_SHAPE", 3: "TQ_ERR_ALIG
 
 EXPORTS = ["tq_init", "tq_status_str", "tq_packed_size", "tq_pack_weights", "tq_pack_weights_shared", "tq_unpack_weights", "tq_route",
            "tq_permute_workspace_size", "tq_permute", "tq_moe_workspace_size", "tq_moe_forward", "tq_moe_forward_static",
-           "tq_set_profile_events", "tq_debug_stream", "tq_debug_issue_probe", "tq_lotile_packed_size", "tq_lotile_pack", "tq_lotile_pack_fp8",
+           "tq_set_profile_events", "tq_debug_stream", "tq_debug_issue_probe", "tq_sketch_workspace_size", "tq_sketch_lowrank", "tq_lotile_packed_size", "tq_lotile_pack", "tq_lotile_pack_fp8",
            "tq_lotile_workspace_size", "tq_lotile_forward", "tq_lotile_grid", "tq_lotile_place"]
 
 
@@ -98,6 +98,12 @@ def lib():
         L.tq_moe_forward_static.argtypes = [ctypes.POINTER(LayerDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                             ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                             ctypes.c_void_p]
+        L.tq_sketch_workspace_size.restype = ctypes.c_size_t
+        L.tq_sketch_workspace_size.argtypes = [ctypes.c_int64, ctypes.c_int64]
+        L.tq_sketch_lowrank.restype = ctypes.c_int
+        L.tq_sketch_lowrank.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.c_size_t, ctypes.c_void_p]
         L.tq_debug_issue_probe.restype = ctypes.c_int
         L.tq_debug_issue_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.tq_debug_stream.restype = ctypes.c_int
@@ -249,6 +255,23 @@ def tq_set_profile_events(events) -> None:
     n = len(events)
     arr = (ctypes.c_void_p * max(n, 1))(*events)
     _check(lib().tq_set_profile_events(arr, n), "tq_set_profile_events")
+
+
+def tq_sketch_lowrank(W, r: int, it: int, sketch, workspace=None):
+    """Rank-r sketch decomposition of the fp32 device matrix W [rows, cols] (OVERWRITTEN with the residual).
+    sketch: fp32 [r, cols].  Returns (U [r, rows], sigma [r], V [r, cols])."""
+    rows, cols = W.shape
+    n = int(lib().tq_sketch_workspace_size(rows, cols))
+    if n == 0:
+        raise TqError(2, "tq_sketch_workspace_size")
+    if workspace is None:
+        workspace = torch.empty(n, dtype=torch.uint8, device=W.device)
+    U = torch.empty((r, rows), dtype=torch.float32, device=W.device)
+    sigma = torch.empty(r, dtype=torch.float32, device=W.device)
+    V = torch.empty((r, cols), dtype=torch.float32, device=W.device)
+    _check(lib().tq_sketch_lowrank(_ptr(W), rows, cols, r, it, _ptr(sketch), _ptr(U), _ptr(sigma), _ptr(V), _ptr(workspace),
+                                   workspace.numel(), _stream()), "tq_sketch_lowrank")
+    return U, sigma, V
 
 
 def tq_debug_issue_probe(level: int, iters: int, scratch) -> None:

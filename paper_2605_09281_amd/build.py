@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_DIR)
 SOURCES = ["tq_api.hip", "tq_pack.hip", "tq_route.hip", "tq_f32.hip", "tq_mfma.hip", "tq_skinny.hip", "tq_prefill.hip", "tq_lotile.hip",
-           "tq_probe.hip"]
+           "tq_probe.hip", "tq_sketch.hip"]
 
 _FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
           # packed-fp32 VALU forms are switched off for all device code of this library

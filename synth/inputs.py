@@ -302,6 +302,37 @@ def make_shared_layer(cfg: LayerConfig, M: Optional[int] = None, N: Optional[int
     return SharedLayer(cfg, layer.codes, layer.scale, layer.zero, us, v, phi)
 
 
+_TID_PLANTED = 14
+
+
+def make_planted_experts(cfg_id: int, n_exp: int, K: int, Nout: int, M: int, N: int, r_true: int, noise: float = 0.02,
+                         strength: float = 0.05, phi: Optional[np.ndarray] = None):
+    """Expert matrices with a planted 2D-tiled structure, standing in for trained experts that resemble each other
+    along rows and columns: W_e [K, Nout] fp32 = L_m(e) R_n(e) + noise * N(0, 1), with M left blocks L_m [K, r_true] and
+    N right blocks R_n [r_true, Nout] ~ N(0, strength / sqrt(r_true)) and a seeded collision-free placement phi (needs
+    M N >= n_exp), or the placement given.  Returns (W [n_exp, K, Nout], phi int32 [n_exp, 2])."""
+    assert M * N >= n_exp
+    rng = _rng(cfg_id, _TID_PLANTED)
+    L = rng.standard_normal((M, K, r_true), dtype=np.float32) * np.float32(np.sqrt(strength / np.sqrt(r_true)))
+    R = rng.standard_normal((N, r_true, Nout), dtype=np.float32) * np.float32(np.sqrt(strength / np.sqrt(r_true)))
+    tiles = rng.permutation(M * N)[:n_exp]
+    if phi is None:
+        phi = np.stack([tiles // N, tiles % N], axis=1).astype(np.int32)
+    W = np.stack([L[phi[e, 0]] @ R[phi[e, 1]] for e in range(n_exp)])
+    W += rng.standard_normal(W.shape, dtype=np.float32) * np.float32(noise)
+    return W.astype(np.float32), phi
+
+
+def tile_matrix(W: np.ndarray, phi: np.ndarray, M: int, N: int) -> np.ndarray:
+    """Experts W [n_exp, K, Nout] placed on the M x N grid by phi (the tiled matrix of Eq. 11; empty cells are zero)."""
+    n_exp, K, Nout = W.shape
+    big = np.zeros((M * K, N * Nout), dtype=np.float32)
+    for e in range(n_exp):
+        m, n = int(phi[e, 0]), int(phi[e, 1])
+        big[m * K:(m + 1) * K, n * Nout:(n + 1) * Nout] = W[e]
+    return big
+
+
 def lotile_grid(E: int):
     """The paper's near-square tile grid for E experts: M = round(sqrt(E)), N = ceil(E / M)."""
     M = max(1, int(round(float(np.sqrt(E)))))
