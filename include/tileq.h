@@ -44,10 +44,10 @@
  *          kk = 64c + 16w + 8hf + i, i = 0..7; code i sits in nibble position (i/2) + 4*(i%2), i.e.
  *          the nibbles from least significant upward hold i = 0,2,4,6,1,3,5,7.
  *   sz     uint32 [pairs][K/g][2 tiles][32]      low half = scale fp16 bits, high half = zero fp16 bits
- *   zc     bf16   [pairs][3*ceil(G/16)][2 tiles][64 lanes][8]   (G = K/g)   derived, written by pack only:
+ *   zc     bf16   [pairs][2*ceil(G/16)][2 tiles][64 lanes][8]   (G = K/g)   derived, written by pack only:
  *          c = -scale * (128 + zero), evaluated in fp32, split as hi = bf16(c) and lo = bf16(c - hi), both
- *          round-to-nearest-even.  Element i of (pair, step s, tile, lane) belongs to group 16*(s/3) + 8hf + i
- *          of column (tile, lane%32) and holds hi for s%3 in {0, 1}, lo for s%3 == 2; 0 where the group >= G.
+ *          round-to-nearest-even.  Element i of (pair, fragment s, tile, lane) belongs to group 16*(s/2) + 8hf + i
+ *          of column (tile, lane%32) and holds hi for even s, lo for odd s; 0 where the group >= G.
  *          (The MFMA path feeds the codes as 128 + q; c times the group sum of the activations is what that
  *          leaves to add.)
  *   bfrag  fp16   [pairs][r16/16][2 tiles][64 lanes][8]
@@ -148,9 +148,9 @@ const char *tq_status_str(tq_status s);
 tq_status tq_init(void);
 
 /* Bytes of the packed blob for this layer; 0 if the descriptor is invalid.  Host only.  With r a multiple
- * of 32 and K/g a multiple of 16 this is 256 + (E+S) * 3HF * (4 + 32/g + 48/g + 16 r (1/H + 1/F)) / 8:
+ * of 32 and K/g a multiple of 16 this is 256 + (E+S) * 3HF * (4 + 32/g + 32/g + 16 r (1/H + 1/F)) / 8:
  * the per-expert low-rank storage count of Appendix A.3 with a 16-bit scale and a 16-bit zero per group
- * (4 + 32/g + 16 r (1/H + 1/F) bits per weight), plus the derived zc part (48/g bits per weight). */
+ * (4 + 32/g + 16 r (1/H + 1/F) bits per weight), plus the derived zc part (32/g bits per weight: two bf16 values per group). */
 size_t tq_packed_size(const tq_layer_desc *desc);
 
 /* Packs canonical weights into the blob (layout above).  `err_flag` (device int32, may be NULL) is set

@@ -33,11 +33,11 @@ def _zero_coeff_parts(scale_bits: np.ndarray, zero_bits: np.ndarray, g16: int):
 
 
 def _zc_part(hi: np.ndarray, lo: np.ndarray) -> np.ndarray:
-    """[N, 16*g16] -> [N, g16 (block), 3 (which), 2 (hf), 8 (i)]: which 0, 1 = hi, which 2 = lo."""
+    """[N, 16*g16] -> [N, g16 (block), 2 (which), 2 (hf), 8 (i)]: which 0 = hi, which 1 = lo."""
     N = hi.shape[0]
     h = hi.reshape(N, -1, 2, 8)
     l = lo.reshape(N, -1, 2, 8)
-    return np.stack([h, h, l], axis=2)
+    return np.stack([h, l], axis=2)
 
 
 _NIBBLE_POS = [(i // 2) + 4 * (i % 2) for i in range(8)]
@@ -142,9 +142,9 @@ def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r, dense_bits=0, factors
             parts.append(np.ascontiguousarray(sz.transpose(1, 3, 0, 2)).tobytes())
             g16 = (K // g + 15) // 16
             if not dense_bits:
-                zc = np.stack([_zc_part(*_zero_coeff_parts(scale3[p], zero3[p], g16)).reshape(pairs, 32, g16, 3, 2, 8)
+                zc = np.stack([_zc_part(*_zero_coeff_parts(scale3[p], zero3[p], g16)).reshape(pairs, 32, g16, 2, 2, 8)
                                for p in (0, 1)], axis=0)
-                # [tile, pairs, col, block, which, hf, i] -> [pairs, step = 3*block + which, tile, hf, col, i]
+                # [tile, pairs, col, block, which, hf, i] -> [pairs, fragment = 2*block + which, tile, hf, col, i]
                 parts.append(np.ascontiguousarray(zc.transpose(1, 3, 4, 0, 5, 2, 6)).tobytes())
             if r > 0 and factors:
                 parts.append(_bfrag_gu(B3[0], B3[1], r16, pairs))
@@ -163,7 +163,7 @@ def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r, dense_bits=0, factors
             parts.append(np.ascontiguousarray(sz.transpose(0, 3, 1, 2)).tobytes())
             g16 = (K // g + 15) // 16
             if not dense_bits:
-                zc = _zc_part(*_zero_coeff_parts(scale3[2], zero3[2], g16)).reshape(pairs, 2, 32, g16, 3, 2, 8)
+                zc = _zc_part(*_zero_coeff_parts(scale3[2], zero3[2], g16)).reshape(pairs, 2, 32, g16, 2, 2, 8)
                 # [pairs, tile, col, block, which, hf, i] -> [pairs, step, tile, hf, col, i]
                 parts.append(np.ascontiguousarray(zc.transpose(0, 3, 4, 1, 5, 2, 6)).tobytes())
             if r > 0 and factors:

@@ -10,7 +10,7 @@
 #include "tileq.h"
 
 #define TQ_BLOB_MAGIC 0x31425154u /* "TQB1" */
-#define TQ_BLOB_VERSION 2u
+#define TQ_BLOB_VERSION 3u
 #define TQ_HEADER_BYTES 256
 #define TQ_STATIC_SCRATCH_BYTES TQ_STATIC_SCRATCH_MAX   /* size of the static scratch array (tileq.h) */
 
@@ -25,7 +25,7 @@ struct TqSection {
     int32_t chunks;  // K / 64
     int32_t groups;  // K / g
     int32_t na_tiles;  // 32-wide tiles of the A-factor columns
-    int32_t zsteps;    // 16-wide steps of the zero-point coefficient part: 3 * ceil(groups / 16)
+    int32_t zsteps;    // stored fragments of the zero-point coefficient part per pair and tile: 2 * ceil(groups / 16) (hi, lo)
     // byte offsets from the start of the expert record
     size_t codes, sz, zc, bfrag, afrag, end;
 };
@@ -86,7 +86,7 @@ __host__ inline bool tq_make_layout(const tq_layer_desc* d, TqLayout* L)
         s.pairs = pairs; s.K = K; s.chunks = K / 64; s.groups = K / L->g; s.na_tiles = (na + 31) / 32;
         s.codes = off; off += (size_t)pairs * s.chunks * 512 * L->cw;
         s.sz = off;    off += (size_t)pairs * s.groups * 256;
-        s.zsteps = dense ? 0 : 3 * ((s.groups + 15) / 16);     // only the MFMA prefill kernels read this part
+        s.zsteps = dense ? 0 : 2 * ((s.groups + 15) / 16);     // only the MFMA prefill kernels read this part
         s.zc = off;    off += (size_t)pairs * s.zsteps * 2048;
         // shared factors: the records hold no factor parts (their geometry, na_tiles, still describes the blocks)
         s.bfrag = off; off += shared ? 0 : (size_t)pairs * (L->r16 / 16) * 2048;
@@ -114,6 +114,10 @@ __host__ inline bool tq_make_layout(const tq_layer_desc* d, TqLayout* L)
     }
     return true;
 }
+
+// Correction step s of the K-order (per block of 16 groups: hi(c) against hi(xsum), hi(c) against lo(xsum), lo(c)
+// against hi(xsum)) -> stored fragment of the zc part (per block: hi, lo)
+__host__ __device__ inline int tq_zc_fragment(int step) { const int b = step / 3; return 2 * b + (step - 3 * b == 2 ? 1 : 0); }
 
 // position of code i (0..7, consecutive kk) inside a packed 32-bit word, in nibbles
 __host__ __device__ inline int tq_nibble_pos(int i) { return (i >> 1) + 4 * (i & 1); }

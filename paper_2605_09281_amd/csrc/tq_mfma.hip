@@ -533,7 +533,7 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
                 const int k0 = UNIT_K * st + 16 * w;
                 kind[w] = 0;
                 if (k0 < ZT) {
-                    const int step = k0 / 16;
+                    const int step = tq_zc_fragment(k0 / 16);
                     fq[w][0] = zcp[((size_t)step * 2 + 0) * 64];
                     fq[w][1] = zcp[((size_t)step * 2 + 1) * 64];
                     kind[w] = 1;

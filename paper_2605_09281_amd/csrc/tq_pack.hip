@@ -222,7 +222,7 @@ __global__ void zc_kernel(PackGeom G, uint8_t* __restrict__ blob, const uint16_t
     if (!is_d) { p = tile; n = 32 * pair + col; }
     else       { p = 2;    n = 64 * pair + 32 * tile + col; }
     const size_t HFg = (size_t)G.H * G.F / G.g;
-    const int which = step % 3, gblock = step / 3;
+    const int which = step % 2, gblock = step / 2;       // fragment 0 of a block: hi, 1: lo
     uint16_t* dst = reinterpret_cast<uint16_t*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.zc) + w * 8;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -234,7 +234,7 @@ __global__ void zc_kernel(PackGeom G, uint8_t* __restrict__ blob, const uint16_t
             const float z = __half2float(__ushort_as_half(zero[ci]));
             const float c = -s * (128.0f + z);
             const uint32_t hi = bf16_rne_bits(c);
-            out = which < 2 ? (uint16_t)hi : (uint16_t)bf16_rne_bits(c - __uint_as_float(hi << 16));
+            out = which == 0 ? (uint16_t)hi : (uint16_t)bf16_rne_bits(c - __uint_as_float(hi << 16));
         }
         dst[i] = out;
     }

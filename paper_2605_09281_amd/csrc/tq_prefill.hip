@@ -150,6 +150,7 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
             const int nlr = G.r16 / 16;
             if (!zp) { if (step >= nlr) step -= nlr; if (step >= nlr) step = 0; }
             const u32x4* base = (zp || G.r == 0) ? s.zc : s.bf;
+            if (zp) step = tq_zc_fragment(step);
             if (!zp && G.r == 0) step = 0;
             fq[w][0] = base[((size_t)step * 2 + 0) * 64 + lane];
             fq[w][1] = base[((size_t)step * 2 + 1) * 64 + lane];

@@ -32,9 +32,9 @@ def test_packed_size_closed_form(E, S, H, F, g, r):
     """Appendix A.3, per-expert low-rank storage: d = d_basic + r d_fp (1/i + 1/o) bits per weight, here with
     4-bit codes, a 16-bit scale and a 16-bit zero per group and 16-bit factors (no Sigma is stored)."""
     n = tq.tq_packed_size(tq.make_desc(E, S, 2, H, F, g, 4, r))
-    # the blob also carries a derived part (bf16 hi/lo zero-point coefficients, 3 values per group in blocks of
-    # 16 groups); what remains is the paper's count
-    derived = (E + S) * 2 * (2 * F * 3 * 16 * -(-(H // g) // 16) + H * 3 * 16 * -(-(F // g) // 16))
+    # the blob also carries a derived part (bf16 hi and lo of the zero-point coefficient: 2 values per group, in
+    # blocks of 16 groups); what remains is the paper's count
+    derived = (E + S) * 2 * (2 * F * 2 * 16 * -(-(H // g) // 16) + H * 2 * 16 * -(-(F // g) // 16))
     bits = 8.0 * (n - 256 - derived) / (3 * H * F * (E + S))
     assert abs(bits - (4 + 32 / g + 16 * r * (1 / H + 1 / F))) < 1e-9
     with open(os.path.join(ROOT, "tests", "golden", "bits_per_weight.txt")) as f:
@@ -67,7 +67,7 @@ def test_dense_descriptor_limits():
 
 def test_packed_size_rank_padding_and_zero_rank():
     base = tq.tq_packed_size(tq.make_desc(4, 0, 2, 256, 512, 64, 4, 0))
-    derived = 4 * 2 * (2 * 512 * 48 + 256 * 48)       # H/g = 4 and F/g = 8 groups: one block of 16 each
+    derived = 4 * 2 * (2 * 512 * 32 + 256 * 32)       # H/g = 4 and F/g = 8 groups: one block of 16 each
     assert (base - 256 - derived) * 8 == 4 * 3 * 256 * 512 * (4 + 32 / 64)
     n8 = tq.tq_packed_size(tq.make_desc(4, 0, 2, 256, 512, 64, 4, 8))
     n16 = tq.tq_packed_size(tq.make_desc(4, 0, 2, 256, 512, 64, 4, 16))

@@ -133,23 +133,23 @@ def blob_by_definition(layer, with_factors=True) -> bytes:
                             p, n = col_of(pair, tile, cc)
                             part += struct.pack("<I", int(scale[p][n, gi]) | (int(zero[p][n, gi]) << 16))
             rec += part
-            # ---- zc: bf16 [pairs][3*ceil(G/16)][2 tiles][64 lanes][8]
+            # ---- zc: bf16 [pairs][2*ceil(G/16)][2 tiles][64 lanes][8]
             part = bytearray()
             for pair in range(0 if dense_bits else pairs):          # dense blobs carry no zc part
-                for s in range(3 * ((G + 15) // 16)):
+                for s in range(2 * ((G + 15) // 16)):
                     for tile in range(2):
                         for lane in range(64):
                             p, n = col_of(pair, tile, lane % 32)
                             hf = lane // 32
                             for i in range(8):
-                                gi = 16 * (s // 3) + 8 * hf + i
+                                gi = 16 * (s // 2) + 8 * hf + i
                                 v = 0
                                 if gi < G:
                                     sc = np.float32(scale[p][n, gi:gi + 1].view(np.float16)[0])
                                     ze = np.float32(zero[p][n, gi:gi + 1].view(np.float16)[0])
                                     cf = np.float32(-sc) * np.float32(np.float32(128.0) + ze)
                                     hi = _bf16_rne_scalar(cf)
-                                    v = hi if s % 3 in (0, 1) else _bf16_rne_scalar(np.float32(cf - _bf16_to_f32(hi)))
+                                    v = hi if s % 2 == 0 else _bf16_rne_scalar(np.float32(cf - _bf16_to_f32(hi)))
                                 part += struct.pack("<H", v)
             rec += part
             if r > 0 and with_factors:
@@ -197,7 +197,7 @@ def test_pack_ref_size_is_the_storage_count_of_the_header():
             if cfg.dense:
                 total += pairs * (K // 64) * 2 * 64 * 4 * cfg.bits + pairs * G * 2 * 32 * 4
             else:
-                total += pairs * (K // 64) * 2 * 64 * 16 + pairs * G * 2 * 32 * 4 + pairs * 3 * ((G + 15) // 16) * 2 * 64 * 16
+                total += pairs * (K // 64) * 2 * 64 * 16 + pairs * G * 2 * 32 * 4 + pairs * 2 * ((G + 15) // 16) * 2 * 64 * 16
             if r:
                 total += pairs * (r16 // 16) * 2 * 64 * 16 + ((na + 31) // 32) * (K // 16) * 64 * 16
         assert pack_ref.pack_layer(layer).size == (cfg.E + cfg.S) * _align256(total)
