@@ -329,10 +329,11 @@ def main():
         ev = HipEvents(2)
         iters = 4000
         n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
-        names = {0: "mfma only", 1: "+ lds reads of A", 2: "+ unpack of B", 3: "+ fold (full mix)"}
+        names = {0: "mfma only", 1: "+ lds reads of A", 2: "+ unpack of B", 3: "+ fold (full mix)",
+                 4: "+ tile store and barrier"}
         res = {}
         for rep in range(max(1, args.steps)):
-            for level in range(4):
+            for level in range(5):
                 tq.tq_debug_issue_probe(level, 200, scratch)            # spin-up
                 torch.cuda.synchronize()
                 ev.record(0, stream)

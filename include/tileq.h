@@ -264,7 +264,8 @@ tq_status tq_debug_stream(const void *src, void *dst, size_t bytes, int32_t mode
 /* Measurement aid (not part of the method): runs the instruction mix of the prefill kernels' main loop with no
  * global memory traffic, on every compute unit at the kernels' occupancy.  level 0: MFMAs alone (operands in
  * registers); 1: + the A fragments read from LDS; 2: + the B fragments unpacked from 4-bit codes; 3: + the fold of
- * each group of 8 steps into the accumulators (the full mix).  Each wave issues 32 * iters MFMAs
+ * each group of 8 steps into the accumulators (the full mix); 4: + per group the store of the next activation tile
+ * into an LDS double buffer and the workgroup barrier that publishes it.  Each wave issues 32 * iters MFMAs
  * (v_mfma_f32_32x32x16_bf16, 32768 flops each).  scratch (device, 256-byte aligned, at least 4096 bytes): on
  * return of the kernel its first two uint64 hold the shader-clock cycles and the 100 MHz wall-clock ticks one wave
  * spent in the loop; bytes [256, 512) are read as 64 fp32 scale values (any finite contents). */

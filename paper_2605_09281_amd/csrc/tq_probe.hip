@@ -6,6 +6,8 @@
 //   level 1: + the two A fragments of every step read from LDS (ds_read_b128)
 //   level 2: + the two B fragments of every step unpacked from 4-bit codes (3 shifts and 4 and-or per fragment)
 //   level 3: + the fold of every group's partial sums into the accumulators (16 FMAs per tile and group)
+//   level 4: + per group, the store of the next activation tile into the other half of an LDS double buffer (four
+//            16-byte stores per thread) and the workgroup barrier that publishes it
 // Every level runs with two workgroups per compute unit (two waves per SIMD), as the kernel does.  The kernel reports
 // its own cycle count and wall-clock time, so the clock the chip sustained under that load is known.
 #include "tq_device.h"
@@ -19,10 +21,15 @@ __global__ void __launch_bounds__(256, 2) issue_probe_kernel(float* __restrict__
                                                              const float* __restrict__ scales,
                                                              unsigned long long* __restrict__ clk)
 {
-    constexpr int MT = 2, NT = 2, GS = 8, ROWB = 272;
+    constexpr int MT = 2, NT = 2, GS = 8, ROWB = 272, BUFB = 32 * MT * ROWB;
+    constexpr int NBUF = LEVEL >= 4 ? 2 : 1;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    for (int i = threadIdx.x; i < (32 * MT * ROWB) / 4; i += blockDim.x) reinterpret_cast<uint32_t*>(lds)[i] = 0x3F803F80u + (i & 3);
+    for (int i = threadIdx.x; i < (NBUF * BUFB) / 4; i += blockDim.x) reinterpret_cast<uint32_t*>(lds)[i] = 0x3F803F80u + (i & 3);
     __syncthreads();
+    u32x4 xr[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) { xr[m][0] = 0x3F803F80u; xr[m][1] = 0x3F803F81u; xr[m][2] = 0x3F803F82u; xr[m][3] = 0x3F803F83u; }
+    const uint32_t wr_off = (threadIdx.x >> 4) * ROWB + (threadIdx.x & 15) * 16;      // 16 rows x 256 bytes per pass
     const int lane = threadIdx.x & 63, col = lane & 31, hf = lane >> 5;
     uint32_t magic;
     asm volatile("v_mov_b32 %0, %1" : "=v"(magic) : "s"(magic_s));
@@ -44,12 +51,13 @@ __global__ void __launch_bounds__(256, 2) issue_probe_kernel(float* __restrict__
         areg[0].u[j] = 0x3F803F80u + j; areg[1].u[j] = 0x3F813F80u + j;
         breg[0].u[j] = 0x43014302u + j; breg[1].u[j] = 0x43034304u + j;
     }
-    const uint8_t* base = lds + col * ROWB + hf * 16;
+    const uint8_t* base0 = lds + col * ROWB + hf * 16;
     const unsigned long long c0 = clock64(), w0 = wall_clock64();
     for (int it = 0; it < iters; ++it) {
         float sc[NT];
 #pragma unroll
         for (int t = 0; t < NT; ++t) sc[t] = scales[(it * NT + t) & 63];
+        const uint8_t* base = base0 + (LEVEL >= 4 ? (it & 1) * BUFB : 0);
         f32x16 part[MT][NT];
 #pragma unroll
         for (int ks = 0; ks < GS; ++ks) {
@@ -90,6 +98,12 @@ __global__ void __launch_bounds__(256, 2) issue_probe_kernel(float* __restrict__
                 for (int t = 0; t < NT; ++t)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) acc[m][t][v] = fmaf(sc[t], part[m][t][v], acc[m][t][v]);
+            if (LEVEL >= 4) {
+                uint8_t* dst = lds + ((it + 1) & 1) * BUFB + wr_off;
+#pragma unroll
+                for (int m = 0; m < MT * 2; ++m) *reinterpret_cast<u32x4*>(dst + m * 16 * ROWB) = xr[m % MT];
+                lds_barrier();
+            }
         } else if (LEVEL < 2) {
             // keep the register operands loop-variant so that the steps are not merged
 #pragma unroll
@@ -115,7 +129,7 @@ extern "C" tq_status tq_debug_issue_probe(int32_t level, int32_t iters, void* sc
 {
     if (!scratch) return TQ_ERR_NULL;
     if ((uintptr_t)scratch & 255) return TQ_ERR_ALIGN;
-    if (level < 0 || level > 3 || iters < 1 || iters > (1 << 20)) return TQ_ERR_SHAPE;
+    if (level < 0 || level > 4 || iters < 1 || iters > (1 << 20)) return TQ_ERR_SHAPE;
     if (scratch_bytes < 4096) return TQ_ERR_WORKSPACE;
     const TqDeviceState* ds = nullptr;
     if (tqi_device_state(&ds) != TQ_OK) return TQ_ERR_HIP;
@@ -124,14 +138,15 @@ extern "C" tq_status tq_debug_issue_probe(int32_t level, int32_t iters, void* sc
     unsigned long long* clk = reinterpret_cast<unsigned long long*>(scratch);
     const float* scales = reinterpret_cast<const float*>(reinterpret_cast<uint8_t*>(scratch) + 256);
     float* out = reinterpret_cast<float*>(reinterpret_cast<uint8_t*>(scratch) + 1024);
-    const size_t smem = 32 * 2 * 272 + 64;
+    const size_t smem = (level >= 4 ? 2 : 1) * 32 * 2 * 272 + 64;
     const dim3 grid(2 * ds->n_cu), block(256);
     hipStream_t st = (hipStream_t)stream;
     switch (level) {
     case 0: hipLaunchKernelGGL(issue_probe_kernel<0>, grid, block, smem, st, out, iters, 0x000F000Fu, 0x43004300u, scales, clk); break;
     case 1: hipLaunchKernelGGL(issue_probe_kernel<1>, grid, block, smem, st, out, iters, 0x000F000Fu, 0x43004300u, scales, clk); break;
     case 2: hipLaunchKernelGGL(issue_probe_kernel<2>, grid, block, smem, st, out, iters, 0x000F000Fu, 0x43004300u, scales, clk); break;
-    default: hipLaunchKernelGGL(issue_probe_kernel<3>, grid, block, smem, st, out, iters, 0x000F000Fu, 0x43004300u, scales, clk); break;
+    case 3: hipLaunchKernelGGL(issue_probe_kernel<3>, grid, block, smem, st, out, iters, 0x000F000Fu, 0x43004300u, scales, clk); break;
+    default: hipLaunchKernelGGL(issue_probe_kernel<4>, grid, block, smem, st, out, iters, 0x000F000Fu, 0x43004300u, scales, clk); break;
     }
     TQ_CHECK_LAUNCH();
     return TQ_OK;

@@ -27,7 +27,7 @@ def test_debug_stream_copies_and_checks_its_arguments():
         tq.tq_debug_stream(src, dst, 32, 3)              # no such mode
 
 
-@pytest.mark.parametrize("level", [0, 1, 2, 3])
+@pytest.mark.parametrize("level", [0, 1, 2, 3, 4])
 def test_issue_probe_reports_plausible_counters(level):
     scratch = torch.zeros(4096, dtype=torch.uint8, device=DEV)
     scratch[256:512].view(torch.float32).fill_(0.5)
@@ -45,7 +45,7 @@ def test_issue_probe_reports_plausible_counters(level):
 def test_issue_probe_checks_its_arguments():
     scratch = torch.zeros(4096, dtype=torch.uint8, device=DEV)
     with pytest.raises(tq.TqError):
-        tq.tq_debug_issue_probe(4, 10, scratch)
+        tq.tq_debug_issue_probe(5, 10, scratch)
     with pytest.raises(tq.TqError):
         tq.tq_debug_issue_probe(0, 0, scratch)
     with pytest.raises(tq.TqError):
