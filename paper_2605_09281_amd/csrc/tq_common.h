@@ -25,7 +25,8 @@ struct TqSection {
     int32_t chunks;  // K / 64
     int32_t groups;  // K / g
     int32_t na_tiles;  // 32-wide tiles of the A-factor columns
-    int32_t zsteps;    // stored fragments of the zero-point coefficient part per pair and tile: 2 * ceil(groups / 16) (hi, lo)
+    int32_t zfrag;     // fragments of the zero-point coefficients per pair and tile: 2 * ceil(groups / 16) (hi, lo)
+    int32_t zsteps;    // of which the blob stores: zfrag, or 0 (dense codes: the tiled kernels derive them per call)
     // byte offsets from the start of the expert record
     size_t codes, sz, zc, bfrag, afrag, end;
 };
@@ -43,6 +44,7 @@ struct TqLayout {
     int32_t E, S, k, H, F, g, bits, r, r16;
     TqFactorMap fm;
     int32_t cw;      // 32-bit words of codes per (lane, 64-wide chunk, tile): 4 (4-bit slots), 3 or 2 (dense 3- / 2-bit)
+    int32_t flags;   // the descriptor's
     TqSection gu, d;
     size_t expert_stride;
     size_t total_bytes;
@@ -81,12 +83,14 @@ __host__ inline bool tq_make_layout(const tq_layer_desc* d, TqLayout* L)
     L->E = d->n_experts; L->S = d->n_shared; L->k = d->top_k; L->H = d->hidden; L->F = d->ffn;
     L->g = d->group; L->bits = d->bits; L->r = d->rank; L->r16 = (d->rank + 15) / 16 * 16;
     L->cw = dense ? d->bits : 4;
+    L->flags = d->flags;
     size_t off = 0;
     auto fill = [&](TqSection& s, int pairs, int K, int na) {
         s.pairs = pairs; s.K = K; s.chunks = K / 64; s.groups = K / L->g; s.na_tiles = (na + 31) / 32;
         s.codes = off; off += (size_t)pairs * s.chunks * 512 * L->cw;
         s.sz = off;    off += (size_t)pairs * s.groups * 256;
-        s.zsteps = dense ? 0 : 2 * ((s.groups + 15) / 16);     // only the MFMA prefill kernels read this part
+        s.zfrag = 2 * ((s.groups + 15) / 16);
+        s.zsteps = dense ? 0 : s.zfrag;     // only the MFMA prefill kernels read this part
         s.zc = off;    off += (size_t)pairs * s.zsteps * 2048;
         // shared factors: the records hold no factor parts (their geometry, na_tiles, still describes the blocks)
         s.bfrag = off; off += shared ? 0 : (size_t)pairs * (L->r16 / 16) * 2048;
@@ -139,6 +143,9 @@ struct TqWorkspace {
     size_t h;           // bf16 [A_tot][F]  or fp32 [A_tot][F]
     size_t yd;          // fp32 [nsplit][A_tot][H]
     size_t tpart;       // fp32 partial low-rank intermediates of the decode path (only for small batches)
+    size_t zc_ws;       // dense codes on the tiled kernels: the zero-point coefficient fragments the blob does not store,
+    size_t zc_stride;   // derived per call: [E+S] records of zc_stride bytes, section GU at 0, section D at zc_d_off
+    size_t zc_d_off;
     size_t sk_cnt;      // decode path: next-pair counters [2 stages][rt_max][TQ_MAX_SPLIT], cleared by the permutation
     int32_t sk_cnt_n;   // their number (0 when the batch is too large for the decode path)
     size_t total;
@@ -196,6 +203,13 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
             const size_t nat = (size_t)(2 * L.r16 + 31) / 32;
             W->tpart = take((size_t)(a_tot / 16 + L.E + L.S) * slices * nat * 512 * 4);
         }
+        // dense codes beyond the decode path (more rows than it takes, or a tile path forced)
+        W->zc_ws = off; W->zc_stride = 0; W->zc_d_off = 0;
+        if (L.cw != 4 && (a_tot > TQ_SKINNY_MAX_ROWS || (L.flags & (TQ_FLAG_FORCE_SMALL_TILE | TQ_FLAG_FORCE_LARGE_TILE)))) {
+            W->zc_d_off = (size_t)L.gu.pairs * L.gu.zfrag * 2048;
+            W->zc_stride = W->zc_d_off + (size_t)L.d.pairs * L.d.zfrag * 2048;
+            W->zc_ws = take((size_t)(L.E + L.S) * W->zc_stride);
+        }
         W->sk_cnt = off;
         W->sk_cnt_n = 0;
         if (a_tot <= TQ_SKINNY_MAX_ROWS) {
@@ -204,6 +218,7 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
         }
     } else {
         W->xaug_gu = W->xaug_d = off;
+        W->zc_ws = off; W->zc_stride = 0; W->zc_d_off = 0;
         W->tpart = off;
         W->sk_cnt = off;
         W->sk_cnt_n = 0;
@@ -271,6 +286,8 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
                              int32_t* hist, int32_t nblk, const void* blob, const TqLayout* L,
                              int32_t* zero_buf, int32_t zero_n, hipStream_t stream,
                              const TqPreByAssign* pre = nullptr, int tilings = (1 << TQ_N_TILINGS) - 1);
+// fills W.zc_ws from the blob's scale / zero part (dense codes on the tiled kernels)
+tq_status tqi_derive_zc(const TqLayout& L, const TqWorkspace& W, const uint8_t* blob, uint8_t* ws, hipStream_t stream);
 // whether the bf16 forward of this batch runs on the decode kernels, and whether its gate/up pre-pass is by assignment
 bool tqi_bf16_takes_skinny(const TqLayout& L, const TqWorkspace& W, int flags);
 inline bool tqi_pre_by_assign(const TqLayout& L, const TqWorkspace& W) { return L.r > 0 && W.a_tot <= TQ_PRE_ASSIGN_MAX_ROWS; }

@@ -15,7 +15,16 @@ struct MGeom {
     uint32_t unpack_mask, unpack_magic;   // 0x000F000F, 0x43004300 (see unpack_word)
     size_t expert_stride;
     TqFactorMap fm;
+    const uint8_t* zc_ws;      // zero-point coefficient fragments outside the blob (dense codes), or null
+    size_t zc_stride, zc_d_off;
 };
+
+// base of the zero-point coefficient fragments of expert e in section sec_id (0 GU, 1 D)
+__device__ inline const uint8_t* tq_zc_base(const MGeom& G, const uint8_t* blob, const TqSection& sec, int sec_id, int e)
+{
+    if (G.zc_ws) return G.zc_ws + (size_t)e * G.zc_stride + (sec_id ? G.zc_d_off : 0);
+    return blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.zc;
+}
 
 union Frag {
     bf16x8 v;

@@ -316,7 +316,8 @@ __global__ void __launch_bounds__(256, NAT == 1 ? 3 : 2) aug_staged_kernel(MGeom
 //   STAGE 0: out = h[slot][F] bf16 = silu(gate) * up
 //   STAGE 1: out = yd[split][slot][H] fp32, split = blockIdx.z covering a slice of K
 // GS = quantisation group in MFMA steps (g/16).  A "unit" is max(g, 64) contraction indices.
-template <int MT, int WM, int STAGE, int GS>
+// CW = 32-bit words of codes per lane, tile and 64-wide chunk: 4 (4-bit slots), 3 or 2 (dense 3- / 2-bit codes).
+template <int MT, int WM, int STAGE, int GS, int CW = 4>
 __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mfma_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
                                                        const uint16_t* __restrict__ xin,
                                                        const uint16_t* __restrict__ xaug,
@@ -338,6 +339,8 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
     constexpr int TPR = UNIT_K / 8;     // threads (16-byte segments) per row when loading a unit
     constexpr int RPP = NTHR / TPR;     // rows per pass
     constexpr int NP = BM / RPP;        // passes
+    using WT = std::conditional_t<CW == 4, u32x4, uint32_t>;      // register type of the packed codes
+    constexpr int WN = CW == 4 ? UC : UC * CW;                    // and how many of them one tile of a unit takes
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     int32_t* tokx = reinterpret_cast<int32_t*>(lds + 2 * BUFB);   // [BM] source row of the main operand
@@ -373,8 +376,9 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
 
     const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
     const u32x4* codes = reinterpret_cast<const u32x4*>(rec + sec.codes) + (size_t)pair * sec.chunks * 128 + lane;
+    const uint32_t* codes32 = reinterpret_cast<const uint32_t*>(rec + sec.codes) + (size_t)pair * sec.chunks * (2 * CW * 64) + lane;
     const uint32_t* szp = reinterpret_cast<const uint32_t*>(rec + sec.sz) + (size_t)pair * sec.groups * 64 + col;
-    const u32x4* zcp = reinterpret_cast<const u32x4*>(rec + sec.zc) + (size_t)pair * sec.zsteps * 128 + lane;
+    const u32x4* zcp = reinterpret_cast<const u32x4*>(tq_zc_base(G, blob, sec, STAGE, e)) + (size_t)pair * sec.zfrag * 128 + lane;
     const u32x4* bfr = reinterpret_cast<const u32x4*>(G.r > 0 ? tq_bfrag_base(blob, G.expert_stride, sec, G.fm, STAGE, e)
                                                                : rec + sec.bfrag) + (size_t)pair * (G.r16 / 16) * 128 + lane;
 
@@ -408,11 +412,18 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
             *reinterpret_cast<u32x4*>(lds + buf * BUFB + row * ROWB + seg * 16) = xr[p];
         }
     };
-    auto load_w = [&](u32x4 (&dst)[2][UC], int u) {
+    auto load_w = [&](WT (&dst)[2][WN], int u) {
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int c = 0; c < UC; ++c) dst[t][c] = codes[((size_t)(u * UC + c) * 2 + t) * 64];
+            for (int c = 0; c < UC; ++c) {
+                if constexpr (CW == 4) {
+                    dst[t][c] = codes[((size_t)(u * UC + c) * 2 + t) * 64];
+                } else {
+#pragma unroll
+                    for (int d = 0; d < CW; ++d) dst[t][c * CW + d] = codes32[(((size_t)(u * UC + c) * 2 + t) * CW + d) * 64];
+                }
+            }
     };
     auto load_sz = [&](uint32_t (&dst)[NG][2], int u) {
 #pragma unroll
@@ -434,7 +445,7 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
     uint32_t magic_v;
     asm volatile("v_mov_b32 %0, %1" : "=v"(magic_v) : "s"(G.unpack_magic));
 
-    u32x4 wq[2][2][UC];
+    WT wq[2][2][WN];
     uint32_t szq[2][NG][2];
 
     // ---- prologue ---------------------------------------------------------------------------------
@@ -459,12 +470,12 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
         constexpr int SLOT = decltype(slot_tag)::value;
         const int st = naug + mu;
         load_step(min(st + 1, nsteps - 1));
-        u32x4 wc[2][UC];
+        WT wc[2][WN];
         uint32_t szc[NG][2];
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int c = 0; c < UC; ++c) wc[t][c] = wq[SLOT][t][c];
+            for (int c = 0; c < WN; ++c) wc[t][c] = wq[SLOT][t][c];
 #pragma unroll
         for (int gi = 0; gi < NG; ++gi)
 #pragma unroll
@@ -488,7 +499,10 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
                     }
                     bf16x8 bw[2];
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) bw[t] = unpack_word(word_of(wc[t][kidx / 4], kidx % 4), G.unpack_mask, magic_v);
+                    for (int t = 0; t < 2; ++t) {
+                        if constexpr (CW == 4) bw[t] = unpack_word(word_of(wc[t][kidx / 4], kidx % 4), G.unpack_mask, magic_v);
+                        else bw[t] = unpack_dense<CW>(&wc[t][(kidx / 4) * CW], kidx % 4, G.unpack_mask, magic_v);
+                    }
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
@@ -673,7 +687,7 @@ __global__ void __launch_bounds__(256) combine_bf16_kernel(int T, int H, int k, 
     }
 }
 
-template <int MT, int WM, int STAGE, int GS>
+template <int MT, int WM, int STAGE, int GS, int CW = 4>
 tq_status launch_main(const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin, const uint16_t* xaug,
                       const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
                       const int32_t* offsets, const int32_t* ctrl, int ctrl_idx, void* out, int ka, int nsplit,
@@ -683,7 +697,7 @@ tq_status launch_main(const MGeom& G, const TqSection& sec, const uint8_t* blob,
     constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
     constexpr int ROWB = UNIT_K * 2 + 16;
     const size_t smem = (size_t)2 * BM * ROWB + (size_t)2 * BM * 4;
-    auto kern = moe_mfma_kernel<MT, WM, STAGE, GS>;      // dynamic-LDS limit: raised once per device by tqi_setup_mfma
+    auto kern = moe_mfma_kernel<MT, WM, STAGE, GS, CW>;      // dynamic-LDS limit: raised once per device by tqi_setup_mfma
     const int nb_count = (sec.pairs + 3) / 4;
     const long n_wg = (long)((row_tiles + 7) / 8) * 8 * nb_count;
     if (n_wg > 0x7FFFFFFF || nb_count > 65535) return TQ_ERR_UNSUPPORTED;
@@ -695,7 +709,7 @@ tq_status launch_main(const MGeom& G, const TqSection& sec, const uint8_t* blob,
 }
 
 template <int MT, int WM, int STAGE>
-tq_status launch_main_gs(int gs, const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin, const uint16_t* xaug,
+tq_status launch_main_gs(int gs, int cw, const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin, const uint16_t* xaug,
                          const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
                          const int32_t* offsets, const int32_t* ctrl, int ctrl_idx, void* out, int ka, int nsplit,
                          int row_tiles, hipStream_t st)
@@ -704,6 +718,15 @@ tq_status launch_main_gs(int gs, const MGeom& G, const TqSection& sec, const uin
     case GSV:                                                                                                     \
         return launch_main<MT, WM, STAGE, GSV>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl, ctrl_idx, \
                                            out, ka, nsplit, row_tiles, st)
+    if (cw != 4) {      // dense codes: groups of 64 and 128
+#define TQ_DENSE(GSV, CWV)                                                                                                   \
+    if (gs == GSV && cw == CWV)                                                                                              \
+        return launch_main<MT, WM, STAGE, GSV, CWV>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl, ctrl_idx, \
+                                                    out, ka, nsplit, row_tiles, st)
+        TQ_DENSE(4, 3); TQ_DENSE(8, 3); TQ_DENSE(4, 2); TQ_DENSE(8, 2);
+#undef TQ_DENSE
+        return TQ_ERR_UNSUPPORTED;
+    }
     switch (gs) {
         TQ_CASE(2);
         TQ_CASE(4);
@@ -719,7 +742,7 @@ tq_status launch_main_gs(int gs, const MGeom& G, const TqSection& sec, const uin
     return TQ_ERR_UNSUPPORTED;
 }
 
-template <int MT, int WM, int STAGE, int GS>
+template <int MT, int WM, int STAGE, int GS, int CW = 4>
 bool raise_lds_limit_main()
 {
     constexpr int BM = 32 * MT * WM;
@@ -727,7 +750,7 @@ bool raise_lds_limit_main()
     constexpr int ROWB = UNIT_K * 2 + 16;
     constexpr size_t smem = (size_t)2 * BM * ROWB + (size_t)2 * BM * 4;
     if (smem <= 64 * 1024) return true;
-    return hipFuncSetAttribute((const void*)moe_mfma_kernel<MT, WM, STAGE, GS>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    return hipFuncSetAttribute((const void*)moe_mfma_kernel<MT, WM, STAGE, GS, CW>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                (int)smem) == hipSuccess;
 }
 
@@ -776,6 +799,10 @@ tq_status tqi_setup_mfma()
     TQ_BOTH(2, 2); TQ_BOTH(2, 4); TQ_BOTH(2, 8);
     TQ_BOTH(4, 16);
 #undef TQ_BOTH
+#define TQ_DENSE(MT, GS, CW) ok = ok && raise_lds_limit_main<MT, 1, 0, GS, CW>() && raise_lds_limit_main<MT, 1, 1, GS, CW>()
+    TQ_DENSE(1, 4, 3); TQ_DENSE(1, 8, 3); TQ_DENSE(1, 4, 2); TQ_DENSE(1, 8, 2);
+    TQ_DENSE(2, 4, 3); TQ_DENSE(2, 8, 3); TQ_DENSE(2, 4, 2); TQ_DENSE(2, 8, 2);
+#undef TQ_DENSE
     return ok ? TQ_OK : TQ_ERR_HIP;
 }
 
@@ -794,7 +821,8 @@ bool tqi_bf16_takes_skinny(const TqLayout& L, const TqWorkspace& W, int flags)
 {
     const int64_t avg_rows = (int64_t)W.a_tot / (L.E + L.S);
     bool skinny = !bf16_large_tiles(L, W, flags) && avg_rows <= 12 && !(flags & TQ_FLAG_FORCE_SMALL_TILE);
-    if ((flags & TQ_FLAG_FORCE_SKINNY) || L.cw != 4) skinny = true;      // dense codes: decode kernels only (checked by the caller)
+    // dense codes stay on the decode kernels as long as the batch fits them, unless a tile path is forced
+    if ((flags & TQ_FLAG_FORCE_SKINNY) || (L.cw != 4 && !(flags & (TQ_FLAG_FORCE_SMALL_TILE | TQ_FLAG_FORCE_LARGE_TILE)))) skinny = true;
     return skinny && W.a_tot <= TQ_SKINNY_MAX_ROWS && tqi_skinny_supported(L);
 }
 
@@ -806,7 +834,9 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     MGeom G;
     G.ne = L.E + L.S; G.H = L.H; G.F = L.F; G.g = L.g; G.r = L.r; G.r16 = L.r16; G.k = L.k; G.S = L.S;
     G.a_tot = W.a_tot; G.expert_stride = L.expert_stride; G.fm = L.fm;
-    G.unpack_mask = 0x000F000Fu; G.unpack_magic = 0x43004300u;
+    G.unpack_mask = L.cw == 4 ? 0x000F000Fu : L.cw == 3 ? 0x00070007u : 0x00030003u;
+    G.unpack_magic = 0x43004300u;
+    G.zc_ws = nullptr; G.zc_stride = 0; G.zc_d_off = 0;
     const int32_t* ctrl = reinterpret_cast<const int32_t*>(ws + W.ctrl);
     const int32_t* offsets = reinterpret_cast<const int32_t*>(ws + W.offsets);
     const int32_t* slot_of = reinterpret_cast<const int32_t*>(ws + W.slot_of);
@@ -838,7 +868,15 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
         return TQ_OK;
     }
 
-    tq_status rc = launch_aug<0>(G, L.gu, blob, x, row_token, tile_e, tile_row0, offsets, ctrl, xaug_gu, W.ka_gu, rt32, stream);
+    tq_status rc;
+    if (L.cw != 4) {
+        // dense codes: the blob stores no zero-point coefficient fragments; the tiled kernels read them from the workspace
+        if (W.zc_stride == 0 || gs == 16) return TQ_ERR_UNSUPPORTED;
+        rc = tqi_derive_zc(L, W, blob, ws, stream);
+        if (rc != TQ_OK) return rc;
+        G.zc_ws = ws + W.zc_ws; G.zc_stride = W.zc_stride; G.zc_d_off = W.zc_d_off;
+    }
+    rc = launch_aug<0>(G, L.gu, blob, x, row_token, tile_e, tile_row0, offsets, ctrl, xaug_gu, W.ka_gu, rt32, stream);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(2, stream);
     // many rows per expert: persistent 64-row-tile workgroups (tq_prefill.hip) when the layer qualifies, else one
@@ -853,10 +891,10 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     else if (large)
         // 64-row tiles, four waves of 64x64: two such workgroups share a CU and run out of phase, so one's
         // per-unit tail (fold, staging store, barrier) overlaps the other's MFMAs
-        rc = launch_main_gs<2, 1, 0>(gs, G, L.gu, blob, x, xaug_gu, row_token, tile_e + 3 * (size_t)W.rt_max,
+        rc = launch_main_gs<2, 1, 0>(gs, L.cw, G, L.gu, blob, x, xaug_gu, row_token, tile_e + 3 * (size_t)W.rt_max,
                                      tile_row0 + 3 * (size_t)W.rt_max, offsets, ctrl, 5, h, W.ka_gu, 1, rt64, stream);
     else
-        rc = launch_main_gs<1, 1, 0>(gs, G, L.gu, blob, x, xaug_gu, row_token, tile_e, tile_row0, offsets, ctrl, 1, h, W.ka_gu, 1,
+        rc = launch_main_gs<1, 1, 0>(gs, L.cw, G, L.gu, blob, x, xaug_gu, row_token, tile_e, tile_row0, offsets, ctrl, 1, h, W.ka_gu, 1,
                                   rt32, stream);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(3, stream);
@@ -880,10 +918,10 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
         rc = tqi_forward_prefill_stage(1, L, W, G, blob, h, xaug_d, row_token, tile_e + 3 * (size_t)W.rt_max,
                                        tile_row0 + 3 * (size_t)W.rt_max, offsets, ctrl, 5, yd, stream);
     else if (large)
-        rc = launch_main_gs<2, 1, 1>(gs, G, L.d, blob, h, xaug_d, row_token, tile_e + 3 * (size_t)W.rt_max,
+        rc = launch_main_gs<2, 1, 1>(gs, L.cw, G, L.d, blob, h, xaug_d, row_token, tile_e + 3 * (size_t)W.rt_max,
                                      tile_row0 + 3 * (size_t)W.rt_max, offsets, ctrl, 5, yd, W.ka_d, 1, rt64, stream);
     else
-        rc = launch_main_gs<1, 1, 1>(gs, G, L.d, blob, h, xaug_d, row_token, tile_e, tile_row0, offsets, ctrl, 1, yd, W.ka_d,
+        rc = launch_main_gs<1, 1, 1>(gs, L.cw, G, L.d, blob, h, xaug_d, row_token, tile_e, tile_row0, offsets, ctrl, 1, yd, W.ka_d,
                                   nsplit, rt32, stream);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(5, stream);

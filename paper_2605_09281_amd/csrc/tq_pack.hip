@@ -312,6 +312,54 @@ __global__ void afrag_kernel(PackGeom G, uint8_t* __restrict__ blob, uint16_t* _
     }
 }
 
+// The same fragments as zc_kernel writes, computed from the blob's own sz part into a buffer outside the blob (dense
+// codes on the tiled kernels: such blobs store no zc part).  One thread per (pair, block of 16 groups, tile, lane): it
+// reads its 8 scale / zero words once and writes the hi and the lo fragment.
+__global__ void zc_from_blob_kernel(PackGeom G, const uint8_t* __restrict__ blob, uint8_t* __restrict__ zc_ws,
+                                    size_t zc_stride, size_t zc_d_off)
+{
+    const size_t n_gu = (size_t)G.gu.pairs * (G.gu.zfrag / 2) * 128;
+    const size_t n_d = (size_t)G.d.pairs * (G.d.zfrag / 2) * 128;
+    const size_t per_exp = n_gu + n_d;
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= per_exp * G.n_exp) return;
+    const int e = (int)(idx / per_exp);
+    size_t w = idx % per_exp;
+    const bool is_d = w >= n_gu;
+    const TqSection& sec = is_d ? G.d : G.gu;
+    if (is_d) w -= n_gu;
+    const int lane = (int)(w & 63), tile = (int)((w >> 6) & 1);
+    const size_t ps = w >> 7;
+    const int nblocks = sec.zfrag / 2;
+    const int gblock = (int)(ps % nblocks), pair = (int)(ps / nblocks);
+    const int col = lane & 31, hf = lane >> 5;
+    const uint32_t* sz = reinterpret_cast<const uint32_t*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.sz);
+    uint32_t v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int grp = min(16 * gblock + 8 * hf + i, sec.groups - 1);
+        v[i] = sz[(((size_t)pair * sec.groups + grp) * 2 + tile) * 32 + col];
+    }
+    uint16_t hi16[8], lo16[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int grp = 16 * gblock + 8 * hf + i;
+        const float s = __half2float(__ushort_as_half((uint16_t)(v[i] & 0xFFFF)));
+        const float z = __half2float(__ushort_as_half((uint16_t)(v[i] >> 16)));
+        const float c = -s * (128.0f + z);
+        const uint32_t hi = bf16_rne_bits(c);
+        const bool live = grp < sec.groups;
+        hi16[i] = live ? (uint16_t)hi : (uint16_t)0;
+        lo16[i] = live ? (uint16_t)bf16_rne_bits(c - __uint_as_float(hi << 16)) : (uint16_t)0;
+    }
+    // fragment f of (pair, tile, lane) sits at ((pair * zfrag + f) * 2 + tile) * 64 + lane, 8 values each
+    uint16_t* base = reinterpret_cast<uint16_t*>(zc_ws + (size_t)e * zc_stride + (is_d ? zc_d_off : 0));
+    uint16_t* dh = base + ((((size_t)pair * sec.zfrag + 2 * gblock) * 2 + tile) * 64 + lane) * 8;
+    uint16_t* dl = base + ((((size_t)pair * sec.zfrag + 2 * gblock + 1) * 2 + tile) * 64 + lane) * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { dh[i] = hi16[i]; dl[i] = lo16[i]; }
+}
+
 // Shared 2D-tiled factors.  Left factors: one thread per 8-element fragment of block (section, m); the block has the
 // afrag layout, its columns being [gate factor | up factor] (r16 each) in section GU and the down factor in D.
 __global__ void pool_afrag_kernel(PackGeom G, TqFactorMap fm, uint8_t* __restrict__ blob,
@@ -446,6 +494,17 @@ tq_status run(const TqLayout& L, uint8_t* blob, uint8_t* codes, uint16_t* scale,
 inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
 
 }  // namespace
+
+tq_status tqi_derive_zc(const TqLayout& L, const TqWorkspace& W, const uint8_t* blob, uint8_t* ws, hipStream_t stream)
+{
+    if (W.zc_stride == 0) return TQ_ERR_UNSUPPORTED;
+    const PackGeom G = make_geom(L);
+    const size_t n = ((size_t)L.gu.pairs * (L.gu.zfrag / 2) + (size_t)L.d.pairs * (L.d.zfrag / 2)) * 128 * (L.E + L.S);
+    hipLaunchKernelGGL(zc_from_blob_kernel, dim3(blocks_for(n)), dim3(256), 0, stream, G, blob, ws + W.zc_ws, W.zc_stride,
+                       W.zc_d_off);
+    TQ_CHECK_LAUNCH();
+    return TQ_OK;
+}
 
 extern "C" size_t tq_packed_size(const tq_layer_desc* desc)
 {

@@ -30,12 +30,14 @@ __device__ inline uint32_t opaque_mov(uint32_t x)
 
 struct WSrc {                // weight-side operand bases of one (expert, column pair): wave-uniform
     const u32x4* codes;
+    const uint32_t* codes32;   // the same part seen as dwords (dense 2- / 3-bit layouts)
     const uint32_t* sz;
     const u32x4* zc;
     const u32x4* bf;
 };
 
-template <int STAGE, int GS>
+// CW: 32-bit words of codes per lane, tile and 64-wide chunk: 4 (4-bit slots), 3 or 2 (dense 3- / 2-bit codes).
+template <int STAGE, int GS, int CW = 4>
 __global__ void __launch_bounds__(256, 2)
 moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, const uint16_t* __restrict__ xin,
                    const uint16_t* __restrict__ xaug, const int32_t* __restrict__ row_token,
@@ -53,6 +55,8 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
     constexpr int TPR = UNIT_K / 8;     // threads (16-byte segments) per row when loading a unit
     constexpr int RPP = NTHR / TPR;     // rows per pass
     constexpr int NP = BM / RPP;        // passes
+    using WT = std::conditional_t<CW == 4, u32x4, uint32_t>;      // register type of the packed codes
+    constexpr int WN = CW == 4 ? UC : UC * CW;                    // and how many of them one tile of a unit takes
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     int32_t* tok = reinterpret_cast<int32_t*>(lds + 2 * BUFB);   // [item parity][0: source row, 1: xaug row][BM]
@@ -91,8 +95,9 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
         const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
         WSrc s;
         s.codes = reinterpret_cast<const u32x4*>(rec + sec.codes) + (size_t)pair * sec.chunks * 128;
+        s.codes32 = reinterpret_cast<const uint32_t*>(rec + sec.codes) + (size_t)pair * sec.chunks * (2 * CW * 64);
         s.sz = reinterpret_cast<const uint32_t*>(rec + sec.sz) + (size_t)pair * sec.groups * 64;
-        s.zc = reinterpret_cast<const u32x4*>(rec + sec.zc) + (size_t)pair * sec.zsteps * 128;
+        s.zc = reinterpret_cast<const u32x4*>(tq_zc_base(G, blob, sec, STAGE, e)) + (size_t)pair * sec.zfrag * 128;
         s.bf = reinterpret_cast<const u32x4*>(G.r > 0 ? tq_bfrag_base(blob, G.expert_stride, sec, G.fm, STAGE, e) : rec + sec.bfrag) +
                (size_t)pair * (G.r16 / 16) * 128;
         return s;
@@ -126,11 +131,19 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
         for (int p = 0; p < NP; ++p)
             *reinterpret_cast<u32x4*>(lds + buf * BUFB + p * RPP * ROWB + lds_wr) = xr[p];
     };
-    auto load_w = [&](u32x4 (&dst)[2][UC], const WSrc& s, int u) {
+    auto load_w = [&](WT (&dst)[2][WN], const WSrc& s, int u) {
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int c = 0; c < UC; ++c) dst[t][c] = s.codes[((size_t)(u * UC + c) * 2 + t) * 64 + lane];
+            for (int c = 0; c < UC; ++c) {
+                if constexpr (CW == 4) {
+                    dst[t][c] = s.codes[((size_t)(u * UC + c) * 2 + t) * 64 + lane];
+                } else {
+#pragma unroll
+                    for (int d = 0; d < CW; ++d)
+                        dst[t][c * CW + d] = s.codes32[(((size_t)(u * UC + c) * 2 + t) * CW + d) * 64 + lane];
+                }
+            }
     };
     auto load_sz = [&](uint32_t (&dst)[NG][2], const WSrc& s, int u) {
 #pragma unroll
@@ -173,7 +186,7 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
     uint32_t magic_v;
     asm volatile("v_mov_b32 %0, %1" : "=v"(magic_v) : "s"(G.unpack_magic));
 
-    u32x4 wq[2][2][UC];
+    WT wq[2][2][WN];
     uint32_t szq[2][NG][2];
 
     // ---- start-up: the only place where the chain of dependent loads is exposed -------------------------
@@ -288,7 +301,7 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
             // the next item is fetched after the loop, where registers are free to recompute the row offsets)
             xsb = reinterpret_cast<const uint8_t*>(xin) + (size_t)min(mu + 1, nmain - 1) * UNIT_K * 2;
             load_x();
-            u32x4 wc[2][UC];
+            WT wc[2][WN];
             uint32_t szc[NG][2];
             // The copies are opaque moves: the slot is dead afterwards, so the prefetch below can land in the very
             // same registers.  Left to itself the compiler keeps the old values in place instead and renames the
@@ -296,9 +309,14 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int c = 0; c < UC; ++c)
+                for (int c = 0; c < WN; ++c) {
+                    if constexpr (CW == 4) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) wc[t][c][i] = opaque_mov(wq[SLOT][t][c][i]);
+                        for (int i = 0; i < 4; ++i) wc[t][c][i] = opaque_mov(wq[SLOT][t][c][i]);
+                    } else {
+                        wc[t][c] = opaque_mov(wq[SLOT][t][c]);
+                    }
+                }
 #pragma unroll
             for (int gi = 0; gi < NG; ++gi)
 #pragma unroll
@@ -332,8 +350,10 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
                     if (kidx + 1 < US) read_a(kidx + 1, 0, 1);
                     bf16x8 bw[2];
 #pragma unroll
-                    for (int t = 0; t < 2; ++t)
-                        bw[t] = unpack_word(word_of(wc[t][kidx / 4], kidx % 4), G.unpack_mask, magic_v);
+                    for (int t = 0; t < 2; ++t) {
+                        if constexpr (CW == 4) bw[t] = unpack_word(word_of(wc[t][kidx / 4], kidx % 4), G.unpack_mask, magic_v);
+                        else bw[t] = unpack_dense<CW>(&wc[t][(kidx / 4) * CW], kidx % 4, G.unpack_mask, magic_v);
+                    }
                     auto mfmas = [&](int m0, int m1) {
 #pragma unroll
                         for (int mt = m0; mt < m1; ++mt) {
@@ -443,7 +463,7 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
     }
 }
 
-template <int STAGE, int GS>
+template <int STAGE, int GS, int CW = 4>
 tq_status launch_prefill(const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin,
                          const uint16_t* xaug, const int32_t* row_token, const int32_t* tile_e,
                          const int32_t* tile_row0, const int32_t* offsets, const int32_t* ctrl, int ctrl_idx,
@@ -457,7 +477,7 @@ tq_status launch_prefill(const MGeom& G, const TqSection& sec, const uint8_t* bl
     if (tqi_device_state(&ds) != TQ_OK) return TQ_ERR_HIP;
     const int n_cu = ds->n_cu;
     const int grid = (2 * n_cu) / 8 * 8;     // two workgroups per CU, a whole number per XCD
-    hipLaunchKernelGGL((moe_prefill_kernel<STAGE, GS>), dim3(grid), dim3(256), smem, st, G, sec, blob, xin, xaug, row_token,
+    hipLaunchKernelGGL((moe_prefill_kernel<STAGE, GS, CW>), dim3(grid), dim3(256), smem, st, G, sec, blob, xin, xaug, row_token,
                        tile_e, tile_row0, offsets, ctrl, ctrl_idx, out, ka);
     TQ_CHECK_LAUNCH();
     return TQ_OK;
@@ -493,6 +513,17 @@ tq_status tqi_forward_prefill_stage(int stage, const TqLayout& L, const TqWorksp
                                                    ctrl_idx, out, ka, st)                                             \
                           : launch_prefill<1, GSV>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl, \
                                                    ctrl_idx, out, ka, st)
+    if (L.cw != 4) {      // dense codes: groups of 64 and 128
+#define TQ_DENSE(GSV, CWV)                                                                                                  \
+    if (gs == GSV && L.cw == CWV)                                                                                           \
+        return stage == 0 ? launch_prefill<0, GSV, CWV>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl, \
+                                                        ctrl_idx, out, ka, st)                                              \
+                          : launch_prefill<1, GSV, CWV>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl, \
+                                                        ctrl_idx, out, ka, st)
+        TQ_DENSE(4, 3); TQ_DENSE(8, 3); TQ_DENSE(4, 2); TQ_DENSE(8, 2);
+#undef TQ_DENSE
+        return TQ_ERR_UNSUPPORTED;
+    }
     switch (gs) {
         TQ_CASE(2);
         TQ_CASE(4);

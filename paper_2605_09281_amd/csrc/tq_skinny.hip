@@ -575,6 +575,7 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     G.a_tot = W.a_tot; G.expert_stride = L.expert_stride; G.fm = L.fm;
     G.unpack_mask = L.cw == 4 ? 0x000F000Fu : L.cw == 3 ? 0x00070007u : 0x00030003u;
     G.unpack_magic = 0x43004300u;
+    G.zc_ws = nullptr; G.zc_stride = 0; G.zc_d_off = 0;
     const int32_t* ctrl = reinterpret_cast<const int32_t*>(ws + W.ctrl);
     const int32_t* offsets = reinterpret_cast<const int32_t*>(ws + W.offsets);
     const int32_t* row_token = reinterpret_cast<const int32_t*>(ws + W.row_token);

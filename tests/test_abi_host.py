@@ -132,6 +132,14 @@ def test_workspace_size_never_shrinks_as_tokens_grow(E, S, k, H, F, g, r):
                     2 * 4096 // per, 8192, 20000} - {0})
     sizes = [tq.tq_moe_workspace_size(d, T) for T in marks]
     assert all(b >= a > 0 for a, b in zip(sizes, sizes[1:])), list(zip(marks, sizes))
+    if g >= 64:
+        # dense codes: beyond the decode path the workspace also holds the derived zero-point coefficient fragments
+        dd = tq.make_desc(E, S, k, H, F, g, 3, r, flags=tq.TQ_FLAG_DENSE_CODES)
+        dsizes = [tq.tq_moe_workspace_size(dd, T) for T in marks]
+        assert all(b >= a > 0 for a, b in zip(dsizes, dsizes[1:])), list(zip(marks, dsizes))
+        zc = (E + S) * 2048 * (2 * -(-(H // g) // 16) * (F // 32) + 2 * -(-(F // g) // 16) * (H // 64))
+        assert tq.tq_moe_workspace_size(dd, 1024 // per) == tq.tq_moe_workspace_size(d, 1024 // per)     # decode batches: nothing extra
+        assert tq.tq_moe_workspace_size(dd, 20000) == tq.tq_moe_workspace_size(d, 20000) + zc
 
 
 # ------------------------------------------------------------------ shared-factor low-rank operator (host side)

@@ -122,8 +122,42 @@ def test_dense_forward_fp32(name):
     assert rel_err(got, ref) <= TOL_FP32
 
 
-def test_dense_beyond_the_decode_kernels_is_refused_before_any_launch():
-    cfg = dcfg(820, T=600)              # 1200 assignment rows: more than the decode kernels take
+TILED = {"small_tile": tq.TQ_FLAG_FORCE_SMALL_TILE, "large_tile": tq.TQ_FLAG_FORCE_LARGE_TILE}
+
+
+@pytest.mark.parametrize("path", list(TILED))
+@pytest.mark.parametrize("kind", ["plain", "amplified", "odd_quant"])
+@pytest.mark.parametrize("name", list(CASES))
+def test_dense_forward_bf16_tiled_kernels(name, kind, path):
+    """Dense codes on the 32-row and the 64-row (persistent where the layer qualifies) tiled kernels: the blob stores no
+    zero-point coefficient fragments, the forward derives them into the workspace."""
+    print(f"dense tiled {name} {kind} {path}", flush=True)
+    layer, x, (logits, bias) = get(name)
+    if kind == "amplified":
+        if layer.cfg.r == 0:
+            pytest.skip("no factors")
+        layer = variants.amplified(layer)
+    elif kind == "odd_quant":
+        layer = variants.odd_quant(layer, layer.cfg.cfg_id)
+    got, ref = forward(layer, x, logits, bias, tq.TQ_ACT_BF16, TILED[path])
+    err = rel_err(got, ref)
+    print(f"   rel err {err:.3e}", flush=True)
+    assert err <= TOL_BF16
+    assert err <= (REG_LR_BF16 if kind == "amplified" else REG_BF16)
+
+
+@pytest.mark.parametrize("bits", [3, 2])
+def test_dense_batch_beyond_the_decode_kernels_takes_the_tiled_kernels(bits):
+    cfg = dcfg(820 + bits, bits=bits, E=5, k=2, T=700, H=256, F=384, g=128, r=16)     # 1400 assignment rows, ragged tiles
+    layer = make_layer(cfg, workers=8)
+    got, ref = forward(layer, make_x(cfg), *make_logits(cfg), tq.TQ_ACT_BF16)
+    err = rel_err(got, ref)
+    print(f"dense {bits}-bit, 1400 rows: rel err {err:.3e}", flush=True)
+    assert err <= REG_BF16
+
+
+def test_dense_groups_of_256_have_no_bf16_kernel():
+    cfg = dcfg(829, g=256, H=256, F=256, T=8)
     desc = desc_of(cfg)
     x = torch.zeros((cfg.T, cfg.H), dtype=torch.bfloat16, device=DEV)
     idx = torch.zeros((cfg.T, cfg.k), dtype=torch.int32, device=DEV)
@@ -132,10 +166,29 @@ def test_dense_beyond_the_decode_kernels_is_refused_before_any_launch():
     with pytest.raises(tq.TqError) as ei:
         tq.tq_moe_forward(desc, blob, x, idx, w)
     assert ei.value.status == 6
-    small = dcfg(821, T=8)
-    with pytest.raises(tq.TqError) as ei:
-        tq.tq_moe_forward(desc_of(small, flags=tq.TQ_FLAG_FORCE_LARGE_TILE), blob, x[:8], idx[:8], w[:8])
-    assert ei.value.status == 6
+
+
+def test_dense_prefill_full_shape():
+    """The 66-expert prefill layer (benchmark config 3) re-quantised to 3 bits, stored densely, on the persistent
+    prefill kernel; token rows sampled (rows are independent: each is the oracle's exact row)."""
+    cfg = CONFIGS[3].replace(bits=3, dense=True, cfg_id=840)
+    print("dense config 3 at 3 bits: generating", flush=True)
+    layer = make_layer(cfg, workers=16)
+    x = make_x(cfg)
+    logits, bias = make_logits(cfg)
+    packed = pack_layer_gpu(layer)
+    idx, w = tq.tq_route(torch.from_numpy(logits).to(DEV), None if bias is None else torch.from_numpy(bias).to(DEV), cfg.k)
+    desc = desc_of(cfg)
+    ws = torch.empty(tq.tq_moe_workspace_size(desc, cfg.T), dtype=torch.uint8, device=DEV)
+    y = tq.tq_moe_forward(desc, packed, x_device(x, tq.TQ_ACT_BF16), idx, w, workspace=ws)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32).item()) == 0
+    tokens = np.sort(np.random.default_rng(840).choice(cfg.T, size=48, replace=False)).astype(np.int32)
+    ref = oracle.moe_forward_layer(layer, x, idx.cpu().numpy(), w.cpu().numpy(), tokens=tokens)
+    got = y.float().cpu().numpy()[tokens]
+    err = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+    print(f"dense config 3 at 3 bits: rel err {err:.3e} on {tokens.size} tokens", flush=True)
+    assert err <= REG_BF16
 
 
 @pytest.mark.parametrize("bits", [3, 2])

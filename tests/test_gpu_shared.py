@@ -109,8 +109,6 @@ def test_shared_forward_bf16(name, path):
     print(f"shared bf16 {name} {path}", flush=True)
     sl, x, (logits, bias) = get(name)
     cfg = sl.cfg
-    if cfg.dense and path in ("small_tile", "large_tile"):
-        pytest.skip("dense codes run on the decode kernels only")
     packed, err = pack_shared_gpu(sl)
     assert err == 0
     idx, w = tq.tq_route(torch.from_numpy(logits).to(DEV), None if bias is None else torch.from_numpy(bias).to(DEV), cfg.k)
