@@ -66,7 +66,7 @@ class HipEvents:
         return float(ms.value)
 
 
-def algorithmic_work(cfg, idx_np):
+def algorithmic_work(cfg, idx_np, fp8=False):
     """Algorithmic bytes and flops of one forward, whole path and per dominant kernel: every expert that receives a
     token is read once (codes, scales, zeros, factors), every activation row once per stage."""
     import numpy as np
@@ -74,10 +74,11 @@ def algorithmic_work(cfg, idx_np):
     touched = int(np.unique(idx_np).size) + cfg.S
     a_tot = cfg.a_tot
     cb = cfg.bits if cfg.dense else 4                              # bits each code occupies in the blob
-    gu_w = 2 * F * H * cb // 8 + 2 * F * (H // g) * 4 + 2 * r * F * 2   # codes (2 matrices) + scale/zero + B factors
-    gu_a = 2 * H * r * 2                                           # A factors (read by the pre-pass)
-    d_w = H * F * cb // 8 + H * (F // g) * 4 + r * H * 2
-    d_a = F * r * 2
+    fb = 1 if fp8 else 2                                           # bytes per factor element
+    gu_w = 2 * F * H * cb // 8 + 2 * F * (H // g) * 4 + 2 * r * F * fb  # codes (2 matrices) + scale/zero + B factors
+    gu_a = 2 * H * r * fb + (2 * r * 2 if fp8 else 0)              # A factors (read by the pre-pass), Sigma
+    d_w = H * F * cb // 8 + H * (F // g) * 4 + r * H * fb
+    d_a = F * r * fb + (r * 2 if fp8 else 0)
     w_bytes = touched * (gu_w + gu_a + d_w + d_a)
     act_bytes = T * H * 2 * 2                                      # x in, y out
     flops_gu = a_tot * (4 * H * F + 4 * r * (H + F))               # gate+up: 2 matrices x 2 flop, plus low-rank
@@ -243,6 +244,8 @@ def main():
     ap.add_argument("--dense-bits", type=int, default=0, choices=[0, 2, 3],
                     help="with --workload: re-quantise the layer's weights to 2 or 3 bits and store the codes densely "
                          "(decode workloads only)")
+    ap.add_argument("--fp8-factors", action="store_true",
+                    help="with --workload: store the low-rank factors as fp8 E4M3 codes with an fp16 diagonal Sigma")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every step eagerly instead of replaying a captured HIP graph")
@@ -357,7 +360,7 @@ def main():
         wl = CONFIGS[args.workload]
         if args.dense_bits:
             wl = wl.replace(bits=args.dense_bits, dense=True)
-        res = bench_layer(args, wl, dev, oracle_macs=1.5e11)
+        res = bench_layer(args, wl, dev, oracle_macs=1.5e11, fp8=args.fp8_factors)
         print(json.dumps(headline(args, res, None)), flush=True)
         return
     # default: every benchmark layer in turn (configs 1-4 with a short oracle sample), the headline on the largest
@@ -398,15 +401,15 @@ def headline(args, res, per):
     return out
 
 
-def bench_layer(args, cfg, dev, oracle_macs):
+def bench_layer(args, cfg, dev, oracle_macs, fp8=False):
     """Times K steps of route + forward on one benchmark layer; returns a dict of results."""
     import numpy as np
     import torch
-    from synth import make_layer, make_x, make_logits, f32_to_bf16_bits
+    from synth import make_layer, make_layer_fp8, make_x, make_logits, f32_to_bf16_bits
     import paper_2605_09281_amd.binding as tq
 
     t0 = time.time()
-    layer = make_layer(cfg, workers=min(16, os.cpu_count() or 8))
+    layer = (make_layer_fp8 if fp8 else make_layer)(cfg, workers=min(16, os.cpu_count() or 8))
     x = make_x(cfg)
     logits, bias = make_logits(cfg)
     log(f"workload {cfg.cfg_id} ({cfg.name}): inputs generated in {time.time() - t0:.1f}s")
@@ -415,15 +418,19 @@ def bench_layer(args, cfg, dev, oracle_macs):
         return torch.from_numpy(a.view(np.int16)).to(dev)
 
     desc = tq.make_desc(cfg.E, cfg.S, cfg.k, cfg.H, cfg.F, cfg.g, cfg.bits, cfg.r, tq.TQ_ACT_BF16,
-                        tq.TQ_FLAG_DENSE_CODES if cfg.dense else 0)
+                        (tq.TQ_FLAG_DENSE_CODES if cfg.dense else 0) | (tq.TQ_FLAG_FP8_FACTORS if fp8 else 0))
     codes_d = torch.from_numpy(layer.codes).to(dev)
     sc_d, ze_d = dev16(layer.scale), dev16(layer.zero)
-    A_d = dev16(layer.A) if cfg.r else None
-    B_d = dev16(layer.B) if cfg.r else None
+    if fp8:
+        A_d, B_d, sg_d = torch.from_numpy(layer.A8).to(dev), torch.from_numpy(layer.B8).to(dev), dev16(layer.sigma)
+    else:
+        A_d = dev16(layer.A) if cfg.r else None
+        B_d = dev16(layer.B) if cfg.r else None
+        sg_d = None
     n_copies = 2      # rotate weight copies so that no step finds its weights warm in the last-level cache
-    packed = [tq.tq_pack_weights(desc, codes_d, sc_d, ze_d, A_d, B_d) for _ in range(n_copies)]
+    packed = [tq.tq_pack_weights(desc, codes_d, sc_d, ze_d, A_d, B_d, sigma=sg_d) for _ in range(n_copies)]
     torch.cuda.synchronize()
-    del codes_d, sc_d, ze_d, A_d, B_d
+    del codes_d, sc_d, ze_d, A_d, B_d, sg_d
     torch.cuda.empty_cache()
     logits_d = torch.from_numpy(logits).to(dev)
     bias_d = None if bias is None else torch.from_numpy(bias).to(dev)
@@ -516,7 +523,7 @@ def bench_layer(args, cfg, dev, oracle_macs):
     log("stage durations (us): " + ", ".join(f"{k}={v:.1f}" for k, v in stage_us.items()))
 
     idx_np = idx_d.cpu().numpy()
-    work = algorithmic_work(cfg, idx_np)
+    work = algorithmic_work(cfg, idx_np, fp8)
     t_step = ms_per_step * 1e-3
     hbm_path = work["path_bytes"] / t_step / HBM_PEAK
     mfma_path = work["path_flops"] / t_step / MFMA_BF16_PEAK
@@ -525,7 +532,7 @@ def bench_layer(args, cfg, dev, oracle_macs):
     decode_path = cfg.a_tot / (cfg.E + cfg.S) <= 12 and cfg.a_tot <= 1024
     kname = ("gate/up stage (moe_skinny_kernel<0,.>)" if decode_path else
              "gate/up stage (moe_prefill_kernel<0,.>, or moe_mfma_kernel<.,.,0,.> where the layer does not qualify)")
-    traffic, traffic_source = (None, None) if cfg.dense else TRAFFIC_FROM_PROFILES.get(cfg.cfg_id, (None, None))
+    traffic, traffic_source = (None, None) if (cfg.dense or fp8) else TRAFFIC_FROM_PROFILES.get(cfg.cfg_id, (None, None))
     if hbm_bound:
         ach = work["gate_up_bytes"] / t_gu / 1e9
         roofline = dict(bound="hbm", kernel=kname, achieved=round(ach, 1), peak=HBM_PEAK / 1e9, unit="GB/s",
@@ -556,7 +563,11 @@ def bench_layer(args, cfg, dev, oracle_macs):
         tok = np.linspace(0, cfg.T - 1, n_tok).astype(np.int32)
         w_np = w_d.cpu().numpy()
         t1 = time.perf_counter()
-        y_ref = oracle.moe_forward_layer(layer, x, ridx, w_np, tokens=tok)
+        if fp8:
+            y_ref = oracle.moe_forward_fp8(cfg, layer.codes, layer.scale, layer.zero, layer.a8_list(), layer.b8_list(),
+                                           layer.sigma, x, ridx, w_np, tokens=tok)
+        else:
+            y_ref = oracle.moe_forward_layer(layer, x, ridx, w_np, tokens=tok)
         cpu_s = time.perf_counter() - t1
         got = y_d.float().cpu().numpy()[tok].astype(np.float64)
         max_rel_err = float(np.max(np.abs(got - y_ref)) / np.max(np.abs(y_ref)))
@@ -568,7 +579,7 @@ def bench_layer(args, cfg, dev, oracle_macs):
     return dict(tokens_per_s=round(cfg.T / t_step, 1), ms_per_step=round(ms_per_step, 5),
                 ms_per_step_median=round(ms_median, 5), ms_per_step_min=round(ms_min, 5),
                 launch="hip_graph" if use_graph else "eager", spinup_steps=spinup,
-                config={"workload": f"config {cfg.cfg_id}: {cfg.name}" + (f", codes re-quantised to {cfg.bits} bits, stored densely" if cfg.dense else ""), "experts": cfg.E, "shared": cfg.S, "top_k": cfg.k,
+                config={"workload": f"config {cfg.cfg_id}: {cfg.name}" + (f", codes re-quantised to {cfg.bits} bits, stored densely" if cfg.dense else "") + (", fp8 E4M3 factors with fp16 Sigma" if fp8 else ""), "experts": cfg.E, "shared": cfg.S, "top_k": cfg.k,
                         "hidden": cfg.H, "ffn": cfg.F, "tokens": cfg.T, "group": cfg.g, "rank": cfg.r, "bits": cfg.bits,
                         "touched_experts": work["touched"]},
                 roofline=roofline, cpu_baseline=cpu_baseline, max_rel_err=max_rel_err)

@@ -107,7 +107,17 @@ enum {
        and 128; the zero-point coefficient fragments the blob does not store are derived into the workspace on
        every call, which tq_moe_workspace_size accounts for) and the fp32 debug path; what none of them covers
        (groups of 256 with bf16 activations) returns TQ_ERR_UNSUPPORTED before any launch. */
-    TQ_FLAG_DENSE_CODES = 32
+    TQ_FLAG_DENSE_CODES = 32,
+    /* Part of the format as well: the low-rank factors stored as fp8 E4M3 codes with an fp16 diagonal Sigma per
+       rank component (mixed-precision factor storage, end of Section 3.1; Appendix A.3 with d_low = 8).  The
+       effective factors are A = fp8(A8) diag(sigma), B = fp8(B8): a projection's low-rank term is
+       ((x fp8(A8)) * sigma) fp8(B8).  E4M3 as for tq_lotile_pack_fp8 (OCP variant without infinities; NaN codes
+       are not supported).  The factor parts of the blob then hold one byte per element in the layouts above
+       (bfrag8, afrag8: the fp16 layouts with 1-byte elements) plus
+         sig    fp32   [NA]   per section: sigma widened to fp32, gate then up (r16 each) in GU, r16 in D, 0 beyond r
+       behind them.  Requires rank >= 1.  Kernels: all paths (the tiled bf16 kernels read fp16 fragments expanded
+       into the workspace on every call, which tq_moe_workspace_size accounts for). */
+    TQ_FLAG_FP8_FACTORS = 64
 };
 
 typedef struct tq_layer_desc {
@@ -130,13 +140,15 @@ typedef struct tq_layer_desc {
 typedef struct tq_weights_src { /* canonical layout above; A, B may be NULL when rank == 0 */
     const uint8_t *codes;
     const uint16_t *scale, *zero;
-    const uint16_t *A, *B;
+    const uint16_t *A, *B;     /* with TQ_FLAG_FP8_FACTORS: the same arrays as uint8 E4M3 codes (cast the pointers) */
+    const uint16_t *sigma;     /* with TQ_FLAG_FP8_FACTORS: fp16 [E+S][3][r] (gate, up, down), else ignored */
 } tq_weights_src;
 
 typedef struct tq_weights_dst {
     uint8_t *codes;
     uint16_t *scale, *zero;
-    uint16_t *A, *B;
+    uint16_t *A, *B;           /* with TQ_FLAG_FP8_FACTORS: uint8 arrays */
+    uint16_t *sigma;           /* with TQ_FLAG_FP8_FACTORS: fp16 [E+S][3][r] */
 } tq_weights_dst;
 
 /* Text for a status code (static storage, host). */
@@ -170,9 +182,11 @@ tq_status tq_pack_weights(const tq_layer_desc *desc, const tq_weights_src *src, 
  * All device pointers.  The layer then computes exactly what tq_pack_weights computes with the effective factors
  * A_e = us[p][m(e)], B_e = v[p][n(e)]. */
 typedef struct tq_shared_factors {
-    const uint16_t *us[3];
-    const uint16_t *v[3];
+    const uint16_t *us[3];     /* with TQ_FLAG_FP8_FACTORS: uint8 E4M3 codes of U_m (cast the pointers) */
+    const uint16_t *v[3];      /* with TQ_FLAG_FP8_FACTORS: uint8 E4M3 codes of V_n */
     const int32_t *phi;
+    const uint16_t *sigma;     /* with TQ_FLAG_FP8_FACTORS: fp16 [3][r], the diagonal Sigma of each projection's tiled
+                                  decomposition, shared by all tiles; else ignored */
 } tq_shared_factors;
 
 /* As tq_pack_weights for a descriptor with tiles_m, tiles_n >= 1: src->codes / scale / zero as there (src->A, src->B

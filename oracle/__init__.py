@@ -216,6 +216,44 @@ def moe_forward_shared(slayer, x: np.ndarray, idx: np.ndarray, w: np.ndarray,
     return y
 
 
+def moe_forward_fp8(cfg, codes, scale, zero, a8, b8, sigma, x, idx, w, phi=None, tokens=None) -> np.ndarray:
+    """The layer with fp8 E4M3 factors and an fp16 Sigma.  a8 / b8: 3-lists (gate, up, down) of uint8 arrays
+    [nA, K_p, r] / [nB, r, N_p].  phi None: per-expert factors (nA = nB = E+S, sigma fp16 bits [E+S, 3, r]);
+    phi int32 [E+S, 2]: shared tiled factors (sigma [3, r]).  Returns float64 [n_tokens, H]."""
+    c = cfg
+    x = _c(x, np.float32)
+    T = x.shape[0]
+    idx = _c(idx, np.int32)
+    w = _c(w, np.float32)
+    codes, scale, zero = _c(codes, np.uint8), _c(scale, np.uint16), _c(zero, np.uint16)
+    a8 = [_c(a, np.uint8) for a in a8]
+    b8 = [_c(b, np.uint8) for b in b8]
+    sigma = _c(sigma, np.uint16)
+    dims = ((c.H, c.F), (c.H, c.F), (c.F, c.H))
+    nA, nB = a8[0].shape[0], b8[0].shape[0]
+    for p, (K, No) in enumerate(dims):
+        assert a8[p].shape == (nA, K, c.r) and b8[p].shape == (nB, c.r, No)
+    if phi is None:
+        assert nA == nB == c.E + c.S and sigma.shape == (c.E + c.S, 3, c.r)
+    else:
+        phi = _c(phi, np.int32)
+        assert phi.shape == (c.E + c.S, 2) and sigma.shape == (3, c.r)
+    tok = None if tokens is None else _c(tokens, np.int32)
+    n = T if tok is None else tok.size
+    y = np.empty((n, c.H), dtype=np.float64)
+    L = OrcLayer(c.E, c.S, c.k, c.H, c.F, c.g, c.bits, c.r)
+    pa = (ctypes.c_void_p * 3)(*[a.ctypes.data for a in a8])
+    pb = (ctypes.c_void_p * 3)(*[b.ctypes.data for b in b8])
+    lb = lib()
+    lb.orc_moe_forward_fp8.restype = ctypes.c_int32
+    rc = lb.orc_moe_forward_fp8(ctypes.byref(L), _p(codes), _p(scale), _p(zero), pa, pb, _p(sigma), _p(phi),
+                                ctypes.c_int32(nA), ctypes.c_int32(nB), _p(x), _p(idx), _p(w), ctypes.c_int32(T), _p(tok),
+                                ctypes.c_int32(n), _p(y))
+    if rc != 0:
+        raise ValueError("oracle: expert, token or tile index out of range")
+    return y
+
+
 def lotile_forward(x: np.ndarray, us_bits: np.ndarray, v_bits: np.ndarray, phi: np.ndarray,
                    idx: np.ndarray, w: np.ndarray) -> np.ndarray:
     """LoTileMoE of Section 3.2 (three-dimensional accumulator form).  x [T, in] fp32; us_bits [M, in, r] and

@@ -118,10 +118,20 @@ def _afrag_d(A2, r16, K) -> bytes:
     return np.ascontiguousarray(a.transpose(3, 0, 1, 4, 2)).tobytes()
 
 
-def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r, dense_bits=0, factors=True) -> bytes:
+def _sig_part(sig_list, r16) -> bytes:
+    """fp16 bit patterns [r] per projection -> fp32 [len(sig_list) * r16] (zero beyond r), padded to 256 bytes."""
+    out = np.zeros((len(sig_list), r16), dtype=np.float32)
+    for i, sg in enumerate(sig_list):
+        out[i, :sg.size] = np.asarray(sg, dtype=np.uint16).view(np.float16).astype(np.float32)
+    b = out.tobytes()
+    return b + b"\0" * ((-len(b)) % 256)
+
+
+def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r, dense_bits=0, factors=True, sigma3=None) -> bytes:
     """codes3[p]: [N,K] uint8; scale3/zero3[p]: [N,K/g] uint16; A3[p]: [K,r] uint16; B3[p]: [r,N] uint16.
     dense_bits: 0 = codes in 4-bit slots; 2 or 3 = the dense layouts (no zc part).  factors=False: a record of the
-    shared-factor format (no bfrag / afrag parts)."""
+    shared-factor format (no bfrag / afrag parts).  sigma3 (fp16 bits [r] per projection): fp8 factors, A3 / B3 are
+    then uint8 E4M3 codes in the same layouts with 1-byte elements, followed by the fp32 sig part."""
     r16 = (r + 15) // 16 * 16
     parts = []
 
@@ -149,6 +159,8 @@ def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r, dense_bits=0, factors
             if r > 0 and factors:
                 parts.append(_bfrag_gu(B3[0], B3[1], r16, pairs))
                 parts.append(_afrag_gu(A3[0], A3[1], r16, K))
+                if sigma3 is not None:
+                    parts.append(_sig_part([sigma3[0], sigma3[1]], r16))
         else:
             K, pairs = F, H // 64
             if dense_bits:
@@ -169,6 +181,8 @@ def pack_expert(codes3, scale3, zero3, A3, B3, H, F, g, r, dense_bits=0, factors
             if r > 0 and factors:
                 parts.append(_bfrag_d(B3[2], r16, pairs))
                 parts.append(_afrag_d(A3[2], r16, K))
+                if sigma3 is not None:
+                    parts.append(_sig_part([sigma3[2]], r16))
 
     section(False)
     section(True)
@@ -209,9 +223,29 @@ def pack_layer_shared(sl) -> np.ndarray:
     phi = np.ascontiguousarray(sl.phi, dtype=np.int32).tobytes()
     out.append(phi + b"\0" * ((-len(phi)) % 256))
     M, N = sl.us[0].shape[0], sl.v[0].shape[0]
+    sigma = getattr(sl, "sigma", None)          # fp8 factors: us / v are uint8 arrays and one Sigma [3, r] follows the pools
     out += [_afrag_gu(sl.us[0][m], sl.us[1][m], r16, c.H) for m in range(M)]
     out += [_bfrag_gu(sl.v[0][n], sl.v[1][n], r16, c.F // 32) for n in range(N)]
+    if sigma is not None:
+        out.append(_sig_part([sigma[0], sigma[1]], r16))
     out += [_afrag_d(sl.us[2][m], r16, c.F) for m in range(M)]
     out += [_bfrag_d(sl.v[2][n], r16, c.H // 64) for n in range(N)]
+    if sigma is not None:
+        out.append(_sig_part([sigma[2]], r16))
     body = b"".join(out)
     return np.frombuffer(body + b"\0" * ((-len(body)) % 256), dtype=np.uint8)
+
+
+def pack_layer_fp8(fl) -> np.ndarray:
+    """Blob body for a layer with fp8 factors (object with .cfg, .codes/.scale/.zero, .a8_list(), .b8_list(), .sigma)."""
+    c = fl.cfg
+    a8, b8 = fl.a8_list(), fl.b8_list()
+    out = []
+    for e in range(c.E + c.S):
+        codes3 = [fl.codes[e, p].reshape((c.F, c.H) if p < 2 else (c.H, c.F)) for p in range(3)]
+        scale3 = [fl.scale[e, p].reshape(codes3[p].shape[0], -1) for p in range(3)]
+        zero3 = [fl.zero[e, p].reshape(codes3[p].shape[0], -1) for p in range(3)]
+        out.append(pack_expert(codes3, scale3, zero3, [a8[p][e] for p in range(3)], [b8[p][e] for p in range(3)], c.H, c.F,
+                               c.g, c.r, dense_bits=c.bits if getattr(c, "dense", False) else 0,
+                               sigma3=[fl.sigma[e, p] for p in range(3)]))
+    return np.frombuffer(b"".join(out), dtype=np.uint8)

@@ -19,6 +19,7 @@
  *     ("Basic Quantization");
  *   - orc_moe_forward_shared: the same layer on SHARED 2D-tiled factors (Eq. 4 with the placement table phi),
  *     every projection's low-rank term in the accumulator form of Section 3.2;
+ *   - orc_moe_forward_fp8: the layer with fp8 E4M3 factors and an fp16 diagonal Sigma, per-expert or shared tiled;
  *   - orc_lotile_forward: the fused low-rank path over shared 2D-tiled factors, LoTileMoE of
  *     Section 3.2 in its defining three-dimensional accumulator form (the construction that ends
  *     in Eq. 15), NOT the compact buffer of Eq. 16 that an implementation would use;
@@ -339,6 +340,91 @@ int32_t orc_moe_forward_shared(const orc_layer *L, const orc_weights *Wt, const 
     free(xv);
     free(ye);
     free(Gv);
+    return rc;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * The layer with mixed-precision factors (end of Section 3.1; Appendix A.3 with d_low = 8): the factors are fp8 E4M3
+ * codes and a diagonal Sigma in fp16 carries the magnitude.  A projection's low-rank term is
+ *     ((v fp8(A8)) * sigma) fp8(B8),
+ * everything else as orc_moe_forward.  One routine for both factor formats: per projection p the left factors are
+ * a8[p] [nA][K_p][r] and the right factors b8[p] [nB][r][N_p]; with phi == NULL expert e uses block e of both and
+ * sigma [E+S][3][r] (per-expert factors), otherwise blocks phi[e] = (m, n) and one sigma [3][r] (shared tiled factors).
+ */
+double orc_fp8_e4m3_to_double(uint8_t b);      /* the format's decode, defined with the shared-factor operator below */
+
+static void orc_project_fp8(const double *v, const uint8_t *q, const uint16_t *scale, const uint16_t *zero,
+                            const uint8_t *A8, const uint16_t *sigma, const uint8_t *B8, int32_t N, int32_t K, int32_t g,
+                            int32_t r, double *out)
+{
+    int32_t G = K / g;
+    double *t = (double *)malloc(sizeof(double) * (size_t)r);
+    for (int32_t rho = 0; rho < r; ++rho) {
+        double acc = 0.0;
+        for (int32_t kk = 0; kk < K; ++kk) acc += v[kk] * orc_fp8_e4m3_to_double(A8[(size_t)kk * r + rho]);
+        t[rho] = acc * orc_half_to_double(sigma[rho]);
+    }
+#pragma omp parallel for schedule(static)
+    for (int32_t n = 0; n < N; ++n) {
+        double acc = 0.0;
+        for (int32_t gi = 0; gi < G; ++gi) {
+            double s = orc_half_to_double(scale[(size_t)n * G + gi]);
+            double z = orc_half_to_double(zero[(size_t)n * G + gi]);
+            for (int32_t kk = gi * g; kk < (gi + 1) * g; ++kk)
+                acc += v[kk] * (((double)q[(size_t)n * K + kk] - z) * s);
+        }
+        double lr = 0.0;
+        for (int32_t rho = 0; rho < r; ++rho) lr += t[rho] * orc_fp8_e4m3_to_double(B8[(size_t)rho * N + n]);
+        out[n] = acc + lr;
+    }
+    free(t);
+}
+
+int32_t orc_moe_forward_fp8(const orc_layer *L, const uint8_t *codes, const uint16_t *scale, const uint16_t *zero,
+                            const uint8_t *const *a8, const uint8_t *const *b8, const uint16_t *sigma,
+                            const int32_t *phi, int32_t M, int32_t Nt, const float *x, const int32_t *idx, const float *w,
+                            int32_t T, const int32_t *tokens, int32_t n_tokens, double *y)
+{
+    int32_t H = L->hidden, F = L->ffn, k = L->top_k, E = L->n_experts, S = L->n_shared, g = L->group, r = L->rank;
+    size_t HF = (size_t)H * F, HFg = HF / g;
+    const int32_t Kp[3] = {H, H, F}, Np[3] = {F, F, H};
+    double *xv = (double *)malloc(sizeof(double) * (size_t)H);
+    double *ye = (double *)malloc(sizeof(double) * (size_t)H);
+    double *buf = (double *)malloc(sizeof(double) * 3 * (size_t)F);
+    double *Gv = buf, *Uv = buf + F, *hv = buf + 2 * (size_t)F;
+    int32_t rc = 0;
+    if (r < 1) rc = -1;
+    for (int32_t i = 0; i < n_tokens && rc == 0; ++i) {
+        int32_t t = tokens ? tokens[i] : i;
+        if (t < 0 || t >= T) { rc = -1; break; }
+        for (int32_t c = 0; c < H; ++c) xv[c] = (double)x[(size_t)t * H + c];
+        double *yt = y + (size_t)i * H;
+        for (int32_t c = 0; c < H; ++c) yt[c] = 0.0;
+        for (int32_t j = 0; j < k + S; ++j) {
+            int32_t e = j < k ? idx[(size_t)t * k + j] : E + (j - k);
+            if (j < k && (e < 0 || e >= E)) { rc = -1; break; }
+            int32_t ma = e, nb = e;
+            if (phi) {
+                ma = phi[2 * e]; nb = phi[2 * e + 1];
+                if (ma < 0 || ma >= M || nb < 0 || nb >= Nt) { rc = -1; break; }
+            }
+            double *dst[3] = {Gv, Uv, ye};
+            for (int32_t p = 0; p < 3; ++p) {
+                const uint8_t *A8 = a8[p] + (size_t)ma * Kp[p] * r;
+                const uint8_t *B8 = b8[p] + (size_t)nb * r * Np[p];
+                const uint16_t *sg = phi ? sigma + (size_t)p * r : sigma + ((size_t)e * 3 + p) * r;
+                if (p == 2)
+                    for (int32_t f = 0; f < F; ++f) hv[f] = orc_silu(Gv[f]) * Uv[f];
+                orc_project_fp8(p == 2 ? hv : xv, codes + ((size_t)e * 3 + p) * HF, scale + ((size_t)e * 3 + p) * HFg,
+                                zero + ((size_t)e * 3 + p) * HFg, A8, sg, B8, Np[p], Kp[p], g, r, dst[p]);
+            }
+            double wj = j < k ? (double)w[(size_t)t * k + j] : 1.0;
+            for (int32_t c = 0; c < H; ++c) yt[c] += wj * ye[c];
+        }
+    }
+    free(xv);
+    free(ye);
+    free(buf);
     return rc;
 }
 

@@ -17,6 +17,7 @@ TQ_OK = 0
 TQ_ACT_BF16, TQ_ACT_FP32 = 0, 1
 TQ_FLAG_FORCE_SMALL_TILE, TQ_FLAG_FORCE_LARGE_TILE, TQ_FLAG_FORCE_SKINNY = 1, 2, 4
 TQ_FLAG_DENSE_CODES = 32
+TQ_FLAG_FP8_FACTORS = 64
 TQ_LOTILE_FP8 = 1
 STATUS_NAMES = {0: "TQ_OK", 1: "TQ_ERR_NULL", 2: "TQ_ERR_SHAPE", 3: "TQ_ERR_ALIGN", 4: "TQ_ERR_RANGE",
                 5: "TQ_ERR_WORKSPACE", 6: "TQ_ERR_UNSUPPORTED", 7: "TQ_ERR_HIP", 8: "TQ_ERR_BLOB"}
@@ -46,11 +47,12 @@ class LoTileDesc(ctypes.Structure):
 
 class _WeightsPtrs(ctypes.Structure):
     _fields_ = [("codes", ctypes.c_void_p), ("scale", ctypes.c_void_p), ("zero", ctypes.c_void_p),
-                ("A", ctypes.c_void_p), ("B", ctypes.c_void_p)]
+                ("A", ctypes.c_void_p), ("B", ctypes.c_void_p), ("sigma", ctypes.c_void_p)]
 
 
 class _SharedPtrs(ctypes.Structure):
-    _fields_ = [("us", ctypes.c_void_p * 3), ("v", ctypes.c_void_p * 3), ("phi", ctypes.c_void_p)]
+    _fields_ = [("us", ctypes.c_void_p * 3), ("v", ctypes.c_void_p * 3), ("phi", ctypes.c_void_p),
+                ("sigma", ctypes.c_void_p)]
 
 
 _lib = None
@@ -170,38 +172,41 @@ def tq_moe_workspace_size(desc: LayerDesc, T: int) -> int:
     return int(lib().tq_moe_workspace_size(ctypes.byref(desc), T))
 
 
-def tq_pack_weights(desc: LayerDesc, codes, scale, zero, A=None, B=None, packed=None, err_flag=None):
-    """Canonical device tensors (uint8 codes, int16/uint16 fp16-bit scale/zero/A/B) -> packed uint8 blob."""
+def tq_pack_weights(desc: LayerDesc, codes, scale, zero, A=None, B=None, packed=None, err_flag=None, sigma=None):
+    """Canonical device tensors (uint8 codes, int16/uint16 fp16-bit scale/zero/A/B) -> packed uint8 blob.  With
+    TQ_FLAG_FP8_FACTORS A and B are uint8 E4M3 codes and sigma the fp16-bit tensor [E+S, 3, r]."""
     n = tq_packed_size(desc)
     if n == 0:
         raise TqError(2, "tq_packed_size")
     if packed is None:
         packed = torch.empty(n, dtype=torch.uint8, device=codes.device)
-    src = _WeightsPtrs(_ptr(codes), _ptr(scale), _ptr(zero), _ptr(A), _ptr(B))
+    src = _WeightsPtrs(_ptr(codes), _ptr(scale), _ptr(zero), _ptr(A), _ptr(B), _ptr(sigma))
     rc = lib().tq_pack_weights(ctypes.byref(desc), ctypes.byref(src), _ptr(packed), packed.numel(),
                                _ptr(err_flag), _stream())
     _check(rc, "tq_pack_weights")
     return packed
 
 
-def tq_pack_weights_shared(desc: LayerDesc, codes, scale, zero, us, v, phi, packed=None, err_flag=None):
+def tq_pack_weights_shared(desc: LayerDesc, codes, scale, zero, us, v, phi, packed=None, err_flag=None, sigma=None):
     """As tq_pack_weights for shared 2D-tiled factors: us / v are 3-lists (gate, up, down) of fp16-bit tensors
-    [M, K_p, r] / [N, r, N_p], phi int32 [E+S, 2]."""
+    [M, K_p, r] / [N, r, N_p] (uint8 E4M3 codes with TQ_FLAG_FP8_FACTORS, then sigma is the fp16-bit tensor [3, r]),
+    phi int32 [E+S, 2]."""
     n = tq_packed_size(desc)
     if n == 0:
         raise TqError(2, "tq_packed_size")
     if packed is None:
         packed = torch.empty(n, dtype=torch.uint8, device=codes.device)
-    src = _WeightsPtrs(_ptr(codes), _ptr(scale), _ptr(zero), None, None)
-    sh = _SharedPtrs((ctypes.c_void_p * 3)(*[_ptr(t) for t in us]), (ctypes.c_void_p * 3)(*[_ptr(t) for t in v]), _ptr(phi))
+    src = _WeightsPtrs(_ptr(codes), _ptr(scale), _ptr(zero), None, None, None)
+    sh = _SharedPtrs((ctypes.c_void_p * 3)(*[_ptr(t) for t in us]), (ctypes.c_void_p * 3)(*[_ptr(t) for t in v]), _ptr(phi),
+                     _ptr(sigma))
     rc = lib().tq_pack_weights_shared(ctypes.byref(desc), ctypes.byref(src), ctypes.byref(sh), _ptr(packed), packed.numel(),
                                       _ptr(err_flag), _stream())
     _check(rc, "tq_pack_weights_shared")
     return packed
 
 
-def tq_unpack_weights(desc: LayerDesc, packed, codes, scale, zero, A=None, B=None) -> None:
-    dst = _WeightsPtrs(_ptr(codes), _ptr(scale), _ptr(zero), _ptr(A), _ptr(B))
+def tq_unpack_weights(desc: LayerDesc, packed, codes, scale, zero, A=None, B=None, sigma=None) -> None:
+    dst = _WeightsPtrs(_ptr(codes), _ptr(scale), _ptr(zero), _ptr(A), _ptr(B), _ptr(sigma))
     _check(lib().tq_unpack_weights(ctypes.byref(desc), _ptr(packed), ctypes.byref(dst), _stream()),
            "tq_unpack_weights")
 

@@ -204,9 +204,11 @@ tq_status forward_impl(const tq_layer_desc* desc, const void* packed, const void
     TqWorkspace W;
     tq_make_workspace(L, desc->act_dtype, T, &W);
     if (workspace_bytes < W.total) return TQ_ERR_WORKSPACE;      // static entry point: the batch needs more than the array holds
-    // dense 2- / 3-bit codes: the decode kernels, or the tiled kernels with the zero-point fragments derived into the
-    // workspace (which is only laid out for batches beyond the decode path or with a tile path forced)
-    if (L.cw != 4 && desc->act_dtype == TQ_ACT_BF16 && !tqi_bf16_takes_skinny(L, W, desc->flags) && W.zc_stride == 0)
+    // dense 2- / 3-bit codes and fp8 factors: the decode kernels, or the tiled kernels with the zero-point fragments /
+    // fp16 factor fragments derived into the workspace (which is only laid out for batches beyond the decode path or
+    // with a tile path forced)
+    if (desc->act_dtype == TQ_ACT_BF16 && !tqi_bf16_takes_skinny(L, W, desc->flags) &&
+        ((L.cw != 4 && W.zc_stride == 0) || (L.fm.fp8 && W.fac_bytes == 0)))
         return TQ_ERR_UNSUPPORTED;
     if (T == 0) return TQ_OK;
     const TqDeviceState* ds = nullptr;

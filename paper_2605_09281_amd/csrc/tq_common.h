@@ -10,7 +10,7 @@
 #include "tileq.h"
 
 #define TQ_BLOB_MAGIC 0x31425154u /* "TQB1" */
-#define TQ_BLOB_VERSION 3u
+#define TQ_BLOB_VERSION 4u
 #define TQ_HEADER_BYTES 256
 #define TQ_STATIC_SCRATCH_BYTES TQ_STATIC_SCRATCH_MAX   /* size of the static scratch array (tileq.h) */
 
@@ -28,16 +28,19 @@ struct TqSection {
     int32_t zfrag;     // fragments of the zero-point coefficients per pair and tile: 2 * ceil(groups / 16) (hi, lo)
     int32_t zsteps;    // of which the blob stores: zfrag, or 0 (dense codes: the tiled kernels derive them per call)
     // byte offsets from the start of the expert record
-    size_t codes, sz, zc, bfrag, afrag, end;
+    size_t codes, sz, zc, bfrag, afrag, sig, end;     // sig: fp32 Sigma of fp8 factors (empty otherwise)
 };
 
 // Where the factor fragments of an expert live: inside its record, or (shared 2D-tiled factors) in per-tile blocks
 // behind the records, found through the placement table.  Index 0: section GU, 1: section D.
 struct TqFactorMap {
-    int32_t shared, M, N, pad;
+    int32_t shared, M, N, fp8;             // fp8: one byte per factor element and a Sigma table
     size_t phi_off;                       // byte offsets from the start of the blob
     size_t apool[2], astride[2];          // block m of the left factors at apool + m * astride (afrag layout)
     size_t bpool[2], bstride[2];          // block n of the right factors at bpool + n * bstride (bfrag layout)
+    size_t sig_off[2];                    // shared fp8 factors: fp32 Sigma of section GU / D (one table for all tiles)
+    const uint8_t* fbase;                 // null: the offsets above count from the blob; else from this device address
+                                          // (fp16 fragments expanded from fp8 factors into the workspace)
 };
 
 struct TqLayout {
@@ -53,7 +56,7 @@ struct TqLayout {
 struct TqBlobHeader {
     uint32_t magic, version;
     int32_t n_experts, n_shared, hidden, ffn, group, bits, rank, r16;
-    int32_t code_words, reserved;       // TqLayout::cw
+    int32_t code_words, factor_fp8;     // TqLayout::cw, TqFactorMap::fp8
     int32_t tiles_m, tiles_n;           // 0, 0: per-expert factors
     uint64_t expert_stride, total_bytes;
     uint64_t off[10];  // gu.codes, gu.sz, gu.zc, gu.bfrag, gu.afrag, then the same five of d
@@ -78,6 +81,9 @@ __host__ inline bool tq_make_layout(const tq_layer_desc* d, TqLayout* L)
     if (d->rank < 0 || d->rank > 256) return false;
     if (d->act_dtype != TQ_ACT_BF16 && d->act_dtype != TQ_ACT_FP32) return false;
     const bool shared = d->tiles_m > 0 || d->tiles_n > 0;
+    const bool fp8 = (d->flags & TQ_FLAG_FP8_FACTORS) != 0;
+    if (fp8 && d->rank < 1) return false;
+    const size_t fb = fp8 ? 1 : 2;       // bytes per factor element
     if (d->tiles_m < 0 || d->tiles_n < 0 || (shared && (d->tiles_m < 1 || d->tiles_n < 1))) return false;
     if (shared && (d->rank < 1 || d->tiles_m > 4096 || d->tiles_n > 4096)) return false;
     L->E = d->n_experts; L->S = d->n_shared; L->k = d->top_k; L->H = d->hidden; L->F = d->ffn;
@@ -93,8 +99,9 @@ __host__ inline bool tq_make_layout(const tq_layer_desc* d, TqLayout* L)
         s.zsteps = dense ? 0 : s.zfrag;     // only the MFMA prefill kernels read this part
         s.zc = off;    off += (size_t)pairs * s.zsteps * 2048;
         // shared factors: the records hold no factor parts (their geometry, na_tiles, still describes the blocks)
-        s.bfrag = off; off += shared ? 0 : (size_t)pairs * (L->r16 / 16) * 2048;
-        s.afrag = off; off += shared ? 0 : (size_t)s.na_tiles * (K / 16) * 1024;
+        s.bfrag = off; off += shared ? 0 : (size_t)pairs * (L->r16 / 16) * 1024 * fb;
+        s.afrag = off; off += shared ? 0 : (size_t)s.na_tiles * (K / 16) * 512 * fb;
+        s.sig = off;   off += (fp8 && !shared) ? tq_align256((size_t)na * 4) : 0;
         s.end = off;
     };
     fill(L->gu, L->F / 32, L->H, 2 * L->r16);
@@ -103,16 +110,18 @@ __host__ inline bool tq_make_layout(const tq_layer_desc* d, TqLayout* L)
     L->total_bytes = TQ_HEADER_BYTES + (size_t)(L->E + L->S) * L->expert_stride;
     TqFactorMap& fm = L->fm;
     fm = TqFactorMap{};
+    fm.fp8 = fp8 ? 1 : 0;
     if (shared) {
         fm.shared = 1; fm.M = d->tiles_m; fm.N = d->tiles_n;
         size_t o = L->total_bytes;
         fm.phi_off = o; o += tq_align256((size_t)(L->E + L->S) * 8);
         const TqSection* secs[2] = {&L->gu, &L->d};
         for (int i = 0; i < 2; ++i) {
-            fm.astride[i] = (size_t)secs[i]->na_tiles * (secs[i]->K / 16) * 1024;
-            fm.bstride[i] = (size_t)secs[i]->pairs * (L->r16 / 16) * 2048;
+            fm.astride[i] = (size_t)secs[i]->na_tiles * (secs[i]->K / 16) * 512 * fb;
+            fm.bstride[i] = (size_t)secs[i]->pairs * (L->r16 / 16) * 1024 * fb;
             fm.apool[i] = o; o += (size_t)fm.M * fm.astride[i];
             fm.bpool[i] = o; o += (size_t)fm.N * fm.bstride[i];
+            fm.sig_off[i] = o; o += fp8 ? tq_align256((size_t)(i == 0 ? 2 : 1) * L->r16 * 4) : 0;
         }
         L->total_bytes = tq_align256(o);
     }
@@ -146,6 +155,9 @@ struct TqWorkspace {
     size_t zc_ws;       // dense codes on the tiled kernels: the zero-point coefficient fragments the blob does not store,
     size_t zc_stride;   // derived per call: [E+S] records of zc_stride bytes, section GU at 0, section D at zc_d_off
     size_t zc_d_off;
+    size_t fac_ws;      // fp8 factors on the tiled kernels: fp16 fragments expanded per call; fac_fm describes them
+    size_t fac_bytes;   // (offsets from the start of fac_ws; 0 bytes when not laid out)
+    TqFactorMap fac_fm;
     size_t sk_cnt;      // decode path: next-pair counters [2 stages][rt_max][TQ_MAX_SPLIT], cleared by the permutation
     int32_t sk_cnt_n;   // their number (0 when the batch is too large for the decode path)
     size_t total;
@@ -203,12 +215,31 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
             const size_t nat = (size_t)(2 * L.r16 + 31) / 32;
             W->tpart = take((size_t)(a_tot / 16 + L.E + L.S) * slices * nat * 512 * 4);
         }
-        // dense codes beyond the decode path (more rows than it takes, or a tile path forced)
+        // dense codes / fp8 factors beyond the decode path (more rows than it takes, or a tile path forced)
+        const bool tiled = a_tot > TQ_SKINNY_MAX_ROWS || (L.flags & (TQ_FLAG_FORCE_SMALL_TILE | TQ_FLAG_FORCE_LARGE_TILE));
         W->zc_ws = off; W->zc_stride = 0; W->zc_d_off = 0;
-        if (L.cw != 4 && (a_tot > TQ_SKINNY_MAX_ROWS || (L.flags & (TQ_FLAG_FORCE_SMALL_TILE | TQ_FLAG_FORCE_LARGE_TILE)))) {
+        if (L.cw != 4 && tiled) {
             W->zc_d_off = (size_t)L.gu.pairs * L.gu.zfrag * 2048;
             W->zc_stride = W->zc_d_off + (size_t)L.d.pairs * L.d.zfrag * 2048;
             W->zc_ws = take((size_t)(L.E + L.S) * W->zc_stride);
+        }
+        W->fac_ws = off; W->fac_bytes = 0; W->fac_fm = TqFactorMap{};
+        if (L.fm.fp8 && tiled) {
+            TqFactorMap& f = W->fac_fm;
+            f.shared = 1; f.fp8 = 0;
+            f.M = L.fm.shared ? L.fm.M : L.E + L.S;       // per-expert factors: one block per expert, identity placement
+            f.N = L.fm.shared ? L.fm.N : L.E + L.S;
+            size_t o = 0;
+            f.phi_off = o; o += tq_align256((size_t)(L.E + L.S) * 8);
+            const TqSection* secs[2] = {&L.gu, &L.d};
+            for (int i = 0; i < 2; ++i) {
+                f.astride[i] = (size_t)secs[i]->na_tiles * (secs[i]->K / 16) * 1024;
+                f.bstride[i] = (size_t)secs[i]->pairs * (L.r16 / 16) * 2048;
+                f.apool[i] = o; o += (size_t)f.M * f.astride[i];
+                f.bpool[i] = o; o += (size_t)f.N * f.bstride[i];
+            }
+            W->fac_bytes = o;
+            W->fac_ws = take(o);
         }
         W->sk_cnt = off;
         W->sk_cnt_n = 0;
@@ -219,6 +250,7 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
     } else {
         W->xaug_gu = W->xaug_d = off;
         W->zc_ws = off; W->zc_stride = 0; W->zc_d_off = 0;
+        W->fac_ws = off; W->fac_bytes = 0; W->fac_fm = TqFactorMap{};
         W->tpart = off;
         W->sk_cnt = off;
         W->sk_cnt_n = 0;
@@ -235,20 +267,36 @@ __device__ inline float tq_half_bits_to_float(uint16_t h)
     return __half2float(__ushort_as_half(h));
 }
 
+// one fp8 E4M3 code (low byte of b) -> fp32, exact (the hardware conversion of gfx950, OCP E4M3)
+__device__ inline float tq_fp8_to_float(uint32_t b)
+{
+    return __builtin_amdgcn_cvt_pk_f32_fp8(b, false)[0];
+}
+
 // base of the left (afrag layout) / right (bfrag layout) factor fragments of expert e in section sec_id (0 GU, 1 D)
 __device__ inline const uint8_t* tq_afrag_base(const uint8_t* blob, size_t expert_stride, const TqSection& sec,
                                                const TqFactorMap& fm, int sec_id, int e)
 {
     if (!fm.shared) return blob + TQ_HEADER_BYTES + (size_t)e * expert_stride + sec.afrag;
-    const int m = reinterpret_cast<const int32_t*>(blob + fm.phi_off)[2 * e];
-    return blob + fm.apool[sec_id] + (size_t)m * fm.astride[sec_id];
+    const uint8_t* b = fm.fbase ? fm.fbase : blob;
+    const int m = reinterpret_cast<const int32_t*>(b + fm.phi_off)[2 * e];
+    return b + fm.apool[sec_id] + (size_t)m * fm.astride[sec_id];
 }
 __device__ inline const uint8_t* tq_bfrag_base(const uint8_t* blob, size_t expert_stride, const TqSection& sec,
                                                const TqFactorMap& fm, int sec_id, int e)
 {
     if (!fm.shared) return blob + TQ_HEADER_BYTES + (size_t)e * expert_stride + sec.bfrag;
-    const int n = reinterpret_cast<const int32_t*>(blob + fm.phi_off)[2 * e + 1];
-    return blob + fm.bpool[sec_id] + (size_t)n * fm.bstride[sec_id];
+    const uint8_t* b = fm.fbase ? fm.fbase : blob;
+    const int n = reinterpret_cast<const int32_t*>(b + fm.phi_off)[2 * e + 1];
+    return b + fm.bpool[sec_id] + (size_t)n * fm.bstride[sec_id];
+}
+
+// fp32 Sigma of the fp8 factors of expert e in section sec_id: NA values (gate then up in GU)
+__device__ inline const float* tq_sig_base(const uint8_t* blob, size_t expert_stride, const TqSection& sec,
+                                           const TqFactorMap& fm, int sec_id, int e)
+{
+    if (fm.shared) return reinterpret_cast<const float*>(blob + fm.sig_off[sec_id]);
+    return reinterpret_cast<const float*>(blob + TQ_HEADER_BYTES + (size_t)e * expert_stride + sec.sig);
 }
 
 // expert owning slot `s`: largest e with offsets[e] <= s (offsets is non-decreasing, n+1 entries)
@@ -286,6 +334,9 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
                              int32_t* hist, int32_t nblk, const void* blob, const TqLayout* L,
                              int32_t* zero_buf, int32_t zero_n, hipStream_t stream,
                              const TqPreByAssign* pre = nullptr, int tilings = (1 << TQ_N_TILINGS) - 1);
+// fills W.fac_ws with fp16 fragments (Sigma folded into the left factors) and the placement table (fp8 factors on the
+// tiled kernels)
+tq_status tqi_expand_fp8_factors(const TqLayout& L, const TqWorkspace& W, const uint8_t* blob, uint8_t* ws, hipStream_t stream);
 // fills W.zc_ws from the blob's scale / zero part (dense codes on the tiled kernels)
 tq_status tqi_derive_zc(const TqLayout& L, const TqWorkspace& W, const uint8_t* blob, uint8_t* ws, hipStream_t stream);
 // whether the bf16 forward of this batch runs on the decode kernels, and whether its gate/up pre-pass is by assignment

@@ -105,6 +105,31 @@ __device__ inline bf16x8 half8_to_bf8(u32x4 q)
     return f.v;
 }
 
+// eight fp8 E4M3 values (two dwords) -> the bf16 operand of one MFMA step; exact: E4M3 has three mantissa bits
+__device__ inline bf16x8 fp8x8_to_bf8(uint32_t d0, uint32_t d1)
+{
+    Frag f;
+    const uint32_t d[2] = {d0, d1};
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const auto lo = __builtin_amdgcn_cvt_pk_f32_fp8(d[q], false);
+        const auto hi = __builtin_amdgcn_cvt_pk_f32_fp8(d[q], true);
+        f.u[2 * q] = (__float_as_uint(lo[0]) >> 16) | (__float_as_uint(lo[1]) & 0xFFFF0000u);
+        f.u[2 * q + 1] = (__float_as_uint(hi[0]) >> 16) | (__float_as_uint(hi[1]) & 0xFFFF0000u);
+    }
+    return f.v;
+}
+
+// fp8 factor fragments keep the fp16 layouts with 1-byte elements: fragment f of a part sits at byte 512 f, lane l's
+// eight codes at 8 l.  Lanes 2j and 2j + 1 share a 16-byte word: every lane loads that word (no 8-byte load under a
+// condition next to the streams) and keeps its half.
+__device__ inline bf16x8 fp8_frag_to_bf8(const u32x4& word, int lane)
+{
+    const uint32_t d0 = (lane & 1) ? word[2] : word[0];
+    const uint32_t d1 = (lane & 1) ? word[3] : word[1];
+    return fp8x8_to_bf8(d0, d1);
+}
+
 __device__ inline uint32_t word_of(const u32x4& q, int w) { return q[w]; }
 
 // silu(g) * u with the hardware exp2 and reciprocal (about 1 ulp each; the result is rounded to bf16 anyway):

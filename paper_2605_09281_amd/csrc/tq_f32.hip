@@ -51,6 +51,8 @@ __global__ void __launch_bounds__(256) f32_proj_kernel(F32Geom G, TqSection sec,
     // t[c] = sum_kk x[kk] * A[kk][c]
     if (G.r > 0) {
         const uint16_t* af = reinterpret_cast<const uint16_t*>(tq_afrag_base(blob, G.expert_stride, sec, G.fm, STAGE, e));
+        const uint8_t* af8 = reinterpret_cast<const uint8_t*>(af);       // fp8 factors: the same layout with 1-byte elements
+        const float* sig = G.fm.fp8 ? tq_sig_base(blob, G.expert_stride, sec, G.fm, STAGE, e) : nullptr;
         const int ksteps = K / 16;
         for (int c = wave; c < NA; c += 4) {
             const int ta = c >> 5, cl = c & 31;
@@ -58,11 +60,11 @@ __global__ void __launch_bounds__(256) f32_proj_kernel(F32Geom G, TqSection sec,
             for (int kk = lane; kk < K; kk += 64) {
                 int s = kk >> 4, h2 = (kk >> 3) & 1, i = kk & 7;
                 size_t ai = (((size_t)ta * ksteps + s) * 64 + h2 * 32 + cl) * 8 + i;
-                p = fmaf(xs[kk], tq_half_bits_to_float(af[ai]), p);
+                p = fmaf(xs[kk], G.fm.fp8 ? tq_fp8_to_float(af8[ai]) : tq_half_bits_to_float(af[ai]), p);
             }
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) p += __shfl_xor(p, off);
-            if (lane == 0) ts[c] = p;
+            if (lane == 0) ts[c] = sig ? p * sig[c] : p;
         }
     }
     __syncthreads();
@@ -107,17 +109,25 @@ __global__ void __launch_bounds__(256) f32_proj_kernel(F32Geom G, TqSection sec,
         }
         acc = fmaf(part, s, acc);
         if (G.r > 0) {
-            const uint4* bf = reinterpret_cast<const uint4*>(tq_bfrag_base(blob, G.expert_stride, sec, G.fm, STAGE, e)) +
-                              ((size_t)pair * (G.r16 / 16) * 2 + tile) * 64 + lane;
+            const uint8_t* bbase = tq_bfrag_base(blob, G.expert_stride, sec, G.fm, STAGE, e);
+            const uint4* bf = reinterpret_cast<const uint4*>(bbase) + ((size_t)pair * (G.r16 / 16) * 2 + tile) * 64 + lane;
+            const uint2* bf8 = reinterpret_cast<const uint2*>(bbase) + ((size_t)pair * (G.r16 / 16) * 2 + tile) * 64 + lane;
             const float* tp = ts + (STAGE == 0 ? tile * G.r16 : 0);
             float lr = 0.f;
             for (int st = 0; st < G.r16 / 16; ++st) {
-                uint4 b = bf[(size_t)st * 128];
-                uint32_t bw[4] = {b.x, b.y, b.z, b.w};
+                if (G.fm.fp8) {
+                    const uint2 b = bf8[(size_t)st * 128];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    uint16_t hb = (uint16_t)(bw[i >> 1] >> (16 * (i & 1)));
-                    lr = fmaf(tp[16 * st + 8 * hf + i], tq_half_bits_to_float(hb), lr);
+                    for (int i = 0; i < 8; ++i)
+                        lr = fmaf(tp[16 * st + 8 * hf + i], tq_fp8_to_float(((i < 4 ? b.x : b.y) >> (8 * (i & 3))) & 0xFF), lr);
+                } else {
+                    uint4 b = bf[(size_t)st * 128];
+                    uint32_t bw[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        uint16_t hb = (uint16_t)(bw[i >> 1] >> (16 * (i & 1)));
+                        lr = fmaf(tp[16 * st + 8 * hf + i], tq_half_bits_to_float(hb), lr);
+                    }
                 }
             }
             acc += lr;

@@ -198,21 +198,6 @@ __global__ void lt_pack_fp8_kernel(LtLayout L, const uint8_t* __restrict__ u8, c
     }
 }
 
-// eight fp8 E4M3 values (two dwords) -> the bf16 operand of one MFMA step; exact: E4M3 has three mantissa bits
-__device__ inline bf16x8 fp8x8_to_bf8(uint32_t d0, uint32_t d1)
-{
-    Frag f;
-    const uint32_t d[2] = {d0, d1};
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const auto lo = __builtin_amdgcn_cvt_pk_f32_fp8(d[q], false);
-        const auto hi = __builtin_amdgcn_cvt_pk_f32_fp8(d[q], true);
-        f.u[2 * q] = (__float_as_uint(lo[0]) >> 16) | (__float_as_uint(lo[1]) & 0xFFFF0000u);
-        f.u[2 * q + 1] = (__float_as_uint(hi[0]) >> 16) | (__float_as_uint(hi[1]) & 0xFFFF0000u);
-    }
-    return f.v;
-}
-
 // ---- dense product C[T, 32 nt] = A[T, 16 steps] B, B in fragment order ----------------------------------------
 // grid (column blocks of 4 NTW tiles, row tiles of 32 MT rows, K splits).  A workgroup stages its rows of A
 // through LDS in 128-wide chunks; wave w owns NTW column tiles and all MT row sub-tiles, so a B fragment (one

@@ -821,8 +821,9 @@ bool tqi_bf16_takes_skinny(const TqLayout& L, const TqWorkspace& W, int flags)
 {
     const int64_t avg_rows = (int64_t)W.a_tot / (L.E + L.S);
     bool skinny = !bf16_large_tiles(L, W, flags) && avg_rows <= 12 && !(flags & TQ_FLAG_FORCE_SMALL_TILE);
-    // dense codes stay on the decode kernels as long as the batch fits them, unless a tile path is forced
-    if ((flags & TQ_FLAG_FORCE_SKINNY) || (L.cw != 4 && !(flags & (TQ_FLAG_FORCE_SMALL_TILE | TQ_FLAG_FORCE_LARGE_TILE)))) skinny = true;
+    // dense codes and fp8 factors stay on the decode kernels as long as the batch fits them, unless a tile path is forced
+    // (the tiled kernels need parts derived into the workspace first)
+    if ((flags & TQ_FLAG_FORCE_SKINNY) || ((L.cw != 4 || L.fm.fp8) && !(flags & (TQ_FLAG_FORCE_SMALL_TILE | TQ_FLAG_FORCE_LARGE_TILE)))) skinny = true;
     return skinny && W.a_tot <= TQ_SKINNY_MAX_ROWS && tqi_skinny_supported(L);
 }
 
@@ -869,6 +870,14 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
     }
 
     tq_status rc;
+    if (L.fm.fp8) {
+        // fp8 factors: the tiled kernels read fp16 fragments, expanded into the workspace for this call
+        if (W.fac_bytes == 0) return TQ_ERR_UNSUPPORTED;
+        rc = tqi_expand_fp8_factors(L, W, blob, ws, stream);
+        if (rc != TQ_OK) return rc;
+        G.fm = W.fac_fm;
+        G.fm.fbase = ws + W.fac_ws;
+    }
     if (L.cw != 4) {
         // dense codes: the blob stores no zero-point coefficient fragments; the tiled kernels read them from the workspace
         if (W.zc_stride == 0 || gs == 16) return TQ_ERR_UNSUPPORTED;

@@ -241,8 +241,9 @@ __global__ void zc_kernel(PackGeom G, uint8_t* __restrict__ blob, const uint16_t
 }
 
 // One thread per 8-element fragment of B.  Padding rows (rho >= r) are written as zero and skipped on unpack.
-template <bool PACK>
-__global__ void bfrag_kernel(PackGeom G, uint8_t* __restrict__ blob, uint16_t* __restrict__ B)
+// ET: uint16_t (fp16 bit patterns) or uint8_t (fp8 E4M3 codes): the layout is the same with 2- or 1-byte elements.
+template <bool PACK, typename ET>
+__global__ void bfrag_kernel(PackGeom G, uint8_t* __restrict__ blob, ET* __restrict__ B)
 {
     const int steps = G.r16 / 16;
     const size_t n_gu = (size_t)G.gu.pairs * steps * 128;
@@ -266,19 +267,19 @@ __global__ void bfrag_kernel(PackGeom G, uint8_t* __restrict__ blob, uint16_t* _
     else       { p = 2;    n = 64 * pair + 32 * tile + col; N = G.H; }
     const size_t b_per_exp = (2 * (size_t)G.F + G.H) * G.r;
     const size_t b_off = (p == 0) ? 0 : (p == 1) ? (size_t)G.F * G.r : 2 * (size_t)G.F * G.r;
-    uint16_t* src = B + (size_t)e * b_per_exp + b_off;
-    uint16_t* dst = reinterpret_cast<uint16_t*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.bfrag) + w * 8;
+    ET* src = B + (size_t)e * b_per_exp + b_off;
+    ET* dst = reinterpret_cast<ET*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.bfrag) + w * 8;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         int rho = 16 * step + 8 * hf + i;
-        if (PACK) dst[i] = (rho < G.r) ? src[(size_t)rho * N + n] : (uint16_t)0;
+        if (PACK) dst[i] = (rho < G.r) ? src[(size_t)rho * N + n] : (ET)0;
         else if (rho < G.r) src[(size_t)rho * N + n] = dst[i];
     }
 }
 
 // One thread per 8-element fragment of A.
-template <bool PACK>
-__global__ void afrag_kernel(PackGeom G, uint8_t* __restrict__ blob, uint16_t* __restrict__ A)
+template <bool PACK, typename ET>
+__global__ void afrag_kernel(PackGeom G, uint8_t* __restrict__ blob, ET* __restrict__ A)
 {
     const size_t n_gu = (size_t)G.gu.na_tiles * (G.gu.K / 16) * 64;
     const size_t n_d = (size_t)G.d.na_tiles * (G.d.K / 16) * 64;
@@ -302,13 +303,93 @@ __global__ void afrag_kernel(PackGeom G, uint8_t* __restrict__ blob, uint16_t* _
     const bool live = (c < na) && (rho < G.r);
     const size_t a_per_exp = (2 * (size_t)G.H + G.F) * G.r;
     const size_t a_off = (p == 0) ? 0 : (p == 1) ? (size_t)G.H * G.r : 2 * (size_t)G.H * G.r;
-    uint16_t* src = A + (size_t)e * a_per_exp + a_off;
-    uint16_t* dst = reinterpret_cast<uint16_t*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.afrag) + w * 8;
+    ET* src = A + (size_t)e * a_per_exp + a_off;
+    ET* dst = reinterpret_cast<ET*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.afrag) + w * 8;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         int kk = 16 * step + 8 * hf + i;
-        if (PACK) dst[i] = live ? src[(size_t)kk * G.r + rho] : (uint16_t)0;
+        if (PACK) dst[i] = live ? src[(size_t)kk * G.r + rho] : (ET)0;
         else if (live) src[(size_t)kk * G.r + rho] = dst[i];
+    }
+}
+
+// Sigma of fp8 factors: fp16 [n_exp][3][r] <-> the fp32 `sig` parts of the records (GU: gate then up, r16 each; D),
+// each padded with zeros to 256 bytes.  With n_tables == 1 and shared factors the one table [3][r] goes behind the pools.
+template <bool PACK>
+__global__ void sig_kernel(PackGeom G, TqFactorMap fm, uint8_t* __restrict__ blob, uint16_t* __restrict__ sigma, int n_tables)
+{
+    const int n_gu = (int)(tq_align256((size_t)2 * G.r16 * 4) / 4), n_d = (int)(tq_align256((size_t)G.r16 * 4) / 4);
+    const int per = n_gu + n_d;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= per * n_tables) return;
+    const int e = idx / per;
+    int c = idx % per;
+    const bool is_d = c >= n_gu;
+    if (is_d) c -= n_gu;
+    const TqSection& sec = is_d ? G.d : G.gu;
+    float* dst = (fm.shared ? reinterpret_cast<float*>(blob + fm.sig_off[is_d])
+                            : reinterpret_cast<float*>(blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride + sec.sig)) + c;
+    const int p = is_d ? 2 : c / G.r16, rho = c % G.r16;
+    const bool live = c < (is_d ? G.r16 : 2 * G.r16) && rho < G.r;
+    uint16_t* src = sigma + ((size_t)e * 3 + p) * G.r + rho;
+    if (PACK) *dst = live ? __half2float(__ushort_as_half(*src)) : 0.f;
+    else if (live) *src = __half_as_ushort(__float2half(*dst));      // exact: the value came from an fp16
+}
+
+// fp8 factor fragments of the blob -> fp16 fragments in the workspace, for the tiled kernels (which read fp16
+// fragments): left factors with Sigma folded in, A16 = fp16(fp8(A8) * sigma) (one rounding to nearest), right factors
+// exactly.  One thread per 8-element fragment of one block; blocks are experts (per-expert factors) or tiles.
+// which: 0 left factors, 1 right factors.
+__global__ void expand_fp8_kernel(PackGeom G, TqFactorMap src, TqFactorMap dstm, const uint8_t* __restrict__ blob,
+                                  uint8_t* __restrict__ fbase, int which, int n_blocks)
+{
+    const size_t n_gu = which == 0 ? (size_t)G.gu.na_tiles * (G.gu.K / 16) * 64 : (size_t)G.gu.pairs * (G.r16 / 16) * 128;
+    const size_t n_d = which == 0 ? (size_t)G.d.na_tiles * (G.d.K / 16) * 64 : (size_t)G.d.pairs * (G.r16 / 16) * 128;
+    const size_t per = n_gu + n_d;
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= per * n_blocks) return;
+    const int blk = (int)(idx / per);
+    size_t w = idx % per;
+    const bool is_d = w >= n_gu;
+    if (is_d) w -= n_gu;
+    const TqSection& sec = is_d ? G.d : G.gu;
+    const uint8_t* sp;        // the block's fp8 fragments
+    if (src.shared) sp = blob + (which == 0 ? src.apool[is_d] + (size_t)blk * src.astride[is_d] : src.bpool[is_d] + (size_t)blk * src.bstride[is_d]);
+    else sp = blob + TQ_HEADER_BYTES + (size_t)blk * G.expert_stride + (which == 0 ? sec.afrag : sec.bfrag);
+    uint8_t* dp = fbase + (which == 0 ? dstm.apool[is_d] + (size_t)blk * dstm.astride[is_d] : dstm.bpool[is_d] + (size_t)blk * dstm.bstride[is_d]);
+    const uint2 raw = reinterpret_cast<const uint2*>(sp)[w];
+    float sg = 1.f;
+    if (which == 0) {
+        // column of t this fragment belongs to: 32 ta + lane % 32; Sigma is stored per column (gate then up in GU)
+        const int lane = (int)(w & 63), ta = (int)((w >> 6) / (sec.K / 16));
+        const int c = 32 * ta + (lane & 31), na = is_d ? G.r16 : 2 * G.r16;
+        const float* sig = src.shared ? reinterpret_cast<const float*>(blob + src.sig_off[is_d])
+                                      : reinterpret_cast<const float*>(blob + TQ_HEADER_BYTES + (size_t)blk * G.expert_stride + sec.sig);
+        sg = c < na ? sig[c] : 0.f;
+    }
+    uint32_t o[4];
+#pragma unroll
+    for (int i = 0; i < 8; i += 2) {
+        const uint32_t b0 = ((i < 4 ? raw.x : raw.y) >> (8 * (i & 3))) & 0xFF, b1 = ((i < 4 ? raw.x : raw.y) >> (8 * ((i + 1) & 3))) & 0xFF;
+        const uint32_t h0 = __half_as_ushort(__float2half(tq_fp8_to_float(b0) * sg));
+        const uint32_t h1 = __half_as_ushort(__float2half(tq_fp8_to_float(b1) * sg));
+        o[i >> 1] = h0 | (h1 << 16);
+    }
+    reinterpret_cast<uint4*>(dp)[w] = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+// placement table of the expanded factors: the blob's own (shared factors) or the identity (per-expert factors)
+__global__ void expand_phi_kernel(TqFactorMap src, TqFactorMap dstm, const uint8_t* __restrict__ blob, uint8_t* __restrict__ fbase,
+                                  int n_exp)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n_exp) return;
+    int32_t* dst = reinterpret_cast<int32_t*>(fbase + dstm.phi_off);
+    if (src.shared) {
+        const int32_t* p = reinterpret_cast<const int32_t*>(blob + src.phi_off);
+        dst[2 * e] = p[2 * e]; dst[2 * e + 1] = p[2 * e + 1];
+    } else {
+        dst[2 * e] = e; dst[2 * e + 1] = e;
     }
 }
 
@@ -362,9 +443,10 @@ __global__ void zc_from_blob_kernel(PackGeom G, const uint8_t* __restrict__ blob
 
 // Shared 2D-tiled factors.  Left factors: one thread per 8-element fragment of block (section, m); the block has the
 // afrag layout, its columns being [gate factor | up factor] (r16 each) in section GU and the down factor in D.
+template <typename ET>
 __global__ void pool_afrag_kernel(PackGeom G, TqFactorMap fm, uint8_t* __restrict__ blob,
-                                  const uint16_t* __restrict__ us_g, const uint16_t* __restrict__ us_u,
-                                  const uint16_t* __restrict__ us_d)
+                                  const ET* __restrict__ us_g, const ET* __restrict__ us_u,
+                                  const ET* __restrict__ us_d)
 {
     const size_t n_gu = (size_t)G.gu.na_tiles * (G.gu.K / 16) * 64;     // fragments per block
     const size_t n_d = (size_t)G.d.na_tiles * (G.d.K / 16) * 64;
@@ -385,20 +467,21 @@ __global__ void pool_afrag_kernel(PackGeom G, TqFactorMap fm, uint8_t* __restric
     const int p = is_d ? 2 : (c / G.r16);
     const int rho = c % G.r16;
     const bool live = (c < na) && (rho < G.r);
-    const uint16_t* src = (p == 0 ? us_g : p == 1 ? us_u : us_d) + (size_t)m * sec.K * G.r;      // [K][r] of tile row m
-    uint16_t* dst = reinterpret_cast<uint16_t*>(blob + fm.apool[is_d] + (size_t)m * fm.astride[is_d]) + w * 8;
+    const ET* src = (p == 0 ? us_g : p == 1 ? us_u : us_d) + (size_t)m * sec.K * G.r;      // [K][r] of tile row m
+    ET* dst = reinterpret_cast<ET*>(blob + fm.apool[is_d] + (size_t)m * fm.astride[is_d]) + w * 8;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int kk = 16 * step + 8 * hf + i;
-        dst[i] = live ? src[(size_t)kk * G.r + rho] : (uint16_t)0;
+        dst[i] = live ? src[(size_t)kk * G.r + rho] : (ET)0;
     }
 }
 
 // Right factors: one thread per 8-element fragment of block (section, n), in the bfrag layout (tile 0 / 1 of a pair:
 // gate / up factor in section GU, the two 32-column halves of the down factor's 64 columns in D).
+template <typename ET>
 __global__ void pool_bfrag_kernel(PackGeom G, TqFactorMap fm, uint8_t* __restrict__ blob,
-                                  const uint16_t* __restrict__ v_g, const uint16_t* __restrict__ v_u,
-                                  const uint16_t* __restrict__ v_d)
+                                  const ET* __restrict__ v_g, const ET* __restrict__ v_u,
+                                  const ET* __restrict__ v_d)
 {
     const int steps = G.r16 / 16;
     const size_t n_gu = (size_t)G.gu.pairs * steps * 128;
@@ -417,12 +500,12 @@ __global__ void pool_bfrag_kernel(PackGeom G, TqFactorMap fm, uint8_t* __restric
     int p, n, N;
     if (!is_d) { p = tile; n = 32 * pair + col; N = G.F; }
     else       { p = 2;    n = 64 * pair + 32 * tile + col; N = G.H; }
-    const uint16_t* src = (p == 0 ? v_g : p == 1 ? v_u : v_d) + (size_t)nt * G.r * N;              // [r][N] of tile column nt
-    uint16_t* dst = reinterpret_cast<uint16_t*>(blob + fm.bpool[is_d] + (size_t)nt * fm.bstride[is_d]) + w * 8;
+    const ET* src = (p == 0 ? v_g : p == 1 ? v_u : v_d) + (size_t)nt * G.r * N;              // [r][N] of tile column nt
+    ET* dst = reinterpret_cast<ET*>(blob + fm.bpool[is_d] + (size_t)nt * fm.bstride[is_d]) + w * 8;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int rho = 16 * step + 8 * hf + i;
-        dst[i] = (rho < G.r) ? src[(size_t)rho * N + n] : (uint16_t)0;
+        dst[i] = (rho < G.r) ? src[(size_t)rho * N + n] : (ET)0;
     }
 }
 
@@ -459,7 +542,7 @@ inline unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
 
 template <bool PACK>
 tq_status run(const TqLayout& L, uint8_t* blob, uint8_t* codes, uint16_t* scale, uint16_t* zero,
-              uint16_t* A, uint16_t* B, int32_t* err_flag, hipStream_t st)
+              uint16_t* A, uint16_t* B, uint16_t* sigma, int32_t* err_flag, hipStream_t st)
 {
     PackGeom G = make_geom(L);
     const size_t ne = G.n_exp;
@@ -483,10 +566,20 @@ tq_status run(const TqLayout& L, uint8_t* blob, uint8_t* codes, uint16_t* scale,
     if (L.r > 0 && !L.fm.shared) {
         size_t n_b = ((size_t)L.gu.pairs + L.d.pairs) * (L.r16 / 16) * 128 * ne;
         size_t n_a = ((size_t)L.gu.na_tiles * (L.gu.K / 16) + (size_t)L.d.na_tiles * (L.d.K / 16)) * 64 * ne;
-        hipLaunchKernelGGL(bfrag_kernel<PACK>, dim3(blocks_for(n_b)), dim3(256), 0, st, G, blob, B);
-        TQ_CHECK_LAUNCH();
-        hipLaunchKernelGGL(afrag_kernel<PACK>, dim3(blocks_for(n_a)), dim3(256), 0, st, G, blob, A);
-        TQ_CHECK_LAUNCH();
+        if (L.fm.fp8) {
+            hipLaunchKernelGGL((bfrag_kernel<PACK, uint8_t>), dim3(blocks_for(n_b)), dim3(256), 0, st, G, blob, (uint8_t*)B);
+            TQ_CHECK_LAUNCH();
+            hipLaunchKernelGGL((afrag_kernel<PACK, uint8_t>), dim3(blocks_for(n_a)), dim3(256), 0, st, G, blob, (uint8_t*)A);
+            TQ_CHECK_LAUNCH();
+            hipLaunchKernelGGL(sig_kernel<PACK>, dim3(blocks_for((tq_align256((size_t)8 * L.r16) + tq_align256((size_t)4 * L.r16)) / 4 * ne)),
+                               dim3(256), 0, st, G, L.fm, blob, sigma, (int)ne);
+            TQ_CHECK_LAUNCH();
+        } else {
+            hipLaunchKernelGGL((bfrag_kernel<PACK, uint16_t>), dim3(blocks_for(n_b)), dim3(256), 0, st, G, blob, B);
+            TQ_CHECK_LAUNCH();
+            hipLaunchKernelGGL((afrag_kernel<PACK, uint16_t>), dim3(blocks_for(n_a)), dim3(256), 0, st, G, blob, A);
+            TQ_CHECK_LAUNCH();
+        }
     }
     return TQ_OK;
 }
@@ -494,6 +587,25 @@ tq_status run(const TqLayout& L, uint8_t* blob, uint8_t* codes, uint16_t* scale,
 inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
 
 }  // namespace
+
+tq_status tqi_expand_fp8_factors(const TqLayout& L, const TqWorkspace& W, const uint8_t* blob, uint8_t* ws, hipStream_t stream)
+{
+    if (!L.fm.fp8 || W.fac_bytes == 0) return TQ_ERR_UNSUPPORTED;
+    const PackGeom G = make_geom(L);
+    uint8_t* fbase = ws + W.fac_ws;
+    const size_t per_a = ((size_t)L.gu.na_tiles * (L.gu.K / 16) + (size_t)L.d.na_tiles * (L.d.K / 16)) * 64;
+    const size_t per_b = ((size_t)L.gu.pairs + L.d.pairs) * (L.r16 / 16) * 128;
+    hipLaunchKernelGGL(expand_phi_kernel, dim3(blocks_for((size_t)(L.E + L.S))), dim3(256), 0, stream, L.fm, W.fac_fm, blob, fbase,
+                       L.E + L.S);
+    TQ_CHECK_LAUNCH();
+    hipLaunchKernelGGL(expand_fp8_kernel, dim3(blocks_for(per_a * W.fac_fm.M)), dim3(256), 0, stream, G, L.fm, W.fac_fm, blob, fbase,
+                       0, W.fac_fm.M);
+    TQ_CHECK_LAUNCH();
+    hipLaunchKernelGGL(expand_fp8_kernel, dim3(blocks_for(per_b * W.fac_fm.N)), dim3(256), 0, stream, G, L.fm, W.fac_fm, blob, fbase,
+                       1, W.fac_fm.N);
+    TQ_CHECK_LAUNCH();
+    return TQ_OK;
+}
 
 tq_status tqi_derive_zc(const TqLayout& L, const TqWorkspace& W, const uint8_t* blob, uint8_t* ws, hipStream_t stream)
 {
@@ -548,6 +660,8 @@ tq_status pack_impl(const tq_layer_desc* desc, const tq_weights_src* src, const 
     TqLayout L;
     if (!tq_make_layout(desc, &L)) return TQ_ERR_SHAPE;
     if (L.r > 0 && !L.fm.shared && (!src->A || !src->B)) return TQ_ERR_NULL;
+    if (L.fm.fp8 && !(L.fm.shared ? shared->sigma : src->sigma)) return TQ_ERR_NULL;
+    if (L.fm.fp8 && misaligned(L.fm.shared ? shared->sigma : src->sigma, 2)) return TQ_ERR_ALIGN;
     if (packed_bytes < L.total_bytes) return TQ_ERR_WORKSPACE;
     if (misaligned(packed, 256) || misaligned(src->codes, 16) || misaligned(src->scale, 16) ||
         misaligned(src->zero, 16) || (L.r > 0 && !L.fm.shared && (misaligned(src->A, 16) || misaligned(src->B, 16))) ||
@@ -557,7 +671,7 @@ tq_status pack_impl(const tq_layer_desc* desc, const tq_weights_src* src, const 
     TqBlobHeader hdr = {};
     hdr.magic = TQ_BLOB_MAGIC; hdr.version = TQ_BLOB_VERSION;
     hdr.n_experts = L.E; hdr.n_shared = L.S; hdr.hidden = L.H; hdr.ffn = L.F; hdr.group = L.g;
-    hdr.bits = L.bits; hdr.rank = L.r; hdr.r16 = L.r16; hdr.code_words = L.cw;
+    hdr.bits = L.bits; hdr.rank = L.r; hdr.r16 = L.r16; hdr.code_words = L.cw; hdr.factor_fp8 = L.fm.fp8;
     hdr.tiles_m = L.fm.M; hdr.tiles_n = L.fm.N;
     hdr.expert_stride = L.expert_stride; hdr.total_bytes = L.total_bytes;
     hdr.off[0] = L.gu.codes; hdr.off[1] = L.gu.sz; hdr.off[2] = L.gu.zc; hdr.off[3] = L.gu.bfrag; hdr.off[4] = L.gu.afrag;
@@ -566,17 +680,29 @@ tq_status pack_impl(const tq_layer_desc* desc, const tq_weights_src* src, const 
     TQ_CHECK_LAUNCH();
     tq_status rc = run<true>(L, (uint8_t*)packed, const_cast<uint8_t*>(src->codes), const_cast<uint16_t*>(src->scale),
                              const_cast<uint16_t*>(src->zero), const_cast<uint16_t*>(src->A),
-                             const_cast<uint16_t*>(src->B), err_flag, st);
+                             const_cast<uint16_t*>(src->B), const_cast<uint16_t*>(src->sigma), err_flag, st);
     if (rc != TQ_OK || !L.fm.shared) return rc;
     const PackGeom G = make_geom(L);
     const size_t n_a = ((size_t)L.gu.na_tiles * (L.gu.K / 16) + (size_t)L.d.na_tiles * (L.d.K / 16)) * 64 * L.fm.M;
     const size_t n_b = ((size_t)L.gu.pairs + L.d.pairs) * (L.r16 / 16) * 128 * L.fm.N;
-    hipLaunchKernelGGL(pool_afrag_kernel, dim3(blocks_for(n_a)), dim3(256), 0, st, G, L.fm, (uint8_t*)packed, shared->us[0],
-                       shared->us[1], shared->us[2]);
-    TQ_CHECK_LAUNCH();
-    hipLaunchKernelGGL(pool_bfrag_kernel, dim3(blocks_for(n_b)), dim3(256), 0, st, G, L.fm, (uint8_t*)packed, shared->v[0],
-                       shared->v[1], shared->v[2]);
-    TQ_CHECK_LAUNCH();
+    if (L.fm.fp8) {
+        hipLaunchKernelGGL(pool_afrag_kernel<uint8_t>, dim3(blocks_for(n_a)), dim3(256), 0, st, G, L.fm, (uint8_t*)packed,
+                           (const uint8_t*)shared->us[0], (const uint8_t*)shared->us[1], (const uint8_t*)shared->us[2]);
+        TQ_CHECK_LAUNCH();
+        hipLaunchKernelGGL(pool_bfrag_kernel<uint8_t>, dim3(blocks_for(n_b)), dim3(256), 0, st, G, L.fm, (uint8_t*)packed,
+                           (const uint8_t*)shared->v[0], (const uint8_t*)shared->v[1], (const uint8_t*)shared->v[2]);
+        TQ_CHECK_LAUNCH();
+        hipLaunchKernelGGL(sig_kernel<true>, dim3(blocks_for((tq_align256((size_t)8 * L.r16) + tq_align256((size_t)4 * L.r16)) / 4)),
+                           dim3(256), 0, st, G, L.fm, (uint8_t*)packed, const_cast<uint16_t*>(shared->sigma), 1);
+        TQ_CHECK_LAUNCH();
+    } else {
+        hipLaunchKernelGGL(pool_afrag_kernel<uint16_t>, dim3(blocks_for(n_a)), dim3(256), 0, st, G, L.fm, (uint8_t*)packed,
+                           shared->us[0], shared->us[1], shared->us[2]);
+        TQ_CHECK_LAUNCH();
+        hipLaunchKernelGGL(pool_bfrag_kernel<uint16_t>, dim3(blocks_for(n_b)), dim3(256), 0, st, G, L.fm, (uint8_t*)packed,
+                           shared->v[0], shared->v[1], shared->v[2]);
+        TQ_CHECK_LAUNCH();
+    }
     const int n_padded = (int)(tq_align256((size_t)(L.E + L.S) * 8) / 8);
     hipLaunchKernelGGL(phi_kernel, dim3(blocks_for((size_t)n_padded)), dim3(256), 0, st, L.fm, L.E + L.S, n_padded,
                        (uint8_t*)packed, shared->phi, err_flag);
@@ -592,9 +718,10 @@ extern "C" tq_status tq_unpack_weights(const tq_layer_desc* desc, const void* pa
     TqLayout L;
     if (!tq_make_layout(desc, &L)) return TQ_ERR_SHAPE;
     if (L.r > 0 && !L.fm.shared && (!dst->A || !dst->B)) return TQ_ERR_NULL;      // shared factors: codes, scale, zero only
+    if (L.fm.fp8 && !L.fm.shared && (!dst->sigma || misaligned(dst->sigma, 2))) return TQ_ERR_NULL;
     if (misaligned(packed, 256) || misaligned(dst->codes, 16) || misaligned(dst->scale, 16) ||
         misaligned(dst->zero, 16) || (L.r > 0 && !L.fm.shared && (misaligned(dst->A, 16) || misaligned(dst->B, 16))))
         return TQ_ERR_ALIGN;
     return run<false>(L, const_cast<uint8_t*>((const uint8_t*)packed), dst->codes, dst->scale, dst->zero, dst->A,
-                      dst->B, nullptr, (hipStream_t)stream);
+                      dst->B, dst->sigma, nullptr, (hipStream_t)stream);
 }

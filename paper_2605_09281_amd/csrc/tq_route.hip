@@ -104,7 +104,7 @@ __device__ inline bool blob_header_ok(const TqBlobHeader* hdr, const TqBlobHeade
     return hdr->magic == expect.magic && hdr->version == expect.version && hdr->n_experts == expect.n_experts &&
            hdr->n_shared == expect.n_shared && hdr->hidden == expect.hidden && hdr->ffn == expect.ffn &&
            hdr->group == expect.group && hdr->bits == expect.bits && hdr->rank == expect.rank &&
-           hdr->code_words == expect.code_words && hdr->tiles_m == expect.tiles_m && hdr->tiles_n == expect.tiles_n &&
+           hdr->code_words == expect.code_words && hdr->factor_fp8 == expect.factor_fp8 && hdr->tiles_m == expect.tiles_m && hdr->tiles_n == expect.tiles_n &&
            hdr->expert_stride == expect.expert_stride;
 }
 
@@ -407,7 +407,8 @@ __device__ inline void permute_small_body(const int32_t* __restrict__ idx, const
 }
 
 // One wavefront per (assignment v, 256-wide slice, 32-column tile of t): see TqPreByAssign.  Plain fp32 FMAs on the
-// exact values of x (bf16) and A (fp16), the two halves of a 16-wide step in the two halves of the wave.
+// exact values of x (bf16) and A (fp16, or fp8 with FP8), the two halves of a 16-wide step in the two halves of the wave.
+template <bool FP8>
 __device__ inline void pre_by_assign_block(const TqPreByAssign& P, const int32_t* __restrict__ idx, int T, int E, int k,
                                            int b, int lane)
 {
@@ -429,7 +430,8 @@ __device__ inline void pre_by_assign_block(const TqPreByAssign& P, const int32_t
     for (int u = 0; u < NS; ++u) {
         const int sidx = min(s0 + u, ksteps - 1);
         xa[u] = *reinterpret_cast<const uint4*>(xrow + 16 * sidx + 8 * hf);
-        aq[u] = af[((size_t)ta * ksteps + sidx) * 64 + lane];
+        const size_t f = (size_t)ta * ksteps + sidx;       // fragment; fp8 fragments: 8 bytes per lane, two lanes per word
+        aq[u] = af[FP8 ? f * 32 + (lane >> 1) : f * 64 + lane];
     }
     float acc = 0.f;
 #pragma unroll
@@ -437,10 +439,21 @@ __device__ inline void pre_by_assign_block(const TqPreByAssign& P, const int32_t
         if (s0 + u < ksteps) {
             const uint32_t xw[4] = {xa[u].x, xa[u].y, xa[u].z, xa[u].w};
             const uint32_t aw[4] = {aq[u].x, aq[u].y, aq[u].z, aq[u].w};
+            if (FP8) {
+                const uint32_t d[2] = {(lane & 1) ? aw[2] : aw[0], (lane & 1) ? aw[3] : aw[1]};
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                acc = fmaf(__uint_as_float(xw[j] << 16), tq_half_bits_to_float((uint16_t)(aw[j] & 0xFFFF)), acc);
-                acc = fmaf(__uint_as_float(xw[j] & 0xFFFF0000u), tq_half_bits_to_float((uint16_t)(aw[j] >> 16)), acc);
+                for (int j = 0; j < 4; ++j) {      // elements 2j, 2j + 1: bytes 2 (j % 2), 2 (j % 2) + 1 of word j / 2
+                    const auto a2 = (j & 1) ? __builtin_amdgcn_cvt_pk_f32_fp8(d[j >> 1], true)
+                                            : __builtin_amdgcn_cvt_pk_f32_fp8(d[j >> 1], false);
+                    acc = fmaf(__uint_as_float(xw[j] << 16), a2[0], acc);
+                    acc = fmaf(__uint_as_float(xw[j] & 0xFFFF0000u), a2[1], acc);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    acc = fmaf(__uint_as_float(xw[j] << 16), tq_half_bits_to_float((uint16_t)(aw[j] & 0xFFFF)), acc);
+                    acc = fmaf(__uint_as_float(xw[j] & 0xFFFF0000u), tq_half_bits_to_float((uint16_t)(aw[j] >> 16)), acc);
+                }
             }
         }
     }
@@ -448,17 +461,19 @@ __device__ inline void pre_by_assign_block(const TqPreByAssign& P, const int32_t
     if (hf == 0) P.tpart[(((size_t)v * P.n_slices + slice) * P.na_tiles + ta) * 32 + col] = acc;
 }
 
+template <bool FP8>
 __global__ void __launch_bounds__(64) pre_by_assign_kernel(TqPreByAssign P, const int32_t* __restrict__ idx, int T, int E, int k,
                                                            const TqBlobHeader* __restrict__ hdr, TqBlobHeader expect,
                                                            int check_blob)
 {
     if (check_blob && !blob_header_ok(hdr, expect)) return;      // a blob of another layer is not indexed
-    pre_by_assign_block(P, idx, T, E, k, blockIdx.x, threadIdx.x);
+    pre_by_assign_block<FP8>(P, idx, T, E, k, blockIdx.x, threadIdx.x);
 }
 
 // The whole permutation for a few chunks of assignments in ONE wavefront (one launch instead of five); with
-// HAS_PRE the other workgroups of the launch compute the gate/up low-rank intermediate by assignment.
-template <bool HAS_PRE>
+// PRE != 0 the other workgroups of the launch compute the gate/up low-rank intermediate by assignment (1: fp16
+// factors, 2: fp8 factors).
+template <int PRE>
 __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __restrict__ idx, const float* __restrict__ w,
                                                            int n_assign, int E, int S, int T, int k,
                                                            int32_t* __restrict__ offsets, int32_t* __restrict__ slot_of,
@@ -471,9 +486,9 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
                                                            int check_blob, int32_t* __restrict__ zero_buf, int zero_n,
                                                            TqPreByAssign P, int tilings)
 {
-    if (HAS_PRE && blockIdx.x > 0) {
+    if (PRE != 0 && blockIdx.x > 0) {
         if (check_blob && !blob_header_ok(hdr, expect)) return;      // a blob of another layer is not indexed
-        pre_by_assign_block(P, idx, T, E, k, blockIdx.x - 1, threadIdx.x);
+        pre_by_assign_block<PRE == 2>(P, idx, T, E, k, blockIdx.x - 1, threadIdx.x);
         return;
     }
     permute_small_body(idx, w, n_assign, E, S, T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e,
@@ -506,18 +521,23 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
         expect.magic = TQ_BLOB_MAGIC; expect.version = TQ_BLOB_VERSION;
         expect.n_experts = L->E; expect.n_shared = L->S; expect.hidden = L->H; expect.ffn = L->F;
         expect.group = L->g; expect.bits = L->bits; expect.rank = L->r; expect.expert_stride = L->expert_stride;
-        expect.code_words = L->cw; expect.tiles_m = L->fm.M; expect.tiles_n = L->fm.N;
+        expect.code_words = L->cw; expect.factor_fp8 = L->fm.fp8; expect.tiles_m = L->fm.M; expect.tiles_n = L->fm.N;
     }
     const int ne = E + S;
     if (nblk == 1 && (int64_t)S * T <= 4096) {
         const size_t sm = ((size_t)ne + (ne + 1) + E + TQ_N_TILINGS * (ne + 1)) * 4;
-        if (n_pre > 0)
-            hipLaunchKernelGGL(permute_small_kernel<true>, dim3(1 + (unsigned)n_pre), dim3(64), sm, stream, topk_idx, topk_w,
+        if (n_pre > 0 && pre->fm.fp8)
+            hipLaunchKernelGGL(permute_small_kernel<2>, dim3(1 + (unsigned)n_pre), dim3(64), sm, stream, topk_idx, topk_w,
+                               (int)n_assign, E, S, T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e,
+                               tile_row0, rt_max, ctrl, err_flag, (const TqBlobHeader*)blob, expect, check, zero_buf,
+                               (int)zero_n, *pre, tilings);
+        else if (n_pre > 0)
+            hipLaunchKernelGGL(permute_small_kernel<1>, dim3(1 + (unsigned)n_pre), dim3(64), sm, stream, topk_idx, topk_w,
                                (int)n_assign, E, S, T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e,
                                tile_row0, rt_max, ctrl, err_flag, (const TqBlobHeader*)blob, expect, check, zero_buf,
                                (int)zero_n, *pre, tilings);
         else
-            hipLaunchKernelGGL(permute_small_kernel<false>, dim3(1), dim3(64), sm, stream, topk_idx, topk_w, (int)n_assign,
+            hipLaunchKernelGGL(permute_small_kernel<0>, dim3(1), dim3(64), sm, stream, topk_idx, topk_w, (int)n_assign,
                                E, S, T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e, tile_row0,
                                rt_max, ctrl, err_flag, (const TqBlobHeader*)blob, expect, check, zero_buf, (int)zero_n,
                                TqPreByAssign{}, tilings);
@@ -525,8 +545,12 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
         return TQ_OK;
     }
     if (n_pre > 0) {      // the permutation takes several launches: the pre-pass gets its own
-        hipLaunchKernelGGL(pre_by_assign_kernel, dim3((unsigned)n_pre), dim3(64), 0, stream, *pre, topk_idx, T, E, k,
-                           (const TqBlobHeader*)blob, expect, check);
+        if (pre->fm.fp8)
+            hipLaunchKernelGGL(pre_by_assign_kernel<true>, dim3((unsigned)n_pre), dim3(64), 0, stream, *pre, topk_idx, T, E, k,
+                               (const TqBlobHeader*)blob, expect, check);
+        else
+            hipLaunchKernelGGL(pre_by_assign_kernel<false>, dim3((unsigned)n_pre), dim3(64), 0, stream, *pre, topk_idx, T, E, k,
+                               (const TqBlobHeader*)blob, expect, check);
         TQ_CHECK_LAUNCH();
     }
     if (ctrl) {

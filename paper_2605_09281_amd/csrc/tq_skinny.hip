@@ -33,7 +33,7 @@ __device__ inline int row_of_v(int v, int hf) { return 8 * (v >> 2) + 4 * hf + (
 // One wave per (tile, slice, ta); all of its loads are in flight at once.
 constexpr int SK_PRE_K = 256;
 
-template <int STAGE>
+template <int STAGE, bool FP8>
 __global__ void __launch_bounds__(64) skinny_pre_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
                                                         const uint16_t* __restrict__ xin,
                                                         const int32_t* __restrict__ row_token,
@@ -61,14 +61,17 @@ __global__ void __launch_bounds__(64) skinny_pre_kernel(MGeom G, TqSection sec, 
     for (int u = 0; u < NS; ++u)
         if (u < n) {
             xa[u].q = *reinterpret_cast<const u32x4*>(xrow + 16 * (s0 + u) + 8 * hf);
-            aq[u] = af[((size_t)ta * ksteps + s0 + u) * 64 + lane];
+            const size_t f = (size_t)ta * ksteps + s0 + u;                  // fragment; fp8 fragments are half as long
+            aq[u] = af[FP8 ? f * 32 + (lane >> 1) : f * 64 + lane];
         }
     f32x16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
 #pragma unroll
     for (int u = 0; u < NS; ++u)
-        if (u < n) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[u].v, half8_to_bf8(aq[u]), acc, 0, 0, 0);
+        if (u < n)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[u].v, FP8 ? fp8_frag_to_bf8(aq[u], lane) : half8_to_bf8(aq[u]), acc,
+                                                          0, 0, 0);
     float* dst = tpart + (((size_t)tile * n_slices + slice) * na_tiles + ta) * 512 + lane;
 #pragma unroll
     for (int v = 0; v < 8; ++v) dst[v * 64] = acc[v];
@@ -131,7 +134,10 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     const u32x4* codes = reinterpret_cast<const u32x4*>(rec + sec.codes) + lane;
     const uint32_t* szp = reinterpret_cast<const uint32_t*>(rec + sec.sz) + col;
     const u32x4* bfr = reinterpret_cast<const u32x4*>(G.r > 0 ? tq_bfrag_base(blob, G.expert_stride, sec, G.fm, STAGE, e)
-                                                               : rec + sec.bfrag) + lane;
+                                                               : rec + sec.bfrag);
+    const bool fp8 = G.fm.fp8 != 0;
+    // fragment f of the right factors: 64 lanes x 16 bytes (fp16), or 64 x 8 bytes (fp8: lanes 2j, 2j + 1 share a word)
+    const int b_per = fp8 ? 32 : 64, b_lane = fp8 ? (lane >> 1) : lane;
 
     // Unit and pair indices are clamped into the valid range instead of guarding the loads: a load under a
     // condition makes the compiler wait for ALL outstanding loads at every later use, which would drain the
@@ -191,6 +197,13 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     // ---- the slices of the low-rank intermediate: up to 16 per workgroup range and column tile of t.  Requested
     //         before the weights as well, and unconditionally (layers without factors read a valid dummy word with
     //         weight zero).
+    // Sigma of fp8 factors for this lane's columns of t (requested with the slices; 1 otherwise, from a valid dummy word)
+    float sgv[4];
+    {
+        const float* sp = fp8 ? tq_sig_base(blob, G.expert_stride, sec, G.fm, STAGE, e) : reinterpret_cast<const float*>(ctrl);
+#pragma unroll
+        for (int ta = 0; ta < 4; ++ta) sgv[ta] = sp[fp8 ? min(32 * ta + col, NA - 1) : 0];
+    }
     float tv[4][16];
     {
         const int sl0 = (ub * UNIT_K) / SK_PRE_K;
@@ -247,17 +260,18 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     const int steps_per_tile = G.r16 / 16;
     const int lr_t = (STAGE == 0 && wave >= steps_per_tile) ? 1 : 0;
     const int lr_step = (G.r > 0) ? min(wave - lr_t * steps_per_tile, steps_per_tile - 1) : 0;
-    const u32x4* bsrc = (G.r > 0) ? bfr : codes;
-    const size_t bstride = (G.r > 0) ? (size_t)steps_per_tile * 128 : (size_t)0;      // dummy reads stay in the first 2 KB of the codes
+    const u32x4* bsrc = (G.r > 0) ? bfr + b_lane : codes;
+    const size_t bstride = (G.r > 0) ? (size_t)steps_per_tile * 2 * b_per : (size_t)0;      // dummy reads stay in the first 2 KB of the codes
     auto load_b = [&](u32x4 (&dst)[2], int pair) {
         if (STAGE == 0) {
-            dst[0] = bsrc[(size_t)pair * bstride + ((size_t)lr_step * 2 + lr_t) * 64];
+            dst[0] = bsrc[(size_t)pair * bstride + ((size_t)lr_step * 2 + lr_t) * b_per];
             dst[1] = dst[0];
         } else {
-            dst[0] = bsrc[(size_t)pair * bstride + ((size_t)lr_step * 2 + 0) * 64];
-            dst[1] = bsrc[(size_t)pair * bstride + ((size_t)lr_step * 2 + 1) * 64];
+            dst[0] = bsrc[(size_t)pair * bstride + ((size_t)lr_step * 2 + 0) * b_per];
+            dst[1] = bsrc[(size_t)pair * bstride + ((size_t)lr_step * 2 + 1) * b_per];
         }
     };
+    auto b_operand = [&](const u32x4& raw) -> bf16x8 { return fp8 ? fp8_frag_to_bf8(raw, lane) : half8_to_bf8(raw); };
     u32x4 bq[2];
     load_b(bq, p0);
 
@@ -304,7 +318,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
 #pragma unroll
         for (int ta = 0; ta < 4; ++ta) {
             const int c = 32 * ta + col;
-            if (ta < na_tiles && c < NA) tbuf[m * NA + c] = (uint16_t)f2bf_bits(tsum[ta]);
+            if (ta < na_tiles && c < NA) tbuf[m * NA + c] = (uint16_t)f2bf_bits(fp8 ? tsum[ta] * sgv[ta] : tsum[ta]);
         }
         lds_barrier();
         if (wave < n_lr) tf.q = *reinterpret_cast<const u32x4*>(tbuf + (col & 15) * NA + 16 * wave + 8 * hf);
@@ -390,7 +404,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
 #pragma unroll
                 for (int v = 0; v < 16; ++v) zero[v] = 0.f;
                 if (STAGE == 0) {
-                    const f32x16 lr = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf.v, half8_to_bf8(bc[0]), zero, 0, 0, 0);
+                    const f32x16 lr = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf.v, b_operand(bc[0]), zero, 0, 0, 0);
 #pragma unroll
                     for (int v = 0; v < 8; ++v) {
                         if (lr_t == 0) acc8[0][v] += lr[v]; else acc8[1][v] += lr[v];
@@ -398,7 +412,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
                 } else {
 #pragma unroll
                     for (int t = 0; t < 2; ++t) {
-                        const f32x16 lr = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf.v, half8_to_bf8(bc[t]), zero, 0, 0, 0);
+                        const f32x16 lr = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf.v, b_operand(bc[t]), zero, 0, 0, 0);
 #pragma unroll
                         for (int v = 0; v < 8; ++v) acc8[t][v] += lr[v];
                     }
@@ -597,8 +611,12 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     const bool by_assign = tqi_pre_by_assign(L, W);
     const int32_t* row_src = by_assign ? reinterpret_cast<const int32_t*>(ws + W.row_src) : nullptr;
     if (L.r > 0 && !by_assign) {
-        hipLaunchKernelGGL(skinny_pre_kernel<0>, dim3(rt16, sl_gu, nat_gu), dim3(64), 0, stream, G, L.gu, blob, x, row_token, tile_e,
-                           tile_row0, offsets, ctrl, tpart, sl_gu, nat_gu);
+        if (L.fm.fp8)
+            hipLaunchKernelGGL((skinny_pre_kernel<0, true>), dim3(rt16, sl_gu, nat_gu), dim3(64), 0, stream, G, L.gu, blob, x, row_token,
+                               tile_e, tile_row0, offsets, ctrl, tpart, sl_gu, nat_gu);
+        else
+            hipLaunchKernelGGL((skinny_pre_kernel<0, false>), dim3(rt16, sl_gu, nat_gu), dim3(64), 0, stream, G, L.gu, blob, x, row_token,
+                               tile_e, tile_row0, offsets, ctrl, tpart, sl_gu, nat_gu);
         TQ_CHECK_LAUNCH();
     }
     tqi_record_stage(2, stream);
@@ -609,8 +627,12 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     if (rc != TQ_OK) return rc;
     tqi_record_stage(3, stream);
     if (L.r > 0) {
-        hipLaunchKernelGGL(skinny_pre_kernel<1>, dim3(rt16, sl_d, nat_d), dim3(64), 0, stream, G, L.d, blob, h, row_token, tile_e,
-                           tile_row0, offsets, ctrl, tpart, sl_d, nat_d);
+        if (L.fm.fp8)
+            hipLaunchKernelGGL((skinny_pre_kernel<1, true>), dim3(rt16, sl_d, nat_d), dim3(64), 0, stream, G, L.d, blob, h, row_token,
+                               tile_e, tile_row0, offsets, ctrl, tpart, sl_d, nat_d);
+        else
+            hipLaunchKernelGGL((skinny_pre_kernel<1, false>), dim3(rt16, sl_d, nat_d), dim3(64), 0, stream, G, L.d, blob, h, row_token,
+                               tile_e, tile_row0, offsets, ctrl, tpart, sl_d, nat_d);
         TQ_CHECK_LAUNCH();
     }
     tqi_record_stage(4, stream);

@@ -302,6 +302,49 @@ def make_shared_layer(cfg: LayerConfig, M: Optional[int] = None, N: Optional[int
     return SharedLayer(cfg, layer.codes, layer.scale, layer.zero, us, v, phi)
 
 
+_TID_FP8 = 15
+
+
+@dataclasses.dataclass
+class Fp8Layer:
+    """A layer whose low-rank factors are fp8 E4M3 codes with an fp16 diagonal Sigma: A8 uint8 [E+S, (2H+F) r] and
+    B8 uint8 [E+S, (2F+H) r] in the shapes of Layer.A / Layer.B, sigma uint16 (fp16 bits) [E+S, 3, r]."""
+    cfg: LayerConfig
+    codes: np.ndarray
+    scale: np.ndarray
+    zero: np.ndarray
+    A8: np.ndarray
+    B8: np.ndarray
+    sigma: np.ndarray
+
+    def a8_list(self):
+        c = self.cfg
+        o = (0, c.H * c.r, 2 * c.H * c.r, (2 * c.H + c.F) * c.r)
+        return [np.ascontiguousarray(self.A8[:, o[p]:o[p + 1]]).reshape(c.n_exp, -1, c.r) for p in range(3)]
+
+    def b8_list(self):
+        c = self.cfg
+        o = (0, c.F * c.r, 2 * c.F * c.r, (2 * c.F + c.H) * c.r)
+        return [np.ascontiguousarray(self.B8[:, o[p]:o[p + 1]]).reshape(c.n_exp, c.r, -1) for p in range(3)]
+
+
+def make_layer_fp8(cfg: LayerConfig, layer: Optional["Layer"] = None, sigma_pow2: bool = False, workers: int = 8) -> Fp8Layer:
+    """Codes as make_layer (or taken from `layer`); factors: fp8 codes of N(0, 1) draws (unit scale, as the columns of a
+    normalised factorisation are stored) and sigma = f_std^2 / (1 + rho / 4) per rank component, a decaying spectrum
+    (sigma_pow2: rounded down to powers of two, so that fp8 * sigma is exact in fp16)."""
+    assert cfg.r > 0
+    if layer is None:
+        layer = make_layer(cfg, workers=workers)
+    rng = _rng(cfg.cfg_id, _TID_FP8)
+    ne = cfg.n_exp
+    A8 = fp8_e4m3_encode(rng.standard_normal((ne, (2 * cfg.H + cfg.F) * cfg.r), dtype=np.float32))
+    B8 = fp8_e4m3_encode(rng.standard_normal((ne, (2 * cfg.F + cfg.H) * cfg.r), dtype=np.float32))
+    sg = (cfg.f_std ** 2 / (1.0 + np.arange(cfg.r) / 4.0)) * (1.0 + 0.25 * rng.random((ne, 3, cfg.r)))
+    if sigma_pow2:
+        sg = 2.0 ** np.floor(np.log2(sg))
+    return Fp8Layer(cfg, layer.codes, layer.scale, layer.zero, A8, B8, sg.astype(np.float16).view(np.uint16))
+
+
 _TID_PLANTED = 14
 
 

@@ -1,0 +1,188 @@
+"""Mixed-precision factor storage inside the layer (TQ_FLAG_FP8_FACTORS: fp8 E4M3 factors with an fp16 diagonal Sigma;
+end of Section 3.1, Appendix A.3 with d_low = 8): blob byte for byte against oracle/pack_ref.py, unpack as its
+inverse, and the forward on every path against the oracle's fp8 layer, per-expert and shared tiled factors."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import pack_ref
+from synth import CONFIGS, LayerConfig, make_layer, make_layer_fp8, make_shared_layer, make_x, make_logits, fp8_e4m3_encode
+import paper_2605_09281_amd.binding as tq
+from gpu_util import DEV, dev16, x_device, rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+REG_BF16 = 4 * 2.0 ** -9
+TOL_FP32 = 1e-5
+
+
+def fcfg(cfg_id, **kw):
+    base = dict(name="f8", E=4, S=0, k=2, H=128, F=192, T=9, g=64, r=8, bits=4)
+    base.update(kw)
+    return LayerConfig(cfg_id, **base)
+
+
+CASES = {
+    "r8": fcfg(941),
+    "r32_shared_expert_g128": fcfg(942, H=256, F=384, g=128, r=32, E=6, S=1, k=3, T=13),
+    "r20_g32": fcfg(943, g=32, r=20, T=40),
+    "r48_int3": fcfg(944, H=256, F=128, bits=3, r=48, E=8, T=300),
+    "dense3_r16": fcfg(945, bits=3, dense=True, r=16, T=11),
+    "min_dims_r4": fcfg(946, H=64, F=64, r=4, T=3),
+    "r16_1400_rows": fcfg(947, r=16, T=700),      # beyond the decode kernels: the tiled kernels without a forced path
+}
+_cache = {}
+
+
+def get(name):
+    if name not in _cache:
+        cfg = CASES[name]
+        _cache[name] = (make_layer_fp8(cfg), make_x(cfg), make_logits(cfg))
+    return _cache[name]
+
+
+def desc_fp8(cfg, act=tq.TQ_ACT_BF16, flags=0, M=0, N=0):
+    flags |= tq.TQ_FLAG_FP8_FACTORS
+    if cfg.dense:
+        flags |= tq.TQ_FLAG_DENSE_CODES
+    return tq.make_desc(cfg.E, cfg.S, cfg.k, cfg.H, cfg.F, cfg.g, cfg.bits, cfg.r, act, flags, tiles_m=M, tiles_n=N)
+
+
+def pack_gpu(fl, act=tq.TQ_ACT_BF16):
+    err = torch.zeros(1, dtype=torch.int32, device=DEV)
+    packed = tq.tq_pack_weights(desc_fp8(fl.cfg, act), torch.from_numpy(fl.codes).to(DEV), dev16(fl.scale), dev16(fl.zero),
+                                torch.from_numpy(fl.A8).to(DEV), torch.from_numpy(fl.B8).to(DEV), err_flag=err, sigma=dev16(fl.sigma))
+    torch.cuda.synchronize()
+    assert int(err.item()) == 0
+    return packed
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_fp8_pack_is_byte_exact_and_unpack_inverts(name):
+    fl, _, _ = get(name)
+    cfg = fl.cfg
+    packed = pack_gpu(fl)
+    ref = pack_ref.pack_layer_fp8(fl)
+    body = packed.cpu().numpy()[256:]
+    assert body.size == ref.size == tq.tq_packed_size(desc_fp8(cfg)) - 256
+    assert np.array_equal(body, ref)
+    codes = torch.full(fl.codes.shape, 255, dtype=torch.uint8, device=DEV)
+    scale = torch.zeros(fl.scale.shape, dtype=torch.int16, device=DEV)
+    zero = torch.zeros_like(scale)
+    A8 = torch.zeros(fl.A8.shape, dtype=torch.uint8, device=DEV)
+    B8 = torch.zeros(fl.B8.shape, dtype=torch.uint8, device=DEV)
+    sg = torch.zeros(fl.sigma.shape, dtype=torch.int16, device=DEV)
+    tq.tq_unpack_weights(desc_fp8(cfg), packed, codes, scale, zero, A8, B8, sigma=sg)
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy(), fl.codes)
+    assert np.array_equal(A8.cpu().numpy(), fl.A8) and np.array_equal(B8.cpu().numpy(), fl.B8)
+    assert np.array_equal(sg.cpu().numpy().view(np.uint16), fl.sigma)
+    # the factor bytes are half those of the fp16 format
+    d16 = tq.make_desc(cfg.E, cfg.S, cfg.k, cfg.H, cfg.F, cfg.g, cfg.bits, cfg.r, tq.TQ_ACT_BF16, tq.TQ_FLAG_DENSE_CODES if cfg.dense else 0)
+    d0 = tq.make_desc(cfg.E, cfg.S, cfg.k, cfg.H, cfg.F, cfg.g, cfg.bits, 0, tq.TQ_ACT_BF16, tq.TQ_FLAG_DENSE_CODES if cfg.dense else 0)
+    f16b = tq.tq_packed_size(d16) - tq.tq_packed_size(d0)
+    f8b = tq.tq_packed_size(desc_fp8(cfg)) - tq.tq_packed_size(d0)
+    r16 = (cfg.r + 15) // 16 * 16
+    assert f8b == f16b // 2 + (cfg.E + cfg.S) * 2 * 256 * ((r16 * 8 + 255) // 256 + 0 * r16) or f8b < 0.62 * f16b
+
+
+def forward(fl, x, logits, bias, act, flags=0):
+    cfg = fl.cfg
+    packed = pack_gpu(fl, act)
+    idx, w = tq.tq_route(torch.from_numpy(logits).to(DEV), None if bias is None else torch.from_numpy(bias).to(DEV), cfg.k)
+    desc = desc_fp8(cfg, act, flags)
+    ws = torch.empty(tq.tq_moe_workspace_size(desc, x.shape[0]), dtype=torch.uint8, device=DEV)
+    y = tq.tq_moe_forward(desc, packed, x_device(x, act), idx, w, workspace=ws)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32).item()) == 0
+    ref = oracle.moe_forward_fp8(cfg, fl.codes, fl.scale, fl.zero, fl.a8_list(), fl.b8_list(), fl.sigma, x, idx.cpu().numpy(),
+                                 w.cpu().numpy())
+    return y.float().cpu().numpy(), ref
+
+
+PATHS = {"decode": tq.TQ_FLAG_FORCE_SKINNY, "auto": 0, "small_tile": tq.TQ_FLAG_FORCE_SMALL_TILE, "large_tile": tq.TQ_FLAG_FORCE_LARGE_TILE}
+
+
+@pytest.mark.parametrize("path", list(PATHS))
+@pytest.mark.parametrize("name", list(CASES))
+def test_fp8_forward_bf16(name, path):
+    print(f"fp8 factors bf16 {name} {path}", flush=True)
+    fl, x, (logits, bias) = get(name)
+    got, ref = forward(fl, x, logits, bias, tq.TQ_ACT_BF16, PATHS[path])
+    e = rel_err(got, ref)
+    print(f"   rel err {e:.3e}", flush=True)
+    assert e <= TOL_BF16
+    assert e <= REG_BF16
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_fp8_forward_fp32(name):
+    fl, x, (logits, bias) = get(name)
+    got, ref = forward(fl, x, logits, bias, tq.TQ_ACT_FP32)
+    assert rel_err(got, ref) <= TOL_FP32
+
+
+def test_fp8_factors_carry_weight_in_the_result():
+    """With Sigma scaled up until the low-rank term is as large as the quantised one the bound still holds, and the
+    result moves by far more than the bound when Sigma is dropped (in the oracle)."""
+    cfg = fcfg(950, r=16, T=20)
+    fl = make_layer_fp8(cfg)
+    big = (fl.sigma.view(np.float16).astype(np.float32) * 64.0).astype(np.float16).view(np.uint16)
+    import dataclasses
+    fl2 = dataclasses.replace(fl, sigma=big)
+    x = make_x(cfg)
+    logits, bias = make_logits(cfg)
+    for path in ("decode", "auto"):
+        got, ref = forward(fl2, x, logits, bias, tq.TQ_ACT_BF16, PATHS[path])
+        assert rel_err(got, ref) <= 7 * 2.0 ** -9
+        idx, w = tq.tq_route(torch.from_numpy(logits).to(DEV), None, cfg.k)
+        wrong = oracle.moe_forward_fp8(cfg, fl.codes, fl.scale, fl.zero, fl.a8_list(), fl.b8_list(), fl.sigma, x,
+                                       idx.cpu().numpy(), w.cpu().numpy())
+        assert rel_err(got, wrong) > 0.1
+
+
+def test_shared_fp8_factors():
+    cfg = fcfg(951, E=6, S=1, k=2, H=128, F=256, r=24, T=50)
+    M, N = 2, 3
+    sl = make_shared_layer(cfg, M, N)
+    rng = np.random.default_rng(951)
+    sl.us = [fp8_e4m3_encode(rng.standard_normal(a.shape).astype(np.float32)) for a in sl.us]
+    sl.v = [fp8_e4m3_encode(rng.standard_normal(a.shape).astype(np.float32)) for a in sl.v]
+    sl.sigma = (cfg.f_std ** 2 / (1.0 + np.arange(cfg.r) / 4.0) * (1.0 + 0.25 * rng.random((3, cfg.r)))).astype(np.float16).view(np.uint16)
+    x = make_x(cfg)
+    logits, bias = make_logits(cfg)
+    idx, w = tq.tq_route(torch.from_numpy(logits).to(DEV), None, cfg.k)
+    ref = oracle.moe_forward_fp8(cfg, sl.codes, sl.scale, sl.zero, sl.us, sl.v, sl.sigma, x, idx.cpu().numpy(), w.cpu().numpy(), phi=sl.phi)
+    for act, tol in ((tq.TQ_ACT_BF16, REG_BF16), (tq.TQ_ACT_FP32, TOL_FP32)):
+        for path in (PATHS if act == tq.TQ_ACT_BF16 else {"auto": 0}):
+            desc = desc_fp8(cfg, act, PATHS[path], M, N)
+            err = torch.zeros(1, dtype=torch.int32, device=DEV)
+            packed = tq.tq_pack_weights_shared(desc, torch.from_numpy(sl.codes).to(DEV), dev16(sl.scale), dev16(sl.zero),
+                                               [torch.from_numpy(a).to(DEV) for a in sl.us], [torch.from_numpy(a).to(DEV) for a in sl.v],
+                                               torch.from_numpy(sl.phi).to(DEV), err_flag=err, sigma=dev16(sl.sigma))
+            torch.cuda.synchronize()
+            assert int(err.item()) == 0
+            if act == tq.TQ_ACT_BF16 and path == "decode":
+                assert np.array_equal(packed.cpu().numpy()[256:], pack_ref.pack_layer_shared(sl))
+            ws = torch.empty(tq.tq_moe_workspace_size(desc, cfg.T), dtype=torch.uint8, device=DEV)
+            y = tq.tq_moe_forward(desc, packed, x_device(x, act), idx, w, workspace=ws)
+            torch.cuda.synchronize()
+            assert int(ws[:4].view(torch.int32).item()) == 0
+            e = rel_err(y.float().cpu().numpy(), ref)
+            print(f"shared fp8 {path} act {act}: rel err {e:.3e}", flush=True)
+            assert e <= tol
+
+
+def test_fp8_decode_full_shape():
+    """The Mixtral-shaped decode layer (benchmark config 2) with fp8 factors."""
+    cfg = CONFIGS[2].replace(cfg_id=960)
+    print("fp8 config 2: generating", flush=True)
+    fl = make_layer_fp8(cfg, workers=16)
+    x = make_x(cfg)
+    logits, bias = make_logits(cfg)
+    got, ref = forward(fl, x, logits, bias, tq.TQ_ACT_BF16)
+    e = rel_err(got, ref)
+    print(f"fp8 config 2: rel err {e:.3e}", flush=True)
+    assert e <= REG_BF16

@@ -27,8 +27,9 @@ def _align256(n):
     return (n + 255) // 256 * 256
 
 
-def factor_parts_by_definition(sec, A, B, H, F, r):
-    """(bfrag, afrag) of one section from A[p] [K, r] and B[p] [r, N] (fp16 bit patterns), element by element."""
+def factor_parts_by_definition(sec, A, B, H, F, r, elem="<H"):
+    """(bfrag, afrag) of one section from A[p] [K, r] and B[p] [r, N] (fp16 bit patterns, or fp8 codes with
+    elem = "<B"), element by element."""
     r16 = (r + 15) // 16 * 16
     if sec == "GU":
         K, pairs, na = H, F // 32, 2 * r16
@@ -46,7 +47,7 @@ def factor_parts_by_definition(sec, A, B, H, F, r):
                     hf = lane // 32
                     for i in range(8):
                         rho = 16 * s + 8 * hf + i
-                        bpart += struct.pack("<H", int(B[p][rho, n]) if rho < r else 0)
+                        bpart += struct.pack(elem, int(B[p][rho, n]) if rho < r else 0)
     # ---- afrag: fp16 [ceil(NA/32)][K/16][64 lanes][8]
     apart = bytearray()
     for ta in range((na + 31) // 32):
@@ -61,11 +62,24 @@ def factor_parts_by_definition(sec, A, B, H, F, r):
                         p, rho = (cc // r16, cc % r16) if sec == "GU" else (2, cc)
                         if rho < r:
                             v = int(A[p][kk, rho])
-                    apart += struct.pack("<H", v)
+                    apart += struct.pack(elem, v)
     return bytes(bpart), bytes(apart)
 
 
-def blob_by_definition(layer, with_factors=True) -> bytes:
+def sig_part_by_definition(sec, sigma3, r):
+    """fp32 Sigma of one section: gate then up (r16 each) in GU, r16 in D, zero beyond r, padded to 256 bytes."""
+    r16 = (r + 15) // 16 * 16
+    out = bytearray()
+    for p in ((0, 1) if sec == "GU" else (2,)):
+        for rho in range(r16):
+            v = np.float32(np.asarray(sigma3[p][rho:rho + 1], dtype=np.uint16).view(np.float16)[0]) if rho < r else np.float32(0)
+            out += struct.pack("<f", v)
+    out += b"\0" * (_align256(len(out)) - len(out))
+    return bytes(out)
+
+
+def blob_by_definition(layer, with_factors=True, fp8=None) -> bytes:
+    """fp8: an object with a8_list() / b8_list() / sigma whose factors replace the layer's fp16 ones."""
     c = layer.cfg
     H, F, g, r = c.H, c.F, c.g, c.r
     r16 = (r + 15) // 16 * 16
@@ -152,12 +166,19 @@ def blob_by_definition(layer, with_factors=True) -> bytes:
                                     v = hi if s % 2 == 0 else _bf16_rne_scalar(np.float32(cf - _bf16_to_f32(hi)))
                                 part += struct.pack("<H", v)
             rec += part
-            if r > 0 and with_factors:
+            if r > 0 and with_factors and fp8 is None:
                 A = [layer.a_matrix(e, p).view(np.uint16) for p in range(3)]
                 B = [layer.b_matrix(e, p).view(np.uint16) for p in range(3)]
                 bpart, apart = factor_parts_by_definition(sec, A, B, H, F, r)
                 rec += bpart
                 rec += apart
+            elif r > 0 and with_factors:
+                A = [fp8.a8_list()[p][e] for p in range(3)]
+                B = [fp8.b8_list()[p][e] for p in range(3)]
+                bpart, apart = factor_parts_by_definition(sec, A, B, H, F, r, elem="<B")
+                rec += bpart
+                rec += apart
+                rec += sig_part_by_definition(sec, [fp8.sigma[e, p] for p in range(3)], r)
         rec += b"\0" * (_align256(len(rec)) - len(rec))
         out += rec
     return bytes(out)
@@ -247,3 +268,54 @@ def test_shared_pack_ref_equals_the_layout_written_out_element_by_element(name):
         fact += M * ((na + 31) // 32) * (K // 16) * 1024 + N * pairs * (r16 // 16) * 2048
     rec = len(blob_by_definition(sl.expanded(), with_factors=False))
     assert len(got) == _align256(rec + _align256(8 * (cfg.E + cfg.S)) + fact)
+
+
+FP8_CASES = {
+    "fp8_r20": LayerConfig(921, "p", E=2, S=1, k=1, H=128, F=64, T=1, g=64, r=20, bits=4),
+    "fp8_r4_g32": LayerConfig(922, "p", E=1, S=0, k=1, H=64, F=64, T=1, g=32, r=4, bits=4),
+    "fp8_dense3_r33": LayerConfig(923, "p", E=2, S=0, k=1, H=64, F=128, T=1, g=64, r=33, bits=3, dense=True),
+}
+
+
+@pytest.mark.parametrize("name", list(FP8_CASES))
+def test_fp8_factor_pack_ref_equals_the_layout_written_out_element_by_element(name):
+    from synth import make_layer_fp8, Layer
+    cfg = FP8_CASES[name]
+    fl = make_layer_fp8(cfg, workers=1)
+    dummy = Layer(cfg, fl.codes, fl.scale, fl.zero, None, None)
+    want = blob_by_definition(dummy, fp8=fl)
+    got = pack_ref.pack_layer_fp8(fl).tobytes()
+    assert len(got) == len(want)
+    assert got == want
+
+
+def test_shared_fp8_pack_ref_equals_the_layout_written_out_element_by_element():
+    """Shared tiled fp8 factors: byte pools in the afrag / bfrag layouts and one fp32 Sigma table per section."""
+    from synth import make_shared_layer, fp8_e4m3_encode
+    cfg, M, N = LayerConfig(931, "p", E=3, S=1, k=1, H=64, F=128, T=1, g=32, r=12, bits=4), 2, 3
+    sl = make_shared_layer(cfg, M, N, workers=1)
+    rng = np.random.default_rng(931)
+    sl.us = [fp8_e4m3_encode(rng.standard_normal(a.shape).astype(np.float32)) for a in sl.us]
+    sl.v = [fp8_e4m3_encode(rng.standard_normal(a.shape).astype(np.float32)) for a in sl.v]
+    sl.sigma = (rng.random((3, cfg.r)) + 0.5).astype(np.float16).view(np.uint16)
+    got = pack_ref.pack_layer_shared(sl).tobytes()
+    # by definition: the records, the placement table, then per section M left blocks, N right blocks, Sigma
+    from synth import Layer
+    out = bytearray(blob_by_definition(Layer(cfg, sl.codes, sl.scale, sl.zero, None, None), with_factors=False))
+    for e in range(cfg.E + cfg.S):
+        out += struct.pack("<ii", int(sl.phi[e, 0]), int(sl.phi[e, 1]))
+    out += b"\0" * (_align256(len(out)) - len(out))
+    for sec in ("GU", "D"):
+        for m in range(M):
+            out += factor_parts_by_definition(sec, [sl.us[p][m] for p in range(3)], [sl.v[p][0] for p in range(3)], cfg.H, cfg.F,
+                                              cfg.r, elem="<B")[1]
+        for n in range(N):
+            out += factor_parts_by_definition(sec, [sl.us[p][0] for p in range(3)], [sl.v[p][n] for p in range(3)], cfg.H, cfg.F,
+                                              cfg.r, elem="<B")[0]
+        out += sig_part_by_definition(sec, [sl.sigma[p] for p in range(3)], cfg.r)
+    out += b"\0" * (_align256(len(out)) - len(out))
+    assert got == bytes(out)
+    desc_bytes = None
+    import paper_2605_09281_amd.binding as tq
+    d = tq.make_desc(cfg.E, cfg.S, cfg.k, cfg.H, cfg.F, cfg.g, cfg.bits, cfg.r, flags=tq.TQ_FLAG_FP8_FACTORS, tiles_m=M, tiles_n=N)
+    assert tq.tq_packed_size(d) - 256 == len(got)
