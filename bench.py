@@ -246,6 +246,8 @@ def main():
                          "(decode workloads only)")
     ap.add_argument("--fp8-factors", action="store_true",
                     help="with --workload: store the low-rank factors as fp8 E4M3 codes with an fp16 diagonal Sigma")
+    ap.add_argument("--separate-route", action="store_true",
+                    help="a step calls tq_route and tq_moe_forward one after the other instead of tq_route_moe_forward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every step eagerly instead of replaying a captured HIP graph")
@@ -442,8 +444,11 @@ def bench_layer(args, cfg, dev, oracle_macs, fp8=False):
     tq.tq_init()
 
     def step(i):
-        tq.tq_route(logits_d, bias_d, cfg.k, idx_d, w_d)
-        tq.tq_moe_forward(desc, packed[i % n_copies], x_d, idx_d, w_d, y=y_d, workspace=ws)
+        if args.separate_route:
+            tq.tq_route(logits_d, bias_d, cfg.k, idx_d, w_d)
+            tq.tq_moe_forward(desc, packed[i % n_copies], x_d, idx_d, w_d, y=y_d, workspace=ws)
+        else:      # routing and forward in one call: decode batches route inside the permutation's launch
+            tq.tq_route_moe_forward(desc, packed[i % n_copies], x_d, logits_d, bias_d, idx_d, w_d, y_d, ws)
 
     for i in range(max(args.warmup, n_copies)):
         step(i)

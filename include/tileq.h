@@ -245,6 +245,16 @@ tq_status tq_moe_forward(const tq_layer_desc *desc, const void *packed, const vo
                          const int32_t *topk_idx, const float *topk_w, int32_t T, void *y,
                          void *workspace, size_t workspace_bytes, void *stream);
 
+/* tq_route followed by tq_moe_forward in one call, with the same results bit for bit (Eq. 3: the top-K set, the
+ * routing weights and the weighted sum over the selected experts): logits fp32 [T,E] and bias fp32 [E] or NULL as
+ * for tq_route; topk_idx int32 [T,k] and topk_w fp32 [T,k] are OUTPUTS here (device, 16-byte aligned), everything else
+ * as for tq_moe_forward.  For decode batches (at most 64 tokens, at most 64 routed experts, at most 256 assignments)
+ * the routing runs inside the permutation's launch, which saves one kernel launch per step; other batches run the
+ * two steps one after the other. */
+tq_status tq_route_moe_forward(const tq_layer_desc *desc, const void *packed, const void *x, const float *logits,
+                               const float *bias, int32_t T, int32_t *topk_idx, float *topk_w, void *y,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
 /* For callers that cannot allocate device memory — code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc: tq_moe_forward without a workspace argument.  The same kernels run on a scratch array
  * of TQ_STATIC_SCRATCH_MAX bytes that lives inside the library (a static device array: every GPU the library runs

@@ -23,7 +23,7 @@ STATUS_NAMES = {0: "TQ_OK", 1: "TQ_ERR_NULL", 2: "TQ_ERR_SHAPE", 3: "TQ_ERR_ALIG
                 5: "TQ_ERR_WORKSPACE", 6: "TQ_ERR_UNSUPPORTED", 7: "TQ_ERR_HIP", 8: "TQ_ERR_BLOB"}
 
 EXPORTS = ["tq_init", "tq_status_str", "tq_packed_size", "tq_pack_weights", "tq_pack_weights_shared", "tq_unpack_weights", "tq_route",
-           "tq_permute_workspace_size", "tq_permute", "tq_moe_workspace_size", "tq_moe_forward", "tq_moe_forward_static",
+           "tq_permute_workspace_size", "tq_permute", "tq_moe_workspace_size", "tq_moe_forward", "tq_route_moe_forward", "tq_moe_forward_static",
            "tq_set_profile_events", "tq_debug_stream", "tq_debug_issue_probe", "tq_sketch_workspace_size", "tq_sketch_lowrank", "tq_lotile_packed_size", "tq_lotile_pack", "tq_lotile_pack_fp8",
            "tq_lotile_workspace_size", "tq_lotile_forward", "tq_lotile_grid", "tq_lotile_place"]
 
@@ -96,6 +96,10 @@ def lib():
         L.tq_moe_forward.argtypes = [ctypes.POINTER(LayerDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                      ctypes.c_size_t, ctypes.c_void_p]
+        L.tq_route_moe_forward.restype = ctypes.c_int
+        L.tq_route_moe_forward.argtypes = [ctypes.POINTER(LayerDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.tq_moe_forward_static.restype = ctypes.c_int
         L.tq_moe_forward_static.argtypes = [ctypes.POINTER(LayerDesc), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                             ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
@@ -243,6 +247,23 @@ def tq_moe_forward(desc: LayerDesc, packed, x, topk_idx, topk_w, y=None, workspa
     _check(lib().tq_moe_forward(ctypes.byref(desc), _ptr(packed), _ptr(x), _ptr(topk_idx), _ptr(topk_w), T, _ptr(y),
                                 _ptr(workspace), workspace.numel(), _stream()), "tq_moe_forward")
     return y
+
+
+def tq_route_moe_forward(desc: LayerDesc, packed, x, logits, bias, topk_idx=None, topk_w=None, y=None, workspace=None):
+    """tq_route + tq_moe_forward in one call; returns (y, topk_idx, topk_w)."""
+    T = x.shape[0]
+    if topk_idx is None:
+        topk_idx = torch.empty((T, desc.top_k), dtype=torch.int32, device=x.device)
+    if topk_w is None:
+        topk_w = torch.empty((T, desc.top_k), dtype=torch.float32, device=x.device)
+    if y is None:
+        y = torch.empty_like(x)
+    if workspace is None:
+        workspace = torch.empty(max(tq_moe_workspace_size(desc, T), 256), dtype=torch.uint8, device=x.device)
+    _check(lib().tq_route_moe_forward(ctypes.byref(desc), _ptr(packed), _ptr(x), _ptr(logits), _ptr(bias), T, _ptr(topk_idx),
+                                      _ptr(topk_w), _ptr(y), _ptr(workspace), workspace.numel(), _stream()),
+           "tq_route_moe_forward")
+    return y, topk_idx, topk_w
 
 
 TQ_STATIC_SCRATCH_MAX = 32 << 20

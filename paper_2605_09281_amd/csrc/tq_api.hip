@@ -171,8 +171,18 @@ __global__ void copy_flag_kernel(const int32_t* __restrict__ ctrl, int32_t* __re
 // shared body of tq_moe_forward and tq_moe_forward_static; use_static: the workspace is this device's scratch array
 tq_status forward_impl(const tq_layer_desc* desc, const void* packed, const void* x, const int32_t* topk_idx,
                        const float* topk_w, int32_t T, void* y, void* workspace, size_t workspace_bytes,
-                       bool use_static, int32_t* err_flag, void* stream);
+                       bool use_static, int32_t* err_flag, void* stream, const TqRouteIn* route = nullptr);
 }  // namespace
+
+extern "C" tq_status tq_route_moe_forward(const tq_layer_desc* desc, const void* packed, const void* x,
+                                          const float* logits, const float* bias, int32_t T, int32_t* topk_idx,
+                                          float* topk_w, void* y, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!workspace || !logits) return TQ_ERR_NULL;
+    if (((uintptr_t)logits | (uintptr_t)bias) & 3) return TQ_ERR_ALIGN;
+    const TqRouteIn route = {logits, bias, topk_idx, topk_w};
+    return forward_impl(desc, packed, x, topk_idx, topk_w, T, y, workspace, workspace_bytes, false, nullptr, stream, &route);
+}
 
 extern "C" tq_status tq_moe_forward(const tq_layer_desc* desc, const void* packed, const void* x,
                                     const int32_t* topk_idx, const float* topk_w, int32_t T, void* y,
@@ -193,7 +203,7 @@ extern "C" tq_status tq_moe_forward_static(const tq_layer_desc* desc, const void
 namespace {
 tq_status forward_impl(const tq_layer_desc* desc, const void* packed, const void* x, const int32_t* topk_idx,
                        const float* topk_w, int32_t T, void* y, void* workspace, size_t workspace_bytes,
-                       bool use_static, int32_t* err_flag, void* stream)
+                       bool use_static, int32_t* err_flag, void* stream, const TqRouteIn* route)
 {
     if (!desc || !packed || !x || !topk_idx || !topk_w || !y) return TQ_ERR_NULL;
     TqLayout L;
@@ -226,6 +236,12 @@ tq_status forward_impl(const tq_layer_desc* desc, const void* packed, const void
         pre.sec = L.gu; pre.fm = L.fm; pre.tpart = (float*)(ws + W.tpart); pre.H = L.H;
         pre.n_slices = (L.H + 255) / 256; pre.na_tiles = L.gu.na_tiles; pre.a_tot = W.a_tot;
     }
+    // routing asked for as well: inside the permutation's launch where that is one wave's work, else by its own kernel
+    if (route && !tqi_route_fusable(T, L.E, L.S, L.k, W.nblk)) {
+        const tq_status rr = tq_route(route->logits, route->bias, T, L.E, L.k, route->idx_out, route->w_out, stream);
+        if (rr != TQ_OK) return rr;
+        route = nullptr;
+    }
     tq_status rc = tqi_launch_permute(topk_idx, topk_w, T, L.E, L.S, L.k, (int32_t*)(ws + W.offsets),
                                       (int32_t*)(ws + W.slot_of), L.k + L.S, (int32_t*)(ws + W.row_src),
                                       (int32_t*)(ws + W.row_token), (float*)(ws + W.row_w),
@@ -234,7 +250,8 @@ tq_status forward_impl(const tq_layer_desc* desc, const void* packed, const void
                                       (int32_t*)(ws + W.sk_cnt), W.sk_cnt_n, st, with_pre ? &pre : nullptr,
                                       // the single-wave permutation of decode batches builds only the 16-row tiling
                                       desc->act_dtype == TQ_ACT_BF16 && tqi_bf16_takes_skinny(L, W, desc->flags)
-                                          ? (1 << 2) : (1 << TQ_N_TILINGS) - 1);
+                                          ? (1 << 2) : (1 << TQ_N_TILINGS) - 1,
+                                      route);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(1, st);
     if (desc->act_dtype == TQ_ACT_FP32)

@@ -326,6 +326,20 @@ struct TqPreByAssign {
     int32_t H, n_slices, na_tiles, a_tot;
 };
 
+// Routing inputs of tq_route_moe_forward: when the single-wave permutation runs (one chunk of assignments) and the
+// routing fits one wave's lanes (tqi_route_fusable), the permutation's launch computes the routing itself and writes
+// topk_idx / topk_w as outputs.
+struct TqRouteIn {
+    const float* logits;     // [T][E]
+    const float* bias;       // [E] or null
+    int32_t* idx_out;        // [T][k]
+    float* w_out;            // [T][k]
+};
+inline bool tqi_route_fusable(int64_t T, int E, int S, int k, int nblk)
+{
+    return nblk == 1 && T >= 1 && T <= 64 && E <= 64 && T * k <= TQ_PERM_CHUNK && (int64_t)S * T <= 4096;
+}
+
 // internal entry points implemented across the translation units (host side)
 tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32_t T, int32_t E, int32_t S,
                              int32_t k, int32_t* offsets, int32_t* slot_of, int32_t slot_stride,
@@ -333,7 +347,8 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
                              int32_t* tile_row0, int32_t rt_max, int32_t* ctrl, int32_t* err_flag,
                              int32_t* hist, int32_t nblk, const void* blob, const TqLayout* L,
                              int32_t* zero_buf, int32_t zero_n, hipStream_t stream,
-                             const TqPreByAssign* pre = nullptr, int tilings = (1 << TQ_N_TILINGS) - 1);
+                             const TqPreByAssign* pre = nullptr, int tilings = (1 << TQ_N_TILINGS) - 1,
+                             const TqRouteIn* route = nullptr);
 // fills W.fac_ws with fp16 fragments (Sigma folded into the left factors) and the placement table (fp8 factors on the
 // tiled kernels)
 tq_status tqi_expand_fp8_factors(const TqLayout& L, const TqWorkspace& W, const uint8_t* blob, uint8_t* ws, hipStream_t stream);

@@ -10,6 +10,50 @@ constexpr int kMaxPerLane = 16;  // E <= 64 * 16
 // One wavefront per token.  Lane l holds the scores of experts l, l+64, l+128, ... (PL of them: the per-lane scans
 // are unrolled to the number of experts a lane can hold, not to the maximum).
 // Each of the k rounds takes the wave-wide maximum under the order (score desc, index asc).
+// One selection round over the scores a wave holds (lane l: experts l, l + 64, ...; `taken` marks the ones already
+// chosen or past E): the wave-wide maximum under the order (score desc, index asc), marked as taken in its lane.
+template <int PL>
+__device__ inline void wave_select_round(const float (&v)[PL], uint32_t& taken, int lane, float& bv, int& be)
+{
+    // best candidate of this lane: ascending index scan with a strict compare keeps the lowest index
+    bv = 0.f;
+    be = 0x7FFFFFFF;
+#pragma unroll
+    for (int i = 0; i < PL; ++i) {
+        if (!((taken >> i) & 1u)) {
+            if (be == 0x7FFFFFFF || v[i] > bv) { bv = v[i]; be = lane + 64 * i; }
+        }
+    }
+    // wave-wide arg-max under (score desc, index asc); lanes with nothing left carry index INT_MAX
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        float ov = __shfl_xor(bv, off);
+        int oe = __shfl_xor(be, off);
+        bool take = (oe != 0x7FFFFFFF) && (be == 0x7FFFFFFF || ov > bv || (ov == bv && oe < be));
+        if (take) { bv = ov; be = oe; }
+    }
+    if ((be & 63) == lane) taken |= 1u << (be >> 6);
+}
+
+template <int PL>
+__device__ inline void wave_load_scores(const float* __restrict__ logits_row, const float* __restrict__ bias, int E, int lane,
+                                        float (&v)[PL], uint32_t& taken)
+{
+    taken = 0;
+#pragma unroll
+    for (int i = 0; i < PL; ++i) {
+        int e = lane + 64 * i;
+        float s = -INFINITY;
+        if (e < E) {
+            s = logits_row[e];
+            if (bias) s = s + bias[e];
+        } else {
+            taken |= 1u << i;
+        }
+        v[i] = s;
+    }
+}
+
 template <int PL>
 __global__ void __launch_bounds__(256) route_kernel(const float* __restrict__ logits,
                                                     const float* __restrict__ bias, int T, int E, int k,
@@ -19,39 +63,13 @@ __global__ void __launch_bounds__(256) route_kernel(const float* __restrict__ lo
     const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (t >= T) return;
     float v[PL];
-    uint32_t taken = 0;
-#pragma unroll
-    for (int i = 0; i < PL; ++i) {
-        int e = lane + 64 * i;
-        float s = -INFINITY;
-        if (e < E) {
-            s = logits[(size_t)t * E + e];
-            if (bias) s = s + bias[e];
-        } else {
-            taken |= 1u << i;
-        }
-        v[i] = s;
-    }
+    uint32_t taken;
+    wave_load_scores<PL>(logits + (size_t)t * E, bias, E, lane, v, taken);
     float first = 0.f, denom = 0.f, my_p = 0.f;
     for (int j = 0; j < k; ++j) {
-        // best candidate of this lane: ascending index scan with a strict compare keeps the lowest index
-        float bv = 0.f;
-        int be = 0x7FFFFFFF;
-#pragma unroll
-        for (int i = 0; i < PL; ++i) {
-            if (!((taken >> i) & 1u)) {
-                if (be == 0x7FFFFFFF || v[i] > bv) { bv = v[i]; be = lane + 64 * i; }
-            }
-        }
-        // wave-wide arg-max under (score desc, index asc); lanes with nothing left carry index INT_MAX
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            float ov = __shfl_xor(bv, off);
-            int oe = __shfl_xor(be, off);
-            bool take = (oe != 0x7FFFFFFF) && (be == 0x7FFFFFFF || ov > bv || (ov == bv && oe < be));
-            if (take) { bv = ov; be = oe; }
-        }
-        if ((be & 63) == lane) taken |= 1u << (be >> 6);
+        float bv;
+        int be;
+        wave_select_round<PL>(v, taken, lane, bv, be);
         if (j == 0) first = bv;
         float p = expf(bv - first);       // the same value in every lane
         denom += p;
@@ -59,6 +77,61 @@ __global__ void __launch_bounds__(256) route_kernel(const float* __restrict__ lo
         if (lane == 0) topk_idx[(size_t)t * k + j] = be;
     }
     if (lane < k) topk_w[(size_t)t * k + lane] = my_p / denom;
+}
+
+// The routing of a decode batch inside the permutation's launch (at most 64 tokens and 64 experts): one LANE per
+// token scans its scores serially, the same order (score desc, index asc) and the same arithmetic as route_kernel,
+// so the results are identical bit for bit.  Scores are staged in LDS (row stride E + 1: conflict-free); the results
+// land in LDS (ridx, rw: [T * k]) for the permutation that follows and in memory for the caller.
+__device__ inline void route_small(const TqRouteIn& R, int T, int E, int k, float* sc, int32_t* ridx, float* rw, int lane)
+{
+    for (int i = lane; i < T * E; i += 64) {
+        const int t = i / E, e = i % E;
+        float s = R.logits[i];
+        if (R.bias) s = s + R.bias[e];
+        sc[t * (E + 1) + e] = s;
+    }
+    __syncthreads();
+    if (lane < T) {
+        uint64_t taken = 0;
+        float first = 0.f, denom = 0.f;
+        const float* row = sc + lane * (E + 1);
+        for (int j = 0; j < k; ++j) {
+            float bv = 0.f;
+            int be = -1;
+            for (int e = 0; e < E; ++e) {
+                const float s = row[e];
+                if (!((taken >> e) & 1ull) && (be < 0 || s > bv)) { bv = s; be = e; }
+            }
+            taken |= 1ull << be;
+            if (j == 0) first = bv;
+            const float p = expf(bv - first);
+            denom += p;
+            ridx[lane * k + j] = be;
+            rw[lane * k + j] = p;
+        }
+        for (int j = 0; j < k; ++j) rw[lane * k + j] = rw[lane * k + j] / denom;
+    }
+    __syncthreads();
+    for (int a = lane; a < T * k; a += 64) {
+        R.idx_out[a] = ridx[a];
+        R.w_out[a] = rw[a];
+    }
+}
+
+// The expert of assignment (t, j) recomputed by one wave from the token's scores (E <= 64): the workgroups that share
+// the permutation's launch cannot wait for its routing results.
+__device__ inline int route_expert_of(const TqRouteIn& R, int t, int j, int E, int lane)
+{
+    float v[1];
+    uint32_t taken;
+    wave_load_scores<1>(R.logits + (size_t)t * E, R.bias, E, lane, v, taken);
+    int be = 0;
+    for (int q = 0; q <= j; ++q) {
+        float bv;
+        wave_select_round<1>(v, taken, lane, bv, be);
+    }
+    return be;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -410,14 +483,18 @@ __device__ inline void permute_small_body(const int32_t* __restrict__ idx, const
 // exact values of x (bf16) and A (fp16, or fp8 with FP8), the two halves of a 16-wide step in the two halves of the wave.
 template <bool FP8>
 __device__ inline void pre_by_assign_block(const TqPreByAssign& P, const int32_t* __restrict__ idx, int T, int E, int k,
-                                           int b, int lane)
+                                           int b, int lane, const TqRouteIn* route = nullptr)
 {
     const int ta = b % P.na_tiles;
     const int slice = (b / P.na_tiles) % P.n_slices;
     const int v = b / (P.na_tiles * P.n_slices);
     if (v >= P.a_tot) return;
     int e, t;
-    if (v < T * k) { e = idx[v]; t = v / k; if (e < 0 || e >= E) return; }      // dropped assignments have no row
+    if (v < T * k) {
+        t = v / k;
+        e = route ? route_expert_of(*route, t, v % k, E, lane) : idx[v];
+        if (e < 0 || e >= E) return;      // dropped assignments have no row
+    }
     else { const int q = v - T * k; e = E + q / T; t = q % T; }
     const int col = lane & 31, hf = lane >> 5;
     const int ksteps = P.H / 16;
@@ -473,7 +550,8 @@ __global__ void __launch_bounds__(64) pre_by_assign_kernel(TqPreByAssign P, cons
 // The whole permutation for a few chunks of assignments in ONE wavefront (one launch instead of five); with
 // PRE != 0 the other workgroups of the launch compute the gate/up low-rank intermediate by assignment (1: fp16
 // factors, 2: fp8 factors).
-template <int PRE>
+// With ROUTE the launch also does the routing (route_small; idx and w are then unused).
+template <int PRE, bool ROUTE>
 __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __restrict__ idx, const float* __restrict__ w,
                                                            int n_assign, int E, int S, int T, int k,
                                                            int32_t* __restrict__ offsets, int32_t* __restrict__ slot_of,
@@ -484,12 +562,22 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
                                                            int32_t* __restrict__ err_flag,
                                                            const TqBlobHeader* __restrict__ hdr, TqBlobHeader expect,
                                                            int check_blob, int32_t* __restrict__ zero_buf, int zero_n,
-                                                           TqPreByAssign P, int tilings)
+                                                           TqPreByAssign P, int tilings, TqRouteIn R, int route_off)
 {
     if (PRE != 0 && blockIdx.x > 0) {
         if (check_blob && !blob_header_ok(hdr, expect)) return;      // a blob of another layer is not indexed
-        pre_by_assign_block<PRE == 2>(P, idx, T, E, k, blockIdx.x - 1, threadIdx.x);
+        pre_by_assign_block<PRE == 2>(P, idx, T, E, k, blockIdx.x - 1, threadIdx.x, ROUTE ? &R : nullptr);
         return;
+    }
+    if (ROUTE) {
+        extern __shared__ int32_t sm_all[];
+        float* sc = reinterpret_cast<float*>(sm_all + route_off);
+        int32_t* ridx = sm_all + route_off + 64 * 65;
+        float* rw = reinterpret_cast<float*>(ridx + TQ_PERM_CHUNK);
+        route_small(R, T, E, k, sc, ridx, rw, threadIdx.x);
+        __syncthreads();
+        idx = ridx;
+        w = rw;
     }
     permute_small_body(idx, w, n_assign, E, S, T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e,
                        tile_row0, rt_max, ctrl, err_flag, hdr, expect, check_blob, zero_buf, zero_n, tilings);
@@ -509,7 +597,8 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
                              int32_t* src_of, int32_t* row_token, float* row_w, int32_t* tile_e,
                              int32_t* tile_row0, int32_t rt_max, int32_t* ctrl, int32_t* err_flag,
                              int32_t* hist, int32_t nblk, const void* blob, const TqLayout* L,
-                             int32_t* zero_buf, int32_t zero_n, hipStream_t stream, const TqPreByAssign* pre, int tilings)
+                             int32_t* zero_buf, int32_t zero_n, hipStream_t stream, const TqPreByAssign* pre, int tilings,
+                             const TqRouteIn* route)
 {
     const int64_t n_assign = (int64_t)T * k;
     const int64_t n_pre = pre ? (int64_t)pre->a_tot * pre->n_slices * pre->na_tiles : 0;
@@ -525,25 +614,28 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
     }
     const int ne = E + S;
     if (nblk == 1 && (int64_t)S * T <= 4096) {
-        const size_t sm = ((size_t)ne + (ne + 1) + E + TQ_N_TILINGS * (ne + 1)) * 4;
-        if (n_pre > 0 && pre->fm.fp8)
-            hipLaunchKernelGGL(permute_small_kernel<2>, dim3(1 + (unsigned)n_pre), dim3(64), sm, stream, topk_idx, topk_w,
-                               (int)n_assign, E, S, T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e,
-                               tile_row0, rt_max, ctrl, err_flag, (const TqBlobHeader*)blob, expect, check, zero_buf,
-                               (int)zero_n, *pre, tilings);
-        else if (n_pre > 0)
-            hipLaunchKernelGGL(permute_small_kernel<1>, dim3(1 + (unsigned)n_pre), dim3(64), sm, stream, topk_idx, topk_w,
-                               (int)n_assign, E, S, T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e,
-                               tile_row0, rt_max, ctrl, err_flag, (const TqBlobHeader*)blob, expect, check, zero_buf,
-                               (int)zero_n, *pre, tilings);
-        else
-            hipLaunchKernelGGL(permute_small_kernel<0>, dim3(1), dim3(64), sm, stream, topk_idx, topk_w, (int)n_assign,
-                               E, S, T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e, tile_row0,
-                               rt_max, ctrl, err_flag, (const TqBlobHeader*)blob, expect, check, zero_buf, (int)zero_n,
-                               TqPreByAssign{}, tilings);
+        const int sm_words = ne + (ne + 1) + E + TQ_N_TILINGS * (ne + 1);
+        const bool fused = route != nullptr;
+        if (fused && !tqi_route_fusable(T, E, S, k, nblk)) return TQ_ERR_UNSUPPORTED;
+        const size_t sm = ((size_t)sm_words + (fused ? 64 * 65 + 2 * TQ_PERM_CHUNK : 0)) * 4;
+        const int pre_kind = n_pre > 0 ? (pre->fm.fp8 ? 2 : 1) : 0;
+        const TqRouteIn R = fused ? *route : TqRouteIn{};
+        const TqPreByAssign P = n_pre > 0 ? *pre : TqPreByAssign{};
+#define TQ_PS(PREV, ROUTEV)                                                                                               \
+        hipLaunchKernelGGL((permute_small_kernel<PREV, ROUTEV>), dim3(1 + (unsigned)n_pre), dim3(64), sm, stream, topk_idx, \
+                           topk_w, (int)n_assign, E, S, T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w,     \
+                           tile_e, tile_row0, rt_max, ctrl, err_flag, (const TqBlobHeader*)blob, expect, check, zero_buf,  \
+                           (int)zero_n, P, tilings, R, sm_words)
+        if (fused) {
+            if (pre_kind == 2) TQ_PS(2, true); else if (pre_kind == 1) TQ_PS(1, true); else TQ_PS(0, true);
+        } else {
+            if (pre_kind == 2) TQ_PS(2, false); else if (pre_kind == 1) TQ_PS(1, false); else TQ_PS(0, false);
+        }
+#undef TQ_PS
         TQ_CHECK_LAUNCH();
         return TQ_OK;
     }
+    if (route) return TQ_ERR_UNSUPPORTED;      // the caller routes by itself when the single-wave permutation does not run
     if (n_pre > 0) {      // the permutation takes several launches: the pre-pass gets its own
         if (pre->fm.fp8)
             hipLaunchKernelGGL(pre_by_assign_kernel<true>, dim3((unsigned)n_pre), dim3(64), 0, stream, *pre, topk_idx, T, E, k,
