@@ -762,15 +762,17 @@ tq_status launch_aug(const MGeom& G, const TqSection& sec, const uint8_t* blob, 
     // fewer column tiles leave registers for more loads in flight; eight steps at a time need units of 128
     const int nat = G.r > 0 ? sec.na_tiles : 0;
     const int gs = G.g / 16;
-    // the staged variant: groups up to 128, at most two column tiles of t, 32-bit byte offsets of the rows
+    // the staged variant: groups up to 128, at most two column tiles of t (four with groups up to 64: the factor
+    // fragments of a group and tile wait in registers), 32-bit byte offsets of the rows
     const uint64_t span = (uint64_t)(STAGE == 0 ? G.a_tot / (G.k + G.S) : G.a_tot) * sec.K * 2;
-    if (gs <= 8 && nat <= 2 && span < (1ull << 32)) {
+    if (gs <= 8 && (nat <= 2 || (nat <= 4 && gs <= 4)) && span < (1ull << 32)) {
 #define TQ_AUGS(NATV, GSV)                                                                                          \
     hipLaunchKernelGGL((aug_staged_kernel<STAGE, NATV, GSV>), dim3(rt32), dim3(256),                            \
                        std::max<size_t>((size_t)32 * (4 * GSV * 32 + 16), 4 * 16 * 64 * sizeof(float)) /* staging | reduction */, \
                        st, G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, xaug, ka)
         if (nat <= 1) { if (gs == 8) TQ_AUGS(1, 8); else if (gs == 4) TQ_AUGS(1, 4); else TQ_AUGS(1, 2); }
-        else { if (gs == 8) TQ_AUGS(2, 8); else if (gs == 4) TQ_AUGS(2, 4); else TQ_AUGS(2, 2); }
+        else if (nat == 2) { if (gs == 8) TQ_AUGS(2, 8); else if (gs == 4) TQ_AUGS(2, 4); else TQ_AUGS(2, 2); }
+        else { if (gs == 4) TQ_AUGS(4, 4); else TQ_AUGS(4, 2); }
 #undef TQ_AUGS
         TQ_CHECK_LAUNCH();
         return TQ_OK;

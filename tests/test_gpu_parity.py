@@ -31,6 +31,8 @@ SMALL = {
     "ragged": small_cfg(205, E=16, k=4, H=256, F=320, T=150, g=64, r=32),   # rows/expert ~37: several 32-row tiles
     "one_token": small_cfg(206, T=1, E=8, k=2),
     "g128_r64": small_cfg(207, H=256, F=384, g=128, r=64, E=5, k=5, T=40),
+    "g64_r64": small_cfg(208, H=256, F=192, g=64, r=64, E=6, k=3, T=90),       # four column tiles of t in the gate/up pre-pass
+    "g32_r40": small_cfg(209, H=192, F=256, g=32, r=40, E=4, k=2, T=70),       # three (r16 = 48), groups of 32
 }
 
 _cache = {}
