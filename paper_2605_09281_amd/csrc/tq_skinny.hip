@@ -11,7 +11,8 @@
 //     group sums of the activations computed once per workgroup by an MFMA against a matrix of ones.
 //   * The 8 partial results of a pair are summed across the waves through LDS in a fixed order (the
 //     "wavefront reduction"), then SwiGLU (stage 0) or the store of the split-K plane (stage 1).
-//   * The low-rank intermediate t = x A is produced per 512-wide slice by skinny_pre_kernel; a workgroup
+//   * The low-rank intermediate t = x A is produced per 256-wide slice by skinny_pre_kernel (for decode batches
+//     proper the gate/up slices come per assignment from the permutation's launch instead); a workgroup
 //     adds the slices of its own range, so a split contraction needs no global reduction: the partial
 //     t of a split times B lands in that split's output plane, and the planes are summed by the combine.
 #include "tq_device.h"
