@@ -10,6 +10,7 @@ from oracle import pack_ref
 from synth import CONFIGS, LayerConfig, make_layer, make_layer_fp8, make_shared_layer, make_x, make_logits, fp8_e4m3_encode
 import paper_2605_09281_amd.binding as tq
 from gpu_util import DEV, dev16, x_device, rel_err
+import variants
 
 pytestmark = pytest.mark.gpu
 
@@ -185,4 +186,33 @@ def test_fp8_decode_full_shape():
     got, ref = forward(fl, x, logits, bias, tq.TQ_ACT_BF16)
     e = rel_err(got, ref)
     print(f"fp8 config 2: rel err {e:.3e}", flush=True)
+    assert e <= REG_BF16
+
+
+def test_fp8_prefill_full_shape():
+    """Benchmark config 3 (66-expert prefill, 4096 tokens) with fp8 factors on the persistent tiled kernels, which read
+    the fp16 fragments expanded into the workspace; sampled by slot (segment edges of every expert) plus random tokens."""
+    cfg = CONFIGS[3].replace(cfg_id=961)
+    print("fp8 config 3: generating", flush=True)
+    fl = make_layer_fp8(cfg, workers=16)
+    x = make_x(cfg)
+    logits, bias = make_logits(cfg)
+    packed = pack_gpu(fl)
+    desc = desc_fp8(cfg)
+    lg = torch.from_numpy(logits).to(DEV)
+    bs = None if bias is None else torch.from_numpy(bias).to(DEV)
+    ws = torch.empty(tq.tq_moe_workspace_size(desc, cfg.T), dtype=torch.uint8, device=DEV)
+    print("fp8 config 3: forward", flush=True)
+    y, idx, w = tq.tq_route_moe_forward(desc, packed, x_device(x, tq.TQ_ACT_BF16), lg, bs, workspace=ws)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32).item()) == 0
+    ridx = idx.cpu().numpy()
+    assert np.array_equal(ridx, oracle.route(logits, bias, cfg.k)[0])
+    rng = np.random.default_rng(961)
+    tok = np.unique(np.concatenate([rng.choice(cfg.T, size=16, replace=False), variants.segment_edge_tokens(ridx, cfg.E)])).astype(np.int32)
+    print(f"fp8 config 3: oracle on {tok.size} tokens", flush=True)
+    ref = oracle.moe_forward_fp8(cfg, fl.codes, fl.scale, fl.zero, fl.a8_list(), fl.b8_list(), fl.sigma, x, ridx, w.cpu().numpy(),
+                                 tokens=tok)
+    e = rel_err(y.float().cpu().numpy()[tok], ref)
+    print(f"fp8 config 3: rel err {e:.3e} on {tok.size} tokens", flush=True)
     assert e <= REG_BF16
