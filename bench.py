@@ -244,6 +244,9 @@ def main():
     ap.add_argument("--dense-bits", type=int, default=0, choices=[0, 2, 3],
                     help="with --workload: re-quantise the layer's weights to 2 or 3 bits and store the codes densely "
                          "(decode workloads only)")
+    ap.add_argument("--rank", type=int, default=None,
+                    help="with --workload: override the rank of the low-rank factors (0 = quantised weights alone), for the "
+                         "overhead of the low-rank path over the quantised forward")
     ap.add_argument("--fp8-factors", action="store_true",
                     help="with --workload: store the low-rank factors as fp8 E4M3 codes with an fp16 diagonal Sigma")
     ap.add_argument("--separate-route", action="store_true",
@@ -362,6 +365,8 @@ def main():
         wl = CONFIGS[args.workload]
         if args.dense_bits:
             wl = wl.replace(bits=args.dense_bits, dense=True)
+        if args.rank is not None:
+            wl = wl.replace(r=args.rank)
         res = bench_layer(args, wl, dev, oracle_macs=1.5e11, fp8=args.fp8_factors)
         print(json.dumps(headline(args, res, None)), flush=True)
         return

@@ -234,16 +234,20 @@ __global__ void __launch_bounds__(256, NAT == 1 ? 3 : 2) aug_staged_kernel(MGeom
         // The factor fragments of this chunk are requested BEFORE the next chunk's rows: loads return in order, and
         // behind the gathered rows (memory-side cache or HBM) these L2 hits would wait for them.  Unconditional
         // with a clamped group, so that the compiler can count them.
-        u32x4 aq[GS][NAT];
-        {
-            const int gic = min(gi, groups - 1);
+        // (four column tiles at groups of 128 are 128 registers of fragments: they come in two halves, the second one
+        // requested after the first one's MFMAs)
+        constexpr int NJ = (NAT * GS > 16) ? NAT / 2 : NAT;
+        u32x4 aq[GS][NJ];
+        const int gic = min(gi, groups - 1);
+        auto load_aq = [&](int j0) {
 #pragma unroll
             for (int ks = 0; ks < GS; ++ks)
 #pragma unroll
-                for (int j = 0; j < NAT; ++j)
-                    aq[ks][j] = af[((size_t)min(j, max(na_tiles, 1) - 1) * ksteps + gic * GS + ks) * 64 * af_live];
-        }
-        load_chunk(min(c + 1, nchunks - 1));
+                for (int j = 0; j < NJ; ++j)
+                    aq[ks][j] = af[((size_t)min(j0 + j, max(na_tiles, 1) - 1) * ksteps + gic * GS + ks) * 64 * af_live];
+        };
+        load_aq(0);
+        if constexpr (NJ == NAT) load_chunk(min(c + 1, nchunks - 1));
         // every wave copies its group's fragments out of the one LDS buffer (clamped for a group past the end),
         // then the buffer is free for the next chunk
         Frag xa[GS];
@@ -270,10 +274,17 @@ __global__ void __launch_bounds__(256, NAT == 1 ? 3 : 2) aug_staged_kernel(MGeom
             // the block (a test per MFMA turns into a copy of the accumulator per MFMA)
             if (na_tiles > 0) {
 #pragma unroll
-                for (int ks = 0; ks < GS; ++ks)
+                for (int j0 = 0; j0 < NAT; j0 += NJ) {
+                    if (j0 > 0) load_aq(j0);
+                    // two halves: the next chunk's rows are requested behind the second half's fragments (in front
+                    // of them they would hold those L2 hits back until the rows have arrived)
+                    if (NJ != NAT && j0 + NJ >= NAT) load_chunk(min(c + 1, nchunks - 1));
 #pragma unroll
-                    for (int j = 0; j < NAT; ++j)
-                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[ks].v, half8_to_bf8(aq[ks][j]), acc[j], 0, 0, 0);
+                    for (int ks = 0; ks < GS; ++ks)
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j)
+                            acc[j0 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[ks].v, half8_to_bf8(aq[ks][j]), acc[j0 + j], 0, 0, 0);
+                }
             }
         }
         store_chunk();
@@ -762,17 +773,16 @@ tq_status launch_aug(const MGeom& G, const TqSection& sec, const uint8_t* blob, 
     // fewer column tiles leave registers for more loads in flight; eight steps at a time need units of 128
     const int nat = G.r > 0 ? sec.na_tiles : 0;
     const int gs = G.g / 16;
-    // the staged variant: groups up to 128, at most two column tiles of t (four with groups up to 64: the factor
-    // fragments of a group and tile wait in registers), 32-bit byte offsets of the rows
+    // the staged variant: groups up to 128, at most four column tiles of t, 32-bit byte offsets of the rows
     const uint64_t span = (uint64_t)(STAGE == 0 ? G.a_tot / (G.k + G.S) : G.a_tot) * sec.K * 2;
-    if (gs <= 8 && (nat <= 2 || (nat <= 4 && gs <= 4)) && span < (1ull << 32)) {
+    if (gs <= 8 && nat <= 4 && span < (1ull << 32)) {
 #define TQ_AUGS(NATV, GSV)                                                                                          \
     hipLaunchKernelGGL((aug_staged_kernel<STAGE, NATV, GSV>), dim3(rt32), dim3(256),                            \
                        std::max<size_t>((size_t)32 * (4 * GSV * 32 + 16), 4 * 16 * 64 * sizeof(float)) /* staging | reduction */, \
                        st, G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, xaug, ka)
         if (nat <= 1) { if (gs == 8) TQ_AUGS(1, 8); else if (gs == 4) TQ_AUGS(1, 4); else TQ_AUGS(1, 2); }
         else if (nat == 2) { if (gs == 8) TQ_AUGS(2, 8); else if (gs == 4) TQ_AUGS(2, 4); else TQ_AUGS(2, 2); }
-        else { if (gs == 4) TQ_AUGS(4, 4); else TQ_AUGS(4, 2); }
+        else { if (gs == 8) TQ_AUGS(4, 8); else if (gs == 4) TQ_AUGS(4, 4); else TQ_AUGS(4, 2); }
 #undef TQ_AUGS
         TQ_CHECK_LAUNCH();
         return TQ_OK;
