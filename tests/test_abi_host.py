@@ -260,3 +260,12 @@ def test_lotile_place_matches_oracle_and_its_invariants():
     # fewer cells than experts is refused
     with pytest.raises(tq.TqError):
         tq.tq_lotile_place(np.zeros((5, 2), dtype=np.int32), 2, 2)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark is a one-GPU measurement: asked for more it says so and exits with an error, before touching a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
