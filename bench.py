@@ -560,10 +560,10 @@ def bench_layer(args, cfg, dev, oracle_macs, fp8=False):
     roofline["gate_up_mfma_frac"] = round(work["gate_up_flops"] / t_gu / MFMA_BF16_PEAK, 4)
     roofline["gate_up_hbm_frac"] = round(work["gate_up_bytes"] / t_gu / HBM_PEAK, 4)
     roofline["stage_us"] = {k: round(v, 2) for k, v in stage_us.items()}
-    roofline["stage_note"] = ("intervals between HIP events recorded at the library's stage boundaries in an eager pass; each "
-                              "carries about 4-5 us of event overhead (a stage in which nothing is launched, e.g. aug_gate_up "
-                              "of a decode batch whose pre-pass rides in the permutation's launch, still reads ~5 us); "
-                              "ms_per_step is timed separately over the replayed HIP graph and has no such gaps")
+    roofline["stage_note"] = ("intervals between HIP events recorded at the library's stage boundaries in an eager pass; an "
+                              "interval in which nothing is launched (aug_gate_up of a decode batch, whose pre-pass rides in the "
+                              "permutation's launch) still reads ~5 us of event processing; ms_per_step is timed separately "
+                              "over the replayed HIP graph")
 
     # the oracle beside it: a bounded token sample of the same workload, timed on this machine's host cores
     cpu_baseline = None
