@@ -32,7 +32,8 @@
  *     A      fp16   [E+S][(2H+F)*r]   gate [H,r] | up [H,r] | down [F,r]
  *     B      fp16   [E+S][(2F+H)*r]   gate [r,F] | up [r,F] | down [r,H]
  *
- * Packed blob (what tq_pack_weights writes, version 1).  256-byte header, then one record per expert
+ * Packed blob (what tq_pack_weights writes; the header carries a format version that tq_moe_forward checks on the
+ * device together with the geometry).  256-byte header, then one record per expert
  * at  256 + e * expert_stride.  A record holds two sections, GU (gate and up interleaved; N2 = 2F
  * columns, K = H) and D (down; N2 = H columns, K = F), each made of five 256-byte aligned parts.
  * Columns are taken in tiles of 32 and tiles in pairs: in GU pair j = (gate rows 32j..32j+31,
