@@ -4,9 +4,10 @@
  * The operation (TileQ, arXiv 2605.09281): an MoE layer  MoE(X) = sum_{k in topK} G_k(X) * W_k(X)
  * (Eq. 3) whose expert weights are stored as "quantised residual + rank-r term",
  * W ~ Q(W - W_r) + U V (Eq. 2, Eq. 4), evaluated at inference as the quantised forward plus the
- * low-rank forward (Eq. 14).  The factors taken here are the effective per-expert ones of Eq. 4 /
- * Algorithm 1: A_e = diag(s_e)^-1 U_{m(e)} Sigma  ([in, r]) and B_e = V_{n(e)} ([r, out]); the
- * input-side scaling, Sigma and the position table are folded offline and never reach this API.
+ * low-rank forward (Eq. 14).  The factors tq_pack_weights takes are the effective per-expert ones of Eq. 4 /
+ * Algorithm 1: A_e = diag(s_e)^-1 U_{m(e)} Sigma  ([in, r]) and B_e = V_{n(e)} ([r, out]), with the
+ * input-side scaling, Sigma and the position table folded offline; tq_pack_weights_shared takes the shared
+ * factors U_m Sigma, V_n and the position table of Eq. 4 themselves, and TQ_FLAG_FP8_FACTORS keeps Sigma apart.
  * Each expert is a SwiGLU MLP (gate, up, down); each of the three projections is
  *     proj(v)[n] = sum_kk v[kk] * (q[n,kk] - zero[n,kk/g]) * scale[n,kk/g]
  *                + sum_rho ( sum_kk v[kk] * A[kk,rho] ) * B[rho,n]
