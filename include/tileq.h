@@ -250,7 +250,7 @@ tq_status tq_moe_forward(const tq_layer_desc *desc, const void *packed, const vo
 /* tq_route followed by tq_moe_forward in one call, with the same results bit for bit (Eq. 3: the top-K set, the
  * routing weights and the weighted sum over the selected experts): logits fp32 [T,E] and bias fp32 [E] or NULL as
  * for tq_route; topk_idx int32 [T,k] and topk_w fp32 [T,k] are OUTPUTS here (device, 16-byte aligned), everything else
- * as for tq_moe_forward.  For decode batches (at most 64 tokens, at most 64 routed experts, at most 256 assignments)
+ * as for tq_moe_forward.  For decode batches (at most 64 tokens, at most 16 routed experts, at most 256 assignments)
  * the routing runs inside the permutation's launch, which saves one kernel launch per step; other batches run the
  * two steps one after the other. */
 tq_status tq_route_moe_forward(const tq_layer_desc *desc, const void *packed, const void *x, const float *logits,

@@ -327,7 +327,7 @@ struct TqPreByAssign {
 };
 
 // Routing inputs of tq_route_moe_forward: when the single-wave permutation runs (one chunk of assignments) and the
-// routing fits one wave's lanes (tqi_route_fusable), the permutation's launch computes the routing itself and writes
+// routing is a few scores per token (tqi_route_fusable), the permutation's launch computes the routing itself and writes
 // topk_idx / topk_w as outputs.
 struct TqRouteIn {
     const float* logits;     // [T][E]
@@ -337,7 +337,8 @@ struct TqRouteIn {
 };
 inline bool tqi_route_fusable(int64_t T, int E, int S, int k, int nblk)
 {
-    return nblk == 1 && T >= 1 && T <= 64 && E <= 64 && T * k <= TQ_PERM_CHUNK && (int64_t)S * T <= 4096;
+    // (one lane scans a token's E scores k times: beyond a few experts the routing kernel, a wave per token, is faster)
+    return nblk == 1 && T >= 1 && T <= 64 && E <= 16 && T * k <= TQ_PERM_CHUNK && (int64_t)S * T <= 4096;
 }
 
 // internal entry points implemented across the translation units (host side)

@@ -79,17 +79,32 @@ __global__ void __launch_bounds__(256) route_kernel(const float* __restrict__ lo
     if (lane < k) topk_w[(size_t)t * k + lane] = my_p / denom;
 }
 
-// The routing of a decode batch inside the permutation's launch (at most 64 tokens and 64 experts): one LANE per
+// The routing of a decode batch inside the permutation's launch (at most 64 tokens and 16 experts): one LANE per
 // token scans its scores serially, the same order (score desc, index asc) and the same arithmetic as route_kernel,
 // so the results are identical bit for bit.  Scores are staged in LDS (row stride E + 1: conflict-free); the results
 // land in LDS (ridx, rw: [T * k]) for the permutation that follows and in memory for the caller.
 __device__ inline void route_small(const TqRouteIn& R, int T, int E, int k, float* sc, int32_t* ridx, float* rw, int lane)
 {
-    for (int i = lane; i < T * E; i += 64) {
-        const int t = i / E, e = i % E;
-        float s = R.logits[i];
-        if (R.bias) s = s + R.bias[e];
-        sc[t * (E + 1) + e] = s;
+    // at most 64 x 16 scores: all of a lane's loads are in flight at once
+    {
+        constexpr int NL = 16;
+        float lv[NL], bv[NL];
+        const int n = T * E;
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+            const int i = min(u * 64 + lane, n - 1);
+            lv[u] = R.logits[i];
+            bv[u] = R.bias ? R.bias[i % E] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+            const int i = u * 64 + lane;
+            if (i < n) {
+                float s = lv[u];
+                if (R.bias) s = s + bv[u];
+                sc[(i / E) * (E + 1) + i % E] = s;
+            }
+        }
     }
     __syncthreads();
     if (lane < T) {
@@ -572,7 +587,7 @@ __global__ void __launch_bounds__(64) permute_small_kernel(const int32_t* __rest
     if (ROUTE) {
         extern __shared__ int32_t sm_all[];
         float* sc = reinterpret_cast<float*>(sm_all + route_off);
-        int32_t* ridx = sm_all + route_off + 64 * 65;
+        int32_t* ridx = sm_all + route_off + 64 * 17;
         float* rw = reinterpret_cast<float*>(ridx + TQ_PERM_CHUNK);
         route_small(R, T, E, k, sc, ridx, rw, threadIdx.x);
         __syncthreads();
@@ -617,7 +632,7 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
         const int sm_words = ne + (ne + 1) + E + TQ_N_TILINGS * (ne + 1);
         const bool fused = route != nullptr;
         if (fused && !tqi_route_fusable(T, E, S, k, nblk)) return TQ_ERR_UNSUPPORTED;
-        const size_t sm = ((size_t)sm_words + (fused ? 64 * 65 + 2 * TQ_PERM_CHUNK : 0)) * 4;
+        const size_t sm = ((size_t)sm_words + (fused ? 64 * 17 + 2 * TQ_PERM_CHUNK : 0)) * 4;
         const int pre_kind = n_pre > 0 ? (pre->fm.fp8 ? 2 : 1) : 0;
         const TqRouteIn R = fused ? *route : TqRouteIn{};
         const TqPreByAssign P = n_pre > 0 ? *pre : TqPreByAssign{};
