@@ -822,8 +822,11 @@ tq_status tqi_setup_mfma()
 // decode batches (a handful of rows per expert) take the weight-streaming 16-row path when the layer allows it.
 static bool bf16_large_tiles(const TqLayout& L, const TqWorkspace& W, int flags)
 {
+    // measured crossover of the two tilings (three layer shapes, batches swept across it): at 24 rows per expert the
+    // 32-row kernel is equal or up to 15 % ahead; layers of 60 and more experts gain 13 % from the large tiles at 28
+    // rows and up to 28 % at 48, a layer of 8 wide experts changes over between 28 (32-row kernel 16 % ahead) and 32
     const int64_t avg_rows = (int64_t)W.a_tot / (L.E + L.S);
-    bool large = avg_rows > 48;
+    bool large = avg_rows >= (L.E + L.S <= 16 ? 32 : 28);
     if (flags & TQ_FLAG_FORCE_SMALL_TILE) large = false;
     if (flags & TQ_FLAG_FORCE_LARGE_TILE) large = true;
     return large;
