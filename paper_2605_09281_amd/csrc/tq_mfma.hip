@@ -834,8 +834,17 @@ static bool bf16_large_tiles(const TqLayout& L, const TqWorkspace& W, int flags)
 
 bool tqi_bf16_takes_skinny(const TqLayout& L, const TqWorkspace& W, int flags)
 {
+    // The decode kernels pay where a few large experts hold a handful of rows each: measured against the 32-row
+    // kernel they are 20-35 % ahead up to 8 rows per expert on layers of 8 to 32 experts and fall behind at 12 (an
+    // expert with more than 16 rows streams its weights once per 16-row tile: 190 against 173 us, 224 against 172 us);
+    // on layers of 60 and more experts they are level at best and up to 68 % behind (128 experts, 16 tokens: 277
+    // against 165 us - their grid is sized on the host for the experts that MAY receive rows, and with many small
+    // experts a good part of them receive none).  With 8 experts they stay ahead up to 12 rows (179 against 282 us)
+    // and are level at 16.
     const int64_t avg_rows = (int64_t)W.a_tot / (L.E + L.S);
-    bool skinny = !bf16_large_tiles(L, W, flags) && avg_rows <= 12 && !(flags & TQ_FLAG_FORCE_SMALL_TILE);
+    const int ne = L.E + L.S;
+    bool skinny = !bf16_large_tiles(L, W, flags) && avg_rows <= (ne <= 8 ? 14 : 10) && ne <= 32 &&
+                  !(flags & TQ_FLAG_FORCE_SMALL_TILE);
     // dense codes and fp8 factors stay on the decode kernels as long as the batch fits them, unless a tile path is forced
     // (the tiled kernels need parts derived into the workspace first)
     if ((flags & TQ_FLAG_FORCE_SKINNY) || ((L.cw != 4 || L.fm.fp8) && !(flags & (TQ_FLAG_FORCE_SMALL_TILE | TQ_FLAG_FORCE_LARGE_TILE)))) skinny = true;
