@@ -105,10 +105,10 @@ enum {
     /* Not a test hook but part of the format: codes of `bits` = 2 or 3 bits stored densely (the bit-widths of
        Table 1; Appendix A.3 with d = 2 or 3) instead of in 4-bit slots.  Groups of 64 and more.  The blob then
        has no zc part and its size is the storage count of Appendix A.3 plus padding.  Kernels: the decode path
-       (bf16 activations, at most 1024 assignment rows), the tiled bf16 kernels for larger batches (groups of 64
+       (bf16 activations, a few rows per expert), the tiled bf16 kernels for every other batch (groups of 64
        and 128; the zero-point coefficient fragments the blob does not store are derived into the workspace on
-       every call, which tq_moe_workspace_size accounts for) and the fp32 debug path; what none of them covers
-       (groups of 256 with bf16 activations) returns TQ_ERR_UNSUPPORTED before any launch. */
+       every such call, which tq_moe_workspace_size accounts for) and the fp32 debug path; what none of them covers
+       (groups of 256 with bf16 activations beyond the decode path) returns TQ_ERR_UNSUPPORTED before any launch. */
     TQ_FLAG_DENSE_CODES = 32,
     /* Part of the format as well: the low-rank factors stored as fp8 E4M3 codes with an fp16 diagonal Sigma per
        rank component (mixed-precision factor storage, end of Section 3.1; Appendix A.3 with d_low = 8).  The

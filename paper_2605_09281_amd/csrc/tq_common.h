@@ -181,6 +181,10 @@ __host__ __device__ inline int tq_aug_len(int K, int g, int n_lr)
     return (tq_zero_terms(K, g) + n_lr + unit - 1) / unit * unit;
 }
 
+struct TqLayout;
+bool tqi_bf16_rows_take_skinny(const TqLayout& L, int64_t a_tot, int flags);      // the path rule (tq_mfma.hip)
+bool tqi_skinny_supported(const TqLayout& L);
+
 __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t T, TqWorkspace* W)
 {
     size_t off = 0;
@@ -215,8 +219,8 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
             const size_t nat = (size_t)(2 * L.r16 + 31) / 32;
             W->tpart = take((size_t)(a_tot / 16 + L.E + L.S) * slices * nat * 512 * 4);
         }
-        // dense codes / fp8 factors beyond the decode path (more rows than it takes, or a tile path forced)
-        const bool tiled = a_tot > TQ_SKINNY_MAX_ROWS || (L.flags & (TQ_FLAG_FORCE_SMALL_TILE | TQ_FLAG_FORCE_LARGE_TILE));
+        // dense codes / fp8 factors on the tiled kernels (every batch the decode kernels do not take)
+        const bool tiled = !tqi_bf16_rows_take_skinny(L, a_tot, L.flags);
         W->zc_ws = off; W->zc_stride = 0; W->zc_d_off = 0;
         if (L.cw != 4 && tiled) {
             W->zc_d_off = (size_t)L.gu.pairs * L.gu.zfrag * 2048;

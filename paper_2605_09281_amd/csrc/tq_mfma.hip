@@ -820,19 +820,23 @@ tq_status tqi_setup_mfma()
 
 // Tile choice of the bf16 forward: rows per expert on average decide between the 32-row tile and the large tiles;
 // decode batches (a handful of rows per expert) take the weight-streaming 16-row path when the layer allows it.
-static bool bf16_large_tiles(const TqLayout& L, const TqWorkspace& W, int flags)
+static bool bf16_large_tiles_rows(const TqLayout& L, int64_t a_tot, int flags);
+static bool bf16_large_tiles(const TqLayout& L, const TqWorkspace& W, int flags) { return bf16_large_tiles_rows(L, W.a_tot, flags); }
+static bool bf16_large_tiles_rows(const TqLayout& L, int64_t a_tot, int flags)
 {
     // measured crossover of the two tilings (three layer shapes, batches swept across it): at 24 rows per expert the
     // 32-row kernel is equal or up to 15 % ahead; layers of 60 and more experts gain 13 % from the large tiles at 28
     // rows and up to 28 % at 48, a layer of 8 wide experts changes over between 28 (32-row kernel 16 % ahead) and 32
-    const int64_t avg_rows = (int64_t)W.a_tot / (L.E + L.S);
+    const int64_t avg_rows = a_tot / (L.E + L.S);
     bool large = avg_rows >= (L.E + L.S <= 16 ? 32 : 28);
     if (flags & TQ_FLAG_FORCE_SMALL_TILE) large = false;
     if (flags & TQ_FLAG_FORCE_LARGE_TILE) large = true;
     return large;
 }
 
-bool tqi_bf16_takes_skinny(const TqLayout& L, const TqWorkspace& W, int flags)
+bool tqi_bf16_takes_skinny(const TqLayout& L, const TqWorkspace& W, int flags) { return tqi_bf16_rows_take_skinny(L, W.a_tot, flags); }
+
+bool tqi_bf16_rows_take_skinny(const TqLayout& L, int64_t a_tot, int flags)
 {
     // The decode kernels pay where a few large experts hold a handful of rows each: measured against the 32-row
     // kernel they are 20-35 % ahead up to 8 rows per expert on layers of 8 to 32 experts and fall behind at 12 (an
@@ -841,14 +845,14 @@ bool tqi_bf16_takes_skinny(const TqLayout& L, const TqWorkspace& W, int flags)
     // against 165 us - their grid is sized on the host for the experts that MAY receive rows, and with many small
     // experts a good part of them receive none).  With 8 experts they stay ahead up to 12 rows (179 against 282 us)
     // and are level at 16.
-    const int64_t avg_rows = (int64_t)W.a_tot / (L.E + L.S);
+    const int64_t avg_rows = a_tot / (L.E + L.S);
     const int ne = L.E + L.S;
-    bool skinny = !bf16_large_tiles(L, W, flags) && avg_rows <= (ne <= 8 ? 14 : 10) && ne <= 32 &&
+    bool skinny = !bf16_large_tiles_rows(L, a_tot, flags) && avg_rows <= (ne <= 8 ? 14 : 10) && ne <= 32 &&
                   !(flags & TQ_FLAG_FORCE_SMALL_TILE);
-    // dense codes and fp8 factors stay on the decode kernels as long as the batch fits them, unless a tile path is forced
-    // (the tiled kernels need parts derived into the workspace first)
-    if ((flags & TQ_FLAG_FORCE_SKINNY) || ((L.cw != 4 || L.fm.fp8) && !(flags & (TQ_FLAG_FORCE_SMALL_TILE | TQ_FLAG_FORCE_LARGE_TILE)))) skinny = true;
-    return skinny && W.a_tot <= TQ_SKINNY_MAX_ROWS && tqi_skinny_supported(L);
+    if (flags & TQ_FLAG_FORCE_SKINNY) skinny = true;
+    // (dense codes and fp8 factors follow the same rule: the parts the tiled kernels derive per call are laid out in
+    // the workspace exactly when this returns false)
+    return skinny && a_tot <= TQ_SKINNY_MAX_ROWS && tqi_skinny_supported(L);
 }
 
 tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, const uint8_t* blob,

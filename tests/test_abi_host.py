@@ -138,7 +138,9 @@ def test_workspace_size_never_shrinks_as_tokens_grow(E, S, k, H, F, g, r):
         dsizes = [tq.tq_moe_workspace_size(dd, T) for T in marks]
         assert all(b >= a > 0 for a, b in zip(dsizes, dsizes[1:])), list(zip(marks, dsizes))
         zc = (E + S) * 2048 * (2 * -(-(H // g) // 16) * (F // 32) + 2 * -(-(F // g) // 16) * (H // 64))
-        assert tq.tq_moe_workspace_size(dd, 1024 // per) == tq.tq_moe_workspace_size(d, 1024 // per)     # decode batches: nothing extra
+        # batches the decode kernels take (a few rows per expert on layers of at most 32 experts) need nothing extra
+        extra_small = tq.tq_moe_workspace_size(dd, 2) - tq.tq_moe_workspace_size(d, 2)
+        assert extra_small == (0 if E + S <= 32 else zc)
         assert tq.tq_moe_workspace_size(dd, 20000) == tq.tq_moe_workspace_size(d, 20000) + zc
 
 
