@@ -108,7 +108,7 @@ enum {
        (bf16 activations, a few rows per expert), the tiled bf16 kernels for every other batch (groups of 64
        and 128; the zero-point coefficient fragments the blob does not store are derived into the workspace on
        every such call, which tq_moe_workspace_size accounts for) and the fp32 debug path; what none of them covers
-       (groups of 256 with bf16 activations beyond the decode path) returns TQ_ERR_UNSUPPORTED before any launch. */
+       (groups of 256 with bf16 activations) returns TQ_ERR_UNSUPPORTED before any launch. */
     TQ_FLAG_DENSE_CODES = 32,
     /* Part of the format as well: the low-rank factors stored as fp8 E4M3 codes with an fp16 diagonal Sigma per
        rank component (mixed-precision factor storage, end of Section 3.1; Appendix A.3 with d_low = 8).  The
