@@ -824,11 +824,12 @@ static bool bf16_large_tiles_rows(const TqLayout& L, int64_t a_tot, int flags);
 static bool bf16_large_tiles(const TqLayout& L, const TqWorkspace& W, int flags) { return bf16_large_tiles_rows(L, W.a_tot, flags); }
 static bool bf16_large_tiles_rows(const TqLayout& L, int64_t a_tot, int flags)
 {
-    // measured crossover of the two tilings (three layer shapes, batches swept across it): at 24 rows per expert the
-    // 32-row kernel is equal or up to 15 % ahead; layers of 60 and more experts gain 13 % from the large tiles at 28
-    // rows and up to 28 % at 48, a layer of 8 wide experts changes over between 28 (32-row kernel 16 % ahead) and 32
+    // measured crossover of the two tilings (four layer shapes, batches swept across it): on layers of 60 to 128
+    // experts the large tiles are level with the 32-row kernel at 16 rows per expert or up to 7 % ahead, 15 % ahead at
+    // 24 rows (128 experts) and up to 28 % at 48; a layer of 8 wide experts changes over between 28 rows (32-row
+    // kernel 16 % ahead) and 32
     const int64_t avg_rows = a_tot / (L.E + L.S);
-    bool large = avg_rows >= (L.E + L.S <= 16 ? 32 : 28);
+    bool large = avg_rows >= (L.E + L.S <= 16 ? 32 : 16);
     if (flags & TQ_FLAG_FORCE_SMALL_TILE) large = false;
     if (flags & TQ_FLAG_FORCE_LARGE_TILE) large = true;
     return large;
