@@ -829,7 +829,7 @@ static bool bf16_large_tiles_rows(const TqLayout& L, int64_t a_tot, int flags)
     // 24 rows (128 experts) and up to 28 % at 48; a layer of 8 wide experts changes over between 28 rows (32-row
     // kernel 16 % ahead) and 32
     const int64_t avg_rows = a_tot / (L.E + L.S);
-    bool large = avg_rows >= (L.E + L.S <= 16 ? 32 : 16);
+    bool large = avg_rows >= (L.E + L.S <= 16 ? 32 : 12);      // (12 to 16 rows: level to 10 % ahead on the three shapes)
     if (flags & TQ_FLAG_FORCE_SMALL_TILE) large = false;
     if (flags & TQ_FLAG_FORCE_LARGE_TILE) large = true;
     return large;
