@@ -145,15 +145,16 @@ extern "C" size_t tq_moe_workspace_size(const tq_layer_desc* desc, int32_t T)
     TqLayout L;
     if (!tq_make_layout(desc, &L) || T < 0) return 0;
     if ((int64_t)T * (L.k + L.S) > 0x3FFFFFFF) return 0;
-    // The carve-up is not monotonic in T by itself (small batches keep split-K planes and decode scratch that large
-    // ones drop), and a workspace sized for T must serve every smaller batch: take the maximum over T and the
+    // The carve-up is not monotonic in T by itself (small batches keep split-K planes, decode scratch and pre-pass
+    // slices that large ones drop), and a workspace sized for T must serve every smaller batch: take the maximum over T and the
     // largest batches below it that still qualify for those extras.
     TqWorkspace W;
     tq_make_workspace(L, desc->act_dtype, T, &W);
     size_t need = W.total;
     const int32_t per_tok = L.k + L.S;
-    const int32_t marks[2] = {TQ_SPLITK_MAX_ROWS / per_tok, TQ_SKINNY_MAX_ROWS / per_tok};
-    for (int i = 0; i < 2; ++i) {
+    const int32_t slice_rows = 32 * (TQ_AUG_SLICE_MAX_TILES - (L.E + L.S)) + 31;      // most rows with a sliced pre-pass
+    const int32_t marks[3] = {TQ_SPLITK_MAX_ROWS / per_tok, TQ_SKINNY_MAX_ROWS / per_tok, slice_rows > 0 ? slice_rows / per_tok : 0};
+    for (int i = 0; i < 3; ++i) {
         if (marks[i] >= 1 && marks[i] < T) {
             tq_make_workspace(L, desc->act_dtype, marks[i], &W);
             if (W.total > need) need = W.total;

@@ -151,7 +151,8 @@ struct TqWorkspace {
     size_t xaug_d;      // bf16 [A_tot][ka_d]
     size_t h;           // bf16 [A_tot][F]  or fp32 [A_tot][F]
     size_t yd;          // fp32 [nsplit][A_tot][H]
-    size_t tpart;       // fp32 partial low-rank intermediates of the decode path (only for small batches)
+    size_t tpart;       // fp32 partial low-rank intermediates (only for small batches): slices of the decode path's
+    size_t tpart_bytes; // pre-pass, or of the tiled kernels' pre-pass when it cuts the contraction
     size_t zc_ws;       // dense codes on the tiled kernels: the zero-point coefficient fragments the blob does not store,
     size_t zc_stride;   // derived per call: [E+S] records of zc_stride bytes, section GU at 0, section D at zc_d_off
     size_t zc_d_off;
@@ -168,6 +169,7 @@ struct TqWorkspace {
 #define TQ_PERM_CHUNK 256   // assignments handled by one permutation block
 #define TQ_MAX_SPLIT 8      // K-splits of the down projection on the small-tile path
 #define TQ_SKINNY_MAX_ROWS 1024   // assignment rows up to which the decode (16-row tile) path is considered
+#define TQ_AUG_SLICE_MAX_TILES 128   // 32-row tiles up to which the tiled kernels' pre-pass is cut over K
 #define TQ_SPLITK_MAX_ROWS 4096   // assignment rows up to which the 32-row path may split the down projection's K
 
 __host__ __device__ inline int tq_pad64(int v) { return (v + 63) / 64 * 64; }
@@ -213,11 +215,27 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
         // the small-tile path may split the down projection's K; the large-tile path never does
         size_t planes = (a_tot <= TQ_SPLITK_MAX_ROWS) ? TQ_MAX_SPLIT : 1;
         W->yd = take(planes * (size_t)a_tot * L.H * 4);
-        W->tpart = off;
-        if (a_tot <= TQ_SKINNY_MAX_ROWS && L.r > 0) {
-            const size_t slices = (size_t)((L.H > L.F ? L.H : L.F) + 255) / 256;
-            const size_t nat = (size_t)(2 * L.r16 + 31) / 32;
-            W->tpart = take((size_t)(a_tot / 16 + L.E + L.S) * slices * nat * 512 * 4);
+        W->tpart = off; W->tpart_bytes = 0;
+        if (L.r > 0) {
+            if (a_tot <= TQ_SKINNY_MAX_ROWS) {
+                const size_t slices = (size_t)((L.H > L.F ? L.H : L.F) + 255) / 256;
+                const size_t nat = (size_t)(2 * L.r16 + 31) / 32;
+                W->tpart_bytes = (size_t)(a_tot / 16 + L.E + L.S) * slices * nat * 512 * 4;
+            }
+            // pre-pass of the tiled kernels cut over K (at most TQ_AUG_SLICE_MAX_TILES row tiles): slices of at least
+            // 512 indices, up to 512 + tiles (tile, slice) parts, each the 32x32 fp32 column tiles of t
+            const size_t rt32 = (size_t)(a_tot / 32 + L.E + L.S);
+            const size_t cps_min = (size_t)(512 + 4 * L.g - 1) / (4 * L.g);
+            const size_t ch_gu = (size_t)(L.gu.groups + 3) / 4, ch_d = (size_t)(L.d.groups + 3) / 4;
+            const size_t ch = ch_gu > ch_d ? ch_gu : ch_d;
+            const size_t nsl_max = (ch + cps_min - 1) / cps_min;
+            if (rt32 <= TQ_AUG_SLICE_MAX_TILES && nsl_max > 1) {
+                const size_t nat = (size_t)(2 * L.r16 + 31) / 32, natv = nat <= 1 ? 1 : nat == 2 ? 2 : 4;
+                size_t parts = rt32 * nsl_max;
+                if (parts > 512 + rt32) parts = 512 + rt32;
+                if (parts * natv * 4096 > W->tpart_bytes) W->tpart_bytes = parts * natv * 4096;
+            }
+            if (W->tpart_bytes) W->tpart = take(W->tpart_bytes);
         }
         // dense codes / fp8 factors on the tiled kernels (every batch the decode kernels do not take)
         const bool tiled = !tqi_bf16_rows_take_skinny(L, a_tot, L.flags);
@@ -255,7 +273,7 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
         W->xaug_gu = W->xaug_d = off;
         W->zc_ws = off; W->zc_stride = 0; W->zc_d_off = 0;
         W->fac_ws = off; W->fac_bytes = 0; W->fac_fm = TqFactorMap{};
-        W->tpart = off;
+        W->tpart = off; W->tpart_bytes = 0;
         W->sk_cnt = off;
         W->sk_cnt_n = 0;
         W->h = take((size_t)a_tot * L.F * 4);

@@ -168,7 +168,8 @@ __global__ void __launch_bounds__(256, NAT == 1 ? 3 : 2) aug_staged_kernel(MGeom
                                                             const int32_t* __restrict__ tile_row0,
                                                             const int32_t* __restrict__ offsets,
                                                             const int32_t* __restrict__ ctrl,
-                                                            uint16_t* __restrict__ xaug, int ka)
+                                                            uint16_t* __restrict__ xaug, int ka, int cps,
+                                                            float* __restrict__ tslice)
 {
     constexpr int CK = 4 * GS * 16;        // contraction indices per chunk (four groups)
     constexpr int CKB = CK * 2;            // bytes of one row's chunk
@@ -226,10 +227,13 @@ __global__ void __launch_bounds__(256, NAT == 1 ? 3 : 2) aug_staged_kernel(MGeom
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
 
-    load_chunk(0);
+    // With few row tiles the contraction is cut into slices of cps chunks, one workgroup (blockIdx.y) each: the group
+    // sums of a slice are final, its part of t goes to tslice and aug_slices_kernel adds the parts up.
+    const int c_begin = blockIdx.y * cps, c_end = min(nchunks, c_begin + cps);
+    load_chunk(c_begin);
     store_chunk();
     lds_barrier();
-    for (int c = 0; c < nchunks; ++c) {
+    for (int c = c_begin; c < c_end; ++c) {
         const int gi = 4 * c + wave;
         // The factor fragments of this chunk are requested BEFORE the next chunk's rows: loads return in order, and
         // behind the gathered rows (memory-side cache or HBM) these L2 hits would wait for them.  Unconditional
@@ -247,7 +251,7 @@ __global__ void __launch_bounds__(256, NAT == 1 ? 3 : 2) aug_staged_kernel(MGeom
                     aq[ks][j] = af[((size_t)min(j0 + j, max(na_tiles, 1) - 1) * ksteps + gic * GS + ks) * 64 * af_live];
         };
         load_aq(0);
-        if constexpr (NJ == NAT) load_chunk(min(c + 1, nchunks - 1));
+        if constexpr (NJ == NAT) load_chunk(min(c + 1, c_end - 1));
         // every wave copies its group's fragments out of the one LDS buffer (clamped for a group past the end),
         // then the buffer is free for the next chunk
         Frag xa[GS];
@@ -278,7 +282,7 @@ __global__ void __launch_bounds__(256, NAT == 1 ? 3 : 2) aug_staged_kernel(MGeom
                     if (j0 > 0) load_aq(j0);
                     // two halves: the next chunk's rows are requested behind the second half's fragments (in front
                     // of them they would hold those L2 hits back until the rows have arrived)
-                    if (NJ != NAT && j0 + NJ >= NAT) load_chunk(min(c + 1, nchunks - 1));
+                    if (NJ != NAT && j0 + NJ >= NAT) load_chunk(min(c + 1, c_end - 1));
 #pragma unroll
                     for (int ks = 0; ks < GS; ++ks)
 #pragma unroll
@@ -305,19 +309,52 @@ __global__ void __launch_bounds__(256, NAT == 1 ? 3 : 2) aug_staged_kernel(MGeom
                                   (red[(2 * 16 + v) * 64 + lane] + red[(3 * 16 + v) * 64 + lane]);
                 const int cc = 32 * j + col;
                 const int m2 = 8 * (v / 4) + 4 * hf + (v % 4);
-                if (cc < NA && m2 < rows) xaug[(size_t)(slot0 + m2) * ka + ZT + cc] = (uint16_t)f2bf_bits(sum);
+                if (tslice) tslice[((((size_t)tile * gridDim.y + blockIdx.y) * NAT + j) * 16 + v) * 64 + lane] = sum;
+                else if (cc < NA && m2 < rows) xaug[(size_t)(slot0 + m2) * ka + ZT + cc] = (uint16_t)f2bf_bits(sum);
             }
             __syncthreads();
         }
     }
     // the padding must be finite (it meets zero weights in the MFMA): write zeros
-    if (writer && wave == 0) {
+    if (writer && wave == 0 && blockIdx.y == 0) {
         for (int gi = groups; gi < 16 * ((groups + 15) / 16); ++gi) {
             uint16_t* zb = orow + 48 * (gi >> 4) + (gi & 15);
             zb[0] = 0; zb[16] = 0; zb[32] = 0;
         }
         for (int kk = ZT + ((G.r > 0) ? NA : 0); kk < ka; ++kk) orow[kk] = 0;
     }
+}
+
+// Sum of the slices of t that aug_staged_kernel left in tslice ([tile][slice][NAT][16][64] fp32, in the accumulator
+// layout of the 32x32 MFMA), in slice order, rounded to bf16 into the rows of xaug.  One workgroup per tile, column
+// tile of t and four accumulator registers; eight slices are requested at a time.
+__global__ void __launch_bounds__(256) aug_slices_kernel(const float* __restrict__ tslice, int nsl, int nat, int NA, int ZT,
+                                                         const int32_t* __restrict__ tile_e,
+                                                         const int32_t* __restrict__ tile_row0,
+                                                         const int32_t* __restrict__ offsets,
+                                                         const int32_t* __restrict__ ctrl,
+                                                         uint16_t* __restrict__ xaug, int ka)
+{
+    const int tile = blockIdx.x, j = blockIdx.y;
+    if (tile >= ctrl[1]) return;
+    const int e = tile_e[tile], slot0 = tile_row0[tile];
+    const int rows = min(32, offsets[e + 1] - slot0);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, col = lane & 31, hf = lane >> 5;
+    const int v = 4 * blockIdx.z + wave;
+    const float* src = tslice + (((size_t)tile * nsl * nat + j) * 16 + v) * 64 + lane;
+    const size_t stride = (size_t)nat * 1024;
+    float sum = 0.f;
+    for (int s0 = 0; s0 < nsl; s0 += 8) {
+        float part[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) part[u] = src[(size_t)min(s0 + u, nsl - 1) * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (s0 + u < nsl) sum += part[u];
+    }
+    const int cc = 32 * j + col;
+    const int m2 = 8 * (v / 4) + 4 * hf + (v % 4);
+    if (cc < NA && m2 < rows) xaug[(size_t)(slot0 + m2) * ka + ZT + cc] = (uint16_t)f2bf_bits(sum);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -621,13 +658,14 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
         };
         if (full) emit(std::true_type{}); else emit(std::false_type{});
     } else {
-        // tiles of 64 rows and more are never split over K: their result goes out as bf16, halving the traffic
-        // of this store and of the combine pass; the split-K planes of the 32-row path stay fp32
-        constexpr bool YD16 = MT >= 2;
-        using YT = std::conditional_t<YD16, uint16_t, float>;
-        YT* yd = reinterpret_cast<YT*>(out) + (size_t)split * G.a_tot * G.H + (size_t)slot0 * G.H + 64 * pair + col;
-        auto emit = [&](auto full_tag) {
+        // unsplit tiles of 64 rows and more write their result as bf16, halving the traffic of this store and of the
+        // combine pass; split-K planes (always on the 32-row path, on larger tiles when the batch leaves too few of
+        // them to fill the chip) stay fp32
+        auto emit = [&](auto full_tag, auto yd16_tag) {
             constexpr bool FULL = decltype(full_tag)::value;
+            constexpr bool YD16 = decltype(yd16_tag)::value;
+            using YT = std::conditional_t<YD16, uint16_t, float>;
+            YT* yd = reinterpret_cast<YT*>(out) + (size_t)split * G.a_tot * G.H + (size_t)slot0 * G.H + 64 * pair + col;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -644,7 +682,11 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
                     }
                 }
         };
-        if (full) emit(std::true_type{}); else emit(std::false_type{});
+        if (MT >= 2 && nsplit == 1) {
+            if (full) emit(std::true_type{}, std::true_type{}); else emit(std::false_type{}, std::true_type{});
+        } else {
+            if (full) emit(std::true_type{}, std::false_type{}); else emit(std::false_type{}, std::false_type{});
+        }
     }
 }
 
@@ -768,7 +810,7 @@ bool raise_lds_limit_main()
 template <int STAGE>
 tq_status launch_aug(const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin, const int32_t* row_token,
                 const int32_t* tile_e, const int32_t* tile_row0, const int32_t* offsets, const int32_t* ctrl,
-                uint16_t* xaug, int ka, int rt32, hipStream_t st)
+                uint16_t* xaug, int ka, int rt32, float* tslice, size_t tslice_bytes, hipStream_t st)
 {
     // fewer column tiles leave registers for more loads in flight; eight steps at a time need units of 128
     const int nat = G.r > 0 ? sec.na_tiles : 0;
@@ -776,15 +818,35 @@ tq_status launch_aug(const MGeom& G, const TqSection& sec, const uint8_t* blob, 
     // the staged variant: groups up to 128, at most four column tiles of t, 32-bit byte offsets of the rows
     const uint64_t span = (uint64_t)(STAGE == 0 ? G.a_tot / (G.k + G.S) : G.a_tot) * sec.K * 2;
     if (gs <= 8 && nat <= 4 && span < (1ull << 32)) {
+        // A workgroup per row tile walks the whole contraction: with few tiles (a medium batch on a layer of few
+        // experts) that is a handful of workgroups bound by latency, so the contraction is cut into slices of at
+        // least 512 indices until about 512 workgroups exist, and a second launch adds the slices of t up.
+        const int natv = nat <= 1 ? 1 : nat == 2 ? 2 : 4;
+        const int nchunks = (sec.groups + 3) / 4, ck = 4 * G.g;
+        const int tiles_est = std::max(1, std::min(rt32, (int)G.a_tot));
+        int cps = nchunks, nsl = 1;
+        if (rt32 <= TQ_AUG_SLICE_MAX_TILES) {
+            const int want = (512 + tiles_est - 1) / tiles_est;
+            cps = std::max((nchunks + want - 1) / want, (512 + ck - 1) / ck);
+            nsl = (nchunks + cps - 1) / cps;
+            if (nat > 0 && (size_t)rt32 * nsl * natv * 4096 > tslice_bytes) { cps = nchunks; nsl = 1; }
+        }
+        float* ts = (nsl > 1 && nat > 0) ? tslice : nullptr;
 #define TQ_AUGS(NATV, GSV)                                                                                          \
-    hipLaunchKernelGGL((aug_staged_kernel<STAGE, NATV, GSV>), dim3(rt32), dim3(256),                            \
+    hipLaunchKernelGGL((aug_staged_kernel<STAGE, NATV, GSV>), dim3(rt32, nsl), dim3(256),                       \
                        std::max<size_t>((size_t)32 * (4 * GSV * 32 + 16), 4 * 16 * 64 * sizeof(float)) /* staging | reduction */, \
-                       st, G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, xaug, ka)
+                       st, G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, xaug, ka, cps, ts)
         if (nat <= 1) { if (gs == 8) TQ_AUGS(1, 8); else if (gs == 4) TQ_AUGS(1, 4); else TQ_AUGS(1, 2); }
         else if (nat == 2) { if (gs == 8) TQ_AUGS(2, 8); else if (gs == 4) TQ_AUGS(2, 4); else TQ_AUGS(2, 2); }
         else { if (gs == 8) TQ_AUGS(4, 8); else if (gs == 4) TQ_AUGS(4, 4); else TQ_AUGS(4, 2); }
 #undef TQ_AUGS
         TQ_CHECK_LAUNCH();
+        if (ts) {
+            hipLaunchKernelGGL(aug_slices_kernel, dim3(rt32, nat, 4), dim3(256), 0, st, (const float*)ts, nsl, natv,
+                               STAGE == 0 ? 2 * G.r16 : G.r16, tq_zero_terms(sec.K, G.g), tile_e, tile_row0, offsets, ctrl,
+                               xaug, ka);
+            TQ_CHECK_LAUNCH();
+        }
         return TQ_OK;
     }
     const bool deep = (G.g < 64 ? 64 : G.g) % 128 == 0;
@@ -914,7 +976,8 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
         if (rc != TQ_OK) return rc;
         G.zc_ws = ws + W.zc_ws; G.zc_stride = W.zc_stride; G.zc_d_off = W.zc_d_off;
     }
-    rc = launch_aug<0>(G, L.gu, blob, x, row_token, tile_e, tile_row0, offsets, ctrl, xaug_gu, W.ka_gu, rt32, stream);
+    rc = launch_aug<0>(G, L.gu, blob, x, row_token, tile_e, tile_row0, offsets, ctrl, xaug_gu, W.ka_gu, rt32,
+                       reinterpret_cast<float*>(ws + W.tpart), W.tpart_bytes, stream);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(2, stream);
     // many rows per expert: persistent 64-row-tile workgroups (tq_prefill.hip) when the layer qualifies, else one
@@ -936,7 +999,8 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
                                   rt32, stream);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(3, stream);
-    rc = launch_aug<1>(G, L.d, blob, h, row_token, tile_e, tile_row0, offsets, ctrl, xaug_d, W.ka_d, rt32, stream);
+    rc = launch_aug<1>(G, L.d, blob, h, row_token, tile_e, tile_row0, offsets, ctrl, xaug_d, W.ka_d, rt32,
+                       reinterpret_cast<float*>(ws + W.tpart), W.tpart_bytes, stream);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(4, stream);
     int nsplit = 1;
@@ -949,21 +1013,35 @@ tq_status tqi_forward_bf16(const TqLayout& L, const TqWorkspace& W, int flags, c
         nsplit = want < 1 ? 1 : want > TQ_MAX_SPLIT ? TQ_MAX_SPLIT : want;
         if (nsplit > nu) nsplit = nu;
     }
+    if (large && gs != 16 && W.a_tot <= TQ_SPLITK_MAX_ROWS) {
+        // a medium batch on a layer of few, wide experts leaves the 64-row tiling a few hundred (tile, column block)
+        // items that each walk the whole long contraction: one or two per workgroup, finishing far apart.  Split
+        // over K into about 1500 workgroups of the one-item kernel instead (fp32 planes, summed by the combine), each
+        // with at least 2048 contraction indices: on short contractions (layers of many narrow experts, measured at
+        // 1408) the planes cost more than the balance gains.
+        const int64_t items = (int64_t)((L.d.pairs + 3) / 4) * rt64;
+        if (items < 1024) {
+            int want = (int)((1536 + items - 1) / items);
+            if (want > TQ_MAX_SPLIT) want = TQ_MAX_SPLIT;
+            if (want > L.F / 2048) want = L.F / 2048;
+            if (want > 1) nsplit = want;
+        }
+    }
     if (large && gs == 16)
         rc = launch_main<4, 1, 1, 16>(G, L.d, blob, h, xaug_d, row_token, tile_e + W.rt_max, tile_row0 + W.rt_max,
                                       offsets, ctrl, 2, yd, W.ka_d, 1, rt128, stream);
-    else if (large && persist)
+    else if (large && persist && nsplit == 1)
         rc = tqi_forward_prefill_stage(1, L, W, G, blob, h, xaug_d, row_token, tile_e + 3 * (size_t)W.rt_max,
                                        tile_row0 + 3 * (size_t)W.rt_max, offsets, ctrl, 5, yd, stream);
     else if (large)
         rc = launch_main_gs<2, 1, 1>(gs, L.cw, G, L.d, blob, h, xaug_d, row_token, tile_e + 3 * (size_t)W.rt_max,
-                                     tile_row0 + 3 * (size_t)W.rt_max, offsets, ctrl, 5, yd, W.ka_d, 1, rt64, stream);
+                                     tile_row0 + 3 * (size_t)W.rt_max, offsets, ctrl, 5, yd, W.ka_d, nsplit, rt64, stream);
     else
         rc = launch_main_gs<1, 1, 1>(gs, L.cw, G, L.d, blob, h, xaug_d, row_token, tile_e, tile_row0, offsets, ctrl, 1, yd, W.ka_d,
                                   nsplit, rt32, stream);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(5, stream);
-    if (large)
+    if (large && nsplit == 1)
         hipLaunchKernelGGL(combine_bf16_kernel<true>, dim3(T, (L.H / 8 + 255) / 256), dim3(256), 0, stream, T, L.H, L.k,
                            L.S, 1, (size_t)0, slot_of, topk_w, yd, y);
     else
