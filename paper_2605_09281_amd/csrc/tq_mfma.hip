@@ -365,6 +365,11 @@ __global__ void __launch_bounds__(256) aug_slices_kernel(const float* __restrict
 //   STAGE 1: out = yd[split][slot][H] fp32, split = blockIdx.z covering a slice of K
 // GS = quantisation group in MFMA steps (g/16).  A "unit" is max(g, 64) contraction indices.
 // CW = 32-bit words of codes per lane, tile and 64-wide chunk: 4 (4-bit slots), 3 or 2 (dense 3- / 2-bit codes).
+// Staging units between two workgroup barriers of moe_mfma_kernel: the 32-row tile is bound by the weight stream, and
+// a barrier per unit would tie its four waves to the slowest arrival of every unit; with four units per barrier (two
+// for groups of 256: LDS) they drift apart inside a chunk.  Larger tiles keep one unit per barrier (LDS per workgroup).
+constexpr int mfma_chunk_units(int MT, int GS) { return MT == 1 ? (GS == 16 ? 2 : 4) : 1; }
+
 template <int MT, int WM, int STAGE, int GS, int CW = 4>
 __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mfma_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
                                                        const uint16_t* __restrict__ xin,
@@ -384,6 +389,7 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
     constexpr int NG = US / GS;         // quantisation groups per unit
     constexpr int ROWB = UNIT_K * 2 + 16;   // LDS bytes per activation row (16 B pad: conflict-free b128 reads)
     constexpr int BUFB = BM * ROWB;
+    constexpr int CH = mfma_chunk_units(MT, GS);   // units per chunk: two chunks of CH unit buffers, a barrier per chunk
     constexpr int TPR = UNIT_K / 8;     // threads (16-byte segments) per row when loading a unit
     constexpr int RPP = NTHR / TPR;     // rows per pass
     constexpr int NP = BM / RPP;        // passes
@@ -391,7 +397,7 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
     constexpr int WN = CW == 4 ? UC : UC * CW;                    // and how many of them one tile of a unit takes
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    int32_t* tokx = reinterpret_cast<int32_t*>(lds + 2 * BUFB);   // [BM] source row of the main operand
+    int32_t* tokx = reinterpret_cast<int32_t*>(lds + 2 * CH * BUFB);   // [BM] source row of the main operand
     int32_t* toka = tokx + BM;                                    // [BM] row in xaug
 
     const int K = sec.K;
@@ -440,7 +446,7 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
     // ---- staging helpers: steps 0..naug-1 are units of the augmented rows (zero-point and low-rank terms; they go
     //      first so that the latency of their operands overlaps with the start-up of the main stream), the
     //      remaining steps are the main units u0, u0+1, ...
-    auto load_step = [&](int st) {
+    auto load_step_to = [&](u32x4 (&dst)[NP], int st) {
         const bool is_main = st >= naug;
         const uint16_t* base = is_main ? xin : xaug;
         const int32_t* tok = is_main ? tokx : toka;
@@ -449,16 +455,25 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             int row = p * RPP + tid / TPR, seg = tid % TPR;
-            xr[p] = *reinterpret_cast<const u32x4*>(base + (size_t)tok[row] * stride + koff + seg * 8);
+            dst[p] = *reinterpret_cast<const u32x4*>(base + (size_t)tok[row] * stride + koff + seg * 8);
         }
     };
-    auto store_step = [&](int st) {
-        const int buf = st & 1;
+    auto load_step = [&](int st) { load_step_to(xr, st); };
+    // step st lives in unit buffer (st mod 2 CH): chunk parity times CH plus the position inside the chunk
+    auto store_step_from = [&](const u32x4 (&src)[NP], int st) {
+        const int buf = st % (2 * CH);
 #pragma unroll
         for (int p = 0; p < NP; ++p) {
             int row = p * RPP + tid / TPR, seg = tid % TPR;
-            *reinterpret_cast<u32x4*>(lds + buf * BUFB + row * ROWB + seg * 16) = xr[p];
+            *reinterpret_cast<u32x4*>(lds + buf * BUFB + row * ROWB + seg * 16) = src[p];
         }
+    };
+    auto store_step = [&](int st) { store_step_from(xr, st); };
+    // Steps are staged one chunk ahead: step st requests step st + CH at its start and writes it at its end, into the
+    // chunk that nobody reads before the next barrier; the barrier stands at the end of every chunk.
+    auto end_step = [&](int st) {
+        store_step(st + CH);     // past the last step this refills an idle buffer with the last step: harmless
+        if ((st + 1) % CH == 0) lds_barrier();
     };
     auto load_w = [&](WT (&dst)[2][WN], int u) {
 #pragma unroll
@@ -501,10 +516,16 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
     // under a condition makes the compiler wait for ALL outstanding loads at every later use, which would
     // drain the prefetch queue once per unit.
     const int ulast = u1 - 1;
-    load_step(0);
-    load_w(wq[0], min(u0, ulast)); load_sz(szq[0], min(u0, ulast));
-    load_w(wq[1], min(u0 + 1, ulast)); load_sz(szq[1], min(u0 + 1, ulast));
-    store_step(0);
+    {
+        // the whole first chunk is requested at once, ahead of the first weights
+        u32x4 x0[CH][NP];
+#pragma unroll
+        for (int c = 0; c < CH; ++c) load_step_to(x0[c], min(c, nsteps - 1));
+        load_w(wq[0], min(u0, ulast)); load_sz(szq[0], min(u0, ulast));
+        load_w(wq[1], min(u0 + 1, ulast)); load_sz(szq[1], min(u0 + 1, ulast));
+#pragma unroll
+        for (int c = 0; c < CH; ++c) store_step_from(x0[c], c);
+    }
     lds_barrier();
 
     auto lds_frag = [&](int buf, int mt, int kstep) -> bf16x8 {
@@ -517,7 +538,7 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
     auto main_unit = [&](int mu, auto slot_tag) {      // mu: index of the main unit inside this split
         constexpr int SLOT = decltype(slot_tag)::value;
         const int st = naug + mu;
-        load_step(min(st + 1, nsteps - 1));
+        load_step(min(st + CH, nsteps - 1));
         WT wc[2][WN];
         uint32_t szc[NG][2];
 #pragma unroll
@@ -529,7 +550,7 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
 #pragma unroll
             for (int t = 0; t < 2; ++t) szc[gi][t] = szq[SLOT][gi][t];
         load_w(wq[SLOT], min(u0 + mu + 2, ulast)); load_sz(szq[SLOT], min(u0 + mu + 2, ulast));
-        const int buf = st & 1;
+        const int buf = st % (2 * CH);
         if (active) {
             bf16x8 xa[2][MT];
 #pragma unroll
@@ -576,8 +597,7 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
                 }
             }
         }
-        store_step(st + 1);      // at the very last step this refills the idle buffer with the same step: harmless
-        lds_barrier();
+        end_step(st);
     };
 
     // ---- augmented units: zero-point correction and the low-rank term ----------------------------------
@@ -585,8 +605,8 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
     // instead of one per step (and the first one coincides with the start-up of the main stream).
     const int ZT = tq_zero_terms(K, G.g);
     for (int st = 0; st < naug; ++st) {
-        load_step(min(st + 1, nsteps - 1));
-        const int buf = st & 1;
+        load_step(min(st + CH, nsteps - 1));
+        const int buf = st % (2 * CH);
         if (active) {
             u32x4 fq[US][2];
             int kind[US];          // 0 skip, 1 zero-point step (both tiles), 2 low-rank tile 0, 3 low-rank tile 1, 4 both tiles
@@ -629,8 +649,7 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mf
                 }
             }
         }
-        store_step(st + 1);
-        lds_barrier();
+        end_step(st);
     }
 
     int mu = 0;
@@ -749,7 +768,7 @@ tq_status launch_main(const MGeom& G, const TqSection& sec, const uint8_t* blob,
     constexpr int BM = 32 * MT * WM;
     constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
     constexpr int ROWB = UNIT_K * 2 + 16;
-    const size_t smem = (size_t)2 * BM * ROWB + (size_t)2 * BM * 4;
+    const size_t smem = (size_t)2 * mfma_chunk_units(MT, GS) * BM * ROWB + (size_t)2 * BM * 4;
     auto kern = moe_mfma_kernel<MT, WM, STAGE, GS, CW>;      // dynamic-LDS limit: raised once per device by tqi_setup_mfma
     const int nb_count = (sec.pairs + 3) / 4;
     const long n_wg = (long)((row_tiles + 7) / 8) * 8 * nb_count;
@@ -801,7 +820,7 @@ bool raise_lds_limit_main()
     constexpr int BM = 32 * MT * WM;
     constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
     constexpr int ROWB = UNIT_K * 2 + 16;
-    constexpr size_t smem = (size_t)2 * BM * ROWB + (size_t)2 * BM * 4;
+    constexpr size_t smem = (size_t)2 * mfma_chunk_units(MT, GS) * BM * ROWB + (size_t)2 * BM * 4;
     if (smem <= 64 * 1024) return true;
     return hipFuncSetAttribute((const void*)moe_mfma_kernel<MT, WM, STAGE, GS, CW>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                (int)smem) == hipSuccess;
