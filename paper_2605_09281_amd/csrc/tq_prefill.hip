@@ -13,6 +13,7 @@
 // XCD x takes the x-th eighth of the row tiles, a contiguous range, and its workgroups walk (row tile, column
 // block) in row-tile-major order, so the workgroups of one XCD are on a few neighbouring row tiles at any time:
 // they share their activations in that L2, and neighbouring tiles mostly share an expert's weights there too.
+// (With few row tiles the XCDs share out the column blocks of every tile instead: see by_cols.)
 #include "tq_device.h"
 
 #include <type_traits>
@@ -68,7 +69,13 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
     const int last_row = ctrl[3] - 1;       // last assignment row the permutation filled in
     const int per_x = (ntiles + 7) >> 3;
     const int tiles_x = min(max(ntiles - xcd * per_x, 0), per_x);
-    const int items_x = tiles_x * nb_count;
+    // With few row tiles an eighth of them per XCD is a poor deal (12 tiles: six XCDs with two each, two with
+    // none).  Then XCD x takes the column blocks x, x + 8, ... of EVERY row tile instead, whenever that leaves the
+    // busiest XCD at least a tenth fewer items; still row-tile-major, so its workgroups stay on neighbouring tiles.
+    const int nbx_max = (nb_count + 7) >> 3;
+    const bool by_cols = (long long)ntiles * nbx_max * 10 <= (long long)per_x * nb_count * 9;
+    const int nbx = xcd < nb_count ? (nb_count - xcd + 7) >> 3 : 0;
+    const int items_x = by_cols ? ntiles * nbx : tiles_x * nb_count;
     int q = blockIdx.x >> 3;
     if (q >= items_x) return;
     // The two workgroups of a CU: the one launched first wins every issue arbitration (oldest first) and runs
@@ -87,7 +94,8 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
     const int ZT = tq_zero_terms(K, G.g);
 
     // ---- item bookkeeping (everything wave-uniform) ---------------------------------------------------
-    auto tile_of = [&](int qq) { return xcd * per_x + qq / nb_count; };
+    auto tile_of = [&](int qq) { return by_cols ? qq / nbx : xcd * per_x + qq / nb_count; };
+    auto nb_of = [&](int qq) { return by_cols ? xcd + 8 * (qq % nbx) : qq % nb_count; };
     auto make_src = [&](int e, int nb, bool& active) {
         const int pair_raw = nb * 4 + wn;
         active = pair_raw < sec.pairs;
@@ -196,7 +204,7 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
         const int rt = tile_of(q);
         cur_e = __builtin_amdgcn_readfirstlane(tile_e[rt]);
         cur_slot0 = __builtin_amdgcn_readfirstlane(tile_row0[rt]);
-        cur_nb = q % nb_count;
+        cur_nb = nb_of(q);
         cur_rows = min(BM, __builtin_amdgcn_readfirstlane(offsets[cur_e + 1]) - cur_slot0);
         const int rtn = tile_of(min(q + wgx, items_x - 1));
         nxt_e = __builtin_amdgcn_readfirstlane(tile_e[rtn]);
@@ -225,7 +233,7 @@ moe_prefill_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob, con
         const bool has_next = qn < items_x;
         // next item: its tile header was fetched one item ago, its row ids are requested now and written to
         // LDS after the augmented units; the header of the item after it is requested now as well
-        const int nxt_nb = has_next ? qn % nb_count : cur_nb;
+        const int nxt_nb = has_next ? nb_of(qn) : cur_nb;
         bool nxt_active;
         const WSrc nxt = make_src(nxt_e, nxt_nb, nxt_active);
         int ntx, nta;

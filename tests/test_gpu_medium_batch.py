@@ -1,6 +1,6 @@
 """Medium batches on layers of few, wide experts (tens of rows per expert, a handful of row tiles): the tiled kernels'
 pre-pass then cuts the contraction into slices summed by a second launch, and the 64-row tiling splits the down
-projection over K into fp32 planes.  Every path against the oracle on layers wide enough for several slices and
+projection over K into fp32 planes and deals the column blocks of every row tile to the XCDs.  Every path against the oracle on layers wide enough for several slices and
 two planes; run-to-run determinism of the sliced sums; the same layers with fp8 factors and dense 3-bit codes."""
 import numpy as np
 import pytest
@@ -31,6 +31,7 @@ WIDE = {
     "g64_r64_6_experts": wide(1205, r=64, E=6, k=3, T=130),     # four column tiles of t in the gate/up pre-pass
     "rank0": wide(1206, r=0, T=90),                             # slices of group sums only, no second launch
     "ragged_last_chunk": wide(1207, H=1088, F=4160, T=80),      # 17 and 65 groups: a short last chunk in the last slice
+    "11_column_blocks": wide(1208, H=512, F=1408, E=3, T=60),   # gate/up: 11 blocks of 4 column pairs over 8 XCDs
 }
 
 _cache = {}
