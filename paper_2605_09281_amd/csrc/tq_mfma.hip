@@ -367,11 +367,13 @@ __global__ void __launch_bounds__(256) aug_slices_kernel(const float* __restrict
 // CW = 32-bit words of codes per lane, tile and 64-wide chunk: 4 (4-bit slots), 3 or 2 (dense 3- / 2-bit codes).
 // Staging units between two workgroup barriers of moe_mfma_kernel: the 32-row tile is bound by the weight stream, and
 // a barrier per unit would tie its four waves to the slowest arrival of every unit; with four units per barrier (two
-// for groups of 256: LDS) they drift apart inside a chunk.  Larger tiles keep one unit per barrier (LDS per workgroup).
-constexpr int mfma_chunk_units(int MT, int GS) { return MT == 1 ? (GS == 16 ? 2 : 4) : 1; }
+// for groups of 128 and 256: LDS) they drift apart inside a chunk.  Larger tiles keep one unit per barrier (LDS per
+// workgroup).  The 32-row tile is also compiled for four waves per SIMD (three for groups of 128, at the price of a
+// few spilled registers outside the unit loop): its waves stall on their own operands, and more of them hide that.
+constexpr int mfma_chunk_units(int MT, int GS) { return MT == 1 ? (GS >= 8 ? 2 : 4) : 1; }
 
 template <int MT, int WM, int STAGE, int GS, int CW = 4>
-__global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : 1) moe_mfma_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
+__global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : (MT == 1 && GS <= 4) ? 4 : (MT == 1 && GS == 8) ? 3 : 1) moe_mfma_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
                                                        const uint16_t* __restrict__ xin,
                                                        const uint16_t* __restrict__ xaug,
                                                        const int32_t* __restrict__ row_token,
