@@ -169,7 +169,7 @@ struct TqWorkspace {
 #define TQ_PERM_CHUNK 256   // assignments handled by one permutation block
 #define TQ_MAX_SPLIT 8      // K-splits of the down projection on the small-tile path
 #define TQ_SKINNY_MAX_ROWS 1024   // assignment rows up to which the decode (16-row tile) path is considered
-#define TQ_AUG_SLICE_MAX_TILES 128   // 32-row tiles up to which the tiled kernels' pre-pass is cut over K
+#define TQ_AUG_SLICE_MAX_TILES 160   // 32-row tiles up to which the tiled kernels' pre-pass is cut over K
 #define TQ_SPLITK_MAX_ROWS 4096   // assignment rows up to which the 32-row path may split the down projection's K
 
 __host__ __device__ inline int tq_pad64(int v) { return (v + 63) / 64 * 64; }

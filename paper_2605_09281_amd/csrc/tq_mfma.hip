@@ -839,14 +839,17 @@ tq_status launch_aug(const MGeom& G, const TqSection& sec, const uint8_t* blob, 
     // the staged variant: groups up to 128, at most four column tiles of t, 32-bit byte offsets of the rows
     const uint64_t span = (uint64_t)(STAGE == 0 ? G.a_tot / (G.k + G.S) : G.a_tot) * sec.K * 2;
     if (gs <= 8 && nat <= 4 && span < (1ull << 32)) {
-        // A workgroup per row tile walks the whole contraction: with few tiles (a medium batch on a layer of few
-        // experts) that is a handful of workgroups bound by latency, so the contraction is cut into slices of at
-        // least 512 indices until about 512 workgroups exist, and a second launch adds the slices of t up.
+        // A workgroup per row tile walks the whole contraction, some 3 us of dependent latency per chunk: with fewer
+        // tiles than workgroup slots (a medium batch on a layer of few experts, a small one on many experts) the
+        // contraction is cut into slices of at least 512 indices until about 512 workgroups exist, and a second launch
+        // adds the slices of t up.
         const int natv = nat <= 1 ? 1 : nat == 2 ? 2 : 4;
         const int nchunks = (sec.groups + 3) / 4, ck = 4 * G.g;
         const int tiles_est = std::max(1, std::min(rt32, (int)G.a_tot));
         int cps = nchunks, nsl = 1;
-        if (rt32 <= TQ_AUG_SLICE_MAX_TILES) {
+        // (measured: a gain up to 128 row tiles on every layer shape, up to 160 only on contractions of 4096 and more;
+        // beyond that the tiles alone fill the chip and the second launch is a loss)
+        if (rt32 <= 128 || (rt32 <= TQ_AUG_SLICE_MAX_TILES && sec.K >= 4096)) {
             const int want = (512 + tiles_est - 1) / tiles_est;
             cps = std::max((nchunks + want - 1) / want, (512 + ck - 1) / ck);
             nsl = (nchunks + cps - 1) / cps;
