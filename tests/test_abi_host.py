@@ -125,10 +125,13 @@ def test_workspace_grows_with_tokens():
                                            (64, 2, 6, 2048, 1408, 128, 16), (4, 0, 1, 64, 64, 32, 0)])
 def test_workspace_size_never_shrinks_as_tokens_grow(E, S, k, H, F, g, r):
     """A workspace sized for T tokens must serve every smaller batch: the size is non-decreasing in T, in particular
-    across the batch sizes where the split-K planes (4096 assignment rows) and the decode scratch (1024) are dropped."""
+    across the batch sizes where the split-K planes (4096 assignment rows), the decode scratch (1024) and the slices of
+    the pre-pass (160 row tiles) are dropped."""
     d = tq.make_desc(E, S, k, H, F, g, 4, r)
     per = k + S
+    slice_rows = 32 * (160 - (E + S)) + 31        # the most rows whose pre-pass may be cut over K (160 row tiles of 32)
     marks = sorted({1, 2, 1024 // per - 1, 1024 // per, 1024 // per + 1, 4096 // per - 1, 4096 // per, 4096 // per + 1,
+                    slice_rows // per - 1, slice_rows // per, slice_rows // per + 1, slice_rows // per + 2,
                     2 * 4096 // per, 8192, 20000} - {0})
     sizes = [tq.tq_moe_workspace_size(d, T) for T in marks]
     assert all(b >= a > 0 for a, b in zip(sizes, sizes[1:])), list(zip(marks, sizes))
@@ -142,6 +145,17 @@ def test_workspace_size_never_shrinks_as_tokens_grow(E, S, k, H, F, g, r):
         extra_small = tq.tq_moe_workspace_size(dd, 2) - tq.tq_moe_workspace_size(d, 2)
         assert extra_small == (0 if E + S <= 32 else zc)
         assert tq.tq_moe_workspace_size(dd, 20000) == tq.tq_moe_workspace_size(d, 20000) + zc
+
+
+@pytest.mark.parametrize("E,S,k,H,F,g,r", [(8, 0, 2, 4096, 14336, 128, 32), (60, 0, 4, 2048, 1408, 64, 64), (128, 1, 8, 4096, 1536, 128, 32)])
+def test_workspace_size_is_monotonic_over_every_batch_size(E, S, k, H, F, g, r):
+    """Brute force over every T up to past the last threshold (4096 assignment rows)."""
+    d = tq.make_desc(E, S, k, H, F, g, 4, r)
+    last = 0
+    for T in range(1, 4096 // (k + S) + 40):
+        size = tq.tq_moe_workspace_size(d, T)
+        assert size >= last > 0 or T == 1, (T, size, last)
+        last = size
 
 
 # ------------------------------------------------------------------ shared-factor low-rank operator (host side)
