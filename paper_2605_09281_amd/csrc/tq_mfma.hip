@@ -930,11 +930,11 @@ bool tqi_bf16_rows_take_skinny(const TqLayout& L, int64_t a_tot, int flags)
     // expert with more than 16 rows streams its weights once per 16-row tile: 190 against 173 us, 224 against 172 us);
     // on layers of 60 and more experts they are level at best and up to 68 % behind (128 experts, 16 tokens: 277
     // against 165 us - their grid is sized on the host for the experts that MAY receive rows, and with many small
-    // experts a good part of them receive none).  With 8 experts they stay ahead up to 12 rows (179 against 282 us)
-    // and are level at 16.
+    // experts a good part of them receive none).  With 8 experts they stay ahead up to 12 rows (181 against 230 us)
+    // and lose at 14 (281 against 231 us: some expert then holds more than 16).
     const int64_t avg_rows = a_tot / (L.E + L.S);
     const int ne = L.E + L.S;
-    bool skinny = !bf16_large_tiles_rows(L, a_tot, flags) && avg_rows <= (ne <= 8 ? 14 : 10) && ne <= 32 &&
+    bool skinny = !bf16_large_tiles_rows(L, a_tot, flags) && avg_rows <= (ne <= 8 ? 12 : 10) && ne <= 32 &&
                   !(flags & TQ_FLAG_FORCE_SMALL_TILE);
     if (flags & TQ_FLAG_FORCE_SKINNY) skinny = true;
     // (dense codes and fp8 factors follow the same rule: the parts the tiled kernels derive per call are laid out in
