@@ -325,11 +325,15 @@ __global__ void __launch_bounds__(1024) scan_kernel(int32_t* __restrict__ hist, 
     if (check_blob && ctrl && tid == 0 && (ctrl[0] & TQ_FLAG_BIT_BLOB)) { ctrl[1] = 0; ctrl[2] = 0; ctrl[3] = 0; ctrl[4] = 0; ctrl[5] = 0; }
 }
 
-// stable placement of one chunk of assignments by one wavefront; cursor[e] (LDS) = next free slot of expert e
+// stable placement of one chunk of assignments by one wavefront; cursor[e] (LDS) = next free slot of expert e.
+// `sync` orders this wavefront's reads of cursor before its writes and the writes before the next round's reads: a
+// workgroup barrier where the workgroup is this one wave, a wave-level fence where several waves each place a chunk
+// of their own (their trip counts differ, so they cannot meet at a workgroup barrier).
+template <typename Sync>
 __device__ inline void scatter_chunk(const int32_t* __restrict__ idx, const float* __restrict__ w, int64_t a0,
                                      int64_t n_assign, int E, int k, int32_t* cursor, int lane,
                                      int32_t* __restrict__ slot_of, int slot_stride, int32_t* __restrict__ src_of,
-                                     int32_t* __restrict__ row_token, float* __restrict__ row_w)
+                                     int32_t* __restrict__ row_token, float* __restrict__ row_w, Sync sync)
 {
     for (int i0 = 0; i0 < TQ_PERM_CHUNK; i0 += 64) {
         if (a0 + i0 >= n_assign) break;
@@ -349,9 +353,9 @@ __device__ inline void scatter_chunk(const int32_t* __restrict__ idx, const floa
         const int before = __popcll(same & ((1ull << lane) - 1ull));
         const bool last = (same >> lane) <= 1ull;      // no higher lane with this expert
         const int slot = e >= 0 ? cursor[e] + before : -1;
-        __syncthreads();
+        sync();
         if (e >= 0 && last) cursor[e] = slot + 1;   // the last lane of each expert moves its cursor
-        __syncthreads();
+        sync();
         if (a < n_assign) {
             int t = (int)(a / k), j = (int)(a % k);
             if (slot_of) slot_of[(size_t)t * slot_stride + j] = slot;
@@ -377,7 +381,7 @@ __global__ void __launch_bounds__(64) scatter_kernel(const int32_t* __restrict__
     for (int e = lane; e < E; e += 64) cursor[e] = offsets[e] + hist[(size_t)blockIdx.x * E + e];
     __syncthreads();
     scatter_chunk(idx, w, (int64_t)blockIdx.x * TQ_PERM_CHUNK, n_assign, E, k, cursor, lane, slot_of, slot_stride,
-                  src_of, row_token, row_w);
+                  src_of, row_token, row_w, [] { __syncthreads(); });
     // shared experts: every token, weight 1, identity order
     if (S > 0) {
         const int64_t total = (int64_t)S * T;
@@ -390,6 +394,95 @@ __global__ void __launch_bounds__(64) scatter_kernel(const int32_t* __restrict__
             if (row_w) row_w[slot] = 1.0f;
         }
     }
+}
+
+// Batches of 2 to TQ_PERM_MID_CHUNKS chunks (a few thousand assignments): the whole permutation in ONE workgroup of 16
+// waves instead of four launches (clear, histogram, scan, scatter) that each cost a few microseconds of latency for
+// microseconds of work.  Wave w takes chunks w, w + 16, ...; the per-chunk histograms live in LDS and turn, after the
+// scans, into the per-chunk cursors.  Same slots as the several-launch path: chunk-major, stable inside a chunk.
+constexpr int TQ_PERM_MID_CHUNKS = 16;      // measured: 16 chunks -2 % on the step, 32 chunks +1 % against the several launches
+__global__ void __launch_bounds__(1024) permute_mid_kernel(const int32_t* __restrict__ idx, const float* __restrict__ w,
+                                                           int n_assign, int nblk, int E, int S, int T, int k,
+                                                           int32_t* __restrict__ offsets, int32_t* __restrict__ slot_of,
+                                                           int slot_stride, int32_t* __restrict__ src_of,
+                                                           int32_t* __restrict__ row_token, float* __restrict__ row_w,
+                                                           int32_t* __restrict__ tile_e, int32_t* __restrict__ tile_row0,
+                                                           int rt_max, int32_t* __restrict__ ctrl,
+                                                           int32_t* __restrict__ err_flag,
+                                                           const TqBlobHeader* __restrict__ hdr, TqBlobHeader expect,
+                                                           int check_blob, int32_t* __restrict__ zero_buf, int zero_n,
+                                                           int tilings)
+{
+    extern __shared__ int32_t sm[];   // counts[ne] | offs[ne+1] | tile scratch TQ_N_TILINGS*(ne+1) | flags[1] | hist[nblk][E]
+    const int ne = E + S;
+    int32_t* counts = sm;
+    int32_t* offs = counts + ne;
+    int32_t* tsm = offs + ne + 1;
+    int32_t* flagw = tsm + TQ_N_TILINGS * (ne + 1);
+    int32_t* hist = flagw + 1;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    TqBlobHeader hv = expect;
+    if (check_blob && tid == 0) hv = *hdr;
+    if (ctrl && tid < 64) ctrl[tid] = 0;
+    for (int i = tid; i < zero_n; i += 1024) zero_buf[i] = 0;
+    if (tid == 0) {
+        if (err_flag && err_flag != ctrl) *err_flag = 0;
+        *flagw = 0;
+    }
+    for (int i = tid; i < nblk * E; i += 1024) hist[i] = 0;
+    __syncthreads();
+    // per-chunk histograms
+    bool bad = false;
+    for (int b = wave; b < nblk; b += 16) {
+        for (int i = lane; i < TQ_PERM_CHUNK; i += 64) {
+            const int a = b * TQ_PERM_CHUNK + i;
+            if (a < n_assign) {
+                const int e = idx[a];
+                if (e >= 0 && e < E) atomicAdd(&hist[b * E + e], 1); else bad = true;
+            }
+        }
+    }
+    if (bad) atomicOr(flagw, TQ_FLAG_BIT_RANGE);
+    if (check_blob && tid == 0 && !blob_header_ok(&hv, expect)) atomicOr(flagw, TQ_FLAG_BIT_BLOB);
+    __syncthreads();
+    // per expert: exclusive scan over the chunks (at most 16: one round of a wave), total into counts
+    for (int e = wave; e < E; e += 16) {
+        const int v = lane < nblk ? hist[lane * E + e] : 0;
+        const int inc = wave_incl_scan(v, lane);
+        if (lane < nblk) hist[lane * E + e] = inc - v;
+        if (lane == 63) counts[e] = inc;
+    }
+    for (int sidx = tid; sidx < S; sidx += 1024) counts[E + sidx] = T;
+    __syncthreads();
+    if (wave == 0) {
+        const int total = wave_excl_scan(counts, offs, ne, lane, [](int v) { return v; });
+        if (lane == 0 && ctrl) ctrl[3] = total;
+    }
+    __syncthreads();
+    for (int e = tid; e <= ne; e += 1024) offsets[e] = offs[e];
+    if (tile_e) build_tile_tables(offs, tsm, ne, tile_e, tile_row0, rt_max, ctrl, tid, 1024, tilings);
+    for (int i = tid; i < nblk * E; i += 1024) hist[i] += offs[i % E];      // the chunks' cursors
+    __syncthreads();
+    for (int b = wave; b < nblk; b += 16)
+        scatter_chunk(idx, w, (int64_t)b * TQ_PERM_CHUNK, n_assign, E, k, hist + b * E, lane, slot_of, slot_stride, src_of,
+                      row_token, row_w, [] {
+                          __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                          __builtin_amdgcn_wave_barrier();
+                          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                      });
+    for (int i = tid; i < S * T; i += 1024) {      // shared experts: every token, weight 1, identity order
+        const int sidx = i / T, t = i % T;
+        const int slot = offs[E + sidx] + t;
+        if (slot_of) slot_of[(size_t)t * slot_stride + k + sidx] = slot;
+        if (src_of) src_of[slot] = n_assign + i;
+        if (row_token) row_token[slot] = t;
+        if (row_w) row_w[slot] = 1.0f;
+    }
+    const int flags = *flagw;
+    if (flags && tid == 0 && err_flag) atomicOr(err_flag, flags);
+    // a blob that does not belong to the descriptor: no row tiles and no rows, so that every later kernel of the
+    // forward ends at once instead of indexing the blob with the wrong geometry
+    if ((flags & TQ_FLAG_BIT_BLOB) && ctrl && tid == 0) { ctrl[1] = 0; ctrl[2] = 0; ctrl[3] = 0; ctrl[4] = 0; ctrl[5] = 0; }
 }
 
 __device__ inline void permute_small_body(const int32_t* __restrict__ idx, const float* __restrict__ w,
@@ -659,6 +752,14 @@ tq_status tqi_launch_permute(const int32_t* topk_idx, const float* topk_w, int32
             hipLaunchKernelGGL(pre_by_assign_kernel<false>, dim3((unsigned)n_pre), dim3(64), 0, stream, *pre, topk_idx, T, E, k,
                                (const TqBlobHeader*)blob, expect, check);
         TQ_CHECK_LAUNCH();
+    }
+    const size_t sm_mid = ((size_t)ne + (ne + 1) + TQ_N_TILINGS * (ne + 1) + 1 + (size_t)nblk * E) * 4;
+    if (nblk <= TQ_PERM_MID_CHUNKS && sm_mid <= 64 * 1024 && (int64_t)S * T <= 0x3FFFFFFF) {
+        hipLaunchKernelGGL(permute_mid_kernel, dim3(1), dim3(1024), sm_mid, stream, topk_idx, topk_w, (int)n_assign, (int)nblk, E, S,
+                           T, k, offsets, slot_of, slot_stride, src_of, row_token, row_w, tile_e, tile_row0, rt_max, ctrl,
+                           err_flag, (const TqBlobHeader*)blob, expect, check, zero_buf, (int)zero_n, tilings);
+        TQ_CHECK_LAUNCH();
+        return TQ_OK;
     }
     if (ctrl) {
         hipLaunchKernelGGL(clear_ctrl_kernel, dim3(1), dim3(64), 0, stream, ctrl, err_flag, zero_buf, (int)zero_n);
