@@ -157,11 +157,13 @@ def test_permute_bit_exact(T, E, k, seed):
 
 @pytest.mark.parametrize("T,E,k,S_unused,seed", [(129, 8, 2, 0, 10), (1024, 60, 4, 0, 11), (4096, 64, 6, 0, 12), (4097, 64, 8, 0, 13),
                                                  (2731, 100, 12, 0, 14), (2000, 700, 2, 0, 15), (300, 1024, 1, 0, 16),
-                                                 (5000, 1024, 3, 0, 17), (32768, 5, 1, 0, 18), (33, 128, 8, 0, 19)])
+                                                 (5000, 1024, 3, 0, 17), (32768, 5, 1, 0, 18), (33, 128, 8, 0, 19),
+                                                 (1365, 7, 3, 0, 21), (1366, 7, 3, 0, 22), (2048, 3, 2, 0, 23), (512, 250, 8, 0, 24)])
 def test_permute_mid_sized_batches_bit_exact(T, E, k, S_unused, seed):
-    """Batches of 2 to 129 chunks of 256 assignments on the multi-kernel permutation (per-chunk histograms, chunk scan
-    in the offsets kernel up to 64 chunks and in a kernel of its own beyond): ragged last chunks, empty experts,
-    skewed loads, few and many experts."""
+    """Batches of 2 to 129 chunks of 256 assignments: up to 16 chunks in the one-workgroup kernel (per-chunk
+    histograms and cursors in LDS), beyond on the several-launch permutation (chunk scan in the offsets kernel up to
+    64 chunks and in a kernel of its own beyond): ragged last chunks, empty experts, skewed loads, few and many
+    experts, 4095 / 4098 assignments on either side of the 16-chunk limit."""
     print(f"permute T={T} E={E} k={k}", flush=True)
     rng = np.random.default_rng(seed)
     p = rng.random(E) ** 3
