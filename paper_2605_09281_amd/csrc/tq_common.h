@@ -145,7 +145,7 @@ struct TqWorkspace {
     size_t row_w;       // float [A_tot]
     size_t row_src;     // int32 [A_tot]  assignment behind each slot: t * k + j (routed), T * k + s * T + t (shared expert s)
     size_t tile_e;      // int32 [4][RT]  expert of each row tile, for the 32-, 128-, 16- and 64-row tilings
-    size_t tile_row0;   // int32 [4][RT]  first slot of each row tile
+    size_t tile_row0;   // int32 [4][RT]  first slot of each row tile, followed by int32 [4][RT] its number of rows
     size_t hist;        // int32 [nblk][E] permutation scratch
     size_t xaug_gu;     // bf16 [A_tot][ka_gu]   (bf16 path)
     size_t xaug_d;      // bf16 [A_tot][ka_d]
@@ -206,7 +206,7 @@ __host__ inline void tq_make_workspace(const TqLayout& L, int act_dtype, int32_t
     W->row_w = take((size_t)a_tot * 4);
     W->row_src = take((size_t)a_tot * 4);
     W->tile_e = take((size_t)TQ_N_TILINGS * W->rt_max * 4);
-    W->tile_row0 = take((size_t)TQ_N_TILINGS * W->rt_max * 4);
+    W->tile_row0 = take((size_t)2 * TQ_N_TILINGS * W->rt_max * 4);      // first slots, then row counts
     W->hist = take((size_t)W->nblk * L.E * 4);
     if (act_dtype == TQ_ACT_BF16) {
         W->xaug_gu = take((size_t)a_tot * W->ka_gu * 2);

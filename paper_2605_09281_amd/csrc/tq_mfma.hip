@@ -927,15 +927,15 @@ bool tqi_bf16_rows_take_skinny(const TqLayout& L, int64_t a_tot, int flags)
 {
     // The decode kernels pay where a few large experts hold a handful of rows each: measured against the 32-row
     // kernel they are 20-35 % ahead up to 8 rows per expert on layers of 8 to 32 experts and fall behind at 12 (an
-    // expert with more than 16 rows streams its weights once per 16-row tile: 190 against 173 us, 224 against 172 us);
-    // on layers of 60 and more experts they are level at best and up to 68 % behind (128 experts, 16 tokens: 277
-    // against 165 us - their grid is sized on the host for the experts that MAY receive rows, and with many small
-    // experts a good part of them receive none).  With 8 experts they stay ahead up to 12 rows (181 against 230 us)
-    // and lose at 14 (281 against 231 us: some expert then holds more than 16).
+    // expert with more than 16 rows streams its weights once per 16-row tile: 190 against 173 us, 224 against 172 us).
+    // With 8 experts they stay ahead up to 12 rows (181 against 230 us) and lose at 14 (281 against 231 us: some
+    // expert then holds more than 16).  On layers of 60 and more experts every (tile, column pair) costs them the same
+    // 5 us whether the tile holds one row or sixteen, so they only win while few experts are hit at all: up to 2 rows
+    // per expert on average they are 3-9 % ahead (128 experts, 16 tokens: 139 against 152 us), at 4 rows 4-20 % behind.
     const int64_t avg_rows = a_tot / (L.E + L.S);
     const int ne = L.E + L.S;
-    bool skinny = !bf16_large_tiles_rows(L, a_tot, flags) && avg_rows <= (ne <= 8 ? 12 : 10) && ne <= 32 &&
-                  !(flags & TQ_FLAG_FORCE_SMALL_TILE);
+    const bool few_rows = ne <= 32 ? avg_rows <= (ne <= 8 ? 12 : 10) : a_tot <= 2 * (int64_t)ne;
+    bool skinny = !bf16_large_tiles_rows(L, a_tot, flags) && few_rows && !(flags & TQ_FLAG_FORCE_SMALL_TILE);
     if (flags & TQ_FLAG_FORCE_SKINNY) skinny = true;
     // (dense codes and fp8 factors follow the same rule: the parts the tiled kernels derive per call are laid out in
     // the workspace exactly when this returns false)

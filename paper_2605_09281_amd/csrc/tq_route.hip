@@ -222,7 +222,8 @@ __global__ void __launch_bounds__(64) hist_kernel(const int32_t* __restrict__ id
     }
 }
 
-// writes the row-tile tables from offs[0..ne] (LDS); `sm_base` is LDS scratch of TQ_N_TILINGS*(ne+1) ints
+// writes the row-tile tables from offs[0..ne] (LDS); `sm_base` is LDS scratch of TQ_N_TILINGS*(ne+1) ints;
+// tile_row0 holds 2 * TQ_N_TILINGS * rt_max ints: the first slots, then the row counts
 __device__ inline void build_tile_tables(const int32_t* offs, int32_t* sm_base, int ne, int32_t* tile_e,
                                          int32_t* tile_row0, int rt_max, int32_t* ctrl, int tid, int nthreads,
                                          int tilings = (1 << TQ_N_TILINGS) - 1)
@@ -260,6 +261,8 @@ __device__ inline void build_tile_tables(const int32_t* offs, int32_t* sm_base, 
             }
             te[n] = lo;
             tr[n] = offs[lo] + (n - base[lo]) * bm;
+            // the tile's row count, behind the first-slot tables: saves the decode kernels a dependent load of offsets
+            tr[n + (size_t)TQ_N_TILINGS * rt_max] = min(bm, offs[lo + 1] - tr[n]);
         }
     }
 }

@@ -17,6 +17,7 @@
 //     t of a split times B lands in that split's output plane, and the planes are summed by the combine.
 #include "tq_device.h"
 
+#include <algorithm>
 #include <type_traits>
 
 using namespace tqdev;
@@ -80,7 +81,9 @@ __global__ void __launch_bounds__(64) skinny_pre_kernel(MGeom G, TqSection sec, 
 
 // STAGE 0: out = h[slot][F] bf16 = silu(gate) * up.   STAGE 1: out = yd[split][slot][H] fp32.
 // CW: 32-bit words of codes per lane, tile and 64-wide chunk: 4 (4-bit slots), 3 or 2 (dense 3- / 2-bit codes).
-template <int STAGE, int GS, int CW>
+// DEAL: the workgroups share out the (tile, split) combinations that exist among themselves (1-D grid) instead of
+// taking the one their 3-D block index names; see below.
+template <int STAGE, int GS, int CW, bool DEAL>
 __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
                                                          const uint16_t* __restrict__ xin,
                                                          const int32_t* __restrict__ row_token,
@@ -91,7 +94,8 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
                                                          const float* __restrict__ tpart, int n_slices, int na_tiles,
                                                          void* __restrict__ out, int32_t* __restrict__ pair_cnt,
                                                          int units_per_split, int RB, int red_off, int xs_off, int mb_off,
-                                                         const int32_t* __restrict__ row_src)
+                                                         const int32_t* __restrict__ row_src, int nsplit,
+                                                         const int32_t* __restrict__ tile_rows)
 {
     constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
     constexpr int UC = UNIT_K / 64;
@@ -106,12 +110,38 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     float* xs = reinterpret_cast<float*>(lds + xs_off);
     uint16_t* tbuf = reinterpret_cast<uint16_t*>(lds + red_off);   // [16][NA] bf16; lives only before the pair loop
 
-    const int rt = blockIdx.y;
-    if (rt >= ctrl[4]) return;
+    // Which (row tile, split) this workgroup works on, its number `part` among the g_wg workgroups on it:
+    //  * 3-D grid (layers of few experts, where the host knows how many tiles will exist): blockIdx itself;
+    //  * DEAL, 1-D grid (many small experts, most of the tiles the host has to allow for are empty): the
+    //    workgroups are shared out among the combinations that EXIST, a number only the device knows.  Each of the
+    //    n_v combinations gets G = grid / n_v consecutive workgroups (consecutive ids sit on different XCDs, so a
+    //    combination's weight stream is spread over all of them), the first grid mod n_v one more from the end.
+    //    (A template argument, not a run-time switch or the only form: the kernel is short of scalar registers, and
+    //    the second form measured 1-2 % slower per stage on the 8-expert decode layer in every spelling tried; its
+    //    surplus workgroups leave inside the block below because the same test further down cost the down stage 70
+    //    more spilled scalar registers.)
+    int rt, split, part, g_wg;
+    if constexpr (!DEAL) {
+        rt = blockIdx.y;
+        if (rt >= ctrl[4]) return;
+        split = blockIdx.z;
+        part = blockIdx.x;
+        g_wg = gridDim.x;
+    } else {
+        const int n_t = ctrl[4], n_v = n_t * nsplit;
+        if (n_v == 0) return;
+        const int G_lo = (int)gridDim.x / n_v, n_full = G_lo * n_v;      // the grid has at least n_v workgroups
+        const bool extra = (int)blockIdx.x >= n_full;
+        const int vt = extra ? (int)blockIdx.x - n_full : (int)blockIdx.x / G_lo;
+        part = extra ? G_lo : (int)blockIdx.x % G_lo;
+        if (part >= sec.pairs) return;      // more workgroups on this combination than it has pairs
+        g_wg = G_lo + (vt < (int)gridDim.x - n_full ? 1 : 0);
+        rt = vt % n_t;
+        split = vt / n_t;
+    }
     const int e = tile_e[rt], slot0 = tile_row0[rt];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int K = sec.K, NU = K / UNIT_K;
-    const int split = blockIdx.z;
     const int NA = STAGE == 0 ? 2 * G.r16 : G.r16;
     const int n_lr = (G.r > 0) ? NA / 16 : 0;       // low-rank MFMA steps; step j is applied by wave j
     const int ub = split * units_per_split;
@@ -120,16 +150,16 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     int nuw = min(UPW, ue - (ub + wave * UPW));     // units of this wave (0 for idle waves)
     if (nuw < 0) nuw = 0;
     const int wk0 = wave * UPW * US;                // first MFMA step of this wave inside the workgroup's range
-    // Column-tile pairs are dealt out dynamically among the workgroups of this (tile, split): the first one is the
-    // workgroup's index, every further one comes from a counter (cleared by the permutation), fetched one pair
+    // Column-tile pairs are dealt out dynamically among the g_wg workgroups of this (tile, split): the first one is the
+    // workgroup's number among them, every further one comes from a counter (cleared by the permutation), fetched one pair
     // ahead of its use so that the weight prefetch knows where to go.  Workgroups that get a better share of the
     // memory system take more pairs, and all of them finish together.
     const int npairs = sec.pairs;
-    const int p0 = blockIdx.x;
+    const int p0 = part;
     int32_t* cnt = pair_cnt + (size_t)rt * TQ_MAX_SPLIT + split;
     int* pq = reinterpret_cast<int*>(lds + mb_off);            // two mailbox words
     int got_v = 0;
-    if (tid == 0) got_v = (int)gridDim.x + atomicAdd(cnt, 1);
+    if (tid == 0) got_v = g_wg + atomicAdd(cnt, 1);
 
     const uint8_t* rec = blob + TQ_HEADER_BYTES + (size_t)e * G.expert_stride;
     const u32x4* codes = reinterpret_cast<const u32x4*>(rec + sec.codes) + lane;
@@ -178,7 +208,9 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     //         Everything the set-up needs (these rows, the low-rank slices) is requested and awaited BEFORE the first
     //         weights are asked for: at kernel start every workgroup asks for its first pair at once, and small
     //         loads queued behind that burst would arrive only after it.
-    const int rows = min(16, offsets[e + 1] - slot0);
+    // (DEAL reads the tile's row count from the tile table: its tile index already waited for a load, and offsets
+    // would be one more in the chain)
+    const int rows = DEAL ? tile_rows[rt] : min(16, offsets[e + 1] - slot0);
     const int gran = range_k / 8;                 // 16-byte chunks per row
     const int total = rows * gran;
     auto stage_load = [&](int c0, u32x4 (&v)[4], int (&dst)[4]) {
@@ -334,7 +366,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
                                                                      // factors hit the cache; the codes are fetched again, once
                                                                      // per workgroup: measured cheaper than a guarded prefetch)
         int fetched = 0;
-        if (tid == 0) fetched = (int)gridDim.x + atomicAdd(cnt, 1);       // the pair after the next one
+        if (tid == 0) fetched = g_wg + atomicAdd(cnt, 1);       // the pair after the next one
         float acc8[2][8];
 #pragma unroll
         for (int t = 0; t < 2; ++t)
@@ -477,8 +509,8 @@ template <int STAGE, int GS, int CW>
 tq_status launch_skinny(const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin,
                         const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
                         const int32_t* offsets, const int32_t* ctrl, float* tpart, int n_slices, int na_tiles,
-                        void* out, int32_t* pair_cnt, int row_tiles, int nsplit, int units_per_split, int tiles_est,
-                        hipStream_t st, const int32_t* row_src)
+                        void* out, int32_t* pair_cnt, int row_tiles, int nsplit, int units_per_split,
+                        hipStream_t st, const int32_t* row_src, const int32_t* tile_rows)
 {
     constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
     const int range_k = units_per_split * UNIT_K;
@@ -488,21 +520,37 @@ tq_status launch_skinny(const MGeom& G, const TqSection& sec, const uint8_t* blo
     const int mb_off = xs_off + (range_k / G.g) * 16 * 4;      // mailbox of the pair scheduler
     const size_t smem = (size_t)mb_off + 16;
     if (smem > 160 * 1024) return TQ_ERR_UNSUPPORTED;
-    auto kern = moe_skinny_kernel<STAGE, GS, CW>;      // dynamic-LDS limit: raised once per device by tqi_setup_skinny
-    // one workgroup per compute unit over the tiles that are expected to exist: a workgroup fills a CU (LDS),
-    // and fewer, longer workgroups amortise the set-up (activation staging, group sums) over more pairs
+    // one workgroup per compute unit (a workgroup fills a CU's LDS; fewer, longer workgroups amortise the set-up -
+    // activation staging, group sums - over more pairs)
     const TqDeviceState* ds = nullptr;
     if (tqi_device_state(&ds) != TQ_OK) return TQ_ERR_HIP;
-    const int target = ds->n_cu;
-    long total = (long)sec.pairs * tiles_est * nsplit;
-    int ppw = (int)((total + target - 1) / target);
-    if (ppw < 1) ppw = 1;
-    if (ppw > sec.pairs) ppw = sec.pairs;
-    dim3 grid((sec.pairs + ppw - 1) / ppw, row_tiles, nsplit);
-    if (grid.y > 65535) return TQ_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl,
-                       (const float*)tpart, n_slices, na_tiles, out, pair_cnt, units_per_split, RB, red_off, xs_off, mb_off,
-                       row_src);
+    dim3 grid;
+    int deal_nsplit = 0;
+    if (G.ne <= 32) {
+        // few experts: nearly all of them receive rows, the host's count of the tiles is good
+        const int tiles_est = (int)std::min<int64_t>(G.a_tot, std::min(G.ne, row_tiles));
+        long total = (long)sec.pairs * tiles_est * nsplit;
+        int ppw = (int)((total + ds->n_cu - 1) / ds->n_cu);
+        ppw = std::max(1, std::min(ppw, sec.pairs));
+        grid = dim3((sec.pairs + ppw - 1) / ppw, row_tiles, nsplit);
+        if (grid.y > 65535) return TQ_ERR_UNSUPPORTED;
+    } else {
+        // many experts: at least one workgroup per (tile, split) that may exist; the kernel shares them out among
+        // those that do
+        const long n_wg = std::max<long>(ds->n_cu, (long)row_tiles * nsplit);
+        if (n_wg > 0x7FFFFFFF) return TQ_ERR_UNSUPPORTED;
+        grid = dim3((unsigned)n_wg);
+        deal_nsplit = nsplit;
+    }
+    // (dynamic-LDS limit of both instantiations: raised once per device by tqi_setup_skinny)
+    if (deal_nsplit == 0)
+        hipLaunchKernelGGL((moe_skinny_kernel<STAGE, GS, CW, false>), grid, dim3(512), smem, st, G, sec, blob, xin, row_token, tile_e,
+                           tile_row0, offsets, ctrl, (const float*)tpart, n_slices, na_tiles, out, pair_cnt, units_per_split,
+                           RB, red_off, xs_off, mb_off, row_src, deal_nsplit, tile_rows);
+    else
+        hipLaunchKernelGGL((moe_skinny_kernel<STAGE, GS, CW, true>), grid, dim3(512), smem, st, G, sec, blob, xin, row_token, tile_e,
+                           tile_row0, offsets, ctrl, (const float*)tpart, n_slices, na_tiles, out, pair_cnt, units_per_split,
+                           RB, red_off, xs_off, mb_off, row_src, deal_nsplit, tile_rows);
     TQ_CHECK_LAUNCH();
     return TQ_OK;
 }
@@ -511,12 +559,12 @@ template <int STAGE>
 tq_status launch_skinny_gs(int gs, int cw, const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin,
                            const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
                            const int32_t* offsets, const int32_t* ctrl, float* tpart, int n_slices, int na_tiles,
-                           void* out, int32_t* pair_cnt, int row_tiles, int nsplit, int units_per_split, int tiles_est,
-                           hipStream_t st, const int32_t* row_src)
+                           void* out, int32_t* pair_cnt, int row_tiles, int nsplit, int units_per_split,
+                           hipStream_t st, const int32_t* row_src, const int32_t* tile_rows)
 {
 #define TQ_SK(GSV, CWV)                                                                                                   \
     return launch_skinny<STAGE, GSV, CWV>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, \
-                                          na_tiles, out, pair_cnt, row_tiles, nsplit, units_per_split, tiles_est, st, row_src)
+                                          na_tiles, out, pair_cnt, row_tiles, nsplit, units_per_split, st, row_src, tile_rows)
     if (cw == 4) {
         switch (gs) {
             case 2: TQ_SK(2, 4);
@@ -554,7 +602,11 @@ inline void plan_split(int K, int g, int* nsplit, int* units_per_split)
 tq_status tqi_setup_skinny()
 {
     bool ok = true;
-#define TQ_ONE(ST, GS, CW) ok = ok && hipFuncSetAttribute((const void*)moe_skinny_kernel<ST, GS, CW>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) == hipSuccess
+#define TQ_ONE(ST, GS, CW)                                                                                                        \
+    ok = ok && hipFuncSetAttribute((const void*)moe_skinny_kernel<ST, GS, CW, false>, hipFuncAttributeMaxDynamicSharedMemorySize,    \
+                                   160 * 1024) == hipSuccess &&                                                                       \
+         hipFuncSetAttribute((const void*)moe_skinny_kernel<ST, GS, CW, true>, hipFuncAttributeMaxDynamicSharedMemorySize,           \
+                             160 * 1024) == hipSuccess
     TQ_ONE(0, 2, 4); TQ_ONE(0, 4, 4); TQ_ONE(0, 8, 4); TQ_ONE(0, 16, 4);
     TQ_ONE(1, 2, 4); TQ_ONE(1, 4, 4); TQ_ONE(1, 8, 4); TQ_ONE(1, 16, 4);
     TQ_ONE(0, 4, 3); TQ_ONE(0, 8, 3); TQ_ONE(1, 4, 3); TQ_ONE(1, 8, 3);
@@ -596,13 +648,12 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     const int32_t* row_token = reinterpret_cast<const int32_t*>(ws + W.row_token);
     const int32_t* tile_e = reinterpret_cast<const int32_t*>(ws + W.tile_e) + 2 * (size_t)W.rt_max;      // 16-row tiling
     const int32_t* tile_row0 = reinterpret_cast<const int32_t*>(ws + W.tile_row0) + 2 * (size_t)W.rt_max;
+    const int32_t* tile_rows = tile_row0 + (size_t)TQ_N_TILINGS * W.rt_max;      // row counts of the same tiling
     uint16_t* h = reinterpret_cast<uint16_t*>(ws + W.h);
     float* yd = reinterpret_cast<float*>(ws + W.yd);
     float* tpart = reinterpret_cast<float*>(ws + W.tpart);
     const int gs = L.g / 16;
     const int rt16 = W.a_tot / 16 + L.E + L.S;
-    const int ne = L.E + L.S;
-    const int tiles_est = W.a_tot < ne ? W.a_tot : (ne > rt16 ? rt16 : ne);
 
     int ns, ups;
     plan_split(L.H, L.g, &ns, &ups);
@@ -624,7 +675,7 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     int32_t* pair_cnt = reinterpret_cast<int32_t*>(ws + W.sk_cnt);
     if (W.sk_cnt_n < 2 * W.rt_max * TQ_MAX_SPLIT) return TQ_ERR_UNSUPPORTED;
     tq_status rc = launch_skinny_gs<0>(gs, L.cw, G, L.gu, blob, x, row_token, tile_e, tile_row0, offsets, ctrl, tpart, sl_gu, nat_gu,
-                                       h, pair_cnt, rt16, 1, ups, tiles_est, stream, row_src);
+                                       h, pair_cnt, rt16, 1, ups, stream, row_src, tile_rows);
     if (rc != TQ_OK) return rc;
     tqi_record_stage(3, stream);
     if (L.r > 0) {
@@ -639,7 +690,7 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     tqi_record_stage(4, stream);
     plan_split(L.F, L.g, &ns, &ups);
     rc = launch_skinny_gs<1>(gs, L.cw, G, L.d, blob, h, row_token, tile_e, tile_row0, offsets, ctrl, tpart, sl_d, nat_d, yd,
-                             pair_cnt + (size_t)W.rt_max * TQ_MAX_SPLIT, rt16, ns, ups, tiles_est, stream, nullptr);
+                             pair_cnt + (size_t)W.rt_max * TQ_MAX_SPLIT, rt16, ns, ups, stream, nullptr, tile_rows);
     if (rc != TQ_OK) return rc;
     *nsplit_out = ns;
     return TQ_OK;
