@@ -930,11 +930,14 @@ bool tqi_bf16_rows_take_skinny(const TqLayout& L, int64_t a_tot, int flags)
     // expert with more than 16 rows streams its weights once per 16-row tile: 190 against 173 us, 224 against 172 us).
     // With 8 experts they stay ahead up to 12 rows (181 against 230 us) and lose at 14 (281 against 231 us: some
     // expert then holds more than 16).  On layers of 60 and more experts every (tile, column pair) costs them the same
-    // 5 us whether the tile holds one row or sixteen, so they only win while few experts are hit at all: up to 2 rows
-    // per expert on average they are 3-9 % ahead (128 experts, 16 tokens: 139 against 152 us), at 4 rows 4-20 % behind.
+    // time whether the tile holds one row or sixteen - 5 us on a contraction of 4096, half of that up to 2048, where a
+    // wave's slice is 256 wide - so how long they stay ahead goes by the hidden size: with 4096 up to 3 rows per
+    // expert on average (128 experts: 124 against 149 us at 1 row, 179 against 192 at 3, 212 against 196 at 4), with
+    // 2048 up to 8 (60 experts, groups of 64: 94 against 120 us at 1 row, 122 against 142 at 8; 66 experts, groups of
+    // 128: 76 against 91 at 2 rows, level at 8).
     const int64_t avg_rows = a_tot / (L.E + L.S);
     const int ne = L.E + L.S;
-    const bool few_rows = ne <= 32 ? avg_rows <= (ne <= 8 ? 12 : 10) : a_tot <= 2 * (int64_t)ne;
+    const bool few_rows = ne <= 32 ? avg_rows <= (ne <= 8 ? 12 : 10) : a_tot <= (L.H <= 2048 ? 8 : 3) * (int64_t)ne;
     bool skinny = !bf16_large_tiles_rows(L, a_tot, flags) && few_rows && !(flags & TQ_FLAG_FORCE_SMALL_TILE);
     if (flags & TQ_FLAG_FORCE_SKINNY) skinny = true;
     // (dense codes and fp8 factors follow the same rule: the parts the tiled kernels derive per call are laid out in

@@ -3,7 +3,7 @@
 //
 //   * A row tile holds at most 16 assignment rows of one expert.  Its activations for the whole
 //     contraction range of the workgroup (up to 4096 values per row) are staged in LDS ONCE.
-//   * A workgroup has 8 waves; wave w owns a 512-wide slice of the contraction range and walks over the
+//   * A workgroup has 8 waves; wave w owns a 512-wide slice (256 on contractions up to 2048) of the contraction range and walks over the
 //     workgroup's column-tile pairs, streaming its slice of the packed codes (already in MFMA fragment
 //     order) straight from global memory into registers, one pair ahead.  No barrier in that stream.
 //   * Codes go to v_mfma_f32_32x32x16_bf16 as 128 + q (rows 16..31 of the tile are padding); each
@@ -25,7 +25,6 @@ using namespace tqdev;
 namespace {
 
 constexpr int SK_NW = 8;        // waves per workgroup
-constexpr int SK_WAVE_K = 512;  // contraction indices per wave
 constexpr int SK_RED_BYTES = SK_NW * 7 * 2 * 64 * 4;   // per wave: 7 of its 8 row groups, 2 tiles, 64 lanes
 
 __device__ inline int row_of_v(int v, int hf) { return 8 * (v >> 2) + 4 * hf + (v & 3); }
@@ -83,7 +82,8 @@ __global__ void __launch_bounds__(64) skinny_pre_kernel(MGeom G, TqSection sec, 
 // CW: 32-bit words of codes per lane, tile and 64-wide chunk: 4 (4-bit slots), 3 or 2 (dense 3- / 2-bit codes).
 // DEAL: the workgroups share out the (tile, split) combinations that exist among themselves (1-D grid) instead of
 // taking the one their 3-D block index names; see below.
-template <int STAGE, int GS, int CW, bool DEAL>
+// WK: contraction indices per wave (512, or 256 on contractions of at most 2048 so that all eight waves have a slice).
+template <int STAGE, int GS, int CW, bool DEAL, int WK>
 __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
                                                          const uint16_t* __restrict__ xin,
                                                          const int32_t* __restrict__ row_token,
@@ -101,7 +101,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     constexpr int UC = UNIT_K / 64;
     constexpr int US = UNIT_K / 16;
     constexpr int NG = US / GS;
-    constexpr int UPW = SK_WAVE_K / UNIT_K;   // units per wave
+    constexpr int UPW = WK / UNIT_K;   // units per wave
     using WT = std::conditional_t<CW == 4, u32x4, uint32_t>;      // register type of the packed codes
     constexpr int WN = CW == 4 ? UC : UC * CW;                    // and how many of them one tile of a unit takes
 
@@ -505,7 +505,7 @@ __global__ void __launch_bounds__(512) moe_skinny_kernel(MGeom G, TqSection sec,
     }
 }
 
-template <int STAGE, int GS, int CW>
+template <int STAGE, int GS, int CW, int WK>
 tq_status launch_skinny(const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin,
                         const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
                         const int32_t* offsets, const int32_t* ctrl, float* tpart, int n_slices, int na_tiles,
@@ -544,11 +544,11 @@ tq_status launch_skinny(const MGeom& G, const TqSection& sec, const uint8_t* blo
     }
     // (dynamic-LDS limit of both instantiations: raised once per device by tqi_setup_skinny)
     if (deal_nsplit == 0)
-        hipLaunchKernelGGL((moe_skinny_kernel<STAGE, GS, CW, false>), grid, dim3(512), smem, st, G, sec, blob, xin, row_token, tile_e,
+        hipLaunchKernelGGL((moe_skinny_kernel<STAGE, GS, CW, false, WK>), grid, dim3(512), smem, st, G, sec, blob, xin, row_token, tile_e,
                            tile_row0, offsets, ctrl, (const float*)tpart, n_slices, na_tiles, out, pair_cnt, units_per_split,
                            RB, red_off, xs_off, mb_off, row_src, deal_nsplit, tile_rows);
     else
-        hipLaunchKernelGGL((moe_skinny_kernel<STAGE, GS, CW, true>), grid, dim3(512), smem, st, G, sec, blob, xin, row_token, tile_e,
+        hipLaunchKernelGGL((moe_skinny_kernel<STAGE, GS, CW, true, WK>), grid, dim3(512), smem, st, G, sec, blob, xin, row_token, tile_e,
                            tile_row0, offsets, ctrl, (const float*)tpart, n_slices, na_tiles, out, pair_cnt, units_per_split,
                            RB, red_off, xs_off, mb_off, row_src, deal_nsplit, tile_rows);
     TQ_CHECK_LAUNCH();
@@ -560,11 +560,18 @@ tq_status launch_skinny_gs(int gs, int cw, const MGeom& G, const TqSection& sec,
                            const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
                            const int32_t* offsets, const int32_t* ctrl, float* tpart, int n_slices, int na_tiles,
                            void* out, int32_t* pair_cnt, int row_tiles, int nsplit, int units_per_split,
-                           hipStream_t st, const int32_t* row_src, const int32_t* tile_rows)
+                           hipStream_t st, const int32_t* row_src, const int32_t* tile_rows, int wave_k)
 {
 #define TQ_SK(GSV, CWV)                                                                                                   \
-    return launch_skinny<STAGE, GSV, CWV>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, \
-                                          na_tiles, out, pair_cnt, row_tiles, nsplit, units_per_split, st, row_src, tile_rows)
+    do {                                                                                                                  \
+        if (wave_k == 256 && GSV * 16 <= 256)                                                                             \
+            return launch_skinny<STAGE, GSV, CWV, (GSV * 16 <= 256 ? 256 : 512)>(                                         \
+                G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart, n_slices, na_tiles, out, pair_cnt, \
+                row_tiles, nsplit, units_per_split, st, row_src, tile_rows);                                              \
+        return launch_skinny<STAGE, GSV, CWV, 512>(G, sec, blob, xin, row_token, tile_e, tile_row0, offsets, ctrl, tpart,  \
+                                                   n_slices, na_tiles, out, pair_cnt, row_tiles, nsplit, units_per_split, \
+                                                   st, row_src, tile_rows);                                               \
+    } while (0)
     if (cw == 4) {
         switch (gs) {
             case 2: TQ_SK(2, 4);
@@ -583,11 +590,15 @@ tq_status launch_skinny_gs(int gs, int cw, const MGeom& G, const TqSection& sec,
     return TQ_ERR_UNSUPPORTED;
 }
 
-// contraction split of one stage: nsplit workgroups along K, each a whole number of 512-wide wave slices
+// contraction indices per wave of a stage: 512, or 256 on contractions of at most 2048 - a workgroup works on one
+// column-tile pair at a time, and with 512-wide slices a contraction of 1536 would leave five of its eight waves idle
+inline int wave_k_of(int K, int g) { return (K <= 2048 && g <= 256) ? 256 : 512; }
+
+// contraction split of one stage: nsplit workgroups along K, each a whole number of wave slices
 inline void plan_split(int K, int g, int* nsplit, int* units_per_split)
 {
     const int unit_k = g < 64 ? 64 : g;
-    const int upw = SK_WAVE_K / unit_k;
+    const int upw = wave_k_of(K, g) / unit_k;
     const int nu = K / unit_k;
     const int max_units = SK_NW * upw;
     int ns = (nu + max_units - 1) / max_units;
@@ -602,16 +613,18 @@ inline void plan_split(int K, int g, int* nsplit, int* units_per_split)
 tq_status tqi_setup_skinny()
 {
     bool ok = true;
-#define TQ_ONE(ST, GS, CW)                                                                                                        \
-    ok = ok && hipFuncSetAttribute((const void*)moe_skinny_kernel<ST, GS, CW, false>, hipFuncAttributeMaxDynamicSharedMemorySize,    \
-                                   160 * 1024) == hipSuccess &&                                                                       \
-         hipFuncSetAttribute((const void*)moe_skinny_kernel<ST, GS, CW, true>, hipFuncAttributeMaxDynamicSharedMemorySize,           \
-                             160 * 1024) == hipSuccess
+#define TQ_ATTR(ST, GS, CW, DL, WK)                                                                                  \
+    ok = ok && hipFuncSetAttribute((const void*)moe_skinny_kernel<ST, GS, CW, DL, WK>,                                  \
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) == hipSuccess
+#define TQ_ONE(ST, GS, CW)                                                                                           \
+    TQ_ATTR(ST, GS, CW, false, 512); TQ_ATTR(ST, GS, CW, true, 512);                                                 \
+    TQ_ATTR(ST, GS, CW, false, (GS * 16 <= 256 ? 256 : 512)); TQ_ATTR(ST, GS, CW, true, (GS * 16 <= 256 ? 256 : 512))
     TQ_ONE(0, 2, 4); TQ_ONE(0, 4, 4); TQ_ONE(0, 8, 4); TQ_ONE(0, 16, 4);
     TQ_ONE(1, 2, 4); TQ_ONE(1, 4, 4); TQ_ONE(1, 8, 4); TQ_ONE(1, 16, 4);
     TQ_ONE(0, 4, 3); TQ_ONE(0, 8, 3); TQ_ONE(1, 4, 3); TQ_ONE(1, 8, 3);
     TQ_ONE(0, 4, 2); TQ_ONE(0, 8, 2); TQ_ONE(1, 4, 2); TQ_ONE(1, 8, 2);
 #undef TQ_ONE
+#undef TQ_ATTR
     return ok ? TQ_OK : TQ_ERR_HIP;
 }
 
@@ -675,7 +688,7 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     int32_t* pair_cnt = reinterpret_cast<int32_t*>(ws + W.sk_cnt);
     if (W.sk_cnt_n < 2 * W.rt_max * TQ_MAX_SPLIT) return TQ_ERR_UNSUPPORTED;
     tq_status rc = launch_skinny_gs<0>(gs, L.cw, G, L.gu, blob, x, row_token, tile_e, tile_row0, offsets, ctrl, tpart, sl_gu, nat_gu,
-                                       h, pair_cnt, rt16, 1, ups, stream, row_src, tile_rows);
+                                       h, pair_cnt, rt16, 1, ups, stream, row_src, tile_rows, wave_k_of(L.H, L.g));
     if (rc != TQ_OK) return rc;
     tqi_record_stage(3, stream);
     if (L.r > 0) {
@@ -690,7 +703,7 @@ tq_status tqi_forward_skinny(const TqLayout& L, const TqWorkspace& W, const uint
     tqi_record_stage(4, stream);
     plan_split(L.F, L.g, &ns, &ups);
     rc = launch_skinny_gs<1>(gs, L.cw, G, L.d, blob, h, row_token, tile_e, tile_row0, offsets, ctrl, tpart, sl_d, nat_d, yd,
-                             pair_cnt + (size_t)W.rt_max * TQ_MAX_SPLIT, rt16, ns, ups, stream, nullptr, tile_rows);
+                             pair_cnt + (size_t)W.rt_max * TQ_MAX_SPLIT, rt16, ns, ups, stream, nullptr, tile_rows, wave_k_of(L.F, L.g));
     if (rc != TQ_OK) return rc;
     *nsplit_out = ns;
     return TQ_OK;
