@@ -910,12 +910,14 @@ static bool bf16_large_tiles_rows(const TqLayout& L, int64_t a_tot, int flags);
 static bool bf16_large_tiles(const TqLayout& L, const TqWorkspace& W, int flags) { return bf16_large_tiles_rows(L, W.a_tot, flags); }
 static bool bf16_large_tiles_rows(const TqLayout& L, int64_t a_tot, int flags)
 {
-    // measured crossover of the two tilings (four layer shapes, batches swept across it): on layers of 60 to 128
-    // experts the large tiles are level with the 32-row kernel at 16 rows per expert or up to 7 % ahead, 15 % ahead at
-    // 24 rows (128 experts) and up to 28 % at 48; a layer of 8 wide experts changes over between 28 rows (32-row
-    // kernel 16 % ahead) and 32
+    // measured crossover of the two tilings (four layer shapes, batches swept across it): a layer of 8 wide experts
+    // changes over between 28 rows per expert (32-row kernel 16 % ahead) and 32; the 128-expert layer (hidden size
+    // 4096) between 16 rows (32-row kernel 4 % ahead) and 20 (large tiles 4 % ahead, 5.5 % at 24); the 60- and
+    // 66-expert layers (hidden size 2048) between 24 rows (32-row kernel 4-5 % ahead) and 32 (large tiles 3 % ahead).
+    // (Before the 32-row kernel was compiled for more waves per SIMD and its pre-pass cut over K, these crossovers
+    // lay at 12 to 16 rows.)
     const int64_t avg_rows = a_tot / (L.E + L.S);
-    bool large = avg_rows >= (L.E + L.S <= 16 ? 32 : 12);      // (12 to 16 rows: level to 10 % ahead on the three shapes)
+    bool large = avg_rows >= (L.E + L.S <= 16 ? 32 : L.H <= 2048 ? 28 : 20);
     if (flags & TQ_FLAG_FORCE_SMALL_TILE) large = false;
     if (flags & TQ_FLAG_FORCE_LARGE_TILE) large = true;
     return large;
