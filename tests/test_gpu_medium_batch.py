@@ -1,7 +1,9 @@
 """Medium batches on layers of few, wide experts (tens of rows per expert, a handful of row tiles): the tiled kernels'
 pre-pass then cuts the contraction into slices summed by a second launch, and the 64-row tiling splits the down
 projection over K into fp32 planes and deals the column blocks of every row tile to the XCDs.  Every path against the oracle on layers wide enough for several slices and
-two planes; run-to-run determinism of the sliced sums; the same layers with fp8 factors and dense 3-bit codes."""
+two planes; run-to-run determinism of the sliced sums; the same layers with fp8 factors and dense 3-bit codes.
+Second part: small batches on layers of many experts, which the decode kernels take with a device-side deal of their
+workgroups."""
 import numpy as np
 import pytest
 import torch
@@ -97,3 +99,31 @@ def test_wide_experts_fp8_factors(flags):
 def test_wide_experts_dense_3bit(flags):
     y, ref = run(wide(1211, bits=3, dense=True, T=100), flags)
     assert rel_err(y.float().cpu().numpy(), ref) <= TOL_BF16
+
+
+# ------------------------------------------------------------------ small batches on layers of many experts
+# The decode kernels on layers of more than 32 experts: their workgroups share out the row tiles that exist (most
+# experts receive no row), wave slices of 256 contraction indices up to a contraction of 2048 and of 512 beyond.
+MANY = {
+    "40_experts_10_tokens": wide(1301, E=40, k=4, H=256, F=384, T=10),
+    "70_experts_shared": wide(1302, E=70, S=1, k=6, H=256, F=320, g=32, r=24, T=9),
+    "36_experts_skewed_tall_tiles": wide(1303, E=36, k=2, H=192, F=256, T=100, zipf_s=1.3),     # hot experts hold several 16-row tiles
+    "wave_slices_of_512": wide(1304, E=33, k=3, H=2304, F=2176, g=128, r=16, T=8),             # 4.5 and 4.25 slices of 512
+    "more_tiles_than_cus": wide(1305, E=300, k=1, H=128, F=128, r=0, T=290),                    # one workgroup per tile, some tiles without any
+}
+
+
+@pytest.mark.parametrize("flags", [tq.TQ_FLAG_FORCE_SKINNY, 0], ids=["tile16", "auto"])
+@pytest.mark.parametrize("name", list(MANY))
+def test_many_experts_small_batch(name, flags):
+    print(f"many experts {name} flags {flags}", flush=True)
+    y, ref = run(MANY[name], flags)
+    assert rel_err(y.float().cpu().numpy(), ref) <= TOL_BF16
+
+
+def test_many_experts_run_to_run_deterministic():
+    cfg = MANY["36_experts_skewed_tall_tiles"]
+    a, _ = run(cfg, tq.TQ_FLAG_FORCE_SKINNY)
+    b, _ = run(cfg, tq.TQ_FLAG_FORCE_SKINNY)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
