@@ -337,7 +337,8 @@ __device__ inline int tq_find_expert(const int32_t* __restrict__ offsets, int n,
 // table only, not the permutation) so that it can share the permutation's launch:
 //   tpart[v][slice][ta][c] = sum over the 256-wide slice of x[token(v)][kk] * A_e(v)[kk][32 ta + c]   (fp32)
 // v = t * k + j for routed assignments, T * k + s * T + t for shared expert s.
-#define TQ_PRE_ASSIGN_MAX_ROWS 64     // assignment rows up to which the decode path takes this form (A_e is read per row)
+#define TQ_PRE_ASSIGN_MAX_ROWS 256    // assignment rows up to which the decode path takes this form (A_e is read per row;
+                                      // measured: saves 7 % of the step at 96 rows, 5 % at 160, 1-2 % at 256)
 struct TqPreByAssign {
     const uint16_t* x;       // [T][H] bf16
     const uint8_t* blob;
