@@ -372,7 +372,10 @@ __global__ void __launch_bounds__(256) aug_slices_kernel(const float* __restrict
 // few spilled registers outside the unit loop): its waves stall on their own operands, and more of them hide that.
 constexpr int mfma_chunk_units(int MT, int GS) { return MT == 1 ? (GS >= 8 ? 2 : 4) : 1; }
 
-template <int MT, int WM, int STAGE, int GS, int CW = 4>
+// G2 (with GS = 4 on the 32-row tile): the layer's groups are 128 wide and a unit is HALF a group - the partial sums
+// run over two units (even unit: start, odd unit: fold) and both units read the group's scale.  Half the registers
+// of codes and staging per unit, which is what lets groups of 128 run at four waves per SIMD like groups of 64.
+template <int MT, int WM, int STAGE, int GS, int CW = 4, bool G2 = false>
 __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : (MT == 1 && GS <= 4) ? 4 : (MT == 1 && GS == 8) ? 3 : 1) moe_mfma_kernel(MGeom G, TqSection sec, const uint8_t* __restrict__ blob,
                                                        const uint16_t* __restrict__ xin,
                                                        const uint16_t* __restrict__ xaug,
@@ -439,7 +442,8 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : (MT == 1 
                                                                : rec + sec.bfrag) + (size_t)pair * (G.r16 / 16) * 128 + lane;
 
     const int NU = K / UNIT_K;
-    const int u0 = (int)((long)split * NU / nsplit), u1 = (int)((long)(split + 1) * NU / nsplit);
+    constexpr int UPG = G2 ? 2 : 1;      // units per group where a unit is a part of one: splits fall on whole groups
+    const int u0 = UPG * (int)((long)split * (NU / UPG) / nsplit), u1 = UPG * (int)((long)(split + 1) * (NU / UPG) / nsplit);
     const int nmain = u1 - u0;
     const int naug = (split == 0) ? ka / UNIT_K : 0;
     const int nsteps = nmain + naug;
@@ -494,7 +498,7 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : (MT == 1 
 #pragma unroll
         for (int gi = 0; gi < NG; ++gi)
 #pragma unroll
-            for (int t = 0; t < 2; ++t) dst[gi][t] = szp[((size_t)(u * NG + gi) * 2 + t) * 32];
+            for (int t = 0; t < 2; ++t) dst[gi][t] = szp[((size_t)((G2 ? u >> 1 : u) * NG + gi) * 2 + t) * 32];
     };
 
     f32x16 acc[MT][2];
@@ -512,6 +516,7 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : (MT == 1 
 
     WT wq[2][2][WN];
     uint32_t szq[2][NG][2];
+    f32x16 part2[G2 ? MT : 1][2];      // G2: the group's partial sums between its two units
 
     // ---- prologue ---------------------------------------------------------------------------------
     // Prefetches are issued unconditionally with clamped indices (a repeated, unused load at the tail): a load
@@ -559,7 +564,10 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : (MT == 1 
             for (int mt = 0; mt < MT; ++mt) xa[0][mt] = lds_frag(buf, mt, 0);
 #pragma unroll
             for (int gi = 0; gi < NG; ++gi) {
-                f32x16 part[MT][2];
+                f32x16 part_loc[MT][2];
+                auto& part = [&]() -> f32x16 (&)[MT][2] {
+                    if constexpr (G2) return part2; else return part_loc;
+                }();
 #pragma unroll
                 for (int ks = 0; ks < GS; ++ks) {
                     const int kidx = gi * GS + ks;
@@ -578,7 +586,7 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : (MT == 1 
                     for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
                         for (int t = 0; t < 2; ++t) {
-                            if (ks == 0) {
+                            if (ks == 0 && !(G2 && SLOT == 1)) {      // (G2: the odd unit goes on with the even unit's sums)
                                 f32x16 zero;
 #pragma unroll
                                 for (int v = 0; v < 16; ++v) zero[v] = 0.f;
@@ -589,13 +597,15 @@ __global__ void __launch_bounds__(256 * WM, (MT == 2 && WM == 1) ? 2 : (MT == 1 
                         }
                     }
                 }
+                if (!(G2 && SLOT == 0)) {      // (G2: the group is complete after its odd unit)
 #pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const float s = tq_half_bits_to_float((uint16_t)(szc[gi][t] & 0xFFFF));
+                    for (int t = 0; t < 2; ++t) {
+                        const float s = tq_half_bits_to_float((uint16_t)(szc[gi][t] & 0xFFFF));
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
+                        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) acc[mt][t][v] = fmaf(s, part[mt][t][v], acc[mt][t][v]);
+                            for (int v = 0; v < 16; ++v) acc[mt][t][v] = fmaf(s, part[mt][t][v], acc[mt][t][v]);
+                    }
                 }
             }
         }
@@ -761,7 +771,7 @@ __global__ void __launch_bounds__(256) combine_bf16_kernel(int T, int H, int k, 
     }
 }
 
-template <int MT, int WM, int STAGE, int GS, int CW = 4>
+template <int MT, int WM, int STAGE, int GS, int CW = 4, bool G2 = false>
 tq_status launch_main(const MGeom& G, const TqSection& sec, const uint8_t* blob, const uint16_t* xin, const uint16_t* xaug,
                       const int32_t* row_token, const int32_t* tile_e, const int32_t* tile_row0,
                       const int32_t* offsets, const int32_t* ctrl, int ctrl_idx, void* out, int ka, int nsplit,
@@ -771,7 +781,7 @@ tq_status launch_main(const MGeom& G, const TqSection& sec, const uint8_t* blob,
     constexpr int UNIT_K = (GS * 16 < 64) ? 64 : GS * 16;
     constexpr int ROWB = UNIT_K * 2 + 16;
     const size_t smem = (size_t)2 * mfma_chunk_units(MT, GS) * BM * ROWB + (size_t)2 * BM * 4;
-    auto kern = moe_mfma_kernel<MT, WM, STAGE, GS, CW>;      // dynamic-LDS limit: raised once per device by tqi_setup_mfma
+    auto kern = moe_mfma_kernel<MT, WM, STAGE, GS, CW, G2>;      // dynamic-LDS limit: raised once per device by tqi_setup_mfma
     const int nb_count = (sec.pairs + 3) / 4;
     const long n_wg = (long)((row_tiles + 7) / 8) * 8 * nb_count;
     if (n_wg > 0x7FFFFFFF || nb_count > 65535) return TQ_ERR_UNSUPPORTED;
@@ -801,6 +811,12 @@ tq_status launch_main_gs(int gs, int cw, const MGeom& G, const TqSection& sec, c
 #undef TQ_DENSE
         return TQ_ERR_UNSUPPORTED;
     }
+    if constexpr (MT == 1) {
+        // groups of 128 on the 32-row tile: units of half a group (see G2)
+        if (gs == 8)
+            return launch_main<MT, WM, STAGE, 4, 4, true>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl,
+                                                          ctrl_idx, out, ka, nsplit, row_tiles, st);
+    }
     switch (gs) {
         TQ_CASE(2);
         TQ_CASE(4);
@@ -816,7 +832,7 @@ tq_status launch_main_gs(int gs, int cw, const MGeom& G, const TqSection& sec, c
     return TQ_ERR_UNSUPPORTED;
 }
 
-template <int MT, int WM, int STAGE, int GS, int CW = 4>
+template <int MT, int WM, int STAGE, int GS, int CW = 4, bool G2 = false>
 bool raise_lds_limit_main()
 {
     constexpr int BM = 32 * MT * WM;
@@ -824,7 +840,7 @@ bool raise_lds_limit_main()
     constexpr int ROWB = UNIT_K * 2 + 16;
     constexpr size_t smem = (size_t)2 * mfma_chunk_units(MT, GS) * BM * ROWB + (size_t)2 * BM * 4;
     if (smem <= 64 * 1024) return true;
-    return hipFuncSetAttribute((const void*)moe_mfma_kernel<MT, WM, STAGE, GS, CW>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    return hipFuncSetAttribute((const void*)moe_mfma_kernel<MT, WM, STAGE, GS, CW, G2>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                (int)smem) == hipSuccess;
 }
 
@@ -894,6 +910,7 @@ tq_status tqi_setup_mfma()
     bool ok = true;
 #define TQ_BOTH(MT, GS) ok = ok && raise_lds_limit_main<MT, 1, 0, GS>() && raise_lds_limit_main<MT, 1, 1, GS>()
     TQ_BOTH(1, 2); TQ_BOTH(1, 4); TQ_BOTH(1, 8); TQ_BOTH(1, 16);
+    ok = ok && raise_lds_limit_main<1, 1, 0, 4, 4, true>() && raise_lds_limit_main<1, 1, 1, 4, 4, true>();
     TQ_BOTH(2, 2); TQ_BOTH(2, 4); TQ_BOTH(2, 8);
     TQ_BOTH(4, 16);
 #undef TQ_BOTH
