@@ -803,6 +803,14 @@ tq_status launch_main_gs(int gs, int cw, const MGeom& G, const TqSection& sec, c
         return launch_main<MT, WM, STAGE, GSV>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl, ctrl_idx, \
                                            out, ka, nsplit, row_tiles, st)
     if (cw != 4) {      // dense codes: groups of 64 and 128
+        if constexpr (MT == 1) {      // groups of 128 on the 32-row tile: units of half a group (see G2)
+            if (gs == 8 && cw == 3)
+                return launch_main<MT, WM, STAGE, 4, 3, true>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl,
+                                                              ctrl_idx, out, ka, nsplit, row_tiles, st);
+            if (gs == 8 && cw == 2)
+                return launch_main<MT, WM, STAGE, 4, 2, true>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl,
+                                                              ctrl_idx, out, ka, nsplit, row_tiles, st);
+        }
 #define TQ_DENSE(GSV, CWV)                                                                                                   \
     if (gs == GSV && cw == CWV)                                                                                              \
         return launch_main<MT, WM, STAGE, GSV, CWV>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl, ctrl_idx, \
@@ -911,6 +919,8 @@ tq_status tqi_setup_mfma()
 #define TQ_BOTH(MT, GS) ok = ok && raise_lds_limit_main<MT, 1, 0, GS>() && raise_lds_limit_main<MT, 1, 1, GS>()
     TQ_BOTH(1, 2); TQ_BOTH(1, 4); TQ_BOTH(1, 8); TQ_BOTH(1, 16);
     ok = ok && raise_lds_limit_main<1, 1, 0, 4, 4, true>() && raise_lds_limit_main<1, 1, 1, 4, 4, true>();
+    ok = ok && raise_lds_limit_main<1, 1, 0, 4, 3, true>() && raise_lds_limit_main<1, 1, 1, 4, 3, true>();
+    ok = ok && raise_lds_limit_main<1, 1, 0, 4, 2, true>() && raise_lds_limit_main<1, 1, 1, 4, 2, true>();
     TQ_BOTH(2, 2); TQ_BOTH(2, 4); TQ_BOTH(2, 8);
     TQ_BOTH(4, 16);
 #undef TQ_BOTH
@@ -928,13 +938,14 @@ static bool bf16_large_tiles(const TqLayout& L, const TqWorkspace& W, int flags)
 static bool bf16_large_tiles_rows(const TqLayout& L, int64_t a_tot, int flags)
 {
     // measured crossover of the two tilings (four layer shapes, batches swept across it): a layer of 8 wide experts
-    // changes over between 28 rows per expert (32-row kernel 16 % ahead) and 32; the 128-expert layer (hidden size
+    // changes over between 28 rows per expert (32-row kernel 11 % ahead) and 30 (large tiles 13 % ahead: by then
+    // most experts hold more than 32 rows, a second tile for the 32-row kernel); the 128-expert layer (hidden size
     // 4096) between 16 rows (32-row kernel 4 % ahead) and 20 (large tiles 4 % ahead, 5.5 % at 24); the 60- and
     // 66-expert layers (hidden size 2048) between 24 rows (32-row kernel 4-5 % ahead) and 32 (large tiles 3 % ahead).
     // (Before the 32-row kernel was compiled for more waves per SIMD and its pre-pass cut over K, these crossovers
     // lay at 12 to 16 rows.)
     const int64_t avg_rows = a_tot / (L.E + L.S);
-    bool large = avg_rows >= (L.E + L.S <= 16 ? 32 : L.H <= 2048 ? 28 : 20);
+    bool large = avg_rows >= (L.E + L.S <= 16 ? 30 : L.H <= 2048 ? 28 : 20);
     if (flags & TQ_FLAG_FORCE_SMALL_TILE) large = false;
     if (flags & TQ_FLAG_FORCE_LARGE_TILE) large = true;
     return large;
