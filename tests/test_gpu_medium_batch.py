@@ -127,3 +127,40 @@ def test_many_experts_run_to_run_deterministic():
     b, _ = run(cfg, tq.TQ_FLAG_FORCE_SKINNY)
     assert torch.equal(a.view(torch.int16), b.view(torch.int16))
 
+
+@pytest.mark.parametrize("name,flags", [("g128_r32_shared", tq.TQ_FLAG_FORCE_LARGE_TILE), ("g64_r16_50_rows", tq.TQ_FLAG_FORCE_SMALL_TILE),
+                                        ("40_experts_10_tokens", 0)], ids=["large_split", "tile32_sliced", "many_experts_decode"])
+def test_replayed_from_a_hip_graph(name, flags):
+    """The launches these batches add (slice sums, split planes, one-workgroup permutation, device-side deal) captured
+    in a HIP graph: every replay, with eager work in between, equals the eager result bit for bit."""
+    cfg = WIDE.get(name) or MANY[name]
+    layer = get_layer(cfg)
+    x = make_x(cfg)
+    logits, bias = make_logits(cfg)
+    packed = pack_layer_gpu(layer)
+    desc = desc_of(cfg, tq.TQ_ACT_BF16, flags)
+    lg = torch.from_numpy(logits).to(DEV)
+    bs = None if bias is None else torch.from_numpy(bias).to(DEV)
+    xd = x_device(x, tq.TQ_ACT_BF16)
+    ws = torch.empty(tq.tq_moe_workspace_size(desc, cfg.T), dtype=torch.uint8, device=DEV)
+    idx = torch.empty((cfg.T, cfg.k), dtype=torch.int32, device=DEV)
+    w = torch.empty((cfg.T, cfg.k), dtype=torch.float32, device=DEV)
+    y = torch.empty_like(xd)
+    tq.tq_init()
+    tq.tq_route_moe_forward(desc, packed, xd, lg, bs, idx, w, y, ws)
+    torch.cuda.synchronize()
+    y_eager = y.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            tq.tq_route_moe_forward(desc, packed, xd, lg, bs, idx, w, y, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(3):
+        y.zero_()
+        ws.fill_(0x3C)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), y_eager.view(torch.int16))
+
