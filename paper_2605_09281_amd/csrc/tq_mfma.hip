@@ -368,8 +368,8 @@ __global__ void __launch_bounds__(256) aug_slices_kernel(const float* __restrict
 // Staging units between two workgroup barriers of moe_mfma_kernel: the 32-row tile is bound by the weight stream, and
 // a barrier per unit would tie its four waves to the slowest arrival of every unit; with four units per barrier (two
 // for groups of 128 and 256: LDS) they drift apart inside a chunk.  Larger tiles keep one unit per barrier (LDS per
-// workgroup).  The 32-row tile is also compiled for four waves per SIMD (three for groups of 128, at the price of a
-// few spilled registers outside the unit loop): its waves stall on their own operands, and more of them hide that.
+// workgroup).  The 32-row tile is also compiled for four waves per SIMD (groups of 128 run as half-group units of the
+// instantiation for groups of 64, see G2): its waves stall on their own operands, and more of them hide that.
 constexpr int mfma_chunk_units(int MT, int GS) { return MT == 1 ? (GS >= 8 ? 2 : 4) : 1; }
 
 // G2 (with GS = 4 on the 32-row tile): the layer's groups are 128 wide and a unit is HALF a group - the partial sums
@@ -815,7 +815,8 @@ tq_status launch_main_gs(int gs, int cw, const MGeom& G, const TqSection& sec, c
     if (gs == GSV && cw == CWV)                                                                                              \
         return launch_main<MT, WM, STAGE, GSV, CWV>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl, ctrl_idx, \
                                                     out, ka, nsplit, row_tiles, st)
-        TQ_DENSE(4, 3); TQ_DENSE(8, 3); TQ_DENSE(4, 2); TQ_DENSE(8, 2);
+        TQ_DENSE(4, 3); TQ_DENSE(4, 2);
+        if constexpr (MT != 1) { TQ_DENSE(8, 3); TQ_DENSE(8, 2); }      // (the 32-row tile took its groups of 128 above)
 #undef TQ_DENSE
         return TQ_ERR_UNSUPPORTED;
     }
@@ -828,7 +829,12 @@ tq_status launch_main_gs(int gs, int cw, const MGeom& G, const TqSection& sec, c
     switch (gs) {
         TQ_CASE(2);
         TQ_CASE(4);
-        TQ_CASE(8);
+        case 8:
+            if constexpr (MT != 1) {      // (the 32-row tile took its groups of 128 above)
+                return launch_main<MT, WM, STAGE, 8>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl, ctrl_idx,
+                                                     out, ka, nsplit, row_tiles, st);
+            }
+            break;
         case 16:
             if constexpr (MT == 1) {
                 return launch_main<MT, WM, STAGE, 16>(G, sec, blob, xin, xaug, row_token, tile_e, tile_row0, offsets, ctrl, ctrl_idx,
@@ -917,7 +923,7 @@ tq_status tqi_setup_mfma()
 {
     bool ok = true;
 #define TQ_BOTH(MT, GS) ok = ok && raise_lds_limit_main<MT, 1, 0, GS>() && raise_lds_limit_main<MT, 1, 1, GS>()
-    TQ_BOTH(1, 2); TQ_BOTH(1, 4); TQ_BOTH(1, 8); TQ_BOTH(1, 16);
+    TQ_BOTH(1, 2); TQ_BOTH(1, 4); TQ_BOTH(1, 16);
     ok = ok && raise_lds_limit_main<1, 1, 0, 4, 4, true>() && raise_lds_limit_main<1, 1, 1, 4, 4, true>();
     ok = ok && raise_lds_limit_main<1, 1, 0, 4, 3, true>() && raise_lds_limit_main<1, 1, 1, 4, 3, true>();
     ok = ok && raise_lds_limit_main<1, 1, 0, 4, 2, true>() && raise_lds_limit_main<1, 1, 1, 4, 2, true>();
@@ -925,7 +931,7 @@ tq_status tqi_setup_mfma()
     TQ_BOTH(4, 16);
 #undef TQ_BOTH
 #define TQ_DENSE(MT, GS, CW) ok = ok && raise_lds_limit_main<MT, 1, 0, GS, CW>() && raise_lds_limit_main<MT, 1, 1, GS, CW>()
-    TQ_DENSE(1, 4, 3); TQ_DENSE(1, 8, 3); TQ_DENSE(1, 4, 2); TQ_DENSE(1, 8, 2);
+    TQ_DENSE(1, 4, 3); TQ_DENSE(1, 4, 2);
     TQ_DENSE(2, 4, 3); TQ_DENSE(2, 8, 3); TQ_DENSE(2, 4, 2); TQ_DENSE(2, 8, 2);
 #undef TQ_DENSE
     return ok ? TQ_OK : TQ_ERR_HIP;
