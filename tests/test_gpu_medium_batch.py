@@ -164,3 +164,24 @@ def test_replayed_from_a_hip_graph(name, flags):
         torch.cuda.synchronize()
         assert torch.equal(y.view(torch.int16), y_eager.view(torch.int16))
 
+
+def test_blob_of_another_layer_in_a_mid_sized_batch():
+    """400 assignments (two chunks: the one-workgroup permutation) with a blob whose header does not match the
+    descriptor: flag bit 1 is set and the tile counts are cleared, so that no later kernel indexes the blob."""
+    cfg = wide(1401, H=128, F=192, T=200, r=8)
+    other = wide(1402, H=128, F=256, T=200, r=8)
+    layer = get_layer(cfg)
+    packed = pack_layer_gpu(layer)
+    logits, bias = make_logits(cfg)
+    idx, w = tq.tq_route(torch.from_numpy(logits).to(DEV), None, cfg.k)
+    desc = desc_of(other, tq.TQ_ACT_BF16, 0)
+    big = torch.zeros(tq.tq_packed_size(desc), dtype=torch.uint8, device=DEV)
+    big[:packed.numel()] = packed                      # readable at the other layer's size, wrong header
+    ws = torch.empty(tq.tq_moe_workspace_size(desc, cfg.T), dtype=torch.uint8, device=DEV)
+    ws.fill_(0x11)
+    tq.tq_moe_forward(desc, big, x_device(make_x(cfg), tq.TQ_ACT_BF16), idx, w, workspace=ws)
+    torch.cuda.synchronize()
+    ctrl = ws[:24].view(torch.int32).cpu().numpy()
+    assert ctrl[0] & 2
+    assert ctrl[1] == 0 and ctrl[2] == 0 and ctrl[3] == 0 and ctrl[4] == 0 and ctrl[5] == 0
+
