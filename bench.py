@@ -247,6 +247,8 @@ def main():
     ap.add_argument("--rank", type=int, default=None,
                     help="with --workload: override the rank of the low-rank factors (0 = quantised weights alone), for the "
                          "overhead of the low-rank path over the quantised forward")
+    ap.add_argument("--tokens", type=int, default=None,
+                    help="with --workload: the layer of that config at another batch size (the library picks the path)")
     ap.add_argument("--fp8-factors", action="store_true",
                     help="with --workload: store the low-rank factors as fp8 E4M3 codes with an fp16 diagonal Sigma")
     ap.add_argument("--separate-route", action="store_true",
@@ -367,6 +369,11 @@ def main():
             wl = wl.replace(bits=args.dense_bits, dense=True)
         if args.rank is not None:
             wl = wl.replace(r=args.rank)
+        if args.tokens is not None:
+            if args.tokens < 1:
+                print("bench.py: --tokens must be at least 1", file=sys.stderr)
+                sys.exit(2)
+            wl = wl.replace(T=args.tokens)
         res = bench_layer(args, wl, dev, oracle_macs=1.5e11, fp8=args.fp8_factors)
         print(json.dumps(headline(args, res, None)), flush=True)
         return
